@@ -1,0 +1,645 @@
+// CPU oracle of the action-level elastic scheduling step (ARL-Tangram, arXiv 2603.13019).
+//
+// TEST INFRASTRUCTURE ONLY.  A plain, single-threaded, deliberately unoptimised
+// restatement of what the scheduling step computes, written from the paper:
+//   * Eq. 1 (Sec. 4.1)      duration of an action on m units, in integer microseconds
+//   * Eq. 2 (Sec. 4.2)      action completion time = queueing + execution
+//   * Alg. 1 (Sec. 4.2)     FCFS candidate prefix at minimum units, greedy tail eviction
+//   * Alg. 2 (App. A)       approximated objective: exact part + completion-heap estimate
+//   * Alg. 3 (App. B)       DPArrange over used units (basic operator)
+//   * Alg. 4 (App. B)       DPArrange over free-chunk states (GPU operator, sizes 1/2/4/8)
+//   * Sec. 5.1-5.3          capacity models: quota, per-node cores + trajectory pin, buddy chunks
+// It shares no code, header, table or helper with the HIP library; only tests, the
+// smoke check and the benchmark's CPU-baseline leg may call it.
+//
+// Every function below is pinned by tests against closed forms, brute force or an
+// independent second algorithm (tests/test_oracle_*.py); none is "parity unpinned".
+//
+// Integer conventions: times are int64 microseconds relative to the snapshot instant,
+// durations are rounded up and never below 1, INF = INT64_MAX marks "not a candidate".
+
+#include <algorithm>
+#include <cstdint>
+#include <cstring>
+#include <functional>
+#include <queue>
+#include <vector>
+
+namespace {
+
+constexpr int64_t INF = INT64_MAX;
+enum { T_CPU = 0, T_GPU = 1, T_API = 2, N_TYPES = 3 };
+enum { R_NONE = 0, R_PREFIX = 1, R_EVICTED = 2, R_INFEASIBLE = 3 };
+
+struct Tables {
+  int K;
+  const int32_t* k_list;       // ascending unit counts
+  const int32_t* type_k;       // how many leading entries of k_list each type may use
+  const uint32_t* speedup_q16; // [class][q] = round(65536 * E(k_q) * k_q)
+  int depth;
+};
+
+struct Act {
+  int type, model;
+  int64_t T, age;
+  uint32_t kmask, param;
+  int pin, task;
+};
+
+struct Node {
+  int type, cap, free;
+  int64_t backlog;
+  int chunks[4];               // free chunks of size 1,2,4,8 (GPU nodes)
+  std::vector<int64_t> busy;   // release time of every unit held by a running action
+};
+
+// ---- Eq. 1: getDur(m) = T_ori / (E(m) * m), rounded up to whole microseconds -------------
+int64_t duration(const Tables& tb, const Act& a, int q) {
+  const int64_t k = tb.k_list[q];
+  if (a.model == 0) return a.T;                       // elasticity unknown: constant
+  unsigned __int128 num, den;
+  if (a.model == 1) {                                 // Amdahl: E(k) = 1 / ((1-p) k + p)
+    const int64_t p = a.param;                        // parallel fraction in ppm
+    num = (unsigned __int128)a.T * (unsigned __int128)((1000000 - p) * k + p);
+    den = (unsigned __int128)1000000 * k;
+  } else {                                            // table: E(k) k = speedup / 65536
+    num = (unsigned __int128)a.T * 65536u;
+    den = tb.speedup_q16[(size_t)a.param * tb.K + q];
+  }
+  int64_t d = (int64_t)((num + den - 1) / den);
+  return d < 1 ? 1 : d;
+}
+
+// allowed option indices of an action (Sec. 4.1: the discrete set of unit counts)
+std::vector<int> options(const Tables& tb, const Act& a) {
+  std::vector<int> o;
+  for (int q = 0; q < tb.type_k[a.type]; ++q)
+    if (a.kmask >> q & 1u) {
+      o.push_back(q);
+      if (a.model == 0) break;                        // non-elastic: minimum units only
+    }
+  return o;
+}
+
+std::vector<int> options_on(const Tables& tb, const Act& a, const Node& nd) {
+  std::vector<int> o;
+  for (int q : options(tb, a))
+    if (tb.k_list[q] <= nd.cap) o.push_back(q);
+  return o;
+}
+
+// ---- Sec. 5.3: chunk allocation on counts of free chunks --------------------------------
+int chunk_level(int k) { int a = 0; while ((1 << a) < k) ++a; return a; }
+
+bool chunk_fits(const int c[4], int k) {
+  for (int b = chunk_level(k); b < 4; ++b) if (c[b] > 0) return true;
+  return false;
+}
+
+bool chunk_take(int c[4], int k) {                    // smallest chunk of level >= a, split down
+  const int a = chunk_level(k);
+  if (a > 3) return false;
+  for (int b = a; b < 4; ++b)
+    if (c[b] > 0) {
+      --c[b];
+      for (int x = a; x < b; ++x) ++c[x];
+      return true;
+    }
+  return false;
+}
+
+// ---- Alg. 3: DPArrange with the basic operator (state = units used) ----------------------
+// dur[i*K+q] = duration of task i with k_list[q] units, INF if the option is not allowed.
+int64_t dp_units(int m, const int64_t* dur, const int32_t* k_list, int K, int U, int32_t* k_out) {
+  int64_t sum_max = 0;
+  for (int i = 0; i < m; ++i) {
+    int mx = 0;
+    for (int q = 0; q < K; ++q) if (dur[(size_t)i * K + q] != INF) mx = k_list[q];
+    sum_max += mx;
+  }
+  const int n = (int)std::min<int64_t>(U, sum_max);
+  std::vector<std::vector<int64_t>> dp(m + 1, std::vector<int64_t>(n + 1, INF));
+  std::vector<std::vector<int>> choice(m + 1, std::vector<int>(n + 1, -1));
+  dp[0][0] = 0;
+  for (int i = 1; i <= m; ++i)
+    for (int j = 0; j <= n; ++j)
+      for (int q = 0; q < K; ++q) {
+        const int64_t t = dur[(size_t)(i - 1) * K + q];
+        const int jp = j - k_list[q];
+        if (t == INF || jp < 0 || dp[i - 1][jp] == INF) continue;
+        if (dp[i - 1][jp] + t < dp[i][j]) { dp[i][j] = dp[i - 1][jp] + t; choice[i][j] = q; }
+      }
+  int js = -1;
+  for (int j = 0; j <= n; ++j) if (dp[m][j] != INF && (js < 0 || dp[m][j] < dp[m][js])) js = j;
+  if (js < 0) return INF;
+  const int64_t best = dp[m][js];
+  for (int i = m, j = js; i >= 1; --i) {
+    const int q = choice[i][j];
+    if (k_out) k_out[i - 1] = k_list[q];
+    j -= k_list[q];
+  }
+  return best;
+}
+
+// ---- Alg. 3 with Alg. 4's operator (state = encoded counts of free chunks) ---------------
+struct Radix { int n[4]; int size() const { return (n[0]+1)*(n[1]+1)*(n[2]+1)*(n[3]+1); } };
+int encode(const Radix& r, const int c[4]) {
+  return c[0] + (r.n[0]+1) * (c[1] + (r.n[1]+1) * (c[2] + (r.n[2]+1) * c[3]));
+}
+void decode(const Radix& r, int j, int c[4]) {
+  c[0] = j % (r.n[0]+1); j /= (r.n[0]+1);
+  c[1] = j % (r.n[1]+1); j /= (r.n[1]+1);
+  c[2] = j % (r.n[2]+1); j /= (r.n[2]+1);
+  c[3] = j;
+}
+
+int64_t dp_chunks(int m, const int64_t* dur, const int32_t* k_list, int K, const int start[4], int32_t* k_out) {
+  Radix r;                                            // a split never leaves two equal new chunks
+  for (int x = 0; x < 4; ++x) r.n[x] = std::max(start[x], 1);
+  const int S = r.size();
+  std::vector<std::vector<int64_t>> dp(m + 1, std::vector<int64_t>(S, INF));
+  std::vector<std::vector<int>> from(m + 1, std::vector<int>(S, -1)), opt(m + 1, std::vector<int>(S, -1));
+  dp[0][encode(r, start)] = 0;
+  for (int i = 1; i <= m; ++i)
+    for (int s = 0; s < S; ++s) {
+      if (dp[i - 1][s] == INF) continue;
+      for (int q = 0; q < K; ++q) {
+        const int64_t t = dur[(size_t)(i - 1) * K + q];
+        if (t == INF) continue;
+        int c[4]; decode(r, s, c);
+        if (!chunk_take(c, k_list[q])) continue;
+        const int s2 = encode(r, c);
+        if (dp[i - 1][s] + t < dp[i][s2]) { dp[i][s2] = dp[i - 1][s] + t; from[i][s2] = s; opt[i][s2] = q; }
+      }
+    }
+  int ss = -1;
+  for (int s = 0; s < S; ++s) if (dp[m][s] != INF && (ss < 0 || dp[m][s] < dp[m][ss])) ss = s;
+  if (ss < 0) return INF;
+  const int64_t best = dp[m][ss];
+  for (int i = m, s = ss; i >= 1; --i) {
+    if (k_out) k_out[i - 1] = k_list[opt[i][s]];
+    s = from[i][s];
+  }
+  return best;
+}
+
+// ---- Alg. 2, estimate(): sequential insertion into the completion heap -------------------
+// heap: release time of every unit; ac_dur[a*K+q]: durations of the waiting actions (INF = not
+// allowed); all but the first use their minimum units, the first tries its d-th smallest option.
+int64_t estimate(const std::vector<int64_t>& heap0, int n_ac, const int64_t* ac_dur,
+                 const int32_t* k_list, int K, int depth) {
+  const int H = (int)heap0.size();
+  std::vector<std::vector<int>> opts;                 // usable options per waiting action
+  std::vector<int> keep;
+  for (int a = 0; a < n_ac; ++a) {
+    std::vector<int> o;
+    for (int q = 0; q < K; ++q) if (ac_dur[(size_t)a * K + q] != INF && k_list[q] <= H) o.push_back(q);
+    if (!o.empty()) { keep.push_back(a); opts.push_back(o); }   // cannot ever fit: left out
+  }
+  if (keep.empty()) return 0;
+  int64_t best = INF;
+  for (int d = 1; d <= depth; ++d) {
+    if ((int)opts[0].size() < d) break;
+    std::priority_queue<int64_t, std::vector<int64_t>, std::greater<int64_t>> h(heap0.begin(), heap0.end());
+    int64_t obj = 0;
+    for (size_t x = 0; x < keep.size(); ++x) {
+      const int q = (x == 0) ? opts[0][d - 1] : opts[x][0];
+      const int u = k_list[q];
+      int64_t ts = 0;
+      for (int c = 0; c < u; ++c) { ts = h.top(); h.pop(); }    // start when the u-th unit frees
+      const int64_t fin = ts + ac_dur[(size_t)keep[x] * K + q];
+      for (int c = 0; c < u; ++c) h.push(fin);
+      obj += fin;
+    }
+    best = std::min(best, obj);
+  }
+  return best;
+}
+
+struct StepOut {
+  std::vector<int32_t> node, units;
+  std::vector<int64_t> act;
+  std::vector<uint8_t> reason;
+  std::vector<int64_t> node_obj;                      // final approximated objective per node, -1 if none
+  std::vector<int32_t> home;                          // node an action was admitted to (kept when evicted)
+};
+
+// ---- one scheduling step on one snapshot (Alg. 1 applied per resource pool) -------------
+StepOut step(const Tables& tb, const std::vector<Act>& acts, std::vector<Node> nodes) {
+  const int N = (int)acts.size(), M = (int)nodes.size(), K = tb.K;
+  StepOut o;
+  o.node.assign(N, -1); o.units.assign(N, 0); o.act.assign(N, -1); o.reason.assign(N, R_NONE);
+  o.node_obj.assign(M, -1); o.home.assign(N, -1);
+
+  // static infeasibility: no option, bad pin, or minimum units above every candidate node
+  std::vector<int> kmin(N, 0);
+  for (int i = 0; i < N; ++i) {
+    const Act& a = acts[i];
+    std::vector<int> op = options(tb, a);
+    bool ok = !op.empty();
+    if (ok) {
+      kmin[i] = tb.k_list[op[0]];
+      if (a.pin >= 0) ok = a.pin < M && nodes[a.pin].type == a.type && kmin[i] <= nodes[a.pin].cap;
+      else {
+        ok = false;
+        for (int j = 0; j < M; ++j) if (nodes[j].type == a.type && kmin[i] <= nodes[j].cap) ok = true;
+      }
+    }
+    if (!ok) o.reason[i] = R_INFEASIBLE;
+  }
+
+  // Alg. 1 l.1-2: FCFS prefix admitted with minimum units; node choice by least estimated ACT
+  std::vector<int> rem(M);
+  std::vector<std::vector<int>> placed(M), waiting_pinned(M);
+  std::vector<char> closed(M, 0);
+  std::vector<int> ch(M * 4);
+  for (int j = 0; j < M; ++j) { rem[j] = nodes[j].free; for (int x = 0; x < 4; ++x) ch[j*4+x] = nodes[j].chunks[x]; }
+  char type_closed[N_TYPES] = {0, 0, 0};
+  auto fits = [&](int j, int k) {
+    return nodes[j].type == T_GPU ? chunk_fits(&ch[j*4], k) : rem[j] >= k;
+  };
+  for (int i = 0; i < N; ++i) {
+    if (o.reason[i] == R_INFEASIBLE) continue;
+    const Act& a = acts[i];
+    if (type_closed[a.type] || (a.pin >= 0 && closed[a.pin])) {
+      o.reason[i] = R_PREFIX;
+      if (a.pin >= 0) waiting_pinned[a.pin].push_back(i);
+      continue;
+    }
+    int bj = -1; int64_t be = INF;
+    for (int j = 0; j < M; ++j) {
+      if (nodes[j].type != a.type || closed[j]) continue;
+      if (a.pin >= 0 && a.pin != j) continue;
+      if (!fits(j, kmin[i])) continue;
+      int qs = -1;
+      for (int q : options_on(tb, a, nodes[j])) if (fits(j, tb.k_list[q])) qs = q;
+      const int64_t e = nodes[j].backlog + duration(tb, a, qs);      // Eq. 2 on this node
+      if (e < be) { be = e; bj = j; }
+    }
+    if (bj < 0) {
+      if (a.pin >= 0) { closed[a.pin] = 1; waiting_pinned[a.pin].push_back(i); }
+      else type_closed[a.type] = 1;
+      o.reason[i] = R_PREFIX;
+      continue;
+    }
+    o.node[i] = bj; o.home[i] = bj;
+    if (nodes[bj].type == T_GPU) chunk_take(&ch[bj*4], kmin[i]); else rem[bj] -= kmin[i];
+    placed[bj].push_back(i);
+  }
+
+  // Alg. 1 l.3-14 per node: DPArrange + greedy tail eviction on the approximated objective
+  for (int j = 0; j < M; ++j) {
+    const std::vector<int>& C = placed[j];
+    const int m = (int)C.size();
+    if (m == 0) continue;
+    const Node& nd = nodes[j];
+    bool any_elastic = false;
+    for (int i : C) if (acts[i].model != 0) any_elastic = true;
+    std::vector<int32_t> ks(m);
+    int L = m;
+    if (!any_elastic) {
+      for (int x = 0; x < m; ++x) ks[x] = kmin[C[x]];
+    } else {
+      auto dur_row = [&](int i, int64_t* row) {
+        for (int q = 0; q < K; ++q) row[q] = INF;
+        for (int q : options_on(tb, acts[i], nd)) row[q] = duration(tb, acts[i], q);
+      };
+      std::vector<int64_t> cdur((size_t)m * K);
+      for (int x = 0; x < m; ++x) dur_row(C[x], &cdur[(size_t)x * K]);
+      // Alg. 2: exact part by DPArrange, rest of this pool's queue estimated on the heap
+      auto objective = [&](int Lc, std::vector<int32_t>& kk) -> int64_t {
+        kk.assign(Lc, 0);
+        const int64_t exact = nd.type == T_GPU
+            ? dp_chunks(Lc, cdur.data(), tb.k_list, K, nd.chunks, kk.data())
+            : dp_units(Lc, cdur.data(), tb.k_list, K, nd.free, kk.data());
+        std::vector<int64_t> heap(nd.busy);
+        int used = 0;
+        for (int x = 0; x < Lc; ++x) {
+          int q = 0; while (tb.k_list[q] != kk[x]) ++q;
+          for (int c = 0; c < kk[x]; ++c) heap.push_back(nd.backlog + cdur[(size_t)x * K + q]);
+          used += kk[x];
+        }
+        for (int c = used; c < nd.free; ++c) heap.push_back(nd.backlog);
+        std::vector<int> ac(C.begin() + Lc, C.end());
+        ac.insert(ac.end(), waiting_pinned[j].begin(), waiting_pinned[j].end());
+        std::vector<int64_t> adur((size_t)ac.size() * K);
+        for (size_t x = 0; x < ac.size(); ++x) dur_row(ac[x], &adur[x * K]);
+        const int64_t approx = estimate(heap, (int)ac.size(), adur.data(), tb.k_list, K, tb.depth);
+        return exact + (int64_t)Lc * nd.backlog + approx;
+      };
+      std::vector<int32_t> kk;
+      int64_t obj = objective(L, ks);
+      while (L > 1) {
+        const int64_t nobj = objective(L - 1, kk);
+        if (nobj >= obj) break;                        // a tie stops the eviction
+        obj = nobj; ks = kk; --L;
+      }
+      o.node_obj[j] = obj;
+    }
+    for (int x = 0; x < m; ++x) {
+      const int i = C[x];
+      if (x >= L) { o.node[i] = -1; o.reason[i] = R_EVICTED; continue; }
+      int q = 0; while (tb.k_list[q] != ks[x]) ++q;
+      o.units[i] = ks[x];
+      o.act[i] = acts[i].age + nd.backlog + duration(tb, acts[i], q);
+    }
+  }
+  return o;
+}
+
+}  // namespace
+
+// =========================================================================================
+// flat C entry points (loaded by the tests through ctypes)
+// =========================================================================================
+extern "C" {
+
+struct orc_problem {
+  int32_t B, N, M, K, n_classes, n_tasks, depth, pad_;
+  const int32_t* k_list; const int32_t* type_k; const uint32_t* speedup_q16;
+  const uint8_t* node_type; const int32_t* node_cap; const int32_t* node_free;
+  const int64_t* node_backlog_us; const uint8_t* node_chunks;
+  const int32_t* node_busy_off; const int64_t* node_busy_rel_us;
+  const uint8_t* act_type; const uint8_t* act_model; const int64_t* act_t_ori_us; const int64_t* act_age_us;
+  const uint32_t* act_kmask; const uint32_t* act_param; const int32_t* act_pin_node; const int32_t* act_task;
+};
+
+struct orc_summary {
+  int64_t sum_act_us;
+  int32_t n_assigned, n_prefix, n_evicted, n_infeasible;
+  int64_t units_used[3], units_free[3];
+  double mean_act_us, util[3];
+};
+
+struct orc_trace {
+  int32_t S, A, M, K, n_classes, depth, max_ticks, pad_;
+  int64_t tick_us;
+  const int32_t* k_list; const int32_t* type_k; const uint32_t* speedup_q16;
+  const uint8_t* node_type; const int32_t* node_cap; const int32_t* quota_rate; const int64_t* quota_tok0_micro;
+  const int64_t* arrival_us; const uint8_t* act_type; const uint8_t* act_model; const int64_t* act_t_ori_us;
+  const uint32_t* act_kmask; const uint32_t* act_param; const int32_t* act_pin_node;
+};
+
+}  // extern "C"
+
+namespace {
+
+Tables tables_of(const orc_problem* p) { return Tables{p->K, p->k_list, p->type_k, p->speedup_q16, p->depth}; }
+
+std::vector<Act> acts_of(const orc_problem* p, int b) {
+  std::vector<Act> v(p->N);
+  for (int i = 0; i < p->N; ++i) {
+    const size_t g = (size_t)b * p->N + i;
+    v[i] = Act{p->act_type[g], p->act_model[g], p->act_t_ori_us[g], p->act_age_us ? p->act_age_us[g] : 0,
+               p->act_kmask[g], p->act_param[g], p->act_pin_node[g], p->act_task ? p->act_task[g] : 0};
+  }
+  return v;
+}
+
+std::vector<Node> nodes_of(const orc_problem* p, int b) {
+  std::vector<Node> v(p->M);
+  for (int j = 0; j < p->M; ++j) {
+    const size_t g = (size_t)b * p->M + j;
+    Node& nd = v[j];
+    nd.type = p->node_type[g]; nd.cap = p->node_cap[g]; nd.free = p->node_free[g];
+    nd.backlog = p->node_backlog_us[g];
+    for (int x = 0; x < 4; ++x) nd.chunks[x] = 0;
+    if (nd.type == T_GPU) {
+      if (p->node_chunks) for (int x = 0; x < 4; ++x) nd.chunks[x] = p->node_chunks[g * 4 + x];
+      else { nd.chunks[3] = nd.free / 8; for (int x = 0; x < 3; ++x) nd.chunks[x] = (nd.free % 8) >> x & 1; }
+    }
+    if (p->node_busy_off)
+      nd.busy.assign(p->node_busy_rel_us + p->node_busy_off[g], p->node_busy_rel_us + p->node_busy_off[g + 1]);
+  }
+  return v;
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t orc_duration(int model, int64_t T, uint32_t param, int k, uint32_t speedup) {
+  int32_t kl[1] = {k}; int32_t tk[3] = {1, 1, 1}; uint32_t sp[1] = {speedup};
+  Tables tb{1, kl, tk, sp, 1};
+  Act a{0, model, T, 0, 1u, model == 2 ? 0u : param, -1, 0};
+  return duration(tb, a, 0);
+}
+
+// Score tensor (Eq. 1 + Eq. 2 for every type-compatible candidate): for snapshot b, then type t,
+// a block [actions of type t in FCFS order][nodes of type t in index order][type_k[t]].
+int64_t orc_num_candidates(const orc_problem* p) {
+  int64_t total = 0;
+  for (int b = 0; b < p->B; ++b)
+    for (int t = 0; t < N_TYPES; ++t) {
+      int64_t na = 0, nn = 0;
+      for (int i = 0; i < p->N; ++i) na += p->act_type[(size_t)b * p->N + i] == t;
+      for (int j = 0; j < p->M; ++j) nn += p->node_type[(size_t)b * p->M + j] == t;
+      total += na * nn * p->type_k[t];
+    }
+  return total;
+}
+
+void orc_score(const orc_problem* p, int64_t* cost) {
+  const Tables tb = tables_of(p);
+  size_t w = 0;
+  for (int b = 0; b < p->B; ++b) {
+    const std::vector<Act> acts = acts_of(p, b);
+    const std::vector<Node> nodes = nodes_of(p, b);
+    for (int t = 0; t < N_TYPES; ++t)
+      for (int i = 0; i < p->N; ++i) {
+        if (acts[i].type != t) continue;
+        const std::vector<int> op = options(tb, acts[i]);
+        for (int j = 0; j < p->M; ++j) {
+          if (nodes[j].type != t) continue;
+          for (int q = 0; q < tb.type_k[t]; ++q) {
+            const bool ok = std::find(op.begin(), op.end(), q) != op.end() && tb.k_list[q] <= nodes[j].cap &&
+                            (acts[i].pin < 0 || acts[i].pin == j);
+            cost[w++] = ok ? nodes[j].backlog + duration(tb, acts[i], q) : INF;
+          }
+        }
+      }
+  }
+}
+
+void orc_assign(const orc_problem* p, int32_t* node, int32_t* units, int64_t* act_us, uint8_t* reason,
+                orc_summary* summary, int32_t* node_used, int64_t* task_sum, int64_t* node_obj, int32_t* home) {
+  const Tables tb = tables_of(p);
+  for (int b = 0; b < p->B; ++b) {
+    const std::vector<Act> acts = acts_of(p, b);
+    const std::vector<Node> nodes = nodes_of(p, b);
+    const StepOut o = step(tb, acts, nodes);
+    const size_t a0 = (size_t)b * p->N, n0 = (size_t)b * p->M;
+    orc_summary s;
+    std::memset(&s, 0, sizeof s);
+    if (node_used) for (int j = 0; j < p->M; ++j) node_used[n0 + j] = 0;
+    if (task_sum) for (int t = 0; t < p->n_tasks; ++t) task_sum[(size_t)b * p->n_tasks + t] = 0;
+    for (int j = 0; j < p->M; ++j) s.units_free[nodes[j].type] += nodes[j].free;
+    for (int i = 0; i < p->N; ++i) {
+      node[a0 + i] = o.node[i]; units[a0 + i] = o.units[i]; act_us[a0 + i] = o.act[i]; reason[a0 + i] = o.reason[i];
+      switch (o.reason[i]) {
+        case R_PREFIX: ++s.n_prefix; break;
+        case R_EVICTED: ++s.n_evicted; break;
+        case R_INFEASIBLE: ++s.n_infeasible; break;
+        default:
+          ++s.n_assigned; s.sum_act_us += o.act[i]; s.units_used[acts[i].type] += o.units[i];
+          if (node_used) node_used[n0 + o.node[i]] += o.units[i];
+          if (task_sum) task_sum[(size_t)b * p->n_tasks + acts[i].task] += o.act[i];
+      }
+    }
+    s.mean_act_us = s.n_assigned ? (double)s.sum_act_us / (double)s.n_assigned : 0.0;
+    for (int t = 0; t < N_TYPES; ++t)
+      s.util[t] = s.units_free[t] ? (double)s.units_used[t] / (double)s.units_free[t] : 0.0;
+    if (summary) summary[b] = s;
+    if (node_obj) for (int j = 0; j < p->M; ++j) node_obj[n0 + j] = o.node_obj[j];
+    if (home) for (int i = 0; i < p->N; ++i) home[a0 + i] = o.home[i];
+  }
+}
+
+int64_t orc_dp_units(int m, const int64_t* dur, const int32_t* k_list, int K, int U, int32_t* k_out) {
+  return dp_units(m, dur, k_list, K, U, k_out);
+}
+
+int64_t orc_dp_chunks(int m, const int64_t* dur, const int32_t* k_list, int K, const uint8_t* chunks, int32_t* k_out) {
+  const int st[4] = {chunks[0], chunks[1], chunks[2], chunks[3]};
+  return dp_chunks(m, dur, k_list, K, st, k_out);
+}
+
+int64_t orc_estimate(const int64_t* heap, int H, int n_ac, const int64_t* ac_dur, const int32_t* k_list, int K, int depth) {
+  return estimate(std::vector<int64_t>(heap, heap + H), n_ac, ac_dur, k_list, K, depth);
+}
+
+int orc_chunk_take(uint8_t* chunks, int k) {
+  int c[4] = {chunks[0], chunks[1], chunks[2], chunks[3]};
+  const bool ok = chunk_take(c, k);
+  for (int x = 0; x < 4; ++x) chunks[x] = (uint8_t)c[x];
+  return ok;
+}
+
+int orc_chunk_encode_roundtrip(const uint8_t* bound, int j, uint8_t* out) {
+  Radix r; for (int x = 0; x < 4; ++x) r.n[x] = bound[x];
+  int c[4]; decode(r, j, c);
+  for (int x = 0; x < 4; ++x) out[x] = (uint8_t)c[x];
+  return encode(r, c);
+}
+
+// ---- trace replay: the step above run every tick on the live cluster state ---------------
+// free GPUs of an 8-GPU node are a bit mask; a free chunk is a maximal aligned free block.
+static void mask_chunks(int mask, int c[4]) {
+  c[0] = c[1] = c[2] = c[3] = 0;
+  for (int lvl = 3; lvl >= 0; --lvl) {
+    const int sz = 1 << lvl;
+    for (int s = 0; s < 8; s += sz) {
+      const int blk = ((1 << sz) - 1) << s;
+      if ((mask & blk) != blk) continue;
+      bool parent_free = false;
+      if (lvl < 3) { const int ps = s & ~(2 * sz - 1); const int pb = ((1 << (2 * sz)) - 1) << ps; parent_free = (mask & pb) == pb; }
+      if (!parent_free) ++c[lvl];
+    }
+  }
+}
+
+static int mask_alloc(int& mask, int k) {               // best fit, lowest address; returns start
+  const int a = chunk_level(k);
+  for (int lvl = a; lvl < 4; ++lvl) {
+    const int sz = 1 << lvl;
+    for (int s = 0; s < 8; s += sz) {
+      const int blk = ((1 << sz) - 1) << s;
+      if ((mask & blk) != blk) continue;
+      if (lvl < 3) { const int ps = s & ~(2 * sz - 1); const int pb = ((1 << (2 * sz)) - 1) << ps; if ((mask & pb) == pb) continue; }
+      mask &= ~(((1 << (1 << a)) - 1) << s);
+      return s;
+    }
+  }
+  return -1;
+}
+
+int orc_mask_chunks(int mask, uint8_t* out) { int c[4]; mask_chunks(mask, c); for (int x = 0; x < 4; ++x) out[x] = (uint8_t)c[x]; return 0; }
+int orc_mask_alloc(int* mask, int k) { return mask_alloc(*mask, k); }
+
+void orc_replay(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us, int64_t* finish_us, int32_t* units,
+                int32_t* node, double* mean_act, int64_t* p99_act, int32_t* n_started, int32_t* n_ticks) {
+  const Tables tb{t->K, t->k_list, t->type_k, t->speedup_q16, t->depth};
+  const int A = t->A, M = t->M;
+  for (int s = s_lo; s < s_hi; ++s) {
+    const size_t a0 = (size_t)s * A, n0 = (size_t)s * M;
+    struct Run { int64_t fin; int node, k, gstart; };
+    std::vector<Run> running;
+    std::vector<int> rem(M, 0), gmask(M, 0);
+    std::vector<int64_t> tok(M, 0);
+    for (int j = 0; j < M; ++j) {
+      rem[j] = t->node_cap[n0 + j];
+      if (t->node_type[n0 + j] == T_GPU) gmask[j] = (1 << t->node_cap[n0 + j]) - 1;
+      if (t->node_type[n0 + j] == T_API) tok[j] = t->quota_tok0_micro[n0 + j];
+    }
+    for (int i = 0; i < A; ++i) { start_us[a0 + i] = -1; finish_us[a0 + i] = -1; units[a0 + i] = 0; node[a0 + i] = -1; }
+    std::vector<int> waiting;
+    int next = 0, started = 0, tick = 0;
+    for (; tick < t->max_ticks && started < A; ++tick) {
+      const int64_t now = (int64_t)tick * t->tick_us;
+      // (1) finished actions give their units back
+      for (size_t r = 0; r < running.size();) {
+        if (running[r].fin <= now) {
+          const Run& u = running[r];
+          if (t->node_type[n0 + u.node] == T_GPU) gmask[u.node] |= ((1 << (1 << chunk_level(u.k))) - 1) << u.gstart;
+          rem[u.node] += u.k;
+          running[r] = running.back(); running.pop_back();
+        } else ++r;
+      }
+      // (2) quotas refill (Sec. 5.1, quota-based pattern), in millionths of a token
+      if (tick > 0)
+        for (int j = 0; j < M; ++j)
+          if (t->node_type[n0 + j] == T_API)
+            tok[j] = std::min<int64_t>((int64_t)t->node_cap[n0 + j] * 1000000, tok[j] + (int64_t)t->quota_rate[n0 + j] * t->tick_us);
+      // (3) waiting queue in arrival order
+      while (next < A && t->arrival_us[a0 + next] <= now) waiting.push_back(next++);
+      if (waiting.empty()) continue;
+      std::vector<Act> acts;
+      for (int i : waiting)
+        acts.push_back(Act{t->act_type[a0 + i], t->act_model[a0 + i], t->act_t_ori_us[a0 + i], now - t->arrival_us[a0 + i],
+                           t->act_kmask[a0 + i], t->act_param[a0 + i], t->act_pin_node[a0 + i], 0});
+      std::vector<Node> nodes(M);
+      for (int j = 0; j < M; ++j) {
+        Node& nd = nodes[j];
+        nd.type = t->node_type[n0 + j]; nd.cap = t->node_cap[n0 + j]; nd.backlog = 0;
+        for (int x = 0; x < 4; ++x) nd.chunks[x] = 0;
+        if (nd.type == T_API) nd.free = (int)(tok[j] / 1000000);
+        else if (nd.type == T_GPU) { mask_chunks(gmask[j], nd.chunks); nd.free = __builtin_popcount(gmask[j]); }
+        else nd.free = rem[j];
+      }
+      for (const Run& u : running)                       // executing queue seeds the completion heap
+        if (nodes[u.node].type != T_API)
+          for (int c = 0; c < u.k; ++c) nodes[u.node].busy.push_back(u.fin - now);
+      // (4) the scheduling step; (5) selected actions start now
+      const StepOut o = step(tb, acts, nodes);
+      std::vector<int> still;
+      for (size_t w = 0; w < waiting.size(); ++w) {
+        const int i = waiting[w];
+        if (o.node[w] < 0) { still.push_back(i); continue; }
+        const int j = o.node[w], k = o.units[w];
+        int q = 0; while (tb.k_list[q] != k) ++q;
+        const int64_t dur = duration(tb, acts[w], q);
+        Run u{now + dur, j, k, 0};
+        if (nodes[j].type == T_API) tok[j] -= (int64_t)k * 1000000;
+        else {
+          if (nodes[j].type == T_GPU) u.gstart = mask_alloc(gmask[j], k);
+          rem[j] -= k;
+          running.push_back(u);
+        }
+        start_us[a0 + i] = now; finish_us[a0 + i] = now + dur; units[a0 + i] = k; node[a0 + i] = j;
+        ++started;
+      }
+      waiting.swap(still);
+    }
+    std::vector<int64_t> acts_done;
+    int64_t sum = 0;
+    for (int i = 0; i < A; ++i)
+      if (start_us[a0 + i] >= 0) { acts_done.push_back(finish_us[a0 + i] - t->arrival_us[a0 + i]); sum += acts_done.back(); }
+    std::sort(acts_done.begin(), acts_done.end());
+    const int n = (int)acts_done.size();
+    n_started[s] = n; n_ticks[s] = tick;
+    mean_act[s] = n ? (double)sum / (double)n : 0.0;
+    p99_act[s] = n ? acts_done[(size_t)((99 * (int64_t)n + 99) / 100) - 1] : -1;   // nearest rank
+  }
+}
+
+}  // extern "C"
