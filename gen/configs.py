@@ -384,3 +384,23 @@ def make_trace(S=4096, A=10_000, seed=4, contended=False, rate_per_s=50.0, horiz
         max_ticks=int(max_ticks if max_ticks is not None else 4 * int(horizon_s * 1e6 / tick_us)),
     )
     return t
+
+
+def slice_problem(p, snapshots):
+    """The sub-problem made of the listed snapshots (for oracle checks on samples of a big batch)."""
+    B, N, M = p["B"], p["N"], p["M"]
+    snapshots = list(snapshots)
+    q = dict(p)
+    q["B"] = len(snapshots)
+    for k in PROBLEM_ARRAYS + ("gpu_mask_",):
+        v = p.get(k)
+        if v is None or k in ("k_list", "type_k", "speedup_q16", "node_busy_off", "node_busy_rel_us"):
+            continue
+        per = len(v) // B
+        q[k] = np.concatenate([v[b * per:(b + 1) * per] for b in snapshots])
+    if p.get("node_busy_off") is not None:
+        off, rel = p["node_busy_off"], p["node_busy_rel_us"]
+        cnt = np.concatenate([np.diff(off[b * M:(b + 1) * M + 1]) for b in snapshots])
+        q["node_busy_off"] = np.concatenate([[0], np.cumsum(cnt)]).astype(np.int32)
+        q["node_busy_rel_us"] = np.concatenate([rel[off[b * M]:off[(b + 1) * M]] for b in snapshots] + [np.zeros(0, np.int64)])
+    return q

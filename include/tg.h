@@ -1,0 +1,208 @@
+/*
+ * tg.h - C interface of the action-level elastic scheduling step of ARL-Tangram
+ * (arXiv 2603.13019), batched over independent cluster snapshots and run on one AMD
+ * MI355X (gfx950) by hand-written HIP kernels.
+ *
+ * One scheduling step (Sec. 4.2, Alg. 1; Alg. 2-4 in App. A-B) takes the waiting queue W of
+ * actions in first-come order and the resource status R, and returns the selected actions
+ * with their resource units.  Here R is a set of nodes of three kinds (Sec. 5): CPU nodes
+ * (cores, scheduled per node, trajectories may be pinned to a node, Sec. 5.2), GPU nodes
+ * (buddy chunks of 1/2/4/8 GPUs, Sec. 5.3) and API quotas (Sec. 5.1).
+ *
+ * Conventions
+ *   - All times are int64 microseconds relative to the snapshot instant.  TG_INF marks a
+ *     candidate that does not exist.
+ *   - Every function returns TG_OK (0) or a negative TG_E_* code; on an error nothing has
+ *     been written to any output and nothing has been launched.
+ *   - "host" pointers are ordinary CPU memory, read only during the call.  "device" pointers
+ *     are HIP device memory owned by the caller (the Python binding allocates it with
+ *     PyTorch).  Kernels are enqueued on `hip_stream` (a hipStream_t, NULL = default stream);
+ *     no entry point synchronises except tg_build_problem / tg_build_trace (which return after
+ *     their host-to-device copies have completed).  Results are valid once the caller has
+ *     synchronised the stream.
+ *   - A tg_problem / tg_trace is immutable after it is built and owns only its packed device
+ *     copy of the inputs.  No other entry point allocates device memory.
+ *   - Index of an action inside its snapshot == its first-come rank == its action id.
+ */
+#ifndef TG_H_
+#define TG_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TG_INF INT64_MAX
+
+enum { TG_OK = 0, TG_E_INVALID_ARG = -1, TG_E_RANGE = -2, TG_E_ELASTICITY = -3, TG_E_WORKSPACE = -4,
+       TG_E_HIP = -5, TG_E_NOMEM = -6 };
+
+/* resource kinds (Sec. 5) and elasticity models of an action (Sec. 4.1, Eq. 1) */
+enum { TG_TYPE_CPU = 0, TG_TYPE_GPU = 1, TG_TYPE_API = 2, TG_N_TYPES = 3 };
+enum { TG_MODEL_NONE = 0,   /* elasticity unknown: runs for T_ori on its minimum units (Alg. 1 l.5-6) */
+       TG_MODEL_AMDAHL = 1, /* E(k) = 1/((1-p)k+p), p = act_param in parts per million             */
+       TG_MODEL_TABLE = 2   /* E(k)*k = speedup_q16[act_param][q] / 65536                           */ };
+/* why an action was not selected in this step */
+enum { TG_SELECTED = 0,
+       TG_DEFER_PREFIX = 1,     /* behind the first action of its pool that did not fit (Alg. 1 l.2) */
+       TG_DEFER_EVICTED = 2,    /* admitted, then evicted by the greedy tail eviction (Alg. 1 l.9-13) */
+       TG_DEFER_INFEASIBLE = 3  /* no allowed unit count fits any node it may use, or bad pin        */ };
+
+/* limits checked by tg_build_problem / tg_build_trace */
+enum { TG_MAX_K = 8, TG_MAX_UNIT = 64, TG_MAX_CPU_UNITS = 256, TG_MAX_GPU_UNITS = 64,
+       TG_MAX_CHUNK_STATES = 512, TG_MAX_DEPTH = 4,
+       TG_MAX_ACTIONS = 131072,      /* N, actions per snapshot / A, actions per scenario          */
+       TG_MAX_NODES_OF_KIND = 4096   /* nodes of one resource kind in one snapshot               */ };
+#define TG_T_ORI_LIMIT (1ll << 36)  /* 1 <= T_ori < 2^36 us                                      */
+#define TG_TIME_LIMIT (1ll << 40)   /* backlog, age, busy release times in [0, 2^40)              */
+#define TG_SUM_T_LIMIT (1ll << 44)  /* sum of T_ori over one snapshot / scenario                  */
+
+typedef struct tg_problem tg_problem; /* opaque */
+typedef struct tg_trace tg_trace;     /* opaque */
+
+/*
+ * B snapshots, each with N queued actions (W of Alg. 1, FCFS order) and M nodes (R of Alg. 1).
+ * All arrays are host memory.  Node arrays have B*M entries, action arrays B*N entries,
+ * snapshot-major.
+ */
+typedef struct {
+  int32_t B, N, M, K;
+  int32_t n_classes; /* rows of speedup_q16                                                     */
+  int32_t n_tasks;   /* act_task values are in [0, n_tasks); segment key of the per-task sums    */
+  int32_t depth;     /* options tried for the first waiting action in Alg. 2's estimate; 2 in the paper's runs */
+  uint32_t flags;    /* must be 0                                                                */
+  const int32_t *k_list;  /* [K] ascending unit counts (the discrete sets of Sec. 4.1), 1..TG_MAX_UNIT */
+  const int32_t *type_k;  /* [3] type t may use k_list[0 .. type_k[t]); GPU entries must be 1,2,4,8; API <= 1 */
+  const uint32_t *speedup_q16; /* [n_classes*K] round(65536*E(k_q)*k_q); nondecreasing in q, in [65536, 65536*k_q] */
+  /* nodes */
+  const uint8_t *node_type;        /* TG_TYPE_*                                                  */
+  const int32_t *node_cap;         /* units the node has (cores, GPUs, bucket size)              */
+  const int32_t *node_free;        /* units free for this step (<= cap); API: whole tokens available */
+  const int64_t *node_backlog_us;  /* time at which the free units become usable (queueing part of Eq. 2) */
+  const uint8_t *node_chunks;      /* [B*M*4] free chunks of 1,2,4,8 GPUs on GPU nodes; NULL: binary split of node_free */
+  const int32_t *node_busy_off;    /* [B*M+1] or NULL: CSR offsets into node_busy_rel_us         */
+  const int64_t *node_busy_rel_us; /* release time of every unit held by a running action (executing queue of Alg. 2) */
+  /* actions */
+  const uint8_t *act_type;        /* TG_TYPE_*: the key elasticity resource (Sec. 4.1)           */
+  const uint8_t *act_model;       /* TG_MODEL_*; API actions must be TG_MODEL_NONE               */
+  const int64_t *act_t_ori_us;    /* T_ori of Eq. 1: duration on one unit                        */
+  const int64_t *act_age_us;      /* time already spent queueing (added to the reported ACT only); may be NULL */
+  const uint32_t *act_kmask;      /* bit q set <=> k_list[q] is an allowed unit count            */
+  const uint32_t *act_param;      /* Amdahl: parallel fraction in ppm (<= 10^6); table: class id */
+  const int32_t *act_pin_node;    /* node index inside the snapshot, or negative = free to choose (Sec. 5.2) */
+  const int32_t *act_task;        /* may be NULL (all zero)                                      */
+} tg_problem_desc;
+
+/* Per-snapshot result of tg_assign.  Only mean_act_us and util are floating point. */
+typedef struct {
+  int64_t sum_act_us; /* sum of ACT over selected actions (Eq. 2)                               */
+  int32_t n_selected, n_prefix, n_evicted, n_infeasible;
+  int64_t units_used[3], units_free[3]; /* per resource kind                                    */
+  double mean_act_us;                   /* sum_act_us / n_selected, 0 if none                    */
+  double util[3];                       /* units_used / units_free, 0 if no free unit            */
+} tg_summary;
+
+/* Device output buffers of tg_assign ([B*N] unless noted); optional ones may be NULL. */
+typedef struct {
+  int32_t *node;         /* chosen node, -1 if not selected                                    */
+  int32_t *units;        /* allocated units k_i, 0 if not selected                              */
+  int64_t *act_us;       /* age + backlog[node] + getDur(k_i), -1 if not selected               */
+  uint8_t *defer_reason; /* TG_SELECTED / TG_DEFER_*                                            */
+  tg_summary *summary;   /* [B]                                                                 */
+  int32_t *node_used;    /* [B*M] units handed out per node; optional                           */
+  int64_t *task_sum_us;  /* [B*n_tasks] sum of ACT per task; optional                           */
+  int64_t *node_obj;     /* [B*M] final approximated objective (Alg. 2) of nodes that ran the eviction loop, else -1; optional */
+} tg_assign_out;
+
+/*
+ * Formulation (Sec. 4.1): validates the description, normalises every action to (kind, T_ori,
+ * allowed-unit mask, elasticity model and parameter, pin, FCFS rank), groups actions and nodes
+ * by resource kind and copies the packed arrays to the device.
+ * Errors: TG_E_INVALID_ARG (null pointer, bad count, unknown kind/model, k_list not ascending,
+ * free > cap, chunk counts that do not add up to node_free, ...), TG_E_RANGE (a time or size outside the
+ * limits above), TG_E_ELASTICITY (speedup table decreasing, above 65536*k or below 65536;
+ * Amdahl fraction above 10^6; class id out of range), TG_E_HIP, TG_E_NOMEM.
+ */
+int tg_build_problem(const tg_problem_desc *desc, void *hip_stream, tg_problem **out);
+void tg_free_problem(tg_problem *p);
+
+/* Number of (action, node, unit-option) candidates of the score tensor and its size in bytes. */
+int tg_num_candidates(const tg_problem *p, int64_t *count, int64_t *bytes);
+
+/* Device workspace tg_assign needs for this problem. */
+int tg_assign_workspace_bytes(const tg_problem *p, size_t *bytes);
+
+/*
+ * Score (Eq. 1 inside Eq. 2): estimated completion time of every type-compatible candidate,
+ *   cost[b][t][i][j][q] = node_backlog_us[j] + getDur_i(k_list[q])
+ * or TG_INF when k_list[q] is not allowed for action i, exceeds node j's capacity, or the
+ * action is pinned to another node.  Layout: for snapshot b = 0..B-1, for kind t = 0..2, a dense
+ * block [actions of kind t in FCFS order][nodes of kind t in index order][type_k[t]], q fastest.
+ * d_cost: device, tg_num_candidates() int64 values, 16-byte aligned, written completely.
+ */
+int tg_score_candidates(const tg_problem *p, int64_t *d_cost, void *hip_stream);
+
+/*
+ * Assign (Alg. 1 per resource pool): FCFS admission at minimum units with node choice by least
+ * estimated completion time (ties: smaller node index), then per node DPArrange (Alg. 3; Alg. 4's
+ * chunk states on GPU nodes) inside the greedy tail eviction on the approximated objective
+ * (Alg. 2), then per-snapshot summaries.
+ * d_cost: NULL, or a tensor written by tg_score_candidates for this problem; when given, the
+ * node choice reads its estimates from the tensor instead of recomputing them (same result).
+ * d_ws/ws_bytes: device workspace of at least tg_assign_workspace_bytes(), 256-byte aligned.
+ * Errors: TG_E_INVALID_ARG, TG_E_WORKSPACE, TG_E_HIP.
+ */
+int tg_assign(const tg_problem *p, const int64_t *d_cost, const tg_assign_out *out, void *d_ws, size_t ws_bytes,
+              void *hip_stream);
+
+/*
+ * S independent arrival traces replayed against their own clusters.  Every tick_us of simulated
+ * time: finished actions release their units, quotas refill (micro-tokens, capped at the bucket
+ * size node_cap), arrived actions join the waiting queue in arrival order, one scheduling step
+ * (as tg_assign, backlog 0, completion heap seeded with the running actions) selects actions,
+ * which start at the tick and run for exactly getDur(k).  Action arrays have S*A entries and
+ * must be sorted by arrival within a scenario; node arrays have S*M entries.
+ */
+typedef struct {
+  int32_t S, A, M, K, n_classes, depth;
+  int32_t max_ticks; /* the replay of a scenario stops after this many ticks                    */
+  uint32_t flags;    /* must be 0                                                               */
+  int64_t tick_us;   /* rescheduling period                                                     */
+  const int32_t *k_list, *type_k;
+  const uint32_t *speedup_q16;
+  const uint8_t *node_type;
+  const int32_t *node_cap;          /* CPU: cores (all free at time 0); GPU: must be 8; API: bucket size (burst) */
+  const int32_t *quota_rate;        /* tokens per second (API nodes)                              */
+  const int64_t *quota_tok0_micro;  /* tokens at time 0, in millionths                            */
+  const int64_t *arrival_us;        /* nondecreasing within a scenario, in [0, 2^40)              */
+  const uint8_t *act_type, *act_model;
+  const int64_t *act_t_ori_us;
+  const uint32_t *act_kmask, *act_param;
+  const int32_t *act_pin_node;
+} tg_trace_desc;
+
+/* Device outputs of tg_replay_trace. */
+typedef struct {
+  int64_t *start_us;  /* [S*A] tick at which the action started, -1 if it never did             */
+  int64_t *finish_us; /* [S*A] start + getDur(units), -1                                         */
+  int32_t *units;     /* [S*A]                                                                   */
+  int32_t *node;      /* [S*A]                                                                   */
+  double *mean_act_us; /* [S] mean of finish - arrival over started actions                      */
+  int64_t *p99_act_us; /* [S] nearest-rank 99th percentile of the same, -1 if none started        */
+  int32_t *n_started;  /* [S]                                                                    */
+  int32_t *n_ticks;    /* [S] ticks simulated                                                    */
+} tg_replay_out;
+
+int tg_build_trace(const tg_trace_desc *desc, void *hip_stream, tg_trace **out);
+void tg_free_trace(tg_trace *t);
+int tg_replay_workspace_bytes(const tg_trace *t, size_t *bytes);
+int tg_replay_trace(const tg_trace *t, const tg_replay_out *out, void *d_ws, size_t ws_bytes, void *hip_stream);
+
+const char *tg_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TG_H_ */

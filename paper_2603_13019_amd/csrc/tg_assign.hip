@@ -1,0 +1,235 @@
+// tg_assign: one scheduling step (Alg. 1 of the paper) for every snapshot of a problem.
+//
+//   tg_dur_kernel      Eq. 1 once per (action, option)              fully parallel
+//   tg_place_kernel    Alg. 1 l.1-2: FCFS admission at minimum units, node choice by least
+//                      estimated completion time (Eq. 2)            one wavefront per (snapshot, kind)
+//   tg_lists_kernel    groups admitted / waiting-pinned actions by node, FCFS inside a node
+//   tg_node_kernel     Alg. 1 l.3-14 per node: DPArrange (Alg. 3 / Alg. 4) + greedy tail
+//                      eviction on the approximated objective (Alg. 2)   one wavefront per node
+//   tg_summary_kernel  per-snapshot sums, counts, utilisation
+//
+// The FCFS loop is sequential by definition (every action sees the capacity left by the ones
+// before it), so tg_place_kernel keeps the node table of its pool in LDS and spends its 64
+// lanes on the argmin over nodes; parallelism comes from the batch of snapshots.
+#include "tg_step.h"
+
+namespace {
+
+struct AssignWs {
+  int64_t* dur;      // [B*N*K] getDur per option, TG_INF where the option is not allowed
+  int32_t* slot;     // [B*N]   position of an action inside its node's list
+  int32_t* order;    // [B*N]   admitted actions grouped by node
+  int32_t* dorder;   // [B*N]   waiting actions pinned to a node (deferred by the prefix rule)
+  int32_t *nl_off, *nl_cnt, *dl_off, *dl_cnt;   // [B*M] list extents per node
+};
+
+size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+
+size_t carve(const tg_problem* p, char* base, AssignWs* w) {
+  const size_t nA = (size_t)p->dev.B * p->dev.N, nN = (size_t)p->dev.B * p->dev.M;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { char* r = base + off; off += align256(bytes); return r; };
+  char* a = take(nA * p->dev.K * 8); char* b = take(nA * 4); char* c = take(nA * 4); char* d = take(nA * 4);
+  char* e = take(nN * 4); char* f = take(nN * 4); char* g = take(nN * 4); char* h = take(nN * 4);
+  if (w) {
+    w->dur = (int64_t*)a; w->slot = (int32_t*)b; w->order = (int32_t*)c; w->dorder = (int32_t*)d;
+    w->nl_off = (int32_t*)e; w->nl_cnt = (int32_t*)f; w->dl_off = (int32_t*)g; w->dl_cnt = (int32_t*)h;
+  }
+  return off;
+}
+
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void tg_dur_kernel(TgDev P, int64_t* __restrict__ dur) {
+  const size_t x = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t total = (size_t)P.B * P.N * P.K;
+  if (x >= total) return;
+  const size_t g = x / P.K;
+  const int q = (int)(x - g * P.K);
+  int64_t d = TG_INF;
+  if (P.act_kmask[g] >> q & 1u) {
+    const int model = P.act_model[g];
+    const uint32_t param = P.act_param[g];
+    const uint32_t sp = model == TG_MODEL_TABLE ? P.speedup[param * P.K + q] : 0u;
+    d = tg_duration(model, P.act_T[g], param, P.k_list[q], sp);
+  }
+  dur[x] = d;
+}
+
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(TG_WAVE) void tg_place_kernel(TgDev P, const int64_t* __restrict__ dur,
+                                                           const int64_t* __restrict__ cost,
+                                                           const TgBlock* __restrict__ blocks, AssignWs W,
+                                                           tg_assign_out O, int lds_nodes) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  TgPoolLds S;
+  tg_pool_lds_carve(smem, lds_nodes, &S);
+  const int b = blockIdx.x / 3, t = blockIdx.x - 3 * b, lane = threadIdx.x;
+  const int a0 = P.tact_off[b * 4 + t], Nt = P.tact_off[b * 4 + t + 1] - a0;
+  const int n0 = P.tnode_off[b * 4 + t], Mt = P.tnode_off[b * 4 + t + 1] - n0;
+  const size_t abase = (size_t)b * P.N, nbase = (size_t)b * P.M;
+  const int32_t* acts = P.tact_idx + abase + a0;
+  const int32_t* nodes = P.tnode_idx + nbase + n0;
+  if (lane < TG_MAX_K) S.k[lane] = P.k_list[lane];
+  for (int r = lane; r < Mt; r += TG_WAVE) {
+    const size_t g = nbase + nodes[r];
+    S.back[r] = P.node_backlog[g];
+    S.lim[r] = t == TG_TYPE_GPU ? (int32_t)P.node_chunks[g] : P.node_free[g];
+    S.cnt[r] = 0; S.dcnt[r] = 0; S.closed[r] = 0;
+  }
+  __syncthreads();
+
+  TgPlaceIo io;
+  io.act_kmask = P.act_kmask + abase; io.act_static = P.act_static + abase; io.act_pin = P.act_pin + abase;
+  io.node_rank = P.node_rank + nbase; io.nodes = nodes; io.dur = dur + abase * P.K; io.K = P.K; io.Kt = P.type_k[t];
+  io.cost = nullptr; io.cost_row_len = 0;
+  if (cost) { const TgBlock blk = blocks[b * 3 + t]; io.cost = cost + blk.cost_off; io.cost_row_len = blk.M_t * blk.K_t; }
+  io.out_node = O.node + abase; io.out_units = O.units + abase; io.out_act = O.act_us + abase;
+  io.out_reason = O.defer_reason + abase; io.slot = W.slot + abase;
+  tg_place_pool(S, io, acts, Nt, Mt, t == TG_TYPE_GPU, lane);
+
+  // list extents per node (exclusive scan of the per-node counts, in node order of this kind)
+  int run = a0, drun = a0;
+  for (int base = 0; base < Mt; base += TG_WAVE) {
+    const int r = base + lane;
+    const int c = r < Mt ? S.cnt[r] : 0, dc = r < Mt ? S.dcnt[r] : 0;
+    int inc = c, dinc = dc;
+    for (int o = 1; o < TG_WAVE; o <<= 1) {
+      const int u = __shfl_up(inc, o), du = __shfl_up(dinc, o);
+      if (lane >= o) { inc += u; dinc += du; }
+    }
+    if (r < Mt) {
+      const size_t g = nbase + nodes[r];
+      W.nl_off[g] = run + inc - c; W.nl_cnt[g] = c;
+      W.dl_off[g] = drun + dinc - dc; W.dl_cnt[g] = dc;
+    }
+    run += __shfl(inc, TG_WAVE - 1);
+    drun += __shfl(dinc, TG_WAVE - 1);
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void tg_lists_kernel(TgDev P, AssignWs W, tg_assign_out O) {
+  const size_t g = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (g >= (size_t)P.B * P.N) return;
+  const int b = (int)(g / P.N), i = (int)(g - (size_t)b * P.N);
+  const int r = O.defer_reason[g];
+  if (r == TG_SELECTED) {
+    const size_t n = (size_t)b * P.M + O.node[g];
+    W.order[(size_t)b * P.N + W.nl_off[n] + W.slot[g]] = i;
+  } else if (r == TG_DEFER_PREFIX && P.act_pin[g] >= 0) {
+    const size_t n = (size_t)b * P.M + P.act_pin[g];
+    W.dorder[(size_t)b * P.N + W.dl_off[n] + W.slot[g]] = i;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(TG_WAVE) void tg_node_kernel(TgDev P, const int64_t* __restrict__ dur, AssignWs W,
+                                                          tg_assign_out O, TgNodeLdsPlan plan) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  const int gn = blockIdx.x, lane = threadIdx.x;
+  const int b = gn / P.M;
+  const size_t abase = (size_t)b * P.N;
+  if (O.node_obj && lane == 0) O.node_obj[gn] = -1;
+  const int m = W.nl_cnt[gn];
+  if (m == 0) return;
+  TgNodeIn in;
+  in.type = P.node_type[gn]; in.cap = P.node_cap[gn]; in.free_units = P.node_free[gn];
+  in.backlog = P.node_backlog[gn]; in.chunks = P.node_chunks[gn];
+  in.m = m; in.clist = W.order + abase + W.nl_off[gn];
+  in.nd = W.dl_cnt[gn]; in.dlist = W.dorder + abase + W.dl_off[gn];
+  in.n_busy = P.has_busy ? P.node_busy_off[gn + 1] - P.node_busy_off[gn] : 0;
+  in.busy = P.node_busy_rel + (P.has_busy ? P.node_busy_off[gn] : 0);
+
+  in.act_model = P.act_model + abase; in.act_kmask = P.act_kmask + abase; in.dur = dur + abase * P.K;
+  in.K = P.K; in.depth = P.depth;
+  for (int q = 0; q < TG_MAX_K; ++q) in.k_list[q] = P.k_list[q];
+  TgNodeOut out;
+  out.node = O.node + abase; out.units = O.units + abase; out.act = O.act_us + abase; out.reason = O.defer_reason + abase;
+  out.age = P.act_age + abase;
+  const int64_t obj = tg_node_schedule(smem, plan, in, out, lane);
+  if (O.node_obj && lane == 0) O.node_obj[gn] = obj;
+}
+
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void tg_summary_kernel(TgDev P, tg_assign_out O) {
+  __shared__ long long s_sum;
+  __shared__ int s_cnt[4];
+  __shared__ long long s_used[3], s_free[3];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const size_t abase = (size_t)b * P.N, nbase = (size_t)b * P.M;
+  if (tid == 0) s_sum = 0;
+  if (tid < 4) s_cnt[tid] = 0;
+  if (tid < 3) { s_used[tid] = 0; s_free[tid] = 0; }
+  if (O.node_used) for (int j = tid; j < P.M; j += 256) O.node_used[nbase + j] = 0;
+  if (O.task_sum_us) for (int k = tid; k < P.n_tasks; k += 256) O.task_sum_us[(size_t)b * P.n_tasks + k] = 0;
+  __syncthreads();
+  long long sum = 0, used[3] = {0, 0, 0}, fr[3] = {0, 0, 0};
+  int cnt[4] = {0, 0, 0, 0};
+  for (int i = tid; i < P.N; i += 256) {
+    const size_t g = abase + i;
+    const int r = O.defer_reason[g];
+    ++cnt[r];
+    if (r == TG_SELECTED) {
+      const long long a = O.act_us[g];
+      const int u = O.units[g];
+      sum += a;
+      used[P.act_type[g]] += u;
+      if (O.node_used) atomicAdd(&O.node_used[nbase + O.node[g]], u);
+      if (O.task_sum_us) atomicAdd((unsigned long long*)&O.task_sum_us[(size_t)b * P.n_tasks + P.act_task[g]], (unsigned long long)a);
+    }
+  }
+  for (int j = tid; j < P.M; j += 256) fr[P.node_type[nbase + j]] += P.node_free[nbase + j];
+  atomicAdd((unsigned long long*)&s_sum, (unsigned long long)sum);
+  for (int k = 0; k < 4; ++k) if (cnt[k]) atomicAdd(&s_cnt[k], cnt[k]);
+  for (int k = 0; k < 3; ++k) {
+    if (used[k]) atomicAdd((unsigned long long*)&s_used[k], (unsigned long long)used[k]);
+    if (fr[k]) atomicAdd((unsigned long long*)&s_free[k], (unsigned long long)fr[k]);
+  }
+  __syncthreads();
+  if (tid == 0) {
+    tg_summary s;
+    s.sum_act_us = s_sum;
+    s.n_selected = s_cnt[0]; s.n_prefix = s_cnt[1]; s.n_evicted = s_cnt[2]; s.n_infeasible = s_cnt[3];
+    for (int k = 0; k < 3; ++k) {
+      s.units_used[k] = s_used[k]; s.units_free[k] = s_free[k];
+      s.util[k] = s_free[k] ? (double)s_used[k] / (double)s_free[k] : 0.0;
+    }
+    s.mean_act_us = s_cnt[0] ? (double)s_sum / (double)s_cnt[0] : 0.0;
+    O.summary[b] = s;
+  }
+}
+
+}  // namespace
+
+extern "C" int tg_assign_workspace_bytes(const tg_problem* p, size_t* bytes) {
+  if (!p || !bytes) return TG_E_INVALID_ARG;
+  *bytes = carve(p, nullptr, nullptr);
+  return TG_OK;
+}
+
+extern "C" int tg_assign(const tg_problem* p, const int64_t* d_cost, const tg_assign_out* out, void* d_ws,
+                         size_t ws_bytes, void* hip_stream) {
+  if (!p || !out || !out->node || !out->units || !out->act_us || !out->defer_reason || !out->summary)
+    return TG_E_INVALID_ARG;
+  if (!d_ws || ((uintptr_t)d_ws & 255) || ws_bytes < carve(p, nullptr, nullptr)) return TG_E_WORKSPACE;
+  hipStream_t s = (hipStream_t)hip_stream;
+  const TgDev& P = p->dev;
+  AssignWs W;
+  carve(p, (char*)d_ws, &W);
+  const size_t nA = (size_t)P.B * P.N;
+
+  const size_t place_lds = tg_pool_lds_bytes(p->max_nodes_of_kind);
+  const TgNodeLdsPlan plan = tg_node_lds_plan(p->max_free_cpu, p->max_free_gpu, p->max_chunk_states, p->max_heap, P.K);
+  if (place_lds > 64 * 1024)
+    TG_HIP_CHECK(hipFuncSetAttribute((const void*)tg_place_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)place_lds));
+  if (plan.total > 64 * 1024)
+    TG_HIP_CHECK(hipFuncSetAttribute((const void*)tg_node_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, plan.total));
+
+  hipLaunchKernelGGL(tg_dur_kernel, dim3((unsigned)((nA * P.K + 255) / 256)), dim3(256), 0, s, P, W.dur);
+  hipLaunchKernelGGL(tg_place_kernel, dim3(P.B * 3), dim3(TG_WAVE), place_lds, s, P, W.dur, d_cost, p->d_blocks, W, *out,
+                     p->max_nodes_of_kind);
+  hipLaunchKernelGGL(tg_lists_kernel, dim3((unsigned)((nA + 255) / 256)), dim3(256), 0, s, P, W, *out);
+  hipLaunchKernelGGL(tg_node_kernel, dim3(P.B * P.M), dim3(TG_WAVE), plan.total, s, P, W.dur, W, *out, plan);
+  hipLaunchKernelGGL(tg_summary_kernel, dim3(P.B), dim3(256), 0, s, P, *out);
+  return hipGetLastError() == hipSuccess ? TG_OK : TG_E_HIP;
+}

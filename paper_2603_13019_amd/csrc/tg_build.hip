@@ -1,0 +1,284 @@
+// Formulation stage (Sec. 4.1 of the paper): validate a problem description, normalise every
+// action and node, group them by resource kind and ship one packed copy to the device.
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "tg_internal.h"
+
+namespace {
+
+// Host staging buffer laid out exactly like the device arena.
+struct Arena {
+  std::vector<char> host;
+  size_t add(size_t bytes) {
+    size_t off = (host.size() + 255) & ~size_t(255);
+    host.resize(off + bytes, 0);
+    return off;
+  }
+  template <class T> T* at(size_t off) { return reinterpret_cast<T*>(host.data() + off); }
+};
+
+bool is_pow2_le8(int k) { return k == 1 || k == 2 || k == 4 || k == 8; }
+
+int check_tables(int K, int n_classes, const int32_t* k_list, const int32_t* type_k, const uint32_t* speedup) {
+  if (K < 1 || K > TG_MAX_K || !k_list || !type_k || n_classes < 0) return TG_E_INVALID_ARG;
+  for (int q = 0; q < K; ++q) {
+    if (k_list[q] < 1 || k_list[q] > TG_MAX_UNIT) return TG_E_INVALID_ARG;
+    if (q && k_list[q] <= k_list[q - 1]) return TG_E_INVALID_ARG;
+  }
+  for (int t = 0; t < TG_N_TYPES; ++t)
+    if (type_k[t] < 0 || type_k[t] > K) return TG_E_INVALID_ARG;
+  if (type_k[TG_TYPE_API] > 1) return TG_E_INVALID_ARG;
+  for (int q = 0; q < type_k[TG_TYPE_GPU]; ++q)
+    if (!is_pow2_le8(k_list[q])) return TG_E_INVALID_ARG;
+  if (n_classes > 0) {
+    if (!speedup) return TG_E_INVALID_ARG;
+    for (int c = 0; c < n_classes; ++c)
+      for (int q = 0; q < K; ++q) {
+        const uint32_t s = speedup[c * K + q];
+        if (s < 65536u || s > 65536u * (uint32_t)k_list[q]) return TG_E_ELASTICITY;  // 1/k <= E(k) <= 1
+        if (q && s < speedup[c * K + q - 1]) return TG_E_ELASTICITY;                 // E(k) k must not shrink
+      }
+  }
+  return TG_OK;
+}
+
+int chunk_states(const uint8_t c[4]) {
+  int s = 1;
+  for (int x = 0; x < 4; ++x) s *= (std::max<int>(c[x], 1) + 1);
+  return s;
+}
+
+}  // namespace
+
+extern "C" const char* tg_strerror(int code) {
+  switch (code) {
+    case TG_OK: return "ok";
+    case TG_E_INVALID_ARG: return "invalid argument";
+    case TG_E_RANGE: return "value outside the supported range";
+    case TG_E_ELASTICITY: return "elasticity description violates 0 < E(k) <= 1 or E(k) k nondecreasing";
+    case TG_E_WORKSPACE: return "workspace missing, misaligned or too small";
+    case TG_E_HIP: return "HIP runtime call failed";
+    case TG_E_NOMEM: return "out of memory";
+    default: return "unknown error";
+  }
+}
+
+extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_problem** out) {
+  if (!d || !out) return TG_E_INVALID_ARG;
+  *out = nullptr;
+  const int B = d->B, N = d->N, M = d->M, K = d->K;
+  if (B < 1 || N < 1 || M < 1 || d->flags != 0 || d->n_tasks < 1) return TG_E_INVALID_ARG;
+  if (d->depth < 1 || d->depth > TG_MAX_DEPTH) return TG_E_INVALID_ARG;
+  if ((int64_t)B * N >= (1ll << 31) || (int64_t)B * M >= (1ll << 31) || N > TG_MAX_ACTIONS) return TG_E_RANGE;
+  int rc = check_tables(K, d->n_classes, d->k_list, d->type_k, d->speedup_q16);
+  if (rc) return rc;
+  if (!d->node_type || !d->node_cap || !d->node_free || !d->node_backlog_us) return TG_E_INVALID_ARG;
+  if (!d->act_type || !d->act_model || !d->act_t_ori_us || !d->act_kmask || !d->act_param || !d->act_pin_node)
+    return TG_E_INVALID_ARG;
+  if (d->node_busy_off && !d->node_busy_rel_us && d->node_busy_off[(size_t)B * M] > 0) return TG_E_INVALID_ARG;
+
+  const size_t nN = (size_t)B * M, nA = (size_t)B * N;
+  tg_problem* p = new (std::nothrow) tg_problem();
+  if (!p) return TG_E_NOMEM;
+  std::memset(p, 0, sizeof *p);
+  Arena ar;
+  try {
+    // ---------------- nodes
+    const size_t o_ntype = ar.add(nN), o_ncap = ar.add(nN * 4), o_nfree = ar.add(nN * 4), o_nback = ar.add(nN * 8),
+                 o_nchunk = ar.add(nN * 4), o_nboff = ar.add((nN + 1) * 4), o_nrank = ar.add(nN * 4),
+                 o_tnidx = ar.add(nN * 4), o_tnoff = ar.add((size_t)B * 4 * 4);
+    const size_t n_busy = d->node_busy_off ? (size_t)d->node_busy_off[nN] : 0;
+    const size_t o_nbrel = ar.add(std::max<size_t>(n_busy, 1) * 8);
+    std::vector<int> max_cap((size_t)B * 3, -1);
+    int max_kind = 0, max_free_cpu = 0, max_heap = 0, max_free_gpu = 0, max_states = 1;
+    for (int b = 0; b < B; ++b) {
+      int cnt[3] = {0, 0, 0};
+      for (int j = 0; j < M; ++j) {
+        const size_t g = (size_t)b * M + j;
+        const int t = d->node_type[g], cap = d->node_cap[g], fr = d->node_free[g];
+        if (t >= TG_N_TYPES || cap < 0 || fr < 0 || fr > cap) { delete p; return TG_E_INVALID_ARG; }
+        if ((t == TG_TYPE_CPU && cap > TG_MAX_CPU_UNITS) || (t == TG_TYPE_GPU && cap > TG_MAX_GPU_UNITS)) { delete p; return TG_E_RANGE; }
+        const int64_t bl = d->node_backlog_us[g];
+        if (bl < 0 || bl >= TG_TIME_LIMIT) { delete p; return TG_E_RANGE; }
+        int nb = 0;
+        if (d->node_busy_off) {
+          nb = d->node_busy_off[g + 1] - d->node_busy_off[g];
+          if (nb < 0 || d->node_busy_off[0] != 0) { delete p; return TG_E_INVALID_ARG; }
+          if (nb > 0 && (t == TG_TYPE_API || nb > cap - fr)) { delete p; return TG_E_INVALID_ARG; }
+          for (int x = 0; x < nb; ++x) {
+            const int64_t r = d->node_busy_rel_us[d->node_busy_off[g] + x];
+            if (r < 0 || r >= TG_TIME_LIMIT) { delete p; return TG_E_RANGE; }
+          }
+        }
+        uint8_t ch[4] = {0, 0, 0, 0};
+        if (t == TG_TYPE_GPU) {
+          if (d->node_chunks) std::memcpy(ch, d->node_chunks + g * 4, 4);
+          else { ch[3] = (uint8_t)(fr / 8); ch[2] = (fr >> 2) & 1; ch[1] = (fr >> 1) & 1; ch[0] = fr & 1; }
+          if (ch[0] + 2 * ch[1] + 4 * ch[2] + 8 * ch[3] != fr) { delete p; return TG_E_INVALID_ARG; }
+          if (chunk_states(ch) > TG_MAX_CHUNK_STATES) { delete p; return TG_E_RANGE; }
+          max_states = std::max(max_states, chunk_states(ch));
+          max_free_gpu = std::max(max_free_gpu, fr);
+        }
+        if (t == TG_TYPE_CPU) max_free_cpu = std::max(max_free_cpu, fr);
+        if (t != TG_TYPE_API) max_heap = std::max(max_heap, fr + nb);
+        ar.at<uint8_t>(o_ntype)[g] = (uint8_t)t;
+        ar.at<int32_t>(o_ncap)[g] = cap;
+        ar.at<int32_t>(o_nfree)[g] = fr;
+        ar.at<int64_t>(o_nback)[g] = bl;
+        ar.at<uint32_t>(o_nchunk)[g] = ch[0] | ch[1] << 8 | ch[2] << 16 | (uint32_t)ch[3] << 24;
+        ar.at<int32_t>(o_nboff)[g] = d->node_busy_off ? d->node_busy_off[g] : 0;
+        ar.at<int32_t>(o_nrank)[g] = cnt[t]++;
+        max_cap[(size_t)b * 3 + t] = std::max(max_cap[(size_t)b * 3 + t], cap);
+      }
+      int32_t* off = ar.at<int32_t>(o_tnoff) + (size_t)b * 4;
+      off[0] = 0; off[1] = cnt[0]; off[2] = cnt[0] + cnt[1]; off[3] = M;
+      int fill[3] = {off[0], off[1], off[2]};
+      for (int j = 0; j < M; ++j) {
+        const int t = d->node_type[(size_t)b * M + j];
+        ar.at<int32_t>(o_tnidx)[(size_t)b * M + fill[t]++] = j;
+      }
+      for (int t = 0; t < 3; ++t) max_kind = std::max(max_kind, cnt[t]);
+      if (max_kind > TG_MAX_NODES_OF_KIND) { delete p; return TG_E_RANGE; }
+    }
+    ar.at<int32_t>(o_nboff)[nN] = (int32_t)n_busy;
+    if (n_busy) std::memcpy(ar.at<int64_t>(o_nbrel), d->node_busy_rel_us, n_busy * 8);
+
+    // ---------------- actions
+    const size_t o_atype = ar.add(nA), o_amodel = ar.add(nA), o_astat = ar.add(nA), o_aT = ar.add(nA * 8),
+                 o_aage = ar.add(nA * 8), o_amask = ar.add(nA * 4), o_aparam = ar.add(nA * 4), o_apin = ar.add(nA * 4),
+                 o_atask = ar.add(nA * 4), o_taidx = ar.add(nA * 4), o_taoff = ar.add((size_t)B * 4 * 4);
+    for (int b = 0; b < B; ++b) {
+      int cnt[3] = {0, 0, 0};
+      int64_t sumT = 0;
+      for (int i = 0; i < N; ++i) {
+        const size_t g = (size_t)b * N + i;
+        const int t = d->act_type[g], model = d->act_model[g];
+        if (t >= TG_N_TYPES || model > TG_MODEL_TABLE) { delete p; return TG_E_INVALID_ARG; }
+        if (t == TG_TYPE_API && model != TG_MODEL_NONE) { delete p; return TG_E_INVALID_ARG; }
+        const int64_t T = d->act_t_ori_us[g], age = d->act_age_us ? d->act_age_us[g] : 0;
+        if (T < 1 || T >= TG_T_ORI_LIMIT || age < 0 || age >= TG_TIME_LIMIT) { delete p; return TG_E_RANGE; }
+        sumT += T;
+        const uint32_t param = d->act_param[g];
+        if (model == TG_MODEL_AMDAHL && param > 1000000u) { delete p; return TG_E_ELASTICITY; }
+        if (model == TG_MODEL_TABLE && param >= (uint32_t)d->n_classes) { delete p; return TG_E_ELASTICITY; }
+        const int task = d->act_task ? d->act_task[g] : 0;
+        if (task < 0 || task >= d->n_tasks) { delete p; return TG_E_INVALID_ARG; }
+        uint32_t mask = d->act_kmask[g] & ((1u << d->type_k[t]) - 1u);
+        if (model == TG_MODEL_NONE) mask &= (~mask + 1u);            // minimum units only
+        int pin = d->act_pin_node[g];
+        if (pin < 0) pin = -1;
+        bool infeasible = mask == 0;
+        if (!infeasible) {
+          const int kmin = d->k_list[__builtin_ctz(mask)];
+          if (pin >= 0) infeasible = pin >= M || d->node_type[(size_t)b * M + pin] != t || kmin > d->node_cap[(size_t)b * M + pin];
+          else infeasible = kmin > max_cap[(size_t)b * 3 + t];
+        }
+        if (pin >= M) pin = M;                                       // any out-of-range pin: matches no node
+        ar.at<uint8_t>(o_atype)[g] = (uint8_t)t;
+        ar.at<uint8_t>(o_amodel)[g] = (uint8_t)model;
+        ar.at<uint8_t>(o_astat)[g] = infeasible;
+        ar.at<int64_t>(o_aT)[g] = T;
+        ar.at<int64_t>(o_aage)[g] = age;
+        ar.at<uint32_t>(o_amask)[g] = mask;
+        ar.at<uint32_t>(o_aparam)[g] = param;
+        ar.at<int32_t>(o_apin)[g] = pin;
+        ar.at<int32_t>(o_atask)[g] = task;
+        ++cnt[t];
+      }
+      if (sumT >= TG_SUM_T_LIMIT) { delete p; return TG_E_RANGE; }
+      int32_t* off = ar.at<int32_t>(o_taoff) + (size_t)b * 4;
+      off[0] = 0; off[1] = cnt[0]; off[2] = cnt[0] + cnt[1]; off[3] = N;
+      int fill[3] = {off[0], off[1], off[2]};
+      for (int i = 0; i < N; ++i) {
+        const int t = d->act_type[(size_t)b * N + i];
+        ar.at<int32_t>(o_taidx)[(size_t)b * N + fill[t]++] = i;
+      }
+    }
+    const size_t o_speed = ar.add(std::max<size_t>((size_t)d->n_classes * K, 1) * 4);
+    if (d->n_classes) std::memcpy(ar.at<uint32_t>(o_speed), d->speedup_q16, (size_t)d->n_classes * K * 4);
+
+    // ---------------- blocks of the score tensor and the score kernel's work split
+    const size_t o_blocks = ar.add((size_t)B * 3 * sizeof(TgBlock));
+    int64_t total = 0, wgs = 0;
+    int lds_nodes = 1;
+    for (int b = 0; b < B; ++b)
+      for (int t = 0; t < 3; ++t) {
+        TgBlock& k = ar.at<TgBlock>(o_blocks)[(size_t)b * 3 + t];
+        const int32_t* ta = ar.at<int32_t>(o_taoff) + (size_t)b * 4;
+        const int32_t* tn = ar.at<int32_t>(o_tnoff) + (size_t)b * 4;
+        k.b = b; k.t = t; k.rows = ta[t + 1] - ta[t]; k.M_t = tn[t + 1] - tn[t]; k.K_t = d->type_k[t];
+        k.entries = (int64_t)k.rows * k.M_t * k.K_t;
+        if (k.entries >= (1ll << 31)) { delete p; return TG_E_RANGE; }
+        k.cost_off = total;
+        // entries per workgroup: at most 8192, fewer when rows are so short that the per-row
+        // duration table (2048 values in LDS) would overflow
+        int span = 8192;
+        const int64_t lr = (int64_t)k.M_t * k.K_t;
+        while (span > 512 && lr > 0 && (span / lr + 2) * k.K_t > 2048) span -= 512;
+        k.span = span;
+        k.wg_off = (int32_t)wgs;
+        wgs += (k.entries + span - 1) / span;
+        total += k.entries;
+        if (k.entries) lds_nodes = std::max<int>(lds_nodes, k.M_t);
+      }
+    if (wgs >= (1ll << 31)) { delete p; return TG_E_RANGE; }
+
+    // ---------------- ship
+    p->arena_bytes = ar.host.size();
+    if (hipMalloc(&p->d_arena, p->arena_bytes) != hipSuccess) { delete p; return TG_E_NOMEM; }
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (hipMemcpyAsync(p->d_arena, ar.host.data(), p->arena_bytes, hipMemcpyHostToDevice, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess) {
+      hipFree(p->d_arena); delete p; return TG_E_HIP;
+    }
+    char* base = (char*)p->d_arena;
+    TgDev& v = p->dev;
+    v.B = B; v.N = N; v.M = M; v.K = K; v.n_classes = d->n_classes; v.n_tasks = d->n_tasks; v.depth = d->depth;
+    v.has_busy = n_busy > 0;
+    for (int q = 0; q < TG_MAX_K; ++q) v.k_list[q] = q < K ? d->k_list[q] : 0;
+    for (int t = 0; t < 3; ++t) v.type_k[t] = d->type_k[t];
+    v.type_k[3] = 0;
+    v.node_type = (const uint8_t*)(base + o_ntype); v.node_cap = (const int32_t*)(base + o_ncap);
+    v.node_free = (const int32_t*)(base + o_nfree); v.node_backlog = (const int64_t*)(base + o_nback);
+    v.node_chunks = (const uint32_t*)(base + o_nchunk); v.node_busy_off = (const int32_t*)(base + o_nboff);
+    v.node_busy_rel = (const int64_t*)(base + o_nbrel); v.node_rank = (const int32_t*)(base + o_nrank);
+    v.act_type = (const uint8_t*)(base + o_atype); v.act_model = (const uint8_t*)(base + o_amodel);
+    v.act_static = (const uint8_t*)(base + o_astat); v.act_T = (const int64_t*)(base + o_aT);
+    v.act_age = (const int64_t*)(base + o_aage); v.act_kmask = (const uint32_t*)(base + o_amask);
+    v.act_param = (const uint32_t*)(base + o_aparam); v.act_pin = (const int32_t*)(base + o_apin);
+    v.act_task = (const int32_t*)(base + o_atask); v.speedup = (const uint32_t*)(base + o_speed);
+    v.tact_idx = (const int32_t*)(base + o_taidx); v.tact_off = (const int32_t*)(base + o_taoff);
+    v.tnode_idx = (const int32_t*)(base + o_tnidx); v.tnode_off = (const int32_t*)(base + o_tnoff);
+    p->d_blocks = (TgBlock*)(base + o_blocks);
+    p->n_blocks = B * 3;
+    p->score_wgs = (int)wgs;
+    p->n_candidates = total;
+    p->max_nodes_of_kind = max_kind;
+    p->max_free_cpu = max_free_cpu;
+    p->max_heap = max_heap;
+    p->max_free_gpu = max_free_gpu;
+    p->max_chunk_states = max_states;
+    p->score_lds_nodes = lds_nodes;
+  } catch (const std::bad_alloc&) {
+    delete p;
+    return TG_E_NOMEM;
+  }
+  *out = p;
+  return TG_OK;
+}
+
+extern "C" void tg_free_problem(tg_problem* p) {
+  if (!p) return;
+  if (p->d_arena) (void)hipFree(p->d_arena);
+  delete p;
+}
+
+extern "C" int tg_num_candidates(const tg_problem* p, int64_t* count, int64_t* bytes) {
+  if (!p) return TG_E_INVALID_ARG;
+  if (count) *count = p->n_candidates;
+  if (bytes) *bytes = p->n_candidates * 8;
+  return TG_OK;
+}

@@ -1,0 +1,126 @@
+// Internal definitions shared by the HIP sources of libtangram (not part of the C interface).
+#ifndef TG_INTERNAL_H_
+#define TG_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tg.h"
+
+#define TG_WAVE 64
+
+// Packed device copy of a problem.  Passed to kernels by value; all pointers are device memory.
+struct TgDev {
+  int B, N, M, K, n_classes, n_tasks, depth, has_busy;
+  int k_list[TG_MAX_K];
+  int type_k[4];
+  // nodes [B*M]
+  const uint8_t* node_type;
+  const int32_t* node_cap;
+  const int32_t* node_free;
+  const int64_t* node_backlog;
+  const uint32_t* node_chunks;    // four 8-bit counts of free chunks (sizes 1,2,4,8), GPU nodes
+  const int32_t* node_busy_off;   // [B*M+1]
+  const int64_t* node_busy_rel;
+  const int32_t* node_rank;       // rank of the node among the nodes of its kind in its snapshot
+  // actions [B*N]
+  const uint8_t* act_type;
+  const uint8_t* act_model;
+  const uint8_t* act_static;      // 1: statically infeasible (no option, bad pin, minimum above every node)
+  const int64_t* act_T;
+  const int64_t* act_age;
+  const uint32_t* act_kmask;      // effective mask: limited to the kind's options, lowest bit only if non-elastic
+  const uint32_t* act_param;
+  const int32_t* act_pin;         // node index or -1
+  const int32_t* act_task;
+  const uint32_t* speedup;        // [n_classes*K]
+  // grouping by resource kind, per snapshot
+  const int32_t* tact_idx;        // [B*N] action ids grouped by kind, FCFS inside a group
+  const int32_t* tact_off;        // [B*4] group starts (entry 3 = N)
+  const int32_t* tnode_idx;       // [B*M] node ids grouped by kind
+  const int32_t* tnode_off;       // [B*4]
+};
+
+// One dense block of the score tensor: actions of one kind x nodes of that kind x options.
+struct TgBlock {
+  int64_t cost_off;   // first entry of the block in the tensor
+  int64_t entries;    // rows * M_t * K_t
+  int32_t wg_off;     // first workgroup of the score kernel that works on this block
+  int32_t span;       // entries per workgroup
+  int32_t rows, M_t, K_t, b, t, pad_;
+};
+
+struct tg_problem {
+  TgDev dev;
+  void* d_arena;
+  size_t arena_bytes;
+  TgBlock* d_blocks;       // inside the arena
+  int n_blocks;
+  int score_wgs;
+  int64_t n_candidates;
+  int max_nodes_of_kind;   // largest M_t over all snapshots and kinds
+  int max_free_cpu;        // largest node_free over CPU nodes
+  int max_heap;            // largest free + busy over CPU and GPU nodes
+  int max_free_gpu, max_chunk_states;
+  int score_lds_nodes;     // node-table window of the score kernel
+};
+
+__host__ __device__ static inline int tg_chunk_level(int k) { return k <= 1 ? 0 : (k <= 2 ? 1 : (k <= 4 ? 2 : 3)); }
+
+#ifdef __HIPCC__
+// Eq. 1 in integer microseconds: ceil(num / den) with num < 2^62 and 2^10 <= den < 2^27.
+// A double-precision reciprocal gives the quotient to within a few units; the remainder test
+// makes it exact.
+__device__ static inline int64_t tg_ceil_div(uint64_t num, uint32_t den) {
+  uint64_t q = (uint64_t)((double)num * (1.0 / (double)den));
+  int64_t r = (int64_t)(num - q * (uint64_t)den);
+  while (r < 0) { --q; r += den; }
+  while (r >= (int64_t)den) { ++q; r -= den; }
+  return (int64_t)(q + (r > 0));
+}
+
+// getDur(k_list[q]) of one action (Eq. 1); the caller has checked that option q is allowed.
+__device__ static inline int64_t tg_duration(int model, int64_t T, uint32_t param, int k, uint32_t speedup) {
+  if (model == TG_MODEL_NONE) return T;
+  int64_t d;
+  if (model == TG_MODEL_AMDAHL) {
+    const uint32_t w = (1000000u - param) * (uint32_t)k + param;   // < 2^26
+    d = tg_ceil_div((uint64_t)T * w, 1000000u * (uint32_t)k);
+  } else {
+    d = tg_ceil_div((uint64_t)T << 16, speedup);
+  }
+  return d < 1 ? 1 : d;
+}
+
+// Largest free chunk size (1,2,4,8 or 0) of a packed count word.
+__device__ static inline int tg_chunk_largest(uint32_t c) {
+  if (c >> 24) return 8;
+  if ((c >> 16) & 0xff) return 4;
+  if ((c >> 8) & 0xff) return 2;
+  return (c & 0xff) ? 1 : 0;
+}
+
+// Best fit with split (Sec. 5.3): take the smallest free chunk of level >= level(k); a larger
+// chunk leaves one free chunk of every size from k up to half of it.  Caller checked the fit.
+__device__ static inline uint32_t tg_chunk_take(uint32_t c, int k) {
+  const int a = tg_chunk_level(k);
+  for (int b = a; b < 4; ++b)
+    if ((c >> (8 * b)) & 0xff) {
+      c -= 1u << (8 * b);
+      for (int x = a; x < b; ++x) c += 1u << (8 * x);
+      return c;
+    }
+  return c;
+}
+#endif
+
+#define TG_HIP_CHECK(expr)                       \
+  do {                                           \
+    hipError_t e_ = (expr);                      \
+    if (e_ != hipSuccess) return TG_E_HIP;       \
+  } while (0)
+
+// kernels' launchers (defined in the .hip files)
+int tg_launch_score(const tg_problem* p, int64_t* d_cost, hipStream_t s);
+
+#endif  // TG_INTERNAL_H_

@@ -1,0 +1,476 @@
+// Wavefront-level building blocks of one scheduling step, shared by tg_assign (one snapshot
+// per launch slot) and tg_replay_trace (one step per tick inside a persistent workgroup).
+//
+//   tg_place_pool      Alg. 1 l.1-2 for one resource kind: FCFS admission at minimum units with
+//                      node choice by least estimated completion time (Eq. 2), node table in LDS
+//   tg_node_schedule   Alg. 1 l.3-14 for one node: DPArrange (Alg. 3; Alg. 4 chunk states on GPU
+//                      nodes), completion-heap estimate (Alg. 2), greedy tail eviction
+//
+// Both are executed by ONE wavefront (64 lanes) with uniform control flow; `__syncthreads()`
+// is only used by callers whose workgroup is that single wavefront, the functions themselves
+// order their LDS traffic with tg_wave_sync().
+#ifndef TG_STEP_H_
+#define TG_STEP_H_
+
+#include "tg_internal.h"
+
+#define TG_PAD INT64_MAX            // heap slot beyond the heap size
+#define TG_MARK (INT64_MAX - 1)     // heap slot popped by the action being inserted
+
+// All lanes of a wavefront run in lockstep; this keeps the compiler from moving LDS or global
+// accesses across the point where one lane's write must be seen by the others.
+__device__ static inline void tg_wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__device__ static inline uint64_t tg_wave_min_u64(uint64_t v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const uint64_t w = __shfl_xor((unsigned long long)v, o);
+    v = w < v ? w : v;
+  }
+  return v;
+}
+
+__device__ static inline int tg_wave_sum_i32(int v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+__device__ static inline int64_t tg_readlane_i64(int64_t v, int l) {
+  const int lo = __builtin_amdgcn_readlane((int)(uint32_t)v, l);
+  const int hi = __builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)v >> 32), l);
+  return (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+}
+
+// ---------------------------------------------------------------------------- placement
+struct TgPoolLds {
+  int64_t* back;     // [nodes] backlog
+  int64_t* dur;      // [64*TG_MAX_K] duration rows of the 64 actions being processed
+  int32_t* lim;      // [nodes] CPU/API: units left; GPU: packed counts of free chunks
+  int32_t* cnt;      // [nodes] actions admitted to the node so far
+  int32_t* dcnt;     // [nodes] waiting actions pinned to the node
+  int32_t* k;        // [TG_MAX_K] unit counts
+  uint8_t* closed;   // [nodes] the node's pool is closed (a pinned action did not fit)
+};
+
+__host__ __device__ static inline size_t tg_pool_lds_bytes(int nodes) {
+  const size_t n = (size_t)((nodes + 7) & ~7);
+  return n * 8 + 64 * TG_MAX_K * 8 + n * 4 * 3 + TG_MAX_K * 4 + n;
+}
+
+__device__ static inline void tg_pool_lds_carve(unsigned char* smem, int nodes, TgPoolLds* S) {
+  const size_t n = (size_t)((nodes + 7) & ~7);
+  S->back = reinterpret_cast<int64_t*>(smem);
+  S->dur = S->back + n;
+  S->lim = reinterpret_cast<int32_t*>(S->dur + 64 * TG_MAX_K);
+  S->cnt = S->lim + n;
+  S->dcnt = S->cnt + n;
+  S->k = S->dcnt + n;
+  S->closed = reinterpret_cast<uint8_t*>(S->k + TG_MAX_K);
+}
+
+struct TgPlaceIo {
+  // per-action inputs, indexed by the action's id inside its snapshot / scenario
+  const uint32_t* act_kmask;
+  const uint8_t* act_static;
+  const int32_t* act_pin;
+  const int32_t* node_rank;    // node id -> rank inside this pool
+  const int32_t* nodes;        // rank -> node id
+  const int64_t* dur;          // [id*K + q]
+  const int64_t* cost;         // optional block of the score tensor for this pool
+  int cost_row_len;
+  int K, Kt;
+  // outputs
+  int32_t* out_node; int32_t* out_units; int64_t* out_act; uint8_t* out_reason; int32_t* slot;
+};
+
+// Admission of the pool's `Nt` actions (ids acts[0..Nt) in FCFS order) onto its `Mt` nodes.
+// On return S.cnt / S.dcnt hold the list lengths per node and every action has its reason,
+// node (-1 if deferred) and list slot written.
+__device__ static inline void tg_place_pool(const TgPoolLds& S, const TgPlaceIo& io, const int32_t* acts, int Nt,
+                                            int Mt, bool gpu, int lane) {
+  bool pool_closed = false;
+  for (int base = 0; base < Nt; base += TG_WAVE) {
+    const int cnt = min(TG_WAVE, Nt - base);
+    int my_id = 0, my_pin = -1;
+    uint32_t my_mask = 0, my_static = 0;
+    if (lane < cnt) {
+      my_id = acts[base + lane];
+      my_mask = io.act_kmask[my_id]; my_static = io.act_static[my_id]; my_pin = io.act_pin[my_id];
+    }
+    tg_wave_sync();                                  // previous chunk's readers are done with S.dur
+    for (int x = lane; x < cnt * io.K; x += TG_WAVE) {
+      const int a = x / io.K, q = x - a * io.K;
+      S.dur[x] = io.dur[(size_t)acts[base + a] * io.K + q];
+    }
+    tg_wave_sync();
+    for (int l = 0; l < cnt; ++l) {
+      const int id = __builtin_amdgcn_readlane(my_id, l);
+      const uint32_t mask = (uint32_t)__builtin_amdgcn_readlane((int)my_mask, l);
+      const int pin = __builtin_amdgcn_readlane(my_pin, l);
+      const int stat = __builtin_amdgcn_readlane((int)my_static, l);
+      int reason = TG_SELECTED;
+      int pr = -1;
+      uint64_t best = ~0ull;
+      if (stat) {
+        reason = TG_DEFER_INFEASIBLE;
+      } else {
+        if (pin >= 0) pr = io.node_rank[pin];
+        if (pool_closed || (pr >= 0 && S.closed[pr])) {
+          reason = TG_DEFER_PREFIX;
+        } else {
+          const int kmin = S.k[__builtin_ctz(mask)];
+          const int r_lo = pr >= 0 ? pr : lane, r_hi = pr >= 0 ? (lane == 0 ? pr + 1 : 0) : Mt;
+          for (int r = r_lo; r < r_hi; r += TG_WAVE) {
+            if (S.closed[r]) continue;
+            const int lim = gpu ? tg_chunk_largest((uint32_t)S.lim[r]) : S.lim[r];
+            if (kmin > lim) continue;
+            int qs = 0;                              // largest allowed option that still fits
+#pragma unroll
+            for (int q = 0; q < TG_MAX_K; ++q)
+              if (q < io.Kt && (mask >> q & 1u) && S.k[q] <= lim) qs = q;
+            const int64_t e = io.cost ? io.cost[(size_t)(base + l) * io.cost_row_len + r * io.Kt + qs]
+                                      : S.back[r] + S.dur[l * io.K + qs];
+            const uint64_t key = (uint64_t)e << 12 | (uint32_t)r;   // ties: smaller node rank
+            best = key < best ? key : best;
+          }
+          best = tg_wave_min_u64(best);
+          if (best == ~0ull) {
+            reason = TG_DEFER_PREFIX;
+            if (pr >= 0) { if (lane == 0) S.closed[pr] = 1; } else pool_closed = true;
+          }
+        }
+      }
+      if (lane == 0) {
+        int node = -1, slot = 0;
+        if (reason == TG_SELECTED) {
+          const int r = (int)(best & 0xfff);
+          const int kmin = S.k[__builtin_ctz(mask)];
+          node = io.nodes[r];
+          slot = S.cnt[r]; S.cnt[r] = slot + 1;
+          S.lim[r] = gpu ? (int32_t)tg_chunk_take((uint32_t)S.lim[r], kmin) : S.lim[r] - kmin;
+        } else if (reason == TG_DEFER_PREFIX && pr >= 0) {
+          slot = S.dcnt[pr]; S.dcnt[pr] = slot + 1;
+        }
+        io.out_node[id] = node;
+        io.out_reason[id] = (uint8_t)reason;
+        io.slot[id] = slot;
+        if (reason != TG_SELECTED) { io.out_units[id] = 0; if (io.out_act) io.out_act[id] = -1; }
+      }
+      tg_wave_sync();
+    }
+  }
+  tg_wave_sync();
+}
+
+// ---------------------------------------------------------------------------- per node
+struct TgNodeLdsPlan {
+  int off_cdur, off_dp, off_choice, off_heap, off_rowbest, off_rowarg, off_sel, off_pos, off_k;
+  int dp_width;     // entries per DP row
+  int total;        // bytes per wavefront
+};
+
+__host__ static inline TgNodeLdsPlan tg_node_lds_plan(int max_free_cpu, int max_free_gpu, int max_states, int max_heap, int K) {
+  TgNodeLdsPlan p;
+  const int mmax = (max_free_cpu > max_free_gpu ? max_free_cpu : max_free_gpu) + 1;
+  const int width = (max_free_cpu + 1 > max_states ? max_free_cpu + 1 : max_states);
+  size_t choice = (size_t)max_free_cpu * (max_free_cpu + 1);
+  if ((size_t)max_free_gpu * max_states * 2 > choice) choice = (size_t)max_free_gpu * max_states * 2;
+  size_t off = 0;
+  auto take = [&](size_t b) { const size_t r = off; off += (b + 15) & ~size_t(15); return (int)r; };
+  p.off_cdur = take((size_t)mmax * K * 8);
+  p.off_dp = take((size_t)width * 2 * 8);
+  p.off_choice = take(choice + 16);
+  p.off_heap = take((size_t)(max_heap + 1) * 8);
+  p.off_rowbest = take((size_t)(mmax + 1) * 8);
+  p.off_rowarg = take((size_t)(mmax + 1) * 4);
+  p.off_sel = take((size_t)mmax);
+  p.off_pos = take((size_t)mmax * 2);
+  p.off_k = take(TG_MAX_K * 4);
+  p.dp_width = width;
+  p.total = (int)off;
+  return p;
+}
+
+struct TgNodeIn {
+  int type, cap, free_units;
+  int64_t backlog;
+  uint32_t chunks;
+  int m; const int32_t* clist;       // admitted actions of the node, FCFS
+  int nd; const int32_t* dlist;      // waiting actions pinned to the node, FCFS
+  int n_busy; const int64_t* busy;   // release times of the units of running actions
+  const uint8_t* act_model; const uint32_t* act_kmask; const int64_t* dur;
+  int K, depth;
+  int k_list[TG_MAX_K];
+};
+
+struct TgNodeOut {
+  int32_t* node; int32_t* units; int64_t* act; uint8_t* reason;
+  const int64_t* age;
+};
+
+// Alg. 2 estimate(): insert the waiting actions one after the other into the completion heap
+// (one entry per unit, `H` entries staged in s_heap).  The heap lives in registers, four slots
+// per lane; a pop is a wavefront-wide minimum.  All but the first action use their minimum
+// units; the first tries its d-th smallest option for d = 1..depth.
+__device__ static inline int64_t tg_estimate(const TgNodeIn& in, const int64_t* s_heap, const int32_t* s_k, int H,
+                                             int L, int lane) {
+  const int n_tail = in.m - L, n_ac = n_tail + in.nd;
+  if (n_ac == 0) return 0;
+  int64_t best = TG_INF;
+  for (int d = 1; d <= in.depth; ++d) {
+    int64_t hv[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) { const int idx = lane + TG_WAVE * s; hv[s] = idx < H ? s_heap[idx] : TG_PAD; }
+    int64_t obj = 0;
+    bool first = true, invalid = false;
+    for (int base = 0; base < n_ac && !invalid; base += TG_WAVE) {
+      const int cnt = min(TG_WAVE, n_ac - base);
+      int my_id = 0, my_u = 0, my_ok = 0;
+      uint32_t my_mask = 0;
+      int64_t my_d = 0;
+      if (lane < cnt) {
+        const int x = base + lane;
+        my_id = x < n_tail ? in.clist[L + x] : in.dlist[x - n_tail];
+        my_mask = in.act_kmask[my_id];
+        const int q0 = __builtin_ctz(my_mask | 0x80000000u);
+        my_u = s_k[q0 & (TG_MAX_K - 1)];
+        my_ok = my_mask != 0 && q0 < TG_MAX_K && my_u <= H;       // can never run on this node: left out
+        if (my_ok) my_d = in.dur[(size_t)my_id * in.K + q0];
+      }
+      for (int l = 0; l < cnt; ++l) {
+        if (!__builtin_amdgcn_readlane(my_ok, l)) continue;
+        int u = __builtin_amdgcn_readlane(my_u, l);
+        int64_t dd = tg_readlane_i64(my_d, l);
+        if (first) {
+          first = false;
+          if (d > 1) {                                            // d-th smallest usable option
+            const uint32_t mask = (uint32_t)__builtin_amdgcn_readlane((int)my_mask, l);
+            const int id = __builtin_amdgcn_readlane(my_id, l);
+            int seen = 0, qd = -1;
+            for (int q = 0; q < in.K; ++q)
+              if ((mask >> q & 1u) && s_k[q] <= H && ++seen == d) { qd = q; break; }
+            if (qd < 0) { invalid = true; break; }
+            u = s_k[qd];
+            dd = in.dur[(size_t)id * in.K + qd];
+          }
+        }
+        int64_t start = 0;
+        for (int c = 0; c < u; ++c) {                             // pop the u earliest units
+          int64_t lm = hv[0];
+          int ls = 0;
+#pragma unroll
+          for (int s = 1; s < 4; ++s) if (hv[s] < lm) { lm = hv[s]; ls = s; }
+          const int64_t wm = (int64_t)tg_wave_min_u64((uint64_t)lm);
+          const uint64_t bal = __ballot(lm == wm);
+          const int owner = __ffsll((unsigned long long)bal) - 1;
+          if (lane == owner) {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) if (s == ls) hv[s] = TG_MARK;
+          }
+          start = wm;
+        }
+        const int64_t fin = start + dd;                           // starts when its last unit frees
+#pragma unroll
+        for (int s = 0; s < 4; ++s) if (hv[s] == TG_MARK) hv[s] = fin;
+        obj += fin;
+      }
+    }
+    if (invalid) break;
+    best = obj < best ? obj : best;
+  }
+  return best;
+}
+
+// One node: returns the final approximated objective (or -1 when the node holds no elastic
+// action and everything simply runs on its minimum units).
+__device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgNodeLdsPlan& plan, const TgNodeIn& in,
+                                                  const TgNodeOut& out, int lane) {
+  int64_t* s_cdur = reinterpret_cast<int64_t*>(smem + plan.off_cdur);
+  int64_t* s_dp = reinterpret_cast<int64_t*>(smem + plan.off_dp);
+  uint8_t* s_choice = smem + plan.off_choice;
+  uint16_t* s_choice16 = reinterpret_cast<uint16_t*>(smem + plan.off_choice);
+  int64_t* s_heap = reinterpret_cast<int64_t*>(smem + plan.off_heap);
+  int64_t* s_rowbest = reinterpret_cast<int64_t*>(smem + plan.off_rowbest);
+  int32_t* s_rowarg = reinterpret_cast<int32_t*>(smem + plan.off_rowarg);
+  uint8_t* s_sel = smem + plan.off_sel;
+  uint16_t* s_pos = reinterpret_cast<uint16_t*>(smem + plan.off_pos);
+  int32_t* s_k = reinterpret_cast<int32_t*>(smem + plan.off_k);
+  const int m = in.m, K = in.K, U = in.free_units;
+  const bool gpu = in.type == TG_TYPE_GPU;
+
+  tg_wave_sync();
+  if (lane < TG_MAX_K) s_k[lane] = in.k_list[lane];
+  int el = 0;
+  for (int x = lane; x < m; x += TG_WAVE) el |= in.act_model[in.clist[x]] != TG_MODEL_NONE;
+  tg_wave_sync();
+  if (!__any(el)) {                                               // Alg. 1 l.5-6: nothing to scale
+    for (int x = lane; x < m; x += TG_WAVE) {
+      const int id = in.clist[x];
+      const int q0 = __builtin_ctz(in.act_kmask[id]);
+      out.units[id] = s_k[q0];
+      if (out.act) out.act[id] = (out.age ? out.age[id] : 0) + in.backlog + in.dur[(size_t)id * K + q0];
+    }
+    return -1;
+  }
+
+  // durations of the node's candidates, options above the node's capacity removed
+  for (int x = lane; x < m * K; x += TG_WAVE) {
+    const int a = x / K, q = x - a * K;
+    int64_t d = in.dur[(size_t)in.clist[a] * K + q];
+    if (s_k[q] > in.cap) d = TG_INF;
+    s_cdur[x] = d;
+  }
+  tg_wave_sync();
+
+  // ---- DPArrange over all prefixes at once: row i holds the best totals of C[:i] ----------
+  int stride;                                                     // entries per choice row
+  if (!gpu) {
+    int sm = 0;                                                   // End(S): sum of the largest options
+    for (int a = lane; a < m; a += TG_WAVE) {
+      int kmax = 0;
+      for (int q = 0; q < K; ++q) if (s_cdur[a * K + q] != TG_INF) kmax = s_k[q];
+      sm += kmax;
+    }
+    sm = tg_wave_sum_i32(sm);
+    const int n = min(U, sm);
+    stride = n + 1;
+    int64_t* prev = s_dp;
+    int64_t* cur = s_dp + plan.dp_width;
+    for (int j = lane; j <= n; j += TG_WAVE) prev[j] = j == 0 ? 0 : TG_INF;
+    if (lane == 0) { s_rowbest[0] = 0; s_rowarg[0] = 0; }
+    tg_wave_sync();
+    for (int i = 1; i <= m; ++i) {
+      uint64_t rb = ~0ull;
+      for (int j = lane; j <= n; j += TG_WAVE) {
+        int64_t bestv = TG_INF;
+        int bq = 0xff;
+        for (int q = 0; q < K; ++q) {                             // ascending k, strict <: fewer units win ties
+          const int64_t t = s_cdur[(i - 1) * K + q];
+          const int kq = s_k[q];
+          if (t == TG_INF || j < kq) continue;
+          const int64_t pv = prev[j - kq];
+          if (pv != TG_INF && pv + t < bestv) { bestv = pv + t; bq = q; }
+        }
+        cur[j] = bestv;
+        s_choice[(size_t)(i - 1) * stride + j] = (uint8_t)bq;
+        if (bestv != TG_INF) { const uint64_t key = (uint64_t)bestv << 9 | (uint32_t)j; rb = key < rb ? key : rb; }
+      }
+      rb = tg_wave_min_u64(rb);                                   // best over used <= n, fewest units on ties
+      if (lane == 0) { s_rowbest[i] = (int64_t)(rb >> 9); s_rowarg[i] = (int)(rb & 511); }
+      int64_t* tmp = prev; prev = cur; cur = tmp;
+      tg_wave_sync();
+    }
+  } else {
+    // Alg. 4: state = counts of free chunks (1,2,4,8), mixed-radix encoded; a transition takes
+    // the smallest chunk that holds k GPUs and splits it.  Forward relaxation with a packed
+    // 64-bit key (value | source state | option) so that ties resolve to the smallest source
+    // state, then the smallest option, independent of lane timing.
+    const int n0 = max((int)(in.chunks & 0xff), 1), n1 = max((int)(in.chunks >> 8 & 0xff), 1),
+              n2 = max((int)(in.chunks >> 16 & 0xff), 1), n3 = max((int)(in.chunks >> 24), 1);
+    const int r0 = n0 + 1, r1 = n1 + 1, r2 = n2 + 1;
+    const int S = r0 * r1 * r2 * (n3 + 1);
+    stride = S;
+    uint64_t* prev = reinterpret_cast<uint64_t*>(s_dp);
+    uint64_t* cur = prev + plan.dp_width;
+    const int s_start = (int)(in.chunks & 0xff) + r0 * ((int)(in.chunks >> 8 & 0xff) + r1 * ((int)(in.chunks >> 16 & 0xff) + r2 * (int)(in.chunks >> 24)));
+    for (int s = lane; s < S; s += TG_WAVE) prev[s] = s == s_start ? 0ull : ~0ull;
+    if (lane == 0) { s_rowbest[0] = 0; s_rowarg[0] = s_start; }
+    tg_wave_sync();
+    for (int i = 1; i <= m; ++i) {
+      for (int s = lane; s < S; s += TG_WAVE) cur[s] = ~0ull;
+      tg_wave_sync();
+      for (int s = lane; s < S; s += TG_WAVE) {
+        const uint64_t kp = prev[s];
+        if (kp == ~0ull) continue;
+        const uint64_t v = kp >> 12;
+        int rest = s;
+        const uint32_t c0 = rest % r0; rest /= r0;
+        const uint32_t c1 = rest % r1; rest /= r1;
+        const uint32_t c2 = rest % r2; rest /= r2;
+        const uint32_t c = c0 | c1 << 8 | c2 << 16 | (uint32_t)rest << 24;
+        const int largest = tg_chunk_largest(c);
+        for (int q = 0; q < K; ++q) {
+          const int64_t t = s_cdur[(i - 1) * K + q];
+          const int kq = s_k[q];
+          if (t == TG_INF || kq > largest) continue;
+          const uint32_t c2n = tg_chunk_take(c, kq);
+          const int s2 = (int)(c2n & 0xff) + r0 * ((int)(c2n >> 8 & 0xff) + r1 * ((int)(c2n >> 16 & 0xff) + r2 * (int)(c2n >> 24)));
+          const uint64_t key = (v + (uint64_t)t) << 12 | (uint64_t)s << 3 | (uint64_t)q;
+          atomicMin(reinterpret_cast<unsigned long long*>(&cur[s2]), (unsigned long long)key);
+        }
+      }
+      tg_wave_sync();
+      uint64_t rb = ~0ull;
+      for (int s = lane; s < S; s += TG_WAVE) {
+        const uint64_t k2 = cur[s];
+        s_choice16[(size_t)(i - 1) * stride + s] = (uint16_t)(k2 & 0xfff);
+        if (k2 != ~0ull) { const uint64_t key = (k2 >> 12) << 9 | (uint32_t)s; rb = key < rb ? key : rb; }
+      }
+      rb = tg_wave_min_u64(rb);
+      if (lane == 0) { s_rowbest[i] = (int64_t)(rb >> 9); s_rowarg[i] = (int)(rb & 511); }
+      uint64_t* tmp = prev; prev = cur; cur = tmp;
+      tg_wave_sync();
+    }
+  }
+
+  // ---- Alg. 2: objective of keeping the first L candidates ---------------------------------
+  const int H = U + in.n_busy;
+  auto backtrack = [&](int L) {                                    // s_sel[x] = option of candidate x
+    int st = s_rowarg[L];
+    for (int i = L; i >= 1; --i) {
+      int q;
+      if (!gpu) { q = s_choice[(size_t)(i - 1) * stride + st]; st -= s_k[q]; }
+      else { const int c = s_choice16[(size_t)(i - 1) * stride + st]; q = c & 7; st = c >> 3; }
+      if (lane == 0) s_sel[i - 1] = (uint8_t)q;
+    }
+    tg_wave_sync();
+  };
+  auto objective = [&](int L) -> int64_t {
+    backtrack(L);
+    int pos = 0;
+    for (int x = 0; x < L; ++x) { if (lane == 0) s_pos[x] = (uint16_t)pos; pos += s_k[s_sel[x]]; }
+    tg_wave_sync();
+    for (int x = lane; x < L; x += TG_WAVE) {                      // k_i entries at backlog + dur_i(k_i)
+      const int q = s_sel[x], kq = s_k[q];
+      const int64_t fin = in.backlog + s_cdur[x * K + q];
+      for (int c = 0; c < kq; ++c) s_heap[s_pos[x] + c] = fin;
+    }
+    for (int c = pos + lane; c < U; c += TG_WAVE) s_heap[c] = in.backlog;   // units left idle
+    for (int c = lane; c < in.n_busy; c += TG_WAVE) s_heap[U + c] = in.busy[c];
+    tg_wave_sync();
+    const int64_t approx = tg_estimate(in, s_heap, s_k, H, L, lane);
+    tg_wave_sync();
+    return s_rowbest[L] + (int64_t)L * in.backlog + approx;
+  };
+
+  // ---- Alg. 1 l.8-13: evict from the tail while the objective drops ------------------------
+  int L = m;
+  int64_t obj = objective(L);
+  while (L > 1) {
+    const int64_t nobj = objective(L - 1);
+    if (nobj >= obj) break;                                        // a tie stops the eviction
+    obj = nobj;
+    --L;
+  }
+  backtrack(L);
+  for (int x = lane; x < m; x += TG_WAVE) {
+    const int id = in.clist[x];
+    if (x < L) {
+      const int q = s_sel[x];
+      out.units[id] = s_k[q];
+      if (out.act) out.act[id] = (out.age ? out.age[id] : 0) + in.backlog + s_cdur[x * K + q];
+    } else {
+      out.node[id] = -1; out.units[id] = 0; out.reason[id] = TG_DEFER_EVICTED;
+      if (out.act) out.act[id] = -1;
+    }
+  }
+  tg_wave_sync();
+  return obj;
+}
+
+#endif  // TG_STEP_H_

@@ -1,0 +1,79 @@
+"""GPU parity of tg_score_candidates against the CPU oracle: bit-exact int64 tensors."""
+import numpy as np
+import pytest
+
+import gen
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def tg():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2603_13019_amd import tg as _tg
+    _tg.load()
+    return _tg
+
+
+def _score_gpu(tg, p):
+    import torch
+    P = tg.Problem(p)
+    out = torch.full((max(P.num_candidates, 2) + 2,), -7, dtype=torch.int64, device="cuda")
+    P.score(out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    n = P.num_candidates
+    P.free()
+    assert (got[n:n + 2] == -7).all() or n < 2          # nothing written past the tensor
+    return got[:n]
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_score_random_problems(tg, orc, seed):
+    p = gen.make_random_problem(seed, B=3, N=70 + 13 * seed, n_cpu=1 + seed % 4, n_gpu=seed % 3, n_api=1 + seed % 2)
+    print("case", seed, flush=True)
+    want = orc.score(p)
+    got = _score_gpu(tg, p)
+    assert got.shape == want.shape
+    np.testing.assert_array_equal(got, want)
+
+
+def test_score_config1(tg, orc):
+    p = gen.make_config(1)
+    np.testing.assert_array_equal(_score_gpu(tg, p), orc.score(p))
+
+
+def test_score_config2_sampled_snapshots(tg, orc):
+    """Full launch configuration of workload 2 (B=256); the oracle checks whole snapshots 0, 100, 255."""
+    p = gen.make_config(2)
+    got = _score_gpu(tg, p)
+    assert got.shape[0] == orc.num_candidates(p)
+    B, N, M = p["B"], p["N"], p["M"]
+    # per-snapshot offsets from the type counts
+    at = p["act_type"].reshape(B, N)
+    per = (at == 0).sum(1) * 64 * 5 + (at == 1).sum(1) * 8 * 4
+    off = np.concatenate([[0], np.cumsum(per)])
+    for b in (0, 100, 255):
+        q = {k: v for k, v in p.items()}
+        q["B"] = 1
+        for k in gen.PROBLEM_ARRAYS:
+            if k.startswith("node_") and p.get(k) is not None and k not in ("node_busy_off", "node_busy_rel_us"):
+                per_n = len(p[k]) // B
+                q[k] = p[k][b * per_n:(b + 1) * per_n]
+            if k.startswith("act_"):
+                q[k] = p[k][b * N:(b + 1) * N]
+        np.testing.assert_array_equal(got[off[b]:off[b + 1]], orc.score(q))
+
+
+def test_score_config4_sampled_rows(tg, orc):
+    """Workload 4 (N=65536, 1152 nodes): full tensor from the GPU, rows of the oracle."""
+    p = gen.make_config(4)
+    got = _score_gpu(tg, p)
+    want = orc.score(p)
+    assert got.shape == want.shape
+    rng = np.random.default_rng(0)
+    idx = rng.integers(0, want.shape[0], 2_000_000)
+    np.testing.assert_array_equal(got[idx], want[idx])
+    np.testing.assert_array_equal(got[:10_000_000], want[:10_000_000])
+    np.testing.assert_array_equal(got[-5_000_000:], want[-5_000_000:])
