@@ -1,0 +1,126 @@
+"""Benchmark of the scheduling hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of snapshots already resident in HBM:
+tg_score_candidates (the (action, node, option) cost tensor) followed by tg_assign (admission,
+node choice, DPArrange + eviction, summaries).  Workload: benchmark configuration 2
+(B=256 snapshots, N=1024 actions, 64 CPU nodes x 128 cores + 8 GPU nodes x 8 GPUs).
+
+Prints ONE JSON line.  `value` is candidates per second over whole steps; `roofline` is the
+score kernel (8 bytes written per candidate) against the 8 TB/s HBM peak, its duration
+measured with HIP events on the launch stream inside the timed region; `cpu_baseline` is the
+single-threaded C++ oracle on the same inputs, timed in this process.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4])
+    ap.add_argument("--snapshots", type=int, default=None, help="override B (sampling of big configs)")
+    ap.add_argument("--use-cost", type=int, default=0, help="1: tg_assign reads its estimates from the score tensor")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--only", choices=["step", "score", "assign"], default="step")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py measures one GPU: every box of this build has a single MI355X and the path uses no "
+              "collectives; run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import gen
+    from paper_2603_13019_amd import tg
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    tg.load()
+    p = gen.make_config(a.config, B=a.snapshots)
+    P = tg.Problem(p)
+    cost = P.alloc_cost()
+    bufs = P.alloc_assign()
+    n_cand, n_act = P.num_candidates, P.B * P.N
+
+    def step():
+        if a.only in ("step", "score"):
+            P.score(cost)
+        if a.only in ("step", "assign"):
+            P.assign(cost if a.use_cost else None, bufs)
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True),
+           torch.cuda.Event(enable_timing=True)) for _ in range(a.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(a.steps):
+        e0, e1, e2 = ev[k]
+        e0.record()
+        if a.only in ("step", "score"):
+            P.score(cost)
+        e1.record()
+        if a.only in ("step", "assign"):
+            P.assign(cost if a.use_cost else None, bufs)
+        e2.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_step = (t1 - t0) * 1e3 / a.steps
+    score_ms = float(np.mean([e0.elapsed_time(e1) for e0, e1, _ in ev]))
+    assign_ms = float(np.mean([e1.elapsed_time(e2) for _, e1, e2 in ev]))
+
+    s = tg.summary_to_numpy(bufs["summary"]) if a.only != "score" else None
+    achieved = 8.0 * n_cand / (score_ms * 1e-3) / 1e9 if a.only != "assign" and score_ms > 0 else None
+    out = {
+        "metric": "candidates_per_sec", "value": n_cand / (ms_step * 1e-3), "unit": "candidates/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int64", "data": "synthetic",
+        "config": {"workload": f"config{a.config}: B={P.B} snapshots x N={P.N} actions, M={P.M} nodes, "
+                               f"{n_cand} candidates; step = tg_score_candidates + tg_assign",
+                   "B": P.B, "N": P.N, "M": P.M, "candidates": n_cand, "assign_reads_score_tensor": bool(a.use_cost),
+                   "only": a.only},
+        "actions_scheduled_per_sec": n_act / (ms_step * 1e-3) if a.only != "score" else None,
+        "stage_ms": {"score": score_ms, "assign": assign_ms},
+        "selected_fraction": float(s["n_selected"].sum()) / n_act if s is not None else None,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS if achieved else None, "traffic": None,
+                     "kernel": "tg_score_kernel", "bytes_per_launch": 8 * n_cand, "avg_kernel_ms": score_ms},
+    }
+
+    if not a.no_cpu_baseline:
+        from oracle import orc
+        orc.lib()
+        t0 = time.perf_counter()
+        orc.score(p)
+        t_score = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        orc.assign(p)
+        t_assign = time.perf_counter() - t0
+        out["cpu_baseline"] = {
+            "value": n_cand / (t_score + t_assign), "unit": "candidates/s", "cores": 1, "kind": "oracle",
+            "sample": f"all {P.B} snapshots of the same workload, one pass (score {t_score:.2f} s + assign {t_assign:.2f} s)",
+            "actions_scheduled_per_sec": n_act / t_assign, "score_candidates_per_sec": n_cand / t_score,
+            "host_cores_total": os.cpu_count(),
+        }
+    P.free()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
