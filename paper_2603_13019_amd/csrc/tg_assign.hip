@@ -87,24 +87,7 @@ __global__ __launch_bounds__(TG_WAVE) void tg_place_kernel(TgDev P, const int64_
   io.out_reason = O.defer_reason + abase; io.slot = W.slot + abase;
   tg_place_pool(S, io, acts, Nt, Mt, t == TG_TYPE_GPU, lane);
 
-  // list extents per node (exclusive scan of the per-node counts, in node order of this kind)
-  int run = a0, drun = a0;
-  for (int base = 0; base < Mt; base += TG_WAVE) {
-    const int r = base + lane;
-    const int c = r < Mt ? S.cnt[r] : 0, dc = r < Mt ? S.dcnt[r] : 0;
-    int inc = c, dinc = dc;
-    for (int o = 1; o < TG_WAVE; o <<= 1) {
-      const int u = __shfl_up(inc, o), du = __shfl_up(dinc, o);
-      if (lane >= o) { inc += u; dinc += du; }
-    }
-    if (r < Mt) {
-      const size_t g = nbase + nodes[r];
-      W.nl_off[g] = run + inc - c; W.nl_cnt[g] = c;
-      W.dl_off[g] = drun + dinc - dc; W.dl_cnt[g] = dc;
-    }
-    run += __shfl(inc, TG_WAVE - 1);
-    drun += __shfl(dinc, TG_WAVE - 1);
-  }
+  tg_pool_extents(S, nodes, Mt, a0, W.nl_off + nbase, W.nl_cnt + nbase, W.dl_off + nbase, W.dl_cnt + nbase, lane);
 }
 
 // ------------------------------------------------------------------------------------------

@@ -1,7 +1,599 @@
-// Batched trace replay (placeholder entry points until the replay kernel lands).
-#include "tg_internal.h"
+// tg_replay_trace: S independent arrival traces, one persistent workgroup per scenario.
+//
+// Every tick the workgroup runs the same scheduling step as tg_assign (the wavefront-level
+// functions of tg_step.h) on the scenario's live state: the three resource pools are placed by
+// three wavefronts in parallel, the nodes that received candidates are spread over all
+// wavefronts for DPArrange + eviction, and selected actions start at the tick.  The tick loop
+// is bounded by max_ticks, so every wavefront leaves the kernel.
+//
+// Live state per scenario (global workspace, L2 resident): free cores per CPU node, free-GPU
+// bit mask per GPU node (a free chunk is a maximal aligned free block, so releasing coalesces
+// by itself), micro-tokens per quota, the running set (finish, node, units, first GPU), and
+// one FCFS waiting list per resource kind.
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <vector>
 
-extern "C" int tg_build_trace(const tg_trace_desc*, void*, tg_trace** out) { if (out) *out = nullptr; return TG_E_INVALID_ARG; }
-extern "C" void tg_free_trace(tg_trace*) {}
-extern "C" int tg_replay_workspace_bytes(const tg_trace*, size_t*) { return TG_E_INVALID_ARG; }
-extern "C" int tg_replay_trace(const tg_trace*, const tg_replay_out*, void*, size_t, void*) { return TG_E_INVALID_ARG; }
+#include "tg_step.h"
+
+struct TgTraceDev {
+  int S, A, M, K, n_classes, depth, max_ticks, pad_;
+  int64_t tick_us;
+  int k_list[TG_MAX_K];
+  int type_k[4];
+  const uint8_t* node_type; const int32_t* node_cap; const int32_t* quota_rate; const int64_t* quota_tok0;
+  const int32_t* node_rank; const int32_t* tnode_idx; const int32_t* tnode_off;   // [S*M], [S*M], [S*4]
+  const int64_t* arrival; const uint8_t* act_type; const uint8_t* act_model; const uint8_t* act_static;
+  const int64_t* act_T; const uint32_t* act_kmask; const uint32_t* act_param; const int32_t* act_pin;
+  const uint32_t* speedup;
+};
+
+struct tg_trace {
+  TgTraceDev dev;
+  void* d_arena;
+  size_t arena_bytes;
+  int max_nodes_of_kind, max_cap_cpu, max_heap, max_chunk_states;
+};
+
+namespace {
+
+constexpr int kWaves = 4;
+constexpr int kThreads = kWaves * TG_WAVE;
+
+struct ReplayWs {
+  int64_t* dur;        // [S*A*K]
+  int32_t* slot;       // [S*A]
+  int32_t* order;      // [S*A]
+  int32_t* dorder;     // [S*A]
+  int32_t* wlist;      // [S*3*A] waiting list per kind
+  int64_t* run_fin;    // [S*A]
+  int32_t* run_info;   // [S*A] node | units << 16 | first GPU << 24
+  uint8_t* reason;     // [S*A]
+  int32_t *nl_off, *nl_cnt, *dl_off, *dl_cnt;   // [S*M]
+  int32_t* live_free;  // [S*M] free cores / free-GPU mask
+  int64_t* live_tok;   // [S*M]
+};
+
+size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+
+size_t carve(const TgTraceDev& T, char* base, ReplayWs* w) {
+  const size_t nA = (size_t)T.S * T.A, nN = (size_t)T.S * T.M;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { char* r = base + off; off += align256(bytes); return r; };
+  char* p[14];
+  p[0] = take(nA * T.K * 8); p[1] = take(nA * 4); p[2] = take(nA * 4); p[3] = take(nA * 4); p[4] = take(nA * 3 * 4);
+  p[5] = take(nA * 8); p[6] = take(nA * 4); p[7] = take(nA);
+  for (int x = 8; x < 13; ++x) p[x] = take(nN * 4);
+  p[13] = take(nN * 8);
+  if (w) {
+    w->dur = (int64_t*)p[0]; w->slot = (int32_t*)p[1]; w->order = (int32_t*)p[2]; w->dorder = (int32_t*)p[3];
+    w->wlist = (int32_t*)p[4]; w->run_fin = (int64_t*)p[5]; w->run_info = (int32_t*)p[6]; w->reason = (uint8_t*)p[7];
+    w->nl_off = (int32_t*)p[8]; w->nl_cnt = (int32_t*)p[9]; w->dl_off = (int32_t*)p[10]; w->dl_cnt = (int32_t*)p[11];
+    w->live_free = (int32_t*)p[12]; w->live_tok = (int64_t*)p[13];
+  }
+  return off;
+}
+
+__global__ __launch_bounds__(256) void tg_trace_dur_kernel(TgTraceDev T, int64_t* __restrict__ dur) {
+  const size_t x = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t total = (size_t)T.S * T.A * T.K;
+  if (x >= total) return;
+  const size_t g = x / T.K;
+  const int q = (int)(x - g * T.K);
+  int64_t d = TG_INF;
+  if (T.act_kmask[g] >> q & 1u) {
+    const int model = T.act_model[g];
+    const uint32_t param = T.act_param[g];
+    const uint32_t sp = model == TG_MODEL_TABLE ? T.speedup[param * T.K + q] : 0u;
+    d = tg_duration(model, T.act_T[g], param, T.k_list[q], sp);
+  }
+  dur[x] = d;
+}
+
+// free chunks (sizes 1,2,4,8) of an 8-GPU node as packed 8-bit counts: a chunk is an aligned
+// free block whose enclosing block of twice the size is not entirely free
+__device__ inline uint32_t mask_chunks(uint32_t m) {
+  if (m == 0xffu) return 1u << 24;
+  uint32_t c = 0;
+#pragma unroll
+  for (int half = 0; half < 8; half += 4) {
+    const uint32_t h = (m >> half) & 0xfu;
+    if (h == 0xfu) { c += 1u << 16; continue; }
+#pragma unroll
+    for (int pair = 0; pair < 4; pair += 2) {
+      const uint32_t p = (h >> pair) & 0x3u;
+      if (p == 0x3u) c += 1u << 8; else c += __popc(p);
+    }
+  }
+  return c;
+}
+
+// best fit, lowest address (Sec. 5.3): returns the first GPU of the allocation and clears its bits
+__device__ inline int mask_alloc(uint32_t& m, int k) {
+  const int a = tg_chunk_level(k);
+  for (int lvl = a; lvl < 4; ++lvl) {
+    const int sz = 1 << lvl;
+    for (int s = 0; s < 8; s += sz) {
+      const uint32_t blk = ((1u << sz) - 1u) << s;
+      if ((m & blk) != blk) continue;
+      if (lvl < 3) {
+        const int ps = s & ~(2 * sz - 1);
+        const uint32_t pb = ((1u << (2 * sz)) - 1u) << ps;
+        if ((m & pb) == pb) continue;
+      }
+      m &= ~(((1u << (1 << a)) - 1u) << s);
+      return s;
+    }
+  }
+  return -1;
+}
+
+// Stable in-place compaction of list[0..n) keeping the entries with keep(id); returns the new
+// length.  All threads of the workgroup take part.
+template <class Keep>
+__device__ inline int compact_stable(int32_t* list, int n, Keep keep, int* s_wave_cnt) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int out = 0;
+  for (int base = 0; base < n; base += kThreads) {
+    const int x = base + tid;
+    int id = 0, k = 0;
+    if (x < n) { id = list[x]; k = keep(id) ? 1 : 0; }
+    const uint64_t bal = __ballot(k);
+    if (lane == 0) s_wave_cnt[wave] = __popcll(bal);
+    __syncthreads();                       // also: every read of this chunk precedes its writes
+    int before = 0, total = 0;
+    for (int w = 0; w < kWaves; ++w) { const int c = s_wave_cnt[w]; if (w < wave) before += c; total += c; }
+    if (k) list[out + before + __popcll(bal & ((1ull << lane) - 1ull))] = id;
+    out += total;
+    __syncthreads();
+  }
+  return out;
+}
+
+__global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, ReplayWs W, tg_replay_out O, int pool_nodes,
+                                                             TgNodeLdsPlan plan, int busy_slots) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  __shared__ int s_wcnt[3], s_next, s_started, s_nrun, s_wave_cnt[kWaves], s_hist[256], s_sel[2];
+  __shared__ long long s_sum;
+  const int s = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int A = T.A, M = T.M, K = T.K;
+  const size_t abase = (size_t)s * A, nbase = (size_t)s * M;
+
+  const size_t pool_bytes = (tg_pool_lds_bytes(pool_nodes) + 15) & ~size_t(15);
+  unsigned char* pool_mem = smem + (size_t)(wave < 3 ? wave : 0) * pool_bytes;
+  unsigned char* node_mem = smem + 3 * pool_bytes + (size_t)wave * (size_t)(plan.total + busy_slots * 8);
+  int64_t* s_busy = reinterpret_cast<int64_t*>(node_mem + plan.total);
+
+  const int64_t* arrival = T.arrival + abase;
+  const uint8_t* act_type = T.act_type + abase;
+  const int64_t* dur = W.dur + abase * K;
+  int32_t* wl[3] = {W.wlist + abase * 3, W.wlist + abase * 3 + A, W.wlist + abase * 3 + 2 * (size_t)A};
+  int64_t* run_fin = W.run_fin + abase;
+  int32_t* run_info = W.run_info + abase;
+  int32_t* live_free = W.live_free + nbase;
+  int64_t* live_tok = W.live_tok + nbase;
+  int32_t *nl_off = W.nl_off + nbase, *nl_cnt = W.nl_cnt + nbase, *dl_off = W.dl_off + nbase, *dl_cnt = W.dl_cnt + nbase;
+  int32_t* order = W.order + abase;
+  int32_t* dorder = W.dorder + abase;
+  int32_t* slot = W.slot + abase;
+  uint8_t* reason = W.reason + abase;
+  int32_t* o_node = O.node + abase;
+  int32_t* o_units = O.units + abase;
+  int64_t* o_start = O.start_us + abase;
+  int64_t* o_fin = O.finish_us + abase;
+
+  for (int i = tid; i < A; i += kThreads) { o_node[i] = -1; o_units[i] = 0; o_start[i] = -1; o_fin[i] = -1; }
+  for (int j = tid; j < M; j += kThreads) {
+    const int ty = T.node_type[nbase + j], cap = T.node_cap[nbase + j];
+    live_free[j] = ty == TG_TYPE_GPU ? (int)((1u << cap) - 1u) : cap;
+    live_tok[j] = ty == TG_TYPE_API ? T.quota_tok0[nbase + j] : 0;
+    nl_cnt[j] = 0; dl_cnt[j] = 0;
+  }
+  if (tid == 0) { s_wcnt[0] = s_wcnt[1] = s_wcnt[2] = 0; s_next = 0; s_started = 0; s_nrun = 0; }
+  __syncthreads();
+
+  int tick = 0, last_tick = 0;
+  while (tick < T.max_ticks) {
+    if (s_started >= A) break;
+    // nothing waiting: jump to the tick of the next arrival (releases and refills commute with idle ticks)
+    if (s_wcnt[0] + s_wcnt[1] + s_wcnt[2] == 0) {
+      const int64_t na = arrival[s_next];                       // s_next < A because not everything has started
+      const int64_t tk = (na + T.tick_us - 1) / T.tick_us;
+      if (tk >= T.max_ticks) { tick = T.max_ticks; break; }
+      if ((int)tk > tick) tick = (int)tk;
+    }
+    const int64_t now = (int64_t)tick * T.tick_us;
+    const int dticks = tick - last_tick;
+    last_tick = tick;
+    __syncthreads();                       // everyone has read the shared counters of the previous tick
+
+    // (1) finished actions give their units back; the running set is compacted (order is free)
+    {
+      const int n = s_nrun;
+      int out = 0;
+      for (int base = 0; base < n; base += kThreads) {
+        const int x = base + tid;
+        int keep = 0, info = 0;
+        int64_t fin = 0;
+        if (x < n) {
+          fin = run_fin[x]; info = run_info[x];
+          keep = fin > now;
+          if (!keep) {
+            const int node = info & 0xffff, k = (info >> 16) & 0xff, g0 = (info >> 24) & 0xff;
+            if (T.node_type[nbase + node] == TG_TYPE_GPU) atomicOr(&live_free[node], (int)(((1u << (1 << tg_chunk_level(k))) - 1u) << g0));
+            else atomicAdd(&live_free[node], k);
+          }
+        }
+        const uint64_t bal = __ballot(keep);
+        if (lane == 0) s_wave_cnt[wave] = __popcll(bal);
+        __syncthreads();
+        int before = 0, total = 0;
+        for (int w = 0; w < kWaves; ++w) { const int c = s_wave_cnt[w]; if (w < wave) before += c; total += c; }
+        if (keep) { const int d = out + before + __popcll(bal & ((1ull << lane) - 1ull)); run_fin[d] = fin; run_info[d] = info; }
+        out += total;
+        __syncthreads();
+      }
+      if (tid == 0) s_nrun = out;
+    }
+    // (2) quota refill for the ticks since the last step (saturating, so idle ticks compose)
+    if (dticks > 0)
+      for (int j = tid; j < M; j += kThreads)
+        if (T.node_type[nbase + j] == TG_TYPE_API) {
+          const int64_t capu = (int64_t)T.node_cap[nbase + j] * 1000000, inc = (int64_t)T.quota_rate[nbase + j] * T.tick_us;
+          int64_t tok = live_tok[j];
+          if (inc > 0) {
+            const int64_t need = capu - tok;
+            tok = (need <= 0 || (int64_t)dticks >= (need + inc - 1) / inc) ? (tok > capu ? tok : capu) : tok + dticks * inc;
+          }
+          live_tok[j] = tok;
+        }
+    // (3) arrivals join their kind's waiting list in arrival order
+    if (tid == 0) {
+      int nx = s_next;
+      while (nx < A && arrival[nx] <= now) { const int ty = act_type[nx]; wl[ty][s_wcnt[ty]++] = nx; ++nx; }
+      s_next = nx;
+    }
+    __threadfence_block();
+    __syncthreads();
+    const int wc0 = s_wcnt[0], wc1 = s_wcnt[1], wc2 = s_wcnt[2];
+    const int wcs[3] = {wc0, wc1, wc2};
+    const int woff[3] = {0, wc0, wc0 + wc1};
+
+    // (4a) admission + node choice, one wavefront per resource kind
+    for (int ty = wave; ty < 3; ty += kWaves) {
+      const int n0 = T.tnode_off[s * 4 + ty], Mt = T.tnode_off[s * 4 + ty + 1] - n0;
+      const int32_t* nodes = T.tnode_idx + nbase + n0;
+      TgPoolLds S;
+      tg_pool_lds_carve(pool_mem, pool_nodes, &S);
+      if (lane < TG_MAX_K) S.k[lane] = T.k_list[lane];
+      for (int r = lane; r < Mt; r += TG_WAVE) {
+        const int j = nodes[r];
+        S.back[r] = 0;
+        S.lim[r] = ty == TG_TYPE_GPU ? (int32_t)mask_chunks((uint32_t)live_free[j])
+                 : ty == TG_TYPE_API ? (int32_t)(live_tok[j] / 1000000) : live_free[j];
+        S.cnt[r] = 0; S.dcnt[r] = 0; S.closed[r] = 0;
+      }
+      tg_wave_sync();
+      TgPlaceIo io;
+      io.act_kmask = T.act_kmask + abase; io.act_static = T.act_static + abase; io.act_pin = T.act_pin + abase;
+      io.node_rank = T.node_rank + nbase; io.nodes = nodes; io.dur = dur; io.cost = nullptr; io.cost_row_len = 0;
+      io.K = K; io.Kt = T.type_k[ty];
+      io.out_node = o_node; io.out_units = o_units; io.out_act = nullptr; io.out_reason = reason; io.slot = slot;
+      tg_place_pool(S, io, wl[ty], wcs[ty], Mt, ty == TG_TYPE_GPU, lane);
+      tg_pool_extents(S, nodes, Mt, woff[ty], nl_off, nl_cnt, dl_off, dl_cnt, lane);
+    }
+    __threadfence_block();
+    __syncthreads();
+    // (4b) group candidates and waiting pinned actions by node
+    for (int ty = 0; ty < 3; ++ty)
+      for (int x = tid; x < wcs[ty]; x += kThreads) {
+        const int id = wl[ty][x];
+        const int r = reason[id];
+        if (r == TG_SELECTED) order[nl_off[o_node[id]] + slot[id]] = id;
+        else if (r == TG_DEFER_PREFIX && T.act_pin[abase + id] >= 0) dorder[dl_off[T.act_pin[abase + id]] + slot[id]] = id;
+      }
+    __threadfence_block();
+    __syncthreads();
+    // (4c) per node: DPArrange + greedy eviction; the running actions of the node seed the heap
+    for (int j = wave; j < M; j += kWaves) {
+      const int m = nl_cnt[j];
+      if (m == 0) continue;
+      const int ty = T.node_type[nbase + j];
+      int nb = 0;
+      if (ty != TG_TYPE_API) {
+        const int n = s_nrun;
+        for (int base = 0; base < n; base += TG_WAVE) {
+          const int x = base + lane;
+          int k = 0;
+          int64_t fin = 0;
+          if (x < n) { const int info = run_info[x]; if ((info & 0xffff) == j) { k = (info >> 16) & 0xff; fin = run_fin[x] - now; } }
+          int inc = k;
+          for (int o = 1; o < TG_WAVE; o <<= 1) { const int u = __shfl_up(inc, o); if (lane >= o) inc += u; }
+          for (int c = 0; c < k; ++c) s_busy[nb + inc - k + c] = fin;
+          nb += __shfl(inc, TG_WAVE - 1);
+        }
+      }
+      TgNodeIn in;
+      in.type = ty; in.cap = T.node_cap[nbase + j];
+      const uint32_t lf = (uint32_t)live_free[j];
+      in.free_units = ty == TG_TYPE_GPU ? __popc(lf) : ty == TG_TYPE_API ? (int)(live_tok[j] / 1000000) : (int)lf;
+      in.chunks = ty == TG_TYPE_GPU ? mask_chunks(lf) : 0;
+      in.backlog = 0;
+      in.m = m; in.clist = order + nl_off[j]; in.nd = dl_cnt[j]; in.dlist = dorder + dl_off[j];
+      in.n_busy = nb; in.busy = s_busy;
+      in.act_model = T.act_model + abase; in.act_kmask = T.act_kmask + abase; in.dur = dur; in.K = K; in.depth = T.depth;
+      for (int q = 0; q < TG_MAX_K; ++q) in.k_list[q] = T.k_list[q];
+      TgNodeOut out;
+      out.node = o_node; out.units = o_units; out.act = nullptr; out.reason = reason; out.age = nullptr;
+      tg_node_schedule(node_mem, plan, in, out, lane);
+    }
+    __threadfence_block();
+    __syncthreads();
+    // (5) selected actions start now.  CPU / API: any order; GPU nodes: FCFS order on the mask
+    for (int ty = 0; ty < 3; ++ty)
+      for (int x = tid; x < wcs[ty]; x += kThreads) {
+        const int id = wl[ty][x];
+        const int j = o_node[id];
+        if (j < 0) continue;
+        const int k = o_units[id];
+        int q = 0;
+        while (q < K - 1 && T.k_list[q] != k) ++q;
+        const int64_t fin = now + dur[(size_t)id * K + q];
+        o_start[id] = now; o_fin[id] = fin;
+        atomicAdd(&s_started, 1);
+        if (ty == TG_TYPE_API) { atomicAdd((unsigned long long*)&live_tok[j], (unsigned long long)(-(int64_t)k * 1000000)); }
+        else if (ty == TG_TYPE_CPU) {
+          atomicSub(&live_free[j], k);
+          const int d = atomicAdd(&s_nrun, 1);
+          run_fin[d] = fin; run_info[d] = j | k << 16;
+        }
+      }
+    for (int r = tid; r < T.tnode_off[s * 4 + 2] - T.tnode_off[s * 4 + 1]; r += kThreads) {
+      const int j = T.tnode_idx[nbase + T.tnode_off[s * 4 + 1] + r];
+      const int m = nl_cnt[j];
+      if (m == 0) continue;
+      uint32_t mk = (uint32_t)live_free[j];
+      for (int x = 0; x < m; ++x) {
+        const int id = order[nl_off[j] + x];
+        if (o_node[id] < 0) break;                                // evicted tail
+        const int k = o_units[id];
+        int q = 0;
+        while (q < K - 1 && T.k_list[q] != k) ++q;
+        const int g0 = mask_alloc(mk, k) & 7;
+        const int d = atomicAdd(&s_nrun, 1);
+        run_fin[d] = now + dur[(size_t)id * K + q]; run_info[d] = j | k << 16 | g0 << 24;
+      }
+      live_free[j] = (int)mk;
+    }
+    for (int j = tid; j < M; j += kThreads) { nl_cnt[j] = 0; dl_cnt[j] = 0; }
+    __threadfence_block();
+    __syncthreads();
+    // waiting lists keep the actions that did not start, in order
+    for (int ty = 0; ty < 3; ++ty) {
+      const int n = compact_stable(wl[ty], wcs[ty], [&](int id) { return o_node[id] < 0; }, s_wave_cnt);
+      if (tid == 0) s_wcnt[ty] = n;
+    }
+    __syncthreads();
+    ++tick;
+  }
+
+  // ---- per-scenario statistics: mean and nearest-rank p99 of ACT = finish - arrival ----------
+  __syncthreads();
+  if (tid == 0) s_sum = 0;
+  __syncthreads();
+  const int n_started = s_started;
+  long long sum = 0;
+  for (int i = tid; i < A; i += kThreads) if (o_start[i] >= 0) sum += o_fin[i] - arrival[i];
+  atomicAdd((unsigned long long*)&s_sum, (unsigned long long)sum);
+  __syncthreads();
+  // radix select of the rank-th smallest ACT, one byte per pass from the top
+  int64_t p99 = -1;
+  if (n_started > 0) {
+    int rank = (int)((99ll * n_started + 99) / 100);             // 1-based
+    uint64_t prefix = 0;
+    for (int shift = 56; shift >= 0; shift -= 8) {
+      s_hist[tid] = 0;
+      __syncthreads();
+      for (int i = tid; i < A; i += kThreads)
+        if (o_start[i] >= 0) {
+          const uint64_t key = (uint64_t)(o_fin[i] - arrival[i]);
+          if (shift == 56 || (key >> (shift + 8)) == prefix) atomicAdd(&s_hist[(key >> shift) & 255], 1);
+        }
+      __syncthreads();
+      if (tid == 0) {
+        int cum = 0, bin = 0;
+        for (; bin < 256; ++bin) { if (cum + s_hist[bin] >= rank) break; cum += s_hist[bin]; }
+        s_sel[0] = bin; s_sel[1] = rank - cum;
+      }
+      __syncthreads();
+      prefix = prefix << 8 | (uint64_t)s_sel[0];
+      rank = s_sel[1];
+      __syncthreads();
+    }
+    p99 = (int64_t)prefix;
+  }
+  if (tid == 0) {
+    O.n_started[s] = n_started;
+    O.n_ticks[s] = tick;
+    O.mean_act_us[s] = n_started ? (double)s_sum / (double)n_started : 0.0;
+    O.p99_act_us[s] = p99;
+  }
+}
+
+}  // namespace
+
+extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace** out) {
+  if (!d || !out) return TG_E_INVALID_ARG;
+  *out = nullptr;
+  const int S = d->S, A = d->A, M = d->M, K = d->K;
+  if (S < 1 || A < 1 || M < 1 || d->flags != 0 || d->max_ticks < 1 || d->tick_us < 1) return TG_E_INVALID_ARG;
+  if (d->depth < 1 || d->depth > TG_MAX_DEPTH) return TG_E_INVALID_ARG;
+  if (A > TG_MAX_ACTIONS || M > 65535 || (int64_t)S * A >= (1ll << 31) || (int64_t)S * M >= (1ll << 31)) return TG_E_RANGE;
+  if (d->tick_us >= TG_TIME_LIMIT || (int64_t)d->max_ticks * d->tick_us >= (1ll << 44)) return TG_E_RANGE;
+  if (K < 1 || K > TG_MAX_K || !d->k_list || !d->type_k) return TG_E_INVALID_ARG;
+  for (int q = 0; q < K; ++q) {
+    if (d->k_list[q] < 1 || d->k_list[q] > TG_MAX_UNIT || (q && d->k_list[q] <= d->k_list[q - 1])) return TG_E_INVALID_ARG;
+  }
+  for (int t = 0; t < 3; ++t) if (d->type_k[t] < 0 || d->type_k[t] > K) return TG_E_INVALID_ARG;
+  if (d->type_k[TG_TYPE_API] > 1) return TG_E_INVALID_ARG;
+  for (int q = 0; q < d->type_k[TG_TYPE_GPU]; ++q) {
+    const int k = d->k_list[q];
+    if (!(k == 1 || k == 2 || k == 4 || k == 8)) return TG_E_INVALID_ARG;
+  }
+  if (d->n_classes < 0 || (d->n_classes > 0 && !d->speedup_q16)) return TG_E_INVALID_ARG;
+  for (int c = 0; c < d->n_classes; ++c)
+    for (int q = 0; q < K; ++q) {
+      const uint32_t sp = d->speedup_q16[c * K + q];
+      if (sp < 65536u || sp > 65536u * (uint32_t)d->k_list[q] || (q && sp < d->speedup_q16[c * K + q - 1])) return TG_E_ELASTICITY;
+    }
+  if (!d->node_type || !d->node_cap || !d->quota_rate || !d->quota_tok0_micro || !d->arrival_us || !d->act_type ||
+      !d->act_model || !d->act_t_ori_us || !d->act_kmask || !d->act_param || !d->act_pin_node)
+    return TG_E_INVALID_ARG;
+
+  const size_t nN = (size_t)S * M, nA = (size_t)S * A;
+  std::vector<char> host;
+  auto add = [&](size_t bytes) { size_t off = (host.size() + 255) & ~size_t(255); host.resize(off + bytes, 0); return off; };
+  tg_trace* t = new (std::nothrow) tg_trace();
+  if (!t) return TG_E_NOMEM;
+  std::memset(t, 0, sizeof *t);
+  try {
+    const size_t o_ntype = add(nN), o_ncap = add(nN * 4), o_rate = add(nN * 4), o_tok = add(nN * 8), o_rank = add(nN * 4),
+                 o_tnidx = add(nN * 4), o_tnoff = add((size_t)S * 16);
+    const size_t o_arr = add(nA * 8), o_atype = add(nA), o_amodel = add(nA), o_astat = add(nA), o_aT = add(nA * 8),
+                 o_amask = add(nA * 4), o_aparam = add(nA * 4), o_apin = add(nA * 4);
+    const size_t o_speed = add(std::max<size_t>((size_t)d->n_classes * K, 1) * 4);
+    auto at = [&](size_t off) { return host.data() + off; };
+    int max_kind = 0, max_cap_cpu = 0, max_heap = 0;
+    std::vector<int> max_cap((size_t)S * 3, -1);
+    for (int s = 0; s < S; ++s) {
+      int cnt[3] = {0, 0, 0};
+      for (int j = 0; j < M; ++j) {
+        const size_t g = (size_t)s * M + j;
+        const int ty = d->node_type[g], cap = d->node_cap[g];
+        if (ty >= TG_N_TYPES || cap < 0) { delete t; return TG_E_INVALID_ARG; }
+        if (ty == TG_TYPE_GPU && cap != 8) { delete t; return TG_E_INVALID_ARG; }
+        if (ty == TG_TYPE_CPU && cap > TG_MAX_CPU_UNITS) { delete t; return TG_E_RANGE; }
+        if (ty == TG_TYPE_API) {
+          const int64_t tok = d->quota_tok0_micro[g];
+          if (d->quota_rate[g] < 0 || tok < 0 || tok > (int64_t)cap * 1000000) { delete t; return TG_E_INVALID_ARG; }
+          if ((int64_t)d->quota_rate[g] * d->tick_us >= (1ll << 50)) { delete t; return TG_E_RANGE; }
+        } else {
+          max_heap = std::max(max_heap, cap);
+          if (ty == TG_TYPE_CPU) max_cap_cpu = std::max(max_cap_cpu, cap);
+        }
+        ((uint8_t*)at(o_ntype))[g] = (uint8_t)ty;
+        ((int32_t*)at(o_ncap))[g] = cap;
+        ((int32_t*)at(o_rate))[g] = d->quota_rate[g];
+        ((int64_t*)at(o_tok))[g] = d->quota_tok0_micro[g];
+        ((int32_t*)at(o_rank))[g] = cnt[ty]++;
+        max_cap[(size_t)s * 3 + ty] = std::max(max_cap[(size_t)s * 3 + ty], cap);
+      }
+      int32_t* off = (int32_t*)at(o_tnoff) + (size_t)s * 4;
+      off[0] = 0; off[1] = cnt[0]; off[2] = cnt[0] + cnt[1]; off[3] = M;
+      int fill[3] = {off[0], off[1], off[2]};
+      for (int j = 0; j < M; ++j) ((int32_t*)at(o_tnidx))[(size_t)s * M + fill[d->node_type[(size_t)s * M + j]]++] = j;
+      for (int k = 0; k < 3; ++k) max_kind = std::max(max_kind, cnt[k]);
+      if (max_kind > TG_MAX_NODES_OF_KIND) { delete t; return TG_E_RANGE; }
+      int64_t sumT = 0, prev = 0;
+      for (int i = 0; i < A; ++i) {
+        const size_t g = (size_t)s * A + i;
+        const int ty = d->act_type[g], model = d->act_model[g];
+        if (ty >= TG_N_TYPES || model > TG_MODEL_TABLE || (ty == TG_TYPE_API && model != TG_MODEL_NONE)) { delete t; return TG_E_INVALID_ARG; }
+        const int64_t T = d->act_t_ori_us[g], arr = d->arrival_us[g];
+        if (T < 1 || T >= TG_T_ORI_LIMIT || arr < 0 || arr >= TG_TIME_LIMIT) { delete t; return TG_E_RANGE; }
+        if (arr < prev) { delete t; return TG_E_INVALID_ARG; }
+        prev = arr;
+        sumT += T;
+        const uint32_t param = d->act_param[g];
+        if (model == TG_MODEL_AMDAHL && param > 1000000u) { delete t; return TG_E_ELASTICITY; }
+        if (model == TG_MODEL_TABLE && param >= (uint32_t)d->n_classes) { delete t; return TG_E_ELASTICITY; }
+        uint32_t mask = d->act_kmask[g] & ((1u << d->type_k[ty]) - 1u);
+        if (model == TG_MODEL_NONE) mask &= (~mask + 1u);
+        int pin = d->act_pin_node[g];
+        if (pin < 0) pin = -1;
+        bool infeasible = mask == 0;
+        if (!infeasible) {
+          const int kmin = d->k_list[__builtin_ctz(mask)];
+          if (pin >= 0) infeasible = pin >= M || d->node_type[(size_t)s * M + pin] != ty || kmin > d->node_cap[(size_t)s * M + pin];
+          else infeasible = kmin > max_cap[(size_t)s * 3 + ty];
+        }
+        if (pin >= M) pin = M;
+        ((int64_t*)at(o_arr))[g] = arr;
+        ((uint8_t*)at(o_atype))[g] = (uint8_t)ty;
+        ((uint8_t*)at(o_amodel))[g] = (uint8_t)model;
+        ((uint8_t*)at(o_astat))[g] = infeasible;
+        ((int64_t*)at(o_aT))[g] = T;
+        ((uint32_t*)at(o_amask))[g] = mask;
+        ((uint32_t*)at(o_aparam))[g] = param;
+        ((int32_t*)at(o_apin))[g] = pin;
+      }
+      if (sumT >= TG_SUM_T_LIMIT) { delete t; return TG_E_RANGE; }
+    }
+    if (d->n_classes) std::memcpy(at(o_speed), d->speedup_q16, (size_t)d->n_classes * K * 4);
+
+    t->arena_bytes = host.size();
+    if (hipMalloc(&t->d_arena, t->arena_bytes) != hipSuccess) { delete t; return TG_E_NOMEM; }
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (hipMemcpyAsync(t->d_arena, host.data(), t->arena_bytes, hipMemcpyHostToDevice, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess) {
+      (void)hipFree(t->d_arena); delete t; return TG_E_HIP;
+    }
+    char* base = (char*)t->d_arena;
+    TgTraceDev& v = t->dev;
+    v.S = S; v.A = A; v.M = M; v.K = K; v.n_classes = d->n_classes; v.depth = d->depth; v.max_ticks = d->max_ticks;
+    v.tick_us = d->tick_us;
+    for (int q = 0; q < TG_MAX_K; ++q) v.k_list[q] = q < K ? d->k_list[q] : 0;
+    for (int k = 0; k < 3; ++k) v.type_k[k] = d->type_k[k];
+    v.type_k[3] = 0;
+    v.node_type = (const uint8_t*)(base + o_ntype); v.node_cap = (const int32_t*)(base + o_ncap);
+    v.quota_rate = (const int32_t*)(base + o_rate); v.quota_tok0 = (const int64_t*)(base + o_tok);
+    v.node_rank = (const int32_t*)(base + o_rank); v.tnode_idx = (const int32_t*)(base + o_tnidx);
+    v.tnode_off = (const int32_t*)(base + o_tnoff);
+    v.arrival = (const int64_t*)(base + o_arr); v.act_type = (const uint8_t*)(base + o_atype);
+    v.act_model = (const uint8_t*)(base + o_amodel); v.act_static = (const uint8_t*)(base + o_astat);
+    v.act_T = (const int64_t*)(base + o_aT); v.act_kmask = (const uint32_t*)(base + o_amask);
+    v.act_param = (const uint32_t*)(base + o_aparam); v.act_pin = (const int32_t*)(base + o_apin);
+    v.speedup = (const uint32_t*)(base + o_speed);
+    t->max_nodes_of_kind = max_kind; t->max_cap_cpu = max_cap_cpu; t->max_heap = max_heap;
+    t->max_chunk_states = 60;   // an 8-GPU node never has more than 4,2,1,1 free chunks of size 1,2,4,8
+  } catch (const std::bad_alloc&) {
+    delete t;
+    return TG_E_NOMEM;
+  }
+  *out = t;
+  return TG_OK;
+}
+
+extern "C" void tg_free_trace(tg_trace* t) {
+  if (!t) return;
+  if (t->d_arena) (void)hipFree(t->d_arena);
+  delete t;
+}
+
+extern "C" int tg_replay_workspace_bytes(const tg_trace* t, size_t* bytes) {
+  if (!t || !bytes) return TG_E_INVALID_ARG;
+  *bytes = carve(t->dev, nullptr, nullptr);
+  return TG_OK;
+}
+
+extern "C" int tg_replay_trace(const tg_trace* t, const tg_replay_out* out, void* d_ws, size_t ws_bytes, void* hip_stream) {
+  if (!t || !out || !out->start_us || !out->finish_us || !out->units || !out->node || !out->mean_act_us ||
+      !out->p99_act_us || !out->n_started || !out->n_ticks)
+    return TG_E_INVALID_ARG;
+  if (!d_ws || ((uintptr_t)d_ws & 255) || ws_bytes < carve(t->dev, nullptr, nullptr)) return TG_E_WORKSPACE;
+  hipStream_t s = (hipStream_t)hip_stream;
+  const TgTraceDev& T = t->dev;
+  ReplayWs W;
+  carve(T, (char*)d_ws, &W);
+  const TgNodeLdsPlan plan = tg_node_lds_plan(t->max_cap_cpu, 8, t->max_chunk_states, t->max_heap, T.K);
+  const int busy_slots = (t->max_heap + 1 + 1) & ~1;
+  const size_t pool_bytes = (tg_pool_lds_bytes(t->max_nodes_of_kind) + 15) & ~size_t(15);
+  const size_t lds = 3 * pool_bytes + (size_t)kWaves * ((size_t)plan.total + (size_t)busy_slots * 8);
+  if (lds > 160 * 1024 - 2048) return TG_E_RANGE;
+  TG_HIP_CHECK(hipFuncSetAttribute((const void*)tg_replay_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  const size_t total = (size_t)T.S * T.A * T.K;
+  hipLaunchKernelGGL(tg_trace_dur_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, T, W.dur);
+  hipLaunchKernelGGL(tg_replay_kernel, dim3(T.S), dim3(kThreads), lds, s, T, W, *out, t->max_nodes_of_kind, plan, busy_slots);
+  return hipGetLastError() == hipSuccess ? TG_OK : TG_E_HIP;
+}

@@ -167,6 +167,29 @@ __device__ static inline void tg_place_pool(const TgPoolLds& S, const TgPlaceIo&
   tg_wave_sync();
 }
 
+// List extents per node after tg_place_pool: exclusive scan of the per-node counts in rank
+// order, starting at `a0` (the pool's first slot in the order arrays).
+__device__ static inline void tg_pool_extents(const TgPoolLds& S, const int32_t* nodes, int Mt, int a0, int32_t* nl_off,
+                                              int32_t* nl_cnt, int32_t* dl_off, int32_t* dl_cnt, int lane) {
+  int run = a0, drun = a0;
+  for (int base = 0; base < Mt; base += TG_WAVE) {
+    const int r = base + lane;
+    const int c = r < Mt ? S.cnt[r] : 0, dc = r < Mt ? S.dcnt[r] : 0;
+    int inc = c, dinc = dc;
+    for (int o = 1; o < TG_WAVE; o <<= 1) {
+      const int u = __shfl_up(inc, o), du = __shfl_up(dinc, o);
+      if (lane >= o) { inc += u; dinc += du; }
+    }
+    if (r < Mt) {
+      const int g = nodes[r];
+      nl_off[g] = run + inc - c; nl_cnt[g] = c;
+      dl_off[g] = drun + dinc - dc; dl_cnt[g] = dc;
+    }
+    run += __shfl(inc, TG_WAVE - 1);
+    drun += __shfl(dinc, TG_WAVE - 1);
+  }
+}
+
 // ---------------------------------------------------------------------------- per node
 struct TgNodeLdsPlan {
   int off_cdur, off_dp, off_choice, off_heap, off_rowbest, off_rowarg, off_sel, off_pos, off_k;

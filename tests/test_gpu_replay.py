@@ -1,0 +1,102 @@
+"""GPU parity of tg_replay_trace against the CPU oracle: start / finish / units / node of every
+action and the per-scenario count, tick count and p99 bit for bit; mean ACT within 1e-9."""
+import numpy as np
+import pytest
+
+import gen
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def tg():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2603_13019_amd import tg as _tg
+    _tg.load()
+    return _tg
+
+
+def _replay_gpu(tg, t):
+    import torch
+    T = tg.Trace(t)
+    bufs = T.alloc()
+    for k in ("start_us", "finish_us", "units", "node", "p99_act_us", "n_started", "n_ticks"):
+        bufs[k].fill_(-5)
+    T.replay(bufs)
+    torch.cuda.synchronize()
+    out = {k: v.cpu().numpy() for k, v in bufs.items() if k != "ws"}
+    T.free()
+    return out
+
+
+def _compare(got, want, scenarios, A):
+    for s in scenarios:
+        sl = slice(s * A, (s + 1) * A)
+        for k in ("start_us", "finish_us", "units", "node"):
+            np.testing.assert_array_equal(got[k][sl], want[k][sl], err_msg=f"scenario {s} {k}")
+        assert got["n_started"][s] == want["n_started"][s]
+        assert got["n_ticks"][s] == want["n_ticks"][s]
+        assert got["p99_act_us"][s] == want["p99_act"][s]
+        np.testing.assert_allclose(got["mean_act_us"][s], want["mean_act"][s], rtol=1e-9, atol=0)
+
+
+CASES = {
+    "contended_small": dict(S=6, A=400, seed=21, contended=True, rate_per_s=80.0, horizon_s=5.0, max_ticks=20000),
+    "contended_burst": dict(S=4, A=700, seed=22, contended=True, rate_per_s=400.0, horizon_s=2.0, max_ticks=30000),
+    "default_cluster": dict(S=4, A=1500, seed=23, rate_per_s=50.0, horizon_s=30.0),
+    "cpu_only_tiny_cluster": dict(S=5, A=300, seed=24, cluster=(2, 6, 0, 0), rate_per_s=30.0, horizon_s=10.0, max_ticks=50000),
+    "gpu_only": dict(S=5, A=300, seed=25, cluster=(0, 0, 3, 0), type_probs=(0, 1, 0), rate_per_s=30.0, horizon_s=10.0, max_ticks=50000),
+    "api_only": dict(S=3, A=500, seed=26, cluster=(0, 0, 0, 2), type_probs=(0, 0, 1), rate_per_s=300.0, horizon_s=2.0, max_ticks=50000),
+    "tick_limit": dict(S=3, A=500, seed=27, contended=True, rate_per_s=500.0, horizon_s=1.0, max_ticks=40),
+    "single_action": dict(S=2, A=1, seed=28, contended=True),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_replay_small(tg, orc, name):
+    print("case", name, flush=True)
+    t = gen.make_trace(**CASES[name])
+    want = orc.replay(t)
+    got = _replay_gpu(tg, t)
+    _compare(got, want, range(t["S"]), t["A"])
+
+
+def test_replay_depth_and_ties(tg, orc):
+    t = gen.make_trace(S=4, A=500, seed=31, contended=True, rate_per_s=120.0, horizon_s=4.0, max_ticks=30000)
+    t["depth"] = 3
+    t["act_t_ori_us"][:] = (t["act_t_ori_us"] // 500_000 + 1) * 500_000      # few distinct durations: ties
+    _compare(_replay_gpu(tg, t), orc.replay(t), range(4), 500)
+
+
+def test_replay_config5_sampled(tg, orc):
+    """Workload 5 shape (10 000 arrivals over 200 s per scenario, default cluster) on 64 scenarios in one
+    launch; the oracle replays 3 of them."""
+    t = gen.make_trace(S=64, A=10_000, seed=4)
+    got = _replay_gpu(tg, t)
+    pick = [0, 31, 63]
+    want = orc.replay(t, 0, 1)
+    for s in pick[1:]:
+        w = orc.replay(t, s, s + 1)
+        for k in want:
+            if want[k].shape[0] == t["S"]:
+                want[k][s] = w[k][s]
+            else:
+                want[k][s * t["A"]:(s + 1) * t["A"]] = w[k][s * t["A"]:(s + 1) * t["A"]]
+    _compare(got, want, pick, t["A"])
+    assert (got["n_started"] == t["A"]).all()
+    assert (got["start_us"] >= t["arrival_us"]).all() and (got["start_us"] % t["tick_us"] == 0).all()
+
+
+def test_replay_config5_contended_sampled(tg, orc):
+    t = gen.make_trace(S=32, A=10_000, seed=5, contended=True, max_ticks=200_000)
+    got = _replay_gpu(tg, t)
+    pick = [0, 31]
+    want = orc.replay(t, 0, 1)
+    w = orc.replay(t, 31, 32)
+    for k in want:
+        if want[k].shape[0] == t["S"]:
+            want[k][31] = w[k][31]
+        else:
+            want[k][31 * t["A"]:32 * t["A"]] = w[k][31 * t["A"]:32 * t["A"]]
+    _compare(got, want, pick, t["A"])
