@@ -1,0 +1,116 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol
+include/tg.h declares, and rejects bad descriptions with the documented error codes before
+anything touches the device."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import gen
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def tg():
+    from paper_2603_13019_amd import tg as _tg
+    _tg.load()
+    return _tg
+
+
+def test_header_symbols_are_exported(tg):
+    hdr = open(os.path.join(ROOT, "include", "tg.h")).read()
+    declared = set(re.findall(r"\b(tg_[a-z_]+)\s*\(", hdr))
+    assert declared == set(tg.EXPORTS)
+    lib = tg.load()
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_strerror(tg):
+    assert tg.strerror(0) == "ok"
+    for code in range(-6, 0):
+        assert tg.strerror(code) not in ("ok", "unknown error")
+    assert tg.strerror(-99) == "unknown error"
+
+
+def test_struct_layouts_match_header(tg):
+    assert C.sizeof(tg.ProblemDesc) == 8 * 4 + 18 * 8
+    assert C.sizeof(tg.AssignOut) == 8 * 8
+    assert C.sizeof(tg.TraceDesc) == 8 * 4 + 8 + 14 * 8
+    assert C.sizeof(tg.ReplayOut) == 8 * 8
+    assert tg.SUMMARY_DTYPE.itemsize == 8 + 16 + 24 + 24 + 8 + 24
+
+
+def _build_rc(tg, p):
+    d = tg.ProblemDesc()
+    for n in ("B", "N", "M", "K", "n_classes", "n_tasks", "depth"):
+        setattr(d, n, int(p[n]))
+    d.flags = int(p.get("flags", 0))
+    keep = []
+    tg._fill(d, p, [f[0] for f in tg.ProblemDesc._fields_[8:]], keep)
+    h = C.c_void_p()
+    rc = tg.load().tg_build_problem(C.byref(d), None, C.byref(h))
+    assert rc != 0 and not h.value
+    return rc
+
+
+BAD = {
+    "k_list_not_ascending": (lambda p: p["k_list"].__setitem__(1, 1), -1),
+    "unit_above_limit": (lambda p: p["k_list"].__setitem__(3, 65), -1),
+    "flags": (lambda p: p.__setitem__("flags", 1), -1),
+    "depth": (lambda p: p.__setitem__("depth", 9), -1),
+    "free_above_cap": (lambda p: p["node_free"].__setitem__(0, 33), -1),
+    "node_kind": (lambda p: p["node_type"].__setitem__(0, 7), -1),
+    "model": (lambda p: p["act_model"].__setitem__(5, 3), -1),
+    "missing_array": (lambda p: p.__setitem__("act_kmask", None), -1),
+    "t_ori_zero": (lambda p: p["act_t_ori_us"].__setitem__(3, 0), -2),
+    "t_ori_too_large": (lambda p: p["act_t_ori_us"].__setitem__(3, 1 << 36), -2),
+    "backlog_negative": (lambda p: p["node_backlog_us"].__setitem__(1, -1), -2),
+    "age_too_large": (lambda p: p["act_age_us"].__setitem__(1, 1 << 40), -2),
+    "cpu_node_too_large": (lambda p: p["node_cap"].__setitem__(0, 257), -2),
+    "amdahl_fraction": (lambda p: p["act_param"].__setitem__(2, 1_000_001), -3),
+    "speedup_decreasing": (lambda p: p["speedup_q16"].__setitem__(1, 65536 // 2), -3),
+    "speedup_superlinear": (lambda p: p["speedup_q16"].__setitem__(1, 65536 * 2 + 1), -3),
+    "task_out_of_range": (lambda p: p["act_task"].__setitem__(0, 5), -1),
+}
+
+
+@pytest.mark.parametrize("name", list(BAD))
+def test_build_rejects(tg, name):
+    p = gen.make_config(1)
+    p = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in p.items()}
+    mutate, want = BAD[name]
+    mutate(p)
+    assert _build_rc(tg, p) == want
+
+
+def test_build_rejects_gpu_specifics(tg):
+    p = gen.make_random_problem(2, B=1, N=10, n_cpu=1, n_gpu=1, n_api=1, shuffle_nodes=False, busy=False)
+    q = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in p.items()}
+    q["node_chunks"][1 * 4 + 0] += 1                       # chunk counts no longer add up to node_free
+    assert _build_rc(tg, q) == -1
+    q = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in p.items()}
+    q["k_list"] = np.array([1, 2, 3, 8], np.int32)         # GPU options must be 1, 2, 4, 8
+    assert _build_rc(tg, q) == -1
+    q = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in p.items()}
+    api = np.flatnonzero(q["act_type"] == gen.TYPE_API)
+    if api.size:
+        q["act_model"][api[0]] = 1                         # API actions cannot be elastic
+        assert _build_rc(tg, q) == -1
+
+
+def test_null_arguments(tg):
+    L = tg.load()
+    assert L.tg_build_problem(None, None, None) == -1
+    assert L.tg_num_candidates(None, None, None) == -1
+    assert L.tg_assign_workspace_bytes(None, None) == -1
+    assert L.tg_score_candidates(None, None, None) == -1
+    assert L.tg_assign(None, None, None, None, 0, None) == -1
+    assert L.tg_build_trace(None, None, None) == -1
+    assert L.tg_replay_workspace_bytes(None, None) == -1
+    assert L.tg_replay_trace(None, None, None, 0, None) == -1
+    L.tg_free_problem(None)
+    L.tg_free_trace(None)
