@@ -2,6 +2,7 @@
 // action and node, group them by resource kind and ship one packed copy to the device.
 #include <algorithm>
 #include <cstring>
+#include <cstdlib>
 #include <new>
 #include <vector>
 
@@ -202,35 +203,64 @@ extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_p
 
     // ---------------- blocks of the score tensor and the score kernel's work split
     const size_t o_blocks = ar.add((size_t)B * 3 * sizeof(TgBlock));
+    const size_t o_rowrec = ar.add(nA * sizeof(TgRowRec)), o_rowpin = ar.add(nA * 4), o_nword = ar.add(nN * 8);
     int64_t total = 0, wgs = 0;
-    int lds_nodes = 1;
+    int lds_nodes = 1, dur_slots = 2, row_slots = 2;
     for (int b = 0; b < B; ++b)
       for (int t = 0; t < 3; ++t) {
         TgBlock& k = ar.at<TgBlock>(o_blocks)[(size_t)b * 3 + t];
         const int32_t* ta = ar.at<int32_t>(o_taoff) + (size_t)b * 4;
         const int32_t* tn = ar.at<int32_t>(o_tnoff) + (size_t)b * 4;
         k.b = b; k.t = t; k.rows = ta[t + 1] - ta[t]; k.M_t = tn[t + 1] - tn[t]; k.K_t = d->type_k[t];
+        k.a_off = (int32_t)((size_t)b * N + ta[t]); k.n_off = (int32_t)((size_t)b * M + tn[t]);
         k.entries = (int64_t)k.rows * k.M_t * k.K_t;
-        if (k.entries >= (1ll << 31)) { delete p; return TG_E_RANGE; }
+        if (k.entries >= (1ll << 31) - (1 << 20)) { delete p; return TG_E_RANGE; }   // 32-bit indices inside a block
+        const uint32_t lr = (uint32_t)(k.M_t * k.K_t);
+        k.magic_lr = lr > 1 ? (uint32_t)((1ull << 32) / lr) + 1u : 0u;
+        k.magic_k = k.K_t > 1 ? (uint32_t)((1ull << 32) / (uint32_t)k.K_t) + 1u : 0u;
         k.cost_off = total;
-        // entries per workgroup: at most 8192, fewer when rows are so short that the per-row
-        // duration table (2048 values in LDS) would overflow
-        int span = 8192;
-        const int64_t lr = (int64_t)k.M_t * k.K_t;
-        while (span > 512 && lr > 0 && (span / lr + 2) * k.K_t > 2048) span -= 512;
-        k.span = span;
         k.wg_off = (int32_t)wgs;
-        wgs += (k.entries + span - 1) / span;
+        wgs += (k.entries ? (k.entries + (k.cost_off & 1) + TG_SCORE_SPAN - 1) / TG_SCORE_SPAN : 0);
         total += k.entries;
-        if (k.entries) lds_nodes = std::max<int>(lds_nodes, k.M_t);
+        if (k.entries) {
+          const int rows = (int)std::min<int64_t>(TG_SCORE_SPAN / lr + 2, k.rows);
+          lds_nodes = std::max<int>(lds_nodes, k.M_t);   // a span that crosses a row end needs every node
+          row_slots = std::max(row_slots, rows);
+          dur_slots = std::max(dur_slots, rows * k.K_t);
+        }
+        // kind-grouped views: row of every action, pin rank per row, node word per rank
+        for (int r = 0; r < k.rows; ++r) {
+          const int i = ar.at<int32_t>(o_taidx)[(size_t)b * N + ta[t] + r];
+          const size_t g = (size_t)b * N + i;
+          TgRowRec& rr = ar.at<TgRowRec>(o_rowrec)[(size_t)b * N + ta[t] + r];
+          rr.T = ar.at<int64_t>(o_aT)[g]; rr.param = ar.at<uint32_t>(o_aparam)[g];
+          rr.kmask = (uint16_t)ar.at<uint32_t>(o_amask)[g]; rr.model = ar.at<uint8_t>(o_amodel)[g]; rr.pad_ = 0;
+          const int pin = ar.at<int32_t>(o_apin)[g];
+          int pr = -1;
+          if (pin >= 0) pr = (pin < M && d->node_type[(size_t)b * M + pin] == t) ? ar.at<int32_t>(o_nrank)[(size_t)b * M + pin] : -2;
+          ar.at<int32_t>(o_rowpin)[(size_t)b * N + ta[t] + r] = pr;
+        }
+        for (int r = 0; r < k.M_t; ++r) {
+          const size_t g = (size_t)b * M + ar.at<int32_t>(o_tnidx)[(size_t)b * M + tn[t] + r];
+          uint64_t qmax = 0;
+          while ((int)qmax < k.K_t && d->k_list[qmax] <= d->node_cap[g]) ++qmax;
+          ar.at<uint64_t>(o_nword)[(size_t)b * M + tn[t] + r] = (uint64_t)d->node_backlog_us[g] | qmax << 48;
+        }
       }
     if (wgs >= (1ll << 31)) { delete p; return TG_E_RANGE; }
+    // workgroup -> block lookup of the score kernel (one load instead of a search)
+    const size_t o_wgtab = ar.add(std::max<size_t>((size_t)wgs, 1) * 4);
+    for (int x = 0; x < B * 3; ++x) {
+      const TgBlock& k = ar.at<TgBlock>(o_blocks)[x];
+      const int64_t n = (k.entries ? (k.entries + (k.cost_off & 1) + TG_SCORE_SPAN - 1) / TG_SCORE_SPAN : 0);
+      for (int64_t w = 0; w < n; ++w) ar.at<int32_t>(o_wgtab)[k.wg_off + w] = x;
+    }
 
     // ---------------- ship
     p->arena_bytes = ar.host.size();
     if (hipMalloc(&p->d_arena, p->arena_bytes) != hipSuccess) { delete p; return TG_E_NOMEM; }
     hipStream_t s = (hipStream_t)hip_stream;
-    if (hipMemcpyAsync(p->d_arena, ar.host.data(), p->arena_bytes, hipMemcpyHostToDevice, s) != hipSuccess ||
+    if (hipMemcpyAsync(p->d_arena, ar.host.data(), ar.host.size(), hipMemcpyHostToDevice, s) != hipSuccess ||
         hipStreamSynchronize(s) != hipSuccess) {
       hipFree(p->d_arena); delete p; return TG_E_HIP;
     }
@@ -252,7 +282,10 @@ extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_p
     v.act_task = (const int32_t*)(base + o_atask); v.speedup = (const uint32_t*)(base + o_speed);
     v.tact_idx = (const int32_t*)(base + o_taidx); v.tact_off = (const int32_t*)(base + o_taoff);
     v.tnode_idx = (const int32_t*)(base + o_tnidx); v.tnode_off = (const int32_t*)(base + o_tnoff);
+    v.row_rec = (const TgRowRec*)(base + o_rowrec); v.row_pin = (const int32_t*)(base + o_rowpin);
+    v.node_word = (const uint64_t*)(base + o_nword);
     p->d_blocks = (TgBlock*)(base + o_blocks);
+    p->d_wg_block = (const int32_t*)(base + o_wgtab);
     p->n_blocks = B * 3;
     p->score_wgs = (int)wgs;
     p->n_candidates = total;
@@ -261,7 +294,7 @@ extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_p
     p->max_heap = max_heap;
     p->max_free_gpu = max_free_gpu;
     p->max_chunk_states = max_states;
-    p->score_lds_nodes = lds_nodes;
+    p->score_lds_nodes = lds_nodes; p->score_dur_slots = (dur_slots + 1) & ~1; p->score_row_slots = row_slots;
   } catch (const std::bad_alloc&) {
     delete p;
     return TG_E_NOMEM;

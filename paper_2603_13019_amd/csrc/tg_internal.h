@@ -8,6 +8,7 @@
 #include "tg.h"
 
 #define TG_WAVE 64
+#define TG_SCORE_SPAN 4096  // entries of the score tensor per workgroup: 8 steps of 256 lanes x 2 entries
 
 // Packed device copy of a problem.  Passed to kernels by value; all pointers are device memory.
 struct TgDev {
@@ -39,15 +40,30 @@ struct TgDev {
   const int32_t* tact_off;        // [B*4] group starts (entry 3 = N)
   const int32_t* tnode_idx;       // [B*M] node ids grouped by kind
   const int32_t* tnode_off;       // [B*4]
+  // kind-grouped views used by the score kernel
+  const struct TgRowRec* row_rec; // [B*N] kind-grouped: what Eq. 1 needs of an action
+  const int32_t* row_pin;         // [B*N] kind-grouped: rank of the pinned node inside the kind, -1 free, -2 matches nothing
+  const uint64_t* node_word;      // [B*M] kind-grouped: backlog | (options admitted by the capacity) << 48
+};
+
+// Kind-grouped copy of the fields of an action that Eq. 1 reads (16 bytes, one load).
+struct TgRowRec {
+  int64_t T;
+  uint32_t param;
+  uint16_t kmask;
+  uint8_t model, pad_;
 };
 
 // One dense block of the score tensor: actions of one kind x nodes of that kind x options.
 struct TgBlock {
   int64_t cost_off;   // first entry of the block in the tensor
-  int64_t entries;    // rows * M_t * K_t
+  int64_t entries;    // rows * M_t * K_t  (< 2^31)
   int32_t wg_off;     // first workgroup of the score kernel that works on this block
-  int32_t span;       // entries per workgroup
-  int32_t rows, M_t, K_t, b, t, pad_;
+  int32_t rows, M_t, K_t, b, t;
+  int32_t a_off;      // b*N + first action of the kind in the kind-grouped order
+  int32_t n_off;      // b*M + first node of the kind in the kind-grouped order
+  uint32_t magic_lr;  // floor(2^32 / (M_t*K_t)) + 1: x / (M_t*K_t) == umulhi(x, magic) for the x used
+  uint32_t magic_k;   // same for K_t
 };
 
 struct tg_problem {
@@ -55,6 +71,7 @@ struct tg_problem {
   void* d_arena;
   size_t arena_bytes;
   TgBlock* d_blocks;       // inside the arena
+  const int32_t* d_wg_block;  // score kernel: workgroup -> block index
   int n_blocks;
   int score_wgs;
   int64_t n_candidates;
@@ -62,7 +79,8 @@ struct tg_problem {
   int max_free_cpu;        // largest node_free over CPU nodes
   int max_heap;            // largest free + busy over CPU and GPU nodes
   int max_free_gpu, max_chunk_states;
-  int score_lds_nodes;     // node-table window of the score kernel
+  int score_lds_nodes;     // largest node table a score workgroup stages
+  int score_dur_slots, score_row_slots;   // (row, option) durations and rows one workgroup may touch
 };
 
 __host__ __device__ static inline int tg_chunk_level(int k) { return k <= 1 ? 0 : (k <= 2 ? 1 : (k <= 4 ? 2 : 3)); }
