@@ -11,6 +11,8 @@
 // The FCFS loop is sequential by definition (every action sees the capacity left by the ones
 // before it), so tg_place_kernel keeps the node table of its pool in LDS and spends its 64
 // lanes on the argmin over nodes; parallelism comes from the batch of snapshots.
+#include <algorithm>
+
 #include "tg_step.h"
 
 namespace {
@@ -21,7 +23,15 @@ struct AssignWs {
   int32_t* order;    // [B*N]   admitted actions grouped by node
   int32_t* dorder;   // [B*N]   waiting actions pinned to a node (deferred by the prefix rule)
   int32_t *nl_off, *nl_cnt, *dl_off, *dl_cnt;   // [B*M] list extents per node
+  int32_t* class_list;   // [kClasses][B*M] nodes with candidates, binned by how many
+  int32_t* class_ctl;    // [2*kClasses] per class: number of nodes, next node to hand out
 };
+
+// Nodes are processed in classes of candidate count so that the LDS a wavefront needs (the
+// choice table grows with m) does not cap the occupancy of the many small nodes.
+constexpr int kClasses = 3;
+constexpr int kClassCap0 = 16, kClassCap1 = 64;
+__host__ __device__ constexpr int class_cap(int c) { return c == 0 ? kClassCap0 : c == 1 ? kClassCap1 : 1 << 30; }
 
 size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
@@ -31,7 +41,9 @@ size_t carve(const tg_problem* p, char* base, AssignWs* w) {
   auto take = [&](size_t bytes) { char* r = base + off; off += align256(bytes); return r; };
   char* a = take(nA * p->dev.K * 8); char* b = take(nA * 4); char* c = take(nA * 4); char* d = take(nA * 4);
   char* e = take(nN * 4); char* f = take(nN * 4); char* g = take(nN * 4); char* h = take(nN * 4);
+  char* cl = take(nN * 4 * kClasses); char* cc = take(2 * kClasses * 4);
   if (w) {
+    w->class_list = (int32_t*)cl; w->class_ctl = (int32_t*)cc;
     w->dur = (int64_t*)a; w->slot = (int32_t*)b; w->order = (int32_t*)c; w->dorder = (int32_t*)d;
     w->nl_off = (int32_t*)e; w->nl_cnt = (int32_t*)f; w->dl_off = (int32_t*)g; w->dl_cnt = (int32_t*)h;
   }
@@ -39,8 +51,9 @@ size_t carve(const tg_problem* p, char* base, AssignWs* w) {
 }
 
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void tg_dur_kernel(TgDev P, int64_t* __restrict__ dur) {
+__global__ __launch_bounds__(256) void tg_dur_kernel(TgDev P, int64_t* __restrict__ dur, int32_t* __restrict__ class_ctl) {
   const size_t x = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (x < 2 * kClasses) class_ctl[x] = 0;
   const size_t total = (size_t)P.B * P.N * P.K;
   if (x >= total) return;
   const size_t g = x / P.K;
@@ -93,58 +106,83 @@ __global__ __launch_bounds__(TG_WAVE) void tg_place_kernel(TgDev P, const int64_
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void tg_lists_kernel(TgDev P, AssignWs W, tg_assign_out O) {
   const size_t g = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (g >= (size_t)P.B * P.N) return;
-  const int b = (int)(g / P.N), i = (int)(g - (size_t)b * P.N);
-  const int r = O.defer_reason[g];
-  if (r == TG_SELECTED) {
-    const size_t n = (size_t)b * P.M + O.node[g];
-    W.order[(size_t)b * P.N + W.nl_off[n] + W.slot[g]] = i;
-  } else if (r == TG_DEFER_PREFIX && P.act_pin[g] >= 0) {
-    const size_t n = (size_t)b * P.M + P.act_pin[g];
-    W.dorder[(size_t)b * P.N + W.dl_off[n] + W.slot[g]] = i;
+  const size_t nA = (size_t)P.B * P.N, nN = (size_t)P.B * P.M;
+  if (g < nA) {
+    const int b = (int)(g / P.N), i = (int)(g - (size_t)b * P.N);
+    const int r = O.defer_reason[g];
+    if (r == TG_SELECTED) {
+      const size_t n = (size_t)b * P.M + O.node[g];
+      W.order[(size_t)b * P.N + W.nl_off[n] + W.slot[g]] = i;
+    } else if (r == TG_DEFER_PREFIX && P.act_pin[g] >= 0) {
+      const size_t n = (size_t)b * P.M + P.act_pin[g];
+      W.dorder[(size_t)b * P.N + W.dl_off[n] + W.slot[g]] = i;
+    }
+  } else if (g < nA + nN) {                    // one thread per node: class bins, defaults of idle nodes
+    const size_t gn = g - nA;
+    const int m = W.nl_cnt[gn];
+    if (O.node_obj) O.node_obj[gn] = -1;
+    if (m == 0) { if (O.node_used) O.node_used[gn] = 0; return; }
+    const int c = m <= kClassCap0 ? 0 : m <= kClassCap1 ? 1 : 2;
+    const int pos = atomicAdd(&W.class_ctl[2 * c], 1);       // order inside a class does not matter
+    W.class_list[(size_t)c * nN + pos] = (int32_t)gn;
   }
 }
 
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(TG_WAVE) void tg_node_kernel(TgDev P, const int64_t* __restrict__ dur, AssignWs W,
-                                                          tg_assign_out O, TgNodeLdsPlan plan) {
+                                                          tg_assign_out O, TgNodeLdsPlan plan, int cls) {
   extern __shared__ __align__(16) unsigned char smem[];
-  const int gn = blockIdx.x, lane = threadIdx.x;
-  const int b = gn / P.M;
-  const size_t abase = (size_t)b * P.N;
-  if (O.node_obj && lane == 0) O.node_obj[gn] = -1;
-  const int m = W.nl_cnt[gn];
-  if (m == 0) return;
-  TgNodeIn in;
-  in.type = P.node_type[gn]; in.cap = P.node_cap[gn]; in.free_units = P.node_free[gn];
-  in.backlog = P.node_backlog[gn]; in.chunks = P.node_chunks[gn];
-  in.m = m; in.clist = W.order + abase + W.nl_off[gn];
-  in.nd = W.dl_cnt[gn]; in.dlist = W.dorder + abase + W.dl_off[gn];
-  in.n_busy = P.has_busy ? P.node_busy_off[gn + 1] - P.node_busy_off[gn] : 0;
-  in.busy = P.node_busy_rel + (P.has_busy ? P.node_busy_off[gn] : 0);
-
-  in.act_model = P.act_model + abase; in.act_kmask = P.act_kmask + abase; in.dur = dur + abase * P.K;
-  in.K = P.K; in.depth = P.depth;
-  for (int q = 0; q < TG_MAX_K; ++q) in.k_list[q] = P.k_list[q];
-  TgNodeOut out;
-  out.node = O.node + abase; out.units = O.units + abase; out.act = O.act_us + abase; out.reason = O.defer_reason + abase;
-  out.age = P.act_age + abase;
-  const int64_t obj = tg_node_schedule(smem, plan, in, out, lane);
-  if (O.node_obj && lane == 0) O.node_obj[gn] = obj;
+  const int lane = threadIdx.x;
+  const size_t nN = (size_t)P.B * P.M;
+  const int n_nodes = W.class_ctl[2 * cls];
+  const int32_t* list = W.class_list + (size_t)cls * nN;
+  for (;;) {
+    int idx = 0;
+    if (lane == 0) idx = atomicAdd(&W.class_ctl[2 * cls + 1], 1);     // next unprocessed node of the class
+    idx = __builtin_amdgcn_readfirstlane(idx);
+    if (idx >= n_nodes) break;
+    const int gn = list[idx];
+    const int b = gn / P.M;
+    const size_t abase = (size_t)b * P.N;
+    TgNodeIn in;
+    in.type = P.node_type[gn]; in.cap = P.node_cap[gn]; in.free_units = P.node_free[gn];
+    in.backlog = P.node_backlog[gn]; in.chunks = P.node_chunks[gn];
+    in.m = W.nl_cnt[gn]; in.clist = W.order + abase + W.nl_off[gn];
+    in.nd = W.dl_cnt[gn]; in.dlist = W.dorder + abase + W.dl_off[gn];
+    in.n_busy = P.has_busy ? P.node_busy_off[gn + 1] - P.node_busy_off[gn] : 0;
+    in.busy = P.node_busy_rel + (P.has_busy ? P.node_busy_off[gn] : 0);
+    in.busy_lds_off = -1;
+    in.act_model = P.act_model + abase; in.act_kmask = P.act_kmask + abase; in.dur = dur + abase * P.K;
+    in.K = P.K; in.depth = P.depth;
+    for (int q = 0; q < TG_MAX_K; ++q) in.k_list[q] = P.k_list[q];
+    TgNodeOut out;
+    out.node = O.node + abase; out.units = O.units + abase; out.act = O.act_us + abase; out.reason = O.defer_reason + abase;
+    out.age = P.act_age + abase;
+    int used = 0;
+    const int64_t obj = tg_node_schedule(smem, plan, in, out, lane, &used);
+    if (lane == 0) {
+      if (O.node_obj) O.node_obj[gn] = obj;
+      if (O.node_used) O.node_used[gn] = used;
+    }
+  }
 }
 
 // ------------------------------------------------------------------------------------------
+constexpr int kTaskLds = 2048;
+
 __global__ __launch_bounds__(256) void tg_summary_kernel(TgDev P, tg_assign_out O) {
   __shared__ long long s_sum;
   __shared__ int s_cnt[4];
   __shared__ long long s_used[3], s_free[3];
+  __shared__ long long s_task[kTaskLds];
   const int b = blockIdx.x, tid = threadIdx.x;
   const size_t abase = (size_t)b * P.N, nbase = (size_t)b * P.M;
+  const bool task_lds = O.task_sum_us && P.n_tasks <= kTaskLds;
   if (tid == 0) s_sum = 0;
   if (tid < 4) s_cnt[tid] = 0;
   if (tid < 3) { s_used[tid] = 0; s_free[tid] = 0; }
-  if (O.node_used) for (int j = tid; j < P.M; j += 256) O.node_used[nbase + j] = 0;
-  if (O.task_sum_us) for (int k = tid; k < P.n_tasks; k += 256) O.task_sum_us[(size_t)b * P.n_tasks + k] = 0;
+  if (task_lds) for (int k = tid; k < P.n_tasks; k += 256) s_task[k] = 0;
+  else if (O.task_sum_us) for (int k = tid; k < P.n_tasks; k += 256) O.task_sum_us[(size_t)b * P.n_tasks + k] = 0;
   __syncthreads();
   long long sum = 0, used[3] = {0, 0, 0}, fr[3] = {0, 0, 0};
   int cnt[4] = {0, 0, 0, 0};
@@ -154,21 +192,29 @@ __global__ __launch_bounds__(256) void tg_summary_kernel(TgDev P, tg_assign_out 
     ++cnt[r];
     if (r == TG_SELECTED) {
       const long long a = O.act_us[g];
-      const int u = O.units[g];
       sum += a;
-      used[P.act_type[g]] += u;
-      if (O.node_used) atomicAdd(&O.node_used[nbase + O.node[g]], u);
-      if (O.task_sum_us) atomicAdd((unsigned long long*)&O.task_sum_us[(size_t)b * P.n_tasks + P.act_task[g]], (unsigned long long)a);
+      used[P.act_type[g]] += O.units[g];
+      if (task_lds) atomicAdd((unsigned long long*)&s_task[P.act_task[g]], (unsigned long long)a);
+      else if (O.task_sum_us) atomicAdd((unsigned long long*)&O.task_sum_us[(size_t)b * P.n_tasks + P.act_task[g]], (unsigned long long)a);
     }
   }
   for (int j = tid; j < P.M; j += 256) fr[P.node_type[nbase + j]] += P.node_free[nbase + j];
-  atomicAdd((unsigned long long*)&s_sum, (unsigned long long)sum);
-  for (int k = 0; k < 4; ++k) if (cnt[k]) atomicAdd(&s_cnt[k], cnt[k]);
-  for (int k = 0; k < 3; ++k) {
-    if (used[k]) atomicAdd((unsigned long long*)&s_used[k], (unsigned long long)used[k]);
-    if (fr[k]) atomicAdd((unsigned long long*)&s_free[k], (unsigned long long)fr[k]);
+  // wavefront-level integer sums first, one LDS atomic per wavefront and quantity
+  for (int o = 32; o > 0; o >>= 1) {
+    sum += __shfl_xor(sum, o);
+    for (int k = 0; k < 4; ++k) cnt[k] += __shfl_xor(cnt[k], o);
+    for (int k = 0; k < 3; ++k) { used[k] += __shfl_xor(used[k], o); fr[k] += __shfl_xor(fr[k], o); }
+  }
+  if ((tid & 63) == 0) {
+    atomicAdd((unsigned long long*)&s_sum, (unsigned long long)sum);
+    for (int k = 0; k < 4; ++k) atomicAdd(&s_cnt[k], cnt[k]);
+    for (int k = 0; k < 3; ++k) {
+      atomicAdd((unsigned long long*)&s_used[k], (unsigned long long)used[k]);
+      atomicAdd((unsigned long long*)&s_free[k], (unsigned long long)fr[k]);
+    }
   }
   __syncthreads();
+  if (task_lds) for (int k = tid; k < P.n_tasks; k += 256) O.task_sum_us[(size_t)b * P.n_tasks + k] = s_task[k];
   if (tid == 0) {
     tg_summary s;
     s.sum_act_us = s_sum;
@@ -202,17 +248,28 @@ extern "C" int tg_assign(const tg_problem* p, const int64_t* d_cost, const tg_as
   const size_t nA = (size_t)P.B * P.N;
 
   const size_t place_lds = tg_pool_lds_bytes(p->max_nodes_of_kind);
-  const TgNodeLdsPlan plan = tg_node_lds_plan(p->max_free_cpu, p->max_free_gpu, p->max_chunk_states, p->max_heap, P.K);
   if (place_lds > 64 * 1024)
     TG_HIP_CHECK(hipFuncSetAttribute((const void*)tg_place_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)place_lds));
-  if (plan.total > 64 * 1024)
-    TG_HIP_CHECK(hipFuncSetAttribute((const void*)tg_node_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, plan.total));
+  TgNodeLdsPlan plans[kClasses];
+  int max_lds = 0;
+  for (int c = 0; c < kClasses; ++c) {
+    plans[c] = tg_node_lds_plan(p->max_free_cpu, p->max_free_gpu, p->max_chunk_states, p->max_heap, P.K, class_cap(c));
+    max_lds = plans[c].total > max_lds ? plans[c].total : max_lds;
+  }
+  if (max_lds > 64 * 1024)
+    TG_HIP_CHECK(hipFuncSetAttribute((const void*)tg_node_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds));
 
-  hipLaunchKernelGGL(tg_dur_kernel, dim3((unsigned)((nA * P.K + 255) / 256)), dim3(256), 0, s, P, W.dur);
+  const size_t nN = (size_t)P.B * P.M;
+  hipLaunchKernelGGL(tg_dur_kernel, dim3((unsigned)((nA * P.K + 255) / 256)), dim3(256), 0, s, P, W.dur, W.class_ctl);
   hipLaunchKernelGGL(tg_place_kernel, dim3(P.B * 3), dim3(TG_WAVE), place_lds, s, P, W.dur, d_cost, p->d_blocks, W, *out,
                      p->max_nodes_of_kind);
-  hipLaunchKernelGGL(tg_lists_kernel, dim3((unsigned)((nA + 255) / 256)), dim3(256), 0, s, P, W, *out);
-  hipLaunchKernelGGL(tg_node_kernel, dim3(P.B * P.M), dim3(TG_WAVE), plan.total, s, P, W.dur, W, *out, plan);
+  hipLaunchKernelGGL(tg_lists_kernel, dim3((unsigned)((nA + nN + 255) / 256)), dim3(256), 0, s, P, W, *out);
+  // persistent wavefronts pull nodes of their class; enough of them to fill the LDS of every CU
+  for (int c = 0; c < kClasses; ++c) {
+    const int per_cu = std::max(1, std::min(32, (160 * 1024) / std::max(plans[c].total, 1)));
+    const unsigned grid = (unsigned)std::min<size_t>(nN, (size_t)256 * per_cu);
+    hipLaunchKernelGGL(tg_node_kernel, dim3(grid), dim3(TG_WAVE), plans[c].total, s, P, W.dur, W, *out, plans[c], c);
+  }
   hipLaunchKernelGGL(tg_summary_kernel, dim3(P.B), dim3(256), 0, s, P, *out);
   return hipGetLastError() == hipSuccess ? TG_OK : TG_E_HIP;
 }

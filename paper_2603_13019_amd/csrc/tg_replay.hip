@@ -321,12 +321,13 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
       in.chunks = ty == TG_TYPE_GPU ? mask_chunks(lf) : 0;
       in.backlog = 0;
       in.m = m; in.clist = order + nl_off[j]; in.nd = dl_cnt[j]; in.dlist = dorder + dl_off[j];
-      in.n_busy = nb; in.busy = s_busy;
+      in.n_busy = nb; in.busy = nullptr; in.busy_lds_off = plan.total;
       in.act_model = T.act_model + abase; in.act_kmask = T.act_kmask + abase; in.dur = dur; in.K = K; in.depth = T.depth;
       for (int q = 0; q < TG_MAX_K; ++q) in.k_list[q] = T.k_list[q];
       TgNodeOut out;
       out.node = o_node; out.units = o_units; out.act = nullptr; out.reason = reason; out.age = nullptr;
-      tg_node_schedule(node_mem, plan, in, out, lane);
+      int used_units;
+      tg_node_schedule(node_mem, plan, in, out, lane, &used_units);
     }
     __threadfence_block();
     __syncthreads();
@@ -586,7 +587,7 @@ extern "C" int tg_replay_trace(const tg_trace* t, const tg_replay_out* out, void
   const TgTraceDev& T = t->dev;
   ReplayWs W;
   carve(T, (char*)d_ws, &W);
-  const TgNodeLdsPlan plan = tg_node_lds_plan(t->max_cap_cpu, 8, t->max_chunk_states, t->max_heap, T.K);
+  const TgNodeLdsPlan plan = tg_node_lds_plan(t->max_cap_cpu, 8, t->max_chunk_states, t->max_heap, T.K, 1 << 30, 8);
   const int busy_slots = (t->max_heap + 1 + 1) & ~1;
   const size_t pool_bytes = (tg_pool_lds_bytes(t->max_nodes_of_kind) + 15) & ~size_t(15);
   const size_t lds = 3 * pool_bytes + (size_t)kWaves * ((size_t)plan.total + (size_t)busy_slots * 8);

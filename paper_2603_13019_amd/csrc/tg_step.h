@@ -17,21 +17,34 @@
 #define TG_PAD INT64_MAX            // heap slot beyond the heap size
 #define TG_MARK (INT64_MAX - 1)     // heap slot popped by the action being inserted
 
-// All lanes of a wavefront run in lockstep; this keeps the compiler from moving LDS or global
-// accesses across the point where one lane's write must be seen by the others.
+// All lanes of a wavefront run in lockstep and the LDS executes one wavefront's accesses in
+// order; this only keeps the compiler from moving LDS accesses across the point where one
+// lane's write must be seen by the others (no wait on outstanding global memory traffic).
 __device__ static inline void tg_wave_sync() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
   __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
 }
 
+// Wavefront-wide unsigned 64-bit minimum, broadcast to all lanes.  Data-parallel-primitive
+// moves inside the rows of 16 lanes (shift right by 1, 2, 4, 8: lane 15 of a row then holds the
+// row's minimum because min is idempotent), then row 0 -> 1 and 2 -> 3 (broadcast of lane 15),
+// then rows 0-1 -> 2-3 (broadcast of lane 31); lane 63 ends with the minimum of all 64.
 __device__ static inline uint64_t tg_wave_min_u64(uint64_t v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const uint64_t w = __shfl_xor((unsigned long long)v, o);
-    v = w < v ? w : v;
+  uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
+#define TG_DPP_MIN_STEP(CTRL, ROWMASK)                                                                        \
+  {                                                                                                           \
+    const uint32_t lo2 = (uint32_t)__builtin_amdgcn_update_dpp((int)lo, (int)lo, CTRL, ROWMASK, 0xf, false);  \
+    const uint32_t hi2 = (uint32_t)__builtin_amdgcn_update_dpp((int)hi, (int)hi, CTRL, ROWMASK, 0xf, false);  \
+    const uint64_t w = (uint64_t)hi2 << 32 | lo2, c = (uint64_t)hi << 32 | lo;                                \
+    if (w < c) { lo = lo2; hi = hi2; }                                                                        \
   }
-  return v;
+  TG_DPP_MIN_STEP(0x111, 0xf) TG_DPP_MIN_STEP(0x112, 0xf) TG_DPP_MIN_STEP(0x114, 0xf) TG_DPP_MIN_STEP(0x118, 0xf)
+  TG_DPP_MIN_STEP(0x142, 0xa) TG_DPP_MIN_STEP(0x143, 0xc)
+#undef TG_DPP_MIN_STEP
+  lo = (uint32_t)__builtin_amdgcn_readlane((int)lo, 63);
+  hi = (uint32_t)__builtin_amdgcn_readlane((int)hi, 63);
+  return (uint64_t)hi << 32 | lo;
 }
 
 __device__ static inline int tg_wave_sum_i32(int v) {
@@ -96,12 +109,17 @@ __device__ static inline void tg_place_pool(const TgPoolLds& S, const TgPlaceIo&
   bool pool_closed = false;
   for (int base = 0; base < Nt; base += TG_WAVE) {
     const int cnt = min(TG_WAVE, Nt - base);
-    int my_id = 0, my_pin = -1;
+    // lane l holds action base+l: its inputs now, its result after the loop (one global
+    // round trip per 64 actions instead of one per action)
+    int my_id = 0, my_pr = -1;
     uint32_t my_mask = 0, my_static = 0;
     if (lane < cnt) {
       my_id = acts[base + lane];
-      my_mask = io.act_kmask[my_id]; my_static = io.act_static[my_id]; my_pin = io.act_pin[my_id];
+      my_mask = io.act_kmask[my_id]; my_static = io.act_static[my_id];
+      const int pin = io.act_pin[my_id];
+      if (pin >= 0 && !my_static) my_pr = io.node_rank[pin];
     }
+    int res_rank = -1, res_slot = 0, res_reason = TG_SELECTED;
     tg_wave_sync();                                  // previous chunk's readers are done with S.dur
     for (int x = lane; x < cnt * io.K; x += TG_WAVE) {
       const int a = x / io.K, q = x - a * io.K;
@@ -109,59 +127,56 @@ __device__ static inline void tg_place_pool(const TgPoolLds& S, const TgPlaceIo&
     }
     tg_wave_sync();
     for (int l = 0; l < cnt; ++l) {
-      const int id = __builtin_amdgcn_readlane(my_id, l);
       const uint32_t mask = (uint32_t)__builtin_amdgcn_readlane((int)my_mask, l);
-      const int pin = __builtin_amdgcn_readlane(my_pin, l);
+      const int pr = __builtin_amdgcn_readlane(my_pr, l);
       const int stat = __builtin_amdgcn_readlane((int)my_static, l);
-      int reason = TG_SELECTED;
-      int pr = -1;
-      uint64_t best = ~0ull;
+      int reason = TG_SELECTED, rank = -1, slot = 0;
       if (stat) {
         reason = TG_DEFER_INFEASIBLE;
+      } else if (pool_closed || (pr >= 0 && S.closed[pr])) {
+        reason = TG_DEFER_PREFIX;
       } else {
-        if (pin >= 0) pr = io.node_rank[pin];
-        if (pool_closed || (pr >= 0 && S.closed[pr])) {
-          reason = TG_DEFER_PREFIX;
-        } else {
-          const int kmin = S.k[__builtin_ctz(mask)];
-          const int r_lo = pr >= 0 ? pr : lane, r_hi = pr >= 0 ? (lane == 0 ? pr + 1 : 0) : Mt;
-          for (int r = r_lo; r < r_hi; r += TG_WAVE) {
-            if (S.closed[r]) continue;
-            const int lim = gpu ? tg_chunk_largest((uint32_t)S.lim[r]) : S.lim[r];
-            if (kmin > lim) continue;
-            int qs = 0;                              // largest allowed option that still fits
+        const int kmin = S.k[__builtin_ctz(mask)];
+        uint64_t best = ~0ull;
+        const int r_lo = pr >= 0 ? pr : lane, r_hi = pr >= 0 ? (lane == 0 ? pr + 1 : 0) : Mt;
+        for (int r = r_lo; r < r_hi; r += TG_WAVE) {
+          if (S.closed[r]) continue;
+          const int lim = gpu ? tg_chunk_largest((uint32_t)S.lim[r]) : S.lim[r];
+          if (kmin > lim) continue;
+          int qs = 0;                                // largest allowed option that still fits
 #pragma unroll
-            for (int q = 0; q < TG_MAX_K; ++q)
-              if (q < io.Kt && (mask >> q & 1u) && S.k[q] <= lim) qs = q;
-            const int64_t e = io.cost ? io.cost[(size_t)(base + l) * io.cost_row_len + r * io.Kt + qs]
-                                      : S.back[r] + S.dur[l * io.K + qs];
-            const uint64_t key = (uint64_t)e << 12 | (uint32_t)r;   // ties: smaller node rank
-            best = key < best ? key : best;
-          }
-          best = tg_wave_min_u64(best);
-          if (best == ~0ull) {
-            reason = TG_DEFER_PREFIX;
-            if (pr >= 0) { if (lane == 0) S.closed[pr] = 1; } else pool_closed = true;
+          for (int q = 0; q < TG_MAX_K; ++q)
+            if (q < io.Kt && (mask >> q & 1u) && S.k[q] <= lim) qs = q;
+          const int64_t e = io.cost ? io.cost[(size_t)(base + l) * io.cost_row_len + r * io.Kt + qs]
+                                    : S.back[r] + S.dur[l * io.K + qs];
+          const uint64_t key = (uint64_t)e << 12 | (uint32_t)r;     // ties: smaller node rank
+          best = key < best ? key : best;
+        }
+        best = tg_wave_min_u64(best);
+        if (best == ~0ull) {
+          reason = TG_DEFER_PREFIX;
+          if (pr >= 0) { if (lane == 0) S.closed[pr] = 1; } else pool_closed = true;
+        } else {
+          rank = (int)(best & 0xfff);
+          slot = S.cnt[rank];
+          if (lane == 0) {
+            S.cnt[rank] = slot + 1;
+            S.lim[rank] = gpu ? (int32_t)tg_chunk_take((uint32_t)S.lim[rank], kmin) : S.lim[rank] - kmin;
           }
         }
       }
-      if (lane == 0) {
-        int node = -1, slot = 0;
-        if (reason == TG_SELECTED) {
-          const int r = (int)(best & 0xfff);
-          const int kmin = S.k[__builtin_ctz(mask)];
-          node = io.nodes[r];
-          slot = S.cnt[r]; S.cnt[r] = slot + 1;
-          S.lim[r] = gpu ? (int32_t)tg_chunk_take((uint32_t)S.lim[r], kmin) : S.lim[r] - kmin;
-        } else if (reason == TG_DEFER_PREFIX && pr >= 0) {
-          slot = S.dcnt[pr]; S.dcnt[pr] = slot + 1;
-        }
-        io.out_node[id] = node;
-        io.out_reason[id] = (uint8_t)reason;
-        io.slot[id] = slot;
-        if (reason != TG_SELECTED) { io.out_units[id] = 0; if (io.out_act) io.out_act[id] = -1; }
+      if (reason == TG_DEFER_PREFIX && pr >= 0) {
+        slot = S.dcnt[pr];
+        if (lane == 0) S.dcnt[pr] = slot + 1;
       }
+      if (lane == l) { res_rank = rank; res_slot = slot; res_reason = reason; }
       tg_wave_sync();
+    }
+    if (lane < cnt) {
+      io.out_node[my_id] = res_rank >= 0 ? io.nodes[res_rank] : -1;
+      io.out_reason[my_id] = (uint8_t)res_reason;
+      io.slot[my_id] = res_slot;
+      if (res_reason != TG_SELECTED) { io.out_units[my_id] = 0; if (io.out_act) io.out_act[my_id] = -1; }
     }
   }
   tg_wave_sync();
@@ -192,17 +207,23 @@ __device__ static inline void tg_pool_extents(const TgPoolLds& S, const int32_t*
 
 // ---------------------------------------------------------------------------- per node
 struct TgNodeLdsPlan {
-  int off_cdur, off_dp, off_choice, off_heap, off_rowbest, off_rowarg, off_sel, off_pos, off_k;
+  int off_cdur, off_dp, off_choice, off_heap, off_rowbest, off_rowarg, off_sel, off_k;
   int dp_width;     // entries per DP row
+  int sel_stride;   // candidates per row of the allocation table
+  int sel_rows;     // prefix lengths backtracked per batch (<= 64)
   int total;        // bytes per wavefront
 };
 
-__host__ static inline TgNodeLdsPlan tg_node_lds_plan(int max_free_cpu, int max_free_gpu, int max_states, int max_heap, int K) {
+// LDS layout of one wavefront for nodes with at most `m_cap` candidates (m never exceeds the
+// node's free units either).
+__host__ static inline TgNodeLdsPlan tg_node_lds_plan(int max_free_cpu, int max_free_gpu, int max_states, int max_heap, int K,
+                                                      int m_cap = 1 << 30, int sel_rows = TG_WAVE) {
   TgNodeLdsPlan p;
-  const int mmax = (max_free_cpu > max_free_gpu ? max_free_cpu : max_free_gpu) + 1;
+  const int m_cpu = max_free_cpu < m_cap ? max_free_cpu : m_cap, m_gpu = max_free_gpu < m_cap ? max_free_gpu : m_cap;
+  const int mmax = (m_cpu > m_gpu ? m_cpu : m_gpu) + 1;
   const int width = (max_free_cpu + 1 > max_states ? max_free_cpu + 1 : max_states);
-  size_t choice = (size_t)max_free_cpu * (max_free_cpu + 1);
-  if ((size_t)max_free_gpu * max_states * 2 > choice) choice = (size_t)max_free_gpu * max_states * 2;
+  size_t choice = (size_t)m_cpu * (max_free_cpu + 1);
+  if ((size_t)m_gpu * max_states * 2 > choice) choice = (size_t)m_gpu * max_states * 2;
   size_t off = 0;
   auto take = [&](size_t b) { const size_t r = off; off += (b + 15) & ~size_t(15); return (int)r; };
   p.off_cdur = take((size_t)mmax * K * 8);
@@ -211,8 +232,9 @@ __host__ static inline TgNodeLdsPlan tg_node_lds_plan(int max_free_cpu, int max_
   p.off_heap = take((size_t)(max_heap + 1) * 8);
   p.off_rowbest = take((size_t)(mmax + 1) * 8);
   p.off_rowarg = take((size_t)(mmax + 1) * 4);
-  p.off_sel = take((size_t)mmax);
-  p.off_pos = take((size_t)mmax * 2);
+  p.off_sel = take((size_t)mmax * sel_rows);    // allocations of sel_rows consecutive prefix lengths
+  p.sel_stride = mmax;
+  p.sel_rows = sel_rows;
   p.off_k = take(TG_MAX_K * 4);
   p.dp_width = width;
   p.total = (int)off;
@@ -225,7 +247,8 @@ struct TgNodeIn {
   uint32_t chunks;
   int m; const int32_t* clist;       // admitted actions of the node, FCFS
   int nd; const int32_t* dlist;      // waiting actions pinned to the node, FCFS
-  int n_busy; const int64_t* busy;   // release times of the units of running actions
+  int n_busy; const int64_t* busy;   // release times of the units of running actions (global memory), or
+  int busy_lds_off;                  // >= 0: the list sits at this byte offset of the wavefront's LDS block instead
   const uint8_t* act_model; const uint32_t* act_kmask; const int64_t* dur;
   int K, depth;
   int k_list[TG_MAX_K];
@@ -312,7 +335,7 @@ __device__ static inline int64_t tg_estimate(const TgNodeIn& in, const int64_t* 
 // One node: returns the final approximated objective (or -1 when the node holds no elastic
 // action and everything simply runs on its minimum units).
 __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgNodeLdsPlan& plan, const TgNodeIn& in,
-                                                  const TgNodeOut& out, int lane) {
+                                                  const TgNodeOut& out, int lane, int* used_units) {
   int64_t* s_cdur = reinterpret_cast<int64_t*>(smem + plan.off_cdur);
   int64_t* s_dp = reinterpret_cast<int64_t*>(smem + plan.off_dp);
   uint8_t* s_choice = smem + plan.off_choice;
@@ -320,24 +343,30 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
   int64_t* s_heap = reinterpret_cast<int64_t*>(smem + plan.off_heap);
   int64_t* s_rowbest = reinterpret_cast<int64_t*>(smem + plan.off_rowbest);
   int32_t* s_rowarg = reinterpret_cast<int32_t*>(smem + plan.off_rowarg);
-  uint8_t* s_sel = smem + plan.off_sel;
-  uint16_t* s_pos = reinterpret_cast<uint16_t*>(smem + plan.off_pos);
+  uint8_t* s_sel = smem + plan.off_sel;                           // [64][sel_stride] option of candidate x for L = top - l
   int32_t* s_k = reinterpret_cast<int32_t*>(smem + plan.off_k);
   const int m = in.m, K = in.K, U = in.free_units;
   const bool gpu = in.type == TG_TYPE_GPU;
 
   tg_wave_sync();
   if (lane < TG_MAX_K) s_k[lane] = in.k_list[lane];
+  uint64_t kword = 0;                                             // unit counts, one byte each
+#pragma unroll
+  for (int q = 0; q < TG_MAX_K; ++q) kword |= (uint64_t)(uint32_t)in.k_list[q] << (8 * q);
+  auto k_of = [&](int q) { return (int)(kword >> (8 * q) & 0xff); };
   int el = 0;
   for (int x = lane; x < m; x += TG_WAVE) el |= in.act_model[in.clist[x]] != TG_MODEL_NONE;
   tg_wave_sync();
   if (!__any(el)) {                                               // Alg. 1 l.5-6: nothing to scale
+    int used = 0;
     for (int x = lane; x < m; x += TG_WAVE) {
       const int id = in.clist[x];
       const int q0 = __builtin_ctz(in.act_kmask[id]);
       out.units[id] = s_k[q0];
+      used += s_k[q0];
       if (out.act) out.act[id] = (out.age ? out.age[id] : 0) + in.backlog + in.dur[(size_t)id * K + q0];
     }
+    *used_units = tg_wave_sum_i32(used);
     return -1;
   }
 
@@ -369,15 +398,18 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
     tg_wave_sync();
     for (int i = 1; i <= m; ++i) {
       uint64_t rb = ~0ull;
+      int64_t tq[TG_MAX_K];                                       // durations of candidate i, same for all lanes
+#pragma unroll
+      for (int q = 0; q < TG_MAX_K; ++q) tq[q] = q < K ? s_cdur[(i - 1) * K + q] : TG_INF;
       for (int j = lane; j <= n; j += TG_WAVE) {
         int64_t bestv = TG_INF;
         int bq = 0xff;
-        for (int q = 0; q < K; ++q) {                             // ascending k, strict <: fewer units win ties
-          const int64_t t = s_cdur[(i - 1) * K + q];
-          const int kq = s_k[q];
-          if (t == TG_INF || j < kq) continue;
+#pragma unroll
+        for (int q = 0; q < TG_MAX_K; ++q) {                      // ascending k, strict <: fewer units win ties
+          const int kq = k_of(q);
+          if (tq[q] == TG_INF || j < kq) continue;
           const int64_t pv = prev[j - kq];
-          if (pv != TG_INF && pv + t < bestv) { bestv = pv + t; bq = q; }
+          if (pv != TG_INF && pv + tq[q] < bestv) { bestv = pv + tq[q]; bq = q; }
         }
         cur[j] = bestv;
         s_choice[(size_t)(i - 1) * stride + j] = (uint8_t)bq;
@@ -443,28 +475,46 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
 
   // ---- Alg. 2: objective of keeping the first L candidates ---------------------------------
   const int H = U + in.n_busy;
-  auto backtrack = [&](int L) {                                    // s_sel[x] = option of candidate x
-    int st = s_rowarg[L];
-    for (int i = L; i >= 1; --i) {
-      int q;
-      if (!gpu) { q = s_choice[(size_t)(i - 1) * stride + st]; st -= s_k[q]; }
-      else { const int c = s_choice16[(size_t)(i - 1) * stride + st]; q = c & 7; st = c >> 3; }
-      if (lane == 0) s_sel[i - 1] = (uint8_t)q;
+  // Allocations of up to 64 consecutive prefix lengths at once: lane l walks the choice table back from
+  // the best end state of C[:top-l].  The eviction loop then only looks allocations up.
+  int top = 0;
+  auto backtrack_batch = [&](int new_top) {
+    top = new_top;
+    const int Lm = top - lane;
+    if (lane < plan.sel_rows && Lm >= 1) {
+      int st = s_rowarg[Lm];
+      uint8_t* row = s_sel + (size_t)lane * plan.sel_stride;
+      for (int i = Lm; i >= 1; --i) {
+        int q;
+        if (!gpu) { q = s_choice[(size_t)(i - 1) * stride + st]; st -= k_of(q); }
+        else { const int c = s_choice16[(size_t)(i - 1) * stride + st]; q = c & 7; st = c >> 3; }
+        row[i - 1] = (uint8_t)q;
+      }
     }
     tg_wave_sync();
   };
   auto objective = [&](int L) -> int64_t {
-    backtrack(L);
-    int pos = 0;
-    for (int x = 0; x < L; ++x) { if (lane == 0) s_pos[x] = (uint16_t)pos; pos += s_k[s_sel[x]]; }
-    tg_wave_sync();
-    for (int x = lane; x < L; x += TG_WAVE) {                      // k_i entries at backlog + dur_i(k_i)
-      const int q = s_sel[x], kq = s_k[q];
-      const int64_t fin = in.backlog + s_cdur[x * K + q];
-      for (int c = 0; c < kq; ++c) s_heap[s_pos[x] + c] = fin;
+    if (L > top || L <= top - plan.sel_rows) backtrack_batch(L);
+    const uint8_t* sel = s_sel + (size_t)(top - L) * plan.sel_stride;
+    int pos = 0;                                                   // units handed out so far
+    for (int base = 0; base < L; base += TG_WAVE) {
+      const int x = base + lane;
+      const int q = x < L ? sel[x] : 0, kq = x < L ? k_of(q) : 0;
+      int inc = kq;                                                // inclusive scan of the unit counts
+      for (int o = 1; o < TG_WAVE; o <<= 1) { const int u = __shfl_up(inc, o); if (lane >= o) inc += u; }
+      if (x < L) {                                                 // k_i entries at backlog + dur_i(k_i)
+        const int64_t fin = in.backlog + s_cdur[x * K + q];
+        for (int c = 0; c < kq; ++c) s_heap[pos + inc - kq + c] = fin;
+      }
+      pos += __shfl(inc, TG_WAVE - 1);
     }
     for (int c = pos + lane; c < U; c += TG_WAVE) s_heap[c] = in.backlog;   // units left idle
-    for (int c = lane; c < in.n_busy; c += TG_WAVE) s_heap[U + c] = in.busy[c];
+    if (in.busy_lds_off >= 0) {
+      const int64_t* bl = reinterpret_cast<const int64_t*>(smem + in.busy_lds_off);
+      for (int c = lane; c < in.n_busy; c += TG_WAVE) s_heap[U + c] = bl[c];
+    } else {
+      for (int c = lane; c < in.n_busy; c += TG_WAVE) s_heap[U + c] = in.busy[c];
+    }
     tg_wave_sync();
     const int64_t approx = tg_estimate(in, s_heap, s_k, H, L, lane);
     tg_wave_sync();
@@ -480,18 +530,22 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
     obj = nobj;
     --L;
   }
-  backtrack(L);
+  if (L > top || L <= top - plan.sel_rows) backtrack_batch(L);
+  const uint8_t* sel = s_sel + (size_t)(top - L) * plan.sel_stride;
+  int used = 0;
   for (int x = lane; x < m; x += TG_WAVE) {
     const int id = in.clist[x];
     if (x < L) {
-      const int q = s_sel[x];
+      const int q = sel[x];
       out.units[id] = s_k[q];
+      used += s_k[q];
       if (out.act) out.act[id] = (out.age ? out.age[id] : 0) + in.backlog + s_cdur[x * K + q];
     } else {
       out.node[id] = -1; out.units[id] = 0; out.reason[id] = TG_DEFER_EVICTED;
       if (out.act) out.act[id] = -1;
     }
   }
+  *used_units = tg_wave_sum_i32(used);
   tg_wave_sync();
   return obj;
 }
