@@ -30,6 +30,7 @@ struct AssignWs {
 // Nodes are processed in classes of candidate count so that the LDS a wavefront needs (the
 // choice table grows with m) does not cap the occupancy of the many small nodes.
 constexpr int kClasses = 3;
+constexpr int kClassWaves[kClasses] = {1, 1, 1};   // wavefronts that share one node of the class
 constexpr int kClassCap0 = 16, kClassCap1 = 64;
 __host__ __device__ constexpr int class_cap(int c) { return c == 0 ? kClassCap0 : c == 1 ? kClassCap1 : 1 << 30; }
 
@@ -117,29 +118,49 @@ __global__ __launch_bounds__(256) void tg_lists_kernel(TgDev P, AssignWs W, tg_a
       const size_t n = (size_t)b * P.M + P.act_pin[g];
       W.dorder[(size_t)b * P.N + W.dl_off[n] + W.slot[g]] = i;
     }
-  } else if (g < nA + nN) {                    // one thread per node: class bins, defaults of idle nodes
-    const size_t gn = g - nA;
+  }
+  // one thread per node: class bins (one atomic per wavefront and class), defaults of idle nodes
+  const bool is_node = g >= nA && g < nA + nN;
+  const size_t gn = g - nA;
+  int cls = -1;
+  if (is_node) {
     const int m = W.nl_cnt[gn];
     if (O.node_obj) O.node_obj[gn] = -1;
-    if (m == 0) { if (O.node_used) O.node_used[gn] = 0; return; }
-    const int c = m <= kClassCap0 ? 0 : m <= kClassCap1 ? 1 : 2;
-    const int pos = atomicAdd(&W.class_ctl[2 * c], 1);       // order inside a class does not matter
-    W.class_list[(size_t)c * nN + pos] = (int32_t)gn;
+    if (m == 0) { if (O.node_used) O.node_used[gn] = 0; }
+    else cls = m <= kClassCap0 ? 0 : m <= kClassCap1 ? 1 : 2;
+  }
+  const int lane = threadIdx.x & 63;
+  for (int c = 0; c < kClasses; ++c) {
+    const uint64_t bal = __ballot(cls == c);
+    if (bal == 0) continue;
+    const int leader = __ffsll((unsigned long long)bal) - 1;
+    int base = 0;
+    if (lane == leader) base = atomicAdd(&W.class_ctl[2 * c], __popcll(bal));   // order inside a class does not matter
+    base = __shfl(base, leader);
+    if (cls == c) W.class_list[(size_t)c * nN + base + __popcll(bal & ((1ull << lane) - 1ull))] = (int32_t)gn;
   }
 }
 
 // ------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(TG_WAVE) void tg_node_kernel(TgDev P, const int64_t* __restrict__ dur, AssignWs W,
-                                                          tg_assign_out O, TgNodeLdsPlan plan, int cls) {
+template <int NW>
+__global__ __launch_bounds__(TG_WAVE * NW) void tg_node_kernel(TgDev P, const int64_t* __restrict__ dur, AssignWs W,
+                                                               tg_assign_out O, TgNodeLdsPlan plan, int cls) {
   extern __shared__ __align__(16) unsigned char smem[];
-  const int lane = threadIdx.x;
+  __shared__ int s_idx;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const size_t nN = (size_t)P.B * P.M;
   const int n_nodes = W.class_ctl[2 * cls];
   const int32_t* list = W.class_list + (size_t)cls * nN;
   for (;;) {
     int idx = 0;
-    if (lane == 0) idx = atomicAdd(&W.class_ctl[2 * cls + 1], 1);     // next unprocessed node of the class
-    idx = __builtin_amdgcn_readfirstlane(idx);
+    if (NW == 1) {
+      if (lane == 0) idx = atomicAdd(&W.class_ctl[2 * cls + 1], 1);   // next unprocessed node of the class
+      idx = __builtin_amdgcn_readfirstlane(idx);
+    } else {
+      if (threadIdx.x == 0) s_idx = atomicAdd(&W.class_ctl[2 * cls + 1], 1);
+      __syncthreads();
+      idx = s_idx;                                                    // rewritten only after the team's next barriers
+    }
     if (idx >= n_nodes) break;
     const int gn = list[idx];
     const int b = gn / P.M;
@@ -154,13 +175,13 @@ __global__ __launch_bounds__(TG_WAVE) void tg_node_kernel(TgDev P, const int64_t
     in.busy_lds_off = -1;
     in.act_model = P.act_model + abase; in.act_kmask = P.act_kmask + abase; in.dur = dur + abase * P.K;
     in.K = P.K; in.depth = P.depth;
-    for (int q = 0; q < TG_MAX_K; ++q) in.k_list[q] = P.k_list[q];
+    in.kword = tg_pack_k(P.k_list);
     TgNodeOut out;
     out.node = O.node + abase; out.units = O.units + abase; out.act = O.act_us + abase; out.reason = O.defer_reason + abase;
     out.age = P.act_age + abase;
     int used = 0;
-    const int64_t obj = tg_node_schedule(smem, plan, in, out, lane, &used);
-    if (lane == 0) {
+    const int64_t obj = tg_node_schedule<NW>(smem, plan, in, out, lane, wave, &used);
+    if (threadIdx.x == 0) {
       if (O.node_obj) O.node_obj[gn] = obj;
       if (O.node_used) O.node_used[gn] = used;
     }
@@ -253,11 +274,14 @@ extern "C" int tg_assign(const tg_problem* p, const int64_t* d_cost, const tg_as
   TgNodeLdsPlan plans[kClasses];
   int max_lds = 0;
   for (int c = 0; c < kClasses; ++c) {
-    plans[c] = tg_node_lds_plan(p->max_free_cpu, p->max_free_gpu, p->max_chunk_states, p->max_heap, P.K, class_cap(c));
+    plans[c] = tg_node_lds_plan(p->max_free_cpu, p->max_free_gpu, p->max_chunk_states, p->max_heap, P.K, class_cap(c), TG_WAVE, kClassWaves[c]);
     max_lds = plans[c].total > max_lds ? plans[c].total : max_lds;
   }
-  if (max_lds > 64 * 1024)
-    TG_HIP_CHECK(hipFuncSetAttribute((const void*)tg_node_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds));
+  if (max_lds > 64 * 1024) {
+    TG_HIP_CHECK(hipFuncSetAttribute((const void*)tg_node_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds));
+    TG_HIP_CHECK(hipFuncSetAttribute((const void*)tg_node_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds));
+    TG_HIP_CHECK(hipFuncSetAttribute((const void*)tg_node_kernel<8>, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds));
+  }
 
   const size_t nN = (size_t)P.B * P.M;
   hipLaunchKernelGGL(tg_dur_kernel, dim3((unsigned)((nA * P.K + 255) / 256)), dim3(256), 0, s, P, W.dur, W.class_ctl);
@@ -266,9 +290,12 @@ extern "C" int tg_assign(const tg_problem* p, const int64_t* d_cost, const tg_as
   hipLaunchKernelGGL(tg_lists_kernel, dim3((unsigned)((nA + nN + 255) / 256)), dim3(256), 0, s, P, W, *out);
   // persistent wavefronts pull nodes of their class; enough of them to fill the LDS of every CU
   for (int c = 0; c < kClasses; ++c) {
-    const int per_cu = std::max(1, std::min(32, (160 * 1024) / std::max(plans[c].total, 1)));
+    const int nw = kClassWaves[c];
+    const int per_cu = std::max(1, std::min(32 / nw, (160 * 1024) / std::max(plans[c].total, 1)));
     const unsigned grid = (unsigned)std::min<size_t>(nN, (size_t)256 * per_cu);
-    hipLaunchKernelGGL(tg_node_kernel, dim3(grid), dim3(TG_WAVE), plans[c].total, s, P, W.dur, W, *out, plans[c], c);
+    if (nw == 1) hipLaunchKernelGGL(tg_node_kernel<1>, dim3(grid), dim3(TG_WAVE), plans[c].total, s, P, W.dur, W, *out, plans[c], c);
+    else if (nw == 2) hipLaunchKernelGGL(tg_node_kernel<2>, dim3(grid), dim3(TG_WAVE * 2), plans[c].total, s, P, W.dur, W, *out, plans[c], c);
+    else hipLaunchKernelGGL(tg_node_kernel<8>, dim3(grid), dim3(TG_WAVE * 8), plans[c].total, s, P, W.dur, W, *out, plans[c], c);
   }
   hipLaunchKernelGGL(tg_summary_kernel, dim3(P.B), dim3(256), 0, s, P, *out);
   return hipGetLastError() == hipSuccess ? TG_OK : TG_E_HIP;

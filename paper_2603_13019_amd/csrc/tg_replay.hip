@@ -323,11 +323,11 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
       in.m = m; in.clist = order + nl_off[j]; in.nd = dl_cnt[j]; in.dlist = dorder + dl_off[j];
       in.n_busy = nb; in.busy = nullptr; in.busy_lds_off = plan.total;
       in.act_model = T.act_model + abase; in.act_kmask = T.act_kmask + abase; in.dur = dur; in.K = K; in.depth = T.depth;
-      for (int q = 0; q < TG_MAX_K; ++q) in.k_list[q] = T.k_list[q];
+      in.kword = tg_pack_k(T.k_list);
       TgNodeOut out;
       out.node = o_node; out.units = o_units; out.act = nullptr; out.reason = reason; out.age = nullptr;
       int used_units;
-      tg_node_schedule(node_mem, plan, in, out, lane, &used_units);
+      tg_node_schedule<1>(node_mem, plan, in, out, lane, 0, &used_units);
     }
     __threadfence_block();
     __syncthreads();

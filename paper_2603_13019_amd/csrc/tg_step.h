@@ -12,6 +12,8 @@
 #ifndef TG_STEP_H_
 #define TG_STEP_H_
 
+#include <type_traits>
+
 #include "tg_internal.h"
 
 #define TG_PAD INT64_MAX            // heap slot beyond the heap size
@@ -45,6 +47,19 @@ __device__ static inline uint64_t tg_wave_min_u64(uint64_t v) {
   lo = (uint32_t)__builtin_amdgcn_readlane((int)lo, 63);
   hi = (uint32_t)__builtin_amdgcn_readlane((int)hi, 63);
   return (uint64_t)hi << 32 | lo;
+}
+
+// 32-bit variant: the minimum rides on the data-parallel-primitive move itself.
+__device__ static inline uint32_t tg_wave_min_u32(uint32_t v) {
+#define TG_DPP_MIN32_STEP(CTRL, ROWMASK)                                                                  \
+  {                                                                                                       \
+    const uint32_t w = (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, ROWMASK, 0xf, false);  \
+    v = w < v ? w : v;                                                                                    \
+  }
+  TG_DPP_MIN32_STEP(0x111, 0xf) TG_DPP_MIN32_STEP(0x112, 0xf) TG_DPP_MIN32_STEP(0x114, 0xf) TG_DPP_MIN32_STEP(0x118, 0xf)
+  TG_DPP_MIN32_STEP(0x142, 0xa) TG_DPP_MIN32_STEP(0x143, 0xc)
+#undef TG_DPP_MIN32_STEP
+  return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
 
 __device__ static inline int tg_wave_sum_i32(int v) {
@@ -211,13 +226,16 @@ struct TgNodeLdsPlan {
   int dp_width;     // entries per DP row
   int sel_stride;   // candidates per row of the allocation table
   int sel_rows;     // prefix lengths backtracked per batch (<= 64)
+  int off_F;        // objectives of one round of evaluations + flags
+  int off_q0;       // minimum-unit option of every candidate
+  int heap_slots;   // heap entries per wavefront of the team
   int total;        // bytes per wavefront
 };
 
 // LDS layout of one wavefront for nodes with at most `m_cap` candidates (m never exceeds the
 // node's free units either).
 __host__ static inline TgNodeLdsPlan tg_node_lds_plan(int max_free_cpu, int max_free_gpu, int max_states, int max_heap, int K,
-                                                      int m_cap = 1 << 30, int sel_rows = TG_WAVE) {
+                                                      int m_cap = 1 << 30, int sel_rows = TG_WAVE, int n_waves = 1) {
   TgNodeLdsPlan p;
   const int m_cpu = max_free_cpu < m_cap ? max_free_cpu : m_cap, m_gpu = max_free_gpu < m_cap ? max_free_gpu : m_cap;
   const int mmax = (m_cpu > m_gpu ? m_cpu : m_gpu) + 1;
@@ -229,7 +247,10 @@ __host__ static inline TgNodeLdsPlan tg_node_lds_plan(int max_free_cpu, int max_
   p.off_cdur = take((size_t)mmax * K * 8);
   p.off_dp = take((size_t)width * 2 * 8);
   p.off_choice = take(choice + 16);
-  p.off_heap = take((size_t)(max_heap + 1) * 8);
+  p.heap_slots = (max_heap + 2) & ~1;
+  p.off_heap = take((size_t)p.heap_slots * 8 * n_waves);
+  p.off_F = take((size_t)(n_waves + 4) * 8);
+  p.off_q0 = take((size_t)mmax);
   p.off_rowbest = take((size_t)(mmax + 1) * 8);
   p.off_rowarg = take((size_t)(mmax + 1) * 4);
   p.off_sel = take((size_t)mmax * sel_rows);    // allocations of sel_rows consecutive prefix lengths
@@ -251,8 +272,14 @@ struct TgNodeIn {
   int busy_lds_off;                  // >= 0: the list sits at this byte offset of the wavefront's LDS block instead
   const uint8_t* act_model; const uint32_t* act_kmask; const int64_t* dur;
   int K, depth;
-  int k_list[TG_MAX_K];
+  uint64_t kword;                    // the unit counts k_list[0..8), one byte each
 };
+
+__host__ __device__ static inline uint64_t tg_pack_k(const int* k_list) {
+  uint64_t w = 0;
+  for (int q = 0; q < TG_MAX_K; ++q) w |= (uint64_t)(uint32_t)k_list[q] << (8 * q);
+  return w;
+}
 
 struct TgNodeOut {
   int32_t* node; int32_t* units; int64_t* act; uint8_t* reason;
@@ -262,31 +289,43 @@ struct TgNodeOut {
 // Alg. 2 estimate(): insert the waiting actions one after the other into the completion heap
 // (one entry per unit, `H` entries staged in s_heap).  The heap lives in registers, four slots
 // per lane; a pop is a wavefront-wide minimum.  All but the first action use their minimum
-// units; the first tries its d-th smallest option for d = 1..depth.
-__device__ static inline int64_t tg_estimate(const TgNodeIn& in, const int64_t* s_heap, const int32_t* s_k, int H,
-                                             int L, int lane) {
+// units; the first tries its d-th smallest option for d = 1..depth.  The evicted tail C[L:] is
+// read from LDS (s_cdur, s_q0); only actions pinned to the node that never got in come from
+// global memory.  N32: every time of this node fits in 32 bits above `lo` (checked by the
+// caller), so the heap holds 32-bit offsets and a pop costs a dozen instructions.
+template <bool N32>
+__device__ static inline int64_t tg_estimate(const TgNodeIn& in, const int64_t* s_heap, const int64_t* s_cdur,
+                                             const uint8_t* s_q0, const int32_t* s_k, int H, int L, int lane, int64_t lo) {
+  typedef typename std::conditional<N32, uint32_t, uint64_t>::type V;
+  const V kPad = (V)~(V)0, kMark = (V)(kPad - 1);
   const int n_tail = in.m - L, n_ac = n_tail + in.nd;
   if (n_ac == 0) return 0;
   int64_t best = TG_INF;
   for (int d = 1; d <= in.depth; ++d) {
-    int64_t hv[4];
+    V hv[4];
 #pragma unroll
-    for (int s = 0; s < 4; ++s) { const int idx = lane + TG_WAVE * s; hv[s] = idx < H ? s_heap[idx] : TG_PAD; }
+    for (int s = 0; s < 4; ++s) { const int idx = lane + TG_WAVE * s; hv[s] = idx < H ? (V)(uint64_t)(s_heap[idx] - (N32 ? lo : 0)) : kPad; }
     int64_t obj = 0;
     bool first = true, invalid = false;
     for (int base = 0; base < n_ac && !invalid; base += TG_WAVE) {
       const int cnt = min(TG_WAVE, n_ac - base);
-      int my_id = 0, my_u = 0, my_ok = 0;
+      int my_id = -1, my_u = 0, my_ok = 0, my_x = 0;
       uint32_t my_mask = 0;
       int64_t my_d = 0;
       if (lane < cnt) {
         const int x = base + lane;
-        my_id = x < n_tail ? in.clist[L + x] : in.dlist[x - n_tail];
-        my_mask = in.act_kmask[my_id];
-        const int q0 = __builtin_ctz(my_mask | 0x80000000u);
-        my_u = s_k[q0 & (TG_MAX_K - 1)];
-        my_ok = my_mask != 0 && q0 < TG_MAX_K && my_u <= H;       // can never run on this node: left out
-        if (my_ok) my_d = in.dur[(size_t)my_id * in.K + q0];
+        if (x < n_tail) {                                         // evicted candidate: everything is in LDS
+          my_x = L + x;
+          const int q0 = s_q0[my_x];
+          my_u = s_k[q0]; my_ok = 1; my_d = s_cdur[my_x * in.K + q0];
+        } else {
+          my_id = in.dlist[x - n_tail];
+          my_mask = in.act_kmask[my_id];
+          const int q0 = __builtin_ctz(my_mask | 0x80000000u);
+          my_u = s_k[q0 & (TG_MAX_K - 1)];
+          my_ok = my_mask != 0 && q0 < TG_MAX_K && my_u <= H;     // can never run on this node: left out
+          if (my_ok) my_d = in.dur[(size_t)my_id * in.K + q0];
+        }
       }
       for (int l = 0; l < cnt; ++l) {
         if (!__builtin_amdgcn_readlane(my_ok, l)) continue;
@@ -295,35 +334,39 @@ __device__ static inline int64_t tg_estimate(const TgNodeIn& in, const int64_t* 
         if (first) {
           first = false;
           if (d > 1) {                                            // d-th smallest usable option
-            const uint32_t mask = (uint32_t)__builtin_amdgcn_readlane((int)my_mask, l);
             const int id = __builtin_amdgcn_readlane(my_id, l);
+            const int xx = __builtin_amdgcn_readlane(my_x, l);
+            const uint32_t mask = (uint32_t)__builtin_amdgcn_readlane((int)my_mask, l);
             int seen = 0, qd = -1;
-            for (int q = 0; q < in.K; ++q)
-              if ((mask >> q & 1u) && s_k[q] <= H && ++seen == d) { qd = q; break; }
+            for (int q = 0; q < in.K; ++q) {
+              const bool allowed = id < 0 ? s_cdur[xx * in.K + q] != TG_INF : (mask >> q & 1u) != 0;
+              if (allowed && s_k[q] <= H && ++seen == d) { qd = q; break; }
+            }
             if (qd < 0) { invalid = true; break; }
             u = s_k[qd];
-            dd = in.dur[(size_t)id * in.K + qd];
+            dd = id < 0 ? s_cdur[xx * in.K + qd] : in.dur[(size_t)id * in.K + qd];
           }
         }
-        int64_t start = 0;
+        V start = 0;
         for (int c = 0; c < u; ++c) {                             // pop the u earliest units
-          int64_t lm = hv[0];
+          V lm = hv[0];
           int ls = 0;
 #pragma unroll
           for (int s = 1; s < 4; ++s) if (hv[s] < lm) { lm = hv[s]; ls = s; }
-          const int64_t wm = (int64_t)tg_wave_min_u64((uint64_t)lm);
+          V wm;
+          if (N32) wm = (V)tg_wave_min_u32((uint32_t)lm); else wm = (V)tg_wave_min_u64((uint64_t)lm);
           const uint64_t bal = __ballot(lm == wm);
           const int owner = __ffsll((unsigned long long)bal) - 1;
           if (lane == owner) {
 #pragma unroll
-            for (int s = 0; s < 4; ++s) if (s == ls) hv[s] = TG_MARK;
+            for (int s = 0; s < 4; ++s) if (s == ls) hv[s] = kMark;
           }
           start = wm;
         }
-        const int64_t fin = start + dd;                           // starts when its last unit frees
+        const V fin = (V)(start + (V)(uint64_t)dd);               // starts when its last unit frees
 #pragma unroll
-        for (int s = 0; s < 4; ++s) if (hv[s] == TG_MARK) hv[s] = fin;
-        obj += fin;
+        for (int s = 0; s < 4; ++s) if (hv[s] == kMark) hv[s] = fin;
+        obj += (N32 ? lo : 0) + (int64_t)(uint64_t)fin;
       }
     }
     if (invalid) break;
@@ -332,156 +375,237 @@ __device__ static inline int64_t tg_estimate(const TgNodeIn& in, const int64_t* 
   return best;
 }
 
-// One node: returns the final approximated objective (or -1 when the node holds no elastic
-// action and everything simply runs on its minimum units).
+// Alg. 3 with the basic operator (state = units used), all prefixes at once: row i of the table
+// holds the best totals of C[:i]; per row the choice of every cell, the best total over
+// used <= n and its smallest argument are kept.  V = uint32_t when every total of the node
+// fits in 32 bits (the caller checks the sum of the longest durations), else int64_t.
+template <typename V>
+__device__ static inline void tg_dp_units(V* prev, V* cur, const int64_t* s_cdur, uint8_t* s_choice, int64_t* s_rowbest,
+                                          int32_t* s_rowarg, int m, int n, int K, uint64_t kword, int lane) {
+  const V kInf = std::is_same<V, uint32_t>::value ? (V)0xffffffffu : (V)TG_INF;
+  const int stride = n + 1;
+  for (int j = lane; j <= n; j += TG_WAVE) prev[j] = j == 0 ? (V)0 : kInf;
+  if (lane == 0) { s_rowbest[0] = 0; s_rowarg[0] = 0; }
+  tg_wave_sync();
+  for (int i = 1; i <= m; ++i) {
+    V tq[TG_MAX_K];                                               // durations of candidate i, same for all lanes
+#pragma unroll
+    for (int q = 0; q < TG_MAX_K; ++q) {
+      const int64_t t = q < K ? s_cdur[(i - 1) * K + q] : TG_INF;
+      tq[q] = t == TG_INF ? kInf : (V)t;
+    }
+    if (lane == 0) { cur[0] = kInf; s_choice[(size_t)(i - 1) * stride] = 0xff; }   // every candidate takes a unit
+    V bv = kInf;                                                  // this lane's best cell, smallest j on ties
+    uint32_t bj = 0xffffffffu;
+    for (int j = lane + 1; j <= n; j += TG_WAVE) {
+      V bestv = kInf;
+      int bq = 0xff;
+#pragma unroll
+      for (int q = 0; q < TG_MAX_K; ++q) {                        // ascending k, strict <: fewer units win ties
+        const int kq = (int)(kword >> (8 * q) & 0xff);
+        if (tq[q] == kInf || j < kq) continue;
+        const V pv = prev[j - kq];
+        if (pv != kInf && (V)(pv + tq[q]) < bestv) { bestv = (V)(pv + tq[q]); bq = q; }
+      }
+      cur[j] = bestv;
+      s_choice[(size_t)(i - 1) * stride + j] = (uint8_t)bq;
+      if (bestv < bv) { bv = bestv; bj = (uint32_t)j; }
+    }
+    // best over used <= n, fewest units on ties
+    if (std::is_same<V, uint32_t>::value) {
+      const uint32_t vmin = tg_wave_min_u32((uint32_t)bv);
+      const uint32_t jmin = tg_wave_min_u32((uint32_t)bv == vmin ? bj : 0xffffffffu);
+      if (lane == 0) { s_rowbest[i] = (int64_t)vmin; s_rowarg[i] = (int)(jmin & 511); }
+    } else {
+      const uint64_t key = bv == kInf ? ~0ull : ((uint64_t)bv << 9 | (bj & 511));
+      const uint64_t rb = tg_wave_min_u64(key);
+      if (lane == 0) { s_rowbest[i] = (int64_t)(rb >> 9); s_rowarg[i] = (int)(rb & 511); }
+    }
+    V* tmp = prev; prev = cur; cur = tmp;
+    tg_wave_sync();
+  }
+}
+
+// One node, scheduled by a team of NW wavefronts (NW = 1: a single wavefront, no workgroup
+// barrier anywhere).  Wavefront 0 fills the DPArrange table for all prefixes; the objective of
+// NW consecutive prefix lengths is then evaluated in parallel, one per wavefront, and the
+// greedy rule of Alg. 1 (stop at the first length whose objective does not drop) is applied to
+// the values in order, so the result is the sequential algorithm's.  Returns the final
+// approximated objective (or -1 when the node holds no elastic action and everything simply
+// runs on its minimum units).  `smem` is the team's LDS block laid out by `plan`.
+template <int NW>
 __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgNodeLdsPlan& plan, const TgNodeIn& in,
-                                                  const TgNodeOut& out, int lane, int* used_units) {
+                                                  const TgNodeOut& out, int lane, int wave, int* used_units) {
   int64_t* s_cdur = reinterpret_cast<int64_t*>(smem + plan.off_cdur);
   int64_t* s_dp = reinterpret_cast<int64_t*>(smem + plan.off_dp);
   uint8_t* s_choice = smem + plan.off_choice;
   uint16_t* s_choice16 = reinterpret_cast<uint16_t*>(smem + plan.off_choice);
-  int64_t* s_heap = reinterpret_cast<int64_t*>(smem + plan.off_heap);
+  int64_t* s_heap = reinterpret_cast<int64_t*>(smem + plan.off_heap) + (size_t)wave * plan.heap_slots;   // per wavefront
   int64_t* s_rowbest = reinterpret_cast<int64_t*>(smem + plan.off_rowbest);
   int32_t* s_rowarg = reinterpret_cast<int32_t*>(smem + plan.off_rowarg);
-  uint8_t* s_sel = smem + plan.off_sel;                           // [64][sel_stride] option of candidate x for L = top - l
+  uint8_t* s_sel = smem + plan.off_sel;                           // [sel_rows][sel_stride] option of candidate x for L = top - l
   int32_t* s_k = reinterpret_cast<int32_t*>(smem + plan.off_k);
+  int64_t* s_F = reinterpret_cast<int64_t*>(smem + plan.off_F);   // [NW] objectives of one round, [NW] elastic?, [NW+1] time origin, [NW+2] 32-bit times? [NW+3] 32-bit DP?
+  uint8_t* s_q0 = smem + plan.off_q0;                             // minimum-unit option of candidate x
   const int m = in.m, K = in.K, U = in.free_units;
   const bool gpu = in.type == TG_TYPE_GPU;
+  auto team_sync = [&]() { if (NW > 1) __syncthreads(); else tg_wave_sync(); };
 
-  tg_wave_sync();
-  if (lane < TG_MAX_K) s_k[lane] = in.k_list[lane];
-  uint64_t kword = 0;                                             // unit counts, one byte each
-#pragma unroll
-  for (int q = 0; q < TG_MAX_K; ++q) kword |= (uint64_t)(uint32_t)in.k_list[q] << (8 * q);
+  const uint64_t kword = in.kword;                                // unit counts, one byte each
   auto k_of = [&](int q) { return (int)(kword >> (8 * q) & 0xff); };
-  int el = 0;
-  for (int x = lane; x < m; x += TG_WAVE) el |= in.act_model[in.clist[x]] != TG_MODEL_NONE;
-  tg_wave_sync();
-  if (!__any(el)) {                                               // Alg. 1 l.5-6: nothing to scale
+
+  team_sync();
+  if (wave == 0) {
+    if (lane < TG_MAX_K) s_k[lane] = k_of(lane);
+    int el = 0;
+    for (int x = lane; x < m; x += TG_WAVE) el |= in.act_model[in.clist[x]] != TG_MODEL_NONE;
+    const int any_el = __any(el);
+    if (lane == 0) s_F[NW] = any_el ? 1 : 0;
+  }
+  team_sync();
+  if (s_F[NW] == 0) {                                             // Alg. 1 l.5-6: nothing to scale
     int used = 0;
-    for (int x = lane; x < m; x += TG_WAVE) {
-      const int id = in.clist[x];
-      const int q0 = __builtin_ctz(in.act_kmask[id]);
-      out.units[id] = s_k[q0];
-      used += s_k[q0];
-      if (out.act) out.act[id] = (out.age ? out.age[id] : 0) + in.backlog + in.dur[(size_t)id * K + q0];
+    if (wave == 0) {
+      for (int x = lane; x < m; x += TG_WAVE) {
+        const int id = in.clist[x];
+        const int q0 = __builtin_ctz(in.act_kmask[id]);
+        out.units[id] = k_of(q0);
+        used += k_of(q0);
+        if (out.act) out.act[id] = (out.age ? out.age[id] : 0) + in.backlog + in.dur[(size_t)id * K + q0];
+      }
+      used = tg_wave_sum_i32(used);
     }
-    *used_units = tg_wave_sum_i32(used);
+    *used_units = used;
     return -1;
   }
 
-  // durations of the node's candidates, options above the node's capacity removed
-  for (int x = lane; x < m * K; x += TG_WAVE) {
-    const int a = x / K, q = x - a * K;
-    int64_t d = in.dur[(size_t)in.clist[a] * K + q];
-    if (s_k[q] > in.cap) d = TG_INF;
-    s_cdur[x] = d;
-  }
-  tg_wave_sync();
+  int stride = 0;                                                 // entries per choice row
+  if (wave == 0) {
+    // durations of the node's candidates, options above the node's capacity removed
+    for (int x = lane; x < m * K; x += TG_WAVE) {
+      const int a = x / K, q = x - a * K;
+      int64_t d = in.dur[(size_t)in.clist[a] * K + q];
+      if (k_of(q) > in.cap) d = TG_INF;
+      s_cdur[x] = d;
+    }
+    tg_wave_sync();
+    // minimum-unit option of every candidate, and the range all times of this node's estimates
+    // stay in: above `lo`, below the latest initial release plus every waiting duration
+    {
+      int64_t sumd = 0, sumc = 0, maxd = 0, bmin = in.backlog, bmax = 0;
+      for (int x = lane; x < m; x += TG_WAVE) {
+        int q0 = 0;
+        while (q0 < K - 1 && s_cdur[x * K + q0] == TG_INF) ++q0;
+        s_q0[x] = (uint8_t)q0;
+        const int64_t d = s_cdur[x * K + q0];
+        sumc += d; maxd = d > maxd ? d : maxd;
+      }
+      for (int y = lane; y < in.nd; y += TG_WAVE) {
+        const int id = in.dlist[y];
+        const uint32_t mask = in.act_kmask[id];
+        if (mask) sumd += in.dur[(size_t)id * K + __builtin_ctz(mask)];
+      }
+      for (int c = lane; c < in.n_busy; c += TG_WAVE) {
+        const int64_t b = in.busy_lds_off >= 0 ? reinterpret_cast<const int64_t*>(smem + in.busy_lds_off)[c] : in.busy[c];
+        bmin = b < bmin ? b : bmin; bmax = b > bmax ? b : bmax;
+      }
+      for (int o = 32; o > 0; o >>= 1) { sumd += __shfl_xor(sumd, o); sumc += __shfl_xor(sumc, o); }
+      sumd += sumc;
+      maxd = (int64_t)~tg_wave_min_u64(~(uint64_t)maxd);
+      bmax = (int64_t)~tg_wave_min_u64(~(uint64_t)bmax);
+      bmin = (int64_t)tg_wave_min_u64((uint64_t)bmin);
+      const int64_t top_t = in.backlog + maxd > bmax ? in.backlog + maxd : bmax;
+      if (lane == 0) {
+        s_F[NW + 1] = bmin;
+        s_F[NW + 2] = (top_t + sumd - bmin) < 0xfffffff0ll ? 1 : 0;   // estimates in 32 bits
+        s_F[NW + 3] = sumc < 0xfffffff0ll ? 1 : 0;                    // DP totals in 32 bits
+      }
+      tg_wave_sync();
+    }
 
-  // ---- DPArrange over all prefixes at once: row i holds the best totals of C[:i] ----------
-  int stride;                                                     // entries per choice row
-  if (!gpu) {
-    int sm = 0;                                                   // End(S): sum of the largest options
-    for (int a = lane; a < m; a += TG_WAVE) {
-      int kmax = 0;
-      for (int q = 0; q < K; ++q) if (s_cdur[a * K + q] != TG_INF) kmax = s_k[q];
-      sm += kmax;
-    }
-    sm = tg_wave_sum_i32(sm);
-    const int n = min(U, sm);
-    stride = n + 1;
-    int64_t* prev = s_dp;
-    int64_t* cur = s_dp + plan.dp_width;
-    for (int j = lane; j <= n; j += TG_WAVE) prev[j] = j == 0 ? 0 : TG_INF;
-    if (lane == 0) { s_rowbest[0] = 0; s_rowarg[0] = 0; }
-    tg_wave_sync();
-    for (int i = 1; i <= m; ++i) {
-      uint64_t rb = ~0ull;
-      int64_t tq[TG_MAX_K];                                       // durations of candidate i, same for all lanes
-#pragma unroll
-      for (int q = 0; q < TG_MAX_K; ++q) tq[q] = q < K ? s_cdur[(i - 1) * K + q] : TG_INF;
-      for (int j = lane; j <= n; j += TG_WAVE) {
-        int64_t bestv = TG_INF;
-        int bq = 0xff;
-#pragma unroll
-        for (int q = 0; q < TG_MAX_K; ++q) {                      // ascending k, strict <: fewer units win ties
-          const int kq = k_of(q);
-          if (tq[q] == TG_INF || j < kq) continue;
-          const int64_t pv = prev[j - kq];
-          if (pv != TG_INF && pv + tq[q] < bestv) { bestv = pv + tq[q]; bq = q; }
+    // ---- DPArrange over all prefixes at once: row i holds the best totals of C[:i] --------
+    if (!gpu) {
+      int sm = 0;                                                 // End(S): sum of the largest options
+      for (int a = lane; a < m; a += TG_WAVE) {
+        int kmax = 0;
+        for (int q = 0; q < K; ++q) if (s_cdur[a * K + q] != TG_INF) kmax = k_of(q);
+        sm += kmax;
+      }
+      sm = tg_wave_sum_i32(sm);
+      const int n = min(U, sm);
+      stride = n + 1;
+      if (s_F[NW + 3] != 0)
+        tg_dp_units<uint32_t>(reinterpret_cast<uint32_t*>(s_dp), reinterpret_cast<uint32_t*>(s_dp) + plan.dp_width, s_cdur,
+                              s_choice, s_rowbest, s_rowarg, m, n, K, kword, lane);
+      else
+        tg_dp_units<int64_t>(s_dp, s_dp + plan.dp_width, s_cdur, s_choice, s_rowbest, s_rowarg, m, n, K, kword, lane);
+    } else {
+      // Alg. 4: state = counts of free chunks (1,2,4,8), mixed-radix encoded; a transition takes
+      // the smallest chunk that holds k GPUs and splits it.  Forward relaxation with a packed
+      // 64-bit key (value | source state | option) so that ties resolve to the smallest source
+      // state, then the smallest option, independent of lane timing.
+      const int n0 = max((int)(in.chunks & 0xff), 1), n1 = max((int)(in.chunks >> 8 & 0xff), 1),
+                n2 = max((int)(in.chunks >> 16 & 0xff), 1), n3 = max((int)(in.chunks >> 24), 1);
+      const int r0 = n0 + 1, r1 = n1 + 1, r2 = n2 + 1;
+      const int S = r0 * r1 * r2 * (n3 + 1);
+      stride = S;
+      uint64_t* prev = reinterpret_cast<uint64_t*>(s_dp);
+      uint64_t* cur = prev + plan.dp_width;
+      const int s_start = (int)(in.chunks & 0xff) + r0 * ((int)(in.chunks >> 8 & 0xff) + r1 * ((int)(in.chunks >> 16 & 0xff) + r2 * (int)(in.chunks >> 24)));
+      for (int s = lane; s < S; s += TG_WAVE) prev[s] = s == s_start ? 0ull : ~0ull;
+      if (lane == 0) { s_rowbest[0] = 0; s_rowarg[0] = s_start; }
+      tg_wave_sync();
+      for (int i = 1; i <= m; ++i) {
+        for (int s = lane; s < S; s += TG_WAVE) cur[s] = ~0ull;
+        tg_wave_sync();
+        for (int s = lane; s < S; s += TG_WAVE) {
+          const uint64_t kp = prev[s];
+          if (kp == ~0ull) continue;
+          const uint64_t v = kp >> 12;
+          int rest = s;
+          const uint32_t c0 = rest % r0; rest /= r0;
+          const uint32_t c1 = rest % r1; rest /= r1;
+          const uint32_t c2 = rest % r2; rest /= r2;
+          const uint32_t c = c0 | c1 << 8 | c2 << 16 | (uint32_t)rest << 24;
+          const int largest = tg_chunk_largest(c);
+          for (int q = 0; q < K; ++q) {
+            const int64_t t = s_cdur[(i - 1) * K + q];
+            const int kq = k_of(q);
+            if (t == TG_INF || kq > largest) continue;
+            const uint32_t c2n = tg_chunk_take(c, kq);
+            const int s2 = (int)(c2n & 0xff) + r0 * ((int)(c2n >> 8 & 0xff) + r1 * ((int)(c2n >> 16 & 0xff) + r2 * (int)(c2n >> 24)));
+            const uint64_t key = (v + (uint64_t)t) << 12 | (uint64_t)s << 3 | (uint64_t)q;
+            atomicMin(reinterpret_cast<unsigned long long*>(&cur[s2]), (unsigned long long)key);
+          }
         }
-        cur[j] = bestv;
-        s_choice[(size_t)(i - 1) * stride + j] = (uint8_t)bq;
-        if (bestv != TG_INF) { const uint64_t key = (uint64_t)bestv << 9 | (uint32_t)j; rb = key < rb ? key : rb; }
-      }
-      rb = tg_wave_min_u64(rb);                                   // best over used <= n, fewest units on ties
-      if (lane == 0) { s_rowbest[i] = (int64_t)(rb >> 9); s_rowarg[i] = (int)(rb & 511); }
-      int64_t* tmp = prev; prev = cur; cur = tmp;
-      tg_wave_sync();
-    }
-  } else {
-    // Alg. 4: state = counts of free chunks (1,2,4,8), mixed-radix encoded; a transition takes
-    // the smallest chunk that holds k GPUs and splits it.  Forward relaxation with a packed
-    // 64-bit key (value | source state | option) so that ties resolve to the smallest source
-    // state, then the smallest option, independent of lane timing.
-    const int n0 = max((int)(in.chunks & 0xff), 1), n1 = max((int)(in.chunks >> 8 & 0xff), 1),
-              n2 = max((int)(in.chunks >> 16 & 0xff), 1), n3 = max((int)(in.chunks >> 24), 1);
-    const int r0 = n0 + 1, r1 = n1 + 1, r2 = n2 + 1;
-    const int S = r0 * r1 * r2 * (n3 + 1);
-    stride = S;
-    uint64_t* prev = reinterpret_cast<uint64_t*>(s_dp);
-    uint64_t* cur = prev + plan.dp_width;
-    const int s_start = (int)(in.chunks & 0xff) + r0 * ((int)(in.chunks >> 8 & 0xff) + r1 * ((int)(in.chunks >> 16 & 0xff) + r2 * (int)(in.chunks >> 24)));
-    for (int s = lane; s < S; s += TG_WAVE) prev[s] = s == s_start ? 0ull : ~0ull;
-    if (lane == 0) { s_rowbest[0] = 0; s_rowarg[0] = s_start; }
-    tg_wave_sync();
-    for (int i = 1; i <= m; ++i) {
-      for (int s = lane; s < S; s += TG_WAVE) cur[s] = ~0ull;
-      tg_wave_sync();
-      for (int s = lane; s < S; s += TG_WAVE) {
-        const uint64_t kp = prev[s];
-        if (kp == ~0ull) continue;
-        const uint64_t v = kp >> 12;
-        int rest = s;
-        const uint32_t c0 = rest % r0; rest /= r0;
-        const uint32_t c1 = rest % r1; rest /= r1;
-        const uint32_t c2 = rest % r2; rest /= r2;
-        const uint32_t c = c0 | c1 << 8 | c2 << 16 | (uint32_t)rest << 24;
-        const int largest = tg_chunk_largest(c);
-        for (int q = 0; q < K; ++q) {
-          const int64_t t = s_cdur[(i - 1) * K + q];
-          const int kq = s_k[q];
-          if (t == TG_INF || kq > largest) continue;
-          const uint32_t c2n = tg_chunk_take(c, kq);
-          const int s2 = (int)(c2n & 0xff) + r0 * ((int)(c2n >> 8 & 0xff) + r1 * ((int)(c2n >> 16 & 0xff) + r2 * (int)(c2n >> 24)));
-          const uint64_t key = (v + (uint64_t)t) << 12 | (uint64_t)s << 3 | (uint64_t)q;
-          atomicMin(reinterpret_cast<unsigned long long*>(&cur[s2]), (unsigned long long)key);
+        tg_wave_sync();
+        uint64_t rb = ~0ull;
+        for (int s = lane; s < S; s += TG_WAVE) {
+          const uint64_t k2 = cur[s];
+          s_choice16[(size_t)(i - 1) * stride + s] = (uint16_t)(k2 & 0xfff);
+          if (k2 != ~0ull) { const uint64_t key = (k2 >> 12) << 9 | (uint32_t)s; rb = key < rb ? key : rb; }
         }
+        rb = tg_wave_min_u64(rb);
+        if (lane == 0) { s_rowbest[i] = (int64_t)(rb >> 9); s_rowarg[i] = (int)(rb & 511); }
+        uint64_t* tmp = prev; prev = cur; cur = tmp;
+        tg_wave_sync();
       }
-      tg_wave_sync();
-      uint64_t rb = ~0ull;
-      for (int s = lane; s < S; s += TG_WAVE) {
-        const uint64_t k2 = cur[s];
-        s_choice16[(size_t)(i - 1) * stride + s] = (uint16_t)(k2 & 0xfff);
-        if (k2 != ~0ull) { const uint64_t key = (k2 >> 12) << 9 | (uint32_t)s; rb = key < rb ? key : rb; }
-      }
-      rb = tg_wave_min_u64(rb);
-      if (lane == 0) { s_rowbest[i] = (int64_t)(rb >> 9); s_rowarg[i] = (int)(rb & 511); }
-      uint64_t* tmp = prev; prev = cur; cur = tmp;
-      tg_wave_sync();
     }
   }
 
   // ---- Alg. 2: objective of keeping the first L candidates ---------------------------------
   const int H = U + in.n_busy;
-  // Allocations of up to 64 consecutive prefix lengths at once: lane l walks the choice table back from
-  // the best end state of C[:top-l].  The eviction loop then only looks allocations up.
-  int top = 0;
+  team_sync();                                                     // wavefront 0's tables are complete
+  const int64_t t_lo = s_F[NW + 1];
+  const bool narrow = s_F[NW + 2] != 0;
+  // Allocations of up to 64 consecutive prefix lengths at once: lane l of wavefront 0 walks the
+  // choice table back from the best end state of C[:top-l]; evaluations only look them up.
+  int top = 0;                                                     // uniform over the team
   auto backtrack_batch = [&](int new_top) {
     top = new_top;
+    team_sync();                                                   // nobody still reads the old table
     const int Lm = top - lane;
-    if (lane < plan.sel_rows && Lm >= 1) {
+    if (wave == 0 && lane < plan.sel_rows && Lm >= 1) {
       int st = s_rowarg[Lm];
       uint8_t* row = s_sel + (size_t)lane * plan.sel_stride;
       for (int i = Lm; i >= 1; --i) {
@@ -491,10 +615,9 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
         row[i - 1] = (uint8_t)q;
       }
     }
-    tg_wave_sync();
+    team_sync();
   };
-  auto objective = [&](int L) -> int64_t {
-    if (L > top || L <= top - plan.sel_rows) backtrack_batch(L);
+  auto objective = [&](int L) -> int64_t {                         // one wavefront, table covers L
     const uint8_t* sel = s_sel + (size_t)(top - L) * plan.sel_stride;
     int pos = 0;                                                   // units handed out so far
     for (int base = 0; base < L; base += TG_WAVE) {
@@ -516,37 +639,57 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
       for (int c = lane; c < in.n_busy; c += TG_WAVE) s_heap[U + c] = in.busy[c];
     }
     tg_wave_sync();
-    const int64_t approx = tg_estimate(in, s_heap, s_k, H, L, lane);
+    const int64_t approx = narrow ? tg_estimate<true>(in, s_heap, s_cdur, s_q0, s_k, H, L, lane, t_lo)
+                                  : tg_estimate<false>(in, s_heap, s_cdur, s_q0, s_k, H, L, lane, 0);
     tg_wave_sync();
     return s_rowbest[L] + (int64_t)L * in.backlog + approx;
   };
 
   // ---- Alg. 1 l.8-13: evict from the tail while the objective drops ------------------------
-  int L = m;
-  int64_t obj = objective(L);
-  while (L > 1) {
-    const int64_t nobj = objective(L - 1);
-    if (nobj >= obj) break;                                        // a tie stops the eviction
-    obj = nobj;
-    --L;
+  // Round by round, wavefront w evaluates the prefix length base - w; the values are then
+  // consumed in decreasing length exactly as the sequential loop would.
+  int L = m;                                                       // accepted length
+  int64_t obj = 0;
+  bool have = false, done = false;
+  int base = m;
+  while (!done) {
+    const int lowest = max(base - NW + 1, 1);
+    if (base > top || lowest <= top - plan.sel_rows) backtrack_batch(base);
+    const int mine = base - wave;
+    if (mine >= 1) { const int64_t f = objective(mine); if (lane == 0) s_F[wave] = f; }
+    team_sync();
+    for (int w = 0; w < NW && !done; ++w) {
+      const int Lc = base - w;
+      if (Lc < 1) { done = true; break; }
+      const int64_t f = s_F[w];
+      if (!have) { obj = f; have = true; L = Lc; }
+      else if (f >= obj) done = true;                              // a tie stops the eviction
+      else { obj = f; L = Lc; }
+      if (L == 1) done = true;
+    }
+    base -= NW;
+    team_sync();                                                   // s_F is rewritten next round
   }
   if (L > top || L <= top - plan.sel_rows) backtrack_batch(L);
-  const uint8_t* sel = s_sel + (size_t)(top - L) * plan.sel_stride;
   int used = 0;
-  for (int x = lane; x < m; x += TG_WAVE) {
-    const int id = in.clist[x];
-    if (x < L) {
-      const int q = sel[x];
-      out.units[id] = s_k[q];
-      used += s_k[q];
-      if (out.act) out.act[id] = (out.age ? out.age[id] : 0) + in.backlog + s_cdur[x * K + q];
-    } else {
-      out.node[id] = -1; out.units[id] = 0; out.reason[id] = TG_DEFER_EVICTED;
-      if (out.act) out.act[id] = -1;
+  if (wave == 0) {
+    const uint8_t* sel = s_sel + (size_t)(top - L) * plan.sel_stride;
+    for (int x = lane; x < m; x += TG_WAVE) {
+      const int id = in.clist[x];
+      if (x < L) {
+        const int q = sel[x];
+        out.units[id] = k_of(q);
+        used += k_of(q);
+        if (out.act) out.act[id] = (out.age ? out.age[id] : 0) + in.backlog + s_cdur[x * K + q];
+      } else {
+        out.node[id] = -1; out.units[id] = 0; out.reason[id] = TG_DEFER_EVICTED;
+        if (out.act) out.act[id] = -1;
+      }
     }
+    used = tg_wave_sum_i32(used);
   }
-  *used_units = tg_wave_sum_i32(used);
-  tg_wave_sync();
+  *used_units = used;
+  team_sync();
   return obj;
 }
 

@@ -80,6 +80,20 @@ def test_assign_degenerate(tg, orc, case):
     _compare(_assign_gpu(tg, p), orc.assign(p), case)
 
 
+@pytest.mark.parametrize("seed", [40, 41, 42, 43])
+def test_assign_wide_times(tg, orc, seed):
+    """Durations close to 2^36 us and backlogs close to 2^40: sums leave 32 bits, so the 64-bit
+    paths of the dynamic program and of the heap estimate are the ones that run."""
+    print("case wide", seed, flush=True)
+    p = gen.make_random_problem(seed, B=3, N=90, n_cpu=2 + seed % 2, n_gpu=1, n_api=1, depth=2, busy=seed % 2 == 0)
+    rng = np.random.default_rng(seed)
+    p["act_t_ori_us"] = np.minimum(p["act_t_ori_us"] * rng.integers(2000, 9000, p["act_t_ori_us"].shape), (1 << 36) - 1)
+    p["node_backlog_us"] = p["node_backlog_us"] * 200_000 + (p["node_type"] != gen.TYPE_API) * ((1 << 39) * (seed % 2))
+    if p.get("node_busy_rel_us") is not None:
+        p["node_busy_rel_us"] = p["node_busy_rel_us"] * 100_000
+    _compare(_assign_gpu(tg, p), orc.assign(p), f"wide {seed}")
+
+
 def test_assign_config1(tg, orc):
     p = gen.make_config(1)
     want = orc.assign(p)
