@@ -289,14 +289,21 @@ extern "C" int tg_assign(const tg_problem* p, const int64_t* d_cost, const tg_as
                      p->max_nodes_of_kind);
   hipLaunchKernelGGL(tg_lists_kernel, dim3((unsigned)((nA + nN + 255) / 256)), dim3(256), 0, s, P, W, *out);
   // persistent wavefronts pull nodes of their class; enough of them to fill the LDS of every CU
+  // The classes are independent and each is bound by the latency of its own wavefronts, so
+  // the two light classes run on side streams next to the heavy one.
+  TG_HIP_CHECK(hipEventRecord(p->ev_fork, s));
   for (int c = 0; c < kClasses; ++c) {
     const int nw = kClassWaves[c];
     const int per_cu = std::max(1, std::min(32 / nw, (160 * 1024) / std::max(plans[c].total, 1)));
     const unsigned grid = (unsigned)std::min<size_t>(nN, (size_t)256 * per_cu);
-    if (nw == 1) hipLaunchKernelGGL(tg_node_kernel<1>, dim3(grid), dim3(TG_WAVE), plans[c].total, s, P, W.dur, W, *out, plans[c], c);
-    else if (nw == 2) hipLaunchKernelGGL(tg_node_kernel<2>, dim3(grid), dim3(TG_WAVE * 2), plans[c].total, s, P, W.dur, W, *out, plans[c], c);
-    else hipLaunchKernelGGL(tg_node_kernel<8>, dim3(grid), dim3(TG_WAVE * 8), plans[c].total, s, P, W.dur, W, *out, plans[c], c);
+    hipStream_t cs = c < 2 ? p->side_stream[c] : s;
+    if (c < 2) TG_HIP_CHECK(hipStreamWaitEvent(cs, p->ev_fork, 0));
+    if (nw == 1) hipLaunchKernelGGL(tg_node_kernel<1>, dim3(grid), dim3(TG_WAVE), plans[c].total, cs, P, W.dur, W, *out, plans[c], c);
+    else if (nw == 2) hipLaunchKernelGGL(tg_node_kernel<2>, dim3(grid), dim3(TG_WAVE * 2), plans[c].total, cs, P, W.dur, W, *out, plans[c], c);
+    else hipLaunchKernelGGL(tg_node_kernel<8>, dim3(grid), dim3(TG_WAVE * 8), plans[c].total, cs, P, W.dur, W, *out, plans[c], c);
+    if (c < 2) TG_HIP_CHECK(hipEventRecord(p->ev_join[c], cs));
   }
+  for (int c = 0; c < 2; ++c) TG_HIP_CHECK(hipStreamWaitEvent(s, p->ev_join[c], 0));
   hipLaunchKernelGGL(tg_summary_kernel, dim3(P.B), dim3(256), 0, s, P, *out);
   return hipGetLastError() == hipSuccess ? TG_OK : TG_E_HIP;
 }

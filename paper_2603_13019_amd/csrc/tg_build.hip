@@ -264,6 +264,11 @@ extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_p
         hipStreamSynchronize(s) != hipSuccess) {
       hipFree(p->d_arena); delete p; return TG_E_HIP;
     }
+    bool ok = hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming) == hipSuccess;
+    for (int i = 0; i < 2 && ok; ++i)
+      ok = hipStreamCreateWithFlags(&p->side_stream[i], hipStreamNonBlocking) == hipSuccess &&
+           hipEventCreateWithFlags(&p->ev_join[i], hipEventDisableTiming) == hipSuccess;
+    if (!ok) { tg_free_problem(p); return TG_E_HIP; }
     char* base = (char*)p->d_arena;
     TgDev& v = p->dev;
     v.B = B; v.N = N; v.M = M; v.K = K; v.n_classes = d->n_classes; v.n_tasks = d->n_tasks; v.depth = d->depth;
@@ -306,6 +311,11 @@ extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_p
 extern "C" void tg_free_problem(tg_problem* p) {
   if (!p) return;
   if (p->d_arena) (void)hipFree(p->d_arena);
+  for (int i = 0; i < 2; ++i) {
+    if (p->side_stream[i]) (void)hipStreamDestroy(p->side_stream[i]);
+    if (p->ev_join[i]) (void)hipEventDestroy(p->ev_join[i]);
+  }
+  if (p->ev_fork) (void)hipEventDestroy(p->ev_fork);
   delete p;
 }
 

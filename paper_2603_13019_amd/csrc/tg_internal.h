@@ -75,6 +75,10 @@ struct tg_problem {
   int n_blocks;
   int score_wgs;
   int64_t n_candidates;
+  // tg_assign runs the node classes side by side: two side streams (default priority) forked
+  // from and joined back into the caller's stream with events
+  hipStream_t side_stream[2];
+  hipEvent_t ev_fork, ev_join[2];
   int max_nodes_of_kind;   // largest M_t over all snapshots and kinds
   int max_free_cpu;        // largest node_free over CPU nodes
   int max_heap;            // largest free + busy over CPU and GPU nodes
