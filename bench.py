@@ -25,6 +25,42 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 
 
+def replay_section(a, tg, gen, torch):
+    """Workload 5 (batched trace replay): S scenarios x 10 000 Poisson arrivals over 200 s, rescheduling every
+    100 ms, on the default cluster (256x128 cores, 32x8 GPUs, 16 quotas) and on the contended one (4x32 cores,
+    2x8 GPUs).  One launch each after one warm-up launch; actions per second over the whole launch."""
+    res = {}
+    for name, contended in (("default_cluster", False), ("contended_cluster", True)):
+        t = gen.make_trace(S=a.replay_scenarios, A=10_000, seed=4 + int(contended), contended=contended,
+                           max_ticks=8000 if not contended else 200_000)
+        T = tg.Trace(t)
+        bufs = T.alloc()
+        T.replay(bufs)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        T.replay(bufs)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        started = int(bufs["n_started"].sum().item())
+        res[name] = {"scenarios": a.replay_scenarios, "actions": a.replay_scenarios * 10_000, "started": started,
+                     "ms": ms, "actions_scheduled_per_sec": started / (ms * 1e-3),
+                     "mean_act_us": float(bufs["mean_act_us"].mean().item()),
+                     "mean_p99_act_us": float(bufs["p99_act_us"].double().mean().item()),
+                     "mean_ticks": float(bufs["n_ticks"].double().mean().item())}
+        if not a.no_cpu_baseline:
+            from oracle import orc
+            n = 4
+            t0 = time.perf_counter()
+            orc.replay(t, 0, n)
+            dt = time.perf_counter() - t0
+            res[name]["cpu_oracle_actions_per_sec"] = n * 10_000 / dt
+            res[name]["cpu_oracle_sample"] = f"{n} scenarios, 1 core"
+        T.free()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -34,6 +70,8 @@ def main():
     ap.add_argument("--snapshots", type=int, default=None, help="override B (sampling of big configs)")
     ap.add_argument("--use-cost", type=int, default=0, help="1: tg_assign reads its estimates from the score tensor")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--replay-scenarios", type=int, default=512,
+                    help="scenarios of workload 5 (10 000 arrivals each) replayed after the timed steps; 0 = skip")
     ap.add_argument("--only", choices=["step", "score", "assign"], default="step")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -102,6 +140,9 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS if achieved else None, "traffic": None,
                      "kernel": "tg_score_kernel", "bytes_per_launch": 8 * n_cand, "avg_kernel_ms": score_ms},
     }
+
+    if a.replay_scenarios > 0 and a.only == "step":
+        out["replay"] = replay_section(a, tg, gen, torch)
 
     if not a.no_cpu_baseline:
         from oracle import orc
