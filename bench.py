@@ -23,6 +23,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of tg_score_kernel on workload 2 from the FETCH_SIZE / WRITE_SIZE counter runs
+# (profiles/score_config2_hbm_counters.md): 537 696.2 KiB written x 1.000 + 5 642.6 KiB fetched x 2.000.
+# Valid for the kernel as profiled; set to None when tg_score_kernel changes.
+SCORE_TRAFFIC_CONFIG2_BYTES = int((537696.2 + 2.0 * 5642.6) * 1024)
 
 
 def replay_section(a, tg, gen, torch):
@@ -73,6 +77,8 @@ def main():
     ap.add_argument("--replay-scenarios", type=int, default=512,
                     help="scenarios of workload 5 (10 000 arrivals each) replayed after the timed steps; 0 = skip")
     ap.add_argument("--only", choices=["step", "score", "assign"], default="step")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run plain device copies of the score tensor's size (reference for the HBM byte counters)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py measures one GPU: every box of this build has a single MI355X and the path uses no "
@@ -103,6 +109,12 @@ def main():
     for _ in range(a.warmup):
         step()
     torch.cuda.synchronize()
+    if a.calibrate_copy:      # a copy kernel reads and writes exactly 8 * n_cand bytes
+        dst = torch.empty_like(cost)
+        for _ in range(3):
+            dst.copy_(cost)
+        torch.cuda.synchronize()
+        del dst
 
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True),
            torch.cuda.Event(enable_timing=True)) for _ in range(a.steps)]
@@ -137,7 +149,8 @@ def main():
         "stage_ms": {"score": score_ms, "assign": assign_ms},
         "selected_fraction": float(s["n_selected"].sum()) / n_act if s is not None else None,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS if achieved else None, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS if achieved else None,
+                     "traffic": SCORE_TRAFFIC_CONFIG2_BYTES if (a.config == 2 and a.snapshots is None) else None,
                      "kernel": "tg_score_kernel", "bytes_per_launch": 8 * n_cand, "avg_kernel_ms": score_ms},
     }
 
