@@ -62,6 +62,18 @@ def replay_section(a, tg, gen, torch):
             res[name]["cpu_oracle_actions_per_sec"] = n * 10_000 / dt
             res[name]["cpu_oracle_sample"] = f"{n} scenarios, 1 core"
         T.free()
+    # scheduler ablation (the paper's Fig. 7 on synthetic traces): elastic units against fixed DoP 4 and 16
+    t = gen.make_trace(S=64, A=2000, seed=7, cluster=(4, 32, 0, 0), type_probs=(1, 0, 0), rate_per_s=30.0,
+                       horizon_s=2000 / 30.0, max_ticks=400000, pin_frac=0.0)
+    abl = {}
+    for name, tt in (("elastic", t), ("dop4", gen.with_fixed_dop(t, 4)), ("dop16", gen.with_fixed_dop(t, 16))):
+        T = tg.Trace(tt)
+        bufs = T.replay()
+        torch.cuda.synchronize()
+        abl[name] = float(bufs["mean_act_us"].mean().item())
+        T.free()
+    res["ablation_mean_act_us"] = dict(abl, workload="64 scenarios x 2000 CPU actions at 30/s on 4 nodes x 32 cores",
+                                       elastic_vs_dop4=abl["dop4"] / abl["elastic"], elastic_vs_dop16=abl["dop16"] / abl["elastic"])
     return res
 
 

@@ -404,3 +404,14 @@ def slice_problem(p, snapshots):
         q["node_busy_off"] = np.concatenate([[0], np.cumsum(cnt)]).astype(np.int32)
         q["node_busy_rel_us"] = np.concatenate([rel[off[b * M]:off[(b + 1) * M]] for b in snapshots] + [np.zeros(0, np.int64)])
     return q
+
+
+def with_fixed_dop(t, k):
+    """Copy of a trace (or problem) in which every elastic action may only run on exactly ``k`` units
+    (the fixed degree-of-parallelism baselines of the paper's scheduler ablation); actions that do not
+    allow ``k`` keep their own set."""
+    q = {key: (v.copy() if isinstance(v, np.ndarray) else v) for key, v in t.items()}
+    bit = np.uint32(1 << [int(x) for x in t["k_list"]].index(k))
+    sel = (q["act_model"] != MODEL_NONE) & ((q["act_kmask"] & bit) != 0)
+    q["act_kmask"][sel] = bit
+    return q

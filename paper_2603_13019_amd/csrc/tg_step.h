@@ -83,11 +83,12 @@ struct TgPoolLds {
   int32_t* dcnt;     // [nodes] waiting actions pinned to the node
   int32_t* k;        // [TG_MAX_K] unit counts
   uint8_t* closed;   // [nodes] the node's pool is closed (a pinned action did not fit)
+  uint8_t* fit;      // [65] bit q set <=> k_list[q] <= min(units, 64)
 };
 
 __host__ __device__ static inline size_t tg_pool_lds_bytes(int nodes) {
   const size_t n = (size_t)((nodes + 7) & ~7);
-  return n * 8 + 64 * TG_MAX_K * 8 + n * 4 * 3 + TG_MAX_K * 4 + n;
+  return n * 8 + 64 * TG_MAX_K * 8 + n * 4 * 3 + TG_MAX_K * 4 + n + 72;
 }
 
 __device__ static inline void tg_pool_lds_carve(unsigned char* smem, int nodes, TgPoolLds* S) {
@@ -99,6 +100,7 @@ __device__ static inline void tg_pool_lds_carve(unsigned char* smem, int nodes, 
   S->dcnt = S->cnt + n;
   S->k = S->dcnt + n;
   S->closed = reinterpret_cast<uint8_t*>(S->k + TG_MAX_K);
+  S->fit = S->closed + n;
 }
 
 struct TgPlaceIo {
@@ -122,6 +124,19 @@ struct TgPlaceIo {
 __device__ static inline void tg_place_pool(const TgPoolLds& S, const TgPlaceIo& io, const int32_t* acts, int Nt,
                                             int Mt, bool gpu, int lane) {
   bool pool_closed = false;
+  // which options fit into `units` units, for units = 0..64 (every unit count is <= 64)
+  tg_wave_sync();
+  for (int u = lane; u <= TG_MAX_UNIT; u += TG_WAVE) {
+    uint32_t f = 0;
+    for (int q = 0; q < io.Kt; ++q) f |= (S.k[q] <= u ? 1u : 0u) << q;
+    S.fit[u] = (uint8_t)f;
+  }
+  // range of the backlogs: with the largest duration of a chunk it tells whether the chunk's
+  // estimates fit in 32 bits above the smallest backlog (then the argmin runs on 32-bit keys)
+  int64_t bmin = TG_INF, bmax = 0;
+  for (int r = lane; r < Mt; r += TG_WAVE) { const int64_t b = S.back[r]; bmin = b < bmin ? b : bmin; bmax = b > bmax ? b : bmax; }
+  bmin = (int64_t)tg_wave_min_u64((uint64_t)bmin);
+  bmax = (int64_t)~tg_wave_min_u64(~(uint64_t)bmax);
   for (int base = 0; base < Nt; base += TG_WAVE) {
     const int cnt = min(TG_WAVE, Nt - base);
     // lane l holds action base+l: its inputs now, its result after the loop (one global
@@ -136,10 +151,15 @@ __device__ static inline void tg_place_pool(const TgPoolLds& S, const TgPlaceIo&
     }
     int res_rank = -1, res_slot = 0, res_reason = TG_SELECTED;
     tg_wave_sync();                                  // previous chunk's readers are done with S.dur
+    int64_t dmax = 0;
     for (int x = lane; x < cnt * io.K; x += TG_WAVE) {
       const int a = x / io.K, q = x - a * io.K;
-      S.dur[x] = io.dur[(size_t)acts[base + a] * io.K + q];
+      const int64_t d = io.dur[(size_t)acts[base + a] * io.K + q];
+      S.dur[x] = d;
+      if (d != TG_INF && d > dmax) dmax = d;
     }
+    dmax = (int64_t)~tg_wave_min_u64(~(uint64_t)dmax);
+    const bool narrow = !io.cost && Mt > 0 && (bmax + dmax - bmin) < 0xfffffff0ll;
     tg_wave_sync();
     for (int l = 0; l < cnt; ++l) {
       const uint32_t mask = (uint32_t)__builtin_amdgcn_readlane((int)my_mask, l);
@@ -152,27 +172,37 @@ __device__ static inline void tg_place_pool(const TgPoolLds& S, const TgPlaceIo&
         reason = TG_DEFER_PREFIX;
       } else {
         const int kmin = S.k[__builtin_ctz(mask)];
-        uint64_t best = ~0ull;
         const int r_lo = pr >= 0 ? pr : lane, r_hi = pr >= 0 ? (lane == 0 ? pr + 1 : 0) : Mt;
+        // this lane's best node: least estimate, smallest rank on ties (ranks ascend in the loop)
+        uint32_t b32 = 0xffffffffu, brank = 0xffffffffu;
+        uint64_t b64 = ~0ull;
         for (int r = r_lo; r < r_hi; r += TG_WAVE) {
           if (S.closed[r]) continue;
           const int lim = gpu ? tg_chunk_largest((uint32_t)S.lim[r]) : S.lim[r];
-          if (kmin > lim) continue;
-          int qs = 0;                                // largest allowed option that still fits
-#pragma unroll
-          for (int q = 0; q < TG_MAX_K; ++q)
-            if (q < io.Kt && (mask >> q & 1u) && S.k[q] <= lim) qs = q;
-          const int64_t e = io.cost ? io.cost[(size_t)(base + l) * io.cost_row_len + r * io.Kt + qs]
-                                    : S.back[r] + S.dur[l * io.K + qs];
-          const uint64_t key = (uint64_t)e << 12 | (uint32_t)r;     // ties: smaller node rank
-          best = key < best ? key : best;
+          const uint32_t ok = mask & S.fit[lim < TG_MAX_UNIT ? lim : TG_MAX_UNIT];   // allowed options that still fit
+          if (ok == 0) continue;                                                      // not even the minimum units
+          const int qs = 31 - __builtin_clz(ok);                                      // the largest of them
+          if (narrow) {
+            const uint32_t e = (uint32_t)(S.back[r] + S.dur[l * io.K + qs] - bmin);
+            if (e < b32) { b32 = e; brank = (uint32_t)r; }
+          } else {
+            const int64_t e = io.cost ? io.cost[(size_t)(base + l) * io.cost_row_len + r * io.Kt + qs]
+                                      : S.back[r] + S.dur[l * io.K + qs];
+            const uint64_t key = (uint64_t)e << 12 | (uint32_t)r;
+            b64 = key < b64 ? key : b64;
+          }
         }
-        best = tg_wave_min_u64(best);
-        if (best == ~0ull) {
+        if (narrow) {
+          const uint32_t emin = tg_wave_min_u32(b32);
+          rank = (int)tg_wave_min_u32(b32 == emin ? brank : 0xffffffffu);             // 0xffffffff: nobody fits
+        } else {
+          b64 = tg_wave_min_u64(b64);
+          rank = b64 == ~0ull ? -1 : (int)(b64 & 0xfff);
+        }
+        if (rank < 0) {
           reason = TG_DEFER_PREFIX;
           if (pr >= 0) { if (lane == 0) S.closed[pr] = 1; } else pool_closed = true;
         } else {
-          rank = (int)(best & 0xfff);
           slot = S.cnt[rank];
           if (lane == 0) {
             S.cnt[rank] = slot + 1;

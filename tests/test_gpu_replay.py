@@ -100,3 +100,19 @@ def test_replay_config5_contended_sampled(tg, orc):
         else:
             want[k][31 * t["A"]:32 * t["A"]] = w[k][31 * t["A"]:32 * t["A"]]
     _compare(got, want, pick, t["A"])
+
+
+def test_replay_elastic_vs_fixed_dop(tg, orc):
+    """Scheduler ablation of the paper (its Fig. 7) on synthetic contended traces: the elastic policy against
+    fixed DoP 4 and 16 (every elastic action restricted to that unit count).  Parity of the fixed-DoP replays
+    with the oracle, and the qualitative shape: elastic gives the lower mean ACT."""
+    t = gen.make_trace(S=8, A=2000, seed=7, cluster=(4, 32, 0, 0), type_probs=(1, 0, 0), rate_per_s=30.0,
+                       horizon_s=2000 / 30.0, max_ticks=400000, pin_frac=0.0)
+    mean = {}
+    for name, tt in (("elastic", t), ("dop4", gen.with_fixed_dop(t, 4)), ("dop16", gen.with_fixed_dop(t, 16))):
+        got = _replay_gpu(tg, tt)
+        _compare(got, orc.replay(tt, 0, 3), range(3), t["A"])
+        assert (got["n_started"] == t["A"]).all()
+        mean[name] = float(got["mean_act_us"].mean())
+    print({k: round(v / 1e6, 3) for k, v in mean.items()}, flush=True)
+    assert mean["elastic"] < mean["dop4"] < mean["dop16"]
