@@ -114,3 +114,37 @@ def test_null_arguments(tg):
     assert L.tg_replay_trace(None, None, None, 0, None) == -1
     L.tg_free_problem(None)
     L.tg_free_trace(None)
+
+
+def _trace_rc(tg, t):
+    d = tg.TraceDesc()
+    for n in ("S", "A", "M", "K", "n_classes", "depth", "max_ticks"):
+        setattr(d, n, int(t[n]))
+    d.flags = 0
+    d.tick_us = int(t["tick_us"])
+    keep = []
+    tg._fill(d, t, [f[0] for f in tg.TraceDesc._fields_[9:]], keep)
+    h = C.c_void_p()
+    rc = tg.load().tg_build_trace(C.byref(d), None, C.byref(h))
+    assert rc != 0 and not h.value
+    return rc
+
+
+BAD_TRACE = {
+    "arrivals_not_sorted": (lambda t: t["arrival_us"].__setitem__(5, 0), -1),
+    "gpu_node_not_8": (lambda t: t["node_cap"].__setitem__(int(np.flatnonzero(t["node_type"] == gen.TYPE_GPU)[0]), 4), -1),
+    "tick_zero": (lambda t: t.__setitem__("tick_us", 0), -1),
+    "tokens_above_bucket": (lambda t: t["quota_tok0_micro"].__setitem__(int(np.flatnonzero(t["node_type"] == gen.TYPE_API)[0]), 10**12), -1),
+    "t_ori_range": (lambda t: t["act_t_ori_us"].__setitem__(0, 0), -2),
+    "class_out_of_range": (lambda t: (t["act_model"].__setitem__(0, 2), t["act_param"].__setitem__(0, 99), t["act_type"].__setitem__(0, 1)), -3),
+}
+
+
+@pytest.mark.parametrize("name", list(BAD_TRACE))
+def test_build_trace_rejects(tg, name):
+    t = gen.make_trace(S=2, A=50, seed=3, contended=True)
+    t = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in t.items()}
+    t["arrival_us"][5] = max(int(t["arrival_us"][5]), 1)
+    mutate, want = BAD_TRACE[name]
+    mutate(t)
+    assert _trace_rc(tg, t) == want
