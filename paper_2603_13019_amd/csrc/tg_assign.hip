@@ -28,8 +28,13 @@ struct AssignWs {
 };
 
 // Nodes are processed in classes of candidate count so that the LDS a wavefront needs (the
-// choice table grows with m) does not cap the occupancy of the many small nodes.
+// choice table grows with m) does not cap the occupancy of the many small nodes.  The three
+// launches run side by side; a node holds at most as many candidates as it has free units, so
+// the number of nodes with more than 16 / 64 free units (known when the problem is built)
+// bounds the two heavy classes: they get a wavefront per such node as far as the LDS of the
+// chip goes, the light class fills what is left.
 constexpr int kClasses = 3;
+constexpr int kSelRows = 32;     // prefix lengths backtracked per batch
 // Wavefronts that share one node of the class.  Teams of several wavefronts (tg_node_schedule<NW>,
 // NW > 1) are implemented but switched off: on workload 2 a launch with NW = 4 did not finish, and
 // the cause has not been found yet, so only NW = 1 (no workgroup barrier anywhere) is instantiated.
@@ -152,19 +157,27 @@ __global__ __launch_bounds__(TG_WAVE * NW) void tg_node_kernel(TgDev P, const in
   __shared__ int s_idx;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const size_t nN = (size_t)P.B * P.M;
-  const int n_nodes = W.class_ctl[2 * cls];
-  const int32_t* list = W.class_list + (size_t)cls * nN;
+  // own class first, then the lighter ones (their nodes fit into this launch's LDS block too)
+  int cur = cls;
+  int n_nodes = W.class_ctl[2 * cur];
+  const int32_t* list = W.class_list + (size_t)cur * nN;
   for (;;) {
     int idx = 0;
     if (NW == 1) {
-      if (lane == 0) idx = atomicAdd(&W.class_ctl[2 * cls + 1], 1);   // next unprocessed node of the class
+      if (lane == 0) idx = atomicAdd(&W.class_ctl[2 * cur + 1], 1);   // next unprocessed node of the class
       idx = __builtin_amdgcn_readfirstlane(idx);
     } else {
-      if (threadIdx.x == 0) s_idx = atomicAdd(&W.class_ctl[2 * cls + 1], 1);
+      if (threadIdx.x == 0) s_idx = atomicAdd(&W.class_ctl[2 * cur + 1], 1);
       __syncthreads();
       idx = s_idx;                                                    // rewritten only after the team's next barriers
     }
-    if (idx >= n_nodes) break;
+    if (idx >= n_nodes) {
+      if (cur == 0) break;
+      --cur;
+      n_nodes = W.class_ctl[2 * cur];
+      list = W.class_list + (size_t)cur * nN;
+      continue;
+    }
     const int gn = list[idx];
     const int b = gn / P.M;
     const size_t abase = (size_t)b * P.N;
@@ -175,7 +188,9 @@ __global__ __launch_bounds__(TG_WAVE * NW) void tg_node_kernel(TgDev P, const in
     in.nd = W.dl_cnt[gn]; in.dlist = W.dorder + abase + W.dl_off[gn];
     in.n_busy = P.has_busy ? P.node_busy_off[gn + 1] - P.node_busy_off[gn] : 0;
     in.busy = P.node_busy_rel + (P.has_busy ? P.node_busy_off[gn] : 0);
-    in.busy_lds_off = -1;
+    // the release times are read by every objective evaluation: keep them behind the plan's block
+    for (int c = lane; c < in.n_busy; c += TG_WAVE) reinterpret_cast<int64_t*>(smem + plan.total)[c] = in.busy[c];
+    in.busy_lds_off = plan.total;
     in.act_model = P.act_model + abase; in.act_kmask = P.act_kmask + abase; in.dur = dur + abase * P.K;
     in.K = P.K; in.depth = P.depth;
     in.kword = tg_pack_k(P.k_list);
@@ -277,9 +292,11 @@ extern "C" int tg_assign(const tg_problem* p, const int64_t* d_cost, const tg_as
   TgNodeLdsPlan plans[kClasses];
   int max_lds = 0;
   for (int c = 0; c < kClasses; ++c) {
-    plans[c] = tg_node_lds_plan(p->max_free_cpu, p->max_free_gpu, p->max_chunk_states, p->max_heap, P.K, class_cap(c), TG_WAVE, kClassWaves[c]);
+    plans[c] = tg_node_lds_plan(p->max_free_cpu, p->max_free_gpu, p->max_chunk_states, p->max_heap, P.K, class_cap(c), kSelRows, kClassWaves[c]);
     max_lds = plans[c].total > max_lds ? plans[c].total : max_lds;
   }
+  const int busy_lds = ((p->max_heap + 1) & ~1) * 8;              // a node's busy list has at most max_heap entries
+  max_lds += busy_lds;
   if (max_lds > 64 * 1024)
     TG_HIP_CHECK(hipFuncSetAttribute((const void*)tg_node_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds));
 
@@ -288,18 +305,24 @@ extern "C" int tg_assign(const tg_problem* p, const int64_t* d_cost, const tg_as
   hipLaunchKernelGGL(tg_place_kernel, dim3(P.B * 3), dim3(TG_WAVE), place_lds, s, P, W.dur, d_cost, p->d_blocks, W, *out,
                      p->max_nodes_of_kind);
   hipLaunchKernelGGL(tg_lists_kernel, dim3((unsigned)((nA + nN + 255) / 256)), dim3(256), 0, s, P, W, *out);
-  // persistent wavefronts pull nodes of their class; enough of them to fill the LDS of every CU
-  // The classes are independent and each is bound by the latency of its own wavefronts, so
-  // the two light classes run on side streams next to the heavy one.
+  // Persistent wavefronts pull nodes of their class and, when it is exhausted, of the lighter
+  // classes.  The classes are independent and each is bound by the latency of its own
+  // wavefronts, so the two light classes run on side streams next to the heavy one.
   TG_HIP_CHECK(hipEventRecord(p->ev_fork, s));
-  for (int c = 0; c < kClasses; ++c) {
-    const int nw = kClassWaves[c];
-    const int per_cu = std::max(1, std::min(32 / nw, (160 * 1024) / std::max(plans[c].total, 1)));
-    const unsigned grid = (unsigned)std::min<size_t>(nN, (size_t)256 * per_cu);
+  const size_t bound[kClasses] = {nN, p->nodes_free_gt16, p->nodes_free_gt64};
+  const int kCus = 256, kLdsPerCu = 160 * 1024;
+  const int share[kClasses] = {kLdsPerCu, kLdsPerCu / 10, kLdsPerCu * 6 / 10};   // LDS a class may claim on a CU
+  int lds_left = kLdsPerCu;
+  for (int c = kClasses - 1; c >= 0; --c) {                     // heaviest class first
+    const int bytes = plans[c].total + busy_lds;
+    const int want = (int)std::min<size_t>((bound[c] + kCus - 1) / kCus, 32);
+    const int per_cu = std::max(1, std::min(want, std::min(share[c], lds_left) / bytes));
+    lds_left = std::max(0, lds_left - per_cu * bytes);
+    const unsigned grid = (unsigned)std::max<size_t>(1, std::min<size_t>(bound[c], (size_t)kCus * per_cu));
     hipStream_t cs = c < 2 ? p->side_stream[c] : s;
     if (c < 2) TG_HIP_CHECK(hipStreamWaitEvent(cs, p->ev_fork, 0));
     static_assert(kClassWaves[0] == 1 && kClassWaves[1] == 1 && kClassWaves[2] == 1, "only single-wavefront teams are enabled");
-    hipLaunchKernelGGL(tg_node_kernel<1>, dim3(grid), dim3(TG_WAVE), plans[c].total, cs, P, W.dur, W, *out, plans[c], c);
+    hipLaunchKernelGGL(tg_node_kernel<1>, dim3(grid), dim3(TG_WAVE), plans[c].total + busy_lds, cs, P, W.dur, W, *out, plans[c], c);
     if (c < 2) TG_HIP_CHECK(hipEventRecord(p->ev_join[c], cs));
   }
   for (int c = 0; c < 2; ++c) TG_HIP_CHECK(hipStreamWaitEvent(s, p->ev_join[c], 0));

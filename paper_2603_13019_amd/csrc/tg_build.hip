@@ -95,6 +95,7 @@ extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_p
     const size_t o_nbrel = ar.add(std::max<size_t>(n_busy, 1) * 8);
     std::vector<int> max_cap((size_t)B * 3, -1);
     int max_kind = 0, max_free_cpu = 0, max_heap = 0, max_free_gpu = 0, max_states = 1;
+    size_t free_gt16 = 0, free_gt64 = 0;
     for (int b = 0; b < B; ++b) {
       int cnt[3] = {0, 0, 0};
       for (int j = 0; j < M; ++j) {
@@ -125,6 +126,7 @@ extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_p
         }
         if (t == TG_TYPE_CPU) max_free_cpu = std::max(max_free_cpu, fr);
         if (t != TG_TYPE_API) max_heap = std::max(max_heap, fr + nb);
+        free_gt16 += fr > 16; free_gt64 += fr > 64;
         ar.at<uint8_t>(o_ntype)[g] = (uint8_t)t;
         ar.at<int32_t>(o_ncap)[g] = cap;
         ar.at<int32_t>(o_nfree)[g] = fr;
@@ -262,7 +264,7 @@ extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_p
     hipStream_t s = (hipStream_t)hip_stream;
     if (hipMemcpyAsync(p->d_arena, ar.host.data(), ar.host.size(), hipMemcpyHostToDevice, s) != hipSuccess ||
         hipStreamSynchronize(s) != hipSuccess) {
-      hipFree(p->d_arena); delete p; return TG_E_HIP;
+      (void)hipFree(p->d_arena); delete p; return TG_E_HIP;
     }
     bool ok = hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming) == hipSuccess;
     for (int i = 0; i < 2 && ok; ++i)
@@ -297,6 +299,7 @@ extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_p
     p->max_nodes_of_kind = max_kind;
     p->max_free_cpu = max_free_cpu;
     p->max_heap = max_heap;
+    p->nodes_free_gt16 = free_gt16; p->nodes_free_gt64 = free_gt64;
     p->max_free_gpu = max_free_gpu;
     p->max_chunk_states = max_states;
     p->score_lds_nodes = lds_nodes; p->score_dur_slots = (dur_slots + 1) & ~1; p->score_row_slots = row_slots;

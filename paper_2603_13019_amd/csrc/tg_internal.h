@@ -82,6 +82,7 @@ struct tg_problem {
   int max_nodes_of_kind;   // largest M_t over all snapshots and kinds
   int max_free_cpu;        // largest node_free over CPU nodes
   int max_heap;            // largest free + busy over CPU and GPU nodes
+  size_t nodes_free_gt16, nodes_free_gt64;   // nodes with more than 16 / 64 free units: bounds on the nodes that can hold as many candidates
   int max_free_gpu, max_chunk_states;
   int score_lds_nodes;     // largest node table a score workgroup stages
   int score_dur_slots, score_row_slots;   // (row, option) durations and rows one workgroup may touch

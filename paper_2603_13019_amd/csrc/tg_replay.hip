@@ -587,7 +587,7 @@ extern "C" int tg_replay_trace(const tg_trace* t, const tg_replay_out* out, void
   const TgTraceDev& T = t->dev;
   ReplayWs W;
   carve(T, (char*)d_ws, &W);
-  const TgNodeLdsPlan plan = tg_node_lds_plan(t->max_cap_cpu, 8, t->max_chunk_states, t->max_heap, T.K, 1 << 30, 8);
+  const TgNodeLdsPlan plan = tg_node_lds_plan(t->max_cap_cpu, 8, t->max_chunk_states, t->max_heap, T.K, 1 << 30, 8, 1, TG_WAVE);
   const int busy_slots = (t->max_heap + 1 + 1) & ~1;
   const size_t pool_bytes = (tg_pool_lds_bytes(t->max_nodes_of_kind) + 15) & ~size_t(15);
   const size_t lds = 3 * pool_bytes + (size_t)kWaves * ((size_t)plan.total + (size_t)busy_slots * 8);

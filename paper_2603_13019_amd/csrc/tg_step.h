@@ -53,8 +53,8 @@ __device__ static inline uint64_t tg_wave_min_u64(uint64_t v) {
 __device__ static inline uint32_t tg_wave_min_u32(uint32_t v) {
 #define TG_DPP_MIN32_STEP(CTRL, ROWMASK)                                                                  \
   {                                                                                                       \
-    const uint32_t w = (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, ROWMASK, 0xf, false);  \
-    v = w < v ? w : v;                                                                                    \
+    const uint32_t w = (uint32_t)__builtin_amdgcn_update_dpp(-1, (int)v, CTRL, ROWMASK, 0xf, false);      \
+    v = w < v ? w : v;   /* lanes without a source see the identity of min */                             \
   }
   TG_DPP_MIN32_STEP(0x111, 0xf) TG_DPP_MIN32_STEP(0x112, 0xf) TG_DPP_MIN32_STEP(0x114, 0xf) TG_DPP_MIN32_STEP(0x118, 0xf)
   TG_DPP_MIN32_STEP(0x142, 0xa) TG_DPP_MIN32_STEP(0x143, 0xc)
@@ -118,11 +118,162 @@ struct TgPlaceIo {
   int32_t* out_node; int32_t* out_units; int64_t* out_act; uint8_t* out_reason; int32_t* slot;
 };
 
+// Admission with the node table in registers: node r = lane + 64*s is slot s of its lane
+// (Mt <= 64*R), so one action costs no LDS round trip besides its duration row: backlog, units
+// left, the options those units admit and the list lengths never leave the register file, the
+// closed flags are wavefront-uniform bit masks, and with R = 1 the smallest rank among equal
+// estimates is simply the lowest lane.  Same decisions as the LDS variant below.
+template <int R>
+__device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPlaceIo& io, const int32_t* acts, int Nt,
+                                                 int Mt, bool gpu, int lane) {
+  bool pool_closed = false;
+  tg_wave_sync();
+  for (int u = lane; u <= TG_MAX_UNIT; u += TG_WAVE) {
+    uint32_t f = 0;
+    for (int q = 0; q < io.Kt; ++q) f |= (S.k[q] <= u ? 1u : 0u) << q;
+    S.fit[u] = (uint8_t)f;
+  }
+  tg_wave_sync();
+  int64_t backv[R];
+  int32_t limv[R], cntv[R], dcntv[R];
+  uint32_t fitv[R];                                               // options that fit into the units left
+  uint64_t closed[R];
+  int64_t bmin = TG_INF, bmax = 0;
+  auto fit_of = [&](int32_t lim) {
+    const int u = gpu ? tg_chunk_largest((uint32_t)lim) : lim;
+    return (uint32_t)S.fit[u < TG_MAX_UNIT ? u : TG_MAX_UNIT];
+  };
+#pragma unroll
+  for (int s = 0; s < R; ++s) {
+    const int r = lane + TG_WAVE * s;
+    const bool have = r < Mt;
+    backv[s] = have ? S.back[r] : 0;
+    limv[s] = have ? S.lim[r] : 0;
+    fitv[s] = have ? fit_of(limv[s]) : 0u;
+    cntv[s] = 0; dcntv[s] = 0;
+    closed[s] = __ballot(have && S.closed[r] != 0);
+    if (have) { bmin = backv[s] < bmin ? backv[s] : bmin; bmax = backv[s] > bmax ? backv[s] : bmax; }
+  }
+  bmin = (int64_t)tg_wave_min_u64((uint64_t)bmin);
+  bmax = (int64_t)~tg_wave_min_u64(~(uint64_t)bmax);
+  for (int base = 0; base < Nt; base += TG_WAVE) {
+    const int cnt = min(TG_WAVE, Nt - base);
+    int my_id = 0, my_pr = -1;
+    uint32_t my_mask = 0, my_static = 0;
+    if (lane < cnt) {
+      my_id = acts[base + lane];
+      my_mask = io.act_kmask[my_id]; my_static = io.act_static[my_id];
+      const int pin = io.act_pin[my_id];
+      if (pin >= 0 && !my_static) my_pr = io.node_rank[pin];
+    }
+    int res_rank = -1, res_slot = 0, res_reason = TG_SELECTED;
+    tg_wave_sync();                                  // previous chunk's readers are done with S.dur
+    int64_t dmax = 0;
+    for (int x = lane; x < cnt * io.K; x += TG_WAVE) {
+      const int a = x / io.K, q = x - a * io.K;
+      const int64_t d = io.dur[(size_t)acts[base + a] * io.K + q];
+      S.dur[x] = d;
+      if (d != TG_INF && d > dmax) dmax = d;
+    }
+    dmax = (int64_t)~tg_wave_min_u64(~(uint64_t)dmax);
+    const bool narrow = Mt > 0 && (bmax + dmax - bmin) < 0xfffffff0ll;
+    tg_wave_sync();
+    for (int l = 0; l < cnt; ++l) {
+      const uint32_t mask = (uint32_t)__builtin_amdgcn_readlane((int)my_mask, l);
+      const int pr = __builtin_amdgcn_readlane(my_pr, l);
+      const int stat = __builtin_amdgcn_readlane((int)my_static, l);
+      int reason = TG_SELECTED, rank = -1, slot = 0;
+      uint64_t pr_closed = 0;
+#pragma unroll
+      for (int s = 0; s < R; ++s) if (pr >= 0 && (pr >> 6) == s) pr_closed = closed[s] >> (pr & 63) & 1ull;
+      if (stat) {
+        reason = TG_DEFER_INFEASIBLE;
+      } else if (pool_closed || pr_closed) {
+        reason = TG_DEFER_PREFIX;
+      } else {
+        const int kmin = S.k[__builtin_ctz(mask)];
+        uint32_t b32 = 0xffffffffu, brank = 0xffffffffu;
+        uint64_t b64 = ~0ull;
+#pragma unroll
+        for (int s = 0; s < R; ++s) {                 // ascending rank, strict <: the smaller rank wins ties
+          const int r = lane + TG_WAVE * s;
+          const bool cand = !(closed[s] >> lane & 1ull) && (pr < 0 || pr == r);
+          const uint32_t ok = cand ? mask & fitv[s] : 0u;          // allowed options that still fit
+          if (ok == 0) continue;
+          const int qs = 31 - __builtin_clz(ok);                   // the largest of them
+          const int64_t e = backv[s] + S.dur[l * io.K + qs];
+          if (narrow) {
+            const uint32_t e32 = (uint32_t)(e - bmin);
+            if (e32 < b32) { b32 = e32; brank = (uint32_t)r; }
+          } else {
+            const uint64_t key = (uint64_t)e << 12 | (uint32_t)r;
+            b64 = key < b64 ? key : b64;
+          }
+        }
+        if (narrow) {
+          const uint32_t emin = tg_wave_min_u32(b32);
+          if (R == 1) rank = emin == 0xffffffffu ? -1 : __ffsll((unsigned long long)__ballot(b32 == emin)) - 1;
+          else rank = (int)tg_wave_min_u32(b32 == emin ? brank : 0xffffffffu);      // 0xffffffff: nobody fits
+        } else {
+          b64 = tg_wave_min_u64(b64);
+          rank = b64 == ~0ull ? -1 : (int)(b64 & 0xfff);
+        }
+        rank = __builtin_amdgcn_readfirstlane(rank);
+        if (rank < 0) {
+          reason = TG_DEFER_PREFIX;
+          if (pr >= 0) {
+#pragma unroll
+            for (int s = 0; s < R; ++s) if ((pr >> 6) == s) closed[s] |= 1ull << (pr & 63);
+          } else {
+            pool_closed = true;
+          }
+        } else {
+          const int rl = rank & 63;
+#pragma unroll
+          for (int s = 0; s < R; ++s) {
+            if ((rank >> 6) != s) continue;
+            slot = __builtin_amdgcn_readlane(cntv[s], rl);
+            if (lane == rl) {
+              ++cntv[s];
+              limv[s] = gpu ? (int32_t)tg_chunk_take((uint32_t)limv[s], kmin) : limv[s] - kmin;
+              fitv[s] = fit_of(limv[s]);
+            }
+          }
+        }
+      }
+      if (reason == TG_DEFER_PREFIX && pr >= 0) {
+        const int pl = pr & 63;
+#pragma unroll
+        for (int s = 0; s < R; ++s) {
+          if ((pr >> 6) != s) continue;
+          slot = __builtin_amdgcn_readlane(dcntv[s], pl);
+          if (lane == pl) ++dcntv[s];
+        }
+      }
+      if (lane == l) { res_rank = rank; res_slot = slot; res_reason = reason; }
+    }
+    if (lane < cnt) {
+      io.out_node[my_id] = res_rank >= 0 ? io.nodes[res_rank] : -1;
+      io.out_reason[my_id] = (uint8_t)res_reason;
+      io.slot[my_id] = res_slot;
+      if (res_reason != TG_SELECTED) { io.out_units[my_id] = 0; if (io.out_act) io.out_act[my_id] = -1; }
+    }
+  }
+#pragma unroll
+  for (int s = 0; s < R; ++s) {
+    const int r = lane + TG_WAVE * s;
+    if (r < Mt) { S.cnt[r] = cntv[s]; S.dcnt[r] = dcntv[s]; }
+  }
+  tg_wave_sync();
+}
+
 // Admission of the pool's `Nt` actions (ids acts[0..Nt) in FCFS order) onto its `Mt` nodes.
 // On return S.cnt / S.dcnt hold the list lengths per node and every action has its reason,
 // node (-1 if deferred) and list slot written.
 __device__ static inline void tg_place_pool(const TgPoolLds& S, const TgPlaceIo& io, const int32_t* acts, int Nt,
                                             int Mt, bool gpu, int lane) {
+  if (!io.cost && Mt <= TG_WAVE) { tg_place_pool_regs<1>(S, io, acts, Nt, Mt, gpu, lane); return; }
+  if (!io.cost && Mt <= 4 * TG_WAVE) { tg_place_pool_regs<4>(S, io, acts, Nt, Mt, gpu, lane); return; }
   bool pool_closed = false;
   // which options fit into `units` units, for units = 0..64 (every unit count is <= 64)
   tg_wave_sync();
@@ -251,6 +402,15 @@ __device__ static inline void tg_pool_extents(const TgPoolLds& S, const int32_t*
 }
 
 // ---------------------------------------------------------------------------- per node
+// Choice table of the units DP: 4 bits per cell (option index, 0xf: unreachable); byte p of a
+// row holds cells 2p+1 (low) and 2p+2 (high); cell 0 is unreachable in every row but the empty
+// one and is not stored.
+__host__ __device__ static inline int tg_choice_stride(int n) { return (n + 1) >> 1; }
+__device__ static inline int tg_choice_get(const uint8_t* row, int j) {
+  const int b = row[(j - 1) >> 1];
+  return (j - 1) & 1 ? b >> 4 : b & 0xf;
+}
+
 struct TgNodeLdsPlan {
   int off_cdur, off_dp, off_choice, off_heap, off_rowbest, off_rowarg, off_sel, off_k;
   int dp_width;     // entries per DP row
@@ -259,23 +419,26 @@ struct TgNodeLdsPlan {
   int off_F;        // objectives of one round of evaluations + flags
   int off_q0;       // minimum-unit option of every candidate
   int heap_slots;   // heap entries per wavefront of the team
+  int off_wd, off_wu, wait_slots;   // minimum-unit duration and unit count of the first waiting actions pinned to the node
   int total;        // bytes per wavefront
 };
 
 // LDS layout of one wavefront for nodes with at most `m_cap` candidates (m never exceeds the
 // node's free units either).
 __host__ static inline TgNodeLdsPlan tg_node_lds_plan(int max_free_cpu, int max_free_gpu, int max_states, int max_heap, int K,
-                                                      int m_cap = 1 << 30, int sel_rows = TG_WAVE, int n_waves = 1) {
+                                                      int m_cap = 1 << 30, int sel_rows = TG_WAVE, int n_waves = 1,
+                                                      int wait_slots = 2 * TG_WAVE) {
   TgNodeLdsPlan p;
   const int m_cpu = max_free_cpu < m_cap ? max_free_cpu : m_cap, m_gpu = max_free_gpu < m_cap ? max_free_gpu : m_cap;
   const int mmax = (m_cpu > m_gpu ? m_cpu : m_gpu) + 1;
   const int width = (max_free_cpu + 1 > max_states ? max_free_cpu + 1 : max_states);
-  size_t choice = (size_t)m_cpu * (max_free_cpu + 1);
+  size_t choice = (size_t)m_cpu * tg_choice_stride(max_free_cpu);
   if ((size_t)m_gpu * max_states * 2 > choice) choice = (size_t)m_gpu * max_states * 2;
   size_t off = 0;
   auto take = [&](size_t b) { const size_t r = off; off += (b + 15) & ~size_t(15); return (int)r; };
   p.off_cdur = take((size_t)mmax * K * 8);
-  p.off_dp = take((size_t)width * 2 * 8);
+  const size_t dp64 = (size_t)width * 2 * 8, dp32 = (size_t)(width + 2 + TG_WAVE) * 2 * 4;   // 32-bit rows carry sentinels
+  p.off_dp = take(dp64 > dp32 ? dp64 : dp32);
   p.off_choice = take(choice + 16);
   p.heap_slots = (max_heap + 2) & ~1;
   p.off_heap = take((size_t)p.heap_slots * 8 * n_waves);
@@ -287,6 +450,9 @@ __host__ static inline TgNodeLdsPlan tg_node_lds_plan(int max_free_cpu, int max_
   p.sel_stride = mmax;
   p.sel_rows = sel_rows;
   p.off_k = take(TG_MAX_K * 4);
+  p.wait_slots = wait_slots;
+  p.off_wd = take((size_t)wait_slots * 8);
+  p.off_wu = take((size_t)wait_slots);
   p.dp_width = width;
   p.total = (int)off;
   return p;
@@ -316,91 +482,253 @@ struct TgNodeOut {
   const int64_t* age;
 };
 
-// Alg. 2 estimate(): insert the waiting actions one after the other into the completion heap
-// (one entry per unit, `H` entries staged in s_heap).  The heap lives in registers, four slots
-// per lane; a pop is a wavefront-wide minimum.  All but the first action use their minimum
-// units; the first tries its d-th smallest option for d = 1..depth.  The evicted tail C[L:] is
-// read from LDS (s_cdur, s_q0); only actions pinned to the node that never got in come from
-// global memory.  N32: every time of this node fits in 32 bits above `lo` (checked by the
-// caller), so the heap holds 32-bit offsets and a pop costs a dozen instructions.
-template <bool N32>
-__device__ static inline int64_t tg_estimate(const TgNodeIn& in, const int64_t* s_heap, const int64_t* s_cdur,
-                                             const uint8_t* s_q0, const int32_t* s_k, int H, int L, int lane, int64_t lo) {
-  typedef typename std::conditional<N32, uint32_t, uint64_t>::type V;
-  const V kPad = (V)~(V)0, kMark = (V)(kPad - 1);
-  const int n_tail = in.m - L, n_ac = n_tail + in.nd;
-  if (n_ac == 0) return 0;
-  int64_t best = TG_INF;
-  for (int d = 1; d <= in.depth; ++d) {
-    V hv[4];
+// Waiting actions pinned to the node, as Alg. 2 sees them: duration on the minimum units and
+// that unit count (0: can never run here, left out) of the first `slots` of them, in LDS.
+struct TgWaitLds {
+  const int64_t* d; const uint8_t* u; int slots;
+};
+
+// ---------------------------------------------------------------------------- Alg. 2 heaps
+// The completion heap of Alg. 2 (one entry per unit of the node: when it frees) lives in the
+// registers of the wavefront.  An action that takes u units removes the u earliest entries,
+// starts when the last of them frees and puts u copies of its finish time back.
+//
+// TgHeapSorted<NS>: 32-bit times, kept sorted ascending across the wavefront (element
+// s*64 + lane sits in h[s]; unused positions hold the pad value at the end).  The u earliest
+// entries are then simply the first u, and re-inserting is one count (how many entries are
+// earlier than the finish time) plus a shift of the entries in between by one lane - a single
+// data-parallel-primitive move per 64 entries instead of a wavefront-wide minimum per unit.
+// The initial entries are sorted once per estimate by a bitonic network.
+template <int NS>
+struct TgHeapSorted {
+  typedef uint32_t V;
+  static constexpr int kSlots = NS;
+  static constexpr uint32_t kPad = 0xffffffffu;
+
+  __device__ static inline void load(V (&h)[NS], const int64_t* s_heap, int H, int64_t lo, int lane) {
 #pragma unroll
-    for (int s = 0; s < 4; ++s) { const int idx = lane + TG_WAVE * s; hv[s] = idx < H ? (V)(uint64_t)(s_heap[idx] - (N32 ? lo : 0)) : kPad; }
-    int64_t obj = 0;
-    bool first = true, invalid = false;
-    for (int base = 0; base < n_ac && !invalid; base += TG_WAVE) {
-      const int cnt = min(TG_WAVE, n_ac - base);
-      int my_id = -1, my_u = 0, my_ok = 0, my_x = 0;
-      uint32_t my_mask = 0;
-      int64_t my_d = 0;
-      if (lane < cnt) {
-        const int x = base + lane;
-        if (x < n_tail) {                                         // evicted candidate: everything is in LDS
-          my_x = L + x;
-          const int q0 = s_q0[my_x];
-          my_u = s_k[q0]; my_ok = 1; my_d = s_cdur[my_x * in.K + q0];
-        } else {
-          my_id = in.dlist[x - n_tail];
-          my_mask = in.act_kmask[my_id];
-          const int q0 = __builtin_ctz(my_mask | 0x80000000u);
-          my_u = s_k[q0 & (TG_MAX_K - 1)];
-          my_ok = my_mask != 0 && q0 < TG_MAX_K && my_u <= H;     // can never run on this node: left out
-          if (my_ok) my_d = in.dur[(size_t)my_id * in.K + q0];
-        }
-      }
-      for (int l = 0; l < cnt; ++l) {
-        if (!__builtin_amdgcn_readlane(my_ok, l)) continue;
-        int u = __builtin_amdgcn_readlane(my_u, l);
-        int64_t dd = tg_readlane_i64(my_d, l);
-        if (first) {
-          first = false;
-          if (d > 1) {                                            // d-th smallest usable option
-            const int id = __builtin_amdgcn_readlane(my_id, l);
-            const int xx = __builtin_amdgcn_readlane(my_x, l);
-            const uint32_t mask = (uint32_t)__builtin_amdgcn_readlane((int)my_mask, l);
-            int seen = 0, qd = -1;
-            for (int q = 0; q < in.K; ++q) {
-              const bool allowed = id < 0 ? s_cdur[xx * in.K + q] != TG_INF : (mask >> q & 1u) != 0;
-              if (allowed && s_k[q] <= H && ++seen == d) { qd = q; break; }
+    for (int s = 0; s < NS; ++s) { const int idx = lane + TG_WAVE * s; h[s] = idx < H ? (V)(uint64_t)(s_heap[idx] - lo) : kPad; }
+#pragma unroll
+    for (int k = 2; k <= TG_WAVE * NS; k <<= 1) {
+#pragma unroll
+      for (int j = k >> 1; j > 0; j >>= 1) {
+        if (j >= TG_WAVE) {                                       // partner in another slot of the same lane
+#pragma unroll
+          for (int s = 0; s < NS; ++s) {
+            const int t = s ^ (j >> 6);
+            if (t > s) {
+              const bool asc = ((s * TG_WAVE) & k) == 0;
+              const V lo2 = h[s] < h[t] ? h[s] : h[t], hi2 = h[s] < h[t] ? h[t] : h[s];
+              h[s] = asc ? lo2 : hi2; h[t] = asc ? hi2 : lo2;
             }
-            if (qd < 0) { invalid = true; break; }
-            u = s_k[qd];
-            dd = id < 0 ? s_cdur[xx * in.K + qd] : in.dur[(size_t)id * in.K + qd];
+          }
+        } else {                                                  // partner lane ^ j of the same slot
+#pragma unroll
+          for (int s = 0; s < NS; ++s) {
+            const V o = (V)__shfl_xor((int)h[s], j);
+            const int idx = s * TG_WAVE + lane;
+            const bool keep_min = ((idx & j) == 0) == ((idx & k) == 0);
+            const V lo2 = h[s] < o ? h[s] : o, hi2 = h[s] < o ? o : h[s];
+            h[s] = keep_min ? lo2 : hi2;
           }
         }
-        V start = 0;
-        for (int c = 0; c < u; ++c) {                             // pop the u earliest units
-          V lm = hv[0];
-          int ls = 0;
-#pragma unroll
-          for (int s = 1; s < 4; ++s) if (hv[s] < lm) { lm = hv[s]; ls = s; }
-          V wm;
-          if (N32) wm = (V)tg_wave_min_u32((uint32_t)lm); else wm = (V)tg_wave_min_u64((uint64_t)lm);
-          const uint64_t bal = __ballot(lm == wm);
-          const int owner = __ffsll((unsigned long long)bal) - 1;
-          if (lane == owner) {
-#pragma unroll
-            for (int s = 0; s < 4; ++s) if (s == ls) hv[s] = kMark;
-          }
-          start = wm;
-        }
-        const V fin = (V)(start + (V)(uint64_t)dd);               // starts when its last unit frees
-#pragma unroll
-        for (int s = 0; s < 4; ++s) if (hv[s] == kMark) hv[s] = fin;
-        obj += (N32 ? lo : 0) + (int64_t)(uint64_t)fin;
       }
     }
-    if (invalid) break;
-    best = obj < best ? obj : best;
+  }
+
+  // entries earlier than t (the pad is later than every time)
+  __device__ static inline int count_below(const V (&h)[NS], V t) {
+    int p = 0;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) p += __popcll(__ballot(h[s] < t));
+    return p;
+  }
+
+  __device__ static inline V take(V (&h)[NS], int u, V dd, int lane) {
+    const V fin = (V)__builtin_amdgcn_readlane((int)h[0], u - 1) + dd;   // u <= 64 entries leave
+    if (u == 1) {
+      // the first entry leaves, entries 1..p-1 move down one place, the finish time lands behind them
+      const int p = count_below(h, fin);
+#pragma unroll
+      for (int s = 0; s < NS; ++s) {
+        const V nxt = s + 1 < NS ? (V)__builtin_amdgcn_readlane((int)h[s + 1 < NS ? s + 1 : s], 0) : kPad;
+        const V sh = (V)__builtin_amdgcn_update_dpp((int)nxt, (int)h[s], 0x130, 0xf, 0xf, false);   // lane i <- lane i+1, lane 63 <- nxt
+        const int idx = s * TG_WAVE + lane;
+        h[s] = idx < p - 1 ? sh : (idx == p - 1 ? fin : h[s]);
+      }
+    } else {
+      for (int c = 0; c < u; ++c) {                               // drop the first entry
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+          const V nxt = s + 1 < NS ? (V)__builtin_amdgcn_readlane((int)h[s + 1 < NS ? s + 1 : s], 0) : kPad;
+          h[s] = (V)__builtin_amdgcn_update_dpp((int)nxt, (int)h[s], 0x130, 0xf, 0xf, false);
+        }
+      }
+      for (int c = 0; c < u; ++c) {                               // insert one copy: the pads at the end fall off
+        const int p = count_below(h, fin);
+#pragma unroll
+        for (int s = NS - 1; s >= 0; --s) {
+          const V prv = s > 0 ? (V)__builtin_amdgcn_readlane((int)h[s > 0 ? s - 1 : 0], 63) : fin;
+          const V sh = (V)__builtin_amdgcn_update_dpp((int)prv, (int)h[s], 0x138, 0xf, 0xf, false);  // lane i <- lane i-1, lane 0 <- prv
+          const int idx = s * TG_WAVE + lane;
+          h[s] = idx < p ? h[s] : (idx == p ? fin : sh);
+        }
+      }
+    }
+    return fin;
+  }
+};
+
+// TgHeapWide: 64-bit times, unsorted, four slots per lane; a unit is found by a wavefront-wide
+// minimum.  Only nodes whose times do not fit in 32 bits above their earliest one use it.
+struct TgHeapWide {
+  typedef uint64_t V;
+  static constexpr int kSlots = 4;
+  static constexpr uint64_t kPad = ~0ull, kMark = ~0ull - 1;
+
+  __device__ static inline void load(V (&h)[4], const int64_t* s_heap, int H, int64_t, int lane) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) { const int idx = lane + TG_WAVE * s; h[s] = idx < H ? (V)s_heap[idx] : kPad; }
+  }
+
+  __device__ static inline V take(V (&h)[4], int u, V dd, int lane) {
+    V start = 0;
+    for (int c = 0; c < u; ++c) {                                 // pop the u earliest units
+      V lm = h[0];
+      int ls = 0;
+#pragma unroll
+      for (int s = 1; s < 4; ++s) if (h[s] < lm) { lm = h[s]; ls = s; }
+      const V wm = tg_wave_min_u64(lm);
+      const int owner = __ffsll((unsigned long long)__ballot(lm == wm)) - 1;
+      if (lane == owner) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) if (s == ls) h[s] = kMark;
+      }
+      start = wm;
+    }
+    const V fin = start + dd;                                     // starts when its last unit frees
+#pragma unroll
+    for (int s = 0; s < 4; ++s) if (h[s] == kMark) h[s] = fin;
+    return fin;
+  }
+};
+
+// Alg. 2 estimate(): insert the waiting actions one after the other into the completion heap
+// (`H` entries staged in s_heap).  All but the first action use their minimum units; the first
+// tries its d-th smallest option for d = 1..depth.  The evicted tail C[L:] is read from LDS
+// (s_cdur, s_q0); only actions pinned to the node that never got in come from global memory.
+//
+// tg_estimate_run simulates D consecutive depths d0 .. d0+D-1 side by side on D heaps: they
+// differ only in the option of the first action, and a lone wavefront is bound by the latency
+// of its dependent instructions, so independent heaps overlap.  ok[k] is false when depth
+// d0+k does not exist (the first action has fewer usable options).  Times are offsets from
+// `lo` (0 with TgHeapWide).
+template <typename HP, int D>
+__device__ static inline void tg_estimate_run(const TgNodeIn& in, const TgWaitLds& W, const int64_t* s_heap,
+                                              const int64_t* s_cdur, const uint8_t* s_q0, const int32_t* s_k, int H, int L,
+                                              int lane, int64_t lo, int d0, int64_t* obj_out, bool* ok_out) {
+  typedef typename HP::V V;
+  const int n_tail = in.m - L, n_ac = n_tail + in.nd;
+  V hv[D][HP::kSlots];
+  HP::load(hv[0], s_heap, H, lo, lane);
+#pragma unroll
+  for (int k = 1; k < D; ++k)
+#pragma unroll
+    for (int s = 0; s < HP::kSlots; ++s) hv[k][s] = hv[0][s];
+  int64_t obj[D];
+  bool ok[D];
+#pragma unroll
+  for (int k = 0; k < D; ++k) { obj[k] = 0; ok[k] = true; }
+  bool first = true;
+  for (int base = 0; base < n_ac && ok[0]; base += TG_WAVE) {
+    const int cnt = min(TG_WAVE, n_ac - base);
+    int my_u = 0, my_ok = 0;
+    int64_t my_d = 0;
+    if (lane < cnt) {
+      const int x = base + lane;
+      if (x < n_tail) {                                         // evicted candidate: everything is in LDS
+        const int q0 = s_q0[L + x];
+        my_u = s_k[q0]; my_ok = 1; my_d = s_cdur[(L + x) * in.K + q0];
+      } else if (x - n_tail < W.slots) {                        // staged when the node was set up
+        my_u = W.u[x - n_tail]; my_ok = my_u != 0; my_d = W.d[x - n_tail];
+      } else {
+        const int id = in.dlist[x - n_tail];
+        const uint32_t mask = in.act_kmask[id];
+        const int q0 = __builtin_ctz(mask | 0x80000000u);
+        my_u = s_k[q0 & (TG_MAX_K - 1)];
+        my_ok = mask != 0 && q0 < TG_MAX_K && my_u <= H;        // can never run on this node: left out
+        if (my_ok) my_d = in.dur[(size_t)id * in.K + q0];
+      }
+    }
+    for (int l = 0; l < cnt; ++l) {
+      if (!__builtin_amdgcn_readlane(my_ok, l)) continue;
+      int u[D];
+      V dd[D];
+      {
+        const int u0 = __builtin_amdgcn_readlane(my_u, l);
+        const V d0v = (V)(uint64_t)tg_readlane_i64(my_d, l);
+#pragma unroll
+        for (int k = 0; k < D; ++k) { u[k] = u0; dd[k] = d0v; }
+      }
+      if (first) {
+        first = false;
+        const int x = base + l;
+        int id = -1, xx = 0;
+        uint32_t mask = 0;
+        if (x < n_tail) xx = L + x;
+        else { id = in.dlist[x - n_tail]; mask = in.act_kmask[id]; }
+#pragma unroll
+        for (int k = 0; k < D; ++k) {
+          const int d = d0 + k;
+          if (d == 1) continue;                                 // the minimum-unit option, already set
+          int seen = 0, qd = -1;                                // d-th smallest usable option
+          for (int q = 0; q < in.K; ++q) {
+            const bool allowed = id < 0 ? s_cdur[xx * in.K + q] != TG_INF : (mask >> q & 1u) != 0;
+            if (allowed && s_k[q] <= H && ++seen == d) { qd = q; break; }
+          }
+          if (qd < 0) { ok[k] = false; continue; }              // simulated with the minimum option, result unused
+          u[k] = s_k[qd];
+          dd[k] = (V)(uint64_t)(id < 0 ? s_cdur[xx * in.K + qd] : in.dur[(size_t)id * in.K + qd]);
+        }
+        if (!ok[0]) break;
+      }
+#pragma unroll
+      for (int k = 0; k < D; ++k) {
+        const V fin = HP::take(hv[k], u[k], dd[k], lane);
+        obj[k] += lo + (int64_t)(uint64_t)fin;
+      }
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < D; ++k) { obj_out[k] = obj[k]; ok_out[k] = ok[k]; }
+}
+
+// N32: every time of this node fits in 32 bits above `lo` (checked by the caller).
+template <bool N32>
+__device__ static inline int64_t tg_estimate(const TgNodeIn& in, const TgWaitLds& W, const int64_t* s_heap,
+                                             const int64_t* s_cdur, const uint8_t* s_q0, const int32_t* s_k, int H, int L,
+                                             int lane, int64_t lo) {
+  if (in.m - L + in.nd == 0) return 0;
+  int64_t best = TG_INF;
+  for (int d0 = 1; d0 <= in.depth; d0 += 2) {
+    int64_t obj[2] = {TG_INF, TG_INF};
+    bool ok[2] = {false, false};
+    const bool two = d0 < in.depth;
+#define TG_RUN(HP)                                                                                             \
+  {                                                                                                            \
+    if (two) tg_estimate_run<HP, 2>(in, W, s_heap, s_cdur, s_q0, s_k, H, L, lane, N32 ? lo : 0, d0, obj, ok); \
+    else tg_estimate_run<HP, 1>(in, W, s_heap, s_cdur, s_q0, s_k, H, L, lane, N32 ? lo : 0, d0, obj, ok);     \
+  }
+    if (!N32) TG_RUN(TgHeapWide)
+    else if (H <= TG_WAVE) TG_RUN(TgHeapSorted<1>)
+    else if (H <= 2 * TG_WAVE) TG_RUN(TgHeapSorted<2>)
+    else TG_RUN(TgHeapSorted<4>)
+#undef TG_RUN
+    if (!ok[0]) break;                                          // no d-th option: larger depths do not exist either
+    best = obj[0] < best ? obj[0] : best;
+    if (!two) break;
+    if (!ok[1]) break;
+    best = obj[1] < best ? obj[1] : best;
   }
   return best;
 }
@@ -409,37 +737,64 @@ __device__ static inline int64_t tg_estimate(const TgNodeIn& in, const int64_t* 
 // holds the best totals of C[:i]; per row the choice of every cell, the best total over
 // used <= n and its smallest argument are kept.  V = uint32_t when every total of the node
 // fits in 32 bits (the caller checks the sum of the longest durations), else int64_t.
+
 template <typename V>
 __device__ static inline void tg_dp_units(V* prev, V* cur, const int64_t* s_cdur, uint8_t* s_choice, int64_t* s_rowbest,
                                           int32_t* s_rowarg, int m, int n, int K, uint64_t kword, int lane) {
+  typedef typename std::make_unsigned<V>::type UV;
   const V kInf = std::is_same<V, uint32_t>::value ? (V)0xffffffffu : (V)TG_INF;
-  const int stride = n + 1;
+  const int stride = tg_choice_stride(n);
   for (int j = lane; j <= n; j += TG_WAVE) prev[j] = j == 0 ? (V)0 : kInf;
   if (lane == 0) { s_rowbest[0] = 0; s_rowarg[0] = 0; }
-  tg_wave_sync();
-  for (int i = 1; i <= m; ++i) {
-    V tq[TG_MAX_K];                                               // durations of candidate i, same for all lanes
+  V tq[TG_MAX_K];                                                 // durations of candidate i, same for all lanes
+  auto load_tq = [&](int i) {                                     // unconditional reads (index clamped), masked after
 #pragma unroll
     for (int q = 0; q < TG_MAX_K; ++q) {
-      const int64_t t = q < K ? s_cdur[(i - 1) * K + q] : TG_INF;
-      tq[q] = t == TG_INF ? kInf : (V)t;
+      const int64_t t = s_cdur[(i - 1) * K + (q < K ? q : K - 1)];
+      tq[q] = (q >= K || t == TG_INF) ? kInf : (V)t;
     }
-    if (lane == 0) { cur[0] = kInf; s_choice[(size_t)(i - 1) * stride] = 0xff; }   // every candidate takes a unit
+  };
+  load_tq(1);
+  tg_wave_sync();
+  for (int i = 1; i <= m; ++i) {
+    V tc[TG_MAX_K];
+#pragma unroll
+    for (int q = 0; q < TG_MAX_K; ++q) tc[q] = tq[q];
+    if (i < m) load_tq(i + 1);                                    // next row's durations arrive while this row is computed
+    if (lane == 0) cur[0] = kInf;                                 // every candidate takes a unit
     V bv = kInf;                                                  // this lane's best cell, smallest j on ties
     uint32_t bj = 0xffffffffu;
-    for (int j = lane + 1; j <= n; j += TG_WAVE) {
-      V bestv = kInf;
-      int bq = 0xff;
+    // Two adjacent cells per pass and every read of the previous row issued unconditionally
+    // (index clamped, result masked): the reads of a pass overlap instead of costing one LDS
+    // round trip per option.
+    for (int j = 2 * lane + 1; j <= n; j += 2 * TG_WAVE) {
+      const int j2 = j + 1;
+      const bool have2 = j2 <= n;
+      V pa[TG_MAX_K], pb[TG_MAX_K];
+#pragma unroll
+      for (int q = 0; q < TG_MAX_K; ++q) {
+        const int kq = (int)(kword >> (8 * q) & 0xff);
+        pa[q] = prev[j >= kq ? j - kq : 0];
+        pb[q] = prev[have2 && j2 >= kq ? j2 - kq : 0];
+      }
+      V besta = kInf, bestb = kInf;
+      int qa = 0xf, qb = 0xf;
 #pragma unroll
       for (int q = 0; q < TG_MAX_K; ++q) {                        // ascending k, strict <: fewer units win ties
         const int kq = (int)(kword >> (8 * q) & 0xff);
-        if (tq[q] == kInf || j < kq) continue;
-        const V pv = prev[j - kq];
-        if (pv != kInf && (V)(pv + tq[q]) < bestv) { bestv = (V)(pv + tq[q]); bq = q; }
+        const V ca = (V)((UV)pa[q] + (UV)tc[q]), cb = (V)((UV)pb[q] + (UV)tc[q]);   // masked below where a term is infinite
+        const bool ta = tc[q] != kInf && j >= kq && pa[q] != kInf && ca < besta;
+        const bool tb = tc[q] != kInf && j2 >= kq && pb[q] != kInf && cb < bestb;
+        besta = ta ? ca : besta; qa = ta ? q : qa;
+        bestb = tb ? cb : bestb; qb = tb ? q : qb;
       }
-      cur[j] = bestv;
-      s_choice[(size_t)(i - 1) * stride + j] = (uint8_t)bq;
-      if (bestv < bv) { bv = bestv; bj = (uint32_t)j; }
+      cur[j] = besta;
+      if (besta < bv) { bv = besta; bj = (uint32_t)j; }
+      if (have2) {
+        cur[j2] = bestb;
+        if (bestb < bv) { bv = bestb; bj = (uint32_t)j2; }
+      }
+      s_choice[(size_t)(i - 1) * stride + (j >> 1)] = (uint8_t)(qa | (have2 ? qb : 0xf) << 4);
     }
     // best over used <= n, fewest units on ties
     if (std::is_same<V, uint32_t>::value) {
@@ -452,6 +807,67 @@ __device__ static inline void tg_dp_units(V* prev, V* cur, const int64_t* s_cdur
       if (lane == 0) { s_rowbest[i] = (int64_t)(rb >> 9); s_rowarg[i] = (int)(rb & 511); }
     }
     V* tmp = prev; prev = cur; cur = tmp;
+    tg_wave_sync();
+  }
+}
+
+// The same table for nodes whose totals stay below 2^30 (the caller checks the sum of the
+// longest durations): 32-bit cells with kDpInf32 = 2^30 standing for "unreachable", so that
+// "previous cell + duration" needs no validity test - an unreachable term keeps the sum at or
+// above 2^30 without wrapping, and 64 unreachable sentinel cells below cell 0 stand in for the
+// cells j - k < 0.  An option then costs an add, a compare, a select and a min per cell.  KK is
+// the number of options.  prev / cur point at cell 0 of two rows laid out by the caller.
+constexpr uint32_t kDpInf32 = 0x40000000u;
+
+template <int KK>
+__device__ static inline void tg_dp_units32(uint32_t* prev, uint32_t* cur, const int64_t* s_cdur, uint8_t* s_choice,
+                                            int64_t* s_rowbest, int32_t* s_rowarg, int m, int n, uint64_t kword, int lane) {
+  const int stride = tg_choice_stride(n);
+  for (int j = lane - TG_WAVE; j <= n + 1; j += TG_WAVE) { prev[j] = j == 0 ? 0u : kDpInf32; cur[j] = kDpInf32; }
+  if (lane == 0) { s_rowbest[0] = 0; s_rowarg[0] = 0; }
+  uint32_t tq[KK];                                                // durations of candidate i, same for all lanes
+  auto load_tq = [&](int i) {
+#pragma unroll
+    for (int q = 0; q < KK; ++q) {
+      const int64_t t = s_cdur[(i - 1) * KK + q];
+      tq[q] = t == TG_INF ? kDpInf32 : (uint32_t)t;
+    }
+  };
+  load_tq(1);
+  tg_wave_sync();
+  for (int i = 1; i <= m; ++i) {
+    uint32_t tc[KK];
+#pragma unroll
+    for (int q = 0; q < KK; ++q) tc[q] = tq[q];
+    if (i < m) load_tq(i + 1);                                    // next row's durations arrive while this row is computed
+    uint32_t bv = kDpInf32, bj = 0xffffffffu;                     // this lane's best cell, smallest j on ties
+    for (int j = 2 * lane + 1; j <= n; j += 2 * TG_WAVE) {        // cells j and j+1 (cell n+1 is scratch)
+      uint32_t pa[KK], pb[KK];
+#pragma unroll
+      for (int q = 0; q < KK; ++q) {
+        const int kq = (int)(kword >> (8 * q) & 0xff);
+        pa[q] = prev[j - kq];
+        pb[q] = prev[j + 1 - kq];
+      }
+      uint32_t besta = kDpInf32, bestb = kDpInf32, qa = 0xf, qb = 0xf;
+#pragma unroll
+      for (int q = 0; q < KK; ++q) {                              // ascending k, strict <: fewer units win ties
+        const uint32_t ca = pa[q] + tc[q], cb = pb[q] + tc[q];
+        qa = ca < besta ? (uint32_t)q : qa; besta = ca < besta ? ca : besta;
+        qb = cb < bestb ? (uint32_t)q : qb; bestb = cb < bestb ? cb : bestb;
+      }
+      const bool have2 = j + 1 <= n;
+      cur[j] = besta;
+      cur[j + 1] = bestb;
+      s_choice[(size_t)(i - 1) * stride + (j >> 1)] = (uint8_t)(qa | qb << 4);
+      if (besta < bv) { bv = besta; bj = (uint32_t)j; }
+      if (have2 && bestb < bv) { bv = bestb; bj = (uint32_t)(j + 1); }
+    }
+    // best over used <= n, fewest units on ties
+    const uint32_t vmin = tg_wave_min_u32(bv);
+    const uint32_t jmin = tg_wave_min_u32(bv == vmin ? bj : 0xffffffffu);
+    if (lane == 0) { s_rowbest[i] = (int64_t)vmin; s_rowarg[i] = (int)(jmin & 511); cur[0] = kDpInf32; }
+    uint32_t* tmp = prev; prev = cur; cur = tmp;
     tg_wave_sync();
   }
 }
@@ -477,6 +893,9 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
   int32_t* s_k = reinterpret_cast<int32_t*>(smem + plan.off_k);
   int64_t* s_F = reinterpret_cast<int64_t*>(smem + plan.off_F);   // [NW] objectives of one round, [NW] elastic?, [NW+1] time origin, [NW+2] 32-bit times? [NW+3] 32-bit DP?
   uint8_t* s_q0 = smem + plan.off_q0;                             // minimum-unit option of candidate x
+  int64_t* s_wd = reinterpret_cast<int64_t*>(smem + plan.off_wd);
+  uint8_t* s_wu = smem + plan.off_wu;
+  const TgWaitLds W = {s_wd, s_wu, plan.wait_slots};
   const int m = in.m, K = in.K, U = in.free_units;
   const bool gpu = in.type == TG_TYPE_GPU;
   auto team_sync = [&]() { if (NW > 1) __syncthreads(); else tg_wave_sync(); };
@@ -533,7 +952,12 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
       for (int y = lane; y < in.nd; y += TG_WAVE) {
         const int id = in.dlist[y];
         const uint32_t mask = in.act_kmask[id];
-        if (mask) sumd += in.dur[(size_t)id * K + __builtin_ctz(mask)];
+        const int q0 = __builtin_ctz(mask | 0x80000000u);
+        const int u = k_of(q0 & (TG_MAX_K - 1));
+        const bool runs = mask != 0 && q0 < TG_MAX_K && u <= U + in.n_busy;   // else it can never run on this node
+        int64_t d = 0;
+        if (mask) { d = in.dur[(size_t)id * K + __builtin_ctz(mask)]; sumd += d; }
+        if (y < plan.wait_slots) { s_wd[y] = runs ? d : 0; s_wu[y] = runs ? (uint8_t)u : 0; }
       }
       for (int c = lane; c < in.n_busy; c += TG_WAVE) {
         const int64_t b = in.busy_lds_off >= 0 ? reinterpret_cast<const int64_t*>(smem + in.busy_lds_off)[c] : in.busy[c];
@@ -548,7 +972,7 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
       if (lane == 0) {
         s_F[NW + 1] = bmin;
         s_F[NW + 2] = (top_t + sumd - bmin) < 0xfffffff0ll ? 1 : 0;   // estimates in 32 bits
-        s_F[NW + 3] = sumc < 0xfffffff0ll ? 1 : 0;                    // DP totals in 32 bits
+        s_F[NW + 3] = sumc < (int64_t)kDpInf32 ? 1 : 0;               // DP totals below the 32-bit "unreachable" mark
       }
       tg_wave_sync();
     }
@@ -563,11 +987,16 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
       }
       sm = tg_wave_sum_i32(sm);
       const int n = min(U, sm);
-      stride = n + 1;
-      if (s_F[NW + 3] != 0)
-        tg_dp_units<uint32_t>(reinterpret_cast<uint32_t*>(s_dp), reinterpret_cast<uint32_t*>(s_dp) + plan.dp_width, s_cdur,
-                              s_choice, s_rowbest, s_rowarg, m, n, K, kword, lane);
-      else
+      stride = tg_choice_stride(n);
+      if (s_F[NW + 3] != 0) {
+        uint32_t* r0 = reinterpret_cast<uint32_t*>(s_dp) + TG_WAVE;               // cell 0 of the two rows
+        uint32_t* r1 = r0 + plan.dp_width + 2 + TG_WAVE;
+        switch (K) {
+#define TG_DP32(KK) case KK: tg_dp_units32<KK>(r0, r1, s_cdur, s_choice, s_rowbest, s_rowarg, m, n, kword, lane); break;
+          TG_DP32(1) TG_DP32(2) TG_DP32(3) TG_DP32(4) TG_DP32(5) TG_DP32(6) TG_DP32(7) TG_DP32(8)
+#undef TG_DP32
+        }
+      } else
         tg_dp_units<int64_t>(s_dp, s_dp + plan.dp_width, s_cdur, s_choice, s_rowbest, s_rowarg, m, n, K, kword, lane);
     } else {
       // Alg. 4: state = counts of free chunks (1,2,4,8), mixed-radix encoded; a transition takes
@@ -640,7 +1069,7 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
       uint8_t* row = s_sel + (size_t)lane * plan.sel_stride;
       for (int i = Lm; i >= 1; --i) {
         int q;
-        if (!gpu) { q = s_choice[(size_t)(i - 1) * stride + st]; st -= k_of(q); }
+        if (!gpu) { q = tg_choice_get(s_choice + (size_t)(i - 1) * stride, st); st -= k_of(q); }
         else { const int c = s_choice16[(size_t)(i - 1) * stride + st]; q = c & 7; st = c >> 3; }
         row[i - 1] = (uint8_t)q;
       }
@@ -669,8 +1098,8 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
       for (int c = lane; c < in.n_busy; c += TG_WAVE) s_heap[U + c] = in.busy[c];
     }
     tg_wave_sync();
-    const int64_t approx = narrow ? tg_estimate<true>(in, s_heap, s_cdur, s_q0, s_k, H, L, lane, t_lo)
-                                  : tg_estimate<false>(in, s_heap, s_cdur, s_q0, s_k, H, L, lane, 0);
+    const int64_t approx = narrow ? tg_estimate<true>(in, W, s_heap, s_cdur, s_q0, s_k, H, L, lane, t_lo)
+                                  : tg_estimate<false>(in, W, s_heap, s_cdur, s_q0, s_k, H, L, lane, 0);
     tg_wave_sync();
     return s_rowbest[L] + (int64_t)L * in.backlog + approx;
   };
