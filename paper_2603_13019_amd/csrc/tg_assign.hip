@@ -311,7 +311,7 @@ extern "C" int tg_assign(const tg_problem* p, const int64_t* d_cost, const tg_as
   TG_HIP_CHECK(hipEventRecord(p->ev_fork, s));
   const size_t bound[kClasses] = {nN, p->nodes_free_gt16, p->nodes_free_gt64};
   const int kCus = 256, kLdsPerCu = 160 * 1024;
-  const int share[kClasses] = {kLdsPerCu, kLdsPerCu / 10, kLdsPerCu * 6 / 10};   // LDS a class may claim on a CU
+  const int share[kClasses] = {kLdsPerCu, kLdsPerCu / 10, kLdsPerCu * 8 / 10};   // LDS a class may claim on a CU
   int lds_left = kLdsPerCu;
   for (int c = kClasses - 1; c >= 0; --c) {                     // heaviest class first
     const int bytes = plans[c].total + busy_lds;

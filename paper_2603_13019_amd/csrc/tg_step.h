@@ -119,9 +119,12 @@ struct TgPlaceIo {
 };
 
 // Admission with the node table in registers: node r = lane + 64*s is slot s of its lane
-// (Mt <= 64*R), so one action costs no LDS round trip besides its duration row: backlog, units
-// left, the options those units admit and the list lengths never leave the register file, the
-// closed flags are wavefront-uniform bit masks, and with R = 1 the smallest rank among equal
+// (Mt <= 64*R).  A lone wavefront is bound by the number of instructions it issues per action,
+// so the loop is kept short: backlog (32-bit offsets where the pool's range allows), units
+// left, the options those units admit (zero for a closed node) and the list lengths never
+// leave the register file; what the loop needs of an action travels in one packed word and its
+// result goes back into the action's lane as one word; an action pinned to a node has a
+// single candidate and is handled with scalar code; with R = 1 the smallest rank among equal
 // estimates is simply the lowest lane.  Same decisions as the LDS variant below.
 template <int R>
 __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPlaceIo& io, const int32_t* acts, int Nt,
@@ -135,9 +138,10 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
   }
   tg_wave_sync();
   int64_t backv[R];
+  uint32_t back32[R];                                             // backlog above the pool's smallest
   int32_t limv[R], cntv[R], dcntv[R];
-  uint32_t fitv[R];                                               // options that fit into the units left
-  uint64_t closed[R];
+  uint32_t fitv[R];                                               // options that fit into the units left; 0: closed
+  uint64_t closed[R];                                             // wavefront-uniform copies of the closed flags
   int64_t bmin = TG_INF, bmax = 0;
   auto fit_of = [&](int32_t lim) {
     const int u = gpu ? tg_chunk_largest((uint32_t)lim) : lim;
@@ -147,26 +151,34 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
   for (int s = 0; s < R; ++s) {
     const int r = lane + TG_WAVE * s;
     const bool have = r < Mt;
+    const bool shut = have && S.closed[r] != 0;
     backv[s] = have ? S.back[r] : 0;
     limv[s] = have ? S.lim[r] : 0;
-    fitv[s] = have ? fit_of(limv[s]) : 0u;
+    fitv[s] = have && !shut ? fit_of(limv[s]) : 0u;
     cntv[s] = 0; dcntv[s] = 0;
-    closed[s] = __ballot(have && S.closed[r] != 0);
+    closed[s] = __ballot(shut);
     if (have) { bmin = backv[s] < bmin ? backv[s] : bmin; bmax = backv[s] > bmax ? backv[s] : bmax; }
   }
   bmin = (int64_t)tg_wave_min_u64((uint64_t)bmin);
   bmax = (int64_t)~tg_wave_min_u64(~(uint64_t)bmax);
+#pragma unroll
+  for (int s = 0; s < R; ++s) back32[s] = (uint32_t)(backv[s] - bmin);
+  // result word of an action: rank + 1 (13 bits) | list slot (17 bits) | reason (2 bits)
+  auto pack_res = [](int rank, int slot, int reason) { return (uint32_t)(rank + 1) | (uint32_t)slot << 13 | (uint32_t)reason << 30; };
   for (int base = 0; base < Nt; base += TG_WAVE) {
     const int cnt = min(TG_WAVE, Nt - base);
-    int my_id = 0, my_pr = -1;
-    uint32_t my_mask = 0, my_static = 0;
+    // lane l holds action base+l: its inputs now (mask | static << 8 | minimum units << 9 |
+    // (pinned rank + 1) << 16), its result after the loop
+    int my_id = 0;
+    uint32_t my_w = 0, my_res = 0;
     if (lane < cnt) {
       my_id = acts[base + lane];
-      my_mask = io.act_kmask[my_id]; my_static = io.act_static[my_id];
+      const uint32_t mask = io.act_kmask[my_id], stat = io.act_static[my_id] ? 1u : 0u;
       const int pin = io.act_pin[my_id];
-      if (pin >= 0 && !my_static) my_pr = io.node_rank[pin];
+      const int pr = pin >= 0 && !stat ? io.node_rank[pin] : -1;
+      const uint32_t kmin = mask ? (uint32_t)S.k[__builtin_ctz(mask)] : 0u;
+      my_w = (mask & 0xffu) | stat << 8 | kmin << 9 | (uint32_t)(pr + 1) << 16;
     }
-    int res_rank = -1, res_slot = 0, res_reason = TG_SELECTED;
     tg_wave_sync();                                  // previous chunk's readers are done with S.dur
     int64_t dmax = 0;
     for (int x = lane; x < cnt * io.K; x += TG_WAVE) {
@@ -176,83 +188,100 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
       if (d != TG_INF && d > dmax) dmax = d;
     }
     dmax = (int64_t)~tg_wave_min_u64(~(uint64_t)dmax);
+    // every estimate of the chunk fits in 32 bits above the smallest backlog (durations included)
     const bool narrow = Mt > 0 && (bmax + dmax - bmin) < 0xfffffff0ll;
+    const uint32_t* dur32 = reinterpret_cast<const uint32_t*>(S.dur);   // low words
     tg_wave_sync();
     for (int l = 0; l < cnt; ++l) {
-      const uint32_t mask = (uint32_t)__builtin_amdgcn_readlane((int)my_mask, l);
-      const int pr = __builtin_amdgcn_readlane(my_pr, l);
-      const int stat = __builtin_amdgcn_readlane((int)my_static, l);
-      int reason = TG_SELECTED, rank = -1, slot = 0;
-      uint64_t pr_closed = 0;
+      const uint32_t w = (uint32_t)__builtin_amdgcn_readlane((int)my_w, l);
+      const uint32_t mask = w & 0xffu;
+      const int kmin = (int)(w >> 9 & 0x7fu), pr = (int)(w >> 16) - 1;
+      uint32_t res;
+      int take_rank = -1;                                          // node that admits the action
+      if (w & 0x100u) {
+        res = pack_res(-1, 0, TG_DEFER_INFEASIBLE);
+      } else if (pr >= 0) {
+        // pinned: one candidate, decided on scalars
+        const int pl = pr & 63;
+        uint64_t cw = 0;
+        uint32_t f = 0;
+        int dslot = 0;
 #pragma unroll
-      for (int s = 0; s < R; ++s) if (pr >= 0 && (pr >> 6) == s) pr_closed = closed[s] >> (pr & 63) & 1ull;
-      if (stat) {
-        reason = TG_DEFER_INFEASIBLE;
-      } else if (pool_closed || pr_closed) {
-        reason = TG_DEFER_PREFIX;
-      } else {
-        const int kmin = S.k[__builtin_ctz(mask)];
-        uint32_t b32 = 0xffffffffu, brank = 0xffffffffu;
-        uint64_t b64 = ~0ull;
-#pragma unroll
-        for (int s = 0; s < R; ++s) {                 // ascending rank, strict <: the smaller rank wins ties
-          const int r = lane + TG_WAVE * s;
-          const bool cand = !(closed[s] >> lane & 1ull) && (pr < 0 || pr == r);
-          const uint32_t ok = cand ? mask & fitv[s] : 0u;          // allowed options that still fit
-          if (ok == 0) continue;
-          const int qs = 31 - __builtin_clz(ok);                   // the largest of them
-          const int64_t e = backv[s] + S.dur[l * io.K + qs];
-          if (narrow) {
-            const uint32_t e32 = (uint32_t)(e - bmin);
-            if (e32 < b32) { b32 = e32; brank = (uint32_t)r; }
-          } else {
-            const uint64_t key = (uint64_t)e << 12 | (uint32_t)r;
-            b64 = key < b64 ? key : b64;
-          }
+        for (int s = 0; s < R; ++s) {
+          if ((pr >> 6) != s) continue;
+          cw = closed[s];
+          f = (uint32_t)__builtin_amdgcn_readlane((int)fitv[s], pl);
+          dslot = __builtin_amdgcn_readlane(dcntv[s], pl);
         }
+        const bool open = !pool_closed && !(cw >> pl & 1ull);
+        if (open && (mask & f) != 0) {
+          take_rank = pr;
+          res = 0;
+        } else {
+          if (open) {                                              // did not fit: the node's pool closes
+#pragma unroll
+            for (int s = 0; s < R; ++s) {
+              if ((pr >> 6) != s) continue;
+              closed[s] |= 1ull << pl;
+              if (lane == pl) fitv[s] = 0;
+            }
+          }
+#pragma unroll
+          for (int s = 0; s < R; ++s) if ((pr >> 6) == s && lane == pl) ++dcntv[s];
+          res = pack_res(-1, dslot, TG_DEFER_PREFIX);
+        }
+      } else if (pool_closed) {
+        res = pack_res(-1, 0, TG_DEFER_PREFIX);
+      } else {
+        int rank;
         if (narrow) {
+          uint32_t b32 = 0xffffffffu, brank = 0xffffffffu;
+#pragma unroll
+          for (int s = 0; s < R; ++s) {               // ascending rank, strict <: the smaller rank wins ties
+            const uint32_t ok = mask & fitv[s];                    // allowed options that still fit
+            const int qs = 31 - __builtin_clz(ok | 1u);            // the largest of them
+            const uint32_t e32 = ok ? back32[s] + dur32[2 * (l * io.K + qs)] : 0xffffffffu;
+            if (R > 1) { if (e32 < b32) { b32 = e32; brank = (uint32_t)(lane + TG_WAVE * s); } }
+            else b32 = e32;
+          }
           const uint32_t emin = tg_wave_min_u32(b32);
           if (R == 1) rank = emin == 0xffffffffu ? -1 : __ffsll((unsigned long long)__ballot(b32 == emin)) - 1;
-          else rank = (int)tg_wave_min_u32(b32 == emin ? brank : 0xffffffffu);      // 0xffffffff: nobody fits
+          else rank = (int)tg_wave_min_u32(b32 == emin ? brank : 0xffffffffu);     // 0xffffffff: nobody fits
         } else {
+          uint64_t b64 = ~0ull;
+#pragma unroll
+          for (int s = 0; s < R; ++s) {
+            const uint32_t ok = mask & fitv[s];
+            const int qs = 31 - __builtin_clz(ok | 1u);
+            const uint64_t key = (uint64_t)(backv[s] + S.dur[l * io.K + qs]) << 12 | (uint32_t)(lane + TG_WAVE * s);
+            if (ok && key < b64) b64 = key;
+          }
           b64 = tg_wave_min_u64(b64);
           rank = b64 == ~0ull ? -1 : (int)(b64 & 0xfff);
         }
         rank = __builtin_amdgcn_readfirstlane(rank);
-        if (rank < 0) {
-          reason = TG_DEFER_PREFIX;
-          if (pr >= 0) {
-#pragma unroll
-            for (int s = 0; s < R; ++s) if ((pr >> 6) == s) closed[s] |= 1ull << (pr & 63);
-          } else {
-            pool_closed = true;
-          }
-        } else {
-          const int rl = rank & 63;
-#pragma unroll
-          for (int s = 0; s < R; ++s) {
-            if ((rank >> 6) != s) continue;
-            slot = __builtin_amdgcn_readlane(cntv[s], rl);
-            if (lane == rl) {
-              ++cntv[s];
-              limv[s] = gpu ? (int32_t)tg_chunk_take((uint32_t)limv[s], kmin) : limv[s] - kmin;
-              fitv[s] = fit_of(limv[s]);
-            }
-          }
-        }
+        if (rank < 0) { pool_closed = true; res = pack_res(-1, 0, TG_DEFER_PREFIX); }
+        else { take_rank = rank; res = 0; }
       }
-      if (reason == TG_DEFER_PREFIX && pr >= 0) {
-        const int pl = pr & 63;
+      if (take_rank >= 0) {
+        const int rl = take_rank & 63;
+        int slot = 0;
 #pragma unroll
         for (int s = 0; s < R; ++s) {
-          if ((pr >> 6) != s) continue;
-          slot = __builtin_amdgcn_readlane(dcntv[s], pl);
-          if (lane == pl) ++dcntv[s];
+          if ((take_rank >> 6) != s) continue;
+          slot = __builtin_amdgcn_readlane(cntv[s], rl);
+          if (lane == rl) {
+            ++cntv[s];
+            limv[s] = gpu ? (int32_t)tg_chunk_take((uint32_t)limv[s], kmin) : limv[s] - kmin;
+            fitv[s] = fit_of(limv[s]);
+          }
         }
+        res = pack_res(take_rank, slot, TG_SELECTED);
       }
-      if (lane == l) { res_rank = rank; res_slot = slot; res_reason = reason; }
+      if (lane == l) my_res = res;
     }
     if (lane < cnt) {
+      const int res_rank = (int)(my_res & 0x1fffu) - 1, res_slot = (int)(my_res >> 13 & 0x1ffffu), res_reason = (int)(my_res >> 30);
       io.out_node[my_id] = res_rank >= 0 ? io.nodes[res_rank] : -1;
       io.out_reason[my_id] = (uint8_t)res_reason;
       io.slot[my_id] = res_slot;
@@ -406,6 +435,10 @@ __device__ static inline void tg_pool_extents(const TgPoolLds& S, const int32_t*
 // row holds cells 2p+1 (low) and 2p+2 (high); cell 0 is unreachable in every row but the empty
 // one and is not stored.
 __host__ __device__ static inline int tg_choice_stride(int n) { return (n + 1) >> 1; }
+__device__ static inline int tg_sel_get(const uint8_t* row, int x) {   // allocation table: candidate x of a row
+  const int b = row[x >> 1];
+  return x & 1 ? b >> 4 : b & 0xf;
+}
 __device__ static inline int tg_choice_get(const uint8_t* row, int j) {
   const int b = row[(j - 1) >> 1];
   return (j - 1) & 1 ? b >> 4 : b & 0xf;
@@ -414,7 +447,7 @@ __device__ static inline int tg_choice_get(const uint8_t* row, int j) {
 struct TgNodeLdsPlan {
   int off_cdur, off_dp, off_choice, off_heap, off_rowbest, off_rowarg, off_sel, off_k;
   int dp_width;     // entries per DP row
-  int sel_stride;   // candidates per row of the allocation table
+  int sel_stride;   // bytes per row of the allocation table (two candidates per byte)
   int sel_rows;     // prefix lengths backtracked per batch (<= 64)
   int off_F;        // objectives of one round of evaluations + flags
   int off_q0;       // minimum-unit option of every candidate
@@ -427,7 +460,7 @@ struct TgNodeLdsPlan {
 // node's free units either).
 __host__ static inline TgNodeLdsPlan tg_node_lds_plan(int max_free_cpu, int max_free_gpu, int max_states, int max_heap, int K,
                                                       int m_cap = 1 << 30, int sel_rows = TG_WAVE, int n_waves = 1,
-                                                      int wait_slots = 2 * TG_WAVE) {
+                                                      int wait_slots = TG_WAVE) {
   TgNodeLdsPlan p;
   const int m_cpu = max_free_cpu < m_cap ? max_free_cpu : m_cap, m_gpu = max_free_gpu < m_cap ? max_free_gpu : m_cap;
   const int mmax = (m_cpu > m_gpu ? m_cpu : m_gpu) + 1;
@@ -438,16 +471,20 @@ __host__ static inline TgNodeLdsPlan tg_node_lds_plan(int max_free_cpu, int max_
   auto take = [&](size_t b) { const size_t r = off; off += (b + 15) & ~size_t(15); return (int)r; };
   p.off_cdur = take((size_t)mmax * K * 8);
   const size_t dp64 = (size_t)width * 2 * 8, dp32 = (size_t)(width + 2 + TG_WAVE) * 2 * 4;   // 32-bit rows carry sentinels
-  p.off_dp = take(dp64 > dp32 ? dp64 : dp32);
-  p.off_choice = take(choice + 16);
+  size_t dp = dp64 > dp32 ? dp64 : dp32;
   p.heap_slots = (max_heap + 2) & ~1;
-  p.off_heap = take((size_t)p.heap_slots * 8 * n_waves);
+  const size_t heap = (size_t)p.heap_slots * 8;
+  // a single wavefront fills the DP rows first and stages heaps only afterwards: one block serves both
+  if (n_waves == 1 && heap > dp) dp = heap;
+  p.off_dp = take(dp);
+  p.off_choice = take(choice + 16);
+  p.off_heap = n_waves == 1 ? p.off_dp : take(heap * n_waves);
   p.off_F = take((size_t)(n_waves + 4) * 8);
   p.off_q0 = take((size_t)mmax);
   p.off_rowbest = take((size_t)(mmax + 1) * 8);
   p.off_rowarg = take((size_t)(mmax + 1) * 4);
-  p.off_sel = take((size_t)mmax * sel_rows);    // allocations of sel_rows consecutive prefix lengths
-  p.sel_stride = mmax;
+  p.sel_stride = (mmax + 1) >> 1;               // 4 bits per candidate
+  p.off_sel = take((size_t)p.sel_stride * sel_rows);    // allocations of sel_rows consecutive prefix lengths
   p.sel_rows = sel_rows;
   p.off_k = take(TG_MAX_K * 4);
   p.wait_slots = wait_slots;
@@ -495,9 +532,9 @@ struct TgWaitLds {
 //
 // TgHeapSorted<NS>: 32-bit times, kept sorted ascending across the wavefront (element
 // s*64 + lane sits in h[s]; unused positions hold the pad value at the end).  The u earliest
-// entries are then simply the first u, and re-inserting is one count (how many entries are
-// earlier than the finish time) plus a shift of the entries in between by one lane - a single
-// data-parallel-primitive move per 64 entries instead of a wavefront-wide minimum per unit.
+// entries are then simply the first u, and re-inserting a finish time is a shift by one lane
+// (a single data-parallel-primitive move per 64 entries) followed by a max and a min - instead
+// of a wavefront-wide minimum per unit.
 // The initial entries are sorted once per estimate by a bitonic network.
 template <int NS>
 struct TgHeapSorted {
@@ -536,43 +573,19 @@ struct TgHeapSorted {
     }
   }
 
-  // entries earlier than t (the pad is later than every time)
-  __device__ static inline int count_below(const V (&h)[NS], V t) {
-    int p = 0;
-#pragma unroll
-    for (int s = 0; s < NS; ++s) p += __popcll(__ballot(h[s] < t));
-    return p;
-  }
-
+  // One unit leaves and one copy of `fin` (later than the u earliest entries) enters: with
+  // sh[i] = h[i+1], the new sorted sequence is min(sh[i], max(h[i], fin)) - below the insertion
+  // point the entries move down one place, at it max() yields fin, above it nothing changes.
+  // Repeating the step u times removes the u earliest entries and inserts u copies.
   __device__ static inline V take(V (&h)[NS], int u, V dd, int lane) {
-    const V fin = (V)__builtin_amdgcn_readlane((int)h[0], u - 1) + dd;   // u <= 64 entries leave
-    if (u == 1) {
-      // the first entry leaves, entries 1..p-1 move down one place, the finish time lands behind them
-      const int p = count_below(h, fin);
+    const V fin = (V)__builtin_amdgcn_readlane((int)h[0], u - 1) + dd;   // u <= 64; starts when its last unit frees
+    for (int c = 0; c < u; ++c) {
 #pragma unroll
       for (int s = 0; s < NS; ++s) {
         const V nxt = s + 1 < NS ? (V)__builtin_amdgcn_readlane((int)h[s + 1 < NS ? s + 1 : s], 0) : kPad;
         const V sh = (V)__builtin_amdgcn_update_dpp((int)nxt, (int)h[s], 0x130, 0xf, 0xf, false);   // lane i <- lane i+1, lane 63 <- nxt
-        const int idx = s * TG_WAVE + lane;
-        h[s] = idx < p - 1 ? sh : (idx == p - 1 ? fin : h[s]);
-      }
-    } else {
-      for (int c = 0; c < u; ++c) {                               // drop the first entry
-#pragma unroll
-        for (int s = 0; s < NS; ++s) {
-          const V nxt = s + 1 < NS ? (V)__builtin_amdgcn_readlane((int)h[s + 1 < NS ? s + 1 : s], 0) : kPad;
-          h[s] = (V)__builtin_amdgcn_update_dpp((int)nxt, (int)h[s], 0x130, 0xf, 0xf, false);
-        }
-      }
-      for (int c = 0; c < u; ++c) {                               // insert one copy: the pads at the end fall off
-        const int p = count_below(h, fin);
-#pragma unroll
-        for (int s = NS - 1; s >= 0; --s) {
-          const V prv = s > 0 ? (V)__builtin_amdgcn_readlane((int)h[s > 0 ? s - 1 : 0], 63) : fin;
-          const V sh = (V)__builtin_amdgcn_update_dpp((int)prv, (int)h[s], 0x138, 0xf, 0xf, false);  // lane i <- lane i-1, lane 0 <- prv
-          const int idx = s * TG_WAVE + lane;
-          h[s] = idx < p ? h[s] : (idx == p ? fin : sh);
-        }
+        const V hi = h[s] > fin ? h[s] : fin;
+        h[s] = sh < hi ? sh : hi;
       }
     }
     return fin;
@@ -635,72 +648,85 @@ __device__ static inline void tg_estimate_run(const TgNodeIn& in, const TgWaitLd
   for (int k = 1; k < D; ++k)
 #pragma unroll
     for (int s = 0; s < HP::kSlots; ++s) hv[k][s] = hv[0][s];
-  int64_t obj[D];
+  uint64_t obj[D];                                              // sums of finish-time offsets (wavefront-uniform)
   bool ok[D];
 #pragma unroll
   for (int k = 0; k < D; ++k) { obj[k] = 0; ok[k] = true; }
+  int n_done = 0;
   bool first = true;
   for (int base = 0; base < n_ac && ok[0]; base += TG_WAVE) {
     const int cnt = min(TG_WAVE, n_ac - base);
-    int my_u = 0, my_ok = 0;
-    int64_t my_d = 0;
+    int my_u = 0;
+    bool my_ok = false;
+    V my_d = 0;
     if (lane < cnt) {
       const int x = base + lane;
       if (x < n_tail) {                                         // evicted candidate: everything is in LDS
         const int q0 = s_q0[L + x];
-        my_u = s_k[q0]; my_ok = 1; my_d = s_cdur[(L + x) * in.K + q0];
+        my_u = s_k[q0]; my_ok = true; my_d = (V)(uint64_t)s_cdur[(L + x) * in.K + q0];
       } else if (x - n_tail < W.slots) {                        // staged when the node was set up
-        my_u = W.u[x - n_tail]; my_ok = my_u != 0; my_d = W.d[x - n_tail];
+        my_u = W.u[x - n_tail]; my_ok = my_u != 0; my_d = (V)(uint64_t)W.d[x - n_tail];
       } else {
         const int id = in.dlist[x - n_tail];
         const uint32_t mask = in.act_kmask[id];
         const int q0 = __builtin_ctz(mask | 0x80000000u);
         my_u = s_k[q0 & (TG_MAX_K - 1)];
         my_ok = mask != 0 && q0 < TG_MAX_K && my_u <= H;        // can never run on this node: left out
-        if (my_ok) my_d = in.dur[(size_t)id * in.K + q0];
+        if (my_ok) my_d = (V)(uint64_t)in.dur[(size_t)id * in.K + q0];
       }
     }
-    for (int l = 0; l < cnt; ++l) {
-      if (!__builtin_amdgcn_readlane(my_ok, l)) continue;
+    uint64_t todo = __ballot(my_ok);                            // the chunk's actions that take part, FCFS = ascending lane
+    auto lane_d = [&](int l) -> V {
+      if (sizeof(V) == 4) return (V)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)my_d, l);
+      return (V)(uint64_t)tg_readlane_i64((int64_t)(uint64_t)my_d, l);
+    };
+    if (first && todo) {
+      // the very first action tries its d-th smallest usable option, d = d0 + k
+      first = false;
+      const int l = __ffsll((unsigned long long)todo) - 1;
+      todo &= todo - 1;
+      const int x = base + l;
+      int id = -1, xx = 0;
+      uint32_t mask = 0;
+      if (x < n_tail) xx = L + x;
+      else { id = in.dlist[x - n_tail]; mask = in.act_kmask[id]; }
       int u[D];
       V dd[D];
-      {
-        const int u0 = __builtin_amdgcn_readlane(my_u, l);
-        const V d0v = (V)(uint64_t)tg_readlane_i64(my_d, l);
-#pragma unroll
-        for (int k = 0; k < D; ++k) { u[k] = u0; dd[k] = d0v; }
-      }
-      if (first) {
-        first = false;
-        const int x = base + l;
-        int id = -1, xx = 0;
-        uint32_t mask = 0;
-        if (x < n_tail) xx = L + x;
-        else { id = in.dlist[x - n_tail]; mask = in.act_kmask[id]; }
-#pragma unroll
-        for (int k = 0; k < D; ++k) {
-          const int d = d0 + k;
-          if (d == 1) continue;                                 // the minimum-unit option, already set
-          int seen = 0, qd = -1;                                // d-th smallest usable option
-          for (int q = 0; q < in.K; ++q) {
-            const bool allowed = id < 0 ? s_cdur[xx * in.K + q] != TG_INF : (mask >> q & 1u) != 0;
-            if (allowed && s_k[q] <= H && ++seen == d) { qd = q; break; }
-          }
-          if (qd < 0) { ok[k] = false; continue; }              // simulated with the minimum option, result unused
-          u[k] = s_k[qd];
-          dd[k] = (V)(uint64_t)(id < 0 ? s_cdur[xx * in.K + qd] : in.dur[(size_t)id * in.K + qd]);
-        }
-        if (!ok[0]) break;
-      }
 #pragma unroll
       for (int k = 0; k < D; ++k) {
-        const V fin = HP::take(hv[k], u[k], dd[k], lane);
-        obj[k] += lo + (int64_t)(uint64_t)fin;
+        u[k] = __builtin_amdgcn_readlane(my_u, l);
+        dd[k] = lane_d(l);
+        const int d = d0 + k;
+        if (d == 1) continue;                                   // the minimum-unit option
+        int seen = 0, qd = -1;
+        for (int q = 0; q < in.K; ++q) {
+          const bool allowed = id < 0 ? s_cdur[xx * in.K + q] != TG_INF : (mask >> q & 1u) != 0;
+          if (allowed && s_k[q] <= H && ++seen == d) { qd = q; break; }
+        }
+        qd = __builtin_amdgcn_readfirstlane(qd);
+        if (qd < 0) { ok[k] = false; continue; }                // simulated with the minimum option, result unused
+        u[k] = __builtin_amdgcn_readfirstlane(s_k[qd]);
+        const int64_t t = id < 0 ? s_cdur[xx * in.K + qd] : in.dur[(size_t)id * in.K + qd];
+        if (sizeof(V) == 4) dd[k] = (V)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)t);
+        else dd[k] = (V)(uint64_t)tg_readlane_i64(t, 0);
       }
+      if (!ok[0]) break;
+#pragma unroll
+      for (int k = 0; k < D; ++k) obj[k] += (uint64_t)HP::take(hv[k], u[k], dd[k], lane);
+      ++n_done;
+    }
+    while (todo) {                                              // everybody else on the minimum units
+      const int l = __ffsll((unsigned long long)todo) - 1;
+      todo &= todo - 1;
+      const int u = __builtin_amdgcn_readlane(my_u, l);
+      const V dd = lane_d(l);
+#pragma unroll
+      for (int k = 0; k < D; ++k) obj[k] += (uint64_t)HP::take(hv[k], u, dd, lane);
+      ++n_done;
     }
   }
 #pragma unroll
-  for (int k = 0; k < D; ++k) { obj_out[k] = obj[k]; ok_out[k] = ok[k]; }
+  for (int k = 0; k < D; ++k) { obj_out[k] = (int64_t)obj[k] + lo * n_done; ok_out[k] = ok[k]; }
 }
 
 // N32: every time of this node fits in 32 bits above `lo` (checked by the caller).
@@ -1067,11 +1093,13 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
     if (wave == 0 && lane < plan.sel_rows && Lm >= 1) {
       int st = s_rowarg[Lm];
       uint8_t* row = s_sel + (size_t)lane * plan.sel_stride;
+      int hold = 0;                                                // option of the odd candidate of the current byte
       for (int i = Lm; i >= 1; --i) {
         int q;
         if (!gpu) { q = tg_choice_get(s_choice + (size_t)(i - 1) * stride, st); st -= k_of(q); }
         else { const int c = s_choice16[(size_t)(i - 1) * stride + st]; q = c & 7; st = c >> 3; }
-        row[i - 1] = (uint8_t)q;
+        if ((i - 1) & 1) hold = q;
+        else { row[(i - 1) >> 1] = (uint8_t)(q | hold << 4); hold = 0; }
       }
     }
     team_sync();
@@ -1081,7 +1109,7 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
     int pos = 0;                                                   // units handed out so far
     for (int base = 0; base < L; base += TG_WAVE) {
       const int x = base + lane;
-      const int q = x < L ? sel[x] : 0, kq = x < L ? k_of(q) : 0;
+      const int q = x < L ? tg_sel_get(sel, x) : 0, kq = x < L ? k_of(q) : 0;
       int inc = kq;                                                // inclusive scan of the unit counts
       for (int o = 1; o < TG_WAVE; o <<= 1) { const int u = __shfl_up(inc, o); if (lane >= o) inc += u; }
       if (x < L) {                                                 // k_i entries at backlog + dur_i(k_i)
@@ -1136,7 +1164,7 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
     for (int x = lane; x < m; x += TG_WAVE) {
       const int id = in.clist[x];
       if (x < L) {
-        const int q = sel[x];
+        const int q = tg_sel_get(sel, x);
         out.units[id] = k_of(q);
         used += k_of(q);
         if (out.act) out.act[id] = (out.age ? out.age[id] : 0) + in.backlog + s_cdur[x * K + q];
