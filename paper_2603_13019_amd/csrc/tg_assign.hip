@@ -35,9 +35,9 @@ struct AssignWs {
 // chip goes, the light class fills what is left.
 constexpr int kClasses = 3;
 constexpr int kSelRows = 32;     // prefix lengths backtracked per batch
-// Wavefronts that share one node of the class.  Teams of several wavefronts (tg_node_schedule<NW>,
-// NW > 1) are implemented but switched off: on workload 2 a launch with NW = 4 did not finish, and
-// the cause has not been found yet, so only NW = 1 (no workgroup barrier anywhere) is instantiated.
+// One wavefront per node.  Teams of several wavefronts (tg_node_schedule<NW>, NW > 1) are
+// implemented but switched off: on workload 2 a launch with NW = 4 did not finish, and the cause
+// has not been found yet, so only NW = 1 (no workgroup barrier anywhere) is instantiated.
 constexpr int kClassWaves[kClasses] = {1, 1, 1};
 constexpr int kClassCap0 = 16, kClassCap1 = 64;
 __host__ __device__ constexpr int class_cap(int c) { return c == 0 ? kClassCap0 : c == 1 ? kClassCap1 : 1 << 30; }
@@ -150,58 +150,69 @@ __global__ __launch_bounds__(256) void tg_lists_kernel(TgDev P, AssignWs W, tg_a
 }
 
 // ------------------------------------------------------------------------------------------
-template <int NW>
-__global__ __launch_bounds__(TG_WAVE * NW) void tg_node_kernel(TgDev P, const int64_t* __restrict__ dur, AssignWs W,
-                                                               tg_assign_out O, TgNodeLdsPlan plan, int cls) {
+__global__ __launch_bounds__(TG_WAVE) void tg_node_kernel(TgDev P, const int64_t* __restrict__ dur, AssignWs W,
+                                                          tg_assign_out O, TgNodeLdsPlan plan, int cls) {
   extern __shared__ __align__(16) unsigned char smem[];
-  __shared__ int s_idx;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x;
   const size_t nN = (size_t)P.B * P.M;
   // own class first, then the lighter ones (their nodes fit into this launch's LDS block too)
   int cur = cls;
   int n_nodes = W.class_ctl[2 * cur];
   const int32_t* list = W.class_list + (size_t)cur * nN;
   for (;;) {
-    int idx = 0;
-    if (NW == 1) {
-      if (lane == 0) idx = atomicAdd(&W.class_ctl[2 * cur + 1], 1);   // next unprocessed node of the class
-      idx = __builtin_amdgcn_readfirstlane(idx);
-    } else {
-      if (threadIdx.x == 0) s_idx = atomicAdd(&W.class_ctl[2 * cur + 1], 1);
-      __syncthreads();
-      idx = s_idx;                                                    // rewritten only after the team's next barriers
-    }
-    if (idx >= n_nodes) {
+    // A batch of nodes per fetch (the lighter the class, the more): lane j reads the table
+    // entries of the batch's j-th node, so the counter and the node tables cost one memory
+    // round trip per batch instead of several per node.
+    const int batch = cur == 0 ? 4 : cur == 1 ? 2 : 1;
+    int idx0 = 0;
+    if (lane == 0) idx0 = atomicAdd(&W.class_ctl[2 * cur + 1], batch);   // next unprocessed nodes of the class
+    idx0 = __builtin_amdgcn_readfirstlane(idx0);
+    if (idx0 >= n_nodes) {
       if (cur == 0) break;
       --cur;
       n_nodes = W.class_ctl[2 * cur];
       list = W.class_list + (size_t)cur * nN;
       continue;
     }
-    const int gn = list[idx];
-    const int b = gn / P.M;
-    const size_t abase = (size_t)b * P.N;
-    TgNodeIn in;
-    in.type = P.node_type[gn]; in.cap = P.node_cap[gn]; in.free_units = P.node_free[gn];
-    in.backlog = P.node_backlog[gn]; in.chunks = P.node_chunks[gn];
-    in.m = W.nl_cnt[gn]; in.clist = W.order + abase + W.nl_off[gn];
-    in.nd = W.dl_cnt[gn]; in.dlist = W.dorder + abase + W.dl_off[gn];
-    in.n_busy = P.has_busy ? P.node_busy_off[gn + 1] - P.node_busy_off[gn] : 0;
-    in.busy = P.node_busy_rel + (P.has_busy ? P.node_busy_off[gn] : 0);
-    // the release times are read by every objective evaluation: keep them behind the plan's block
-    for (int c = lane; c < in.n_busy; c += TG_WAVE) reinterpret_cast<int64_t*>(smem + plan.total)[c] = in.busy[c];
-    in.busy_lds_off = plan.total;
-    in.act_model = P.act_model + abase; in.act_kmask = P.act_kmask + abase; in.dur = dur + abase * P.K;
-    in.K = P.K; in.depth = P.depth;
-    in.kword = tg_pack_k(P.k_list);
-    TgNodeOut out;
-    out.node = O.node + abase; out.units = O.units + abase; out.act = O.act_us + abase; out.reason = O.defer_reason + abase;
-    out.age = P.act_age + abase;
-    int used = 0;
-    const int64_t obj = tg_node_schedule<NW>(smem, plan, in, out, lane, wave, &used);
-    if (threadIdx.x == 0) {
-      if (O.node_obj) O.node_obj[gn] = obj;
-      if (O.node_used) O.node_used[gn] = used;
+    const int nb = min(batch, n_nodes - idx0);
+    int my_gn = 0, my_type = 0, my_cap = 0, my_free = 0, my_m = 0, my_off = 0, my_nd = 0, my_doff = 0, my_boff = 0, my_nbusy = 0;
+    uint32_t my_chunks = 0;
+    int64_t my_backlog = 0;
+    if (lane < nb) {
+      my_gn = list[idx0 + lane];
+      my_type = P.node_type[my_gn]; my_cap = P.node_cap[my_gn]; my_free = P.node_free[my_gn];
+      my_backlog = P.node_backlog[my_gn]; my_chunks = P.node_chunks[my_gn];
+      my_m = W.nl_cnt[my_gn]; my_off = W.nl_off[my_gn]; my_nd = W.dl_cnt[my_gn]; my_doff = W.dl_off[my_gn];
+      if (P.has_busy) { my_boff = P.node_busy_off[my_gn]; my_nbusy = P.node_busy_off[my_gn + 1] - my_boff; }
+    }
+    for (int j = 0; j < nb; ++j) {
+      const int gn = __builtin_amdgcn_readlane(my_gn, j);
+      const int b = gn / P.M;
+      const size_t abase = (size_t)b * P.N;
+      TgNodeIn in;
+      in.type = __builtin_amdgcn_readlane(my_type, j); in.cap = __builtin_amdgcn_readlane(my_cap, j);
+      in.free_units = __builtin_amdgcn_readlane(my_free, j);
+      in.backlog = tg_readlane_i64(my_backlog, j); in.chunks = (uint32_t)__builtin_amdgcn_readlane((int)my_chunks, j);
+      in.m = __builtin_amdgcn_readlane(my_m, j); in.clist = W.order + abase + __builtin_amdgcn_readlane(my_off, j);
+      in.nd = __builtin_amdgcn_readlane(my_nd, j); in.dlist = W.dorder + abase + __builtin_amdgcn_readlane(my_doff, j);
+      in.n_busy = __builtin_amdgcn_readlane(my_nbusy, j);
+      in.busy = P.node_busy_rel + __builtin_amdgcn_readlane(my_boff, j);
+      // the release times are read by every objective evaluation: keep them behind the plan's block
+      tg_wave_sync();                                             // the previous node's readers are done
+      for (int c = lane; c < in.n_busy; c += TG_WAVE) reinterpret_cast<int64_t*>(smem + plan.total)[c] = in.busy[c];
+      in.busy_lds_off = plan.total;
+      in.act_model = P.act_model + abase; in.act_kmask = P.act_kmask + abase; in.dur = dur + abase * P.K;
+      in.K = P.K; in.depth = P.depth;
+      in.kword = tg_pack_k(P.k_list);
+      TgNodeOut out;
+      out.node = O.node + abase; out.units = O.units + abase; out.act = O.act_us + abase; out.reason = O.defer_reason + abase;
+      out.age = P.act_age + abase;
+      int used = 0;
+      const int64_t obj = tg_node_schedule<1>(smem, plan, in, out, lane, 0, &used);
+      if (lane == 0) {
+        if (O.node_obj) O.node_obj[gn] = obj;
+        if (O.node_used) O.node_used[gn] = used;
+      }
     }
   }
 }
@@ -298,7 +309,7 @@ extern "C" int tg_assign(const tg_problem* p, const int64_t* d_cost, const tg_as
   const int busy_lds = ((p->max_heap + 1) & ~1) * 8;              // a node's busy list has at most max_heap entries
   max_lds += busy_lds;
   if (max_lds > 64 * 1024)
-    TG_HIP_CHECK(hipFuncSetAttribute((const void*)tg_node_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds));
+    TG_HIP_CHECK(hipFuncSetAttribute((const void*)tg_node_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds));
 
   const size_t nN = (size_t)P.B * P.M;
   hipLaunchKernelGGL(tg_dur_kernel, dim3((unsigned)((nA * P.K + 255) / 256)), dim3(256), 0, s, P, W.dur, W.class_ctl);
@@ -322,7 +333,7 @@ extern "C" int tg_assign(const tg_problem* p, const int64_t* d_cost, const tg_as
     hipStream_t cs = c < 2 ? p->side_stream[c] : s;
     if (c < 2) TG_HIP_CHECK(hipStreamWaitEvent(cs, p->ev_fork, 0));
     static_assert(kClassWaves[0] == 1 && kClassWaves[1] == 1 && kClassWaves[2] == 1, "only single-wavefront teams are enabled");
-    hipLaunchKernelGGL(tg_node_kernel<1>, dim3(grid), dim3(TG_WAVE), plans[c].total + busy_lds, cs, P, W.dur, W, *out, plans[c], c);
+    hipLaunchKernelGGL(tg_node_kernel, dim3(grid), dim3(TG_WAVE), plans[c].total + busy_lds, cs, P, W.dur, W, *out, plans[c], c);
     if (c < 2) TG_HIP_CHECK(hipEventRecord(p->ev_join[c], cs));
   }
   for (int c = 0; c < 2; ++c) TG_HIP_CHECK(hipStreamWaitEvent(s, p->ev_join[c], 0));
