@@ -94,6 +94,62 @@ def test_assign_wide_times(tg, orc, seed):
     _compare(_assign_gpu(tg, p), orc.assign(p), f"wide {seed}")
 
 
+def _roomy(p, cap, min1_frac, seed):
+    """CPU nodes get `cap` units, all free but the busy ones, and most CPU actions may run on one
+    unit, so that nodes collect long candidate lists instead of closing their pool early."""
+    rng = np.random.default_rng(seed)
+    cpu = p["node_type"] == gen.TYPE_CPU
+    nb = np.zeros(len(cpu), np.int64)
+    if p.get("node_busy_off") is not None:
+        nb = np.diff(p["node_busy_off"])
+        assert nb[cpu].max(initial=0) <= cap, "generate with cpu_cap_hi <= cap"
+    p["node_cap"][cpu] = cap
+    p["node_free"][cpu] = (cap - nb)[cpu]
+    a = (p["act_type"] == gen.TYPE_CPU) & (rng.random(len(p["act_type"])) < min1_frac)
+    p["act_kmask"][a] |= 1
+    return p
+
+
+CODE_PATHS = {
+    # pools of 65..256 nodes: node table in four register slots per lane; tight capacities so
+    # that pinned actions close nodes and unpinned ones close whole pools
+    "pool_150_cpu_70_gpu_nodes": (dict(seed=50, B=2, N=1500, n_cpu=150, n_gpu=70, n_api=3, cpu_cap_hi=6, pin_frac=0.4), (6, 0.97)),
+    # more than 256 nodes of a kind: node table in LDS
+    "pool_300_cpu_nodes": (dict(seed=51, B=1, N=2000, n_cpu=300, n_gpu=0, n_api=0, cpu_cap_hi=5, pin_frac=0.3), (5, 0.97)),
+    # 256 units per node, some busy: four heap slots per lane, 256-wide DP rows, > 128 candidates
+    "cap_256_nodes": (dict(seed=52, B=2, N=700, n_cpu=2, n_gpu=0, n_api=0, cpu_cap_hi=40, k_list=(1, 2, 4, 8, 16)), (256, 0.995)),
+    "cap_200_no_busy": (dict(seed=53, B=2, N=500, n_cpu=1, n_gpu=1, n_api=1, cpu_cap_hi=40, busy=False, k_list=(1, 2, 4, 8, 16)), (200, 0.995)),
+    # the deepest and an odd depth of Alg. 2 (depths run in pairs)
+    "depth_4": (dict(seed=54, B=3, N=150, n_cpu=2, n_gpu=2, n_api=1, cpu_cap_hi=40, depth=4, k_list=(1, 2, 4, 8, 16)), (40, 0.95)),
+    "depth_3": (dict(seed=55, B=3, N=150, n_cpu=3, n_gpu=1, n_api=0, cpu_cap_hi=24, depth=3, k_list=(1, 2, 4, 8, 16)), (24, 0.95)),
+    # eight options (the 32-bit DP is specialised on the option count)
+    "eight_options": (dict(seed=56, B=2, N=200, n_cpu=2, n_gpu=0, n_api=1, cpu_cap_hi=64, k_list=(1, 2, 3, 4, 6, 8, 12, 16)), (64, 0.95)),
+    "three_options": (dict(seed=57, B=2, N=200, n_cpu=3, n_gpu=1, n_api=1, cpu_cap_hi=20, k_list=(1, 2, 4)), (20, 0.95)),
+    # sums of durations between 2^30 and 2^32 us: 64-bit DP totals, 32-bit heap times
+    "dp_totals_beyond_30_bits": (dict(seed=58, B=2, N=160, n_cpu=1, n_gpu=1, n_api=0, cpu_cap_hi=64, t_median=40_000_000), (64, 0.99)),
+    # many waiting actions pinned to a node (more than the wavefront stages in LDS)
+    "long_pinned_queues": (dict(seed=59, B=2, N=900, n_cpu=2, n_gpu=1, n_api=0, cpu_cap_hi=48, pin_frac=0.9), (48, 0.9)),
+}
+
+
+def _code_path_problem(case):
+    kw, (cap, min1) = CODE_PATHS[case]
+    p = _roomy(gen.make_random_problem(**kw), cap, min1, kw["seed"])
+    if kw["n_gpu"] == 0:
+        p["type_k"][gen.TYPE_GPU] = 0        # no GPU kind: its options need not be buddy sizes
+    return p
+
+
+@pytest.mark.parametrize("case", sorted(CODE_PATHS))
+def test_assign_code_paths(tg, orc, case):
+    """Shapes chosen so that every variant of the kernels' inner loops runs at least once."""
+    print("case", case, flush=True)
+    p = _code_path_problem(case)
+    want = orc.assign(p)
+    _compare(_assign_gpu(tg, p), want, case)
+    assert (want["reason"] == 0).any() and (want["reason"] == 1).any(), "the case should select and defer"
+
+
 def test_assign_config1(tg, orc):
     p = gen.make_config(1)
     want = orc.assign(p)
