@@ -33,7 +33,7 @@ struct tg_trace {
   TgTraceDev dev;
   void* d_arena;
   size_t arena_bytes;
-  int max_nodes_of_kind, max_cap_cpu, max_heap, max_chunk_states;
+  int max_nodes_of_kind, max_nodes_kind[3], max_cap_cpu, max_heap, max_chunk_states;
 };
 
 namespace {
@@ -151,8 +151,16 @@ __device__ inline int compact_stable(int32_t* list, int n, Keep keep, int* s_wav
   return out;
 }
 
-__global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, ReplayWs W, tg_replay_out O, int pool_nodes,
-                                                             TgNodeLdsPlan plan, int busy_slots) {
+struct ReplayLds {
+  int pool_nodes[3];   // node-table capacity of each kind's placement block
+  int pool_off[3];     // byte offsets of those blocks
+  int node_off;        // first per-node block
+  int node_waves;      // wavefronts that own a per-node block (DPArrange + eviction): 4, 2 or 1
+  int busy_slots;
+};
+
+__global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, ReplayWs W, tg_replay_out O, ReplayLds LD,
+                                                             TgNodeLdsPlan plan) {
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int s_wcnt[3], s_next, s_started, s_nrun, s_wave_cnt[kWaves], s_hist[256], s_sel[2];
   __shared__ long long s_sum;
@@ -160,9 +168,7 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
   const int A = T.A, M = T.M, K = T.K;
   const size_t abase = (size_t)s * A, nbase = (size_t)s * M;
 
-  const size_t pool_bytes = (tg_pool_lds_bytes(pool_nodes) + 15) & ~size_t(15);
-  unsigned char* pool_mem = smem + (size_t)(wave < 3 ? wave : 0) * pool_bytes;
-  unsigned char* node_mem = smem + 3 * pool_bytes + (size_t)wave * (size_t)(plan.total + busy_slots * 8);
+  unsigned char* node_mem = smem + LD.node_off + (size_t)(wave < LD.node_waves ? wave : 0) * (size_t)(plan.total + LD.busy_slots * 8);
   int64_t* s_busy = reinterpret_cast<int64_t*>(node_mem + plan.total);
 
   const int64_t* arrival = T.arrival + abase;
@@ -237,22 +243,38 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
       if (tid == 0) s_nrun = out;
     }
     // (2) quota refill for the ticks since the last step (saturating, so idle ticks compose)
-    if (dticks > 0)
-      for (int j = tid; j < M; j += kThreads)
-        if (T.node_type[nbase + j] == TG_TYPE_API) {
-          const int64_t capu = (int64_t)T.node_cap[nbase + j] * 1000000, inc = (int64_t)T.quota_rate[nbase + j] * T.tick_us;
-          int64_t tok = live_tok[j];
-          if (inc > 0) {
-            const int64_t need = capu - tok;
-            tok = (need <= 0 || (int64_t)dticks >= (need + inc - 1) / inc) ? (tok > capu ? tok : capu) : tok + dticks * inc;
-          }
-          live_tok[j] = tok;
+    if (dticks > 0) {
+      const int q0 = T.tnode_off[s * 4 + TG_TYPE_API], nq = T.tnode_off[s * 4 + TG_TYPE_API + 1] - q0;
+      for (int r = tid; r < nq; r += kThreads) {
+        const int j = T.tnode_idx[nbase + q0 + r];
+        const int64_t capu = (int64_t)T.node_cap[nbase + j] * 1000000, inc = (int64_t)T.quota_rate[nbase + j] * T.tick_us;
+        int64_t tok = live_tok[j];
+        if (inc > 0) {
+          const int64_t need = capu - tok;
+          tok = (need <= 0 || (int64_t)dticks >= (need + inc - 1) / inc) ? (tok > capu ? tok : capu) : tok + dticks * inc;
         }
+        live_tok[j] = tok;
+      }
+    }
     // (3) arrivals join their kind's waiting list in arrival order
-    if (tid == 0) {
+    if (wave == 0) {                                              // 64 trace entries per pass; arrivals ascend
       int nx = s_next;
-      while (nx < A && arrival[nx] <= now) { const int ty = act_type[nx]; wl[ty][s_wcnt[ty]++] = nx; ++nx; }
-      s_next = nx;
+      int wc[3] = {s_wcnt[0], s_wcnt[1], s_wcnt[2]};
+      for (;;) {
+        const int x = nx + lane;
+        const bool due = x < A && arrival[x] <= now;
+        const int ty = due ? act_type[x] : -1;
+        const uint64_t bal = __ballot(due);
+#pragma unroll
+        for (int t = 0; t < 3; ++t) {
+          const uint64_t tb = __ballot(ty == t);
+          if (ty == t) wl[t][wc[t] + __popcll(tb & ((1ull << lane) - 1ull))] = x;
+          wc[t] += __popcll(tb);
+        }
+        nx += __popcll(bal);
+        if (bal != ~0ull) break;
+      }
+      if (lane == 0) { s_next = nx; s_wcnt[0] = wc[0]; s_wcnt[1] = wc[1]; s_wcnt[2] = wc[2]; }
     }
     __threadfence_block();
     __syncthreads();
@@ -265,7 +287,7 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
       const int n0 = T.tnode_off[s * 4 + ty], Mt = T.tnode_off[s * 4 + ty + 1] - n0;
       const int32_t* nodes = T.tnode_idx + nbase + n0;
       TgPoolLds S;
-      tg_pool_lds_carve(pool_mem, pool_nodes, &S);
+      tg_pool_lds_carve(smem + LD.pool_off[ty], LD.pool_nodes[ty], &S);
       if (lane < TG_MAX_K) S.k[lane] = T.k_list[lane];
       for (int r = lane; r < Mt; r += TG_WAVE) {
         const int j = nodes[r];
@@ -296,9 +318,17 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
     __threadfence_block();
     __syncthreads();
     // (4c) per node: DPArrange + greedy eviction; the running actions of the node seed the heap
-    for (int j = wave; j < M; j += kWaves) {
-      const int m = nl_cnt[j];
-      if (m == 0) continue;
+    int n_seen = 0;                                               // nodes with candidates met so far
+    for (int jb = 0; jb < M; jb += TG_WAVE) {
+     // every wavefront looks at the same 64 list lengths and takes every kWaves-th node that has candidates
+     const int my_m = jb + lane < M ? nl_cnt[jb + lane] : 0;
+     uint64_t todo = __ballot(my_m > 0);
+     while (todo) {
+      const int jl = __ffsll((unsigned long long)todo) - 1;
+      todo &= todo - 1;
+      if ((n_seen++ & (LD.node_waves - 1)) != wave) continue;     // wavefronts without a block take none
+      const int j = jb + jl;
+      const int m = __builtin_amdgcn_readlane(my_m, jl);
       const int ty = T.node_type[nbase + j];
       int nb = 0;
       if (ty != TG_TYPE_API) {
@@ -328,6 +358,7 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
       out.node = o_node; out.units = o_units; out.act = nullptr; out.reason = reason; out.age = nullptr;
       int used_units;
       tg_node_schedule<1>(node_mem, plan, in, out, lane, 0, &used_units);
+     }
     }
     __threadfence_block();
     __syncthreads();
@@ -466,6 +497,7 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
     const size_t o_speed = add(std::max<size_t>((size_t)d->n_classes * K, 1) * 4);
     auto at = [&](size_t off) { return host.data() + off; };
     int max_kind = 0, max_cap_cpu = 0, max_heap = 0;
+    int max_of_kind[3] = {0, 0, 0};
     std::vector<int> max_cap((size_t)S * 3, -1);
     for (int s = 0; s < S; ++s) {
       int cnt[3] = {0, 0, 0};
@@ -494,7 +526,7 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
       off[0] = 0; off[1] = cnt[0]; off[2] = cnt[0] + cnt[1]; off[3] = M;
       int fill[3] = {off[0], off[1], off[2]};
       for (int j = 0; j < M; ++j) ((int32_t*)at(o_tnidx))[(size_t)s * M + fill[d->node_type[(size_t)s * M + j]]++] = j;
-      for (int k = 0; k < 3; ++k) max_kind = std::max(max_kind, cnt[k]);
+      for (int k = 0; k < 3; ++k) { max_kind = std::max(max_kind, cnt[k]); max_of_kind[k] = std::max(max_of_kind[k], cnt[k]); }
       if (max_kind > TG_MAX_NODES_OF_KIND) { delete t; return TG_E_RANGE; }
       int64_t sumT = 0, prev = 0;
       for (int i = 0; i < A; ++i) {
@@ -557,6 +589,7 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
     v.act_param = (const uint32_t*)(base + o_aparam); v.act_pin = (const int32_t*)(base + o_apin);
     v.speedup = (const uint32_t*)(base + o_speed);
     t->max_nodes_of_kind = max_kind; t->max_cap_cpu = max_cap_cpu; t->max_heap = max_heap;
+    for (int k = 0; k < 3; ++k) t->max_nodes_kind[k] = max_of_kind[k];
     t->max_chunk_states = 60;   // an 8-GPU node never has more than 4,2,1,1 free chunks of size 1,2,4,8
   } catch (const std::bad_alloc&) {
     delete t;
@@ -588,13 +621,27 @@ extern "C" int tg_replay_trace(const tg_trace* t, const tg_replay_out* out, void
   ReplayWs W;
   carve(T, (char*)d_ws, &W);
   const TgNodeLdsPlan plan = tg_node_lds_plan(t->max_cap_cpu, 8, t->max_chunk_states, t->max_heap, T.K, 1 << 30, 8, 1, TG_WAVE);
-  const int busy_slots = (t->max_heap + 1 + 1) & ~1;
-  const size_t pool_bytes = (tg_pool_lds_bytes(t->max_nodes_of_kind) + 15) & ~size_t(15);
-  const size_t lds = 3 * pool_bytes + (size_t)kWaves * ((size_t)plan.total + (size_t)busy_slots * 8);
+  // LDS of a workgroup: one placement block per kind, then one per-node block for each wavefront
+  // that runs DPArrange.  Two workgroups fit a CU when the total stays under half of its LDS, so
+  // large clusters give per-node blocks to fewer wavefronts rather than lose the second workgroup.
+  ReplayLds LD;
+  LD.busy_slots = (t->max_heap + 1 + 1) & ~1;
+  size_t off = 0;
+  for (int k = 0; k < 3; ++k) {
+    LD.pool_nodes[k] = std::max(t->max_nodes_kind[k], 1);
+    LD.pool_off[k] = (int)off;
+    off += (tg_pool_lds_bytes(LD.pool_nodes[k]) + 15) & ~size_t(15);
+  }
+  LD.node_off = (int)off;
+  const size_t node_bytes = (size_t)plan.total + (size_t)LD.busy_slots * 8;
+  const size_t half_cu = 80 * 1024 - 2048;                      // the kernel also has ~1.3 KB of static LDS
+  LD.node_waves = kWaves;
+  while (LD.node_waves > 1 && off + LD.node_waves * node_bytes > half_cu) LD.node_waves >>= 1;
+  const size_t lds = off + LD.node_waves * node_bytes;
   if (lds > 160 * 1024 - 2048) return TG_E_RANGE;
   TG_HIP_CHECK(hipFuncSetAttribute((const void*)tg_replay_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   const size_t total = (size_t)T.S * T.A * T.K;
   hipLaunchKernelGGL(tg_trace_dur_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, T, W.dur);
-  hipLaunchKernelGGL(tg_replay_kernel, dim3(T.S), dim3(kThreads), lds, s, T, W, *out, t->max_nodes_of_kind, plan, busy_slots);
+  hipLaunchKernelGGL(tg_replay_kernel, dim3(T.S), dim3(kThreads), lds, s, T, W, *out, LD, plan);
   return hipGetLastError() == hipSuccess ? TG_OK : TG_E_HIP;
 }
