@@ -45,7 +45,7 @@ def brute():
 
 
 class Problem(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("B", "N", "M", "K", "n_classes", "n_tasks", "depth", "pad_")] + [
+    _fields_ = [(n, C.c_int32) for n in ("B", "N", "M", "K", "n_classes", "n_tasks", "depth", "order_policy")] + [
         (n, C.c_void_p) for n in (
             "k_list", "type_k", "speedup_q16", "node_type", "node_cap", "node_free", "node_backlog_us",
             "node_chunks", "node_busy_off", "node_busy_rel_us", "act_type", "act_model", "act_t_ori_us",
@@ -126,6 +126,7 @@ def _problem(p):
     s = Problem()
     for n in ("B", "N", "M", "K", "n_classes", "n_tasks", "depth"):
         setattr(s, n, int(p[n]))
+    s.order_policy = int(p.get("order_policy", 0))      # 0: first come first served, 1: least estimated ACT first
     _fill(s, p, [f[0] for f in Problem._fields_[8:]], keep)
     return s, keep
 

@@ -224,8 +224,14 @@ struct StepOut {
   std::vector<int32_t> home;                          // node an action was admitted to (kept when evicted)
 };
 
+// Order in which a pool's waiting queue is visited (Sec. 4.2: FCFS in the paper, and the
+// algorithm "can work with other ordering algorithms").  ORDER_COST is one such other order:
+// ascending least estimated ACT (Eq. 2) over the action's candidates at the snapshot, i.e. the
+// smallest entry of its row of the score tensor; equal keys keep their FCFS rank.
+enum { ORDER_FCFS = 0, ORDER_COST = 1 };
+
 // ---- one scheduling step on one snapshot (Alg. 1 applied per resource pool) -------------
-StepOut step(const Tables& tb, const std::vector<Act>& acts, std::vector<Node> nodes) {
+StepOut step(const Tables& tb, const std::vector<Act>& acts, std::vector<Node> nodes, int order_policy = ORDER_FCFS) {
   const int N = (int)acts.size(), M = (int)nodes.size(), K = tb.K;
   StepOut o;
   o.node.assign(N, -1); o.units.assign(N, 0); o.act.assign(N, -1); o.reason.assign(N, R_NONE);
@@ -248,7 +254,22 @@ StepOut step(const Tables& tb, const std::vector<Act>& acts, std::vector<Node> n
     if (!ok) o.reason[i] = R_INFEASIBLE;
   }
 
-  // Alg. 1 l.1-2: FCFS prefix admitted with minimum units; node choice by least estimated ACT
+  std::vector<int> visit(N);
+  for (int i = 0; i < N; ++i) visit[i] = i;
+  if (order_policy == ORDER_COST) {
+    std::vector<int64_t> key(N, INF);
+    for (int i = 0; i < N; ++i) {
+      if (o.reason[i] == R_INFEASIBLE) continue;
+      const Act& a = acts[i];
+      for (int j = 0; j < M; ++j) {
+        if (nodes[j].type != a.type || (a.pin >= 0 && a.pin != j)) continue;
+        for (int q : options_on(tb, a, nodes[j])) key[i] = std::min(key[i], nodes[j].backlog + duration(tb, a, q));
+      }
+    }
+    std::stable_sort(visit.begin(), visit.end(), [&](int x, int y) { return key[x] < key[y]; });
+  }
+
+  // Alg. 1 l.1-2: prefix of the visiting order admitted with minimum units; node choice by least estimated ACT
   std::vector<int> rem(M);
   std::vector<std::vector<int>> placed(M), waiting_pinned(M);
   std::vector<char> closed(M, 0);
@@ -258,7 +279,7 @@ StepOut step(const Tables& tb, const std::vector<Act>& acts, std::vector<Node> n
   auto fits = [&](int j, int k) {
     return nodes[j].type == T_GPU ? chunk_fits(&ch[j*4], k) : rem[j] >= k;
   };
-  for (int i = 0; i < N; ++i) {
+  for (int i : visit) {
     if (o.reason[i] == R_INFEASIBLE) continue;
     const Act& a = acts[i];
     if (type_closed[a.type] || (a.pin >= 0 && closed[a.pin])) {
@@ -355,7 +376,7 @@ StepOut step(const Tables& tb, const std::vector<Act>& acts, std::vector<Node> n
 extern "C" {
 
 struct orc_problem {
-  int32_t B, N, M, K, n_classes, n_tasks, depth, pad_;
+  int32_t B, N, M, K, n_classes, n_tasks, depth, order_policy;
   const int32_t* k_list; const int32_t* type_k; const uint32_t* speedup_q16;
   const uint8_t* node_type; const int32_t* node_cap; const int32_t* node_free;
   const int64_t* node_backlog_us; const uint8_t* node_chunks;
@@ -467,7 +488,7 @@ void orc_assign(const orc_problem* p, int32_t* node, int32_t* units, int64_t* ac
   for (int b = 0; b < p->B; ++b) {
     const std::vector<Act> acts = acts_of(p, b);
     const std::vector<Node> nodes = nodes_of(p, b);
-    const StepOut o = step(tb, acts, nodes);
+    const StepOut o = step(tb, acts, nodes, p->order_policy);
     const size_t a0 = (size_t)b * p->N, n0 = (size_t)b * p->M;
     orc_summary s;
     std::memset(&s, 0, sizeof s);
