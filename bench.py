@@ -29,6 +29,29 @@ HBM_PEAK_GBS = 8000.0
 SCORE_TRAFFIC_CONFIG2_BYTES = int((537696.2 + 2.0 * 5642.6) * 1024)
 
 
+def order_section(a, tg, torch, p, s_fcfs):
+    """The same workload scheduled in the second visiting order (least estimated ACT first instead of first come
+    first served): time of tg_assign, and what the order does to the selected set."""
+    P = tg.Problem(dict(p, order_policy=1))
+    bufs = P.alloc_assign()
+    for _ in range(3):
+        P.assign(None, bufs)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n = max(5, a.steps // 5)
+    e0.record()
+    for _ in range(n):
+        P.assign(None, bufs)
+    e1.record()
+    torch.cuda.synchronize()
+    s = tg.summary_to_numpy(bufs["summary"])
+    P.free()
+    sel_f, sel_c = int(s_fcfs["n_selected"].sum()), int(s["n_selected"].sum())
+    return {"assign_ms": e0.elapsed_time(e1) / n,
+            "selected": {"fcfs": sel_f, "cost": sel_c},
+            "mean_act_us_of_selected": {"fcfs": float(s_fcfs["sum_act_us"].sum()) / max(sel_f, 1),
+                                        "cost": float(s["sum_act_us"].sum()) / max(sel_c, 1)}}
+
+
 def replay_section(a, tg, gen, torch):
     """Workload 5 (batched trace replay): S scenarios x 10 000 Poisson arrivals over 200 s, rescheduling every
     100 ms, on the default cluster (256x128 cores, 32x8 GPUs, 16 quotas) and on the contended one (4x32 cores,
@@ -166,6 +189,8 @@ def main():
                      "kernel": "tg_score_kernel", "bytes_per_launch": 8 * n_cand, "avg_kernel_ms": score_ms},
     }
 
+    if a.only == "step":
+        out["order_policy_cost"] = order_section(a, tg, torch, p, s)
     if a.replay_scenarios > 0 and a.only == "step":
         out["replay"] = replay_section(a, tg, gen, torch)
 

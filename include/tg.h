@@ -50,11 +50,19 @@ enum { TG_SELECTED = 0,
        TG_DEFER_EVICTED = 2,    /* admitted, then evicted by the greedy tail eviction (Alg. 1 l.9-13) */
        TG_DEFER_INFEASIBLE = 3  /* no allowed unit count fits any node it may use, or bad pin        */ };
 
+/* Order in which tg_assign visits the waiting queue of a pool.  The paper schedules first come
+ * first served and notes that its algorithm works with other orderings (Sec. 4.2); TG_ORDER_COST
+ * is one: ascending least estimated ACT (Eq. 2) over the action's candidates - the smallest
+ * finite entry of its row of the score tensor -, equal keys in FCFS order.  The admitted
+ * prefix, the per-node candidate lists and the eviction tail of Alg. 1 all follow that order. */
+enum { TG_ORDER_FCFS = 0, TG_ORDER_COST = 1 };
+
 /* limits checked by tg_build_problem / tg_build_trace */
 enum { TG_MAX_K = 8, TG_MAX_UNIT = 64, TG_MAX_CPU_UNITS = 256, TG_MAX_GPU_UNITS = 64,
        TG_MAX_CHUNK_STATES = 512, TG_MAX_DEPTH = 4,
        TG_MAX_ACTIONS = 131072,      /* N, actions per snapshot / A, actions per scenario          */
-       TG_MAX_NODES_OF_KIND = 4096   /* nodes of one resource kind in one snapshot               */ };
+       TG_MAX_NODES_OF_KIND = 4096,  /* nodes of one resource kind in one snapshot               */
+       TG_MAX_SORTED_POOL = 8192     /* TG_ORDER_COST: actions of one kind in one snapshot       */ };
 #define TG_T_ORI_LIMIT (1ll << 36)  /* 1 <= T_ori < 2^36 us                                      */
 #define TG_TIME_LIMIT (1ll << 40)   /* backlog, age, busy release times in [0, 2^40)              */
 #define TG_SUM_T_LIMIT (1ll << 44)  /* sum of T_ori over one snapshot / scenario                  */
@@ -72,7 +80,7 @@ typedef struct {
   int32_t n_classes; /* rows of speedup_q16                                                     */
   int32_t n_tasks;   /* act_task values are in [0, n_tasks); segment key of the per-task sums    */
   int32_t depth;     /* options tried for the first waiting action in Alg. 2's estimate; 2 in the paper's runs */
-  uint32_t flags;    /* must be 0                                                                */
+  int32_t order_policy; /* TG_ORDER_FCFS (0) or TG_ORDER_COST; the latter needs every pool <= TG_MAX_SORTED_POOL actions, else TG_E_RANGE */
   const int32_t *k_list;  /* [K] ascending unit counts (the discrete sets of Sec. 4.1), 1..TG_MAX_UNIT */
   const int32_t *type_k;  /* [3] type t may use k_list[0 .. type_k[t]); GPU entries must be 1,2,4,8; API <= 1 */
   const uint32_t *speedup_q16; /* [n_classes*K] round(65536*E(k_q)*k_q); nondecreasing in q, in [65536, 65536*k_q] */
@@ -145,12 +153,14 @@ int tg_assign_workspace_bytes(const tg_problem *p, size_t *bytes);
 int tg_score_candidates(const tg_problem *p, int64_t *d_cost, void *hip_stream);
 
 /*
- * Assign (Alg. 1 per resource pool): FCFS admission at minimum units with node choice by least
+ * Assign (Alg. 1 per resource pool): admission in visiting order (FCFS unless the problem was
+ * built with TG_ORDER_COST) at minimum units with node choice by least
  * estimated completion time (ties: smaller node index), then per node DPArrange (Alg. 3; Alg. 4's
  * chunk states on GPU nodes) inside the greedy tail eviction on the approximated objective
  * (Alg. 2), then per-snapshot summaries.
  * d_cost: NULL, or a tensor written by tg_score_candidates for this problem; when given, the
- * node choice reads its estimates from the tensor instead of recomputing them (same result).
+ * node choice reads its estimates from the tensor instead of recomputing them (same result);
+ * with TG_ORDER_COST the estimates are always recomputed (the tensor's rows are in FCFS order).
  * d_ws/ws_bytes: device workspace of at least tg_assign_workspace_bytes(), 256-byte aligned.
  * Errors: TG_E_INVALID_ARG, TG_E_WORKSPACE, TG_E_HIP.
  */

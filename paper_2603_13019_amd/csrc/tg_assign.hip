@@ -25,6 +25,7 @@ struct AssignWs {
   int32_t *nl_off, *nl_cnt, *dl_off, *dl_cnt;   // [B*M] list extents per node
   int32_t* class_list;   // [kClasses][B*M] nodes with candidates, binned by how many
   int32_t* class_ctl;    // [2*kClasses] per class: number of nodes, next node to hand out
+  int32_t* visit;        // [B*N] TG_ORDER_COST: action ids grouped by kind in visiting order (else unused)
 };
 
 // Nodes are processed in classes of candidate count so that the LDS a wavefront needs (the
@@ -51,8 +52,9 @@ size_t carve(const tg_problem* p, char* base, AssignWs* w) {
   char* a = take(nA * p->dev.K * 8); char* b = take(nA * 4); char* c = take(nA * 4); char* d = take(nA * 4);
   char* e = take(nN * 4); char* f = take(nN * 4); char* g = take(nN * 4); char* h = take(nN * 4);
   char* cl = take(nN * 4 * kClasses); char* cc = take(2 * kClasses * 4);
+  char* vi = take(p->order_policy == TG_ORDER_COST ? nA * 4 : 0);
   if (w) {
-    w->class_list = (int32_t*)cl; w->class_ctl = (int32_t*)cc;
+    w->class_list = (int32_t*)cl; w->class_ctl = (int32_t*)cc; w->visit = (int32_t*)vi;
     w->dur = (int64_t*)a; w->slot = (int32_t*)b; w->order = (int32_t*)c; w->dorder = (int32_t*)d;
     w->nl_off = (int32_t*)e; w->nl_cnt = (int32_t*)f; w->dl_off = (int32_t*)g; w->dl_cnt = (int32_t*)h;
   }
@@ -78,10 +80,88 @@ __global__ __launch_bounds__(256) void tg_dur_kernel(TgDev P, int64_t* __restric
 }
 
 // ------------------------------------------------------------------------------------------
+// TG_ORDER_COST: the visiting order of one pool = its actions sorted by (least estimated ACT
+// over the action's candidates, FCFS rank).  Durations do not grow with the units (Eq. 1 with
+// E(k) k nondecreasing), so on a node the best option is the largest allowed one its capacity
+// admits, and nodes that admit the same number of options differ only in their backlog: the key
+// of an unpinned action is a minimum over at most K+1 groups of nodes, each represented by its
+// smallest backlog.  Keys and ranks are packed into one 64-bit word (key < 2^46, rank < 2^17)
+// and sorted by a bitonic network in LDS; one workgroup per (snapshot, kind).
+constexpr int kOrderThreads = 256;
+constexpr uint64_t kOrderKeyInf = (1ull << 46) - 1;
+
+__global__ __launch_bounds__(kOrderThreads) void tg_order_kernel(TgDev P, const int64_t* __restrict__ dur, const TgBlock* __restrict__ blocks,
+                                                                 int32_t* __restrict__ visit, int n_pad_max) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  uint64_t* s_key = reinterpret_cast<uint64_t*>(smem);                       // [n_pad]
+  __shared__ unsigned long long s_minback[TG_MAX_K + 1];                       // by number of options the capacity admits
+  const int b = blockIdx.x / 3, t = blockIdx.x - 3 * b, tid = threadIdx.x;
+  const int a0 = P.tact_off[b * 4 + t], Nt = P.tact_off[b * 4 + t + 1] - a0;
+  const int n0 = P.tnode_off[b * 4 + t], Mt = P.tnode_off[b * 4 + t + 1] - n0;
+  if (Nt == 0) return;
+  const size_t abase = (size_t)b * P.N, nbase = (size_t)b * P.M;
+  const int32_t* acts = P.tact_idx + abase + a0;
+  const TgBlock blk = blocks[b * 3 + t];
+  const uint64_t* words = P.node_word + blk.n_off;                            // backlog | options admitted << 48, rank order
+  if (tid <= TG_MAX_K) s_minback[tid] = ~0ull;
+  __syncthreads();
+  for (int r = tid; r < Mt; r += kOrderThreads) {
+    const uint64_t nw = words[r];
+    atomicMin(&s_minback[nw >> 48], (unsigned long long)(nw & 0xffffffffffffull));
+  }
+  __syncthreads();
+  int n_pad = 1;
+  while (n_pad < Nt) n_pad <<= 1;
+  const int Kt = P.type_k[t];
+  for (int x = tid; x < n_pad; x += kOrderThreads) {
+    uint64_t key = ~0ull;                                                     // padding sorts behind everything
+    if (x < Nt) {
+      const int id = acts[x];
+      const size_t g = abase + id;
+      uint64_t best = kOrderKeyInf;
+      if (!P.act_static[g]) {
+        const uint32_t mask = P.act_kmask[g];
+        const int64_t* drow = dur + g * P.K;
+        const int pin = P.act_pin[g];
+        if (pin >= 0) {
+          const uint64_t nw = words[P.node_rank[nbase + pin]];
+          const uint32_t ok = mask & ((1u << (nw >> 48)) - 1u);
+          if (ok) best = (nw & 0xffffffffffffull) + (uint64_t)drow[31 - __builtin_clz(ok)];
+        } else {
+          for (int c = 1; c <= Kt; ++c) {                                     // nodes whose capacity admits options 0..c-1
+            const uint64_t mb = s_minback[c];
+            const uint32_t ok = mask & ((1u << c) - 1u);
+            if (mb == ~0ull || ok == 0) continue;
+            const uint64_t e = mb + (uint64_t)drow[31 - __builtin_clz(ok)];
+            best = e < best ? e : best;
+          }
+        }
+      }
+      key = best << 17 | (uint32_t)x;
+    }
+    s_key[x] = key;
+  }
+  __syncthreads();
+  for (int k = 2; k <= n_pad; k <<= 1)
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int x = tid; x < n_pad; x += kOrderThreads) {
+        const int y = x ^ j;
+        if (y > x) {
+          const uint64_t a = s_key[x], c = s_key[y];
+          const bool up = (x & k) == 0;
+          if ((a > c) == up) { s_key[x] = c; s_key[y] = a; }
+        }
+      }
+      __syncthreads();
+    }
+  for (int x = tid; x < Nt; x += kOrderThreads) visit[abase + a0 + x] = acts[(int)(s_key[x] & 0x1ffff)];
+}
+
+// ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(TG_WAVE) void tg_place_kernel(TgDev P, const int64_t* __restrict__ dur,
                                                            const int64_t* __restrict__ cost,
                                                            const TgBlock* __restrict__ blocks, AssignWs W,
-                                                           tg_assign_out O, int lds_nodes) {
+                                                           tg_assign_out O, int lds_nodes, const int32_t* __restrict__ visit) {
   extern __shared__ __align__(16) unsigned char smem[];
   TgPoolLds S;
   tg_pool_lds_carve(smem, lds_nodes, &S);
@@ -89,7 +169,7 @@ __global__ __launch_bounds__(TG_WAVE) void tg_place_kernel(TgDev P, const int64_
   const int a0 = P.tact_off[b * 4 + t], Nt = P.tact_off[b * 4 + t + 1] - a0;
   const int n0 = P.tnode_off[b * 4 + t], Mt = P.tnode_off[b * 4 + t + 1] - n0;
   const size_t abase = (size_t)b * P.N, nbase = (size_t)b * P.M;
-  const int32_t* acts = P.tact_idx + abase + a0;
+  const int32_t* acts = (visit ? visit : P.tact_idx) + abase + a0;   // visiting order of the pool
   const int32_t* nodes = P.tnode_idx + nbase + n0;
   if (lane < TG_MAX_K) S.k[lane] = P.k_list[lane];
   for (int r = lane; r < Mt; r += TG_WAVE) {
@@ -313,8 +393,19 @@ extern "C" int tg_assign(const tg_problem* p, const int64_t* d_cost, const tg_as
 
   const size_t nN = (size_t)P.B * P.M;
   hipLaunchKernelGGL(tg_dur_kernel, dim3((unsigned)((nA * P.K + 255) / 256)), dim3(256), 0, s, P, W.dur, W.class_ctl);
-  hipLaunchKernelGGL(tg_place_kernel, dim3(P.B * 3), dim3(TG_WAVE), place_lds, s, P, W.dur, d_cost, p->d_blocks, W, *out,
-                     p->max_nodes_of_kind);
+  const int32_t* visit = nullptr;
+  if (p->order_policy == TG_ORDER_COST) {
+    int n_pad = 1;
+    while (n_pad < p->max_actions_of_kind) n_pad <<= 1;
+    const size_t order_lds = (size_t)n_pad * 8;
+    if (order_lds > 48 * 1024)
+      TG_HIP_CHECK(hipFuncSetAttribute((const void*)tg_order_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)order_lds));
+    hipLaunchKernelGGL(tg_order_kernel, dim3(P.B * 3), dim3(kOrderThreads), order_lds, s, P, W.dur, p->d_blocks, W.visit, n_pad);
+    visit = W.visit;
+  }
+  // the rows of the score tensor are in FCFS order: another visiting order recomputes Eq. 2 instead
+  hipLaunchKernelGGL(tg_place_kernel, dim3(P.B * 3), dim3(TG_WAVE), place_lds, s, P, W.dur, visit ? nullptr : d_cost, p->d_blocks,
+                     W, *out, p->max_nodes_of_kind, visit);
   hipLaunchKernelGGL(tg_lists_kernel, dim3((unsigned)((nA + nN + 255) / 256)), dim3(256), 0, s, P, W, *out);
   // Persistent wavefronts pull nodes of their class and, when it is exhausted, of the lighter
   // classes.  The classes are independent and each is bound by the latency of its own

@@ -71,7 +71,8 @@ extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_p
   if (!d || !out) return TG_E_INVALID_ARG;
   *out = nullptr;
   const int B = d->B, N = d->N, M = d->M, K = d->K;
-  if (B < 1 || N < 1 || M < 1 || d->flags != 0 || d->n_tasks < 1) return TG_E_INVALID_ARG;
+  if (B < 1 || N < 1 || M < 1 || d->n_tasks < 1) return TG_E_INVALID_ARG;
+  if (d->order_policy != TG_ORDER_FCFS && d->order_policy != TG_ORDER_COST) return TG_E_INVALID_ARG;
   if (d->depth < 1 || d->depth > TG_MAX_DEPTH) return TG_E_INVALID_ARG;
   if ((int64_t)B * N >= (1ll << 31) || (int64_t)B * M >= (1ll << 31) || N > TG_MAX_ACTIONS) return TG_E_RANGE;
   int rc = check_tables(K, d->n_classes, d->k_list, d->type_k, d->speedup_q16);
@@ -150,6 +151,7 @@ extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_p
     if (n_busy) std::memcpy(ar.at<int64_t>(o_nbrel), d->node_busy_rel_us, n_busy * 8);
 
     // ---------------- actions
+    int max_acts_kind = 0;
     const size_t o_atype = ar.add(nA), o_amodel = ar.add(nA), o_astat = ar.add(nA), o_aT = ar.add(nA * 8),
                  o_aage = ar.add(nA * 8), o_amask = ar.add(nA * 4), o_aparam = ar.add(nA * 4), o_apin = ar.add(nA * 4),
                  o_atask = ar.add(nA * 4), o_taidx = ar.add(nA * 4), o_taoff = ar.add((size_t)B * 4 * 4);
@@ -192,6 +194,8 @@ extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_p
         ++cnt[t];
       }
       if (sumT >= TG_SUM_T_LIMIT) { delete p; return TG_E_RANGE; }
+      for (int t = 0; t < 3; ++t) max_acts_kind = std::max(max_acts_kind, cnt[t]);
+      if (d->order_policy == TG_ORDER_COST && max_acts_kind > TG_MAX_SORTED_POOL) { delete p; return TG_E_RANGE; }
       int32_t* off = ar.at<int32_t>(o_taoff) + (size_t)b * 4;
       off[0] = 0; off[1] = cnt[0]; off[2] = cnt[0] + cnt[1]; off[3] = N;
       int fill[3] = {off[0], off[1], off[2]};
@@ -297,6 +301,7 @@ extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_p
     p->score_wgs = (int)wgs;
     p->n_candidates = total;
     p->max_nodes_of_kind = max_kind;
+    p->order_policy = d->order_policy; p->max_actions_of_kind = max_acts_kind;
     p->max_free_cpu = max_free_cpu;
     p->max_heap = max_heap;
     p->nodes_free_gt16 = free_gt16; p->nodes_free_gt64 = free_gt64;

@@ -79,6 +79,8 @@ struct tg_problem {
   // from and joined back into the caller's stream with events
   hipStream_t side_stream[2];
   hipEvent_t ev_fork, ev_join[2];
+  int order_policy;        // TG_ORDER_*
+  int max_actions_of_kind; // largest N_t over all snapshots and kinds
   int max_nodes_of_kind;   // largest M_t over all snapshots and kinds
   int max_free_cpu;        // largest node_free over CPU nodes
   int max_heap;            // largest free + busy over CPU and GPU nodes

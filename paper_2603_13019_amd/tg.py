@@ -27,7 +27,7 @@ class TgError(RuntimeError):
 
 class ProblemDesc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("B", "N", "M", "K", "n_classes", "n_tasks", "depth")] + [
-        ("flags", C.c_uint32)] + [(n, C.c_void_p) for n in (
+        ("order_policy", C.c_int32)] + [(n, C.c_void_p) for n in (
             "k_list", "type_k", "speedup_q16", "node_type", "node_cap", "node_free", "node_backlog_us",
             "node_chunks", "node_busy_off", "node_busy_rel_us", "act_type", "act_model", "act_t_ori_us",
             "act_age_us", "act_kmask", "act_param", "act_pin_node", "act_task")]
@@ -133,7 +133,7 @@ class Problem:
         d = ProblemDesc()
         for n in ("B", "N", "M", "K", "n_classes", "n_tasks", "depth"):
             setattr(d, n, int(p[n]))
-        d.flags = int(p.get("flags", 0))
+        d.order_policy = int(p.get("order_policy", 0))
         keep = []
         _fill(d, p, [f[0] for f in ProblemDesc._fields_[8:]], keep)
         h = C.c_void_p()

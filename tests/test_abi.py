@@ -48,7 +48,7 @@ def _build_rc(tg, p):
     d = tg.ProblemDesc()
     for n in ("B", "N", "M", "K", "n_classes", "n_tasks", "depth"):
         setattr(d, n, int(p[n]))
-    d.flags = int(p.get("flags", 0))
+    d.order_policy = int(p.get("order_policy", 0))
     keep = []
     tg._fill(d, p, [f[0] for f in tg.ProblemDesc._fields_[8:]], keep)
     h = C.c_void_p()
@@ -60,7 +60,7 @@ def _build_rc(tg, p):
 BAD = {
     "k_list_not_ascending": (lambda p: p["k_list"].__setitem__(1, 1), -1),
     "unit_above_limit": (lambda p: p["k_list"].__setitem__(3, 65), -1),
-    "flags": (lambda p: p.__setitem__("flags", 1), -1),
+    "order_policy": (lambda p: p.__setitem__("order_policy", 2), -1),
     "depth": (lambda p: p.__setitem__("depth", 9), -1),
     "free_above_cap": (lambda p: p["node_free"].__setitem__(0, 33), -1),
     "node_kind": (lambda p: p["node_type"].__setitem__(0, 7), -1),
@@ -100,6 +100,13 @@ def test_build_rejects_gpu_specifics(tg):
     if api.size:
         q["act_model"][api[0]] = 1                         # API actions cannot be elastic
         assert _build_rc(tg, q) == -1
+
+
+def test_cost_order_needs_pools_it_can_sort(tg):
+    p = gen.make_random_problem(9, B=1, N=8300, n_cpu=2, n_gpu=0, n_api=0)
+    assert (p["act_type"] == gen.TYPE_CPU).all()
+    p["type_k"][gen.TYPE_GPU] = 0
+    assert _build_rc(tg, dict(p, order_policy=1)) == -2        # more than TG_MAX_SORTED_POOL actions in one pool
 
 
 def test_null_arguments(tg):

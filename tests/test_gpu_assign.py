@@ -150,6 +150,34 @@ def test_assign_code_paths(tg, orc, case):
     assert (want["reason"] == 0).any() and (want["reason"] == 1).any(), "the case should select and defer"
 
 
+@pytest.mark.parametrize("seed", range(10))
+def test_assign_cost_order_random_problems(tg, orc, seed):
+    """Second visiting order (least estimated ACT first): keys, sort and everything downstream."""
+    print("case cost order", seed, flush=True)
+    p = gen.make_random_problem(200 + seed, B=3, N=80 + 40 * seed, n_cpu=1 + seed % 4, n_gpu=seed % 3, n_api=seed % 2,
+                                depth=1 + seed % 3, busy=seed % 2 == 0, cpu_cap_hi=24 + 8 * (seed % 3))
+    p["order_policy"] = 1
+    want = orc.assign(p)
+    _compare(_assign_gpu(tg, p, use_cost=seed % 3 == 2), want, f"cost order {seed}")
+    fcfs = orc.assign(dict(p, order_policy=0))
+    assert (fcfs["reason"] != want["reason"]).any() or (fcfs["node"] != want["node"]).any(), "the order should matter"
+
+
+def test_assign_cost_order_code_paths(tg, orc):
+    for case in ("pool_150_cpu_70_gpu_nodes", "cap_256_nodes", "long_pinned_queues"):
+        print("case cost order", case, flush=True)
+        p = _code_path_problem(case)
+        p["order_policy"] = 1
+        _compare(_assign_gpu(tg, p), orc.assign(p), f"cost order {case}")
+
+
+def test_assign_cost_order_config2_full(tg, orc):
+    """Workload 2 at full size under the second visiting order."""
+    p = gen.make_config(2)
+    p["order_policy"] = 1
+    _compare(_assign_gpu(tg, p), orc.assign(p))
+
+
 def test_assign_config1(tg, orc):
     p = gen.make_config(1)
     want = orc.assign(p)
