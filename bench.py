@@ -32,7 +32,12 @@ SCORE_TRAFFIC_CONFIG2_BYTES = int((537696.2 + 2.0 * 5642.6) * 1024)
 def order_section(a, tg, torch, p, s_fcfs):
     """The same workload scheduled in the second visiting order (least estimated ACT first instead of first come
     first served): time of tg_assign, and what the order does to the selected set."""
-    P = tg.Problem(dict(p, order_policy=1))
+    try:
+        P = tg.Problem(dict(p, order_policy=1))
+    except tg.TgError as e:
+        if e.code != -2:
+            raise
+        return {"skipped": "a pool of this workload has more actions than the sort of this order takes (8192)"}
     bufs = P.alloc_assign()
     for _ in range(3):
         P.assign(None, bufs)

@@ -1,8 +1,9 @@
 // Wavefront-level building blocks of one scheduling step, shared by tg_assign (one snapshot
 // per launch slot) and tg_replay_trace (one step per tick inside a persistent workgroup).
 //
-//   tg_place_pool      Alg. 1 l.1-2 for one resource kind: FCFS admission at minimum units with
-//                      node choice by least estimated completion time (Eq. 2), node table in LDS
+//   tg_place_pool      Alg. 1 l.1-2 for one resource kind: admission in visiting order at minimum units
+//                      with node choice by least estimated completion time (Eq. 2), node table in
+//                      registers (pools of up to 1024 nodes) or LDS
 //   tg_node_schedule   Alg. 1 l.3-14 for one node: DPArrange (Alg. 3; Alg. 4 chunk states on GPU
 //                      nodes), completion-heap estimate (Alg. 2), greedy tail eviction
 //
@@ -137,7 +138,6 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
     S.fit[u] = (uint8_t)f;
   }
   tg_wave_sync();
-  int64_t backv[R];
   uint32_t back32[R];                                             // backlog above the pool's smallest
   int32_t limv[R], cntv[R], dcntv[R];
   uint32_t fitv[R];                                               // options that fit into the units left; 0: closed
@@ -152,17 +152,17 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
     const int r = lane + TG_WAVE * s;
     const bool have = r < Mt;
     const bool shut = have && S.closed[r] != 0;
-    backv[s] = have ? S.back[r] : 0;
+    const int64_t bk = have ? S.back[r] : 0;
     limv[s] = have ? S.lim[r] : 0;
     fitv[s] = have && !shut ? fit_of(limv[s]) : 0u;
     cntv[s] = 0; dcntv[s] = 0;
     closed[s] = __ballot(shut);
-    if (have) { bmin = backv[s] < bmin ? backv[s] : bmin; bmax = backv[s] > bmax ? backv[s] : bmax; }
+    if (have) { bmin = bk < bmin ? bk : bmin; bmax = bk > bmax ? bk : bmax; }
   }
   bmin = (int64_t)tg_wave_min_u64((uint64_t)bmin);
   bmax = (int64_t)~tg_wave_min_u64(~(uint64_t)bmax);
 #pragma unroll
-  for (int s = 0; s < R; ++s) back32[s] = (uint32_t)(backv[s] - bmin);
+  for (int s = 0; s < R; ++s) { const int r = lane + TG_WAVE * s; back32[s] = r < Mt ? (uint32_t)(S.back[r] - bmin) : 0u; }   // meaningful where the range fits
   // result word of an action: rank + 1 (13 bits) | list slot (17 bits) | reason (2 bits)
   auto pack_res = [](int rank, int slot, int reason) { return (uint32_t)(rank + 1) | (uint32_t)slot << 13 | (uint32_t)reason << 30; };
   for (int base = 0; base < Nt; base += TG_WAVE) {
@@ -253,7 +253,8 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
           for (int s = 0; s < R; ++s) {
             const uint32_t ok = mask & fitv[s];
             const int qs = 31 - __builtin_clz(ok | 1u);
-            const uint64_t key = (uint64_t)(backv[s] + S.dur[l * io.K + qs]) << 12 | (uint32_t)(lane + TG_WAVE * s);
+            const int r = lane + TG_WAVE * s;                     // 64-bit estimates: backlog from the LDS table
+            const uint64_t key = (uint64_t)(S.back[r < Mt ? r : 0] + S.dur[l * io.K + qs]) << 12 | (uint32_t)r;
             if (ok && key < b64) b64 = key;
           }
           b64 = tg_wave_min_u64(b64);
@@ -299,10 +300,13 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
 // Admission of the pool's `Nt` actions (ids acts[0..Nt) in FCFS order) onto its `Mt` nodes.
 // On return S.cnt / S.dcnt hold the list lengths per node and every action has its reason,
 // node (-1 if deferred) and list slot written.
+// MAXR: the widest register variant the caller wants compiled in (1, 4 or 16 slots per lane).
+template <int MAXR = 4>
 __device__ static inline void tg_place_pool(const TgPoolLds& S, const TgPlaceIo& io, const int32_t* acts, int Nt,
                                             int Mt, bool gpu, int lane) {
   if (!io.cost && Mt <= TG_WAVE) { tg_place_pool_regs<1>(S, io, acts, Nt, Mt, gpu, lane); return; }
-  if (!io.cost && Mt <= 4 * TG_WAVE) { tg_place_pool_regs<4>(S, io, acts, Nt, Mt, gpu, lane); return; }
+  if (MAXR >= 4 && !io.cost && Mt <= 4 * TG_WAVE) { tg_place_pool_regs<(MAXR >= 4 ? 4 : 1)>(S, io, acts, Nt, Mt, gpu, lane); return; }
+  if (MAXR >= 16 && !io.cost && Mt <= 16 * TG_WAVE) { tg_place_pool_regs<(MAXR >= 16 ? 16 : 1)>(S, io, acts, Nt, Mt, gpu, lane); return; }
   bool pool_closed = false;
   // which options fit into `units` units, for units = 0..64 (every unit count is <= 64)
   tg_wave_sync();

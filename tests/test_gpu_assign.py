@@ -114,8 +114,10 @@ CODE_PATHS = {
     # pools of 65..256 nodes: node table in four register slots per lane; tight capacities so
     # that pinned actions close nodes and unpinned ones close whole pools
     "pool_150_cpu_70_gpu_nodes": (dict(seed=50, B=2, N=1500, n_cpu=150, n_gpu=70, n_api=3, cpu_cap_hi=6, pin_frac=0.4), (6, 0.97)),
-    # more than 256 nodes of a kind: node table in LDS
+    # 257..1024 nodes of a kind: sixteen register slots per lane
     "pool_300_cpu_nodes": (dict(seed=51, B=1, N=2000, n_cpu=300, n_gpu=0, n_api=0, cpu_cap_hi=5, pin_frac=0.3), (5, 0.97)),
+    # more than 1024 nodes of a kind: node table in LDS
+    "pool_1100_cpu_nodes": (dict(seed=60, B=1, N=4000, n_cpu=1100, n_gpu=0, n_api=0, cpu_cap_hi=3, pin_frac=0.3), (3, 0.97)),
     # 256 units per node, some busy: four heap slots per lane, 256-wide DP rows, > 128 candidates
     "cap_256_nodes": (dict(seed=52, B=2, N=700, n_cpu=2, n_gpu=0, n_api=0, cpu_cap_hi=40, k_list=(1, 2, 4, 8, 16)), (256, 0.995)),
     "cap_200_no_busy": (dict(seed=53, B=2, N=500, n_cpu=1, n_gpu=1, n_api=1, cpu_cap_hi=40, busy=False, k_list=(1, 2, 4, 8, 16)), (200, 0.995)),
