@@ -114,7 +114,7 @@ def main():
     ap.add_argument("--snapshots", type=int, default=None, help="override B (sampling of big configs)")
     ap.add_argument("--use-cost", type=int, default=0, help="1: tg_assign reads its estimates from the score tensor")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--replay-scenarios", type=int, default=512,
+    ap.add_argument("--replay-scenarios", type=int, default=4096,
                     help="scenarios of workload 5 (10 000 arrivals each) replayed after the timed steps; 0 = skip")
     ap.add_argument("--only", choices=["step", "score", "assign"], default="step")
     ap.add_argument("--calibrate-copy", action="store_true",
