@@ -180,6 +180,35 @@ def test_assign_cost_order_config2_full(tg, orc):
     _compare(_assign_gpu(tg, p), orc.assign(p))
 
 
+def _sweep_problem(seed):
+    rng = np.random.default_rng(seed)
+    k_all = [1, 2, 4, 8, 16, 32]
+    kw = dict(B=int(rng.integers(1, 4)), N=int(rng.integers(1, 700)) if seed % 7 else int(rng.integers(700, 3000)),
+              n_cpu=int(rng.integers(0, 6)), n_gpu=int(rng.integers(0, 4)), n_api=int(rng.integers(0, 3)),
+              cpu_cap_hi=int(rng.choice([4, 16, 40, 100, 256])), k_list=tuple(k_all[:int(rng.integers(1, 7))]),
+              depth=int(rng.integers(1, 5)), busy=bool(rng.integers(0, 2)), pin_frac=float(rng.choice([0.0, 0.3, 0.8])),
+              t_median=int(rng.choice([20_000, 2_000_000, 60_000_000])))
+    if kw["n_cpu"] + kw["n_gpu"] + kw["n_api"] == 0:
+        kw["n_cpu"] = 1
+    p = gen.make_random_problem(seed, **kw)
+    if rng.random() < 0.5:                                   # long candidate lists instead of early pool closure
+        a = (p["act_type"] == gen.TYPE_CPU) & (rng.random(len(p["act_type"])) < 0.95)
+        p["act_kmask"][a] |= 1
+    if kw["n_gpu"] == 0:
+        p["type_k"][gen.TYPE_GPU] = 0
+    p["order_policy"] = int(rng.integers(0, 2))
+    return p, bool(rng.integers(0, 2))
+
+
+def test_assign_random_sweep(tg, orc):
+    """200 problems with every parameter drawn at random (sizes, kinds, capacities, options, depth, busy
+    lists, pins, duration scale, visiting order, with and without the score tensor)."""
+    for seed in range(3000, 3200):
+        p, use_cost = _sweep_problem(seed)
+        _compare(_assign_gpu(tg, p, use_cost=use_cost), orc.assign(p), f"sweep seed {seed}")
+    print("200 problems compared", flush=True)
+
+
 def test_assign_config1(tg, orc):
     p = gen.make_config(1)
     want = orc.assign(p)

@@ -62,6 +62,24 @@ def test_replay_small(tg, orc, name):
     _compare(got, want, range(t["S"]), t["A"])
 
 
+def test_replay_random_sweep(tg, orc):
+    """60 small traces with cluster shape, load, tick limit, pins and depth drawn at random."""
+    for seed in range(500, 560):
+        rng = np.random.default_rng(seed)
+        n_cpu, n_gpu, n_api = int(rng.integers(0, 6)), int(rng.integers(0, 4)), int(rng.integers(0, 4))
+        if n_cpu + n_gpu + n_api == 0:
+            n_cpu = 2
+        probs = np.array([0.6 * (n_cpu > 0), 0.25 * (n_gpu > 0), 0.15 * (n_api > 0)])
+        t = gen.make_trace(S=int(rng.integers(1, 5)), A=int(rng.integers(1, 600)), seed=seed,
+                           cluster=(n_cpu, int(rng.choice([4, 16, 48, 128])), n_gpu, n_api),
+                           type_probs=tuple((probs / probs.sum()).tolist()),
+                           rate_per_s=float(rng.choice([20.0, 100.0, 500.0])), horizon_s=float(rng.choice([1.0, 5.0, 20.0])),
+                           max_ticks=int(rng.choice([60, 5000, 60000])), pin_frac=float(rng.choice([0.0, 0.3, 0.8])))
+        t["depth"] = int(rng.integers(1, 5))
+        _compare(_replay_gpu(tg, t), orc.replay(t), range(t["S"]), t["A"])
+    print("60 traces compared", flush=True)
+
+
 def test_replay_depth_and_ties(tg, orc):
     t = gen.make_trace(S=4, A=500, seed=31, contended=True, rate_per_s=120.0, horizon_s=4.0, max_ticks=30000)
     t["depth"] = 3
