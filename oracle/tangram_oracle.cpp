@@ -44,10 +44,12 @@ struct Act {
   int64_t T, age;
   uint32_t kmask, param;
   int pin, task;
+  int aux = 0;                 // second component of the cost vector (Sec. 4.1), e.g. memory with CPU cores
 };
 
 struct Node {
   int type, cap, free;
+  int aux_free = INT32_MAX;    // what the node has left of the second resource
   int64_t backlog;
   int chunks[4];               // free chunks of size 1,2,4,8 (GPU nodes)
   std::vector<int64_t> busy;   // release time of every unit held by a running action
@@ -270,6 +272,13 @@ StepOut step(const Tables& tb, const std::vector<Act>& acts, std::vector<Node> n
   }
 
   // Alg. 1 l.1-2: prefix of the visiting order admitted with minimum units; node choice by least estimated ACT
+  // Second, co-constrained resource (Sec. 4.1: the cost of an action is a vector; Sec. 5.2: a node
+  // must have the cores for the action and the memory for the whole trajectory when the
+  // trajectory's first action is placed).  An action that is free to choose its node needs
+  // `aux` of it on top of its units; an action pinned to a node belongs to a trajectory whose
+  // share was taken when it was placed there, so it is not charged again.
+  std::vector<int> aux_rem(M);
+  for (int j = 0; j < M; ++j) aux_rem[j] = nodes[j].aux_free;
   std::vector<int> rem(M);
   std::vector<std::vector<int>> placed(M), waiting_pinned(M);
   std::vector<char> closed(M, 0);
@@ -292,6 +301,7 @@ StepOut step(const Tables& tb, const std::vector<Act>& acts, std::vector<Node> n
       if (nodes[j].type != a.type || closed[j]) continue;
       if (a.pin >= 0 && a.pin != j) continue;
       if (!fits(j, kmin[i])) continue;
+      if (a.pin < 0 && a.aux > aux_rem[j]) continue;
       int qs = -1;
       for (int q : options_on(tb, a, nodes[j])) if (fits(j, tb.k_list[q])) qs = q;
       const int64_t e = nodes[j].backlog + duration(tb, a, qs);      // Eq. 2 on this node
@@ -304,6 +314,7 @@ StepOut step(const Tables& tb, const std::vector<Act>& acts, std::vector<Node> n
       continue;
     }
     o.node[i] = bj; o.home[i] = bj;
+    if (a.pin < 0) aux_rem[bj] -= a.aux;
     if (nodes[bj].type == T_GPU) chunk_take(&ch[bj*4], kmin[i]); else rem[bj] -= kmin[i];
     placed[bj].push_back(i);
   }
@@ -383,6 +394,7 @@ struct orc_problem {
   const int32_t* node_busy_off; const int64_t* node_busy_rel_us;
   const uint8_t* act_type; const uint8_t* act_model; const int64_t* act_t_ori_us; const int64_t* act_age_us;
   const uint32_t* act_kmask; const uint32_t* act_param; const int32_t* act_pin_node; const int32_t* act_task;
+  const int32_t* node_aux_free; const int32_t* act_aux;     // both or neither; NULL: no second resource
 };
 
 struct orc_summary {
@@ -412,7 +424,8 @@ std::vector<Act> acts_of(const orc_problem* p, int b) {
   for (int i = 0; i < p->N; ++i) {
     const size_t g = (size_t)b * p->N + i;
     v[i] = Act{p->act_type[g], p->act_model[g], p->act_t_ori_us[g], p->act_age_us ? p->act_age_us[g] : 0,
-               p->act_kmask[g], p->act_param[g], p->act_pin_node[g], p->act_task ? p->act_task[g] : 0};
+               p->act_kmask[g], p->act_param[g], p->act_pin_node[g], p->act_task ? p->act_task[g] : 0,
+               p->act_aux ? p->act_aux[g] : 0};
   }
   return v;
 }
@@ -424,6 +437,7 @@ std::vector<Node> nodes_of(const orc_problem* p, int b) {
     Node& nd = v[j];
     nd.type = p->node_type[g]; nd.cap = p->node_cap[g]; nd.free = p->node_free[g];
     nd.backlog = p->node_backlog_us[g];
+    nd.aux_free = p->node_aux_free ? p->node_aux_free[g] : INT32_MAX;
     for (int x = 0; x < 4; ++x) nd.chunks[x] = 0;
     if (nd.type == T_GPU) {
       if (p->node_chunks) for (int x = 0; x < 4; ++x) nd.chunks[x] = p->node_chunks[g * 4 + x];
