@@ -101,6 +101,13 @@ typedef struct {
   const uint32_t *act_param;      /* Amdahl: parallel fraction in ppm (<= 10^6); table: class id */
   const int32_t *act_pin_node;    /* node index inside the snapshot, or negative = free to choose (Sec. 5.2) */
   const int32_t *act_task;        /* may be NULL (all zero)                                      */
+  /* Second, co-constrained component of the cost vector (Sec. 4.1), e.g. memory next to CPU cores
+   * (Sec. 5.2): an action that is free to choose its node (act_pin_node < 0) is only admitted to a
+   * node that has act_aux left of node_aux_free, and takes it; an action pinned to a node belongs
+   * to a trajectory whose share was taken when it was placed and is not charged again.
+   * Both arrays or neither (NULL, NULL = no second resource); values >= 0. */
+  const int32_t *node_aux_free;   /* [B*M] */
+  const int32_t *act_aux;         /* [B*N] */
 } tg_problem_desc;
 
 /* Per-snapshot result of tg_assign.  Only mean_act_us and util are floating point. */

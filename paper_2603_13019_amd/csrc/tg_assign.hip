@@ -177,17 +177,19 @@ __global__ __launch_bounds__(TG_WAVE) void tg_place_kernel(TgDev P, const int64_
     S.back[r] = P.node_backlog[g];
     S.lim[r] = t == TG_TYPE_GPU ? (int32_t)P.node_chunks[g] : P.node_free[g];
     S.cnt[r] = 0; S.dcnt[r] = 0; S.closed[r] = 0;
+    if (P.node_aux) S.aux[r] = P.node_aux[g];
   }
   __syncthreads();
 
   TgPlaceIo io;
   io.act_kmask = P.act_kmask + abase; io.act_static = P.act_static + abase; io.act_pin = P.act_pin + abase;
+  io.act_aux = P.act_aux ? P.act_aux + abase : nullptr;
   io.node_rank = P.node_rank + nbase; io.nodes = nodes; io.dur = dur + abase * P.K; io.K = P.K; io.Kt = P.type_k[t];
   io.cost = nullptr; io.cost_row_len = 0;
   if (cost) { const TgBlock blk = blocks[b * 3 + t]; io.cost = cost + blk.cost_off; io.cost_row_len = blk.M_t * blk.K_t; }
   io.out_node = O.node + abase; io.out_units = O.units + abase; io.out_act = O.act_us + abase;
   io.out_reason = O.defer_reason + abase; io.slot = W.slot + abase;
-  tg_place_pool<16>(S, io, acts, Nt, Mt, t == TG_TYPE_GPU, lane);
+  tg_place_pool<16, true>(S, io, acts, Nt, Mt, t == TG_TYPE_GPU, lane);
 
   tg_pool_extents(S, nodes, Mt, a0, W.nl_off + nbase, W.nl_cnt + nbase, W.dl_off + nbase, W.dl_cnt + nbase, lane);
 }

@@ -81,6 +81,11 @@ extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_p
   if (!d->act_type || !d->act_model || !d->act_t_ori_us || !d->act_kmask || !d->act_param || !d->act_pin_node)
     return TG_E_INVALID_ARG;
   if (d->node_busy_off && !d->node_busy_rel_us && d->node_busy_off[(size_t)B * M] > 0) return TG_E_INVALID_ARG;
+  if ((d->node_aux_free == nullptr) != (d->act_aux == nullptr)) return TG_E_INVALID_ARG;
+  if (d->act_aux) {
+    for (size_t g = 0; g < (size_t)B * M; ++g) if (d->node_aux_free[g] < 0) return TG_E_INVALID_ARG;
+    for (size_t g = 0; g < (size_t)B * N; ++g) if (d->act_aux[g] < 0) return TG_E_INVALID_ARG;
+  }
 
   const size_t nN = (size_t)B * M, nA = (size_t)B * N;
   tg_problem* p = new (std::nothrow) tg_problem();
@@ -92,6 +97,11 @@ extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_p
     const size_t o_ntype = ar.add(nN), o_ncap = ar.add(nN * 4), o_nfree = ar.add(nN * 4), o_nback = ar.add(nN * 8),
                  o_nchunk = ar.add(nN * 4), o_nboff = ar.add((nN + 1) * 4), o_nrank = ar.add(nN * 4),
                  o_tnidx = ar.add(nN * 4), o_tnoff = ar.add((size_t)B * 4 * 4);
+    const size_t o_naux = ar.add(d->act_aux ? nN * 4 : 0), o_aaux = ar.add(d->act_aux ? nA * 4 : 0);
+    if (d->act_aux) {
+      std::memcpy(ar.at<int32_t>(o_naux), d->node_aux_free, nN * 4);
+      std::memcpy(ar.at<int32_t>(o_aaux), d->act_aux, nA * 4);
+    }
     const size_t n_busy = d->node_busy_off ? (size_t)d->node_busy_off[nN] : 0;
     const size_t o_nbrel = ar.add(std::max<size_t>(n_busy, 1) * 8);
     std::vector<int> max_cap((size_t)B * 3, -1);
@@ -290,6 +300,8 @@ extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_p
     v.act_static = (const uint8_t*)(base + o_astat); v.act_T = (const int64_t*)(base + o_aT);
     v.act_age = (const int64_t*)(base + o_aage); v.act_kmask = (const uint32_t*)(base + o_amask);
     v.act_param = (const uint32_t*)(base + o_aparam); v.act_pin = (const int32_t*)(base + o_apin);
+    v.node_aux = d->act_aux ? (const int32_t*)(base + o_naux) : nullptr;
+    v.act_aux = d->act_aux ? (const int32_t*)(base + o_aaux) : nullptr;
     v.act_task = (const int32_t*)(base + o_atask); v.speedup = (const uint32_t*)(base + o_speed);
     v.tact_idx = (const int32_t*)(base + o_taidx); v.tact_off = (const int32_t*)(base + o_taoff);
     v.tnode_idx = (const int32_t*)(base + o_tnidx); v.tnode_off = (const int32_t*)(base + o_tnoff);

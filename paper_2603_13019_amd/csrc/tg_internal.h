@@ -34,6 +34,8 @@ struct TgDev {
   const uint32_t* act_param;
   const int32_t* act_pin;         // node index or -1
   const int32_t* act_task;
+  const int32_t* node_aux;        // [B*M] second resource left on the node, or nullptr: no second resource
+  const int32_t* act_aux;         // [B*N] what an unpinned action needs of it (nullptr together with node_aux)
   const uint32_t* speedup;        // [n_classes*K]
   // grouping by resource kind, per snapshot
   const int32_t* tact_idx;        // [B*N] action ids grouped by kind, FCFS inside a group

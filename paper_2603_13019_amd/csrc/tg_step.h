@@ -82,6 +82,7 @@ struct TgPoolLds {
   int32_t* lim;      // [nodes] CPU/API: units left; GPU: packed counts of free chunks
   int32_t* cnt;      // [nodes] actions admitted to the node so far
   int32_t* dcnt;     // [nodes] waiting actions pinned to the node
+  int32_t* aux;      // [nodes] second resource left on the node (only read when the actions carry a demand)
   int32_t* k;        // [TG_MAX_K] unit counts
   uint8_t* closed;   // [nodes] the node's pool is closed (a pinned action did not fit)
   uint8_t* fit;      // [65] bit q set <=> k_list[q] <= min(units, 64)
@@ -89,7 +90,7 @@ struct TgPoolLds {
 
 __host__ __device__ static inline size_t tg_pool_lds_bytes(int nodes) {
   const size_t n = (size_t)((nodes + 7) & ~7);
-  return n * 8 + 64 * TG_MAX_K * 8 + n * 4 * 3 + TG_MAX_K * 4 + n + 72;
+  return n * 8 + 64 * TG_MAX_K * 8 + n * 4 * 4 + TG_MAX_K * 4 + n + 72;
 }
 
 __device__ static inline void tg_pool_lds_carve(unsigned char* smem, int nodes, TgPoolLds* S) {
@@ -99,7 +100,8 @@ __device__ static inline void tg_pool_lds_carve(unsigned char* smem, int nodes, 
   S->lim = reinterpret_cast<int32_t*>(S->dur + 64 * TG_MAX_K);
   S->cnt = S->lim + n;
   S->dcnt = S->cnt + n;
-  S->k = S->dcnt + n;
+  S->aux = S->dcnt + n;
+  S->k = S->aux + n;
   S->closed = reinterpret_cast<uint8_t*>(S->k + TG_MAX_K);
   S->fit = S->closed + n;
 }
@@ -109,6 +111,7 @@ struct TgPlaceIo {
   const uint32_t* act_kmask;
   const uint8_t* act_static;
   const int32_t* act_pin;
+  const int32_t* act_aux;      // demand for the node's second resource (charged to unpinned actions), or nullptr
   const int32_t* node_rank;    // node id -> rank inside this pool
   const int32_t* nodes;        // rank -> node id
   const int64_t* dur;          // [id*K + q]
@@ -127,7 +130,7 @@ struct TgPlaceIo {
 // result goes back into the action's lane as one word; an action pinned to a node has a
 // single candidate and is handled with scalar code; with R = 1 the smallest rank among equal
 // estimates is simply the lowest lane.  Same decisions as the LDS variant below.
-template <int R>
+template <int R, bool AUX>
 __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPlaceIo& io, const int32_t* acts, int Nt,
                                                  int Mt, bool gpu, int lane) {
   bool pool_closed = false;
@@ -140,6 +143,7 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
   tg_wave_sync();
   uint32_t back32[R];                                             // backlog above the pool's smallest
   int32_t limv[R], cntv[R], dcntv[R];
+  int32_t auxv[R];                                                // second resource left (Sec. 4.1's cost vector)
   uint32_t fitv[R];                                               // options that fit into the units left; 0: closed
   uint64_t closed[R];                                             // wavefront-uniform copies of the closed flags
   int64_t bmin = TG_INF, bmax = 0;
@@ -156,6 +160,7 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
     limv[s] = have ? S.lim[r] : 0;
     fitv[s] = have && !shut ? fit_of(limv[s]) : 0u;
     cntv[s] = 0; dcntv[s] = 0;
+    auxv[s] = AUX && have ? S.aux[r] : INT32_MAX;
     closed[s] = __ballot(shut);
     if (have) { bmin = bk < bmin ? bk : bmin; bmax = bk > bmax ? bk : bmax; }
   }
@@ -169,10 +174,11 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
     const int cnt = min(TG_WAVE, Nt - base);
     // lane l holds action base+l: its inputs now (mask | static << 8 | minimum units << 9 |
     // (pinned rank + 1) << 16), its result after the loop
-    int my_id = 0;
+    int my_id = 0, my_aux = 0;
     uint32_t my_w = 0, my_res = 0;
     if (lane < cnt) {
       my_id = acts[base + lane];
+      if (AUX) my_aux = io.act_aux[my_id];
       const uint32_t mask = io.act_kmask[my_id], stat = io.act_static[my_id] ? 1u : 0u;
       const int pin = io.act_pin[my_id];
       const int pr = pin >= 0 && !stat ? io.node_rank[pin] : -1;
@@ -196,6 +202,7 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
       const uint32_t w = (uint32_t)__builtin_amdgcn_readlane((int)my_w, l);
       const uint32_t mask = w & 0xffu;
       const int kmin = (int)(w >> 9 & 0x7fu), pr = (int)(w >> 16) - 1;
+      const int aux = AUX && pr < 0 ? __builtin_amdgcn_readlane(my_aux, l) : 0;   // pinned: already charged
       uint32_t res;
       int take_rank = -1;                                          // node that admits the action
       if (w & 0x100u) {
@@ -238,7 +245,7 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
           uint32_t b32 = 0xffffffffu, brank = 0xffffffffu;
 #pragma unroll
           for (int s = 0; s < R; ++s) {               // ascending rank, strict <: the smaller rank wins ties
-            const uint32_t ok = mask & fitv[s];                    // allowed options that still fit
+            const uint32_t ok = !AUX || auxv[s] >= aux ? mask & fitv[s] : 0u;   // allowed options that still fit
             const int qs = 31 - __builtin_clz(ok | 1u);            // the largest of them
             const uint32_t e32 = ok ? back32[s] + dur32[2 * (l * io.K + qs)] : 0xffffffffu;
             if (R > 1) { if (e32 < b32) { b32 = e32; brank = (uint32_t)(lane + TG_WAVE * s); } }
@@ -251,7 +258,7 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
           uint64_t b64 = ~0ull;
 #pragma unroll
           for (int s = 0; s < R; ++s) {
-            const uint32_t ok = mask & fitv[s];
+            const uint32_t ok = !AUX || auxv[s] >= aux ? mask & fitv[s] : 0u;
             const int qs = 31 - __builtin_clz(ok | 1u);
             const int r = lane + TG_WAVE * s;                     // 64-bit estimates: backlog from the LDS table
             const uint64_t key = (uint64_t)(S.back[r < Mt ? r : 0] + S.dur[l * io.K + qs]) << 12 | (uint32_t)r;
@@ -273,6 +280,7 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
           slot = __builtin_amdgcn_readlane(cntv[s], rl);
           if (lane == rl) {
             ++cntv[s];
+            if (AUX) auxv[s] -= aux;
             limv[s] = gpu ? (int32_t)tg_chunk_take((uint32_t)limv[s], kmin) : limv[s] - kmin;
             fitv[s] = fit_of(limv[s]);
           }
@@ -300,13 +308,26 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
 // Admission of the pool's `Nt` actions (ids acts[0..Nt) in FCFS order) onto its `Mt` nodes.
 // On return S.cnt / S.dcnt hold the list lengths per node and every action has its reason,
 // node (-1 if deferred) and list slot written.
-// MAXR: the widest register variant the caller wants compiled in (1, 4 or 16 slots per lane).
-template <int MAXR = 4>
+// MAXR: the widest register variant the caller wants compiled in (1, 4 or 16 slots per lane);
+// AUXOK: whether the caller ever passes a second resource (io.act_aux).
+template <int MAXR = 4, bool AUXOK = false>
 __device__ static inline void tg_place_pool(const TgPoolLds& S, const TgPlaceIo& io, const int32_t* acts, int Nt,
                                             int Mt, bool gpu, int lane) {
-  if (!io.cost && Mt <= TG_WAVE) { tg_place_pool_regs<1>(S, io, acts, Nt, Mt, gpu, lane); return; }
-  if (MAXR >= 4 && !io.cost && Mt <= 4 * TG_WAVE) { tg_place_pool_regs<(MAXR >= 4 ? 4 : 1)>(S, io, acts, Nt, Mt, gpu, lane); return; }
-  if (MAXR >= 16 && !io.cost && Mt <= 16 * TG_WAVE) { tg_place_pool_regs<(MAXR >= 16 ? 16 : 1)>(S, io, acts, Nt, Mt, gpu, lane); return; }
+  if (!io.cost && Mt <= 16 * TG_WAVE) {
+    const int slots = Mt <= TG_WAVE ? 1 : Mt <= 4 * TG_WAVE ? 4 : 16;
+    if (slots <= MAXR) {
+      if (AUXOK && io.act_aux) {
+        if (slots == 1) tg_place_pool_regs<1, AUXOK>(S, io, acts, Nt, Mt, gpu, lane);
+        else if (slots == 4) tg_place_pool_regs<(MAXR >= 4 ? 4 : 1), AUXOK>(S, io, acts, Nt, Mt, gpu, lane);
+        else tg_place_pool_regs<(MAXR >= 16 ? 16 : 1), AUXOK>(S, io, acts, Nt, Mt, gpu, lane);
+      } else {
+        if (slots == 1) tg_place_pool_regs<1, false>(S, io, acts, Nt, Mt, gpu, lane);
+        else if (slots == 4) tg_place_pool_regs<(MAXR >= 4 ? 4 : 1), false>(S, io, acts, Nt, Mt, gpu, lane);
+        else tg_place_pool_regs<(MAXR >= 16 ? 16 : 1), false>(S, io, acts, Nt, Mt, gpu, lane);
+      }
+      return;
+    }
+  }
   bool pool_closed = false;
   // which options fit into `units` units, for units = 0..64 (every unit count is <= 64)
   tg_wave_sync();
@@ -325,13 +346,14 @@ __device__ static inline void tg_place_pool(const TgPoolLds& S, const TgPlaceIo&
     const int cnt = min(TG_WAVE, Nt - base);
     // lane l holds action base+l: its inputs now, its result after the loop (one global
     // round trip per 64 actions instead of one per action)
-    int my_id = 0, my_pr = -1;
+    int my_id = 0, my_pr = -1, my_aux = 0;
     uint32_t my_mask = 0, my_static = 0;
     if (lane < cnt) {
       my_id = acts[base + lane];
       my_mask = io.act_kmask[my_id]; my_static = io.act_static[my_id];
       const int pin = io.act_pin[my_id];
       if (pin >= 0 && !my_static) my_pr = io.node_rank[pin];
+      if (io.act_aux) my_aux = io.act_aux[my_id];
     }
     int res_rank = -1, res_slot = 0, res_reason = TG_SELECTED;
     tg_wave_sync();                                  // previous chunk's readers are done with S.dur
@@ -349,6 +371,7 @@ __device__ static inline void tg_place_pool(const TgPoolLds& S, const TgPlaceIo&
       const uint32_t mask = (uint32_t)__builtin_amdgcn_readlane((int)my_mask, l);
       const int pr = __builtin_amdgcn_readlane(my_pr, l);
       const int stat = __builtin_amdgcn_readlane((int)my_static, l);
+      const int aux = io.act_aux && pr < 0 ? __builtin_amdgcn_readlane(my_aux, l) : 0;   // pinned: already charged
       int reason = TG_SELECTED, rank = -1, slot = 0;
       if (stat) {
         reason = TG_DEFER_INFEASIBLE;
@@ -362,6 +385,7 @@ __device__ static inline void tg_place_pool(const TgPoolLds& S, const TgPlaceIo&
         uint64_t b64 = ~0ull;
         for (int r = r_lo; r < r_hi; r += TG_WAVE) {
           if (S.closed[r]) continue;
+          if (aux > 0 && S.aux[r] < aux) continue;                                    // second resource exhausted
           const int lim = gpu ? tg_chunk_largest((uint32_t)S.lim[r]) : S.lim[r];
           const uint32_t ok = mask & S.fit[lim < TG_MAX_UNIT ? lim : TG_MAX_UNIT];   // allowed options that still fit
           if (ok == 0) continue;                                                      // not even the minimum units
@@ -390,6 +414,7 @@ __device__ static inline void tg_place_pool(const TgPoolLds& S, const TgPlaceIo&
           slot = S.cnt[rank];
           if (lane == 0) {
             S.cnt[rank] = slot + 1;
+            if (aux > 0) S.aux[rank] -= aux;
             S.lim[rank] = gpu ? (int32_t)tg_chunk_take((uint32_t)S.lim[rank], kmin) : S.lim[rank] - kmin;
           }
         }

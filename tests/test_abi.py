@@ -37,7 +37,7 @@ def test_strerror(tg):
 
 
 def test_struct_layouts_match_header(tg):
-    assert C.sizeof(tg.ProblemDesc) == 8 * 4 + 18 * 8
+    assert C.sizeof(tg.ProblemDesc) == 8 * 4 + 20 * 8
     assert C.sizeof(tg.AssignOut) == 8 * 8
     assert C.sizeof(tg.TraceDesc) == 8 * 4 + 8 + 14 * 8
     assert C.sizeof(tg.ReplayOut) == 8 * 8
@@ -100,6 +100,16 @@ def test_build_rejects_gpu_specifics(tg):
     if api.size:
         q["act_model"][api[0]] = 1                         # API actions cannot be elastic
         assert _build_rc(tg, q) == -1
+
+
+def test_second_resource_arrays_come_in_pairs(tg):
+    p = gen.make_random_problem(10, B=1, N=30)
+    q = dict(p, act_aux=np.zeros(30, np.int32))
+    assert _build_rc(tg, q) == -1                              # demand without what the nodes have
+    q = dict(p, node_aux_free=np.zeros(p["M"], np.int32))
+    assert _build_rc(tg, q) == -1
+    q = dict(p, act_aux=np.full(30, -1, np.int32), node_aux_free=np.zeros(p["M"], np.int32))
+    assert _build_rc(tg, q) == -1                              # negative demand
 
 
 def test_cost_order_needs_pools_it_can_sort(tg):

@@ -180,6 +180,37 @@ def test_assign_cost_order_config2_full(tg, orc):
     _compare(_assign_gpu(tg, p), orc.assign(p))
 
 
+def _add_second_resource(p, seed, scarce):
+    """Memory-like demand per action and what every node has left of it (Sec. 4.1's cost vector)."""
+    rng = np.random.default_rng(seed + 77)
+    p["act_aux"] = rng.integers(0, 40, p["B"] * p["N"]).astype(np.int32)
+    p["node_aux_free"] = rng.integers(0, 150 if scarce else 5000, p["B"] * p["M"]).astype(np.int32)
+    return p
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_assign_second_resource_random_problems(tg, orc, seed):
+    print("case second resource", seed, flush=True)
+    p = gen.make_random_problem(400 + seed, B=3, N=150 + 60 * seed, n_cpu=2 + seed % 4, n_gpu=seed % 3, n_api=seed % 2,
+                                depth=1 + seed % 3, busy=seed % 2 == 0, cpu_cap_hi=32 + 16 * (seed % 3), pin_frac=0.3)
+    a = (p["act_type"] == gen.TYPE_CPU)
+    p["act_kmask"][a] |= 1
+    base = orc.assign(p)
+    _add_second_resource(p, seed, scarce=True)
+    p["order_policy"] = seed % 2
+    want = orc.assign(p)
+    _compare(_assign_gpu(tg, p, use_cost=seed % 3 == 1), want, f"second resource {seed}")
+    if p["order_policy"] == 0:
+        assert (base["node"] != want["node"]).any(), "a scarce second resource should change the placement"
+
+
+def test_assign_second_resource_code_paths(tg, orc):
+    for case in ("pool_150_cpu_70_gpu_nodes", "pool_300_cpu_nodes", "pool_1100_cpu_nodes", "cap_256_nodes"):
+        print("case second resource", case, flush=True)
+        p = _add_second_resource(_code_path_problem(case), 5, scarce=True)
+        _compare(_assign_gpu(tg, p), orc.assign(p), f"second resource {case}")
+
+
 def _sweep_problem(seed):
     rng = np.random.default_rng(seed)
     k_all = [1, 2, 4, 8, 16, 32]
@@ -197,6 +228,8 @@ def _sweep_problem(seed):
     if kw["n_gpu"] == 0:
         p["type_k"][gen.TYPE_GPU] = 0
     p["order_policy"] = int(rng.integers(0, 2))
+    if rng.random() < 0.5:
+        _add_second_resource(p, seed, scarce=bool(rng.integers(0, 2)))
     return p, bool(rng.integers(0, 2))
 
 
