@@ -67,3 +67,45 @@ def test_build_problem_time_is_reported(tg):
     print(f"tg_build_problem on workload 2 (262144 actions, 18432 nodes): {dt * 1e3:.1f} ms", flush=True)
     assert P.num_candidates == 68787392
     P.free()
+
+
+def test_step_can_be_captured_into_a_graph(tg):
+    """tg_score_candidates + tg_assign (three streams forked and joined with events, no memsets) recorded
+    into a HIP graph: every replay, with eager launches and synchronisations in between, reproduces the
+    eager result."""
+    import torch
+    p = gen.make_config(2, B=24)
+    P = tg.Problem(p)
+    cost, bufs = P.alloc_cost(), P.alloc_assign()
+
+    def step():
+        P.score(cost)
+        P.assign(cost, bufs)
+
+    step()
+    torch.cuda.synchronize()
+    keys = ("node", "units", "act_us", "defer_reason", "node_used", "node_obj", "summary")
+    ref = {k: bufs[k].clone() for k in keys}
+    ref_cost = cost.clone()
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        step()                                                   # the stream has run the step once before capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        step()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        cost.fill_(0)
+        for k in keys:
+            bufs[k].fill_(0)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(cost, ref_cost), f"replay {rep}: score tensor"
+        for k in keys:
+            assert torch.equal(bufs[k], ref[k]), f"replay {rep}: {k}"
+        step()                                                   # eager work between the replays
+        torch.cuda.synchronize()
+    del g
+    P.free()
