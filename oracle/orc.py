@@ -49,7 +49,8 @@ class Problem(C.Structure):
         (n, C.c_void_p) for n in (
             "k_list", "type_k", "speedup_q16", "node_type", "node_cap", "node_free", "node_backlog_us",
             "node_chunks", "node_busy_off", "node_busy_rel_us", "act_type", "act_model", "act_t_ori_us",
-            "act_age_us", "act_kmask", "act_param", "act_pin_node", "act_task", "node_aux_free", "act_aux")]
+            "act_age_us", "act_kmask", "act_param", "act_pin_node", "act_task", "node_aux_free", "act_aux",
+            "act_service", "node_resident", "restore_us")]
 
 
 class Summary(C.Structure):
@@ -75,7 +76,7 @@ _DT = dict(k_list=np.int32, type_k=np.int32, speedup_q16=np.uint32, node_type=np
            node_busy_rel_us=np.int64, act_type=np.uint8, act_model=np.uint8, act_t_ori_us=np.int64,
            act_age_us=np.int64, act_kmask=np.uint32, act_param=np.uint32, act_pin_node=np.int32,
            act_task=np.int32, quota_rate=np.int32, quota_tok0_micro=np.int64, arrival_us=np.int64,
-           node_aux_free=np.int32, act_aux=np.int32)
+           node_aux_free=np.int32, act_aux=np.int32, act_service=np.int32, node_resident=np.uint64, restore_us=np.int64)
 
 
 def lib():

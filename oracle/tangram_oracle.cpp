@@ -37,6 +37,7 @@ struct Tables {
   const int32_t* type_k;       // how many leading entries of k_list each type may use
   const uint32_t* speedup_q16; // [class][q] = round(65536 * E(k_q) * k_q)
   int depth;
+  const int64_t* restore_us = nullptr;   // [service] time to bring a service back from host memory
 };
 
 struct Act {
@@ -45,11 +46,13 @@ struct Act {
   uint32_t kmask, param;
   int pin, task;
   int aux = 0;                 // second component of the cost vector (Sec. 4.1), e.g. memory with CPU cores
+  int service = -1;            // long-lived service the action calls (Sec. 5.3), -1: none
 };
 
 struct Node {
   int type, cap, free;
   int aux_free = INT32_MAX;    // what the node has left of the second resource
+  uint64_t resident = 0;       // bit s set: service s is cached in the node's device memory (Sec. 5.3)
   int64_t backlog;
   int chunks[4];               // free chunks of size 1,2,4,8 (GPU nodes)
   std::vector<int64_t> busy;   // release time of every unit held by a running action
@@ -70,6 +73,14 @@ int64_t duration(const Tables& tb, const Act& a, int q) {
   }
   int64_t d = (int64_t)((num + den - 1) / den);
   return d < 1 ? 1 : d;
+}
+
+// Sec. 5.3 (evict on execution): an action whose service is resident on the node runs at once;
+// otherwise the service is restored from host memory first, which delays the action by the
+// service's restore time on that node.
+int64_t restore_delay(const Tables& tb, const Act& a, const Node& nd) {
+  if (a.service < 0 || !tb.restore_us || (nd.resident >> a.service & 1ull)) return 0;
+  return tb.restore_us[a.service];
 }
 
 // allowed option indices of an action (Sec. 4.1: the discrete set of unit counts)
@@ -265,7 +276,8 @@ StepOut step(const Tables& tb, const std::vector<Act>& acts, std::vector<Node> n
       const Act& a = acts[i];
       for (int j = 0; j < M; ++j) {
         if (nodes[j].type != a.type || (a.pin >= 0 && a.pin != j)) continue;
-        for (int q : options_on(tb, a, nodes[j])) key[i] = std::min(key[i], nodes[j].backlog + duration(tb, a, q));
+        for (int q : options_on(tb, a, nodes[j]))
+          key[i] = std::min(key[i], nodes[j].backlog + restore_delay(tb, a, nodes[j]) + duration(tb, a, q));
       }
     }
     std::stable_sort(visit.begin(), visit.end(), [&](int x, int y) { return key[x] < key[y]; });
@@ -304,7 +316,7 @@ StepOut step(const Tables& tb, const std::vector<Act>& acts, std::vector<Node> n
       if (a.pin < 0 && a.aux > aux_rem[j]) continue;
       int qs = -1;
       for (int q : options_on(tb, a, nodes[j])) if (fits(j, tb.k_list[q])) qs = q;
-      const int64_t e = nodes[j].backlog + duration(tb, a, qs);      // Eq. 2 on this node
+      const int64_t e = nodes[j].backlog + restore_delay(tb, a, nodes[j]) + duration(tb, a, qs);   // Eq. 2 on this node
       if (e < be) { be = e; bj = j; }
     }
     if (bj < 0) {
@@ -334,7 +346,7 @@ StepOut step(const Tables& tb, const std::vector<Act>& acts, std::vector<Node> n
     } else {
       auto dur_row = [&](int i, int64_t* row) {
         for (int q = 0; q < K; ++q) row[q] = INF;
-        for (int q : options_on(tb, acts[i], nd)) row[q] = duration(tb, acts[i], q);
+        for (int q : options_on(tb, acts[i], nd)) row[q] = restore_delay(tb, acts[i], nd) + duration(tb, acts[i], q);
       };
       std::vector<int64_t> cdur((size_t)m * K);
       for (int x = 0; x < m; ++x) dur_row(C[x], &cdur[(size_t)x * K]);
@@ -373,7 +385,7 @@ StepOut step(const Tables& tb, const std::vector<Act>& acts, std::vector<Node> n
       if (x >= L) { o.node[i] = -1; o.reason[i] = R_EVICTED; continue; }
       int q = 0; while (tb.k_list[q] != ks[x]) ++q;
       o.units[i] = ks[x];
-      o.act[i] = acts[i].age + nd.backlog + duration(tb, acts[i], q);
+      o.act[i] = acts[i].age + nd.backlog + restore_delay(tb, acts[i], nd) + duration(tb, acts[i], q);
     }
   }
   return o;
@@ -395,6 +407,7 @@ struct orc_problem {
   const uint8_t* act_type; const uint8_t* act_model; const int64_t* act_t_ori_us; const int64_t* act_age_us;
   const uint32_t* act_kmask; const uint32_t* act_param; const int32_t* act_pin_node; const int32_t* act_task;
   const int32_t* node_aux_free; const int32_t* act_aux;     // both or neither; NULL: no second resource
+  const int32_t* act_service; const uint64_t* node_resident; const int64_t* restore_us;   // all or none
 };
 
 struct orc_summary {
@@ -417,7 +430,9 @@ struct orc_trace {
 
 namespace {
 
-Tables tables_of(const orc_problem* p) { return Tables{p->K, p->k_list, p->type_k, p->speedup_q16, p->depth}; }
+Tables tables_of(const orc_problem* p) {
+  return Tables{p->K, p->k_list, p->type_k, p->speedup_q16, p->depth, p->act_service ? p->restore_us : nullptr};
+}
 
 std::vector<Act> acts_of(const orc_problem* p, int b) {
   std::vector<Act> v(p->N);
@@ -425,7 +440,7 @@ std::vector<Act> acts_of(const orc_problem* p, int b) {
     const size_t g = (size_t)b * p->N + i;
     v[i] = Act{p->act_type[g], p->act_model[g], p->act_t_ori_us[g], p->act_age_us ? p->act_age_us[g] : 0,
                p->act_kmask[g], p->act_param[g], p->act_pin_node[g], p->act_task ? p->act_task[g] : 0,
-               p->act_aux ? p->act_aux[g] : 0};
+               p->act_aux ? p->act_aux[g] : 0, p->act_service ? p->act_service[g] : -1};
   }
   return v;
 }
@@ -438,6 +453,7 @@ std::vector<Node> nodes_of(const orc_problem* p, int b) {
     nd.type = p->node_type[g]; nd.cap = p->node_cap[g]; nd.free = p->node_free[g];
     nd.backlog = p->node_backlog_us[g];
     nd.aux_free = p->node_aux_free ? p->node_aux_free[g] : INT32_MAX;
+    nd.resident = p->node_resident ? p->node_resident[g] : 0;
     for (int x = 0; x < 4; ++x) nd.chunks[x] = 0;
     if (nd.type == T_GPU) {
       if (p->node_chunks) for (int x = 0; x < 4; ++x) nd.chunks[x] = p->node_chunks[g * 4 + x];
@@ -489,7 +505,7 @@ void orc_score(const orc_problem* p, int64_t* cost) {
           for (int q = 0; q < tb.type_k[t]; ++q) {
             const bool ok = std::find(op.begin(), op.end(), q) != op.end() && tb.k_list[q] <= nodes[j].cap &&
                             (acts[i].pin < 0 || acts[i].pin == j);
-            cost[w++] = ok ? nodes[j].backlog + duration(tb, acts[i], q) : INF;
+            cost[w++] = ok ? nodes[j].backlog + restore_delay(tb, acts[i], nodes[j]) + duration(tb, acts[i], q) : INF;
           }
         }
       }

@@ -10,7 +10,8 @@ import gen
 import pyref
 
 INF = pyref.INF
-PER_ACTION = ("act_type", "act_model", "act_t_ori_us", "act_age_us", "act_kmask", "act_param", "act_pin_node", "act_task")
+PER_ACTION = ("act_type", "act_model", "act_t_ori_us", "act_age_us", "act_kmask", "act_param", "act_pin_node", "act_task",
+              "act_aux", "act_service")
 
 
 def _dur(p, g, q):
@@ -36,9 +37,13 @@ def _keys(p):
                 n = b * M + j
                 if p["node_type"][n] != t or (pin >= 0 and pin != j):
                     continue
+                extra = 0                                   # Sec. 5.3: restore a service that is not resident on the node
+                if p.get("act_service") is not None and p["act_service"][g] >= 0:
+                    sv = int(p["act_service"][g])
+                    extra = 0 if int(p["node_resident"][n]) >> sv & 1 else int(p["restore_us"][sv])
                 for q in qs:
                     if p["k_list"][q] <= p["node_cap"][n]:
-                        key[g] = min(key[g], int(p["node_backlog_us"][n]) + _dur(p, g, q))
+                        key[g] = min(key[g], int(p["node_backlog_us"][n]) + extra + _dur(p, g, q))
     return key
 
 

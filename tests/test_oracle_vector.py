@@ -27,6 +27,14 @@ def _options(p, g):
     return qs[:1] if p["act_model"][g] == 0 else qs
 
 
+def restore_delay(p, g, n):
+    """Sec. 5.3: a service that is not resident on the node is restored before the action runs."""
+    if p.get("act_service") is None or p["act_service"][g] < 0:
+        return 0
+    s = int(p["act_service"][g])
+    return 0 if int(p["node_resident"][n]) >> s & 1 else int(p["restore_us"][s])
+
+
 def _place(p, b):
     """Admission and node choice of one snapshot without GPU nodes: returns (home, reason) with
     reason 0 admitted, 1 deferred behind a misfit, 3 never feasible."""
@@ -58,7 +66,7 @@ def _place(p, b):
             if nt[j] != t or j in closed or rem[j] < kmin or aux > aux_rem[j]:
                 continue
             q = max(q for q in ops if p["k_list"][q] <= cap[j] and p["k_list"][q] <= rem[j])
-            e = (int(back[j]) + _dur(p, g, q), j)
+            e = (int(back[j]) + restore_delay(p, g, b * M + j) + _dur(p, g, q), j)
             best = e if best is None or e < best else best
         if best is None:
             reason[i] = 1
