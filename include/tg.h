@@ -62,7 +62,8 @@ enum { TG_MAX_K = 8, TG_MAX_UNIT = 64, TG_MAX_CPU_UNITS = 256, TG_MAX_GPU_UNITS 
        TG_MAX_CHUNK_STATES = 512, TG_MAX_DEPTH = 4,
        TG_MAX_ACTIONS = 131072,      /* N, actions per snapshot / A, actions per scenario          */
        TG_MAX_NODES_OF_KIND = 4096,  /* nodes of one resource kind in one snapshot               */
-       TG_MAX_SORTED_POOL = 8192     /* TG_ORDER_COST: actions of one kind in one snapshot       */ };
+       TG_MAX_SORTED_POOL = 8192,    /* TG_ORDER_COST: actions of one kind in one snapshot       */
+       TG_MAX_SERVICES = 64 };
 #define TG_T_ORI_LIMIT (1ll << 36)  /* 1 <= T_ori < 2^36 us                                      */
 #define TG_TIME_LIMIT (1ll << 40)   /* backlog, age, busy release times in [0, 2^40)              */
 #define TG_SUM_T_LIMIT (1ll << 44)  /* sum of T_ori over one snapshot / scenario                  */
@@ -108,6 +109,17 @@ typedef struct {
    * Both arrays or neither (NULL, NULL = no second resource); values >= 0. */
   const int32_t *node_aux_free;   /* [B*M] */
   const int32_t *act_aux;         /* [B*N] */
+  /* Long-lived services under evict-on-execution (Sec. 5.3): an action that calls service s runs
+   * at once on a node where s is resident in device memory; elsewhere the service is restored
+   * from host memory first, which delays the action by restore_us[s] on that node.  The delay is
+   * part of every estimate (score tensor, node choice, visiting-order key), of the durations
+   * DPArrange and the completion heap see on that node, and of the reported ACT.
+   * All three arrays or none (then n_services is ignored). */
+  const int32_t *act_service;     /* [B*N] service id in [0, n_services), or negative: none     */
+  const uint64_t *node_resident;  /* [B*M] bit s set <=> service s is resident on the node       */
+  const int64_t *restore_us;      /* [n_services] in [0, 2^36)                                   */
+  int32_t n_services;             /* 1..TG_MAX_SERVICES                                          */
+  int32_t reserved_;              /* 0                                                           */
 } tg_problem_desc;
 
 /* Per-snapshot result of tg_assign.  Only mean_act_us and util are floating point. */

@@ -95,6 +95,7 @@ __global__ __launch_bounds__(kOrderThreads) void tg_order_kernel(TgDev P, const 
   extern __shared__ __align__(16) unsigned char smem[];
   uint64_t* s_key = reinterpret_cast<uint64_t*>(smem);                       // [n_pad]
   __shared__ unsigned long long s_minback[TG_MAX_K + 1];                       // by number of options the capacity admits
+  __shared__ unsigned long long s_minres[TG_MAX_SERVICES][TG_MAX_K + 1];       // the same over the nodes a service is resident on
   const int b = blockIdx.x / 3, t = blockIdx.x - 3 * b, tid = threadIdx.x;
   const int a0 = P.tact_off[b * 4 + t], Nt = P.tact_off[b * 4 + t + 1] - a0;
   const int n0 = P.tnode_off[b * 4 + t], Mt = P.tnode_off[b * 4 + t + 1] - n0;
@@ -103,11 +104,16 @@ __global__ __launch_bounds__(kOrderThreads) void tg_order_kernel(TgDev P, const 
   const int32_t* acts = P.tact_idx + abase + a0;
   const TgBlock blk = blocks[b * 3 + t];
   const uint64_t* words = P.node_word + blk.n_off;                            // backlog | options admitted << 48, rank order
+  const bool svc = P.act_service != nullptr;
   if (tid <= TG_MAX_K) s_minback[tid] = ~0ull;
+  if (svc) for (int x = tid; x < TG_MAX_SERVICES * (TG_MAX_K + 1); x += kOrderThreads) (&s_minres[0][0])[x] = ~0ull;
   __syncthreads();
   for (int r = tid; r < Mt; r += kOrderThreads) {
     const uint64_t nw = words[r];
     atomicMin(&s_minback[nw >> 48], (unsigned long long)(nw & 0xffffffffffffull));
+    if (svc)
+      for (uint64_t left = P.node_res_k[blk.n_off + r]; left; left &= left - 1)
+        atomicMin(&s_minres[__builtin_ctzll(left)][nw >> 48], (unsigned long long)(nw & 0xffffffffffffull));
   }
   __syncthreads();
   int n_pad = 1;
@@ -123,15 +129,21 @@ __global__ __launch_bounds__(kOrderThreads) void tg_order_kernel(TgDev P, const 
         const uint32_t mask = P.act_kmask[g];
         const int64_t* drow = dur + g * P.K;
         const int pin = P.act_pin[g];
+        const int sv = svc ? P.act_service[g] : -1;
+        const uint64_t rest = sv >= 0 ? (uint64_t)P.restore[sv] : 0;           // paid where the service is not resident
         if (pin >= 0) {
-          const uint64_t nw = words[P.node_rank[nbase + pin]];
+          const int pr = P.node_rank[nbase + pin];
+          const uint64_t nw = words[pr];
           const uint32_t ok = mask & ((1u << (nw >> 48)) - 1u);
-          if (ok) best = (nw & 0xffffffffffffull) + (uint64_t)drow[31 - __builtin_clz(ok)];
+          const uint64_t delay = sv >= 0 && !(P.node_res_k[blk.n_off + pr] >> sv & 1ull) ? rest : 0;
+          if (ok) best = (nw & 0xffffffffffffull) + delay + (uint64_t)drow[31 - __builtin_clz(ok)];
         } else {
           for (int c = 1; c <= Kt; ++c) {                                     // nodes whose capacity admits options 0..c-1
-            const uint64_t mb = s_minback[c];
+            uint64_t mb = s_minback[c];
             const uint32_t ok = mask & ((1u << c) - 1u);
             if (mb == ~0ull || ok == 0) continue;
+            mb += rest;                                                       // any node, restoring; or one that has the service
+            if (sv >= 0 && s_minres[sv][c] < mb) mb = s_minres[sv][c];
             const uint64_t e = mb + (uint64_t)drow[31 - __builtin_clz(ok)];
             best = e < best ? e : best;
           }
@@ -178,12 +190,14 @@ __global__ __launch_bounds__(TG_WAVE) void tg_place_kernel(TgDev P, const int64_
     S.lim[r] = t == TG_TYPE_GPU ? (int32_t)P.node_chunks[g] : P.node_free[g];
     S.cnt[r] = 0; S.dcnt[r] = 0; S.closed[r] = 0;
     if (P.node_aux) S.aux[r] = P.node_aux[g];
+    if (P.node_resident) S.res[r] = P.node_resident[g];
   }
   __syncthreads();
 
   TgPlaceIo io;
   io.act_kmask = P.act_kmask + abase; io.act_static = P.act_static + abase; io.act_pin = P.act_pin + abase;
   io.act_aux = P.act_aux ? P.act_aux + abase : nullptr;
+  io.act_service = P.act_service ? P.act_service + abase : nullptr; io.restore = P.restore;
   io.node_rank = P.node_rank + nbase; io.nodes = nodes; io.dur = dur + abase * P.K; io.K = P.K; io.Kt = P.type_k[t];
   io.cost = nullptr; io.cost_row_len = 0;
   if (cost) { const TgBlock blk = blocks[b * 3 + t]; io.cost = cost + blk.cost_off; io.cost_row_len = blk.M_t * blk.K_t; }
@@ -259,13 +273,14 @@ __global__ __launch_bounds__(TG_WAVE) void tg_node_kernel(TgDev P, const int64_t
     const int nb = min(batch, n_nodes - idx0);
     int my_gn = 0, my_type = 0, my_cap = 0, my_free = 0, my_m = 0, my_off = 0, my_nd = 0, my_doff = 0, my_boff = 0, my_nbusy = 0;
     uint32_t my_chunks = 0;
-    int64_t my_backlog = 0;
+    int64_t my_backlog = 0, my_resident = 0;
     if (lane < nb) {
       my_gn = list[idx0 + lane];
       my_type = P.node_type[my_gn]; my_cap = P.node_cap[my_gn]; my_free = P.node_free[my_gn];
       my_backlog = P.node_backlog[my_gn]; my_chunks = P.node_chunks[my_gn];
       my_m = W.nl_cnt[my_gn]; my_off = W.nl_off[my_gn]; my_nd = W.dl_cnt[my_gn]; my_doff = W.dl_off[my_gn];
       if (P.has_busy) { my_boff = P.node_busy_off[my_gn]; my_nbusy = P.node_busy_off[my_gn + 1] - my_boff; }
+      if (P.node_resident) my_resident = (int64_t)P.node_resident[my_gn];
     }
     for (int j = 0; j < nb; ++j) {
       const int gn = __builtin_amdgcn_readlane(my_gn, j);
@@ -286,6 +301,8 @@ __global__ __launch_bounds__(TG_WAVE) void tg_node_kernel(TgDev P, const int64_t
       in.act_model = P.act_model + abase; in.act_kmask = P.act_kmask + abase; in.dur = dur + abase * P.K;
       in.K = P.K; in.depth = P.depth;
       in.kword = tg_pack_k(P.k_list);
+      in.act_service = P.act_service ? P.act_service + abase : nullptr; in.restore = P.restore;
+      in.resident = (uint64_t)tg_readlane_i64(my_resident, j);
       TgNodeOut out;
       out.node = O.node + abase; out.units = O.units + abase; out.act = O.act_us + abase; out.reason = O.defer_reason + abase;
       out.age = P.act_age + abase;

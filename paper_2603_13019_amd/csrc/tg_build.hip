@@ -82,6 +82,15 @@ extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_p
     return TG_E_INVALID_ARG;
   if (d->node_busy_off && !d->node_busy_rel_us && d->node_busy_off[(size_t)B * M] > 0) return TG_E_INVALID_ARG;
   if ((d->node_aux_free == nullptr) != (d->act_aux == nullptr)) return TG_E_INVALID_ARG;
+  const bool svc = d->act_service != nullptr;
+  if (svc != (d->node_resident != nullptr) || svc != (d->restore_us != nullptr)) return TG_E_INVALID_ARG;
+  if (svc) {
+    if (d->n_services < 1 || d->n_services > TG_MAX_SERVICES) return TG_E_INVALID_ARG;
+    for (int s = 0; s < d->n_services; ++s) if (d->restore_us[s] < 0 || d->restore_us[s] >= TG_T_ORI_LIMIT) return TG_E_RANGE;
+    for (size_t g = 0; g < (size_t)B * N; ++g) if (d->act_service[g] >= d->n_services) return TG_E_INVALID_ARG;
+    if (d->n_services < 64)
+      for (size_t g = 0; g < (size_t)B * M; ++g) if (d->node_resident[g] >> d->n_services) return TG_E_INVALID_ARG;
+  }
   if (d->act_aux) {
     for (size_t g = 0; g < (size_t)B * M; ++g) if (d->node_aux_free[g] < 0) return TG_E_INVALID_ARG;
     for (size_t g = 0; g < (size_t)B * N; ++g) if (d->act_aux[g] < 0) return TG_E_INVALID_ARG;
@@ -97,6 +106,13 @@ extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_p
     const size_t o_ntype = ar.add(nN), o_ncap = ar.add(nN * 4), o_nfree = ar.add(nN * 4), o_nback = ar.add(nN * 8),
                  o_nchunk = ar.add(nN * 4), o_nboff = ar.add((nN + 1) * 4), o_nrank = ar.add(nN * 4),
                  o_tnidx = ar.add(nN * 4), o_tnoff = ar.add((size_t)B * 4 * 4);
+    const size_t o_asvc = ar.add(svc ? nA * 4 : 0), o_nres = ar.add(svc ? nN * 8 : 0), o_rest = ar.add(svc ? TG_MAX_SERVICES * 8 : 0),
+                 o_rowsvc = ar.add(svc ? nA * 8 : 0), o_nresk = ar.add(svc ? nN * 8 : 0);
+    if (svc) {
+      for (size_t g = 0; g < nA; ++g) ar.at<int32_t>(o_asvc)[g] = d->act_service[g] < 0 ? -1 : d->act_service[g];
+      std::memcpy(ar.at<uint64_t>(o_nres), d->node_resident, nN * 8);
+      std::memcpy(ar.at<int64_t>(o_rest), d->restore_us, (size_t)d->n_services * 8);
+    }
     const size_t o_naux = ar.add(d->act_aux ? nN * 4 : 0), o_aaux = ar.add(d->act_aux ? nA * 4 : 0);
     if (d->act_aux) {
       std::memcpy(ar.at<int32_t>(o_naux), d->node_aux_free, nN * 4);
@@ -255,12 +271,17 @@ extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_p
           int pr = -1;
           if (pin >= 0) pr = (pin < M && d->node_type[(size_t)b * M + pin] == t) ? ar.at<int32_t>(o_nrank)[(size_t)b * M + pin] : -2;
           ar.at<int32_t>(o_rowpin)[(size_t)b * N + ta[t] + r] = pr;
+          if (svc) {
+            const int sv = ar.at<int32_t>(o_asvc)[g];
+            ar.at<uint64_t>(o_rowsvc)[(size_t)b * N + ta[t] + r] = sv < 0 ? 0ull : (uint64_t)d->restore_us[sv] | (uint64_t)(sv + 1) << 48;
+          }
         }
         for (int r = 0; r < k.M_t; ++r) {
           const size_t g = (size_t)b * M + ar.at<int32_t>(o_tnidx)[(size_t)b * M + tn[t] + r];
           uint64_t qmax = 0;
           while ((int)qmax < k.K_t && d->k_list[qmax] <= d->node_cap[g]) ++qmax;
           ar.at<uint64_t>(o_nword)[(size_t)b * M + tn[t] + r] = (uint64_t)d->node_backlog_us[g] | qmax << 48;
+          if (svc) ar.at<uint64_t>(o_nresk)[(size_t)b * M + tn[t] + r] = d->node_resident[g];
         }
       }
     if (wgs >= (1ll << 31)) { delete p; return TG_E_RANGE; }
@@ -300,6 +321,11 @@ extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_p
     v.act_static = (const uint8_t*)(base + o_astat); v.act_T = (const int64_t*)(base + o_aT);
     v.act_age = (const int64_t*)(base + o_aage); v.act_kmask = (const uint32_t*)(base + o_amask);
     v.act_param = (const uint32_t*)(base + o_aparam); v.act_pin = (const int32_t*)(base + o_apin);
+    v.act_service = svc ? (const int32_t*)(base + o_asvc) : nullptr;
+    v.node_resident = svc ? (const uint64_t*)(base + o_nres) : nullptr;
+    v.restore = svc ? (const int64_t*)(base + o_rest) : nullptr;
+    v.row_svc = svc ? (const uint64_t*)(base + o_rowsvc) : nullptr;
+    v.node_res_k = svc ? (const uint64_t*)(base + o_nresk) : nullptr;
     v.node_aux = d->act_aux ? (const int32_t*)(base + o_naux) : nullptr;
     v.act_aux = d->act_aux ? (const int32_t*)(base + o_aaux) : nullptr;
     v.act_task = (const int32_t*)(base + o_atask); v.speedup = (const uint32_t*)(base + o_speed);

@@ -36,6 +36,12 @@ struct TgDev {
   const int32_t* act_task;
   const int32_t* node_aux;        // [B*M] second resource left on the node, or nullptr: no second resource
   const int32_t* act_aux;         // [B*N] what an unpinned action needs of it (nullptr together with node_aux)
+  // services (Sec. 5.3): all nullptr when the problem has none
+  const int32_t* act_service;     // [B*N] service id or -1
+  const uint64_t* node_resident;  // [B*M] services resident on the node, one bit each
+  const int64_t* restore;         // [TG_MAX_SERVICES] restore time per service
+  const uint64_t* row_svc;        // [B*N] kind-grouped: restore time | (service + 1) << 48 of the row's action
+  const uint64_t* node_res_k;     // [B*M] kind-grouped copy of node_resident (same order as node_word)
   const uint32_t* speedup;        // [n_classes*K]
   // grouping by resource kind, per snapshot
   const int32_t* tact_idx;        // [B*N] action ids grouped by kind, FCFS inside a group

@@ -300,6 +300,7 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
       TgPlaceIo io;
       io.act_kmask = T.act_kmask + abase; io.act_static = T.act_static + abase; io.act_pin = T.act_pin + abase;
       io.act_aux = nullptr;                                       // traces carry no second resource
+      io.act_service = nullptr; io.restore = nullptr;             // and no services
       io.node_rank = T.node_rank + nbase; io.nodes = nodes; io.dur = dur; io.cost = nullptr; io.cost_row_len = 0;
       io.K = K; io.Kt = T.type_k[ty];
       io.out_node = o_node; io.out_units = o_units; io.out_act = nullptr; io.out_reason = reason; io.slot = slot;
@@ -355,6 +356,7 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
       in.n_busy = nb; in.busy = nullptr; in.busy_lds_off = plan.total;
       in.act_model = T.act_model + abase; in.act_kmask = T.act_kmask + abase; in.dur = dur; in.K = K; in.depth = T.depth;
       in.kword = tg_pack_k(T.k_list);
+      in.act_service = nullptr; in.restore = nullptr; in.resident = 0;
       TgNodeOut out;
       out.node = o_node; out.units = o_units; out.act = nullptr; out.reason = reason; out.age = nullptr;
       int used_units;

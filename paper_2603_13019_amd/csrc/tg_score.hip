@@ -20,13 +20,18 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kStep = 2 * kThreads;
 
+// SVC: the problem has services (Sec. 5.3): an entry whose action calls a service that is not
+// resident on the node carries the service's restore time on top of Eq. 2.
+template <bool SVC>
 __global__ __launch_bounds__(kThreads) void tg_score_kernel(TgDev P, const TgBlock* __restrict__ blocks,
                                                             const int32_t* __restrict__ wg_block, int lds_nodes,
-                                                            int dur_slots, int64_t* __restrict__ cost) {
+                                                            int dur_slots, int row_slots, int64_t* __restrict__ cost) {
   extern __shared__ __align__(16) unsigned char smem[];
   int64_t* s_dur = reinterpret_cast<int64_t*>(smem);                    // [dur_slots]
   uint64_t* s_node = reinterpret_cast<uint64_t*>(s_dur + dur_slots);     // [lds_nodes]
-  int32_t* s_pin = reinterpret_cast<int32_t*>(s_node + lds_nodes);       // [row_slots]
+  uint64_t* s_res = s_node + lds_nodes;                                  // [lds_nodes]  services resident on the node   (SVC)
+  uint64_t* s_rsvc = s_res + (SVC ? lds_nodes : 0);                      // [row_slots]  restore time | (service+1) << 48 (SVC)
+  int32_t* s_pin = reinterpret_cast<int32_t*>(s_rsvc + (SVC ? ((row_slots + 1) & ~1) : 0));   // [row_slots]
 
   const int wg = blockIdx.x;
   const TgBlock blk = blocks[wg_block[wg]];
@@ -63,6 +68,10 @@ __global__ __launch_bounds__(kThreads) void tg_score_kernel(TgDev P, const TgBlo
   }
   for (int r = tid; r < nrows; r += kThreads) s_pin[r] = pins[r];
   for (int j = j0 + tid; j <= j1; j += kThreads) s_node[j - j0] = words[j];
+  if (SVC) {
+    for (int r = tid; r < nrows; r += kThreads) s_rsvc[r] = P.row_svc[blk.a_off + row0 + r];
+    for (int j = j0 + tid; j <= j1; j += kThreads) s_res[j - j0] = P.node_res_k[blk.n_off + j];
+  }
   __syncthreads();
 
   int64_t* out = cost + blk.cost_off;
@@ -93,6 +102,11 @@ __global__ __launch_bounds__(kThreads) void tg_score_kernel(TgDev P, const TgBlo
         const int pin = s_pin[rr - row0];
         const bool ok = d != TG_INF && qq < (int)(nw >> 48) && (pin == -1 || pin == jj);
         if (ok) val = (int64_t)(nw & 0xffffffffffffull) + d;
+        if (SVC && ok) {
+          const uint64_t sw = s_rsvc[rr - row0];
+          const int sv = (int)(sw >> 48);                                // service + 1, 0: none
+          if (sv && !(s_res[jj - j0] >> (sv - 1) & 1ull)) val += (int64_t)(sw & 0xffffffffffffull);
+        }
       }
       v[h] = val;
     }
@@ -114,9 +128,15 @@ __global__ __launch_bounds__(kThreads) void tg_score_kernel(TgDev P, const TgBlo
 
 int tg_launch_score(const tg_problem* p, int64_t* d_cost, hipStream_t s) {
   if (p->score_wgs == 0) return TG_OK;
-  const size_t lds = (size_t)p->score_dur_slots * 8 + (size_t)p->score_lds_nodes * 8 + (size_t)p->score_row_slots * 4;
-  hipLaunchKernelGGL(tg_score_kernel, dim3(p->score_wgs), dim3(kThreads), lds, s, p->dev, p->d_blocks, p->d_wg_block,
-                     p->score_lds_nodes, p->score_dur_slots, d_cost);
+  const bool svc = p->dev.act_service != nullptr;
+  const size_t lds = (size_t)p->score_dur_slots * 8 + (size_t)p->score_lds_nodes * 8 + (size_t)p->score_row_slots * 4 +
+                     (svc ? (size_t)p->score_lds_nodes * 8 + (size_t)((p->score_row_slots + 1) & ~1) * 8 : 0);
+  if (svc)
+    hipLaunchKernelGGL(tg_score_kernel<true>, dim3(p->score_wgs), dim3(kThreads), lds, s, p->dev, p->d_blocks, p->d_wg_block,
+                       p->score_lds_nodes, p->score_dur_slots, p->score_row_slots, d_cost);
+  else
+    hipLaunchKernelGGL(tg_score_kernel<false>, dim3(p->score_wgs), dim3(kThreads), lds, s, p->dev, p->d_blocks, p->d_wg_block,
+                       p->score_lds_nodes, p->score_dur_slots, p->score_row_slots, d_cost);
   return hipGetLastError() == hipSuccess ? TG_OK : TG_E_HIP;
 }
 

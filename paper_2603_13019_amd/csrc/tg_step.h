@@ -83,6 +83,7 @@ struct TgPoolLds {
   int32_t* cnt;      // [nodes] actions admitted to the node so far
   int32_t* dcnt;     // [nodes] waiting actions pinned to the node
   int32_t* aux;      // [nodes] second resource left on the node (only read when the actions carry a demand)
+  uint64_t* res;     // [nodes] services resident on the node (only read when the actions call services)
   int32_t* k;        // [TG_MAX_K] unit counts
   uint8_t* closed;   // [nodes] the node's pool is closed (a pinned action did not fit)
   uint8_t* fit;      // [65] bit q set <=> k_list[q] <= min(units, 64)
@@ -90,13 +91,14 @@ struct TgPoolLds {
 
 __host__ __device__ static inline size_t tg_pool_lds_bytes(int nodes) {
   const size_t n = (size_t)((nodes + 7) & ~7);
-  return n * 8 + 64 * TG_MAX_K * 8 + n * 4 * 4 + TG_MAX_K * 4 + n + 72;
+  return n * 8 * 2 + 64 * TG_MAX_K * 8 + n * 4 * 4 + TG_MAX_K * 4 + n + 72;
 }
 
 __device__ static inline void tg_pool_lds_carve(unsigned char* smem, int nodes, TgPoolLds* S) {
   const size_t n = (size_t)((nodes + 7) & ~7);
   S->back = reinterpret_cast<int64_t*>(smem);
-  S->dur = S->back + n;
+  S->res = reinterpret_cast<uint64_t*>(S->back + n);
+  S->dur = S->back + 2 * n;
   S->lim = reinterpret_cast<int32_t*>(S->dur + 64 * TG_MAX_K);
   S->cnt = S->lim + n;
   S->dcnt = S->cnt + n;
@@ -112,6 +114,8 @@ struct TgPlaceIo {
   const uint8_t* act_static;
   const int32_t* act_pin;
   const int32_t* act_aux;      // demand for the node's second resource (charged to unpinned actions), or nullptr
+  const int32_t* act_service;  // service the action calls (-1: none), or nullptr: no services
+  const int64_t* restore;      // [service] restore time where the service is not resident (Sec. 5.3)
   const int32_t* node_rank;    // node id -> rank inside this pool
   const int32_t* nodes;        // rank -> node id
   const int64_t* dur;          // [id*K + q]
@@ -144,6 +148,8 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
   uint32_t back32[R];                                             // backlog above the pool's smallest
   int32_t limv[R], cntv[R], dcntv[R];
   int32_t auxv[R];                                                // second resource left (Sec. 4.1's cost vector)
+  uint64_t resv[R];                                               // services resident on the node (Sec. 5.3)
+  const bool has_aux = AUX && io.act_aux, has_svc = AUX && io.act_service;   // AUX: the extended variant
   uint32_t fitv[R];                                               // options that fit into the units left; 0: closed
   uint64_t closed[R];                                             // wavefront-uniform copies of the closed flags
   int64_t bmin = TG_INF, bmax = 0;
@@ -160,7 +166,8 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
     limv[s] = have ? S.lim[r] : 0;
     fitv[s] = have && !shut ? fit_of(limv[s]) : 0u;
     cntv[s] = 0; dcntv[s] = 0;
-    auxv[s] = AUX && have ? S.aux[r] : INT32_MAX;
+    auxv[s] = has_aux && have ? S.aux[r] : INT32_MAX;
+    resv[s] = has_svc && have ? S.res[r] : 0ull;
     closed[s] = __ballot(shut);
     if (have) { bmin = bk < bmin ? bk : bmin; bmax = bk > bmax ? bk : bmax; }
   }
@@ -174,11 +181,13 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
     const int cnt = min(TG_WAVE, Nt - base);
     // lane l holds action base+l: its inputs now (mask | static << 8 | minimum units << 9 |
     // (pinned rank + 1) << 16), its result after the loop
-    int my_id = 0, my_aux = 0;
+    int my_id = 0, my_aux = 0, my_svc = -1;
+    int64_t my_rest = 0;                             // restore time of the action's service
     uint32_t my_w = 0, my_res = 0;
     if (lane < cnt) {
       my_id = acts[base + lane];
-      if (AUX) my_aux = io.act_aux[my_id];
+      if (has_aux) my_aux = io.act_aux[my_id];
+      if (has_svc) { my_svc = io.act_service[my_id]; if (my_svc >= 0) my_rest = io.restore[my_svc]; }
       const uint32_t mask = io.act_kmask[my_id], stat = io.act_static[my_id] ? 1u : 0u;
       const int pin = io.act_pin[my_id];
       const int pr = pin >= 0 && !stat ? io.node_rank[pin] : -1;
@@ -194,6 +203,7 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
       if (d != TG_INF && d > dmax) dmax = d;
     }
     dmax = (int64_t)~tg_wave_min_u64(~(uint64_t)dmax);
+    if (has_svc) dmax += (int64_t)~tg_wave_min_u64(~(uint64_t)my_rest);   // bound on duration + restore delay
     // every estimate of the chunk fits in 32 bits above the smallest backlog (durations included)
     const bool narrow = Mt > 0 && (bmax + dmax - bmin) < 0xfffffff0ll;
     const uint32_t* dur32 = reinterpret_cast<const uint32_t*>(S.dur);   // low words
@@ -202,7 +212,9 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
       const uint32_t w = (uint32_t)__builtin_amdgcn_readlane((int)my_w, l);
       const uint32_t mask = w & 0xffu;
       const int kmin = (int)(w >> 9 & 0x7fu), pr = (int)(w >> 16) - 1;
-      const int aux = AUX && pr < 0 ? __builtin_amdgcn_readlane(my_aux, l) : 0;   // pinned: already charged
+      const int aux = has_aux && pr < 0 ? __builtin_amdgcn_readlane(my_aux, l) : 0;   // pinned: already charged
+      const int svc = has_svc ? __builtin_amdgcn_readlane(my_svc, l) : -1;
+      const int64_t rest = has_svc ? tg_readlane_i64(my_rest, l) : 0;
       uint32_t res;
       int take_rank = -1;                                          // node that admits the action
       if (w & 0x100u) {
@@ -247,7 +259,8 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
           for (int s = 0; s < R; ++s) {               // ascending rank, strict <: the smaller rank wins ties
             const uint32_t ok = !AUX || auxv[s] >= aux ? mask & fitv[s] : 0u;   // allowed options that still fit
             const int qs = 31 - __builtin_clz(ok | 1u);            // the largest of them
-            const uint32_t e32 = ok ? back32[s] + dur32[2 * (l * io.K + qs)] : 0xffffffffu;
+            uint32_t e32 = ok ? back32[s] + dur32[2 * (l * io.K + qs)] : 0xffffffffu;
+            if (AUX && ok && svc >= 0 && !(resv[s] >> svc & 1ull)) e32 += (uint32_t)rest;   // restore first
             if (R > 1) { if (e32 < b32) { b32 = e32; brank = (uint32_t)(lane + TG_WAVE * s); } }
             else b32 = e32;
           }
@@ -261,7 +274,9 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
             const uint32_t ok = !AUX || auxv[s] >= aux ? mask & fitv[s] : 0u;
             const int qs = 31 - __builtin_clz(ok | 1u);
             const int r = lane + TG_WAVE * s;                     // 64-bit estimates: backlog from the LDS table
-            const uint64_t key = (uint64_t)(S.back[r < Mt ? r : 0] + S.dur[l * io.K + qs]) << 12 | (uint32_t)r;
+            int64_t e = S.back[r < Mt ? r : 0] + S.dur[l * io.K + qs];
+            if (AUX && svc >= 0 && !(resv[s] >> svc & 1ull)) e += rest;
+            const uint64_t key = (uint64_t)e << 12 | (uint32_t)r;
             if (ok && key < b64) b64 = key;
           }
           b64 = tg_wave_min_u64(b64);
@@ -309,14 +324,14 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
 // On return S.cnt / S.dcnt hold the list lengths per node and every action has its reason,
 // node (-1 if deferred) and list slot written.
 // MAXR: the widest register variant the caller wants compiled in (1, 4 or 16 slots per lane);
-// AUXOK: whether the caller ever passes a second resource (io.act_aux).
+// AUXOK: whether the caller ever passes a second resource (io.act_aux) or services (io.act_service).
 template <int MAXR = 4, bool AUXOK = false>
 __device__ static inline void tg_place_pool(const TgPoolLds& S, const TgPlaceIo& io, const int32_t* acts, int Nt,
                                             int Mt, bool gpu, int lane) {
   if (!io.cost && Mt <= 16 * TG_WAVE) {
     const int slots = Mt <= TG_WAVE ? 1 : Mt <= 4 * TG_WAVE ? 4 : 16;
     if (slots <= MAXR) {
-      if (AUXOK && io.act_aux) {
+      if (AUXOK && (io.act_aux || io.act_service)) {
         if (slots == 1) tg_place_pool_regs<1, AUXOK>(S, io, acts, Nt, Mt, gpu, lane);
         else if (slots == 4) tg_place_pool_regs<(MAXR >= 4 ? 4 : 1), AUXOK>(S, io, acts, Nt, Mt, gpu, lane);
         else tg_place_pool_regs<(MAXR >= 16 ? 16 : 1), AUXOK>(S, io, acts, Nt, Mt, gpu, lane);
@@ -346,7 +361,8 @@ __device__ static inline void tg_place_pool(const TgPoolLds& S, const TgPlaceIo&
     const int cnt = min(TG_WAVE, Nt - base);
     // lane l holds action base+l: its inputs now, its result after the loop (one global
     // round trip per 64 actions instead of one per action)
-    int my_id = 0, my_pr = -1, my_aux = 0;
+    int my_id = 0, my_pr = -1, my_aux = 0, my_svc = -1;
+    int64_t my_rest = 0;
     uint32_t my_mask = 0, my_static = 0;
     if (lane < cnt) {
       my_id = acts[base + lane];
@@ -354,6 +370,7 @@ __device__ static inline void tg_place_pool(const TgPoolLds& S, const TgPlaceIo&
       const int pin = io.act_pin[my_id];
       if (pin >= 0 && !my_static) my_pr = io.node_rank[pin];
       if (io.act_aux) my_aux = io.act_aux[my_id];
+      if (io.act_service) { my_svc = io.act_service[my_id]; if (my_svc >= 0) my_rest = io.restore[my_svc]; }
     }
     int res_rank = -1, res_slot = 0, res_reason = TG_SELECTED;
     tg_wave_sync();                                  // previous chunk's readers are done with S.dur
@@ -365,6 +382,7 @@ __device__ static inline void tg_place_pool(const TgPoolLds& S, const TgPlaceIo&
       if (d != TG_INF && d > dmax) dmax = d;
     }
     dmax = (int64_t)~tg_wave_min_u64(~(uint64_t)dmax);
+    if (io.act_service) dmax += (int64_t)~tg_wave_min_u64(~(uint64_t)my_rest);   // bound on duration + restore delay
     const bool narrow = !io.cost && Mt > 0 && (bmax + dmax - bmin) < 0xfffffff0ll;
     tg_wave_sync();
     for (int l = 0; l < cnt; ++l) {
@@ -372,6 +390,8 @@ __device__ static inline void tg_place_pool(const TgPoolLds& S, const TgPlaceIo&
       const int pr = __builtin_amdgcn_readlane(my_pr, l);
       const int stat = __builtin_amdgcn_readlane((int)my_static, l);
       const int aux = io.act_aux && pr < 0 ? __builtin_amdgcn_readlane(my_aux, l) : 0;   // pinned: already charged
+      const int svc = io.act_service ? __builtin_amdgcn_readlane(my_svc, l) : -1;
+      const int64_t rest = io.act_service ? tg_readlane_i64(my_rest, l) : 0;
       int reason = TG_SELECTED, rank = -1, slot = 0;
       if (stat) {
         reason = TG_DEFER_INFEASIBLE;
@@ -390,12 +410,13 @@ __device__ static inline void tg_place_pool(const TgPoolLds& S, const TgPlaceIo&
           const uint32_t ok = mask & S.fit[lim < TG_MAX_UNIT ? lim : TG_MAX_UNIT];   // allowed options that still fit
           if (ok == 0) continue;                                                      // not even the minimum units
           const int qs = 31 - __builtin_clz(ok);                                      // the largest of them
+          const int64_t delay = svc >= 0 && !(S.res[r] >> svc & 1ull) ? rest : 0;     // restore the service first
           if (narrow) {
-            const uint32_t e = (uint32_t)(S.back[r] + S.dur[l * io.K + qs] - bmin);
+            const uint32_t e = (uint32_t)(S.back[r] + S.dur[l * io.K + qs] + delay - bmin);
             if (e < b32) { b32 = e; brank = (uint32_t)r; }
           } else {
             const int64_t e = io.cost ? io.cost[(size_t)(base + l) * io.cost_row_len + r * io.Kt + qs]
-                                      : S.back[r] + S.dur[l * io.K + qs];
+                                      : S.back[r] + S.dur[l * io.K + qs] + delay;
             const uint64_t key = (uint64_t)e << 12 | (uint32_t)r;
             b64 = key < b64 ? key : b64;
           }
@@ -535,7 +556,18 @@ struct TgNodeIn {
   const uint8_t* act_model; const uint32_t* act_kmask; const int64_t* dur;
   int K, depth;
   uint64_t kword;                    // the unit counts k_list[0..8), one byte each
+  // services (Sec. 5.3); act_service == nullptr: none
+  const int32_t* act_service; const int64_t* restore;
+  uint64_t resident;                 // services resident on this node, one bit each
 };
+
+// Delay of an action on this node: the restore time of its service where the service is not
+// resident in the node's device memory (Sec. 5.3), else nothing.
+__device__ static inline int64_t tg_restore_delay(const TgNodeIn& in, int id) {
+  if (!in.act_service) return 0;
+  const int sv = in.act_service[id];
+  return sv >= 0 && !(in.resident >> sv & 1ull) ? in.restore[sv] : 0;
+}
 
 __host__ __device__ static inline uint64_t tg_pack_k(const int* k_list) {
   uint64_t w = 0;
@@ -701,7 +733,7 @@ __device__ static inline void tg_estimate_run(const TgNodeIn& in, const TgWaitLd
         const int q0 = __builtin_ctz(mask | 0x80000000u);
         my_u = s_k[q0 & (TG_MAX_K - 1)];
         my_ok = mask != 0 && q0 < TG_MAX_K && my_u <= H;        // can never run on this node: left out
-        if (my_ok) my_d = (V)(uint64_t)in.dur[(size_t)id * in.K + q0];
+        if (my_ok) my_d = (V)(uint64_t)(in.dur[(size_t)id * in.K + q0] + tg_restore_delay(in, id));
       }
     }
     uint64_t todo = __ballot(my_ok);                            // the chunk's actions that take part, FCFS = ascending lane
@@ -735,7 +767,7 @@ __device__ static inline void tg_estimate_run(const TgNodeIn& in, const TgWaitLd
         qd = __builtin_amdgcn_readfirstlane(qd);
         if (qd < 0) { ok[k] = false; continue; }                // simulated with the minimum option, result unused
         u[k] = __builtin_amdgcn_readfirstlane(s_k[qd]);
-        const int64_t t = id < 0 ? s_cdur[xx * in.K + qd] : in.dur[(size_t)id * in.K + qd];
+        const int64_t t = id < 0 ? s_cdur[xx * in.K + qd] : in.dur[(size_t)id * in.K + qd] + tg_restore_delay(in, id);
         if (sizeof(V) == 4) dd[k] = (V)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)t);
         else dd[k] = (V)(uint64_t)tg_readlane_i64(t, 0);
       }
@@ -975,7 +1007,7 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
         const int q0 = __builtin_ctz(in.act_kmask[id]);
         out.units[id] = k_of(q0);
         used += k_of(q0);
-        if (out.act) out.act[id] = (out.age ? out.age[id] : 0) + in.backlog + in.dur[(size_t)id * K + q0];
+        if (out.act) out.act[id] = (out.age ? out.age[id] : 0) + in.backlog + tg_restore_delay(in, id) + in.dur[(size_t)id * K + q0];
       }
       used = tg_wave_sum_i32(used);
     }
@@ -988,8 +1020,10 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
     // durations of the node's candidates, options above the node's capacity removed
     for (int x = lane; x < m * K; x += TG_WAVE) {
       const int a = x / K, q = x - a * K;
-      int64_t d = in.dur[(size_t)in.clist[a] * K + q];
+      const int id = in.clist[a];
+      int64_t d = in.dur[(size_t)id * K + q];
       if (k_of(q) > in.cap) d = TG_INF;
+      else if (d != TG_INF) d += tg_restore_delay(in, id);        // the durations this node sees
       s_cdur[x] = d;
     }
     tg_wave_sync();
@@ -1011,7 +1045,7 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
         const int u = k_of(q0 & (TG_MAX_K - 1));
         const bool runs = mask != 0 && q0 < TG_MAX_K && u <= U + in.n_busy;   // else it can never run on this node
         int64_t d = 0;
-        if (mask) { d = in.dur[(size_t)id * K + __builtin_ctz(mask)]; sumd += d; }
+        if (mask) { d = in.dur[(size_t)id * K + __builtin_ctz(mask)] + tg_restore_delay(in, id); sumd += d; }
         if (y < plan.wait_slots) { s_wd[y] = runs ? d : 0; s_wu[y] = runs ? (uint8_t)u : 0; }
       }
       for (int c = lane; c < in.n_busy; c += TG_WAVE) {

@@ -37,7 +37,7 @@ def test_strerror(tg):
 
 
 def test_struct_layouts_match_header(tg):
-    assert C.sizeof(tg.ProblemDesc) == 8 * 4 + 20 * 8
+    assert C.sizeof(tg.ProblemDesc) == 8 * 4 + 23 * 8 + 2 * 4
     assert C.sizeof(tg.AssignOut) == 8 * 8
     assert C.sizeof(tg.TraceDesc) == 8 * 4 + 8 + 14 * 8
     assert C.sizeof(tg.ReplayOut) == 8 * 8
@@ -50,7 +50,8 @@ def _build_rc(tg, p):
         setattr(d, n, int(p[n]))
     d.order_policy = int(p.get("order_policy", 0))
     keep = []
-    tg._fill(d, p, [f[0] for f in tg.ProblemDesc._fields_[8:]], keep)
+    tg._fill(d, p, [f[0] for f in tg.ProblemDesc._fields_[8:-2]], keep)
+    d.n_services = int(p.get("n_services", len(p["restore_us"]) if p.get("restore_us") is not None else 0))
     h = C.c_void_p()
     rc = tg.load().tg_build_problem(C.byref(d), None, C.byref(h))
     assert rc != 0 and not h.value
@@ -110,6 +111,23 @@ def test_second_resource_arrays_come_in_pairs(tg):
     assert _build_rc(tg, q) == -1
     q = dict(p, act_aux=np.full(30, -1, np.int32), node_aux_free=np.zeros(p["M"], np.int32))
     assert _build_rc(tg, q) == -1                              # negative demand
+
+
+def test_service_arrays_are_validated(tg):
+    p = gen.make_random_problem(11, B=1, N=30)
+    M = p["M"]
+    full = dict(act_service=np.zeros(30, np.int32), node_resident=np.zeros(M, np.uint64), restore_us=np.array([5, 6], np.int64))
+    for missing in full:
+        q = dict(p, **{k: v for k, v in full.items() if k != missing})
+        assert _build_rc(tg, dict(q, n_services=2)) == -1      # all three arrays or none
+    assert _build_rc(tg, dict(p, **full, n_services=0)) == -1
+    assert _build_rc(tg, dict(p, **full, n_services=65)) == -1
+    q = dict(p, **full); q["act_service"] = np.full(30, 2, np.int32)
+    assert _build_rc(tg, q) == -1                              # service id out of range
+    q = dict(p, **full); q["node_resident"] = np.full(M, 4, np.uint64)
+    assert _build_rc(tg, q) == -1                              # resident bit of a service that does not exist
+    q = dict(p, **full); q["restore_us"] = np.array([5, 1 << 36], np.int64)
+    assert _build_rc(tg, q) == -2
 
 
 def test_cost_order_needs_pools_it_can_sort(tg):

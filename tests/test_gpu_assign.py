@@ -188,6 +188,54 @@ def _add_second_resource(p, seed, scarce):
     return p
 
 
+def _add_services(p, seed, n_services=6, resident_frac=0.5, big=False):
+    """Which service every action calls, which services every node caches, restore times (Sec. 5.3)."""
+    rng = np.random.default_rng(seed + 900)
+    n, m = p["B"] * p["N"], p["B"] * p["M"]
+    p["act_service"] = rng.integers(-1, n_services, n).astype(np.int32)
+    bits = rng.random((m, n_services)) < resident_frac
+    res = np.zeros(m, np.uint64)
+    for sv in range(n_services):
+        res |= bits[:, sv].astype(np.uint64) << np.uint64(sv)
+    p["node_resident"] = res
+    unit = 40_000_000_000 if big else 250_000                  # big: delays beyond 32 bits
+    p["restore_us"] = np.minimum(rng.integers(0, 9, n_services) * unit, (1 << 36) - 1).astype(np.int64)
+    return p
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_assign_services_random_problems(tg, orc, seed):
+    print("case services", seed, flush=True)
+    p = gen.make_random_problem(600 + seed, B=3, N=150 + 60 * seed, n_cpu=2 + seed % 4, n_gpu=1 + seed % 3, n_api=seed % 2,
+                                depth=1 + seed % 3, busy=seed % 2 == 0, cpu_cap_hi=32 + 16 * (seed % 3), pin_frac=0.3)
+    p["act_kmask"][p["act_type"] == gen.TYPE_CPU] |= 1
+    base = orc.assign(p)
+    _add_services(p, seed, n_services=(3, 17, 64)[seed % 3], big=seed == 7)
+    p["order_policy"] = seed % 2
+    if seed % 4 == 3:
+        _add_second_resource(p, seed, scarce=True)
+    want = orc.assign(p)
+    _compare(_assign_gpu(tg, p, use_cost=seed % 3 == 1), want, f"services {seed}")
+    if p["order_policy"] == 0 and seed % 4 != 3:
+        assert (base["act_us"] != want["act_us"]).any(), "restore delays should show"
+
+
+def test_assign_services_code_paths(tg, orc):
+    for case in ("pool_150_cpu_70_gpu_nodes", "pool_300_cpu_nodes", "pool_1100_cpu_nodes", "cap_256_nodes", "long_pinned_queues",
+                 "dp_totals_beyond_30_bits"):
+        for order in (0, 1):
+            print("case services", case, order, flush=True)
+            p = _add_services(_code_path_problem(case), 6, n_services=9)
+            p["order_policy"] = order
+            _compare(_assign_gpu(tg, p), orc.assign(p), f"services {case} order {order}")
+
+
+def test_assign_services_config2_full(tg, orc):
+    """Workload 2 at full size with 8 services cached on half of the nodes each."""
+    p = _add_services(gen.make_config(2), 2, n_services=8)
+    _compare(_assign_gpu(tg, p), orc.assign(p))
+
+
 @pytest.mark.parametrize("seed", range(8))
 def test_assign_second_resource_random_problems(tg, orc, seed):
     print("case second resource", seed, flush=True)
@@ -230,6 +278,8 @@ def _sweep_problem(seed):
     p["order_policy"] = int(rng.integers(0, 2))
     if rng.random() < 0.5:
         _add_second_resource(p, seed, scarce=bool(rng.integers(0, 2)))
+    if rng.random() < 0.5:
+        _add_services(p, seed, n_services=int(rng.choice([1, 5, 64])), big=bool(rng.integers(0, 2)))
     return p, bool(rng.integers(0, 2))
 
 

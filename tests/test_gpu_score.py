@@ -39,6 +39,19 @@ def test_score_random_problems(tg, orc, seed):
     np.testing.assert_array_equal(got, want)
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_score_with_services(tg, orc, seed):
+    """Entries whose action calls a service that is not resident on the node carry its restore time (Sec. 5.3)."""
+    from test_gpu_assign import _add_services
+    print("case services", seed, flush=True)
+    p = gen.make_random_problem(50 + seed, B=3, N=200 + 150 * seed, n_cpu=2 + seed % 4, n_gpu=1 + seed % 3, n_api=seed % 2)
+    base = orc.score(p)
+    _add_services(p, seed, n_services=(2, 20, 64)[seed % 3], big=seed == 5)
+    want = orc.score(p)
+    assert (want != base).any()
+    np.testing.assert_array_equal(_score_gpu(tg, p), want)
+
+
 def test_score_config1(tg, orc):
     p = gen.make_config(1)
     np.testing.assert_array_equal(_score_gpu(tg, p), orc.score(p))
