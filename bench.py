@@ -24,9 +24,9 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of tg_score_kernel on workload 2 from the FETCH_SIZE / WRITE_SIZE counter runs
-# (profiles/score_config2_hbm_counters.md): 537 696.2 KiB written x 1.000 + 5 642.6 KiB fetched x 2.000.
+# (profiles/score_config2_hbm_counters.md): 537 704.4 KiB written x 1.000 + 5 642.5 KiB fetched x 2.000.
 # Valid for the kernel as profiled; set to None when tg_score_kernel changes.
-SCORE_TRAFFIC_CONFIG2_BYTES = int((537696.2 + 2.0 * 5642.6) * 1024)
+SCORE_TRAFFIC_CONFIG2_BYTES = int((537704.4 + 2.0 * 5642.5) * 1024)
 
 
 def order_section(a, tg, torch, p, s_fcfs):
