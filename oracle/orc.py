@@ -65,10 +65,11 @@ SUMMARY_DTYPE = np.dtype([("sum_act_us", "<i8"), ("n_assigned", "<i4"), ("n_pref
 
 
 class Trace(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("S", "A", "M", "K", "n_classes", "depth", "max_ticks", "pad_")] + [
+    _fields_ = [(n, C.c_int32) for n in ("S", "A", "M", "K", "n_classes", "depth", "max_ticks", "cache_slots")] + [
         ("tick_us", C.c_int64)] + [(n, C.c_void_p) for n in (
             "k_list", "type_k", "speedup_q16", "node_type", "node_cap", "quota_rate", "quota_tok0_micro",
-            "arrival_us", "act_type", "act_model", "act_t_ori_us", "act_kmask", "act_param", "act_pin_node")]
+            "arrival_us", "act_type", "act_model", "act_t_ori_us", "act_kmask", "act_param", "act_pin_node",
+            "act_service", "restore_us")]
 
 
 _DT = dict(k_list=np.int32, type_k=np.int32, speedup_q16=np.uint32, node_type=np.uint8, node_cap=np.int32,
@@ -139,6 +140,7 @@ def _trace(t):
     for n in ("S", "A", "M", "K", "n_classes", "depth", "max_ticks"):
         setattr(s, n, int(t[n]))
     s.tick_us = int(t["tick_us"])
+    s.cache_slots = int(t.get("cache_slots", 64))
     _fill(s, t, [f[0] for f in Trace._fields_[9:]], keep)
     return s, keep
 

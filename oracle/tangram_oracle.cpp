@@ -418,12 +418,13 @@ struct orc_summary {
 };
 
 struct orc_trace {
-  int32_t S, A, M, K, n_classes, depth, max_ticks, pad_;
+  int32_t S, A, M, K, n_classes, depth, max_ticks, cache_slots;   // cache_slots: services a node keeps resident
   int64_t tick_us;
   const int32_t* k_list; const int32_t* type_k; const uint32_t* speedup_q16;
   const uint8_t* node_type; const int32_t* node_cap; const int32_t* quota_rate; const int64_t* quota_tok0_micro;
   const int64_t* arrival_us; const uint8_t* act_type; const uint8_t* act_model; const int64_t* act_t_ori_us;
   const uint32_t* act_kmask; const uint32_t* act_param; const int32_t* act_pin_node;
+  const int32_t* act_service; const int64_t* restore_us;           // both or neither (Sec. 5.3)
 };
 
 }  // extern "C"
@@ -609,7 +610,7 @@ int orc_mask_alloc(int* mask, int k) { return mask_alloc(*mask, k); }
 
 void orc_replay(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us, int64_t* finish_us, int32_t* units,
                 int32_t* node, double* mean_act, int64_t* p99_act, int32_t* n_started, int32_t* n_ticks) {
-  const Tables tb{t->K, t->k_list, t->type_k, t->speedup_q16, t->depth};
+  const Tables tb{t->K, t->k_list, t->type_k, t->speedup_q16, t->depth, t->act_service ? t->restore_us : nullptr};
   const int A = t->A, M = t->M;
   for (int s = s_lo; s < s_hi; ++s) {
     const size_t a0 = (size_t)s * A, n0 = (size_t)s * M;
@@ -617,6 +618,11 @@ void orc_replay(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us, int64
     std::vector<Run> running;
     std::vector<int> rem(M, 0), gmask(M, 0);
     std::vector<int64_t> tok(M, 0);
+    // Sec. 5.3: every node caches up to cache_slots services; a restored service stays resident
+    // until it is the least recently used one when room is needed.  Nothing is resident at first.
+    std::vector<uint64_t> resident(M, 0);
+    std::vector<int64_t> used_at((size_t)M * 64, 0);        // per node and service: sequence number of its last use
+    std::vector<int64_t> seq(M, 0);
     for (int j = 0; j < M; ++j) {
       rem[j] = t->node_cap[n0 + j];
       if (t->node_type[n0 + j] == T_GPU) gmask[j] = (1 << t->node_cap[n0 + j]) - 1;
@@ -647,11 +653,13 @@ void orc_replay(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us, int64
       std::vector<Act> acts;
       for (int i : waiting)
         acts.push_back(Act{t->act_type[a0 + i], t->act_model[a0 + i], t->act_t_ori_us[a0 + i], now - t->arrival_us[a0 + i],
-                           t->act_kmask[a0 + i], t->act_param[a0 + i], t->act_pin_node[a0 + i], 0});
+                           t->act_kmask[a0 + i], t->act_param[a0 + i], t->act_pin_node[a0 + i], 0, 0,
+                           t->act_service ? t->act_service[a0 + i] : -1});
       std::vector<Node> nodes(M);
       for (int j = 0; j < M; ++j) {
         Node& nd = nodes[j];
         nd.type = t->node_type[n0 + j]; nd.cap = t->node_cap[n0 + j]; nd.backlog = 0;
+        nd.resident = resident[j];
         for (int x = 0; x < 4; ++x) nd.chunks[x] = 0;
         if (nd.type == T_API) nd.free = (int)(tok[j] / 1000000);
         else if (nd.type == T_GPU) { mask_chunks(gmask[j], nd.chunks); nd.free = __builtin_popcount(gmask[j]); }
@@ -668,7 +676,19 @@ void orc_replay(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us, int64
         if (o.node[w] < 0) { still.push_back(i); continue; }
         const int j = o.node[w], k = o.units[w];
         int q = 0; while (tb.k_list[q] != k) ++q;
-        const int64_t dur = duration(tb, acts[w], q);
+        // realised = modelled duration: the delay is the one the step saw (residency at the tick's start)
+        const int64_t dur = restore_delay(tb, acts[w], nodes[j]) + duration(tb, acts[w], q);
+        const int sv = acts[w].service;
+        if (sv >= 0 && tb.restore_us) {                      // the service is (now) resident and most recently used
+          if (!(resident[j] >> sv & 1ull) && __builtin_popcountll(resident[j]) >= t->cache_slots) {
+            int victim = -1;
+            for (int x = 0; x < 64; ++x)
+              if ((resident[j] >> x & 1ull) && (victim < 0 || used_at[(size_t)j * 64 + x] < used_at[(size_t)j * 64 + victim])) victim = x;
+            resident[j] &= ~(1ull << victim);
+          }
+          resident[j] |= 1ull << sv;
+          used_at[(size_t)j * 64 + sv] = ++seq[j];
+        }
         Run u{now + dur, j, k, 0};
         if (nodes[j].type == T_API) tok[j] -= (int64_t)k * 1000000;
         else {
