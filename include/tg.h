@@ -191,7 +191,8 @@ int tg_assign(const tg_problem *p, const int64_t *d_cost, const tg_assign_out *o
  * time: finished actions release their units, quotas refill (micro-tokens, capped at the bucket
  * size node_cap), arrived actions join the waiting queue in arrival order, one scheduling step
  * (as tg_assign, backlog 0, completion heap seeded with the running actions) selects actions,
- * which start at the tick and run for exactly getDur(k).  Action arrays have S*A entries and
+ * which start at the tick and run for exactly getDur(k) (after the restore delay of their
+ * service, if any).  Action arrays have S*A entries and
  * must be sorted by arrival within a scenario; node arrays have S*M entries.
  */
 typedef struct {
@@ -210,6 +211,16 @@ typedef struct {
   const int64_t *act_t_ori_us;
   const uint32_t *act_kmask, *act_param;
   const int32_t *act_pin_node;
+  /* Services of GPU actions (Sec. 5.3), both arrays or neither: every node keeps up to cache_slots
+   * services resident in device memory, none at time 0.  An action whose service was not resident
+   * on its node when the tick began is delayed by restore_us[service] (the step of that tick
+   * estimated with the same residency); starting an action makes its service resident and the
+   * most recently used one, evicting the least recently used (smaller id on ties) when the node
+   * already holds cache_slots others.  Only actions of kind GPU may call a service. */
+  const int32_t *act_service;       /* [S*A] service id in [0, n_services), or negative: none    */
+  const int64_t *restore_us;        /* [n_services] in [0, 2^36)                                 */
+  int32_t n_services;               /* 1..TG_MAX_SERVICES                                        */
+  int32_t cache_slots;              /* 1..TG_MAX_SERVICES                                        */
 } tg_trace_desc;
 
 /* Device outputs of tg_replay_trace. */

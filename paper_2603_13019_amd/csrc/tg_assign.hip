@@ -203,7 +203,7 @@ __global__ __launch_bounds__(TG_WAVE) void tg_place_kernel(TgDev P, const int64_
   if (cost) { const TgBlock blk = blocks[b * 3 + t]; io.cost = cost + blk.cost_off; io.cost_row_len = blk.M_t * blk.K_t; }
   io.out_node = O.node + abase; io.out_units = O.units + abase; io.out_act = O.act_us + abase;
   io.out_reason = O.defer_reason + abase; io.slot = W.slot + abase;
-  tg_place_pool<16, true>(S, io, acts, Nt, Mt, t == TG_TYPE_GPU, lane);
+  tg_place_pool<16, 16>(S, io, acts, Nt, Mt, t == TG_TYPE_GPU, lane);
 
   tg_pool_extents(S, nodes, Mt, a0, W.nl_off + nbase, W.nl_cnt + nbase, W.dl_off + nbase, W.dl_cnt + nbase, lane);
 }

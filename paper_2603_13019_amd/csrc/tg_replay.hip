@@ -18,7 +18,7 @@
 #include "tg_step.h"
 
 struct TgTraceDev {
-  int S, A, M, K, n_classes, depth, max_ticks, pad_;
+  int S, A, M, K, n_classes, depth, max_ticks, cache_slots;
   int64_t tick_us;
   int k_list[TG_MAX_K];
   int type_k[4];
@@ -27,6 +27,8 @@ struct TgTraceDev {
   const int64_t* arrival; const uint8_t* act_type; const uint8_t* act_model; const uint8_t* act_static;
   const int64_t* act_T; const uint32_t* act_kmask; const uint32_t* act_param; const int32_t* act_pin;
   const uint32_t* speedup;
+  const int32_t* act_service;     // [S*A] service of a GPU action or -1; nullptr: the trace has no services (Sec. 5.3)
+  const int64_t* restore;         // [TG_MAX_SERVICES]
 };
 
 struct tg_trace {
@@ -53,6 +55,10 @@ struct ReplayWs {
   int32_t *nl_off, *nl_cnt, *dl_off, *dl_cnt;   // [S*M]
   int32_t* live_free;  // [S*M] free cores / free-GPU mask
   int64_t* live_tok;   // [S*M]
+  // service cache (only with services)
+  uint64_t* live_res;  // [S*M] services resident on the node
+  int32_t* used_at;    // [S*M*64] per node and service: sequence number of its last use
+  int32_t* use_seq;    // [S*M] uses counted so far
 };
 
 size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
@@ -66,7 +72,10 @@ size_t carve(const TgTraceDev& T, char* base, ReplayWs* w) {
   p[5] = take(nA * 8); p[6] = take(nA * 4); p[7] = take(nA);
   for (int x = 8; x < 13; ++x) p[x] = take(nN * 4);
   p[13] = take(nN * 8);
+  const bool svc = T.act_service != nullptr;
+  char* q0 = take(svc ? nN * 8 : 0); char* q1 = take(svc ? nN * 64 * 4 : 0); char* q2 = take(svc ? nN * 4 : 0);
   if (w) {
+    w->live_res = (uint64_t*)q0; w->used_at = (int32_t*)q1; w->use_seq = (int32_t*)q2;
     w->dur = (int64_t*)p[0]; w->slot = (int32_t*)p[1]; w->order = (int32_t*)p[2]; w->dorder = (int32_t*)p[3];
     w->wlist = (int32_t*)p[4]; w->run_fin = (int64_t*)p[5]; w->run_info = (int32_t*)p[6]; w->reason = (uint8_t*)p[7];
     w->nl_off = (int32_t*)p[8]; w->nl_cnt = (int32_t*)p[9]; w->dl_off = (int32_t*)p[10]; w->dl_cnt = (int32_t*)p[11];
@@ -195,6 +204,7 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
     live_free[j] = ty == TG_TYPE_GPU ? (int)((1u << cap) - 1u) : cap;
     live_tok[j] = ty == TG_TYPE_API ? T.quota_tok0[nbase + j] : 0;
     nl_cnt[j] = 0; dl_cnt[j] = 0;
+    if (T.act_service) { W.live_res[nbase + j] = 0; W.use_seq[nbase + j] = 0; }   // nothing resident at time 0
   }
   if (tid == 0) { s_wcnt[0] = s_wcnt[1] = s_wcnt[2] = 0; s_next = 0; s_started = 0; s_nrun = 0; }
   __syncthreads();
@@ -295,16 +305,17 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
         S.lim[r] = ty == TG_TYPE_GPU ? (int32_t)mask_chunks((uint32_t)live_free[j])
                  : ty == TG_TYPE_API ? (int32_t)(live_tok[j] / 1000000) : live_free[j];
         S.cnt[r] = 0; S.dcnt[r] = 0; S.closed[r] = 0;
+        if (T.act_service) S.res[r] = W.live_res[nbase + j];
       }
       tg_wave_sync();
       TgPlaceIo io;
       io.act_kmask = T.act_kmask + abase; io.act_static = T.act_static + abase; io.act_pin = T.act_pin + abase;
       io.act_aux = nullptr;                                       // traces carry no second resource
-      io.act_service = nullptr; io.restore = nullptr;             // and no services
+      io.act_service = T.act_service ? T.act_service + abase : nullptr; io.restore = T.restore;
       io.node_rank = T.node_rank + nbase; io.nodes = nodes; io.dur = dur; io.cost = nullptr; io.cost_row_len = 0;
       io.K = K; io.Kt = T.type_k[ty];
       io.out_node = o_node; io.out_units = o_units; io.out_act = nullptr; io.out_reason = reason; io.slot = slot;
-      tg_place_pool(S, io, wl[ty], wcs[ty], Mt, ty == TG_TYPE_GPU, lane);
+      tg_place_pool<4, 1>(S, io, wl[ty], wcs[ty], Mt, ty == TG_TYPE_GPU, lane);
       tg_pool_extents(S, nodes, Mt, woff[ty], nl_off, nl_cnt, dl_off, dl_cnt, lane);
     }
     __threadfence_block();
@@ -356,7 +367,8 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
       in.n_busy = nb; in.busy = nullptr; in.busy_lds_off = plan.total;
       in.act_model = T.act_model + abase; in.act_kmask = T.act_kmask + abase; in.dur = dur; in.K = K; in.depth = T.depth;
       in.kword = tg_pack_k(T.k_list);
-      in.act_service = nullptr; in.restore = nullptr; in.resident = 0;
+      in.act_service = T.act_service ? T.act_service + abase : nullptr; in.restore = T.restore;
+      in.resident = T.act_service ? W.live_res[nbase + j] : 0;
       TgNodeOut out;
       out.node = o_node; out.units = o_units; out.act = nullptr; out.reason = reason; out.age = nullptr;
       int used_units;
@@ -374,7 +386,13 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
         const int k = o_units[id];
         int q = 0;
         while (q < K - 1 && T.k_list[q] != k) ++q;
-        const int64_t fin = now + dur[(size_t)id * K + q];
+        // realised = modelled duration: the restore delay is the one the step saw (residency at the tick's start)
+        int64_t delay = 0;
+        if (T.act_service && ty == TG_TYPE_GPU) {
+          const int sv = T.act_service[abase + id];
+          if (sv >= 0 && !(W.live_res[nbase + j] >> sv & 1ull)) delay = T.restore[sv];
+        }
+        const int64_t fin = now + delay + dur[(size_t)id * K + q];
         o_start[id] = now; o_fin[id] = fin;
         atomicAdd(&s_started, 1);
         if (ty == TG_TYPE_API) { atomicAdd((unsigned long long*)&live_tok[j], (unsigned long long)(-(int64_t)k * 1000000)); }
@@ -384,11 +402,16 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
           run_fin[d] = fin; run_info[d] = j | k << 16;
         }
       }
+    if (T.act_service) __syncthreads();                           // the residency of the tick's start has been read
     for (int r = tid; r < T.tnode_off[s * 4 + 2] - T.tnode_off[s * 4 + 1]; r += kThreads) {
       const int j = T.tnode_idx[nbase + T.tnode_off[s * 4 + 1] + r];
       const int m = nl_cnt[j];
       if (m == 0) continue;
       uint32_t mk = (uint32_t)live_free[j];
+      const uint64_t res0 = T.act_service ? W.live_res[nbase + j] : 0;
+      uint64_t res = res0;
+      int32_t* used = W.used_at + (nbase + j) * 64;
+      int seq = T.act_service ? W.use_seq[nbase + j] : 0;
       for (int x = 0; x < m; ++x) {
         const int id = order[nl_off[j] + x];
         if (o_node[id] < 0) break;                                // evicted tail
@@ -397,9 +420,26 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
         while (q < K - 1 && T.k_list[q] != k) ++q;
         const int g0 = mask_alloc(mk, k) & 7;
         const int d = atomicAdd(&s_nrun, 1);
-        run_fin[d] = now + dur[(size_t)id * K + q]; run_info[d] = j | k << 16 | g0 << 24;
+        int64_t delay = 0;
+        const int sv = T.act_service ? T.act_service[abase + id] : -1;
+        if (sv >= 0) {
+          if (!(res0 >> sv & 1ull)) delay = T.restore[sv];
+          // the service is resident from now on and the most recently used one (Sec. 5.3, LRU)
+          if (!(res >> sv & 1ull) && __popcll(res) >= T.cache_slots) {
+            int victim = -1;
+            for (uint64_t left = res; left; left &= left - 1) {   // ascending id: the smaller one wins ties
+              const int y = __builtin_ctzll(left);
+              if (victim < 0 || used[y] < used[victim]) victim = y;
+            }
+            res &= ~(1ull << victim);
+          }
+          res |= 1ull << sv;
+          used[sv] = ++seq;
+        }
+        run_fin[d] = now + delay + dur[(size_t)id * K + q]; run_info[d] = j | k << 16 | g0 << 24;
       }
       live_free[j] = (int)mk;
+      if (T.act_service) { W.live_res[nbase + j] = res; W.use_seq[nbase + j] = seq; }
     }
     for (int j = tid; j < M; j += kThreads) { nl_cnt[j] = 0; dl_cnt[j] = 0; }
     __threadfence_block();
@@ -464,6 +504,12 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
   const int S = d->S, A = d->A, M = d->M, K = d->K;
   if (S < 1 || A < 1 || M < 1 || d->flags != 0 || d->max_ticks < 1 || d->tick_us < 1) return TG_E_INVALID_ARG;
   if (d->depth < 1 || d->depth > TG_MAX_DEPTH) return TG_E_INVALID_ARG;
+  const bool svc = d->act_service != nullptr;
+  if (svc != (d->restore_us != nullptr)) return TG_E_INVALID_ARG;
+  if (svc) {
+    if (d->n_services < 1 || d->n_services > TG_MAX_SERVICES || d->cache_slots < 1 || d->cache_slots > TG_MAX_SERVICES) return TG_E_INVALID_ARG;
+    for (int x = 0; x < d->n_services; ++x) if (d->restore_us[x] < 0 || d->restore_us[x] >= TG_T_ORI_LIMIT) return TG_E_RANGE;
+  }
   if (A > TG_MAX_ACTIONS || M > 65535 || (int64_t)S * A >= (1ll << 31) || (int64_t)S * M >= (1ll << 31)) return TG_E_RANGE;
   if (d->tick_us >= TG_TIME_LIMIT || (int64_t)d->max_ticks * d->tick_us >= (1ll << 44)) return TG_E_RANGE;
   if (K < 1 || K > TG_MAX_K || !d->k_list || !d->type_k) return TG_E_INVALID_ARG;
@@ -497,6 +543,7 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
                  o_tnidx = add(nN * 4), o_tnoff = add((size_t)S * 16);
     const size_t o_arr = add(nA * 8), o_atype = add(nA), o_amodel = add(nA), o_astat = add(nA), o_aT = add(nA * 8),
                  o_amask = add(nA * 4), o_aparam = add(nA * 4), o_apin = add(nA * 4);
+    const size_t o_asvc = add(svc ? nA * 4 : 0), o_rest = add(svc ? TG_MAX_SERVICES * 8 : 0);
     const size_t o_speed = add(std::max<size_t>((size_t)d->n_classes * K, 1) * 4);
     auto at = [&](size_t off) { return host.data() + off; };
     int max_kind = 0, max_cap_cpu = 0, max_heap = 0;
@@ -555,6 +602,11 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
           else infeasible = kmin > max_cap[(size_t)s * 3 + ty];
         }
         if (pin >= M) pin = M;
+        if (svc) {
+          const int sv = d->act_service[g] < 0 ? -1 : d->act_service[g];
+          if (sv >= d->n_services || (sv >= 0 && ty != TG_TYPE_GPU)) { delete t; return TG_E_INVALID_ARG; }
+          ((int32_t*)at(o_asvc))[g] = sv;
+        }
         ((int64_t*)at(o_arr))[g] = arr;
         ((uint8_t*)at(o_atype))[g] = (uint8_t)ty;
         ((uint8_t*)at(o_amodel))[g] = (uint8_t)model;
@@ -567,6 +619,7 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
       if (sumT >= TG_SUM_T_LIMIT) { delete t; return TG_E_RANGE; }
     }
     if (d->n_classes) std::memcpy(at(o_speed), d->speedup_q16, (size_t)d->n_classes * K * 4);
+    if (svc) std::memcpy(at(o_rest), d->restore_us, (size_t)d->n_services * 8);
 
     t->arena_bytes = host.size();
     if (hipMalloc(&t->d_arena, t->arena_bytes) != hipSuccess) { delete t; return TG_E_NOMEM; }
@@ -590,6 +643,9 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
     v.act_model = (const uint8_t*)(base + o_amodel); v.act_static = (const uint8_t*)(base + o_astat);
     v.act_T = (const int64_t*)(base + o_aT); v.act_kmask = (const uint32_t*)(base + o_amask);
     v.act_param = (const uint32_t*)(base + o_aparam); v.act_pin = (const int32_t*)(base + o_apin);
+    v.act_service = svc ? (const int32_t*)(base + o_asvc) : nullptr;
+    v.restore = svc ? (const int64_t*)(base + o_rest) : nullptr;
+    v.cache_slots = svc ? d->cache_slots : 0;
     v.speedup = (const uint32_t*)(base + o_speed);
     t->max_nodes_of_kind = max_kind; t->max_cap_cpu = max_cap_cpu; t->max_heap = max_heap;
     for (int k = 0; k < 3; ++k) t->max_nodes_kind[k] = max_of_kind[k];

@@ -324,17 +324,19 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
 // On return S.cnt / S.dcnt hold the list lengths per node and every action has its reason,
 // node (-1 if deferred) and list slot written.
 // MAXR: the widest register variant the caller wants compiled in (1, 4 or 16 slots per lane);
-// AUXOK: whether the caller ever passes a second resource (io.act_aux) or services (io.act_service).
-template <int MAXR = 4, bool AUXOK = false>
+// MAXR_EXT: the same for the extended variant, taken when the caller passes a second resource
+// (io.act_aux) or services (io.act_service); 0: never (such pools then use the LDS table).
+template <int MAXR = 4, int MAXR_EXT = 0>
 __device__ static inline void tg_place_pool(const TgPoolLds& S, const TgPlaceIo& io, const int32_t* acts, int Nt,
                                             int Mt, bool gpu, int lane) {
   if (!io.cost && Mt <= 16 * TG_WAVE) {
     const int slots = Mt <= TG_WAVE ? 1 : Mt <= 4 * TG_WAVE ? 4 : 16;
-    if (slots <= MAXR) {
-      if (AUXOK && (io.act_aux || io.act_service)) {
-        if (slots == 1) tg_place_pool_regs<1, AUXOK>(S, io, acts, Nt, Mt, gpu, lane);
-        else if (slots == 4) tg_place_pool_regs<(MAXR >= 4 ? 4 : 1), AUXOK>(S, io, acts, Nt, Mt, gpu, lane);
-        else tg_place_pool_regs<(MAXR >= 16 ? 16 : 1), AUXOK>(S, io, acts, Nt, Mt, gpu, lane);
+    const bool ext = io.act_aux || io.act_service;
+    if (ext ? slots <= MAXR_EXT : slots <= MAXR) {
+      if (ext) {
+        if (slots == 1) tg_place_pool_regs<1, (MAXR_EXT >= 1)>(S, io, acts, Nt, Mt, gpu, lane);
+        else if (slots == 4) tg_place_pool_regs<(MAXR_EXT >= 4 ? 4 : 1), (MAXR_EXT >= 1)>(S, io, acts, Nt, Mt, gpu, lane);
+        else tg_place_pool_regs<(MAXR_EXT >= 16 ? 16 : 1), (MAXR_EXT >= 1)>(S, io, acts, Nt, Mt, gpu, lane);
       } else {
         if (slots == 1) tg_place_pool_regs<1, false>(S, io, acts, Nt, Mt, gpu, lane);
         else if (slots == 4) tg_place_pool_regs<(MAXR >= 4 ? 4 : 1), false>(S, io, acts, Nt, Mt, gpu, lane);

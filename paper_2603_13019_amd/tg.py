@@ -43,7 +43,8 @@ class TraceDesc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("S", "A", "M", "K", "n_classes", "depth", "max_ticks")] + [
         ("flags", C.c_uint32), ("tick_us", C.c_int64)] + [(n, C.c_void_p) for n in (
             "k_list", "type_k", "speedup_q16", "node_type", "node_cap", "quota_rate", "quota_tok0_micro",
-            "arrival_us", "act_type", "act_model", "act_t_ori_us", "act_kmask", "act_param", "act_pin_node")]
+            "arrival_us", "act_type", "act_model", "act_t_ori_us", "act_kmask", "act_param", "act_pin_node",
+            "act_service", "restore_us")] + [("n_services", C.c_int32), ("cache_slots", C.c_int32)]
 
 
 class ReplayOut(C.Structure):
@@ -212,7 +213,9 @@ class Trace:
         d.flags = 0
         d.tick_us = int(t["tick_us"])
         keep = []
-        _fill(d, t, [f[0] for f in TraceDesc._fields_[9:]], keep)
+        _fill(d, t, [f[0] for f in TraceDesc._fields_[9:-2]], keep)
+        d.n_services = len(t["restore_us"]) if t.get("restore_us") is not None else 0
+        d.cache_slots = int(t.get("cache_slots", 64))
         h = C.c_void_p()
         _check(L.tg_build_trace(C.byref(d), _stream(), C.byref(h)), "tg_build_trace")
         self._h = h

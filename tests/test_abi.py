@@ -39,7 +39,7 @@ def test_strerror(tg):
 def test_struct_layouts_match_header(tg):
     assert C.sizeof(tg.ProblemDesc) == 8 * 4 + 23 * 8 + 2 * 4
     assert C.sizeof(tg.AssignOut) == 8 * 8
-    assert C.sizeof(tg.TraceDesc) == 8 * 4 + 8 + 14 * 8
+    assert C.sizeof(tg.TraceDesc) == 8 * 4 + 8 + 16 * 8 + 2 * 4
     assert C.sizeof(tg.ReplayOut) == 8 * 8
     assert tg.SUMMARY_DTYPE.itemsize == 8 + 16 + 24 + 24 + 8 + 24
 
@@ -103,6 +103,24 @@ def test_build_rejects_gpu_specifics(tg):
         assert _build_rc(tg, q) == -1
 
 
+def test_trace_services_are_validated(tg):
+    t = gen.make_trace(S=2, A=50, seed=3, contended=True)
+    n = t["S"] * t["A"]
+    gpu = t["act_type"] == gen.TYPE_GPU
+    sv = np.where(gpu, 0, -1).astype(np.int32)
+    ok = dict(act_service=sv, restore_us=np.array([5, 6], np.int64), cache_slots=2)
+    assert _trace_rc(tg, dict(t, act_service=sv)) == -1                      # both arrays or neither
+    assert _trace_rc(tg, dict(t, restore_us=ok["restore_us"])) == -1
+    assert _trace_rc(tg, dict(t, **ok, n_services=0)) == -1
+    assert _trace_rc(tg, dict(t, **dict(ok, cache_slots=0))) == -1
+    assert _trace_rc(tg, dict(t, **dict(ok, cache_slots=65))) == -1
+    assert _trace_rc(tg, dict(t, **dict(ok, act_service=np.where(gpu, 2, -1).astype(np.int32)))) == -1   # id out of range
+    cpu_calls = sv.copy()
+    cpu_calls[np.flatnonzero(~gpu)[0]] = 1
+    assert _trace_rc(tg, dict(t, **dict(ok, act_service=cpu_calls))) == -1   # only GPU actions call services
+    assert _trace_rc(tg, dict(t, **dict(ok, restore_us=np.array([5, 1 << 36], np.int64)))) == -2
+
+
 def test_second_resource_arrays_come_in_pairs(tg):
     p = gen.make_random_problem(10, B=1, N=30)
     q = dict(p, act_aux=np.zeros(30, np.int32))
@@ -158,7 +176,9 @@ def _trace_rc(tg, t):
     d.flags = 0
     d.tick_us = int(t["tick_us"])
     keep = []
-    tg._fill(d, t, [f[0] for f in tg.TraceDesc._fields_[9:]], keep)
+    tg._fill(d, t, [f[0] for f in tg.TraceDesc._fields_[9:-2]], keep)
+    d.n_services = int(t.get("n_services", len(t["restore_us"]) if t.get("restore_us") is not None else 0))
+    d.cache_slots = int(t.get("cache_slots", 64))
     h = C.c_void_p()
     rc = tg.load().tg_build_trace(C.byref(d), None, C.byref(h))
     assert rc != 0 and not h.value

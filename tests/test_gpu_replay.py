@@ -76,8 +76,42 @@ def test_replay_random_sweep(tg, orc):
                            rate_per_s=float(rng.choice([20.0, 100.0, 500.0])), horizon_s=float(rng.choice([1.0, 5.0, 20.0])),
                            max_ticks=int(rng.choice([60, 5000, 60000])), pin_frac=float(rng.choice([0.0, 0.3, 0.8])))
         t["depth"] = int(rng.integers(1, 5))
+        if n_gpu and rng.random() < 0.6:
+            _with_services(t, seed, n_services=int(rng.choice([1, 4, 20])), slots=int(rng.choice([1, 2, 5])))
         _compare(_replay_gpu(tg, t), orc.replay(t), range(t["S"]), t["A"])
     print("60 traces compared", flush=True)
+
+
+def _with_services(t, seed, n_services, slots):
+    rng = np.random.default_rng(seed)
+    sv = rng.integers(-1, n_services, t["S"] * t["A"]).astype(np.int32)
+    sv[t["act_type"] != gen.TYPE_GPU] = -1                     # services live on GPU nodes
+    t["act_service"] = sv
+    t["restore_us"] = (rng.integers(0, 9, n_services) * 150_000).astype(np.int64)
+    t["cache_slots"] = slots
+    return t
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_replay_service_cache(tg, orc, seed):
+    """Restore delays and the per-node LRU cache of resident services (Sec. 5.3)."""
+    print("case service cache", seed, flush=True)
+    t = gen.make_trace(S=3, A=500 + 100 * seed, seed=170 + seed, cluster=(1 + seed % 2, 16, 1 + seed % 3, seed % 2),
+                       type_probs=(0.2, 0.7, 0.1) if seed % 2 else (0.3, 0.7, 0.0),
+                       rate_per_s=(30.0, 60.0, 150.0)[seed % 3], horizon_s=12.0, max_ticks=80000, pin_frac=0.3)
+    base = orc.replay(t)
+    _with_services(t, seed, n_services=(2, 5, 9, 64)[seed % 4], slots=(1, 2, 3, 64)[(seed // 2) % 4])
+    want = orc.replay(t)
+    assert (want["finish_us"] != base["finish_us"]).any()
+    _compare(_replay_gpu(tg, t), want, range(t["S"]), t["A"])
+
+
+def test_replay_service_cache_many_gpu_nodes(tg, orc):
+    """More than 64 GPU nodes: the pool with services takes the LDS node table."""
+    t = gen.make_trace(S=2, A=1500, seed=181, cluster=(0, 0, 70, 0), type_probs=(0, 1, 0), rate_per_s=400.0, horizon_s=4.0,
+                       max_ticks=80000, pin_frac=0.2)
+    _with_services(t, 9, n_services=12, slots=2)
+    _compare(_replay_gpu(tg, t), orc.replay(t), range(t["S"]), t["A"])
 
 
 def test_replay_depth_and_ties(tg, orc):
