@@ -102,6 +102,23 @@ def replay_section(a, tg, gen, torch):
         T.free()
     res["ablation_mean_act_us"] = dict(abl, workload="64 scenarios x 2000 CPU actions at 30/s on 4 nodes x 32 cores",
                                        elastic_vs_dop4=abl["dop4"] / abl["elastic"], elastic_vs_dop16=abl["dop16"] / abl["elastic"])
+    # service cache (evict on execution, LRU): the same GPU trace with room for 1, 2 and all 6 services per node
+    import numpy as np
+    t = gen.make_trace(S=64, A=2000, seed=8, cluster=(0, 0, 4, 0), type_probs=(0, 1, 0), rate_per_s=20.0,
+                       horizon_s=100.0, max_ticks=400000, pin_frac=0.0)
+    rng = np.random.default_rng(8)
+    t["act_service"] = rng.integers(0, 6, t["S"] * t["A"]).astype(np.int32)
+    t["restore_us"] = np.full(6, 2_000_000, np.int64)
+    cache = {}
+    for slots in (1, 2, 6):
+        t["cache_slots"] = slots
+        T = tg.Trace(t)
+        bufs = T.replay()
+        torch.cuda.synchronize()
+        cache[f"slots_{slots}"] = float(bufs["mean_act_us"].mean().item())
+        T.free()
+    res["service_cache_mean_act_us"] = dict(cache, workload="64 scenarios x 2000 GPU actions at 20/s on 4 nodes x 8 GPUs, "
+                                                           "6 services, 2 s to restore one")
     return res
 
 
