@@ -41,13 +41,13 @@ enum { TG_OK = 0, TG_E_INVALID_ARG = -1, TG_E_RANGE = -2, TG_E_ELASTICITY = -3, 
 
 /* resource kinds (Sec. 5) and elasticity models of an action (Sec. 4.1, Eq. 1) */
 enum { TG_TYPE_CPU = 0, TG_TYPE_GPU = 1, TG_TYPE_API = 2, TG_N_TYPES = 3 };
-enum { TG_MODEL_NONE = 0,   /* elasticity unknown: runs for T_ori on its minimum units (Alg. 1 l.5-6) */
+enum { TG_MODEL_NONE = 0,   /* elasticity unknown: runs for T_ori on its minimum units (Alg. 1)        */
        TG_MODEL_AMDAHL = 1, /* E(k) = 1/((1-p)k+p), p = act_param in parts per million             */
        TG_MODEL_TABLE = 2   /* E(k)*k = speedup_q16[act_param][q] / 65536                           */ };
 /* why an action was not selected in this step */
 enum { TG_SELECTED = 0,
-       TG_DEFER_PREFIX = 1,     /* behind the first action of its pool that did not fit (Alg. 1 l.2) */
-       TG_DEFER_EVICTED = 2,    /* admitted, then evicted by the greedy tail eviction (Alg. 1 l.9-13) */
+       TG_DEFER_PREFIX = 1,     /* behind the first action of its pool that did not fit (Alg. 1)  */
+       TG_DEFER_EVICTED = 2,    /* admitted, then evicted by the greedy tail eviction (Alg. 1)      */
        TG_DEFER_INFEASIBLE = 3  /* no allowed unit count fits any node it may use, or bad pin        */ };
 
 /* Order in which tg_assign visits the waiting queue of a pool.  The paper schedules first come

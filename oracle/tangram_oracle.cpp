@@ -283,7 +283,7 @@ StepOut step(const Tables& tb, const std::vector<Act>& acts, std::vector<Node> n
     std::stable_sort(visit.begin(), visit.end(), [&](int x, int y) { return key[x] < key[y]; });
   }
 
-  // Alg. 1 l.1-2: prefix of the visiting order admitted with minimum units; node choice by least estimated ACT
+  // Alg. 1, admission: prefix of the visiting order admitted with minimum units; node choice by least estimated ACT
   // Second, co-constrained resource (Sec. 4.1: the cost of an action is a vector; Sec. 5.2: a node
   // must have the cores for the action and the memory for the whole trajectory when the
   // trajectory's first action is placed).  An action that is free to choose its node needs
@@ -331,7 +331,7 @@ StepOut step(const Tables& tb, const std::vector<Act>& acts, std::vector<Node> n
     placed[bj].push_back(i);
   }
 
-  // Alg. 1 l.3-14 per node: DPArrange + greedy tail eviction on the approximated objective
+  // Alg. 1, per node: DPArrange + greedy tail eviction on the approximated objective
   for (int j = 0; j < M; ++j) {
     const std::vector<int>& C = placed[j];
     const int m = (int)C.size();

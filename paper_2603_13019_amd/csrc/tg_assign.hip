@@ -1,10 +1,10 @@
 // tg_assign: one scheduling step (Alg. 1 of the paper) for every snapshot of a problem.
 //
 //   tg_dur_kernel      Eq. 1 once per (action, option)              fully parallel
-//   tg_place_kernel    Alg. 1 l.1-2: FCFS admission at minimum units, node choice by least
+//   tg_place_kernel    Alg. 1's prefix admission at minimum units, node choice by least
 //                      estimated completion time (Eq. 2)            one wavefront per (snapshot, kind)
 //   tg_lists_kernel    groups admitted / waiting-pinned actions by node, FCFS inside a node
-//   tg_node_kernel     Alg. 1 l.3-14 per node: DPArrange (Alg. 3 / Alg. 4) + greedy tail
+//   tg_node_kernel     the rest of Alg. 1 per node: DPArrange (Alg. 3 / Alg. 4) + greedy tail
 //                      eviction on the approximated objective (Alg. 2)   one wavefront per node
 //   tg_summary_kernel  per-snapshot sums, counts, utilisation
 //

@@ -1,10 +1,10 @@
 // Wavefront-level building blocks of one scheduling step, shared by tg_assign (one snapshot
 // per launch slot) and tg_replay_trace (one step per tick inside a persistent workgroup).
 //
-//   tg_place_pool      Alg. 1 l.1-2 for one resource kind: admission in visiting order at minimum units
+//   tg_place_pool      Alg. 1's admission of a queue prefix for one resource kind: in visiting order, at minimum units,
 //                      with node choice by least estimated completion time (Eq. 2), node table in
 //                      registers (pools of up to 1024 nodes) or LDS
-//   tg_node_schedule   Alg. 1 l.3-14 for one node: DPArrange (Alg. 3; Alg. 4 chunk states on GPU
+//   tg_node_schedule   the rest of Alg. 1 for one node: DPArrange (Alg. 3; Alg. 4 chunk states on GPU
 //                      nodes), completion-heap estimate (Alg. 2), greedy tail eviction
 //
 // Both are executed by ONE wavefront (64 lanes) with uniform control flow; `__syncthreads()`
@@ -1001,7 +1001,7 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
     if (lane == 0) s_F[NW] = any_el ? 1 : 0;
   }
   team_sync();
-  if (s_F[NW] == 0) {                                             // Alg. 1 l.5-6: nothing to scale
+  if (s_F[NW] == 0) {                                             // Alg. 1: no elastic action in the group, nothing to scale
     int used = 0;
     if (wave == 0) {
       for (int x = lane; x < m; x += TG_WAVE) {
@@ -1197,7 +1197,7 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
     return s_rowbest[L] + (int64_t)L * in.backlog + approx;
   };
 
-  // ---- Alg. 1 l.8-13: evict from the tail while the objective drops ------------------------
+  // ---- Alg. 1's eviction loop: evict from the tail while the objective drops ----------------
   // Round by round, wavefront w evaluates the prefix length base - w; the values are then
   // consumed in decreasing length exactly as the sequential loop would.
   int L = m;                                                       // accepted length
