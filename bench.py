@@ -138,7 +138,7 @@ def main():
                     help="also run plain device copies of the score tensor's size (reference for the HBM byte counters)")
     a = ap.parse_args()
     if a.gpus != 1:
-        print("bench.py measures one GPU: every box of this build has a single MI355X and the path uses no "
+        print("bench.py measures one GPU: the path runs on a single MI355X and uses no "
               "collectives; run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 

@@ -57,7 +57,7 @@ def test_replay_is_deterministic(tg):
 
 
 def test_build_problem_time_is_reported(tg):
-    """Boundary-inclusive cost: the formulation stage takes host buffers.  Printed for the design doc."""
+    """Boundary-inclusive cost: the formulation stage takes host buffers; its time is printed."""
     import torch
     p = gen.make_config(2)
     t0 = time.perf_counter()
