@@ -292,6 +292,24 @@ def test_assign_random_sweep(tg, orc):
     print("200 problems compared", flush=True)
 
 
+@pytest.mark.parametrize("case", ["max_actions_per_snapshot", "max_nodes_of_a_kind"])
+def test_assign_at_the_limits(tg, orc, case):
+    """The largest snapshot (131 072 actions) and the largest pool (4096 nodes of one kind) the interface takes."""
+    print("case", case, flush=True)
+    if case == "max_actions_per_snapshot":
+        p = gen.make_random_problem(77, B=1, N=131072, n_cpu=500, n_gpu=0, n_api=0, cpu_cap_hi=64, busy=False, pin_frac=0.2,
+                                    k_list=(1, 2, 4, 8, 16, 32, 48, 64))
+        cap = 64
+    else:
+        p = gen.make_random_problem(78, B=1, N=16000, n_cpu=4096, n_gpu=0, n_api=0, cpu_cap_hi=8, busy=False, pin_frac=0.2)
+        cap = 8
+    p["type_k"][gen.TYPE_GPU] = 0
+    _roomy(p, cap, 0.999, 1)
+    want = orc.assign(p)
+    assert (want["reason"] == 0).sum() > 5000 and (want["reason"] == 2).any()
+    _compare(_assign_gpu(tg, p), want, case)
+
+
 def test_assign_config1(tg, orc):
     p = gen.make_config(1)
     want = orc.assign(p)
