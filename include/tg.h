@@ -21,7 +21,11 @@
  *     their host-to-device copies have completed).  Results are valid once the caller has
  *     synchronised the stream.
  *   - A tg_problem / tg_trace is immutable after it is built and owns only its packed device
- *     copy of the inputs.  No other entry point allocates device memory.
+ *     copy of the inputs (plus, for a tg_problem, two internal streams and their events on
+ *     which tg_assign runs part of its work, forked from and joined back into `hip_stream`).
+ *     No other entry point allocates device memory.  Launches that use the same tg_problem may
+ *     be in flight together (each with its own outputs and workspace), but the host calls that
+ *     enqueue them must not overlap: one thread at a time per tg_problem.
  *   - Index of an action inside its snapshot == its first-come rank == its action id.
  */
 #ifndef TG_H_
