@@ -1,6 +1,7 @@
 // tg_assign: one scheduling step (Alg. 1 of the paper) for every snapshot of a problem.
 //
 //   tg_dur_kernel      Eq. 1 once per (action, option)              fully parallel
+//   tg_order_kernel    only for the second visiting order: keys + sort of every pool's queue
 //   tg_place_kernel    Alg. 1's prefix admission at minimum units, node choice by least
 //                      estimated completion time (Eq. 2)            one wavefront per (snapshot, kind)
 //   tg_lists_kernel    groups admitted / waiting-pinned actions by node, FCFS inside a node
@@ -8,9 +9,11 @@
 //                      eviction on the approximated objective (Alg. 2)   one wavefront per node
 //   tg_summary_kernel  per-snapshot sums, counts, utilisation
 //
-// The FCFS loop is sequential by definition (every action sees the capacity left by the ones
-// before it), so tg_place_kernel keeps the node table of its pool in LDS and spends its 64
-// lanes on the argmin over nodes; parallelism comes from the batch of snapshots.
+// The admission loop is sequential by definition (every action sees the capacity left by the
+// ones before it), so tg_place_kernel keeps the node table of its pool in registers (LDS for
+// very wide pools) and spends its 64 lanes on the argmin over nodes; parallelism comes from the
+// batch of snapshots.  The per-node stage runs as three concurrent launches, one per class of
+// candidate count, whose persistent wavefronts pull nodes from class lists.
 #include <algorithm>
 
 #include "tg_step.h"

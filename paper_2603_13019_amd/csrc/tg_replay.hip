@@ -2,14 +2,16 @@
 //
 // Every tick the workgroup runs the same scheduling step as tg_assign (the wavefront-level
 // functions of tg_step.h) on the scenario's live state: the three resource pools are placed by
-// three wavefronts in parallel, the nodes that received candidates are spread over all
-// wavefronts for DPArrange + eviction, and selected actions start at the tick.  The tick loop
+// three wavefronts in parallel, the nodes that received candidates are spread over the
+// wavefronts that own a per-node LDS block for DPArrange + eviction, and selected actions start
+// at the tick (GPU nodes also update their cache of resident services then).  The tick loop
 // is bounded by max_ticks, so every wavefront leaves the kernel.
 //
 // Live state per scenario (global workspace, L2 resident): free cores per CPU node, free-GPU
 // bit mask per GPU node (a free chunk is a maximal aligned free block, so releasing coalesces
-// by itself), micro-tokens per quota, the running set (finish, node, units, first GPU), and
-// one FCFS waiting list per resource kind.
+// by itself), micro-tokens per quota, the running set (finish, node, units, first GPU), one
+// FCFS waiting list per resource kind and, with services, the resident set of every node with
+// the last use of each service.
 #include <algorithm>
 #include <cstring>
 #include <new>
