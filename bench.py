@@ -57,6 +57,38 @@ def order_section(a, tg, torch, p, s_fcfs):
                                         "cost": float(s["sum_act_us"].sum()) / max(sel_c, 1)}}
 
 
+def core_sets_section(a, tg, gen, torch, p):
+    """The same workload with a core map per CPU node (NUMA domains of 16 cores): tg_assign then also names the
+    cores of every selected CPU action.  Time of tg_assign with that output, and how many of the selected
+    multi-core actions got all their cores inside one domain."""
+    import numpy as np
+    q = gen.with_core_maps(dict(p), 16, 2)
+    P = tg.Problem(q)
+    bufs = P.alloc_assign()
+    for _ in range(3):
+        P.assign(None, bufs)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n = max(5, a.steps // 5)
+    e0.record()
+    for _ in range(n):
+        P.assign(None, bufs)
+    e1.record()
+    torch.cuda.synchronize()
+    sets = bufs["core_set"].cpu().numpy().view(np.uint64).reshape(-1, 4)
+    units = bufs["units"].cpu().numpy()
+    P.free()
+    multi = np.flatnonzero((units > 1) & sets.any(axis=1))
+    one = 0
+    for g in multi:
+        dom = set()
+        for w in range(4):
+            v = int(sets[g][w])
+            dom |= {(64 * w + c) // 16 for c in range(0, 64, 16) if v >> c & 0xffff}
+        one += len(dom) == 1
+    return {"assign_ms": e0.elapsed_time(e1) / n, "numa_cores": 16, "multi_core_actions": int(len(multi)),
+            "in_one_domain": int(one)}
+
+
 def replay_section(a, tg, gen, torch):
     """Workload 5 (batched trace replay): S scenarios x 10 000 Poisson arrivals over 200 s, rescheduling every
     100 ms, on the default cluster (256x128 cores, 32x8 GPUs, 16 quotas) and on the contended one (4x32 cores,
@@ -213,6 +245,7 @@ def main():
 
     if a.only == "step":
         out["order_policy_cost"] = order_section(a, tg, torch, p, s)
+        out["core_sets"] = core_sets_section(a, tg, gen, torch, p)
     if a.replay_scenarios > 0 and a.only == "step":
         out["replay"] = replay_section(a, tg, gen, torch)
 

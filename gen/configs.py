@@ -392,7 +392,7 @@ def slice_problem(p, snapshots):
     snapshots = list(snapshots)
     q = dict(p)
     q["B"] = len(snapshots)
-    for k in PROBLEM_ARRAYS + ("gpu_mask_",):
+    for k in PROBLEM_ARRAYS + ("gpu_mask_", "node_aux_free", "act_aux", "act_service", "node_resident", "node_core_free"):
         v = p.get(k)
         if v is None or k in ("k_list", "type_k", "speedup_q16", "node_busy_off", "node_busy_rel_us"):
             continue
@@ -404,6 +404,22 @@ def slice_problem(p, snapshots):
         q["node_busy_off"] = np.concatenate([[0], np.cumsum(cnt)]).astype(np.int32)
         q["node_busy_rel_us"] = np.concatenate([rel[off[b * M]:off[(b + 1) * M]] for b in snapshots] + [np.zeros(0, np.int64)])
     return q
+
+
+def with_core_maps(p, numa_cores, seed=0):
+    """Adds the core topology of the CPU nodes to a problem (in place): cores in NUMA domains of
+    ``numa_cores`` consecutive ids, and per node a random bitmap (4 x uint64) of its free cores with
+    exactly ``node_free`` bits below ``node_cap``.  Other nodes get an empty map."""
+    rng = np.random.default_rng(seed + 4242)
+    m = p["B"] * p["M"]
+    maps = np.zeros((m, 4), np.uint64)
+    for j in np.flatnonzero(p["node_type"] == TYPE_CPU):
+        cores = rng.choice(int(p["node_cap"][j]), int(p["node_free"][j]), replace=False)
+        for c in cores:
+            maps[j, c // 64] |= np.uint64(1) << np.uint64(c % 64)
+    p["node_core_free"] = maps.reshape(-1)
+    p["numa_cores"] = int(numa_cores)
+    return p
 
 
 def with_fixed_dop(t, k):

@@ -122,8 +122,14 @@ typedef struct {
   const int32_t *act_service;     /* [B*N] service id in [0, n_services), or negative: none     */
   const uint64_t *node_resident;  /* [B*M] bit s set <=> service s is resident on the node       */
   const int64_t *restore_us;      /* [n_services] in [0, 2^36)                                   */
+  /* Core topology of the CPU nodes (Sec. 5.2: the manager names the cores an action runs on and
+   * prefers cores of one NUMA domain).  Cores [d*numa_cores, (d+1)*numa_cores) of a node form its
+   * domain d.  node_core_free: per node four 64-bit words, bit c%64 of word c/64 set <=> core c is
+   * free; on CPU nodes exactly node_free bits, none at or above node_cap; ignored on other nodes.
+   * NULL: no topology (then numa_cores must be 0 and tg_assign_out.core_set NULL). */
+  const uint64_t *node_core_free; /* [B*M*4] */
   int32_t n_services;             /* 1..TG_MAX_SERVICES                                          */
-  int32_t reserved_;              /* 0                                                           */
+  int32_t numa_cores;             /* 4, 8, 16, 32 or 64 with node_core_free                      */
 } tg_problem_desc;
 
 /* Per-snapshot result of tg_assign.  Only mean_act_us and util are floating point. */
@@ -145,6 +151,13 @@ typedef struct {
   int32_t *node_used;    /* [B*M] units handed out per node; optional                           */
   int64_t *task_sum_us;  /* [B*n_tasks] sum of ACT per task; optional                           */
   int64_t *node_obj;     /* [B*M] final approximated objective (Alg. 2) of nodes that ran the eviction loop, else -1; optional */
+  /* [B*N*4] the cores of every selected CPU action as a bitmap laid out like node_core_free, zero
+   * for all other actions; optional, needs a problem built with node_core_free.  The selected
+   * actions of a node take their cores one after the other in visiting order: if a domain has
+   * `units` free cores, from the domain with the fewest free cores that still has them (lowest
+   * domain on ties); otherwise whole domains, the one with the most free cores first (lowest on
+   * ties), which spans the fewest domains; inside a domain the lowest-numbered free cores. */
+  uint64_t *core_set;
 } tg_assign_out;
 
 /*

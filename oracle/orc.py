@@ -50,7 +50,7 @@ class Problem(C.Structure):
             "k_list", "type_k", "speedup_q16", "node_type", "node_cap", "node_free", "node_backlog_us",
             "node_chunks", "node_busy_off", "node_busy_rel_us", "act_type", "act_model", "act_t_ori_us",
             "act_age_us", "act_kmask", "act_param", "act_pin_node", "act_task", "node_aux_free", "act_aux",
-            "act_service", "node_resident", "restore_us")]
+            "act_service", "node_resident", "restore_us", "node_core_free")] + [("numa_cores", C.c_int32)]
 
 
 class Summary(C.Structure):
@@ -77,7 +77,8 @@ _DT = dict(k_list=np.int32, type_k=np.int32, speedup_q16=np.uint32, node_type=np
            node_busy_rel_us=np.int64, act_type=np.uint8, act_model=np.uint8, act_t_ori_us=np.int64,
            act_age_us=np.int64, act_kmask=np.uint32, act_param=np.uint32, act_pin_node=np.int32,
            act_task=np.int32, quota_rate=np.int32, quota_tok0_micro=np.int64, arrival_us=np.int64,
-           node_aux_free=np.int32, act_aux=np.int32, act_service=np.int32, node_resident=np.uint64, restore_us=np.int64)
+           node_aux_free=np.int32, act_aux=np.int32, act_service=np.int32, node_resident=np.uint64, restore_us=np.int64,
+           node_core_free=np.uint64)
 
 
 def lib():
@@ -92,7 +93,9 @@ def lib():
         L.orc_score.restype = None
         L.orc_score.argtypes = [C.c_void_p, C.c_void_p]
         L.orc_assign.restype = None
-        L.orc_assign.argtypes = [C.c_void_p] * 10
+        L.orc_assign.argtypes = [C.c_void_p] * 11
+        L.orc_take_cores.restype = C.c_int
+        L.orc_take_cores.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
         L.orc_dp_units.restype = C.c_int64
         L.orc_dp_units.argtypes = [C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
         L.orc_dp_chunks.restype = C.c_int64
@@ -130,7 +133,8 @@ def _problem(p):
     for n in ("B", "N", "M", "K", "n_classes", "n_tasks", "depth"):
         setattr(s, n, int(p[n]))
     s.order_policy = int(p.get("order_policy", 0))      # 0: first come first served, 1: least estimated ACT first
-    _fill(s, p, [f[0] for f in Problem._fields_[8:]], keep)
+    _fill(s, p, [f[0] for f in Problem._fields_[8:-1]], keep)
+    s.numa_cores = int(p.get("numa_cores", 0))          # cores per NUMA domain (with node_core_free)
     return s, keep
 
 
@@ -169,10 +173,21 @@ def assign(p):
                reason=np.empty(B * N, np.uint8), summary=np.zeros(B, SUMMARY_DTYPE),
                node_used=np.empty(B * M, np.int32), task_sum=np.empty(B * int(p["n_tasks"]), np.int64),
                node_obj=np.empty(B * M, np.int64), home=np.empty(B * N, np.int32))
+    if p.get("node_core_free") is not None:
+        out["core_set"] = np.zeros(B * N * 4, np.uint64)
     assert SUMMARY_DTYPE.itemsize == C.sizeof(Summary)
     lib().orc_assign(C.addressof(s), *[out[k].ctypes.data for k in
-                                       ("node", "units", "act_us", "reason", "summary", "node_used", "task_sum", "node_obj", "home")])
+                                       ("node", "units", "act_us", "reason", "summary", "node_used", "task_sum", "node_obj", "home")],
+                     out["core_set"].ctypes.data if "core_set" in out else None)
     return out
+
+
+def take_cores(free, numa_cores, k):
+    """One allocation on a 0/1 map of free cores; returns (core ids, map afterwards)."""
+    f = np.ascontiguousarray(free, np.uint8).copy()
+    got = np.zeros(max(int(k), 1), np.int32)
+    n = lib().orc_take_cores(f.ctypes.data, len(f), int(numa_cores), int(k), got.ctypes.data)
+    return [int(x) for x in got[:n]], f
 
 
 def dp_units(dur, k_list, U):

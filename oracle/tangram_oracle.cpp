@@ -9,6 +9,7 @@
 //   * Alg. 3 (App. B)       DPArrange over used units (basic operator)
 //   * Alg. 4 (App. B)       DPArrange over free-chunk states (GPU operator, sizes 1/2/4/8)
 //   * Sec. 5.1-5.3          capacity models: quota, per-node cores + trajectory pin, buddy chunks
+//   * Sec. 5.2              which cores an action gets: one NUMA domain if any can hold it
 // It shares no code, header, table or helper with the HIP library; only tests, the
 // smoke check and the benchmark's CPU-baseline leg may call it.
 //
@@ -56,6 +57,7 @@ struct Node {
   int64_t backlog;
   int chunks[4];               // free chunks of size 1,2,4,8 (GPU nodes)
   std::vector<int64_t> busy;   // release time of every unit held by a running action
+  std::vector<char> core_free; // [cap] 1: the core is free (CPU nodes of a problem that gives the core topology)
 };
 
 // ---- Eq. 1: getDur(m) = T_ori / (E(m) * m), rounded up to whole microseconds -------------
@@ -119,6 +121,42 @@ bool chunk_take(int c[4], int k) {                    // smallest chunk of level
       return true;
     }
   return false;
+}
+
+// ---- Sec. 5.2: the set of cores of an action ----------------------------------------------
+// Cores [d*numa, (d+1)*numa) form NUMA domain d.  The manager names the cores an action runs
+// on and prefers cores of one domain.  Reading used here: if some domain has k free cores, take
+// the domain with the fewest free cores among those (the least leftover; lowest domain on ties);
+// otherwise take whole domains, the one with the most free cores first (lowest on ties), which
+// spans as few domains as k cores can; inside a domain the lowest-numbered free cores go first.
+// Returns the chosen cores in increasing order and clears them in `free_`.
+std::vector<int> take_cores(std::vector<char>& free_, int numa, int k) {
+  const int cap = (int)free_.size(), D = (cap + numa - 1) / numa;
+  auto count = [&](int d) { int c = 0; for (int x = d * numa; x < std::min(cap, (d + 1) * numa); ++x) c += free_[x]; return c; };
+  std::vector<int> got;
+  auto take_from = [&](int d, int want) {
+    for (int x = d * numa; x < std::min(cap, (d + 1) * numa) && want > 0; ++x)
+      if (free_[x]) { free_[x] = 0; got.push_back(x); --want; }
+  };
+  int best = -1;
+  for (int d = 0; d < D; ++d) {
+    const int c = count(d);
+    if (c >= k && (best < 0 || c < count(best))) best = d;
+  }
+  if (best >= 0) take_from(best, k);
+  else {
+    int left = k;
+    while (left > 0) {
+      int big = -1;
+      for (int d = 0; d < D; ++d) if (count(d) > 0 && (big < 0 || count(d) > count(big))) big = d;
+      if (big < 0) break;                              // fewer than k free cores: the caller never asks for that
+      const int c = std::min(count(big), left);
+      take_from(big, c);
+      left -= c;
+    }
+  }
+  std::sort(got.begin(), got.end());
+  return got;
 }
 
 // ---- Alg. 3: DPArrange with the basic operator (state = units used) ----------------------
@@ -235,6 +273,7 @@ struct StepOut {
   std::vector<uint8_t> reason;
   std::vector<int64_t> node_obj;                      // final approximated objective per node, -1 if none
   std::vector<int32_t> home;                          // node an action was admitted to (kept when evicted)
+  std::vector<std::vector<int>> cores;                // cores of every selected CPU action (numa_cores > 0)
 };
 
 // Order in which a pool's waiting queue is visited (Sec. 4.2: FCFS in the paper, and the
@@ -244,11 +283,12 @@ struct StepOut {
 enum { ORDER_FCFS = 0, ORDER_COST = 1 };
 
 // ---- one scheduling step on one snapshot (Alg. 1 applied per resource pool) -------------
-StepOut step(const Tables& tb, const std::vector<Act>& acts, std::vector<Node> nodes, int order_policy = ORDER_FCFS) {
+StepOut step(const Tables& tb, const std::vector<Act>& acts, std::vector<Node> nodes, int order_policy = ORDER_FCFS,
+             int numa_cores = 0) {
   const int N = (int)acts.size(), M = (int)nodes.size(), K = tb.K;
   StepOut o;
   o.node.assign(N, -1); o.units.assign(N, 0); o.act.assign(N, -1); o.reason.assign(N, R_NONE);
-  o.node_obj.assign(M, -1); o.home.assign(N, -1);
+  o.node_obj.assign(M, -1); o.home.assign(N, -1); o.cores.assign(N, {});
 
   // static infeasibility: no option, bad pin, or minimum units above every candidate node
   std::vector<int> kmin(N, 0);
@@ -380,12 +420,15 @@ StepOut step(const Tables& tb, const std::vector<Act>& acts, std::vector<Node> n
       }
       o.node_obj[j] = obj;
     }
+    std::vector<char> core_free = nd.core_free;
     for (int x = 0; x < m; ++x) {
       const int i = C[x];
       if (x >= L) { o.node[i] = -1; o.reason[i] = R_EVICTED; continue; }
       int q = 0; while (tb.k_list[q] != ks[x]) ++q;
       o.units[i] = ks[x];
       o.act[i] = acts[i].age + nd.backlog + restore_delay(tb, acts[i], nd) + duration(tb, acts[i], q);
+      // Sec. 5.2: the selected actions of a node name their cores one after the other, in visiting order
+      if (numa_cores > 0 && nd.type == T_CPU) o.cores[i] = take_cores(core_free, numa_cores, ks[x]);
     }
   }
   return o;
@@ -408,6 +451,7 @@ struct orc_problem {
   const uint32_t* act_kmask; const uint32_t* act_param; const int32_t* act_pin_node; const int32_t* act_task;
   const int32_t* node_aux_free; const int32_t* act_aux;     // both or neither; NULL: no second resource
   const int32_t* act_service; const uint64_t* node_resident; const int64_t* restore_us;   // all or none
+  const uint64_t* node_core_free; int32_t numa_cores;       // [B*M*4] free-core bitmaps of CPU nodes, or NULL (then numa_cores = 0)
 };
 
 struct orc_summary {
@@ -462,6 +506,10 @@ std::vector<Node> nodes_of(const orc_problem* p, int b) {
     }
     if (p->node_busy_off)
       nd.busy.assign(p->node_busy_rel_us + p->node_busy_off[g], p->node_busy_rel_us + p->node_busy_off[g + 1]);
+    if (p->node_core_free && nd.type == T_CPU) {
+      nd.core_free.resize(nd.cap);
+      for (int c = 0; c < nd.cap; ++c) nd.core_free[c] = (char)(p->node_core_free[g * 4 + c / 64] >> (c % 64) & 1ull);
+    }
   }
   return v;
 }
@@ -514,12 +562,13 @@ void orc_score(const orc_problem* p, int64_t* cost) {
 }
 
 void orc_assign(const orc_problem* p, int32_t* node, int32_t* units, int64_t* act_us, uint8_t* reason,
-                orc_summary* summary, int32_t* node_used, int64_t* task_sum, int64_t* node_obj, int32_t* home) {
+                orc_summary* summary, int32_t* node_used, int64_t* task_sum, int64_t* node_obj, int32_t* home,
+                uint64_t* core_set) {
   const Tables tb = tables_of(p);
   for (int b = 0; b < p->B; ++b) {
     const std::vector<Act> acts = acts_of(p, b);
     const std::vector<Node> nodes = nodes_of(p, b);
-    const StepOut o = step(tb, acts, nodes, p->order_policy);
+    const StepOut o = step(tb, acts, nodes, p->order_policy, p->node_core_free ? p->numa_cores : 0);
     const size_t a0 = (size_t)b * p->N, n0 = (size_t)b * p->M;
     orc_summary s;
     std::memset(&s, 0, sizeof s);
@@ -544,7 +593,21 @@ void orc_assign(const orc_problem* p, int32_t* node, int32_t* units, int64_t* ac
     if (summary) summary[b] = s;
     if (node_obj) for (int j = 0; j < p->M; ++j) node_obj[n0 + j] = o.node_obj[j];
     if (home) for (int i = 0; i < p->N; ++i) home[a0 + i] = o.home[i];
+    if (core_set)
+      for (int i = 0; i < p->N; ++i) {
+        for (int w = 0; w < 4; ++w) core_set[(a0 + i) * 4 + w] = 0;
+        for (int c : o.cores[i]) core_set[(a0 + i) * 4 + c / 64] |= 1ull << (c % 64);
+      }
   }
+}
+
+// One allocation of Sec. 5.2 on a map of free cores (free_[c] = 0/1, updated); cores_out gets the k core ids.
+int orc_take_cores(uint8_t* free_, int cap, int numa_cores, int k, int32_t* cores_out) {
+  std::vector<char> f(free_, free_ + cap);
+  const std::vector<int> got = take_cores(f, numa_cores, k);
+  for (int c = 0; c < cap; ++c) free_[c] = (uint8_t)f[c];
+  for (size_t x = 0; x < got.size(); ++x) cores_out[x] = got[x];
+  return (int)got.size();
 }
 
 int64_t orc_dp_units(int m, const int64_t* dur, const int32_t* k_list, int K, int U, int32_t* k_out) {

@@ -7,6 +7,7 @@
 //   tg_lists_kernel    groups admitted / waiting-pinned actions by node, FCFS inside a node
 //   tg_node_kernel     the rest of Alg. 1 per node: DPArrange (Alg. 3 / Alg. 4) + greedy tail
 //                      eviction on the approximated objective (Alg. 2)   one wavefront per node
+//   tg_cores_kernel    (problems with a core topology) the cores of every selected CPU action, Sec. 5.2
 //   tg_summary_kernel  per-snapshot sums, counts, utilisation
 //
 // The admission loop is sequential by definition (every action sees the capacity left by the
@@ -380,6 +381,87 @@ __global__ __launch_bounds__(256) void tg_summary_kernel(TgDev P, tg_assign_out 
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Sec. 5.2: which cores every selected CPU action runs on.  One wavefront per node, lane d holds
+// the free cores of NUMA domain d (a domain has 4..64 cores, so it lies inside one 64-bit word
+// of the node's map and a node of up to 256 cores has at most 64 domains).  The node's selected
+// actions take their cores one after the other in the order of its candidate list.
+
+// the k lowest set bits of m (1 <= k <= popcount(m)): binary descent to the k-th set bit
+__device__ static inline uint64_t tg_lowest_bits(uint64_t m, int k) {
+  if (k <= 4) {                                                   // the usual case: peel the bits off one by one
+    uint64_t rest = m;
+    for (int x = 0; x < k; ++x) rest &= rest - 1;
+    return m ^ rest;
+  }
+  int pos = 0, r = k;
+#pragma unroll
+  for (int w = 32; w >= 1; w >>= 1) {
+    const int c = __popcll((m >> pos) & ((1ull << w) - 1));
+    if (r > c) { pos += w; r -= c; }
+  }
+  return m & ((2ull << pos) - 1);
+}
+
+__global__ __launch_bounds__(256) void tg_cores_clear_kernel(unsigned long long* core_set, size_t n) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) core_set[i] = 0;
+}
+
+constexpr int kCoresWaves = 4;
+
+__global__ __launch_bounds__(kCoresWaves * TG_WAVE) void tg_cores_kernel(TgDev P, AssignWs W, tg_assign_out O) {
+  const int wave = threadIdx.x / TG_WAVE, lane = threadIdx.x % TG_WAVE;
+  const size_t gn = (size_t)blockIdx.x * kCoresWaves + wave;
+  if (gn >= (size_t)P.B * P.M || P.node_type[gn] != TG_TYPE_CPU) return;       // the wavefronts of a workgroup never meet
+  const int m = W.nl_cnt[gn];
+  if (m == 0) return;
+  const size_t abase = (gn / P.M) * (size_t)P.N;
+  const int32_t* list = W.order + abase + W.nl_off[gn];
+  const int nc = P.numa_cores, cap = P.node_cap[gn];
+  const int n_dom = (cap + nc - 1) / nc;
+  const int word = (lane * nc) >> 6, shift = (lane * nc) & 63;
+  uint64_t dm = 0;                                                // free cores of this lane's domain
+  if (lane < n_dom) {
+    dm = P.node_cores[gn * 4 + word] >> shift;
+    if (nc < 64) dm &= (1ull << nc) - 1;
+  }
+  for (int base = 0; base < m; base += TG_WAVE) {
+    const int n = m - base < TG_WAVE ? m - base : TG_WAVE;
+    const int my_a = lane < n ? list[base + lane] : 0;
+    const int my_k = lane < n ? O.units[abase + my_a] : 0;
+    for (int l = 0; l < n; ++l) {
+      const int a = __builtin_amdgcn_readlane(my_a, l), k = __builtin_amdgcn_readlane(my_k, l);
+      if (k == 0) continue;                                       // evicted: no cores
+      int cnt = __popcll(dm);
+      uint64_t take = 0;
+      // the domain with the fewest free cores that holds all k; key = (free cores, domain)
+      const uint32_t fit = tg_wave_min_u32(cnt >= k ? (uint32_t)cnt << 8 | (uint32_t)lane : 0xffffffffu);
+      const bool one_domain = fit != 0xffffffffu;
+      if (one_domain) {
+        if (lane == (int)(fit & 0xff)) take = tg_lowest_bits(dm, k);
+      } else {
+        // no domain holds k: whole domains, most free cores first, until k cores are found
+        int left = k;
+        while (left > 0) {
+          const uint32_t big = tg_wave_min_u32(cnt > 0 ? (uint32_t)(64 - cnt) << 8 | (uint32_t)lane : 0xffffffffu);
+          if (big == 0xffffffffu) break;                          // cannot happen: a node hands out at most its free cores
+          const int have = 64 - (int)(big >> 8), t = have < left ? have : left;
+          if (lane == (int)(big & 0xff)) { take = tg_lowest_bits(dm, t); cnt -= t; }
+          left -= t;
+        }
+      }
+      dm ^= take;
+      // the map of every action was cleared before this kernel: only the words that get cores are touched
+      if (take) {
+        unsigned long long* dst = (unsigned long long*)O.core_set + (abase + a) * 4 + word;
+        if (one_domain) *dst = take << shift;
+        else atomicOr(dst, (unsigned long long)(take << shift));  // several domains may share a word; OR commutes
+      }
+    }
+  }
+}
+
 }  // namespace
 
 extern "C" int tg_assign_workspace_bytes(const tg_problem* p, size_t* bytes) {
@@ -392,6 +474,7 @@ extern "C" int tg_assign(const tg_problem* p, const int64_t* d_cost, const tg_as
                          size_t ws_bytes, void* hip_stream) {
   if (!p || !out || !out->node || !out->units || !out->act_us || !out->defer_reason || !out->summary)
     return TG_E_INVALID_ARG;
+  if (out->core_set && !p->dev.node_cores) return TG_E_INVALID_ARG;
   if (!d_ws || ((uintptr_t)d_ws & 255) || ws_bytes < carve(p, nullptr, nullptr)) return TG_E_WORKSPACE;
   hipStream_t s = (hipStream_t)hip_stream;
   const TgDev& P = p->dev;
@@ -450,6 +533,12 @@ extern "C" int tg_assign(const tg_problem* p, const int64_t* d_cost, const tg_as
     if (c < 2) TG_HIP_CHECK(hipEventRecord(p->ev_join[c], cs));
   }
   for (int c = 0; c < 2; ++c) TG_HIP_CHECK(hipStreamWaitEvent(s, p->ev_join[c], 0));
+  if (out->core_set) {
+    hipLaunchKernelGGL(tg_cores_clear_kernel, dim3((unsigned)((nA * 4 + 255) / 256)), dim3(256), 0, s,
+                       (unsigned long long*)out->core_set, nA * 4);
+    hipLaunchKernelGGL(tg_cores_kernel, dim3((unsigned)((nN + kCoresWaves - 1) / kCoresWaves)), dim3(kCoresWaves * TG_WAVE), 0, s,
+                       P, W, *out);
+  }
   hipLaunchKernelGGL(tg_summary_kernel, dim3(P.B), dim3(256), 0, s, P, *out);
   return hipGetLastError() == hipSuccess ? TG_OK : TG_E_HIP;
 }

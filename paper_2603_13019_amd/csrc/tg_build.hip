@@ -91,6 +91,23 @@ extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_p
     if (d->n_services < 64)
       for (size_t g = 0; g < (size_t)B * M; ++g) if (d->node_resident[g] >> d->n_services) return TG_E_INVALID_ARG;
   }
+  if (d->node_core_free) {
+    const int nc = d->numa_cores;
+    if (nc < 4 || nc > 64 || (nc & (nc - 1))) return TG_E_INVALID_ARG;
+    for (size_t g = 0; g < (size_t)B * M; ++g) {
+      if (d->node_type[g] != TG_TYPE_CPU) continue;
+      const int cap = d->node_cap[g];
+      if (cap < 0 || cap > TG_MAX_CPU_UNITS) continue;       // reported by the node checks below
+      int bits = 0;
+      for (int w = 0; w < 4; ++w) {
+        const uint64_t m = d->node_core_free[g * 4 + w];
+        const int lim = cap - 64 * w;                          // cores of this word below the capacity
+        if (lim < 64 && (m >> (lim < 0 ? 0 : lim))) return TG_E_INVALID_ARG;
+        bits += __builtin_popcountll(m);
+      }
+      if (bits != d->node_free[g]) return TG_E_INVALID_ARG;
+    }
+  } else if (d->numa_cores != 0) return TG_E_INVALID_ARG;
   if (d->act_aux) {
     for (size_t g = 0; g < (size_t)B * M; ++g) if (d->node_aux_free[g] < 0) return TG_E_INVALID_ARG;
     for (size_t g = 0; g < (size_t)B * N; ++g) if (d->act_aux[g] < 0) return TG_E_INVALID_ARG;
@@ -118,6 +135,8 @@ extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_p
       std::memcpy(ar.at<int32_t>(o_naux), d->node_aux_free, nN * 4);
       std::memcpy(ar.at<int32_t>(o_aaux), d->act_aux, nA * 4);
     }
+    const size_t o_ncores = ar.add(d->node_core_free ? nN * 32 : 0);
+    if (d->node_core_free) std::memcpy(ar.at<uint64_t>(o_ncores), d->node_core_free, nN * 32);
     const size_t n_busy = d->node_busy_off ? (size_t)d->node_busy_off[nN] : 0;
     const size_t o_nbrel = ar.add(std::max<size_t>(n_busy, 1) * 8);
     std::vector<int> max_cap((size_t)B * 3, -1);
@@ -326,6 +345,8 @@ extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_p
     v.restore = svc ? (const int64_t*)(base + o_rest) : nullptr;
     v.row_svc = svc ? (const uint64_t*)(base + o_rowsvc) : nullptr;
     v.node_res_k = svc ? (const uint64_t*)(base + o_nresk) : nullptr;
+    v.node_cores = d->node_core_free ? (const uint64_t*)(base + o_ncores) : nullptr;
+    v.numa_cores = d->node_core_free ? d->numa_cores : 0;
     v.node_aux = d->act_aux ? (const int32_t*)(base + o_naux) : nullptr;
     v.act_aux = d->act_aux ? (const int32_t*)(base + o_aaux) : nullptr;
     v.act_task = (const int32_t*)(base + o_atask); v.speedup = (const uint32_t*)(base + o_speed);

@@ -31,12 +31,13 @@ class ProblemDesc(C.Structure):
             "k_list", "type_k", "speedup_q16", "node_type", "node_cap", "node_free", "node_backlog_us",
             "node_chunks", "node_busy_off", "node_busy_rel_us", "act_type", "act_model", "act_t_ori_us",
             "act_age_us", "act_kmask", "act_param", "act_pin_node", "act_task", "node_aux_free", "act_aux",
-            "act_service", "node_resident", "restore_us")] + [("n_services", C.c_int32), ("reserved_", C.c_int32)]
+            "act_service", "node_resident", "restore_us", "node_core_free")] + [("n_services", C.c_int32),
+                                                                               ("numa_cores", C.c_int32)]
 
 
 class AssignOut(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("node", "units", "act_us", "defer_reason", "summary", "node_used",
-                                          "task_sum_us", "node_obj")]
+                                          "task_sum_us", "node_obj", "core_set")]
 
 
 class TraceDesc(C.Structure):
@@ -61,7 +62,8 @@ _DT = dict(k_list=np.int32, type_k=np.int32, speedup_q16=np.uint32, node_type=np
            node_busy_rel_us=np.int64, act_type=np.uint8, act_model=np.uint8, act_t_ori_us=np.int64,
            act_age_us=np.int64, act_kmask=np.uint32, act_param=np.uint32, act_pin_node=np.int32,
            act_task=np.int32, quota_rate=np.int32, quota_tok0_micro=np.int64, arrival_us=np.int64,
-           node_aux_free=np.int32, act_aux=np.int32, act_service=np.int32, node_resident=np.uint64, restore_us=np.int64)
+           node_aux_free=np.int32, act_aux=np.int32, act_service=np.int32, node_resident=np.uint64, restore_us=np.int64,
+           node_core_free=np.uint64)
 
 EXPORTS = ("tg_build_problem", "tg_free_problem", "tg_num_candidates", "tg_assign_workspace_bytes",
            "tg_score_candidates", "tg_assign", "tg_build_trace", "tg_free_trace", "tg_replay_workspace_bytes",
@@ -140,6 +142,8 @@ class Problem:
         keep = []
         _fill(d, p, [f[0] for f in ProblemDesc._fields_[8:-2]], keep)
         d.n_services = len(p["restore_us"]) if p.get("restore_us") is not None else 0
+        d.numa_cores = int(p.get("numa_cores", 0))
+        self.has_cores = p.get("node_core_free") is not None
         h = C.c_void_p()
         _check(L.tg_build_problem(C.byref(d), _stream(), C.byref(h)), "tg_build_problem")
         self._h = h
@@ -184,6 +188,8 @@ class Problem:
             node_obj=torch.empty(B * M, dtype=torch.int64, device=dev),
             ws=torch.empty(max(self.assign_ws_bytes, 256), dtype=torch.uint8, device=dev),
         )
+        if self.has_cores:
+            bufs["core_set"] = torch.empty(B * N * 4, dtype=torch.int64, device=dev)   # bit patterns of uint64 words
         return bufs
 
     def assign(self, cost=None, bufs=None):

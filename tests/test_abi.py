@@ -37,8 +37,8 @@ def test_strerror(tg):
 
 
 def test_struct_layouts_match_header(tg):
-    assert C.sizeof(tg.ProblemDesc) == 8 * 4 + 23 * 8 + 2 * 4
-    assert C.sizeof(tg.AssignOut) == 8 * 8
+    assert C.sizeof(tg.ProblemDesc) == 8 * 4 + 24 * 8 + 2 * 4
+    assert C.sizeof(tg.AssignOut) == 9 * 8
     assert C.sizeof(tg.TraceDesc) == 8 * 4 + 8 + 16 * 8 + 2 * 4
     assert C.sizeof(tg.ReplayOut) == 8 * 8
     assert tg.SUMMARY_DTYPE.itemsize == 8 + 16 + 24 + 24 + 8 + 24
@@ -52,6 +52,7 @@ def _build_rc(tg, p):
     keep = []
     tg._fill(d, p, [f[0] for f in tg.ProblemDesc._fields_[8:-2]], keep)
     d.n_services = int(p.get("n_services", len(p["restore_us"]) if p.get("restore_us") is not None else 0))
+    d.numa_cores = int(p.get("numa_cores", 0))
     h = C.c_void_p()
     rc = tg.load().tg_build_problem(C.byref(d), None, C.byref(h))
     assert rc != 0 and not h.value
@@ -146,6 +147,25 @@ def test_service_arrays_are_validated(tg):
     assert _build_rc(tg, q) == -1                              # resident bit of a service that does not exist
     q = dict(p, **full); q["restore_us"] = np.array([5, 1 << 36], np.int64)
     assert _build_rc(tg, q) == -2
+
+
+def test_core_maps_are_validated(tg):
+    p = gen.make_random_problem(12, B=1, N=30, n_cpu=2, n_gpu=1, n_api=1, cpu_cap_hi=40)
+    gen.with_core_maps(p, 8, 0)
+    for numa in (0, 2, 12, 128):
+        assert _build_rc(tg, dict(p, numa_cores=numa)) == -1   # 4, 8, 16, 32 or 64 cores per domain
+    assert _build_rc(tg, dict(p, node_core_free=None)) == -1   # a domain size without the maps
+    j = int(np.flatnonzero((p["node_type"] == gen.TYPE_CPU) & (p["node_free"] > 0))[0])
+    maps = p["node_core_free"].copy().reshape(-1, 4)
+    low = int(maps[j][0]) & -int(maps[j][0])
+    maps[j][0] = np.uint64(int(maps[j][0]) ^ low)
+    assert _build_rc(tg, dict(p, node_core_free=maps.reshape(-1))) == -1      # fewer free cores than node_free
+    maps[j][0] = np.uint64(int(maps[j][0]) | low)
+    cap = int(p["node_cap"][j])
+    moved = maps.copy()
+    moved[j][0] = np.uint64(int(moved[j][0]) ^ low)
+    moved[j][cap // 64] = np.uint64(int(moved[j][cap // 64]) | 1 << (cap % 64))
+    assert _build_rc(tg, dict(p, node_core_free=moved.reshape(-1))) == -1     # a core the node does not have
 
 
 def test_cost_order_needs_pools_it_can_sort(tg):

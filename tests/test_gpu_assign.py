@@ -23,8 +23,9 @@ def _assign_gpu(tg, p, use_cost=False):
     P = tg.Problem(p)
     cost = P.score() if use_cost else None
     bufs = P.alloc_assign()
-    for k in ("node", "units", "act_us", "defer_reason", "node_used", "task_sum_us", "node_obj"):
-        bufs[k].fill_(-3 if bufs[k].dtype != torch.uint8 else 77)      # every entry must be written
+    for k in ("node", "units", "act_us", "defer_reason", "node_used", "task_sum_us", "node_obj", "core_set"):
+        if k in bufs:
+            bufs[k].fill_(-3 if bufs[k].dtype != torch.uint8 else 77)      # every entry must be written
     P.assign(cost, bufs)
     torch.cuda.synchronize()
     out = {k: v.cpu().numpy() for k, v in bufs.items() if k not in ("ws", "summary")}
@@ -44,6 +45,9 @@ def _compare(got, want, where=""):
         np.testing.assert_array_equal(gs[k_got], ws[k_want], err_msg=f"{where} summary.{k_got}")
     np.testing.assert_allclose(gs["mean_act_us"], ws["mean_act_us"], rtol=1e-9, atol=0)
     np.testing.assert_allclose(gs["util"], ws["util"], rtol=1e-9, atol=0)
+    assert ("core_set" in got) == ("core_set" in want)
+    if "core_set" in want:
+        np.testing.assert_array_equal(got["core_set"].view(np.uint64), want["core_set"], err_msg=f"{where} core_set")
 
 
 @pytest.mark.parametrize("seed", range(24))
@@ -280,12 +284,15 @@ def _sweep_problem(seed):
         _add_second_resource(p, seed, scarce=bool(rng.integers(0, 2)))
     if rng.random() < 0.5:
         _add_services(p, seed, n_services=int(rng.choice([1, 5, 64])), big=bool(rng.integers(0, 2)))
-    return p, bool(rng.integers(0, 2))
+    use_cost = bool(rng.integers(0, 2))
+    if rng.random() < 0.5:
+        gen.with_core_maps(p, int(rng.choice([4, 8, 16, 32, 64])), seed)
+    return p, use_cost
 
 
 def test_assign_random_sweep(tg, orc):
     """200 problems with every parameter drawn at random (sizes, kinds, capacities, options, depth, busy
-    lists, pins, duration scale, visiting order, with and without the score tensor)."""
+    lists, pins, duration scale, visiting order, second resource, services, core maps, with and without the score tensor)."""
     for seed in range(3000, 3200):
         p, use_cost = _sweep_problem(seed)
         _compare(_assign_gpu(tg, p, use_cost=use_cost), orc.assign(p), f"sweep seed {seed}")
@@ -345,4 +352,45 @@ def test_assign_config3_sampled(tg, orc):
 def test_assign_config4_full(tg, orc):
     """Workload 4 (one snapshot, N=65536, 1152 nodes): the latency case."""
     p = gen.make_config(4)
+    _compare(_assign_gpu(tg, p), orc.assign(p))
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_assign_core_sets_random_problems(tg, orc, seed):
+    """Sec. 5.2: the cores of every selected CPU action, bit for bit, over all domain sizes."""
+    print("case core sets", seed, flush=True)
+    p = gen.make_random_problem(800 + seed, B=3, N=150 + 50 * seed, n_cpu=2 + seed % 4, n_gpu=seed % 2, n_api=seed % 2,
+                                depth=1 + seed % 3, busy=seed % 2 == 0, cpu_cap_hi=(24, 64, 130, 256)[seed % 4], pin_frac=0.3)
+    p["order_policy"] = seed % 2
+    gen.with_core_maps(p, (4, 8, 16, 32, 64)[seed % 5], seed)
+    want = orc.assign(p)
+    assert want["core_set"].any()
+    _compare(_assign_gpu(tg, p), want, f"core sets {seed}")
+
+
+def test_assign_core_sets_code_paths(tg, orc):
+    for case, numa in (("cap_256_nodes", 4), ("cap_256_nodes", 64), ("pool_300_cpu_nodes", 8), ("long_pinned_queues", 16),
+                       ("eight_options", 32)):
+        print("case core sets", case, numa, flush=True)
+        p = gen.with_core_maps(_code_path_problem(case), numa, 3)
+        _compare(_assign_gpu(tg, p), orc.assign(p), f"core sets {case} numa {numa}")
+
+
+def test_assign_core_sets_fragmented_nodes(tg, orc):
+    """Few free cores scattered over many small domains: most actions have to span domains."""
+    p = gen.make_random_problem(860, B=4, N=300, n_cpu=4, n_gpu=0, n_api=0, cpu_cap_hi=256, busy=True, pin_frac=0.2)
+    gen.with_core_maps(p, 4, 9)
+    want = orc.assign(p)
+    sets = want["core_set"].reshape(-1, 4)
+    spans = 0
+    for g in np.flatnonzero(want["units"] > 1):
+        doms = {c // 4 for w in range(4) for c in range(64 * w, 64 * w + 64) if int(sets[g][w]) >> (c % 64) & 1}
+        spans += len(doms) > 1
+    assert spans > 5
+    _compare(_assign_gpu(tg, p), want, "fragmented")
+
+
+def test_assign_core_sets_config2_full(tg, orc):
+    """Workload 2 at full size with a core map per CPU node (domains of 16 cores)."""
+    p = gen.with_core_maps(gen.make_config(2), 16, 2)
     _compare(_assign_gpu(tg, p), orc.assign(p))
