@@ -8,6 +8,6 @@ path's tests/bench feed from.
 from .configs import (  # noqa: F401
     TYPE_CPU, TYPE_GPU, TYPE_API,
     MODEL_NONE, MODEL_AMDAHL, MODEL_TABLE,
-    make_config, make_random_problem, make_trace, subset_problem, slice_problem, with_fixed_dop, with_core_maps,
+    make_config, make_random_problem, make_trace, subset_problem, slice_problem, with_fixed_dop, with_core_maps, with_extra_quotas,
     PROBLEM_ARRAYS, TRACE_ARRAYS,
 )

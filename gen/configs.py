@@ -256,7 +256,7 @@ def subset_problem(p, lo, hi, n_cpu_nodes=2, cap=8, seed=0):
 
 def make_random_problem(seed, B=2, N=40, n_cpu=3, n_gpu=2, n_api=2, cpu_cap_hi=24,
                         k_list=(1, 2, 4, 8), depth=2, busy=True, pin_frac=0.3,
-                        bad_frac=0.05, shuffle_nodes=True, t_median=2_000_000):
+                        bad_frac=0.05, shuffle_nodes=True, t_median=2_000_000, type_probs=(0.6, 0.25, 0.15)):
     """Adversarial small problems: partly occupied nodes, fragmented GPU nodes, running
     actions (busy units), shuffled node order, pins, non-elastic and infeasible actions,
     duplicate durations (ties)."""
@@ -308,7 +308,7 @@ def make_random_problem(seed, B=2, N=40, n_cpu=3, n_gpu=2, n_api=2, cpu_cap_hi=2
 
     n = B * N
     present = [n_cpu > 0, n_gpu > 0, n_api > 0]
-    probs = np.array([0.6 * present[0], 0.25 * present[1], 0.15 * present[2]])
+    probs = np.array([type_probs[0] * present[0], type_probs[1] * present[1], type_probs[2] * present[2]])
     t = rng.choice(3, size=n, p=probs / probs.sum()).astype(np.uint8)
     # few distinct base durations so that equal costs (ties) are common
     T = (rng.integers(1, 9, n) * (t_median // 4)).astype(np.int64)
@@ -392,7 +392,7 @@ def slice_problem(p, snapshots):
     snapshots = list(snapshots)
     q = dict(p)
     q["B"] = len(snapshots)
-    for k in PROBLEM_ARRAYS + ("gpu_mask_", "node_aux_free", "act_aux", "act_service", "node_resident", "node_core_free"):
+    for k in PROBLEM_ARRAYS + ("gpu_mask_", "node_aux_free", "act_aux", "act_service", "node_resident", "node_core_free", "act_quota_mask"):
         v = p.get(k)
         if v is None or k in ("k_list", "type_k", "speedup_q16", "node_busy_off", "node_busy_rel_us"):
             continue
@@ -419,6 +419,29 @@ def with_core_maps(p, numa_cores, seed=0):
             maps[j, c // 64] |= np.uint64(1) << np.uint64(c % 64)
     p["node_core_free"] = maps.reshape(-1)
     p["numa_cores"] = int(numa_cores)
+    return p
+
+
+def with_extra_quotas(p, frac=0.5, seed=0, max_extra=3):
+    """Adds ``act_quota_mask`` to a problem (in place): a fraction of the API actions that are pinned to a quota
+    also name up to ``max_extra`` other quotas of their snapshot (by rank among its API nodes, first 64 only)."""
+    rng = np.random.default_rng(seed + 515)
+    N, M = p["N"], p["M"]
+    mask = np.zeros(p["B"] * N, np.uint64)
+    for b in range(p["B"]):
+        api = np.flatnonzero(p["node_type"][b * M:(b + 1) * M] == TYPE_API)[:64]
+        if len(api) < 2:
+            continue
+        rank = {int(j): r for r, j in enumerate(api)}
+        for i in range(N):
+            g = b * N + i
+            pin = int(p["act_pin_node"][g])
+            if p["act_type"][g] != TYPE_API or pin not in rank or rng.random() >= frac:
+                continue
+            others = [r for r in range(len(api)) if r != rank[pin]]
+            for r in rng.choice(others, min(len(others), int(rng.integers(1, max_extra + 1))), replace=False):
+                mask[g] |= np.uint64(1) << np.uint64(int(r))
+    p["act_quota_mask"] = mask
     return p
 
 

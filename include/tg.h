@@ -128,6 +128,15 @@ typedef struct {
    * free; on CPU nodes exactly node_free bits, none at or above node_cap; ignored on other nodes.
    * NULL: no topology (then numa_cores must be 0 and tg_assign_out.core_set NULL). */
   const uint64_t *node_core_free; /* [B*M*4] */
+  /* Several quotas per action (Sec. 4.1: an action may query several websites, each with its own
+   * quota, every one a component of its cost vector).  An API action pinned to a quota also
+   * takes one token of every API node whose rank r (the r-th API node of its snapshot in index
+   * order, r < 64) is set in act_quota_mask[i]; it is admitted only if all of them have a token
+   * left, otherwise it does not fit and waits like any pinned action that does not fit.  The
+   * estimates (Eq. 2) use the pinned node only.  Bits must be clear for actions that are not of
+   * kind API or not pinned to an API node, for the action's own node and at or above the number
+   * of API nodes.  node_used and units_used count these tokens.  NULL: none. */
+  const uint64_t *act_quota_mask; /* [B*N] */
   int32_t n_services;             /* 1..TG_MAX_SERVICES                                          */
   int32_t numa_cores;             /* 4, 8, 16, 32 or 64 with node_core_free                      */
 } tg_problem_desc;

@@ -50,7 +50,7 @@ class Problem(C.Structure):
             "k_list", "type_k", "speedup_q16", "node_type", "node_cap", "node_free", "node_backlog_us",
             "node_chunks", "node_busy_off", "node_busy_rel_us", "act_type", "act_model", "act_t_ori_us",
             "act_age_us", "act_kmask", "act_param", "act_pin_node", "act_task", "node_aux_free", "act_aux",
-            "act_service", "node_resident", "restore_us", "node_core_free")] + [("numa_cores", C.c_int32)]
+            "act_service", "node_resident", "restore_us", "act_quota_mask", "node_core_free")] + [("numa_cores", C.c_int32)]
 
 
 class Summary(C.Structure):
@@ -78,7 +78,7 @@ _DT = dict(k_list=np.int32, type_k=np.int32, speedup_q16=np.uint32, node_type=np
            act_age_us=np.int64, act_kmask=np.uint32, act_param=np.uint32, act_pin_node=np.int32,
            act_task=np.int32, quota_rate=np.int32, quota_tok0_micro=np.int64, arrival_us=np.int64,
            node_aux_free=np.int32, act_aux=np.int32, act_service=np.int32, node_resident=np.uint64, restore_us=np.int64,
-           node_core_free=np.uint64)
+           node_core_free=np.uint64, act_quota_mask=np.uint64)
 
 
 def lib():

@@ -48,6 +48,7 @@ struct Act {
   int pin, task;
   int aux = 0;                 // second component of the cost vector (Sec. 4.1), e.g. memory with CPU cores
   int service = -1;            // long-lived service the action calls (Sec. 5.3), -1: none
+  uint64_t extra = 0;          // further quotas the action draws one token from each (Sec. 4.1), by rank among the API nodes
 };
 
 struct Node {
@@ -274,6 +275,7 @@ struct StepOut {
   std::vector<int64_t> node_obj;                      // final approximated objective per node, -1 if none
   std::vector<int32_t> home;                          // node an action was admitted to (kept when evicted)
   std::vector<std::vector<int>> cores;                // cores of every selected CPU action (numa_cores > 0)
+  std::vector<int32_t> extra_used;                    // tokens taken from a quota by actions of other quotas
 };
 
 // Order in which a pool's waiting queue is visited (Sec. 4.2: FCFS in the paper, and the
@@ -288,7 +290,7 @@ StepOut step(const Tables& tb, const std::vector<Act>& acts, std::vector<Node> n
   const int N = (int)acts.size(), M = (int)nodes.size(), K = tb.K;
   StepOut o;
   o.node.assign(N, -1); o.units.assign(N, 0); o.act.assign(N, -1); o.reason.assign(N, R_NONE);
-  o.node_obj.assign(M, -1); o.home.assign(N, -1); o.cores.assign(N, {});
+  o.node_obj.assign(M, -1); o.home.assign(N, -1); o.cores.assign(N, {}); o.extra_used.assign(M, 0);
 
   // static infeasibility: no option, bad pin, or minimum units above every candidate node
   std::vector<int> kmin(N, 0);
@@ -340,6 +342,16 @@ StepOut step(const Tables& tb, const std::vector<Act>& acts, std::vector<Node> n
   auto fits = [&](int j, int k) {
     return nodes[j].type == T_GPU ? chunk_fits(&ch[j*4], k) : rem[j] >= k;
   };
+  // Several quotas per action (Sec. 4.1: one action may query several websites, each with its own
+  // quota, and each is a component of its cost vector): besides the quota it is pinned to, the
+  // action draws one token from every quota named in `extra` and is admitted only if all have one.
+  std::vector<int> api_nodes;
+  for (int j = 0; j < M; ++j) if (nodes[j].type == T_API) api_nodes.push_back(j);
+  auto extras_fit = [&](const Act& a) {
+    for (size_t r = 0; r < api_nodes.size() && r < 64; ++r)
+      if ((a.extra >> r & 1ull) && rem[api_nodes[r]] < 1) return false;
+    return true;
+  };
   for (int i : visit) {
     if (o.reason[i] == R_INFEASIBLE) continue;
     const Act& a = acts[i];
@@ -354,6 +366,7 @@ StepOut step(const Tables& tb, const std::vector<Act>& acts, std::vector<Node> n
       if (a.pin >= 0 && a.pin != j) continue;
       if (!fits(j, kmin[i])) continue;
       if (a.pin < 0 && a.aux > aux_rem[j]) continue;
+      if (a.extra && !extras_fit(a)) continue;
       int qs = -1;
       for (int q : options_on(tb, a, nodes[j])) if (fits(j, tb.k_list[q])) qs = q;
       const int64_t e = nodes[j].backlog + restore_delay(tb, a, nodes[j]) + duration(tb, a, qs);   // Eq. 2 on this node
@@ -367,6 +380,8 @@ StepOut step(const Tables& tb, const std::vector<Act>& acts, std::vector<Node> n
     }
     o.node[i] = bj; o.home[i] = bj;
     if (a.pin < 0) aux_rem[bj] -= a.aux;
+    for (size_t r = 0; r < api_nodes.size() && r < 64; ++r)
+      if (a.extra >> r & 1ull) { rem[api_nodes[r]] -= 1; o.extra_used[api_nodes[r]] += 1; }
     if (nodes[bj].type == T_GPU) chunk_take(&ch[bj*4], kmin[i]); else rem[bj] -= kmin[i];
     placed[bj].push_back(i);
   }
@@ -451,6 +466,7 @@ struct orc_problem {
   const uint32_t* act_kmask; const uint32_t* act_param; const int32_t* act_pin_node; const int32_t* act_task;
   const int32_t* node_aux_free; const int32_t* act_aux;     // both or neither; NULL: no second resource
   const int32_t* act_service; const uint64_t* node_resident; const int64_t* restore_us;   // all or none
+  const uint64_t* act_quota_mask;                           // [B*N] further quotas of an API action, or NULL
   const uint64_t* node_core_free; int32_t numa_cores;       // [B*M*4] free-core bitmaps of CPU nodes, or NULL (then numa_cores = 0)
 };
 
@@ -485,7 +501,8 @@ std::vector<Act> acts_of(const orc_problem* p, int b) {
     const size_t g = (size_t)b * p->N + i;
     v[i] = Act{p->act_type[g], p->act_model[g], p->act_t_ori_us[g], p->act_age_us ? p->act_age_us[g] : 0,
                p->act_kmask[g], p->act_param[g], p->act_pin_node[g], p->act_task ? p->act_task[g] : 0,
-               p->act_aux ? p->act_aux[g] : 0, p->act_service ? p->act_service[g] : -1};
+               p->act_aux ? p->act_aux[g] : 0, p->act_service ? p->act_service[g] : -1,
+               p->act_quota_mask ? p->act_quota_mask[g] : 0};
   }
   return v;
 }
@@ -586,6 +603,10 @@ void orc_assign(const orc_problem* p, int32_t* node, int32_t* units, int64_t* ac
           if (node_used) node_used[n0 + o.node[i]] += o.units[i];
           if (task_sum) task_sum[(size_t)b * p->n_tasks + acts[i].task] += o.act[i];
       }
+    }
+    for (int j = 0; j < p->M; ++j) {                   // tokens drawn from further quotas count as used units
+      s.units_used[T_API] += o.extra_used[j];
+      if (node_used) node_used[n0 + j] += o.extra_used[j];
     }
     s.mean_act_us = s.n_assigned ? (double)s.sum_act_us / (double)s.n_assigned : 0.0;
     for (int t = 0; t < N_TYPES; ++t)

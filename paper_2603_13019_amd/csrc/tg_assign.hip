@@ -202,6 +202,7 @@ __global__ __launch_bounds__(TG_WAVE) void tg_place_kernel(TgDev P, const int64_
   io.act_kmask = P.act_kmask + abase; io.act_static = P.act_static + abase; io.act_pin = P.act_pin + abase;
   io.act_aux = P.act_aux ? P.act_aux + abase : nullptr;
   io.act_service = P.act_service ? P.act_service + abase : nullptr; io.restore = P.restore;
+  io.act_quota = P.act_quota && t == TG_TYPE_API ? P.act_quota + abase : nullptr;
   io.node_rank = P.node_rank + nbase; io.nodes = nodes; io.dur = dur + abase * P.K; io.K = P.K; io.Kt = P.type_k[t];
   io.cost = nullptr; io.cost_row_len = 0;
   if (cost) { const TgBlock blk = blocks[b * 3 + t]; io.cost = cost + blk.cost_off; io.cost_row_len = blk.M_t * blk.K_t; }
@@ -347,6 +348,13 @@ __global__ __launch_bounds__(256) void tg_summary_kernel(TgDev P, tg_assign_out 
       const long long a = O.act_us[g];
       sum += a;
       used[P.act_type[g]] += O.units[g];
+      if (P.act_quota && P.act_quota[g]) {                      // tokens of the action's further quotas (Sec. 4.1)
+        uint64_t more = P.act_quota[g];
+        used[TG_TYPE_API] += __popcll(more);
+        const int32_t* api = P.tnode_idx + nbase + P.tnode_off[b * 4 + TG_TYPE_API];
+        if (O.node_used)
+          for (; more; more &= more - 1) atomicAdd(&O.node_used[nbase + api[__ffsll((unsigned long long)more) - 1]], 1);
+      }
       if (task_lds) atomicAdd((unsigned long long*)&s_task[P.act_task[g]], (unsigned long long)a);
       else if (O.task_sum_us) atomicAdd((unsigned long long*)&O.task_sum_us[(size_t)b * P.n_tasks + P.act_task[g]], (unsigned long long)a);
     }

@@ -135,6 +135,8 @@ extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_p
       std::memcpy(ar.at<int32_t>(o_naux), d->node_aux_free, nN * 4);
       std::memcpy(ar.at<int32_t>(o_aaux), d->act_aux, nA * 4);
     }
+    const size_t o_aquota = ar.add(d->act_quota_mask ? nA * 8 : 0);
+    if (d->act_quota_mask) std::memcpy(ar.at<uint64_t>(o_aquota), d->act_quota_mask, nA * 8);
     const size_t o_ncores = ar.add(d->node_core_free ? nN * 32 : 0);
     if (d->node_core_free) std::memcpy(ar.at<uint64_t>(o_ncores), d->node_core_free, nN * 32);
     const size_t n_busy = d->node_busy_off ? (size_t)d->node_busy_off[nN] : 0;
@@ -225,6 +227,16 @@ extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_p
           const int kmin = d->k_list[__builtin_ctz(mask)];
           if (pin >= 0) infeasible = pin >= M || d->node_type[(size_t)b * M + pin] != t || kmin > d->node_cap[(size_t)b * M + pin];
           else infeasible = kmin > max_cap[(size_t)b * 3 + t];
+        }
+        if (d->act_quota_mask && d->act_quota_mask[g]) {             // further quotas: a pinned API action names other API nodes
+          const uint64_t more = d->act_quota_mask[g];
+          const int32_t* tn = ar.at<int32_t>(o_tnoff) + (size_t)b * 4;
+          const int n_api = tn[3] - tn[2];
+          const bool pinned_api = t == TG_TYPE_API && pin >= 0 && pin < M && d->node_type[(size_t)b * M + pin] == TG_TYPE_API;
+          if (!pinned_api || (n_api < 64 && (more >> n_api)) || (more >> ar.at<int32_t>(o_nrank)[(size_t)b * M + pin] & 1ull)) {
+            delete p;
+            return TG_E_INVALID_ARG;
+          }
         }
         if (pin >= M) pin = M;                                       // any out-of-range pin: matches no node
         ar.at<uint8_t>(o_atype)[g] = (uint8_t)t;
@@ -345,6 +357,7 @@ extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_p
     v.restore = svc ? (const int64_t*)(base + o_rest) : nullptr;
     v.row_svc = svc ? (const uint64_t*)(base + o_rowsvc) : nullptr;
     v.node_res_k = svc ? (const uint64_t*)(base + o_nresk) : nullptr;
+    v.act_quota = d->act_quota_mask ? (const uint64_t*)(base + o_aquota) : nullptr;
     v.node_cores = d->node_core_free ? (const uint64_t*)(base + o_ncores) : nullptr;
     v.numa_cores = d->node_core_free ? d->numa_cores : 0;
     v.node_aux = d->act_aux ? (const int32_t*)(base + o_naux) : nullptr;

@@ -312,7 +312,7 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
       tg_wave_sync();
       TgPlaceIo io;
       io.act_kmask = T.act_kmask + abase; io.act_static = T.act_static + abase; io.act_pin = T.act_pin + abase;
-      io.act_aux = nullptr;                                       // traces carry no second resource
+      io.act_aux = nullptr; io.act_quota = nullptr;               // traces carry no second resource and one quota per action
       io.act_service = T.act_service ? T.act_service + abase : nullptr; io.restore = T.restore;
       io.node_rank = T.node_rank + nbase; io.nodes = nodes; io.dur = dur; io.cost = nullptr; io.cost_row_len = 0;
       io.K = K; io.Kt = T.type_k[ty];

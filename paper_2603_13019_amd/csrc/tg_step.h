@@ -116,6 +116,7 @@ struct TgPlaceIo {
   const int32_t* act_aux;      // demand for the node's second resource (charged to unpinned actions), or nullptr
   const int32_t* act_service;  // service the action calls (-1: none), or nullptr: no services
   const int64_t* restore;      // [service] restore time where the service is not resident (Sec. 5.3)
+  const uint64_t* act_quota;   // further quotas of a pinned action (ranks < 64 inside this pool), or nullptr (Sec. 4.1)
   const int32_t* node_rank;    // node id -> rank inside this pool
   const int32_t* nodes;        // rank -> node id
   const int64_t* dur;          // [id*K + q]
@@ -150,6 +151,7 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
   int32_t auxv[R];                                                // second resource left (Sec. 4.1's cost vector)
   uint64_t resv[R];                                               // services resident on the node (Sec. 5.3)
   const bool has_aux = AUX && io.act_aux, has_svc = AUX && io.act_service;   // AUX: the extended variant
+  const bool has_x = AUX && io.act_quota;                         // actions that draw on several quotas (Sec. 4.1)
   uint32_t fitv[R];                                               // options that fit into the units left; 0: closed
   uint64_t closed[R];                                             // wavefront-uniform copies of the closed flags
   int64_t bmin = TG_INF, bmax = 0;
@@ -184,8 +186,10 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
     int my_id = 0, my_aux = 0, my_svc = -1;
     int64_t my_rest = 0;                             // restore time of the action's service
     uint32_t my_w = 0, my_res = 0;
+    int64_t my_x = 0;
     if (lane < cnt) {
       my_id = acts[base + lane];
+      if (has_x) my_x = (int64_t)io.act_quota[my_id];
       if (has_aux) my_aux = io.act_aux[my_id];
       if (has_svc) { my_svc = io.act_service[my_id]; if (my_svc >= 0) my_rest = io.restore[my_svc]; }
       const uint32_t mask = io.act_kmask[my_id], stat = io.act_static[my_id] ? 1u : 0u;
@@ -215,6 +219,7 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
       const int aux = has_aux && pr < 0 ? __builtin_amdgcn_readlane(my_aux, l) : 0;   // pinned: already charged
       const int svc = has_svc ? __builtin_amdgcn_readlane(my_svc, l) : -1;
       const int64_t rest = has_svc ? tg_readlane_i64(my_rest, l) : 0;
+      const uint64_t more = has_x && pr >= 0 ? (uint64_t)tg_readlane_i64(my_x, l) : 0ull;   // ranks are lanes of slot 0
       uint32_t res;
       int take_rank = -1;                                          // node that admits the action
       if (w & 0x100u) {
@@ -233,7 +238,9 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
           dslot = __builtin_amdgcn_readlane(dcntv[s], pl);
         }
         const bool open = !pool_closed && !(cw >> pl & 1ull);
-        if (open && (mask & f) != 0) {
+        // every further quota must have a token left as well
+        const bool more_ok = !AUX || more == 0 || (more & ~__ballot(limv[0] >= 1)) == 0;
+        if (open && (mask & f) != 0 && more_ok) {
           take_rank = pr;
           res = 0;
         } else {
@@ -300,6 +307,10 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
             fitv[s] = fit_of(limv[s]);
           }
         }
+        if (AUX && more != 0 && (more >> lane & 1ull)) {           // one token of every further quota
+          limv[0] -= 1;
+          if (!(closed[0] >> lane & 1ull)) fitv[0] = fit_of(limv[0]);
+        }
         res = pack_res(take_rank, slot, TG_SELECTED);
       }
       if (lane == l) my_res = res;
@@ -331,7 +342,7 @@ __device__ static inline void tg_place_pool(const TgPoolLds& S, const TgPlaceIo&
                                             int Mt, bool gpu, int lane) {
   if (!io.cost && Mt <= 16 * TG_WAVE) {
     const int slots = Mt <= TG_WAVE ? 1 : Mt <= 4 * TG_WAVE ? 4 : 16;
-    const bool ext = io.act_aux || io.act_service;
+    const bool ext = io.act_aux || io.act_service || io.act_quota;
     if (ext ? slots <= MAXR_EXT : slots <= MAXR) {
       if (ext) {
         if (slots == 1) tg_place_pool_regs<1, (MAXR_EXT >= 1)>(S, io, acts, Nt, Mt, gpu, lane);
@@ -366,8 +377,10 @@ __device__ static inline void tg_place_pool(const TgPoolLds& S, const TgPlaceIo&
     int my_id = 0, my_pr = -1, my_aux = 0, my_svc = -1;
     int64_t my_rest = 0;
     uint32_t my_mask = 0, my_static = 0;
+    int64_t my_x = 0;
     if (lane < cnt) {
       my_id = acts[base + lane];
+      if (io.act_quota) my_x = (int64_t)io.act_quota[my_id];
       my_mask = io.act_kmask[my_id]; my_static = io.act_static[my_id];
       const int pin = io.act_pin[my_id];
       if (pin >= 0 && !my_static) my_pr = io.node_rank[pin];
@@ -394,6 +407,7 @@ __device__ static inline void tg_place_pool(const TgPoolLds& S, const TgPlaceIo&
       const int aux = io.act_aux && pr < 0 ? __builtin_amdgcn_readlane(my_aux, l) : 0;   // pinned: already charged
       const int svc = io.act_service ? __builtin_amdgcn_readlane(my_svc, l) : -1;
       const int64_t rest = io.act_service ? tg_readlane_i64(my_rest, l) : 0;
+      const uint64_t more = io.act_quota && pr >= 0 ? (uint64_t)tg_readlane_i64(my_x, l) : 0ull;   // further quotas, ranks < 64
       int reason = TG_SELECTED, rank = -1, slot = 0;
       if (stat) {
         reason = TG_DEFER_INFEASIBLE;
@@ -401,7 +415,9 @@ __device__ static inline void tg_place_pool(const TgPoolLds& S, const TgPlaceIo&
         reason = TG_DEFER_PREFIX;
       } else {
         const int kmin = S.k[__builtin_ctz(mask)];
-        const int r_lo = pr >= 0 ? pr : lane, r_hi = pr >= 0 ? (lane == 0 ? pr + 1 : 0) : Mt;
+        // every further quota must have a token left as well, else the action does not fit
+        const bool more_ok = more == 0 || (more & ~__ballot(lane < Mt && S.lim[lane < Mt ? lane : 0] >= 1)) == 0;
+        const int r_lo = pr >= 0 ? pr : lane, r_hi = !more_ok ? 0 : pr >= 0 ? (lane == 0 ? pr + 1 : 0) : Mt;
         // this lane's best node: least estimate, smallest rank on ties (ranks ascend in the loop)
         uint32_t b32 = 0xffffffffu, brank = 0xffffffffu;
         uint64_t b64 = ~0ull;
@@ -440,6 +456,7 @@ __device__ static inline void tg_place_pool(const TgPoolLds& S, const TgPlaceIo&
             if (aux > 0) S.aux[rank] -= aux;
             S.lim[rank] = gpu ? (int32_t)tg_chunk_take((uint32_t)S.lim[rank], kmin) : S.lim[rank] - kmin;
           }
+          if (more >> lane & 1ull) S.lim[lane] -= 1;              // one token of every further quota
         }
       }
       if (reason == TG_DEFER_PREFIX && pr >= 0) {

@@ -37,7 +37,7 @@ def test_strerror(tg):
 
 
 def test_struct_layouts_match_header(tg):
-    assert C.sizeof(tg.ProblemDesc) == 8 * 4 + 24 * 8 + 2 * 4
+    assert C.sizeof(tg.ProblemDesc) == 8 * 4 + 25 * 8 + 2 * 4
     assert C.sizeof(tg.AssignOut) == 9 * 8
     assert C.sizeof(tg.TraceDesc) == 8 * 4 + 8 + 16 * 8 + 2 * 4
     assert C.sizeof(tg.ReplayOut) == 8 * 8
@@ -166,6 +166,21 @@ def test_core_maps_are_validated(tg):
     moved[j][0] = np.uint64(int(moved[j][0]) ^ low)
     moved[j][cap // 64] = np.uint64(int(moved[j][cap // 64]) | 1 << (cap % 64))
     assert _build_rc(tg, dict(p, node_core_free=moved.reshape(-1))) == -1     # a core the node does not have
+
+
+def test_quota_masks_are_validated(tg):
+    p = gen.make_random_problem(13, B=1, N=60, n_cpu=1, n_gpu=1, n_api=3, type_probs=(0.3, 0.2, 0.5))
+    gen.with_extra_quotas(p, frac=1.0, seed=0)
+    api = np.flatnonzero(p["node_type"] == gen.TYPE_API)
+    i = int(np.flatnonzero(p["act_quota_mask"] != 0)[0])
+    own = int(np.flatnonzero(api == p["act_pin_node"][i])[0])
+    m = p["act_quota_mask"].copy(); m[i] |= np.uint64(1 << own)
+    assert _build_rc(tg, dict(p, act_quota_mask=m)) == -1       # the action's own quota
+    m = p["act_quota_mask"].copy(); m[i] |= np.uint64(1 << 3)
+    assert _build_rc(tg, dict(p, act_quota_mask=m)) == -1       # a quota the snapshot does not have
+    c = int(np.flatnonzero(p["act_type"] == gen.TYPE_CPU)[0])
+    m = p["act_quota_mask"].copy(); m[c] = np.uint64(1)
+    assert _build_rc(tg, dict(p, act_quota_mask=m)) == -1       # only API actions draw on quotas
 
 
 def test_cost_order_needs_pools_it_can_sort(tg):

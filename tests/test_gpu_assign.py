@@ -286,13 +286,15 @@ def _sweep_problem(seed):
         _add_services(p, seed, n_services=int(rng.choice([1, 5, 64])), big=bool(rng.integers(0, 2)))
     use_cost = bool(rng.integers(0, 2))
     if rng.random() < 0.5:
+        gen.with_extra_quotas(p, frac=float(rng.random()), seed=seed, max_extra=int(rng.integers(1, 6)))
+    if rng.random() < 0.5:
         gen.with_core_maps(p, int(rng.choice([4, 8, 16, 32, 64])), seed)
     return p, use_cost
 
 
 def test_assign_random_sweep(tg, orc):
     """200 problems with every parameter drawn at random (sizes, kinds, capacities, options, depth, busy
-    lists, pins, duration scale, visiting order, second resource, services, core maps, with and without the score tensor)."""
+    lists, pins, duration scale, visiting order, second resource, services, several quotas, core maps, with and without the score tensor)."""
     for seed in range(3000, 3200):
         p, use_cost = _sweep_problem(seed)
         _compare(_assign_gpu(tg, p, use_cost=use_cost), orc.assign(p), f"sweep seed {seed}")
@@ -394,3 +396,30 @@ def test_assign_core_sets_config2_full(tg, orc):
     """Workload 2 at full size with a core map per CPU node (domains of 16 cores)."""
     p = gen.with_core_maps(gen.make_config(2), 16, 2)
     _compare(_assign_gpu(tg, p), orc.assign(p))
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_assign_several_quotas_random_problems(tg, orc, seed):
+    """Sec. 4.1: API actions that draw a token from several quotas at once; with and without the score tensor
+    (register-resident and LDS node table), under both visiting orders."""
+    print("case several quotas", seed, flush=True)
+    p = gen.make_random_problem(900 + seed, B=3, N=200 + 60 * seed, n_cpu=1 + seed % 3, n_gpu=seed % 2, n_api=2 + (7 * seed) % 30,
+                                depth=1 + seed % 3, busy=seed % 2 == 0, pin_frac=0.3, type_probs=(0.4, 0.1, 0.5))
+    base = orc.assign(p)
+    gen.with_extra_quotas(p, frac=0.6, seed=seed, max_extra=1 + seed % 4)
+    p["order_policy"] = seed % 2
+    if seed % 3 == 2:
+        _add_second_resource(p, seed, scarce=False)
+    want = orc.assign(p)
+    assert (base["reason"] != want["reason"]).any() or p["order_policy"] == 1
+    _compare(_assign_gpu(tg, p, use_cost=seed % 2 == 1), want, f"several quotas {seed}")
+
+
+def test_assign_several_quotas_many_api_nodes(tg, orc):
+    """70 and 300 quotas in a snapshot: node tables of 4 and 16 register slots; the masks name quotas among the first 64."""
+    for n_api in (70, 300):
+        print("case several quotas", n_api, flush=True)
+        p = gen.make_random_problem(930 + n_api, B=2, N=1500, n_cpu=1, n_gpu=0, n_api=n_api, type_probs=(0.1, 0.0, 0.9))
+        p["type_k"][gen.TYPE_GPU] = 0
+        gen.with_extra_quotas(p, frac=0.7, seed=n_api, max_extra=5)
+        _compare(_assign_gpu(tg, p), orc.assign(p), f"several quotas, {n_api} API nodes")

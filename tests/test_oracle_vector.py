@@ -46,6 +46,7 @@ def _place(p, b):
     aux_rem = (p["node_aux_free"][b * M:(b + 1) * M].astype(np.int64).copy() if p.get("node_aux_free") is not None
                else np.full(M, 1 << 40))
     home, reason = np.full(N, -1), np.zeros(N, int)
+    api = [j for j in range(M) if nt[j] == gen.TYPE_API][:64]
     closed, type_closed = set(), set()
     for i in range(N):
         g = b * N + i
@@ -61,9 +62,10 @@ def _place(p, b):
             continue
         kmin = int(p["k_list"][ops[0]])
         aux = int(p["act_aux"][g]) if p.get("act_aux") is not None and pin < 0 else 0
+        more = [api[r] for r in range(len(api)) if int(p["act_quota_mask"][g]) >> r & 1] if p.get("act_quota_mask") is not None else []
         best = None
         for j in nodes:
-            if nt[j] != t or j in closed or rem[j] < kmin or aux > aux_rem[j]:
+            if nt[j] != t or j in closed or rem[j] < kmin or aux > aux_rem[j] or any(rem[x] < 1 for x in more):
                 continue
             q = max(q for q in ops if p["k_list"][q] <= cap[j] and p["k_list"][q] <= rem[j])
             e = (int(back[j]) + restore_delay(p, g, b * M + j) + _dur(p, g, q), j)
@@ -76,6 +78,8 @@ def _place(p, b):
         home[i] = j
         rem[j] -= kmin
         aux_rem[j] -= aux
+        for x in more:
+            rem[x] -= 1
     return home, reason
 
 
