@@ -89,6 +89,45 @@ def core_sets_section(a, tg, gen, torch, p):
             "in_one_domain": int(one)}
 
 
+def pooled_section(a, tg, gen, torch, p):
+    """The same workload with the GPU nodes of every snapshot scheduled as one pool of chunks (the GPU actions unpinned,
+    the GPU nodes of a snapshot given their mean backlog, which a pool needs) against the same modified workload
+    scheduled node by node: time of tg_assign, GPU actions selected and their mean ACT."""
+    import numpy as np
+    q = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in p.items()}
+    M = q["M"]
+    gpu_a = q["act_type"] == gen.TYPE_GPU
+    q["act_pin_node"][gpu_a] = -1
+    for b in range(q["B"]):
+        g = np.flatnonzero(q["node_type"][b * M:(b + 1) * M] == gen.TYPE_GPU) + b * M
+        if len(g):
+            q["node_backlog_us"][g] = int(q["node_backlog_us"][g].mean())
+    res = {}
+    for name, pooled in (("per_node", 0), ("pooled", 1)):
+        try:
+            P = tg.Problem(dict(q, gpu_pooled=pooled))
+        except tg.TgError as e:
+            return {"skipped": f"this workload's GPU nodes cannot form a pool ({e})"}
+        bufs = P.alloc_assign()
+        for _ in range(3):
+            P.assign(None, bufs)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        n = max(5, a.steps // 5)
+        e0.record()
+        for _ in range(n):
+            P.assign(None, bufs)
+        e1.record()
+        torch.cuda.synchronize()
+        units = bufs["units"].cpu().numpy()
+        act = bufs["act_us"].cpu().numpy()
+        P.free()
+        sel = gpu_a & (units > 0)
+        res[name] = {"assign_ms": e0.elapsed_time(e1) / n, "gpu_actions_selected": int(sel.sum()),
+                     "mean_act_us": float(act[sel].mean()) if sel.any() else None,
+                     "gpus_handed_out": int(units[sel].sum())}
+    return res
+
+
 def replay_section(a, tg, gen, torch):
     """Workload 5 (batched trace replay): S scenarios x 10 000 Poisson arrivals over 200 s, rescheduling every
     100 ms, on the default cluster (256x128 cores, 32x8 GPUs, 16 quotas) and on the contended one (4x32 cores,
@@ -166,6 +205,9 @@ def main():
     ap.add_argument("--replay-scenarios", type=int, default=4096,
                     help="scenarios of workload 5 (10 000 arrivals each) replayed after the timed steps; 0 = skip")
     ap.add_argument("--only", choices=["step", "score", "assign"], default="step")
+    ap.add_argument("--overlap", type=int, default=1,
+                    help="1: tg_score_candidates runs on a second stream next to tg_assign (which does not read the tensor "
+                         "unless --use-cost 1); 0: one after the other on one stream")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain device copies of the score tensor's size (reference for the HBM byte counters)")
     a = ap.parse_args()
@@ -189,11 +231,41 @@ def main():
     bufs = P.alloc_assign()
     n_cand, n_act = P.num_candidates, P.B * P.N
 
-    def step():
+    # tg_assign does not consume the tensor (unless asked to), so the two calls of a step are independent: the
+    # score kernel (HBM-bound) runs on a second stream of default priority next to the latency-bound assign
+    overlap = bool(a.overlap) and a.only == "step" and not a.use_cost
+    main_stream = torch.cuda.current_stream()
+    side_stream = torch.cuda.Stream() if overlap else None
+
+    def step(ev=None):
+        e0, e1, e2, e3 = ev if ev else (None,) * 4
+        if overlap:
+            fork = torch.cuda.Event()
+            fork.record(main_stream)
+            side_stream.wait_event(fork)
+            with torch.cuda.stream(side_stream):
+                if ev:
+                    e0.record(side_stream)
+                P.score(cost)
+                done = e1 if ev else torch.cuda.Event()
+                done.record(side_stream)
+            if ev:
+                e2.record(main_stream)
+            P.assign(None, bufs)
+            if ev:
+                e3.record(main_stream)
+            main_stream.wait_event(done)
+            return
+        if ev:
+            e0.record()
         if a.only in ("step", "score"):
             P.score(cost)
+        if ev:
+            e1.record(); e2.record()
         if a.only in ("step", "assign"):
             P.assign(cost if a.use_cost else None, bufs)
+        if ev:
+            e3.record()
 
     for _ in range(a.warmup):
         step()
@@ -205,24 +277,16 @@ def main():
         torch.cuda.synchronize()
         del dst
 
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True),
-           torch.cuda.Event(enable_timing=True)) for _ in range(a.steps)]
+    ev = [tuple(torch.cuda.Event(enable_timing=True) for _ in range(4)) for _ in range(a.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(a.steps):
-        e0, e1, e2 = ev[k]
-        e0.record()
-        if a.only in ("step", "score"):
-            P.score(cost)
-        e1.record()
-        if a.only in ("step", "assign"):
-            P.assign(cost if a.use_cost else None, bufs)
-        e2.record()
+        step(ev[k])       # events bracket each call on the stream it is launched on
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_step = (t1 - t0) * 1e3 / a.steps
-    score_ms = float(np.mean([e0.elapsed_time(e1) for e0, e1, _ in ev]))
-    assign_ms = float(np.mean([e1.elapsed_time(e2) for _, e1, e2 in ev]))
+    score_ms = float(np.mean([e0.elapsed_time(e1) for e0, e1, _, _ in ev]))
+    assign_ms = float(np.mean([e2.elapsed_time(e3) for _, _, e2, e3 in ev]))
 
     s = tg.summary_to_numpy(bufs["summary"]) if a.only != "score" else None
     achieved = 8.0 * n_cand / (score_ms * 1e-3) / 1e9 if a.only != "assign" and score_ms > 0 else None
@@ -231,9 +295,10 @@ def main():
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int64", "data": "synthetic",
         "config": {"workload": f"config{a.config}: B={P.B} snapshots x N={P.N} actions, M={P.M} nodes, "
-                               f"{n_cand} candidates; step = tg_score_candidates + tg_assign",
+                               f"{n_cand} candidates; step = tg_score_candidates + tg_assign"
+                               + (" on two streams side by side" if overlap else ", one after the other"),
                    "B": P.B, "N": P.N, "M": P.M, "candidates": n_cand, "assign_reads_score_tensor": bool(a.use_cost),
-                   "only": a.only},
+                   "only": a.only, "score_and_assign_overlap": overlap},
         "actions_scheduled_per_sec": n_act / (ms_step * 1e-3) if a.only != "score" else None,
         "stage_ms": {"score": score_ms, "assign": assign_ms},
         "selected_fraction": float(s["n_selected"].sum()) / n_act if s is not None else None,
@@ -246,6 +311,7 @@ def main():
     if a.only == "step":
         out["order_policy_cost"] = order_section(a, tg, torch, p, s)
         out["core_sets"] = core_sets_section(a, tg, gen, torch, p)
+        out["gpu_pooled"] = pooled_section(a, tg, gen, torch, p)
     if a.replay_scenarios > 0 and a.only == "step":
         out["replay"] = replay_section(a, tg, gen, torch)
 

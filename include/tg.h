@@ -139,6 +139,17 @@ typedef struct {
   const uint64_t *act_quota_mask; /* [B*N] */
   int32_t n_services;             /* 1..TG_MAX_SERVICES                                          */
   int32_t numa_cores;             /* 4, 8, 16, 32 or 64 with node_core_free                      */
+  /* 1: the GPU nodes of a snapshot form one pool (Sec. 5.3 and Alg. 4: the GPU manager schedules
+   * the cluster as a whole and the state counts the free chunks of every size wherever they are).
+   * Admission, DPArrange, the eviction loop and the completion heap then see one resource with the
+   * chunks, units and running actions of all GPU nodes; every selected action gets the smallest
+   * free chunk of the cluster that holds it, on the lowest-numbered node that has one, and `node`
+   * reports that node; node_obj holds the pool's objective at the first GPU node.  Needs per
+   * snapshot: GPU nodes of 8 units, at most TG_MAX_GPU_UNITS units together, one common
+   * node_backlog_us, no GPU action pinned, no services (else TG_E_INVALID_ARG), and pooled chunk
+   * counts within TG_MAX_CHUNK_STATES (else TG_E_RANGE).  0: every node on its own. */
+  int32_t gpu_pooled;
+  int32_t reserved_;              /* 0                                                           */
 } tg_problem_desc;
 
 /* Per-snapshot result of tg_assign.  Only mean_act_us and util are floating point. */

@@ -10,6 +10,7 @@
 //   * Alg. 4 (App. B)       DPArrange over free-chunk states (GPU operator, sizes 1/2/4/8)
 //   * Sec. 5.1-5.3          capacity models: quota, per-node cores + trajectory pin, buddy chunks
 //   * Sec. 5.2              which cores an action gets: one NUMA domain if any can hold it
+//   * Sec. 5.3 + Alg. 4      optionally the whole GPU cluster as one pool of chunks
 // It shares no code, header, table or helper with the HIP library; only tests, the
 // smoke check and the benchmark's CPU-baseline leg may call it.
 //
@@ -286,8 +287,26 @@ enum { ORDER_FCFS = 0, ORDER_COST = 1 };
 
 // ---- one scheduling step on one snapshot (Alg. 1 applied per resource pool) -------------
 StepOut step(const Tables& tb, const std::vector<Act>& acts, std::vector<Node> nodes, int order_policy = ORDER_FCFS,
-             int numa_cores = 0) {
+             int numa_cores = 0, bool gpu_pooled = false) {
   const int N = (int)acts.size(), M = (int)nodes.size(), K = tb.K;
+  // Sec. 5.3 / Alg. 4: the GPU manager runs the algorithm for the GPU cluster as a whole, and the
+  // state of Alg. 4 counts the chunks of every size it has, whichever node they are on.  In that
+  // mode the first GPU node stands for the pool: it gets the chunks, units and running actions of
+  // all GPU nodes (which share one backlog), the others have nothing left to give.  The nodes
+  // themselves come back at the end, when every selected action is given a real chunk.
+  std::vector<std::vector<int>> real_chunks(M, std::vector<int>(4, 0));
+  int pool = -1;
+  if (gpu_pooled)
+    for (int j = 0; j < M; ++j) {
+      if (nodes[j].type != T_GPU) continue;
+      for (int x = 0; x < 4; ++x) real_chunks[j][x] = nodes[j].chunks[x];
+      if (pool < 0) { pool = j; continue; }
+      Node& P = nodes[pool];
+      P.cap += nodes[j].cap; P.free += nodes[j].free;
+      for (int x = 0; x < 4; ++x) { P.chunks[x] += nodes[j].chunks[x]; nodes[j].chunks[x] = 0; }
+      P.busy.insert(P.busy.end(), nodes[j].busy.begin(), nodes[j].busy.end());
+      nodes[j].free = 0; nodes[j].busy.clear();
+    }
   StepOut o;
   o.node.assign(N, -1); o.units.assign(N, 0); o.act.assign(N, -1); o.reason.assign(N, R_NONE);
   o.node_obj.assign(M, -1); o.home.assign(N, -1); o.cores.assign(N, {}); o.extra_used.assign(M, 0);
@@ -444,6 +463,20 @@ StepOut step(const Tables& tb, const std::vector<Act>& acts, std::vector<Node> n
       o.act[i] = acts[i].age + nd.backlog + restore_delay(tb, acts[i], nd) + duration(tb, acts[i], q);
       // Sec. 5.2: the selected actions of a node name their cores one after the other, in visiting order
       if (numa_cores > 0 && nd.type == T_CPU) o.cores[i] = take_cores(core_free, numa_cores, ks[x]);
+      // pooled GPUs: the action's chunk is the smallest free chunk of the cluster that is large
+      // enough (Sec. 5.3's rule over all nodes), on the lowest-numbered node that has one
+      if (j == pool) {
+        int best = -1, best_level = 4;
+        for (int r = 0; r < M; ++r) {
+          if (nodes[r].type != T_GPU) continue;
+          for (int b = chunk_level(ks[x]); b < best_level; ++b)
+            if (real_chunks[r][b] > 0) { best = r; best_level = b; break; }
+        }
+        int c[4] = {real_chunks[best][0], real_chunks[best][1], real_chunks[best][2], real_chunks[best][3]};
+        chunk_take(c, ks[x]);
+        for (int b = 0; b < 4; ++b) real_chunks[best][b] = c[b];
+        o.node[i] = best;
+      }
     }
   }
   return o;
@@ -468,6 +501,7 @@ struct orc_problem {
   const int32_t* act_service; const uint64_t* node_resident; const int64_t* restore_us;   // all or none
   const uint64_t* act_quota_mask;                           // [B*N] further quotas of an API action, or NULL
   const uint64_t* node_core_free; int32_t numa_cores;       // [B*M*4] free-core bitmaps of CPU nodes, or NULL (then numa_cores = 0)
+  int32_t gpu_pooled;                                       // 1: the GPU nodes of a snapshot form one pool of chunks (Alg. 4's state)
 };
 
 struct orc_summary {
@@ -585,7 +619,7 @@ void orc_assign(const orc_problem* p, int32_t* node, int32_t* units, int64_t* ac
   for (int b = 0; b < p->B; ++b) {
     const std::vector<Act> acts = acts_of(p, b);
     const std::vector<Node> nodes = nodes_of(p, b);
-    const StepOut o = step(tb, acts, nodes, p->order_policy, p->node_core_free ? p->numa_cores : 0);
+    const StepOut o = step(tb, acts, nodes, p->order_policy, p->node_core_free ? p->numa_cores : 0, p->gpu_pooled != 0);
     const size_t a0 = (size_t)b * p->N, n0 = (size_t)b * p->M;
     orc_summary s;
     std::memset(&s, 0, sizeof s);

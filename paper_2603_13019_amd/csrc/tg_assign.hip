@@ -7,6 +7,7 @@
 //   tg_lists_kernel    groups admitted / waiting-pinned actions by node, FCFS inside a node
 //   tg_node_kernel     the rest of Alg. 1 per node: DPArrange (Alg. 3 / Alg. 4) + greedy tail
 //                      eviction on the approximated objective (Alg. 2)   one wavefront per node
+//   tg_pool_map_kernel (pooled GPUs) the real chunk of every selected GPU action, Sec. 5.3
 //   tg_cores_kernel    (problems with a core topology) the cores of every selected CPU action, Sec. 5.2
 //   tg_summary_kernel  per-snapshot sums, counts, utilisation
 //
@@ -174,6 +175,9 @@ __global__ __launch_bounds__(kOrderThreads) void tg_order_kernel(TgDev P, const 
 }
 
 // ------------------------------------------------------------------------------------------
+// MAXR / MAXR_EXT / LDS_TABLE: the variants of tg_place_pool compiled into this instantiation;
+// the host picks the narrowest one that takes every pool of the problem.
+template <int MAXR, int MAXR_EXT, bool LDS_TABLE>
 __global__ __launch_bounds__(TG_WAVE) void tg_place_kernel(TgDev P, const int64_t* __restrict__ dur,
                                                            const int64_t* __restrict__ cost,
                                                            const TgBlock* __restrict__ blocks, AssignWs W,
@@ -208,7 +212,7 @@ __global__ __launch_bounds__(TG_WAVE) void tg_place_kernel(TgDev P, const int64_
   if (cost) { const TgBlock blk = blocks[b * 3 + t]; io.cost = cost + blk.cost_off; io.cost_row_len = blk.M_t * blk.K_t; }
   io.out_node = O.node + abase; io.out_units = O.units + abase; io.out_act = O.act_us + abase;
   io.out_reason = O.defer_reason + abase; io.slot = W.slot + abase;
-  tg_place_pool<16, 16>(S, io, acts, Nt, Mt, t == TG_TYPE_GPU, lane);
+  tg_place_pool<MAXR, MAXR_EXT, LDS_TABLE>(S, io, acts, Nt, Mt, t == TG_TYPE_GPU, lane);
 
   tg_pool_extents(S, nodes, Mt, a0, W.nl_off + nbase, W.nl_cnt + nbase, W.dl_off + nbase, W.dl_cnt + nbase, lane);
 }
@@ -470,6 +474,46 @@ __global__ __launch_bounds__(kCoresWaves * TG_WAVE) void tg_cores_kernel(TgDev P
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Pooled GPUs (Sec. 5.3, Alg. 4): the node stage has scheduled the pool as one resource at the
+// snapshot's first GPU node.  One wavefront per snapshot, lane r = the r-th GPU node with its
+// own free chunks: the pool's selected actions, in list order, each take the smallest free
+// chunk of the cluster that holds them, on the lowest-numbered node that has one - the same
+// sequence of takes the pool's chunk counts went through, so every take succeeds.
+__global__ __launch_bounds__(TG_WAVE) void tg_pool_map_kernel(TgDev P, AssignWs W, tg_assign_out O) {
+  const int b = blockIdx.x, lane = threadIdx.x;
+  const size_t abase = (size_t)b * P.N, nbase = (size_t)b * P.M;
+  const int n0 = P.tnode_off[b * 4 + TG_TYPE_GPU], n_gpu = P.tnode_off[b * 4 + TG_TYPE_GPU + 1] - n0;
+  if (n_gpu == 0) return;
+  const int32_t* gpu_nodes = P.tnode_idx + nbase + n0;            // index order; at most 8 of them
+  const int my_node = lane < n_gpu ? gpu_nodes[lane] : -1;
+  uint32_t chunks = lane < n_gpu ? P.node_chunks_real[nbase + my_node] : 0u;
+  int used = 0;
+  const size_t pool = nbase + gpu_nodes[0];
+  const int m = W.nl_cnt[pool];
+  const int32_t* list = W.order + abase + W.nl_off[pool];
+  for (int base = 0; base < m; base += TG_WAVE) {
+    const int n = m - base < TG_WAVE ? m - base : TG_WAVE;
+    const int my_a = lane < n ? list[base + lane] : 0;
+    const int my_k = lane < n ? O.units[abase + my_a] : 0;
+    int my_dst = -1;
+    for (int l = 0; l < n; ++l) {
+      const int k = __builtin_amdgcn_readlane(my_k, l);
+      if (k == 0) continue;                                       // evicted
+      int level = 4;                                              // smallest free chunk of this node that holds k
+      for (int x = 3; x >= tg_chunk_level(k); --x) if ((chunks >> (8 * x)) & 0xffu) level = x;
+      const uint32_t best = tg_wave_min_u32(level < 4 ? (uint32_t)level << 8 | (uint32_t)lane : 0xffffffffu);
+      if (best == 0xffffffffu) continue;                          // cannot happen: the pool's counts had such a chunk
+      const int r = (int)(best & 0xffu);
+      const int dst = __builtin_amdgcn_readlane(my_node, r);
+      if (lane == r) { chunks = tg_chunk_take(chunks, k); used += k; }
+      if (lane == l) my_dst = dst;
+    }
+    if (lane < n && my_dst >= 0) O.node[abase + my_a] = my_dst;
+  }
+  if (O.node_used && lane < n_gpu) O.node_used[nbase + my_node] = used;
+}
+
 }  // namespace
 
 extern "C" int tg_assign_workspace_bytes(const tg_problem* p, size_t* bytes) {
@@ -491,8 +535,6 @@ extern "C" int tg_assign(const tg_problem* p, const int64_t* d_cost, const tg_as
   const size_t nA = (size_t)P.B * P.N;
 
   const size_t place_lds = tg_pool_lds_bytes(p->max_nodes_of_kind);
-  if (place_lds > 64 * 1024)
-    TG_HIP_CHECK(hipFuncSetAttribute((const void*)tg_place_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)place_lds));
   TgNodeLdsPlan plans[kClasses];
   int max_lds = 0;
   for (int c = 0; c < kClasses; ++c) {
@@ -517,8 +559,23 @@ extern "C" int tg_assign(const tg_problem* p, const int64_t* d_cost, const tg_as
     visit = W.visit;
   }
   // the rows of the score tensor are in FCFS order: another visiting order recomputes Eq. 2 instead
-  hipLaunchKernelGGL(tg_place_kernel, dim3(P.B * 3), dim3(TG_WAVE), place_lds, s, P, W.dur, visit ? nullptr : d_cost, p->d_blocks,
-                     W, *out, p->max_nodes_of_kind, visit);
+  {
+    // the node table of a pool lives in registers (1, 4 or 16 nodes per lane) unless the estimates
+    // come from the score tensor or a pool has more than 1024 nodes (then: a table in LDS)
+    const int64_t* place_cost = visit ? nullptr : d_cost;
+    const bool ext = P.act_aux || P.act_service || P.act_quota;
+    const int mk = p->max_nodes_of_kind;
+    const int width = place_cost || mk > 16 * TG_WAVE ? 0 : mk <= TG_WAVE ? 1 : mk <= 4 * TG_WAVE ? 4 : 16;
+    using PlaceKernel = void (*)(TgDev, const int64_t*, const int64_t*, const TgBlock*, AssignWs, tg_assign_out, int, const int32_t*);
+    PlaceKernel k = width == 0 ? tg_place_kernel<0, 0, true>
+                  : width == 1 ? (ext ? tg_place_kernel<1, 1, false> : tg_place_kernel<1, 0, false>)
+                  : width == 4 ? (ext ? tg_place_kernel<4, 4, false> : tg_place_kernel<4, 0, false>)
+                               : (ext ? tg_place_kernel<16, 16, false> : tg_place_kernel<16, 0, false>);
+    if (place_lds > 64 * 1024)
+      TG_HIP_CHECK(hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)place_lds));
+    hipLaunchKernelGGL(k, dim3(P.B * 3), dim3(TG_WAVE), place_lds, s, P, W.dur, place_cost, p->d_blocks, W, *out,
+                       p->max_nodes_of_kind, visit);
+  }
   hipLaunchKernelGGL(tg_lists_kernel, dim3((unsigned)((nA + nN + 255) / 256)), dim3(256), 0, s, P, W, *out);
   // Persistent wavefronts pull nodes of their class and, when it is exhausted, of the lighter
   // classes.  The classes are independent and each is bound by the latency of its own
@@ -541,6 +598,7 @@ extern "C" int tg_assign(const tg_problem* p, const int64_t* d_cost, const tg_as
     if (c < 2) TG_HIP_CHECK(hipEventRecord(p->ev_join[c], cs));
   }
   for (int c = 0; c < 2; ++c) TG_HIP_CHECK(hipStreamWaitEvent(s, p->ev_join[c], 0));
+  if (P.node_chunks_real) hipLaunchKernelGGL(tg_pool_map_kernel, dim3(P.B), dim3(TG_WAVE), 0, s, P, W, *out);
   if (out->core_set) {
     hipLaunchKernelGGL(tg_cores_clear_kernel, dim3((unsigned)((nA * 4 + 255) / 256)), dim3(256), 0, s,
                        (unsigned long long*)out->core_set, nA * 4);

@@ -67,9 +67,91 @@ extern "C" const char* tg_strerror(int code) {
   }
 }
 
-extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_problem** out) {
-  if (!d || !out) return TG_E_INVALID_ARG;
+namespace {
+
+// Pooled GPUs (Sec. 5.3, Alg. 4): the first GPU node of every snapshot stands for the pool.  The
+// folded description gives it the units, chunks and running actions of all GPU nodes of the
+// snapshot and leaves the others with nothing to hand out, so admission, DPArrange, eviction and
+// the completion heap run on one resource without knowing about the mode; `real_chunks` keeps
+// every node's own chunks for the kernel that hands out the real chunks afterwards.
+struct PoolFold {
+  std::vector<int32_t> cap, free_, busy_off;
+  std::vector<uint8_t> chunks;
+  std::vector<int64_t> busy_rel;
+  std::vector<uint32_t> real_chunks;
+};
+
+int fold_gpu_pool(const tg_problem_desc* d, PoolFold* f) {
+  const int B = d->B, N = d->N, M = d->M;
+  const size_t nN = (size_t)B * M;
+  if (d->act_service) return TG_E_INVALID_ARG;
+  for (size_t g = 0; g < (size_t)B * N; ++g)
+    if (d->act_type[g] == TG_TYPE_GPU && d->act_pin_node[g] >= 0) return TG_E_INVALID_ARG;
+  f->cap.assign(d->node_cap, d->node_cap + nN);
+  f->free_.assign(d->node_free, d->node_free + nN);
+  f->chunks.assign(nN * 4, 0);
+  f->real_chunks.assign(nN, 0);
+  f->busy_off.assign(nN + 1, 0);
+  std::vector<std::vector<int64_t>> busy(nN);
+  for (int b = 0; b < B; ++b) {
+    long pool = -1;
+    for (int j = 0; j < M; ++j) {
+      const size_t g = (size_t)b * M + j;
+      if (d->node_busy_off) {
+        const int lo = d->node_busy_off[g], hi = d->node_busy_off[g + 1];
+        if (lo < 0 || hi < lo || (hi > lo && !d->node_busy_rel_us)) return TG_E_INVALID_ARG;
+        busy[g].assign(d->node_busy_rel_us + lo, d->node_busy_rel_us + hi);
+      }
+      if (d->node_type[g] != TG_TYPE_GPU) continue;
+      const int fr = d->node_free[g];
+      if (d->node_cap[g] != 8 || fr < 0 || fr > 8 || (int)busy[g].size() > 8 - fr) return TG_E_INVALID_ARG;
+      uint8_t ch[4];
+      if (d->node_chunks) std::memcpy(ch, d->node_chunks + g * 4, 4);
+      else { ch[3] = (uint8_t)(fr / 8); ch[2] = (fr >> 2) & 1; ch[1] = (fr >> 1) & 1; ch[0] = fr & 1; }
+      if (ch[0] + 2 * ch[1] + 4 * ch[2] + 8 * ch[3] != fr) return TG_E_INVALID_ARG;
+      f->real_chunks[g] = ch[0] | ch[1] << 8 | ch[2] << 16 | (uint32_t)ch[3] << 24;
+      if (pool < 0) {
+        pool = (long)g;
+        std::memcpy(&f->chunks[g * 4], ch, 4);
+        continue;
+      }
+      if (d->node_backlog_us[g] != d->node_backlog_us[pool]) return TG_E_INVALID_ARG;   // a pool has one queueing term
+      if (f->cap[pool] + 8 > TG_MAX_GPU_UNITS) return TG_E_RANGE;
+      f->cap[pool] += 8; f->free_[pool] += fr; f->free_[g] = 0;
+      for (int x = 0; x < 4; ++x) f->chunks[(size_t)pool * 4 + x] += ch[x];
+      busy[pool].insert(busy[pool].end(), busy[g].begin(), busy[g].end());
+      busy[g].clear();
+    }
+  }
+  for (size_t g = 0; g < nN; ++g) {
+    f->busy_off[g + 1] = f->busy_off[g] + (int32_t)busy[g].size();
+    f->busy_rel.insert(f->busy_rel.end(), busy[g].begin(), busy[g].end());
+  }
+  return TG_OK;
+}
+
+}  // namespace
+
+extern "C" int tg_build_problem(const tg_problem_desc* desc, void* hip_stream, tg_problem** out) {
+  if (!desc || !out) return TG_E_INVALID_ARG;
   *out = nullptr;
+  if (desc->gpu_pooled != 0 && desc->gpu_pooled != 1) return TG_E_INVALID_ARG;
+  tg_problem_desc folded = *desc;
+  PoolFold fold;
+  if (desc->gpu_pooled) {
+    if (desc->B < 1 || desc->N < 1 || desc->M < 1 || (int64_t)desc->B * desc->N >= (1ll << 31) || (int64_t)desc->B * desc->M >= (1ll << 31))
+      return TG_E_INVALID_ARG;
+    if (!desc->node_type || !desc->node_cap || !desc->node_free || !desc->node_backlog_us || !desc->act_type || !desc->act_pin_node)
+      return TG_E_INVALID_ARG;
+    try {
+      const int rc = fold_gpu_pool(desc, &fold);
+      if (rc) return rc;
+    } catch (const std::bad_alloc&) { return TG_E_NOMEM; }
+    folded.node_cap = fold.cap.data(); folded.node_free = fold.free_.data(); folded.node_chunks = fold.chunks.data();
+    folded.node_busy_off = desc->node_busy_off ? fold.busy_off.data() : nullptr;
+    folded.node_busy_rel_us = desc->node_busy_off ? fold.busy_rel.data() : nullptr;
+  }
+  const tg_problem_desc* d = &folded;
   const int B = d->B, N = d->N, M = d->M, K = d->K;
   if (B < 1 || N < 1 || M < 1 || d->n_tasks < 1) return TG_E_INVALID_ARG;
   if (d->order_policy != TG_ORDER_FCFS && d->order_policy != TG_ORDER_COST) return TG_E_INVALID_ARG;
@@ -135,6 +217,8 @@ extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_p
       std::memcpy(ar.at<int32_t>(o_naux), d->node_aux_free, nN * 4);
       std::memcpy(ar.at<int32_t>(o_aaux), d->act_aux, nA * 4);
     }
+    const size_t o_nchreal = ar.add(d->gpu_pooled ? nN * 4 : 0);
+    if (d->gpu_pooled) std::memcpy(ar.at<uint32_t>(o_nchreal), fold.real_chunks.data(), nN * 4);
     const size_t o_aquota = ar.add(d->act_quota_mask ? nA * 8 : 0);
     if (d->act_quota_mask) std::memcpy(ar.at<uint64_t>(o_aquota), d->act_quota_mask, nA * 8);
     const size_t o_ncores = ar.add(d->node_core_free ? nN * 32 : 0);
@@ -357,6 +441,7 @@ extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_p
     v.restore = svc ? (const int64_t*)(base + o_rest) : nullptr;
     v.row_svc = svc ? (const uint64_t*)(base + o_rowsvc) : nullptr;
     v.node_res_k = svc ? (const uint64_t*)(base + o_nresk) : nullptr;
+    v.node_chunks_real = d->gpu_pooled ? (const uint32_t*)(base + o_nchreal) : nullptr;
     v.act_quota = d->act_quota_mask ? (const uint64_t*)(base + o_aquota) : nullptr;
     v.node_cores = d->node_core_free ? (const uint64_t*)(base + o_ncores) : nullptr;
     v.numa_cores = d->node_core_free ? d->numa_cores : 0;
@@ -381,7 +466,7 @@ extern "C" int tg_build_problem(const tg_problem_desc* d, void* hip_stream, tg_p
     p->max_chunk_states = max_states;
     p->score_lds_nodes = lds_nodes; p->score_dur_slots = (dur_slots + 1) & ~1; p->score_row_slots = row_slots;
   } catch (const std::bad_alloc&) {
-    delete p;
+    tg_free_problem(p);
     return TG_E_NOMEM;
   }
   *out = p;

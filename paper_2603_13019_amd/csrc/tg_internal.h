@@ -42,6 +42,7 @@ struct TgDev {
   const int64_t* restore;         // [TG_MAX_SERVICES] restore time per service
   const uint64_t* row_svc;        // [B*N] kind-grouped: restore time | (service + 1) << 48 of the row's action
   const uint64_t* node_res_k;     // [B*M] kind-grouped copy of node_resident (same order as node_word)
+  const uint32_t* node_chunks_real;  // [B*M] pooled GPUs: every node's own free chunks (node_chunks holds the pool's at its first node), else nullptr
   const uint64_t* act_quota;      // [B*N] further quotas of an API action (ranks among the snapshot's API nodes), or nullptr
   const uint64_t* node_cores;     // [B*M*4] bitmap of the free cores of CPU nodes, or nullptr: no core topology
   int numa_cores;                 // cores per NUMA domain (power of two, 4..64) when node_cores is given

@@ -334,28 +334,36 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
 // Admission of the pool's `Nt` actions (ids acts[0..Nt) in FCFS order) onto its `Mt` nodes.
 // On return S.cnt / S.dcnt hold the list lengths per node and every action has its reason,
 // node (-1 if deferred) and list slot written.
-// MAXR: the widest register variant the caller wants compiled in (1, 4 or 16 slots per lane);
-// MAXR_EXT: the same for the extended variant, taken when the caller passes a second resource
-// (io.act_aux) or services (io.act_service); 0: never (such pools then use the LDS table).
-template <int MAXR = 4, int MAXR_EXT = 0>
+// MAXR: the widest register variant the caller wants compiled in (0: none, 1, 4 or 16 slots per
+// lane); MAXR_EXT: the same for the extended variant, taken when the caller passes a second
+// resource (io.act_aux), services (io.act_service) or further quotas (io.act_quota).  Pools no
+// compiled variant takes use the LDS table below; LDS_TABLE = false leaves that path out for
+// callers whose pools always fit a compiled variant (the register allocation of a kernel is
+// shared by everything inlined into it, so a kernel does better with only the variants it runs).
+template <int MAXR = 4, int MAXR_EXT = 0, bool LDS_TABLE = true>
 __device__ static inline void tg_place_pool(const TgPoolLds& S, const TgPlaceIo& io, const int32_t* acts, int Nt,
                                             int Mt, bool gpu, int lane) {
   if (!io.cost && Mt <= 16 * TG_WAVE) {
     const int slots = Mt <= TG_WAVE ? 1 : Mt <= 4 * TG_WAVE ? 4 : 16;
     const bool ext = io.act_aux || io.act_service || io.act_quota;
-    if (ext ? slots <= MAXR_EXT : slots <= MAXR) {
-      if (ext) {
-        if (slots == 1) tg_place_pool_regs<1, (MAXR_EXT >= 1)>(S, io, acts, Nt, Mt, gpu, lane);
-        else if (slots == 4) tg_place_pool_regs<(MAXR_EXT >= 4 ? 4 : 1), (MAXR_EXT >= 1)>(S, io, acts, Nt, Mt, gpu, lane);
-        else tg_place_pool_regs<(MAXR_EXT >= 16 ? 16 : 1), (MAXR_EXT >= 1)>(S, io, acts, Nt, Mt, gpu, lane);
-      } else {
-        if (slots == 1) tg_place_pool_regs<1, false>(S, io, acts, Nt, Mt, gpu, lane);
-        else if (slots == 4) tg_place_pool_regs<(MAXR >= 4 ? 4 : 1), false>(S, io, acts, Nt, Mt, gpu, lane);
-        else tg_place_pool_regs<(MAXR >= 16 ? 16 : 1), false>(S, io, acts, Nt, Mt, gpu, lane);
+    if constexpr (MAXR_EXT >= 1) {
+      if (ext && slots <= MAXR_EXT) {
+        if (slots == 1) tg_place_pool_regs<1, true>(S, io, acts, Nt, Mt, gpu, lane);
+        if constexpr (MAXR_EXT >= 4) { if (slots == 4) tg_place_pool_regs<4, true>(S, io, acts, Nt, Mt, gpu, lane); }
+        if constexpr (MAXR_EXT >= 16) { if (slots == 16) tg_place_pool_regs<16, true>(S, io, acts, Nt, Mt, gpu, lane); }
+        return;
       }
-      return;
+    }
+    if constexpr (MAXR >= 1) {
+      if (!ext && slots <= MAXR) {
+        if (slots == 1) tg_place_pool_regs<1, false>(S, io, acts, Nt, Mt, gpu, lane);
+        if constexpr (MAXR >= 4) { if (slots == 4) tg_place_pool_regs<4, false>(S, io, acts, Nt, Mt, gpu, lane); }
+        if constexpr (MAXR >= 16) { if (slots == 16) tg_place_pool_regs<16, false>(S, io, acts, Nt, Mt, gpu, lane); }
+        return;
+      }
     }
   }
+  if constexpr (!LDS_TABLE) return;
   bool pool_closed = false;
   // which options fit into `units` units, for units = 0..64 (every unit count is <= 64)
   tg_wave_sync();

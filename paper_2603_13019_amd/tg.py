@@ -31,8 +31,8 @@ class ProblemDesc(C.Structure):
             "k_list", "type_k", "speedup_q16", "node_type", "node_cap", "node_free", "node_backlog_us",
             "node_chunks", "node_busy_off", "node_busy_rel_us", "act_type", "act_model", "act_t_ori_us",
             "act_age_us", "act_kmask", "act_param", "act_pin_node", "act_task", "node_aux_free", "act_aux",
-            "act_service", "node_resident", "restore_us", "node_core_free", "act_quota_mask")] + [("n_services", C.c_int32),
-                                                                               ("numa_cores", C.c_int32)]
+            "act_service", "node_resident", "restore_us", "node_core_free", "act_quota_mask")] + [(n, C.c_int32) for n in
+                                                                        ("n_services", "numa_cores", "gpu_pooled", "reserved_")]
 
 
 class AssignOut(C.Structure):
@@ -140,9 +140,10 @@ class Problem:
             setattr(d, n, int(p[n]))
         d.order_policy = int(p.get("order_policy", 0))
         keep = []
-        _fill(d, p, [f[0] for f in ProblemDesc._fields_[8:-2]], keep)
+        _fill(d, p, [f[0] for f in ProblemDesc._fields_[8:-4]], keep)
         d.n_services = len(p["restore_us"]) if p.get("restore_us") is not None else 0
         d.numa_cores = int(p.get("numa_cores", 0))
+        d.gpu_pooled = int(p.get("gpu_pooled", 0))
         self.has_cores = p.get("node_core_free") is not None
         h = C.c_void_p()
         _check(L.tg_build_problem(C.byref(d), _stream(), C.byref(h)), "tg_build_problem")

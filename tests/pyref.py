@@ -106,6 +106,28 @@ class Buddy:
         self.mask |= ((1 << size) - 1) << s
 
 
+class BuddyCluster:
+    """Several 8-GPU nodes behind one allocator: the smallest free chunk of the cluster that is large
+    enough, on the lowest-numbered node that has one, lowest address there."""
+
+    def __init__(self, masks):
+        self.nodes = [Buddy(m) for m in masks]
+
+    def counts(self):
+        return tuple(sum(c) for c in zip(*[b.counts() for b in self.nodes])) if self.nodes else (0, 0, 0, 0)
+
+    def alloc(self, k):
+        size = 1
+        while size < k:
+            size *= 2
+        cands = sorted((sz, j, s) for j, b in enumerate(self.nodes) for s, sz in b.chunks() if sz >= size)
+        if not cands:
+            return None
+        sz, j, s = cands[0]
+        self.nodes[j].mask &= ~(((1 << size) - 1) << s)
+        return j, s
+
+
 def best_chunks_exhaustive(opts, mask):
     """min sum of durations over unit vectors that a buddy allocator can serve in order."""
     best = None

@@ -37,7 +37,7 @@ def test_strerror(tg):
 
 
 def test_struct_layouts_match_header(tg):
-    assert C.sizeof(tg.ProblemDesc) == 8 * 4 + 25 * 8 + 2 * 4
+    assert C.sizeof(tg.ProblemDesc) == 8 * 4 + 25 * 8 + 4 * 4
     assert C.sizeof(tg.AssignOut) == 9 * 8
     assert C.sizeof(tg.TraceDesc) == 8 * 4 + 8 + 16 * 8 + 2 * 4
     assert C.sizeof(tg.ReplayOut) == 8 * 8
@@ -50,9 +50,10 @@ def _build_rc(tg, p):
         setattr(d, n, int(p[n]))
     d.order_policy = int(p.get("order_policy", 0))
     keep = []
-    tg._fill(d, p, [f[0] for f in tg.ProblemDesc._fields_[8:-2]], keep)
+    tg._fill(d, p, [f[0] for f in tg.ProblemDesc._fields_[8:-4]], keep)
     d.n_services = int(p.get("n_services", len(p["restore_us"]) if p.get("restore_us") is not None else 0))
     d.numa_cores = int(p.get("numa_cores", 0))
+    d.gpu_pooled = int(p.get("gpu_pooled", 0))
     h = C.c_void_p()
     rc = tg.load().tg_build_problem(C.byref(d), None, C.byref(h))
     assert rc != 0 and not h.value
@@ -181,6 +182,27 @@ def test_quota_masks_are_validated(tg):
     c = int(np.flatnonzero(p["act_type"] == gen.TYPE_CPU)[0])
     m = p["act_quota_mask"].copy(); m[c] = np.uint64(1)
     assert _build_rc(tg, dict(p, act_quota_mask=m)) == -1       # only API actions draw on quotas
+
+
+def test_pooled_gpus_are_validated(tg):
+    p = gen.make_random_problem(14, B=1, N=40, n_cpu=1, n_gpu=3, n_api=0, pin_frac=0.0, shuffle_nodes=False)
+    g = np.flatnonzero(p["node_type"] == gen.TYPE_GPU)
+    p["node_backlog_us"][g] = 0
+    p["gpu_pooled"] = 1
+    assert _build_rc(tg, dict(p, gpu_pooled=2)) == -1
+    q = dict(p); q["node_backlog_us"] = p["node_backlog_us"].copy(); q["node_backlog_us"][g[1]] = 5
+    assert _build_rc(tg, q) == -1                               # a pool has one backlog
+    q = dict(p); q["act_pin_node"] = p["act_pin_node"].copy()
+    q["act_pin_node"][int(np.flatnonzero(p["act_type"] == gen.TYPE_GPU)[0])] = int(g[0])
+    assert _build_rc(tg, q) == -1                               # no GPU action pinned to a node of the pool
+    q = dict(p); q["node_cap"] = p["node_cap"].copy(); q["node_cap"][g[2]] = 16
+    assert _build_rc(tg, q) == -1                               # nodes of 8 GPUs
+    q = dict(p, act_service=np.full(40, -1, np.int32), node_resident=np.zeros(p["M"], np.uint64),
+             restore_us=np.array([5], np.int64))
+    assert _build_rc(tg, q) == -1                               # services need per-node residency
+    big = gen.make_random_problem(15, B=1, N=40, n_cpu=0, n_gpu=9, n_api=0, pin_frac=0.0, bad_frac=0.0)
+    big["node_backlog_us"][:] = 0
+    assert _build_rc(tg, dict(big, gpu_pooled=1)) == -2         # more than 64 GPUs in one pool
 
 
 def test_cost_order_needs_pools_it_can_sort(tg):

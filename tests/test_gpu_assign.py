@@ -285,6 +285,10 @@ def _sweep_problem(seed):
     if rng.random() < 0.5:
         _add_services(p, seed, n_services=int(rng.choice([1, 5, 64])), big=bool(rng.integers(0, 2)))
     use_cost = bool(rng.integers(0, 2))
+    if kw["n_gpu"] and p.get("act_service") is None and rng.random() < 0.5:
+        _pooled(p)                                           # the GPU nodes as one pool of chunks
+        if _pool_states(p) > 512:
+            p["gpu_pooled"] = 0
     if rng.random() < 0.5:
         gen.with_extra_quotas(p, frac=float(rng.random()), seed=seed, max_extra=int(rng.integers(1, 6)))
     if rng.random() < 0.5:
@@ -294,7 +298,7 @@ def _sweep_problem(seed):
 
 def test_assign_random_sweep(tg, orc):
     """200 problems with every parameter drawn at random (sizes, kinds, capacities, options, depth, busy
-    lists, pins, duration scale, visiting order, second resource, services, several quotas, core maps, with and without the score tensor)."""
+    lists, pins, duration scale, visiting order, second resource, services, pooled GPUs, several quotas, core maps, with and without the score tensor)."""
     for seed in range(3000, 3200):
         p, use_cost = _sweep_problem(seed)
         _compare(_assign_gpu(tg, p, use_cost=use_cost), orc.assign(p), f"sweep seed {seed}")
@@ -423,3 +427,58 @@ def test_assign_several_quotas_many_api_nodes(tg, orc):
         p["type_k"][gen.TYPE_GPU] = 0
         gen.with_extra_quotas(p, frac=0.7, seed=n_api, max_extra=5)
         _compare(_assign_gpu(tg, p), orc.assign(p), f"several quotas, {n_api} API nodes")
+
+
+def _pooled(p):
+    """All GPU nodes of a snapshot share one backlog (a pool has one queueing term) and form one pool."""
+    M = p["M"]
+    for b in range(p["B"]):
+        g = np.flatnonzero(p["node_type"][b * M:(b + 1) * M] == gen.TYPE_GPU) + b * M
+        if len(g):
+            p["node_backlog_us"][g] = p["node_backlog_us"][g[0]]
+    p["act_pin_node"][p["act_type"] == gen.TYPE_GPU] = -1      # actions are not pinned to a node of a pool
+    p["gpu_pooled"] = 1
+    return p
+
+
+def _pool_states(p):
+    """Largest number of chunk states a pool of the problem needs (the interface takes up to 512)."""
+    M, worst = p["M"], 1
+    ch = p["node_chunks"].reshape(-1, 4).astype(np.int64)
+    for b in range(p["B"]):
+        g = np.flatnonzero(p["node_type"][b * M:(b + 1) * M] == gen.TYPE_GPU) + b * M
+        if len(g):
+            c = ch[g].sum(axis=0)
+            worst = max(worst, int(np.prod(np.maximum(c, 1) + 1)))
+    return worst
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_assign_pooled_gpus_random_problems(tg, orc, seed):
+    """Sec. 5.3 / Alg. 4 with the GPU cluster as one pool of chunks: units, ACT, reasons and the node whose
+    chunk every action gets."""
+    print("case pooled", seed, flush=True)
+    n_gpu = 1 + seed % 5
+    p = _pooled(gen.make_random_problem(1000 + seed, B=4, N=100 + 30 * seed, n_cpu=1 + seed % 2, n_gpu=n_gpu, n_api=seed % 2,
+                                        depth=1 + seed % 3, busy=seed % 2 == 0, pin_frac=0.0, type_probs=(0.3, 0.6, 0.1)))
+    if _pool_states(p) > 512:
+        pytest.skip("pooled chunk counts beyond the supported number of states")
+    p["order_policy"] = seed % 2
+    want = orc.assign(p)
+    assert (want["units"][p["act_type"] == gen.TYPE_GPU] > 0).sum() > 3
+    _compare(_assign_gpu(tg, p, use_cost=seed % 3 == 1), want, f"pooled {seed}")
+
+
+def test_assign_pooled_gpus_eight_free_nodes(tg, orc):
+    """The largest pool: eight nodes of eight free GPUs, a long queue of elastic GPU actions."""
+    p = gen.make_random_problem(1040, B=3, N=400, n_cpu=1, n_gpu=8, n_api=0, pin_frac=0.0, busy=False, type_probs=(0.1, 0.9, 0.0))
+    g = p["node_type"] == gen.TYPE_GPU
+    p["node_free"][g] = 8
+    ch = p["node_chunks"].reshape(-1, 4)
+    ch[g] = (0, 0, 0, 1)
+    a = p["act_type"] == gen.TYPE_GPU
+    p["act_kmask"][a] |= 1
+    _pooled(p)
+    want = orc.assign(p)
+    assert (want["node_used"][g] > 0).all()                       # every node of the pool hands out chunks
+    _compare(_assign_gpu(tg, p), want, "pooled, 8 nodes")
