@@ -135,9 +135,12 @@ struct TgPlaceIo {
 // result goes back into the action's lane as one word; an action pinned to a node has a
 // single candidate and is handled with scalar code; with R = 1 the smallest rank among equal
 // estimates is simply the lowest lane.  Same decisions as the LDS variant below.
-template <int R, bool AUX>
+template <int R, bool AUX, bool GPU>
 __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPlaceIo& io, const int32_t* acts, int Nt,
-                                                 int Mt, bool gpu, int lane) {
+                                                 int Mt, int lane) {
+  // the sizes are the same in every lane: keep the loop control on scalars
+  Nt = __builtin_amdgcn_readfirstlane(Nt);
+  Mt = __builtin_amdgcn_readfirstlane(Mt);
   bool pool_closed = false;
   tg_wave_sync();
   for (int u = lane; u <= TG_MAX_UNIT; u += TG_WAVE) {
@@ -156,8 +159,16 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
   uint64_t closed[R];                                             // wavefront-uniform copies of the closed flags
   int64_t bmin = TG_INF, bmax = 0;
   auto fit_of = [&](int32_t lim) {
-    const int u = gpu ? tg_chunk_largest((uint32_t)lim) : lim;
+    const int u = GPU ? tg_chunk_largest((uint32_t)lim) : lim;
     return (uint32_t)S.fit[u < TG_MAX_UNIT ? u : TG_MAX_UNIT];
+  };
+  // the same table across the lanes (lane u: what fits into u units), for lookups with a
+  // wavefront-uniform argument in the admission loop: one lane read instead of an LDS round trip
+  const uint32_t fit_tab = S.fit[lane];
+  const uint32_t fit_full = (uint32_t)__builtin_amdgcn_readfirstlane((int)S.fit[TG_MAX_UNIT]);
+  auto fit_of_uniform = [&](int32_t lim) {
+    const int u = GPU ? tg_chunk_largest((uint32_t)lim) : lim;
+    return u >= TG_MAX_UNIT ? fit_full : (uint32_t)__builtin_amdgcn_readlane((int)fit_tab, u);
   };
 #pragma unroll
   for (int s = 0; s < R; ++s) {
@@ -300,11 +311,14 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
         for (int s = 0; s < R; ++s) {
           if ((take_rank >> 6) != s) continue;
           slot = __builtin_amdgcn_readlane(cntv[s], rl);
+          const int32_t lim_old = __builtin_amdgcn_readlane(limv[s], rl);      // the node's new state on scalars
+          const int32_t lim_new = GPU ? (int32_t)tg_chunk_take((uint32_t)lim_old, kmin) : lim_old - kmin;
+          const uint32_t fit_new = fit_of_uniform(lim_new);
           if (lane == rl) {
             ++cntv[s];
             if (AUX) auxv[s] -= aux;
-            limv[s] = gpu ? (int32_t)tg_chunk_take((uint32_t)limv[s], kmin) : limv[s] - kmin;
-            fitv[s] = fit_of(limv[s]);
+            limv[s] = lim_new;
+            fitv[s] = fit_new;
           }
         }
         if (AUX && more != 0 && (more >> lane & 1ull)) {           // one token of every further quota
@@ -331,6 +345,14 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
   tg_wave_sync();
 }
 
+// The loop specialised on whether the pool's units are buddy chunks (GPU) or plain counts.
+template <int R, bool AUX>
+__device__ static inline void tg_place_pool_regs_kind(const TgPoolLds& S, const TgPlaceIo& io, const int32_t* acts, int Nt,
+                                                      int Mt, bool gpu, int lane) {
+  if (gpu) tg_place_pool_regs<R, AUX, true>(S, io, acts, Nt, Mt, lane);
+  else tg_place_pool_regs<R, AUX, false>(S, io, acts, Nt, Mt, lane);
+}
+
 // Admission of the pool's `Nt` actions (ids acts[0..Nt) in FCFS order) onto its `Mt` nodes.
 // On return S.cnt / S.dcnt hold the list lengths per node and every action has its reason,
 // node (-1 if deferred) and list slot written.
@@ -348,17 +370,17 @@ __device__ static inline void tg_place_pool(const TgPoolLds& S, const TgPlaceIo&
     const bool ext = io.act_aux || io.act_service || io.act_quota;
     if constexpr (MAXR_EXT >= 1) {
       if (ext && slots <= MAXR_EXT) {
-        if (slots == 1) tg_place_pool_regs<1, true>(S, io, acts, Nt, Mt, gpu, lane);
-        if constexpr (MAXR_EXT >= 4) { if (slots == 4) tg_place_pool_regs<4, true>(S, io, acts, Nt, Mt, gpu, lane); }
-        if constexpr (MAXR_EXT >= 16) { if (slots == 16) tg_place_pool_regs<16, true>(S, io, acts, Nt, Mt, gpu, lane); }
+        if (slots == 1) tg_place_pool_regs_kind<1, true>(S, io, acts, Nt, Mt, gpu, lane);
+        if constexpr (MAXR_EXT >= 4) { if (slots == 4) tg_place_pool_regs_kind<4, true>(S, io, acts, Nt, Mt, gpu, lane); }
+        if constexpr (MAXR_EXT >= 16) { if (slots == 16) tg_place_pool_regs_kind<16, true>(S, io, acts, Nt, Mt, gpu, lane); }
         return;
       }
     }
     if constexpr (MAXR >= 1) {
       if (!ext && slots <= MAXR) {
-        if (slots == 1) tg_place_pool_regs<1, false>(S, io, acts, Nt, Mt, gpu, lane);
-        if constexpr (MAXR >= 4) { if (slots == 4) tg_place_pool_regs<4, false>(S, io, acts, Nt, Mt, gpu, lane); }
-        if constexpr (MAXR >= 16) { if (slots == 16) tg_place_pool_regs<16, false>(S, io, acts, Nt, Mt, gpu, lane); }
+        if (slots == 1) tg_place_pool_regs_kind<1, false>(S, io, acts, Nt, Mt, gpu, lane);
+        if constexpr (MAXR >= 4) { if (slots == 4) tg_place_pool_regs_kind<4, false>(S, io, acts, Nt, Mt, gpu, lane); }
+        if constexpr (MAXR >= 16) { if (slots == 16) tg_place_pool_regs_kind<16, false>(S, io, acts, Nt, Mt, gpu, lane); }
         return;
       }
     }

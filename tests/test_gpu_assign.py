@@ -482,3 +482,18 @@ def test_assign_pooled_gpus_eight_free_nodes(tg, orc):
     want = orc.assign(p)
     assert (want["node_used"][g] > 0).all()                       # every node of the pool hands out chunks
     _compare(_assign_gpu(tg, p), want, "pooled, 8 nodes")
+
+
+def test_assign_pooled_gpus_config2_full(tg, orc):
+    """Workload 2 at full size with the eight GPU nodes of every snapshot as one pool (GPU actions unpinned, the
+    GPU nodes of a snapshot at their mean backlog)."""
+    p = gen.make_config(2)
+    M = p["M"]
+    for b in range(p["B"]):
+        g = np.flatnonzero(p["node_type"][b * M:(b + 1) * M] == gen.TYPE_GPU) + b * M
+        p["node_backlog_us"][g] = int(p["node_backlog_us"][g].mean())
+    _pooled(p)
+    want = orc.assign(p)
+    gpu = p["node_type"] == gen.TYPE_GPU
+    assert (want["node_used"][gpu] > 0).mean() > 0.9
+    _compare(_assign_gpu(tg, p), want)
