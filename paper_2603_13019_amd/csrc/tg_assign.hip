@@ -207,6 +207,7 @@ __global__ __launch_bounds__(TG_WAVE) void tg_place_kernel(TgDev P, const int64_
   io.act_aux = P.act_aux ? P.act_aux + abase : nullptr;
   io.act_service = P.act_service ? P.act_service + abase : nullptr; io.restore = P.restore;
   io.act_quota = P.act_quota && t == TG_TYPE_API ? P.act_quota + abase : nullptr;
+  io.act_pin_rank = P.act_pin_rank + abase;
   io.node_rank = P.node_rank + nbase; io.nodes = nodes; io.dur = dur + abase * P.K; io.K = P.K; io.Kt = P.type_k[t];
   io.cost = nullptr; io.cost_row_len = 0;
   if (cost) { const TgBlock blk = blocks[b * 3 + t]; io.cost = cost + blk.cost_off; io.cost_row_len = blk.M_t * blk.K_t; }

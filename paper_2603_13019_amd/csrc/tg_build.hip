@@ -285,7 +285,8 @@ extern "C" int tg_build_problem(const tg_problem_desc* desc, void* hip_stream, t
     int max_acts_kind = 0;
     const size_t o_atype = ar.add(nA), o_amodel = ar.add(nA), o_astat = ar.add(nA), o_aT = ar.add(nA * 8),
                  o_aage = ar.add(nA * 8), o_amask = ar.add(nA * 4), o_aparam = ar.add(nA * 4), o_apin = ar.add(nA * 4),
-                 o_atask = ar.add(nA * 4), o_taidx = ar.add(nA * 4), o_taoff = ar.add((size_t)B * 4 * 4);
+                 o_atask = ar.add(nA * 4), o_taidx = ar.add(nA * 4), o_taoff = ar.add((size_t)B * 4 * 4),
+                 o_apinrank = ar.add(nA * 4);
     for (int b = 0; b < B; ++b) {
       int cnt[3] = {0, 0, 0};
       int64_t sumT = 0;
@@ -331,6 +332,7 @@ extern "C" int tg_build_problem(const tg_problem_desc* desc, void* hip_stream, t
         ar.at<uint32_t>(o_amask)[g] = mask;
         ar.at<uint32_t>(o_aparam)[g] = param;
         ar.at<int32_t>(o_apin)[g] = pin;
+        ar.at<int32_t>(o_apinrank)[g] = pin >= 0 && !infeasible ? ar.at<int32_t>(o_nrank)[(size_t)b * M + pin] : -1;
         ar.at<int32_t>(o_atask)[g] = task;
         ++cnt[t];
       }
@@ -436,6 +438,7 @@ extern "C" int tg_build_problem(const tg_problem_desc* desc, void* hip_stream, t
     v.act_static = (const uint8_t*)(base + o_astat); v.act_T = (const int64_t*)(base + o_aT);
     v.act_age = (const int64_t*)(base + o_aage); v.act_kmask = (const uint32_t*)(base + o_amask);
     v.act_param = (const uint32_t*)(base + o_aparam); v.act_pin = (const int32_t*)(base + o_apin);
+    v.act_pin_rank = (const int32_t*)(base + o_apinrank);
     v.act_service = svc ? (const int32_t*)(base + o_asvc) : nullptr;
     v.node_resident = svc ? (const uint64_t*)(base + o_nres) : nullptr;
     v.restore = svc ? (const int64_t*)(base + o_rest) : nullptr;

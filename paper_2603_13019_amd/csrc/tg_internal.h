@@ -33,6 +33,7 @@ struct TgDev {
   const uint32_t* act_kmask;      // effective mask: limited to the kind's options, lowest bit only if non-elastic
   const uint32_t* act_param;
   const int32_t* act_pin;         // node index or -1
+  const int32_t* act_pin_rank;    // rank of the pinned node among the nodes of its kind, -1: free or statically infeasible
   const int32_t* act_task;
   const int32_t* node_aux;        // [B*M] second resource left on the node, or nullptr: no second resource
   const int32_t* act_aux;         // [B*N] what an unpinned action needs of it (nullptr together with node_aux)

@@ -314,6 +314,7 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
       io.act_kmask = T.act_kmask + abase; io.act_static = T.act_static + abase; io.act_pin = T.act_pin + abase;
       io.act_aux = nullptr; io.act_quota = nullptr;               // traces carry no second resource and one quota per action
       io.act_service = T.act_service ? T.act_service + abase : nullptr; io.restore = T.restore;
+      io.act_pin_rank = nullptr;
       io.node_rank = T.node_rank + nbase; io.nodes = nodes; io.dur = dur; io.cost = nullptr; io.cost_row_len = 0;
       io.K = K; io.Kt = T.type_k[ty];
       io.out_node = o_node; io.out_units = o_units; io.out_act = nullptr; io.out_reason = reason; io.slot = slot;

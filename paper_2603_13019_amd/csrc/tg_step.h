@@ -117,6 +117,8 @@ struct TgPlaceIo {
   const int32_t* act_service;  // service the action calls (-1: none), or nullptr: no services
   const int64_t* restore;      // [service] restore time where the service is not resident (Sec. 5.3)
   const uint64_t* act_quota;   // further quotas of a pinned action (ranks < 64 inside this pool), or nullptr (Sec. 4.1)
+  const int32_t* act_pin_rank; // rank of the action's pinned node inside its pool, -1: free or statically infeasible; or
+                               // nullptr: derive it from act_pin and node_rank
   const int32_t* node_rank;    // node id -> rank inside this pool
   const int32_t* nodes;        // rank -> node id
   const int64_t* dur;          // [id*K + q]
@@ -190,35 +192,67 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
   for (int s = 0; s < R; ++s) { const int r = lane + TG_WAVE * s; back32[s] = r < Mt ? (uint32_t)(S.back[r] - bmin) : 0u; }   // meaningful where the range fits
   // result word of an action: rank + 1 (13 bits) | list slot (17 bits) | reason (2 bits)
   auto pack_res = [](int rank, int slot, int reason) { return (uint32_t)(rank + 1) | (uint32_t)slot << 13 | (uint32_t)reason << 30; };
+  // What the loop needs of 64 actions is fetched one chunk ahead (and the action ids two chunks
+  // ahead), lane l taking action base+l with its row of durations, so that the two dependent
+  // global-memory round trips of a chunk run behind the admission of the chunk before it.
+  struct Stage {
+    int id, aux, svc, pin;
+    int64_t x;
+    uint32_t mask, stat;
+    int64_t d[TG_MAX_K];
+  };
+  auto fetch_id = [&](int base) { return base + lane < Nt ? acts[base + lane] : 0; };
+  auto fetch = [&](int base, int id, Stage& st) {
+    st.id = id; st.aux = 0; st.svc = -1; st.pin = -1; st.x = 0; st.mask = 0; st.stat = 0;
+#pragma unroll
+    for (int q = 0; q < TG_MAX_K; ++q) st.d[q] = TG_INF;
+    if (base + lane < Nt) {
+      if (has_x) st.x = (int64_t)io.act_quota[id];
+      if (has_aux) st.aux = io.act_aux[id];
+      if (has_svc) st.svc = io.act_service[id];
+      st.mask = io.act_kmask[id]; st.stat = io.act_static[id] ? 1u : 0u;
+      st.pin = io.act_pin_rank ? io.act_pin_rank[id] : io.act_pin[id];
+#pragma unroll
+      for (int q = 0; q < TG_MAX_K; ++q) if (q < io.K) st.d[q] = io.dur[(size_t)id * io.K + q];
+    }
+  };
+  // restore times across the lanes (lane s: service s), read with a uniform index in the loop
+  const int64_t rest_tab = has_svc ? io.restore[lane] : 0;
+  const int64_t rest_max = has_svc ? (int64_t)~tg_wave_min_u64(~(uint64_t)rest_tab) : 0;
+  int next_id = fetch_id(0);
+  Stage cur;
+  fetch(0, next_id, cur);
+  next_id = fetch_id(TG_WAVE);
   for (int base = 0; base < Nt; base += TG_WAVE) {
     const int cnt = min(TG_WAVE, Nt - base);
     // lane l holds action base+l: its inputs now (mask | static << 8 | minimum units << 9 |
     // (pinned rank + 1) << 16), its result after the loop
-    int my_id = 0, my_aux = 0, my_svc = -1;
-    int64_t my_rest = 0;                             // restore time of the action's service
+    const int my_id = cur.id, my_aux = cur.aux, my_svc = cur.svc;
+    const int64_t my_x = cur.x;
     uint32_t my_w = 0, my_res = 0;
-    int64_t my_x = 0;
     if (lane < cnt) {
-      my_id = acts[base + lane];
-      if (has_x) my_x = (int64_t)io.act_quota[my_id];
-      if (has_aux) my_aux = io.act_aux[my_id];
-      if (has_svc) { my_svc = io.act_service[my_id]; if (my_svc >= 0) my_rest = io.restore[my_svc]; }
-      const uint32_t mask = io.act_kmask[my_id], stat = io.act_static[my_id] ? 1u : 0u;
-      const int pin = io.act_pin[my_id];
-      const int pr = pin >= 0 && !stat ? io.node_rank[pin] : -1;
+      const uint32_t mask = cur.mask, stat = cur.stat;
+      int pr = cur.pin;
+      if (!io.act_pin_rank) pr = pr >= 0 && !stat ? io.node_rank[pr] : -1;
       const uint32_t kmin = mask ? (uint32_t)S.k[__builtin_ctz(mask)] : 0u;
       my_w = (mask & 0xffu) | stat << 8 | kmin << 9 | (uint32_t)(pr + 1) << 16;
     }
     tg_wave_sync();                                  // previous chunk's readers are done with S.dur
     int64_t dmax = 0;
-    for (int x = lane; x < cnt * io.K; x += TG_WAVE) {
-      const int a = x / io.K, q = x - a * io.K;
-      const int64_t d = io.dur[(size_t)acts[base + a] * io.K + q];
-      S.dur[x] = d;
-      if (d != TG_INF && d > dmax) dmax = d;
+    if (lane < cnt) {
+#pragma unroll
+      for (int q = 0; q < TG_MAX_K; ++q)
+        if (q < io.K) {
+          const int64_t d = cur.d[q];
+          S.dur[lane * io.K + q] = d;
+          if (d != TG_INF && d > dmax) dmax = d;
+        }
     }
+    Stage nxt;                                       // in flight while this chunk is admitted
+    fetch(base + TG_WAVE, next_id, nxt);
+    next_id = fetch_id(base + 2 * TG_WAVE);
     dmax = (int64_t)~tg_wave_min_u64(~(uint64_t)dmax);
-    if (has_svc) dmax += (int64_t)~tg_wave_min_u64(~(uint64_t)my_rest);   // bound on duration + restore delay
+    if (has_svc) dmax += rest_max;                   // bound on duration + restore delay
     // every estimate of the chunk fits in 32 bits above the smallest backlog (durations included)
     const bool narrow = Mt > 0 && (bmax + dmax - bmin) < 0xfffffff0ll;
     const uint32_t* dur32 = reinterpret_cast<const uint32_t*>(S.dur);   // low words
@@ -229,7 +263,7 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
       const int kmin = (int)(w >> 9 & 0x7fu), pr = (int)(w >> 16) - 1;
       const int aux = has_aux && pr < 0 ? __builtin_amdgcn_readlane(my_aux, l) : 0;   // pinned: already charged
       const int svc = has_svc ? __builtin_amdgcn_readlane(my_svc, l) : -1;
-      const int64_t rest = has_svc ? tg_readlane_i64(my_rest, l) : 0;
+      const int64_t rest = has_svc && svc >= 0 ? tg_readlane_i64(rest_tab, svc) : 0;
       const uint64_t more = has_x && pr >= 0 ? (uint64_t)tg_readlane_i64(my_x, l) : 0ull;   // ranks are lanes of slot 0
       uint32_t res;
       int take_rank = -1;                                          // node that admits the action
@@ -336,6 +370,7 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
       io.slot[my_id] = res_slot;
       if (res_reason != TG_SELECTED) { io.out_units[my_id] = 0; if (io.out_act) io.out_act[my_id] = -1; }
     }
+    cur = nxt;
   }
 #pragma unroll
   for (int s = 0; s < R; ++s) {
