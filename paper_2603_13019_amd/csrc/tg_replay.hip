@@ -354,10 +354,9 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
           int k = 0;
           int64_t fin = 0;
           if (x < n) { const int info = run_info[x]; if ((info & 0xffff) == j) { k = (info >> 16) & 0xff; fin = run_fin[x] - now; } }
-          int inc = k;
-          for (int o = 1; o < TG_WAVE; o <<= 1) { const int u = __shfl_up(inc, o); if (lane >= o) inc += u; }
+          const int inc = tg_wave_scan_i32(k);
           for (int c = 0; c < k; ++c) s_busy[nb + inc - k + c] = fin;
-          nb += __shfl(inc, TG_WAVE - 1);
+          nb += __builtin_amdgcn_readlane(inc, TG_WAVE - 1);
         }
       }
       TgNodeIn in;

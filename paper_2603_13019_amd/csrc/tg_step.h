@@ -63,16 +63,38 @@ __device__ static inline uint32_t tg_wave_min_u32(uint32_t v) {
   return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
 
-__device__ static inline int tg_wave_sum_i32(int v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+// Inclusive prefix sum across the wavefront on data-parallel-primitive moves: shifts by 1, 2, 4,
+// 8 inside the rows of 16 lanes (lanes without a source add 0), then the total of row 0 into
+// row 1 and of row 2 into row 3, then the total of rows 0-1 into rows 2-3.
+__device__ static inline int tg_wave_scan_i32(int v) {
+#define TG_DPP_ADD_STEP(CTRL, ROWMASK) v += __builtin_amdgcn_update_dpp(0, v, CTRL, ROWMASK, 0xf, false);
+  TG_DPP_ADD_STEP(0x111, 0xf) TG_DPP_ADD_STEP(0x112, 0xf) TG_DPP_ADD_STEP(0x114, 0xf) TG_DPP_ADD_STEP(0x118, 0xf)
+  TG_DPP_ADD_STEP(0x142, 0xa) TG_DPP_ADD_STEP(0x143, 0xc)
+#undef TG_DPP_ADD_STEP
   return v;
 }
+
+__device__ static inline int tg_wave_sum_i32(int v) { return __builtin_amdgcn_readlane(tg_wave_scan_i32(v), TG_WAVE - 1); }
 
 __device__ static inline int64_t tg_readlane_i64(int64_t v, int l) {
   const int lo = __builtin_amdgcn_readlane((int)(uint32_t)v, l);
   const int hi = __builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)v >> 32), l);
   return (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+}
+
+// Wavefront-wide 64-bit sum (same moves as the prefix sum above, both halves), in every lane.
+__device__ static inline int64_t tg_wave_sum_i64(int64_t x) {
+  uint64_t v = (uint64_t)x;
+#define TG_DPP_ADD64_STEP(CTRL, ROWMASK)                                                                                  \
+  {                                                                                                                       \
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)v, CTRL, ROWMASK, 0xf, false);            \
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(v >> 32), CTRL, ROWMASK, 0xf, false);    \
+    v += (uint64_t)hi << 32 | lo;                                                                                         \
+  }
+  TG_DPP_ADD64_STEP(0x111, 0xf) TG_DPP_ADD64_STEP(0x112, 0xf) TG_DPP_ADD64_STEP(0x114, 0xf) TG_DPP_ADD64_STEP(0x118, 0xf)
+  TG_DPP_ADD64_STEP(0x142, 0xa) TG_DPP_ADD64_STEP(0x143, 0xc)
+#undef TG_DPP_ADD64_STEP
+  return tg_readlane_i64((int64_t)v, TG_WAVE - 1);
 }
 
 // ---------------------------------------------------------------------------- placement
@@ -549,18 +571,14 @@ __device__ static inline void tg_pool_extents(const TgPoolLds& S, const int32_t*
   for (int base = 0; base < Mt; base += TG_WAVE) {
     const int r = base + lane;
     const int c = r < Mt ? S.cnt[r] : 0, dc = r < Mt ? S.dcnt[r] : 0;
-    int inc = c, dinc = dc;
-    for (int o = 1; o < TG_WAVE; o <<= 1) {
-      const int u = __shfl_up(inc, o), du = __shfl_up(dinc, o);
-      if (lane >= o) { inc += u; dinc += du; }
-    }
+    const int inc = tg_wave_scan_i32(c), dinc = tg_wave_scan_i32(dc);
     if (r < Mt) {
       const int g = nodes[r];
       nl_off[g] = run + inc - c; nl_cnt[g] = c;
       dl_off[g] = drun + dinc - dc; dl_cnt[g] = dc;
     }
-    run += __shfl(inc, TG_WAVE - 1);
-    drun += __shfl(dinc, TG_WAVE - 1);
+    run += __builtin_amdgcn_readlane(inc, TG_WAVE - 1);
+    drun += __builtin_amdgcn_readlane(dinc, TG_WAVE - 1);
   }
 }
 
@@ -1077,8 +1095,26 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
   team_sync();
   if (wave == 0) {
     if (lane < TG_MAX_K) s_k[lane] = k_of(lane);
+    // lane = candidate: its elasticity model and its row of durations as this node sees them
+    // (options above the node's capacity removed, restore delay added) in two dependent round
+    // trips per 64 candidates
     int el = 0;
-    for (int x = lane; x < m; x += TG_WAVE) el |= in.act_model[in.clist[x]] != TG_MODEL_NONE;
+    for (int x = lane; x < m; x += TG_WAVE) {
+      const int id = in.clist[x];
+      el |= in.act_model[id] != TG_MODEL_NONE;
+      const int64_t delay = tg_restore_delay(in, id);
+      int64_t row[TG_MAX_K];
+#pragma unroll
+      for (int q = 0; q < TG_MAX_K; ++q) row[q] = q < K ? in.dur[(size_t)id * K + q] : TG_INF;
+#pragma unroll
+      for (int q = 0; q < TG_MAX_K; ++q)
+        if (q < K) {
+          int64_t d = row[q];
+          if (k_of(q) > in.cap) d = TG_INF;
+          else if (d != TG_INF) d += delay;
+          s_cdur[x * K + q] = d;
+        }
+    }
     const int any_el = __any(el);
     if (lane == 0) s_F[NW] = any_el ? 1 : 0;
   }
@@ -1101,16 +1137,7 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
 
   int stride = 0;                                                 // entries per choice row
   if (wave == 0) {
-    // durations of the node's candidates, options above the node's capacity removed
-    for (int x = lane; x < m * K; x += TG_WAVE) {
-      const int a = x / K, q = x - a * K;
-      const int id = in.clist[a];
-      int64_t d = in.dur[(size_t)id * K + q];
-      if (k_of(q) > in.cap) d = TG_INF;
-      else if (d != TG_INF) d += tg_restore_delay(in, id);        // the durations this node sees
-      s_cdur[x] = d;
-    }
-    tg_wave_sync();
+    tg_wave_sync();                                               // the rows staged above
     // minimum-unit option of every candidate, and the range all times of this node's estimates
     // stay in: above `lo`, below the latest initial release plus every waiting duration
     {
@@ -1136,7 +1163,7 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
         const int64_t b = in.busy_lds_off >= 0 ? reinterpret_cast<const int64_t*>(smem + in.busy_lds_off)[c] : in.busy[c];
         bmin = b < bmin ? b : bmin; bmax = b > bmax ? b : bmax;
       }
-      for (int o = 32; o > 0; o >>= 1) { sumd += __shfl_xor(sumd, o); sumc += __shfl_xor(sumc, o); }
+      sumd = tg_wave_sum_i64(sumd); sumc = tg_wave_sum_i64(sumc);
       sumd += sumc;
       maxd = (int64_t)~tg_wave_min_u64(~(uint64_t)maxd);
       bmax = (int64_t)~tg_wave_min_u64(~(uint64_t)bmax);
@@ -1257,13 +1284,12 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
     for (int base = 0; base < L; base += TG_WAVE) {
       const int x = base + lane;
       const int q = x < L ? tg_sel_get(sel, x) : 0, kq = x < L ? k_of(q) : 0;
-      int inc = kq;                                                // inclusive scan of the unit counts
-      for (int o = 1; o < TG_WAVE; o <<= 1) { const int u = __shfl_up(inc, o); if (lane >= o) inc += u; }
+      const int inc = tg_wave_scan_i32(kq);                        // inclusive scan of the unit counts
       if (x < L) {                                                 // k_i entries at backlog + dur_i(k_i)
         const int64_t fin = in.backlog + s_cdur[x * K + q];
         for (int c = 0; c < kq; ++c) s_heap[pos + inc - kq + c] = fin;
       }
-      pos += __shfl(inc, TG_WAVE - 1);
+      pos += __builtin_amdgcn_readlane(inc, TG_WAVE - 1);
     }
     for (int c = pos + lane; c < U; c += TG_WAVE) s_heap[c] = in.backlog;   // units left idle
     if (in.busy_lds_off >= 0) {
