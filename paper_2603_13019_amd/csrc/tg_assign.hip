@@ -29,7 +29,8 @@ struct AssignWs {
   int32_t* dorder;   // [B*N]   waiting actions pinned to a node (deferred by the prefix rule)
   int32_t *nl_off, *nl_cnt, *dl_off, *dl_cnt;   // [B*M] list extents per node
   int32_t* class_list;   // [kClasses][B*M] nodes with candidates, binned by how many
-  int32_t* class_ctl;    // [2*kClasses] per class: number of nodes, next node to hand out
+  int32_t* class_ctl;    // [2*kClasses + 2] per class: number of nodes, next node to hand out; then, for the light
+                         // class, how many of its nodes were filed at the front and at the back of its list
   int32_t* visit;        // [B*N] TG_ORDER_COST: action ids grouped by kind in visiting order (else unused)
 };
 
@@ -56,7 +57,7 @@ size_t carve(const tg_problem* p, char* base, AssignWs* w) {
   auto take = [&](size_t bytes) { char* r = base + off; off += align256(bytes); return r; };
   char* a = take(nA * p->dev.K * 8); char* b = take(nA * 4); char* c = take(nA * 4); char* d = take(nA * 4);
   char* e = take(nN * 4); char* f = take(nN * 4); char* g = take(nN * 4); char* h = take(nN * 4);
-  char* cl = take(nN * 4 * kClasses); char* cc = take(2 * kClasses * 4);
+  char* cl = take(nN * 4 * kClasses); char* cc = take((2 * kClasses + 2) * 4);
   char* vi = take(p->order_policy == TG_ORDER_COST ? nA * 4 : 0);
   if (w) {
     w->class_list = (int32_t*)cl; w->class_ctl = (int32_t*)cc; w->visit = (int32_t*)vi;
@@ -69,7 +70,7 @@ size_t carve(const tg_problem* p, char* base, AssignWs* w) {
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void tg_dur_kernel(TgDev P, int64_t* __restrict__ dur, int32_t* __restrict__ class_ctl) {
   const size_t x = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (x < 2 * kClasses) class_ctl[x] = 0;
+  if (x < 2 * kClasses + 2) class_ctl[x] = 0;
   const size_t total = (size_t)P.B * P.N * P.K;
   if (x >= total) return;
   const size_t g = x / P.K;
@@ -244,7 +245,7 @@ __global__ __launch_bounds__(256) void tg_lists_kernel(TgDev P, AssignWs W, tg_a
     else cls = m <= kClassCap0 ? 0 : m <= kClassCap1 ? 1 : 2;
   }
   const int lane = threadIdx.x & 63;
-  for (int c = 0; c < kClasses; ++c) {
+  for (int c = 1; c < kClasses; ++c) {
     const uint64_t bal = __ballot(cls == c);
     if (bal == 0) continue;
     const int leader = __ffsll((unsigned long long)bal) - 1;
@@ -253,11 +254,26 @@ __global__ __launch_bounds__(256) void tg_lists_kernel(TgDev P, AssignWs W, tg_a
     base = __shfl(base, leader);
     if (cls == c) W.class_list[(size_t)c * nN + base + __popcll(bal & ((1ull << lane) - 1ull))] = (int32_t)gn;
   }
+  // The light class holds most nodes and is handed out in batches: its dearer nodes (GPU nodes:
+  // chunk states instead of unit counts) are filed from the front of the list, the others from
+  // the back, so that the batches taken last are the cheap ones.
+  for (int side = 0; side < 2; ++side) {
+    const bool mine = cls == 0 && (P.node_type[is_node ? gn : 0] == TG_TYPE_GPU) == (side == 0);
+    const uint64_t bal = __ballot(mine);
+    if (bal == 0) continue;
+    const int leader = __ffsll((unsigned long long)bal) - 1;
+    int base = 0;
+    if (lane == leader) { base = atomicAdd(&W.class_ctl[2 * kClasses + side], __popcll(bal)); atomicAdd(&W.class_ctl[0], __popcll(bal)); }
+    base = __shfl(base, leader);
+    const size_t pos = (size_t)base + __popcll(bal & ((1ull << lane) - 1ull));
+    if (mine) W.class_list[side == 0 ? pos : nN - 1 - pos] = (int32_t)gn;
+  }
 }
 
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(TG_WAVE) void tg_node_kernel(TgDev P, const int64_t* __restrict__ dur, AssignWs W,
-                                                          tg_assign_out O, TgNodeLdsPlan plan, int cls) {
+                                                          tg_assign_out O, TgNodeLdsPlan plan, int cls, int grid0, int grid1,
+                                                          int grid2) {
   extern __shared__ __align__(16) unsigned char smem[];
   const int lane = threadIdx.x;
   const size_t nN = (size_t)P.B * P.M;
@@ -265,14 +281,24 @@ __global__ __launch_bounds__(TG_WAVE) void tg_node_kernel(TgDev P, const int64_t
   int cur = cls;
   int n_nodes = W.class_ctl[2 * cur];
   const int32_t* list = W.class_list + (size_t)cur * nN;
+  const int n_front = W.class_ctl[2 * kClasses];                  // light class: entries filed from the front of its list
+  bool first = true;
   for (;;) {
     // A batch of nodes per fetch (the lighter the class, the more): lane j reads the table
     // entries of the batch's j-th node, so the counter and the node tables cost one memory
-    // round trip per batch instead of several per node.
+    // round trip per batch instead of several per node.  The head of every list belongs to the
+    // wavefronts of the class's own launch, one batch each by their index (thousands of
+    // wavefronts start together: no queue at the counter); everything behind it is handed out
+    // by the counter.
     const int batch = cur == 0 ? 4 : cur == 1 ? 2 : 1;
+    const int head = (cur == 0 ? grid0 : cur == 1 ? grid1 : grid2) * batch;
     int idx0 = 0;
-    if (lane == 0) idx0 = atomicAdd(&W.class_ctl[2 * cur + 1], batch);   // next unprocessed nodes of the class
-    idx0 = __builtin_amdgcn_readfirstlane(idx0);
+    if (first) idx0 = (int)blockIdx.x * batch;
+    else {
+      if (lane == 0) idx0 = head + atomicAdd(&W.class_ctl[2 * cur + 1], batch);   // next unprocessed nodes of the class
+      idx0 = __builtin_amdgcn_readfirstlane(idx0);
+    }
+    first = false;
     if (idx0 >= n_nodes) {
       if (cur == 0) break;
       --cur;
@@ -285,7 +311,8 @@ __global__ __launch_bounds__(TG_WAVE) void tg_node_kernel(TgDev P, const int64_t
     uint32_t my_chunks = 0;
     int64_t my_backlog = 0, my_resident = 0;
     if (lane < nb) {
-      my_gn = list[idx0 + lane];
+      const int at = idx0 + lane;                                 // the light list continues from its far end
+      my_gn = cur == 0 && at >= n_front ? list[nN - 1 - (size_t)(at - n_front)] : list[at];
       my_type = P.node_type[my_gn]; my_cap = P.node_cap[my_gn]; my_free = P.node_free[my_gn];
       my_backlog = P.node_backlog[my_gn]; my_chunks = P.node_chunks[my_gn];
       my_m = W.nl_cnt[my_gn]; my_off = W.nl_off[my_gn]; my_nd = W.dl_cnt[my_gn]; my_doff = W.dl_off[my_gn];
@@ -582,23 +609,43 @@ extern "C" int tg_assign(const tg_problem* p, const int64_t* d_cost, const tg_as
   // classes.  The classes are independent and each is bound by the latency of its own
   // wavefronts, so the two light classes run on side streams next to the heavy one.
   TG_HIP_CHECK(hipEventRecord(p->ev_fork, s));
+  // LDS decides how many wavefronts a CU holds.  The heaviest class that can have nodes gets one
+  // wavefront per possible node as far as 80 % of a CU's LDS go; its wavefronts that find no node
+  // of their own (and those that finish early) serve the class below, so the middle class is only
+  // launched from what the light class - the bulk of the nodes - leaves over.
   const size_t bound[kClasses] = {nN, p->nodes_free_gt16, p->nodes_free_gt64};
-  const int kCus = 256, kLdsPerCu = 160 * 1024;
-  const int share[kClasses] = {kLdsPerCu, kLdsPerCu / 10, kLdsPerCu * 8 / 10};   // LDS a class may claim on a CU
+  const int kCus = 256, kLdsPerCu = 160 * 1024, kLdsGranule = 1024;   // allocations are rounded up (granule assumed, not documented)
+  const int heavy = bound[2] > 0 ? 2 : bound[1] > 0 ? 1 : 0;      // classes above it are empty
+  int per_cu[kClasses] = {0, 0, 0}, bytes[kClasses], want[kClasses];
+  for (int c = 0; c < kClasses; ++c) {
+    bytes[c] = (plans[c].total + busy_lds + kLdsGranule - 1) / kLdsGranule * kLdsGranule;
+    want[c] = (int)std::min<size_t>((bound[c] + kCus - 1) / kCus, 32);
+  }
   int lds_left = kLdsPerCu;
+  if (heavy > 0) {
+    per_cu[heavy] = std::max(1, std::min(want[heavy], kLdsPerCu * 8 / 10 / bytes[heavy]));
+    lds_left -= per_cu[heavy] * bytes[heavy];
+  }
+  // a thin heavy launch cannot absorb a long middle list: then the middle class keeps wavefronts of its own
+  const int own1 = heavy == 2 && per_cu[2] < 3 && bound[1] > (size_t)kCus * per_cu[2] ? std::min(want[1], 4) : 0;
+  per_cu[0] = std::max(1, std::min(want[0], (lds_left - own1 * bytes[1]) / bytes[0]));
+  lds_left = std::max(0, lds_left - per_cu[0] * bytes[0]);
+  if (heavy == 2) per_cu[1] = std::min(std::max(own1, std::min(want[1], 1)), lds_left / bytes[1]);
+  bool forked[2] = {false, false};
+  int grids[kClasses];
+  for (int c = 0; c < kClasses; ++c)
+    grids[c] = per_cu[c] == 0 ? 0 : (int)std::max<size_t>(1, std::min<size_t>(bound[c], (size_t)kCus * per_cu[c]));
   for (int c = kClasses - 1; c >= 0; --c) {                     // heaviest class first
-    const int bytes = plans[c].total + busy_lds;
-    const int want = (int)std::min<size_t>((bound[c] + kCus - 1) / kCus, 32);
-    const int per_cu = std::max(1, std::min(want, std::min(share[c], lds_left) / bytes));
-    lds_left = std::max(0, lds_left - per_cu * bytes);
-    const unsigned grid = (unsigned)std::max<size_t>(1, std::min<size_t>(bound[c], (size_t)kCus * per_cu));
+    if (per_cu[c] == 0) continue;
+    const unsigned grid = (unsigned)grids[c];
     hipStream_t cs = c < 2 ? p->side_stream[c] : s;
-    if (c < 2) TG_HIP_CHECK(hipStreamWaitEvent(cs, p->ev_fork, 0));
+    if (c < 2) { TG_HIP_CHECK(hipStreamWaitEvent(cs, p->ev_fork, 0)); forked[c] = true; }
     static_assert(kClassWaves[0] == 1 && kClassWaves[1] == 1 && kClassWaves[2] == 1, "only single-wavefront teams are enabled");
-    hipLaunchKernelGGL(tg_node_kernel, dim3(grid), dim3(TG_WAVE), plans[c].total + busy_lds, cs, P, W.dur, W, *out, plans[c], c);
+    hipLaunchKernelGGL(tg_node_kernel, dim3(grid), dim3(TG_WAVE), plans[c].total + busy_lds, cs, P, W.dur, W, *out, plans[c], c,
+                       grids[0], grids[1], grids[2]);
     if (c < 2) TG_HIP_CHECK(hipEventRecord(p->ev_join[c], cs));
   }
-  for (int c = 0; c < 2; ++c) TG_HIP_CHECK(hipStreamWaitEvent(s, p->ev_join[c], 0));
+  for (int c = 0; c < 2; ++c) if (forked[c]) TG_HIP_CHECK(hipStreamWaitEvent(s, p->ev_join[c], 0));
   if (P.node_chunks_real) hipLaunchKernelGGL(tg_pool_map_kernel, dim3(P.B), dim3(TG_WAVE), 0, s, P, W, *out);
   if (out->core_set) {
     hipLaunchKernelGGL(tg_cores_clear_kernel, dim3((unsigned)((nA * 4 + 255) / 256)), dim3(256), 0, s,
