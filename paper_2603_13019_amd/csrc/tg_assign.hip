@@ -257,16 +257,20 @@ __global__ __launch_bounds__(256) void tg_lists_kernel(TgDev P, AssignWs W, tg_a
   // The light class holds most nodes and is handed out in batches: its dearer nodes (GPU nodes:
   // chunk states instead of unit counts) are filed from the front of the list, the others from
   // the back, so that the batches taken last are the cheap ones.
-  for (int side = 0; side < 2; ++side) {
-    const bool mine = cls == 0 && (P.node_type[is_node ? gn : 0] == TG_TYPE_GPU) == (side == 0);
-    const uint64_t bal = __ballot(mine);
-    if (bal == 0) continue;
-    const int leader = __ffsll((unsigned long long)bal) - 1;
-    int base = 0;
-    if (lane == leader) { base = atomicAdd(&W.class_ctl[2 * kClasses + side], __popcll(bal)); atomicAdd(&W.class_ctl[0], __popcll(bal)); }
-    base = __shfl(base, leader);
-    const size_t pos = (size_t)base + __popcll(bal & ((1ull << lane) - 1ull));
-    if (mine) W.class_list[side == 0 ? pos : nN - 1 - pos] = (int32_t)gn;
+  {
+    const bool dear = cls == 0 && P.node_type[is_node ? gn : 0] == TG_TYPE_GPU;
+    const uint64_t bal_f = __ballot(dear), bal_b = __ballot(cls == 0 && !dear);
+    if ((bal_f | bal_b) != 0) {
+      int base_f = 0, base_b = 0;
+      if (lane == 0) {                                            // both counters in flight together
+        if (bal_f) base_f = atomicAdd(&W.class_ctl[2 * kClasses], __popcll(bal_f));
+        if (bal_b) base_b = atomicAdd(&W.class_ctl[2 * kClasses + 1], __popcll(bal_b));
+      }
+      base_f = __builtin_amdgcn_readfirstlane(base_f); base_b = __builtin_amdgcn_readfirstlane(base_b);
+      const uint64_t below = (1ull << lane) - 1ull;
+      if (dear) W.class_list[(size_t)base_f + __popcll(bal_f & below)] = (int32_t)gn;
+      else if (cls == 0) W.class_list[nN - 1 - ((size_t)base_b + __popcll(bal_b & below))] = (int32_t)gn;
+    }
   }
 }
 
@@ -279,9 +283,10 @@ __global__ __launch_bounds__(TG_WAVE) void tg_node_kernel(TgDev P, const int64_t
   const size_t nN = (size_t)P.B * P.M;
   // own class first, then the lighter ones (their nodes fit into this launch's LDS block too)
   int cur = cls;
-  int n_nodes = W.class_ctl[2 * cur];
+  const int n_front = W.class_ctl[2 * kClasses];                  // light class: entries filed from the front of its list,
+  const int n_light = n_front + W.class_ctl[2 * kClasses + 1];    // and all of them
+  int n_nodes = cur == 0 ? n_light : W.class_ctl[2 * cur];
   const int32_t* list = W.class_list + (size_t)cur * nN;
-  const int n_front = W.class_ctl[2 * kClasses];                  // light class: entries filed from the front of its list
   bool first = true;
   for (;;) {
     // A batch of nodes per fetch (the lighter the class, the more): lane j reads the table
@@ -302,7 +307,7 @@ __global__ __launch_bounds__(TG_WAVE) void tg_node_kernel(TgDev P, const int64_t
     if (idx0 >= n_nodes) {
       if (cur == 0) break;
       --cur;
-      n_nodes = W.class_ctl[2 * cur];
+      n_nodes = cur == 0 ? n_light : W.class_ctl[2 * cur];
       list = W.class_list + (size_t)cur * nN;
       continue;
     }
