@@ -14,8 +14,8 @@
 // The admission loop is sequential by definition (every action sees the capacity left by the
 // ones before it), so tg_place_kernel keeps the node table of its pool in registers (LDS for
 // very wide pools) and spends its 64 lanes on the argmin over nodes; parallelism comes from the
-// batch of snapshots.  The per-node stage runs as three concurrent launches, one per class of
-// candidate count, whose persistent wavefronts pull nodes from class lists.
+// batch of snapshots.  The per-node stage runs as up to three concurrent launches, one per class
+// of candidate count, whose persistent wavefronts pull nodes from class lists.
 #include <algorithm>
 
 #include "tg_step.h"
@@ -35,11 +35,11 @@ struct AssignWs {
 };
 
 // Nodes are processed in classes of candidate count so that the LDS a wavefront needs (the
-// choice table grows with m) does not cap the occupancy of the many small nodes.  The three
+// choice table grows with m) does not cap the occupancy of the many small nodes.  The
 // launches run side by side; a node holds at most as many candidates as it has free units, so
 // the number of nodes with more than 16 / 64 free units (known when the problem is built)
-// bounds the two heavy classes: they get a wavefront per such node as far as the LDS of the
-// chip goes, the light class fills what is left.
+// bounds the heavier classes; how the LDS of a CU is split between the launches is decided in
+// tg_assign below.
 constexpr int kClasses = 3;
 constexpr int kSelRows = 32;     // prefix lengths backtracked per batch
 // One wavefront per node.  Teams of several wavefronts (tg_node_schedule<NW>, NW > 1) are
