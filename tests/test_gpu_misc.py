@@ -42,6 +42,38 @@ def test_assign_is_deterministic_and_reentrant(tg):
     P.free()
 
 
+def test_score_and_assign_side_by_side(tg):
+    """tg_score_candidates on a second stream while tg_assign runs on the first (the launch pattern of
+    bench.py): both results equal those of the calls made one after the other."""
+    import torch
+    p = gen.make_config(2, B=48)
+    P = tg.Problem(p)
+    cost_ref = P.score()
+    bufs_ref = P.alloc_assign()
+    P.assign(None, bufs_ref)
+    torch.cuda.synchronize()
+    keys = ("node", "units", "act_us", "defer_reason", "summary", "node_used", "node_obj", "task_sum_us")
+    want = {k: bufs_ref[k].cpu().numpy().copy() for k in keys}
+    main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+    cost, bufs = P.alloc_cost(), P.alloc_assign()
+    for rep in range(5):
+        cost.fill_(-7)
+        fork = torch.cuda.Event()
+        fork.record(main)
+        side.wait_event(fork)
+        with torch.cuda.stream(side):
+            P.score(cost)
+            done = torch.cuda.Event()
+            done.record(side)
+        P.assign(None, bufs)
+        main.wait_event(done)
+        torch.cuda.synchronize()
+        assert torch.equal(cost, cost_ref), f"run {rep}: score tensor"
+        for k in keys:
+            np.testing.assert_array_equal(bufs[k].cpu().numpy(), want[k], err_msg=f"run {rep} {k}")
+    P.free()
+
+
 def test_replay_is_deterministic(tg):
     import torch
     t = gen.make_trace(S=16, A=1500, seed=33, contended=True, rate_per_s=150.0, horizon_s=10.0, max_ticks=50000)
