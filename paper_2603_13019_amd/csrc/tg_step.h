@@ -283,6 +283,46 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
       const uint32_t w = (uint32_t)__builtin_amdgcn_readlane((int)my_w, l);
       const uint32_t mask = w & 0xffu;
       const int kmin = (int)(w >> 9 & 0x7fu), pr = (int)(w >> 16) - 1;
+      if (!AUX && narrow && !pool_closed && (w & 0xffff0100u) == 0) {
+        // the common case in straight-line code: feasible, free to choose its node, 32-bit estimates
+        uint32_t b32 = 0xffffffffu, brank = 0xffffffffu;
+#pragma unroll
+        for (int s = 0; s < R; ++s) {                 // ascending rank, strict <: the smaller rank wins ties
+          const uint32_t ok = mask & fitv[s];         // allowed options that still fit
+          const int qs = 31 - __builtin_clz(ok | 1u); // the largest of them
+          const uint32_t d = dur32[2 * (l * io.K + qs)];   // read by every lane (option 0 where nothing fits): no branch
+          const uint32_t e32 = ok ? back32[s] + d : 0xffffffffu;
+          if (R > 1) { if (e32 < b32) { b32 = e32; brank = (uint32_t)(lane + TG_WAVE * s); } }
+          else b32 = e32;
+        }
+        const uint32_t emin = tg_wave_min_u32(b32);
+        int rank;
+        if (R == 1) {
+          const uint64_t who = __ballot(b32 == emin);
+          rank = emin == 0xffffffffu ? -1 : __ffsll((unsigned long long)who) - 1;
+        } else rank = (int)tg_wave_min_u32(b32 == emin ? brank : 0xffffffffu);     // -1: nobody fits
+        uint32_t res = pack_res(-1, 0, TG_DEFER_PREFIX);
+        if (rank < 0) pool_closed = true;
+        else {
+          const int rl = rank & 63;
+          int slot = 0;
+#pragma unroll
+          for (int s = 0; s < R; ++s) {
+            if ((rank >> 6) != s) continue;
+            slot = __builtin_amdgcn_readlane(cntv[s], rl);
+            const int32_t lim_old = __builtin_amdgcn_readlane(limv[s], rl);
+            const int32_t lim_new = GPU ? (int32_t)tg_chunk_take((uint32_t)lim_old, kmin) : lim_old - kmin;
+            const uint32_t fit_new = fit_of_uniform(lim_new);
+            const bool me = lane == rl;
+            cntv[s] = me ? slot + 1 : cntv[s];
+            limv[s] = me ? lim_new : limv[s];
+            fitv[s] = me ? fit_new : fitv[s];
+          }
+          res = pack_res(rank, slot, TG_SELECTED);
+        }
+        my_res = lane == l ? res : my_res;
+        continue;
+      }
       const int aux = has_aux && pr < 0 ? __builtin_amdgcn_readlane(my_aux, l) : 0;   // pinned: already charged
       const int svc = has_svc ? __builtin_amdgcn_readlane(my_svc, l) : -1;
       const int64_t rest = has_svc && svc >= 0 ? tg_readlane_i64(rest_tab, svc) : 0;
@@ -370,12 +410,11 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
           const int32_t lim_old = __builtin_amdgcn_readlane(limv[s], rl);      // the node's new state on scalars
           const int32_t lim_new = GPU ? (int32_t)tg_chunk_take((uint32_t)lim_old, kmin) : lim_old - kmin;
           const uint32_t fit_new = fit_of_uniform(lim_new);
-          if (lane == rl) {
-            ++cntv[s];
-            if (AUX) auxv[s] -= aux;
-            limv[s] = lim_new;
-            fitv[s] = fit_new;
-          }
+          const bool me = lane == rl;                            // selects, no branch: one lane changes
+          cntv[s] = me ? slot + 1 : cntv[s];
+          if (AUX) auxv[s] = me ? auxv[s] - aux : auxv[s];
+          limv[s] = me ? lim_new : limv[s];
+          fitv[s] = me ? fit_new : fitv[s];
         }
         if (AUX && more != 0 && (more >> lane & 1ull)) {           // one token of every further quota
           limv[0] -= 1;
