@@ -497,3 +497,14 @@ def test_assign_pooled_gpus_config2_full(tg, orc):
     gpu = p["node_type"] == gen.TYPE_GPU
     assert (want["node_used"][gpu] > 0).mean() > 0.9
     _compare(_assign_gpu(tg, p), want)
+
+
+def test_assign_several_quotas_config3_slice(tg, orc):
+    """48 snapshots of workload 3 (4096 actions, 16 quotas each) in which half of the API actions draw on up to three
+    further quotas."""
+    p = gen.slice_problem(gen.make_config(3), range(0, 1024, 22))
+    gen.with_extra_quotas(p, frac=0.5, seed=3)
+    want = orc.assign(p)
+    base = orc.assign(dict(p, act_quota_mask=None))
+    assert (want["reason"] != base["reason"]).any()
+    _compare(_assign_gpu(tg, p), want)
