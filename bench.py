@@ -309,6 +309,15 @@ def main():
     }
 
     if a.only == "step":
+        # the same step through the library's one-call entry point (its own second stream), for comparison
+        for _ in range(3):
+            P.step(cost, bufs)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(a.steps):
+            P.step(cost, bufs)
+        torch.cuda.synchronize()
+        out["tg_step_ms_per_step"] = (time.perf_counter() - t0) * 1e3 / a.steps
         out["order_policy_cost"] = order_section(a, tg, torch, p, s)
         out["core_sets"] = core_sets_section(a, tg, gen, torch, p)
         out["gpu_pooled"] = pooled_section(a, tg, gen, torch, p)

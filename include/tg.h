@@ -21,8 +21,8 @@
  *     their host-to-device copies have completed).  Results are valid once the caller has
  *     synchronised the stream.
  *   - A tg_problem / tg_trace is immutable after it is built and owns only its packed device
- *     copy of the inputs (plus, for a tg_problem, two internal streams and their events on
- *     which tg_assign runs part of its work, forked from and joined back into `hip_stream`).
+ *     copy of the inputs (plus, for a tg_problem, three internal streams and their events on
+ *     which tg_assign and tg_step run part of their work, forked from and joined back into `hip_stream`).
  *     No other entry point allocates device memory.  Launches that use the same tg_problem may
  *     be in flight together (each with its own outputs and workspace), but the host calls that
  *     enqueue them must not overlap: one thread at a time per tg_problem.
@@ -222,6 +222,15 @@ int tg_score_candidates(const tg_problem *p, int64_t *d_cost, void *hip_stream);
  */
 int tg_assign(const tg_problem *p, const int64_t *d_cost, const tg_assign_out *out, void *d_ws, size_t ws_bytes,
               void *hip_stream);
+
+/*
+ * One whole step in one call: tg_score_candidates and tg_assign for the same problem, the score
+ * tensor written on a stream of the problem's own next to the assignment (which recomputes its
+ * estimates and does not read the tensor), forked from and joined back into `hip_stream`.  Same
+ * arguments, results and errors as the two calls (d_cost must not be NULL unless the problem has
+ * no candidate); everything is complete once `hip_stream` has been synchronised.
+ */
+int tg_step(const tg_problem *p, int64_t *d_cost, const tg_assign_out *out, void *d_ws, size_t ws_bytes, void *hip_stream);
 
 /*
  * S independent arrival traces replayed against their own clusters.  Every tick_us of simulated

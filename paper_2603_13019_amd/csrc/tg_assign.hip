@@ -555,12 +555,37 @@ extern "C" int tg_assign_workspace_bytes(const tg_problem* p, size_t* bytes) {
   return TG_OK;
 }
 
-extern "C" int tg_assign(const tg_problem* p, const int64_t* d_cost, const tg_assign_out* out, void* d_ws,
-                         size_t ws_bytes, void* hip_stream) {
+namespace {
+int check_assign_args(const tg_problem* p, const tg_assign_out* out, const void* d_ws, size_t ws_bytes) {
   if (!p || !out || !out->node || !out->units || !out->act_us || !out->defer_reason || !out->summary)
     return TG_E_INVALID_ARG;
   if (out->core_set && !p->dev.node_cores) return TG_E_INVALID_ARG;
   if (!d_ws || ((uintptr_t)d_ws & 255) || ws_bytes < carve(p, nullptr, nullptr)) return TG_E_WORKSPACE;
+  return TG_OK;
+}
+}  // namespace
+
+extern "C" int tg_step(const tg_problem* p, int64_t* d_cost, const tg_assign_out* out, void* d_ws, size_t ws_bytes,
+                       void* hip_stream) {
+  const int rc = check_assign_args(p, out, d_ws, ws_bytes);
+  if (rc) return rc;
+  if ((!d_cost && p->n_candidates) || ((uintptr_t)d_cost & 15)) return TG_E_INVALID_ARG;
+  hipStream_t s = (hipStream_t)hip_stream;
+  // the assignment does not read the tensor: the HBM-bound score kernel runs on a stream of its own
+  // next to the latency-bound assignment, forked from and joined back into the caller's stream
+  TG_HIP_CHECK(hipEventRecord(p->ev_score_fork, s));
+  TG_HIP_CHECK(hipStreamWaitEvent(p->score_stream, p->ev_score_fork, 0));
+  const int rs = tg_launch_score(p, d_cost, p->score_stream);
+  TG_HIP_CHECK(hipEventRecord(p->ev_score_done, p->score_stream));
+  const int ra = tg_assign(p, nullptr, out, d_ws, ws_bytes, hip_stream);
+  TG_HIP_CHECK(hipStreamWaitEvent(s, p->ev_score_done, 0));
+  return rs ? rs : ra;
+}
+
+extern "C" int tg_assign(const tg_problem* p, const int64_t* d_cost, const tg_assign_out* out, void* d_ws,
+                         size_t ws_bytes, void* hip_stream) {
+  const int rc_args = check_assign_args(p, out, d_ws, ws_bytes);
+  if (rc_args) return rc_args;
   hipStream_t s = (hipStream_t)hip_stream;
   const TgDev& P = p->dev;
   AssignWs W;

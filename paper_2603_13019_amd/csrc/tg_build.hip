@@ -422,6 +422,9 @@ extern "C" int tg_build_problem(const tg_problem_desc* desc, void* hip_stream, t
     for (int i = 0; i < 2 && ok; ++i)
       ok = hipStreamCreateWithFlags(&p->side_stream[i], hipStreamNonBlocking) == hipSuccess &&
            hipEventCreateWithFlags(&p->ev_join[i], hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipStreamCreateWithFlags(&p->score_stream, hipStreamNonBlocking) == hipSuccess &&
+         hipEventCreateWithFlags(&p->ev_score_fork, hipEventDisableTiming) == hipSuccess &&
+         hipEventCreateWithFlags(&p->ev_score_done, hipEventDisableTiming) == hipSuccess;
     if (!ok) { tg_free_problem(p); return TG_E_HIP; }
     char* base = (char*)p->d_arena;
     TgDev& v = p->dev;
@@ -484,6 +487,9 @@ extern "C" void tg_free_problem(tg_problem* p) {
     if (p->ev_join[i]) (void)hipEventDestroy(p->ev_join[i]);
   }
   if (p->ev_fork) (void)hipEventDestroy(p->ev_fork);
+  if (p->score_stream) (void)hipStreamDestroy(p->score_stream);
+  if (p->ev_score_fork) (void)hipEventDestroy(p->ev_score_fork);
+  if (p->ev_score_done) (void)hipEventDestroy(p->ev_score_done);
   delete p;
 }
 

@@ -92,6 +92,9 @@ struct tg_problem {
   // from and joined back into the caller's stream with events
   hipStream_t side_stream[2];
   hipEvent_t ev_fork, ev_join[2];
+  // tg_step writes the score tensor on a third stream next to the assignment
+  hipStream_t score_stream;
+  hipEvent_t ev_score_fork, ev_score_done;
   int order_policy;        // TG_ORDER_*
   int max_actions_of_kind; // largest N_t over all snapshots and kinds
   int max_nodes_of_kind;   // largest M_t over all snapshots and kinds

@@ -214,6 +214,7 @@ def test_cost_order_needs_pools_it_can_sort(tg):
 
 def test_null_arguments(tg):
     L = tg.load()
+    assert L.tg_step(None, None, None, None, 0, None) == -1
     assert L.tg_build_problem(None, None, None) == -1
     assert L.tg_num_candidates(None, None, None) == -1
     assert L.tg_assign_workspace_bytes(None, None) == -1

@@ -74,6 +74,30 @@ def test_score_and_assign_side_by_side(tg):
     P.free()
 
 
+def test_step_in_one_call(tg):
+    """tg_step == tg_score_candidates + tg_assign, also back to back without host synchronisation."""
+    import torch
+    p = gen.make_config(2, B=40)
+    P = tg.Problem(p)
+    cost_ref = P.score()
+    bufs_ref = P.alloc_assign()
+    P.assign(None, bufs_ref)
+    torch.cuda.synchronize()
+    keys = ("node", "units", "act_us", "defer_reason", "summary", "node_used", "node_obj", "task_sum_us")
+    cost, bufs = P.alloc_cost(), P.alloc_assign()
+    for rep in range(3):
+        cost.fill_(-7)
+        for k in keys:
+            bufs[k].fill_(0)
+        P.step(cost, bufs)
+        P.step(cost, bufs)
+        torch.cuda.synchronize()
+        assert torch.equal(cost, cost_ref), f"run {rep}: score tensor"
+        for k in keys:
+            np.testing.assert_array_equal(bufs[k].cpu().numpy(), bufs_ref[k].cpu().numpy(), err_msg=f"run {rep} {k}")
+    P.free()
+
+
 def test_replay_is_deterministic(tg):
     import torch
     t = gen.make_trace(S=16, A=1500, seed=33, contended=True, rate_per_s=150.0, horizon_s=10.0, max_ticks=50000)
@@ -101,8 +125,9 @@ def test_build_problem_time_is_reported(tg):
     P.free()
 
 
-def test_step_can_be_captured_into_a_graph(tg):
-    """tg_score_candidates + tg_assign (three streams forked and joined with events, no memsets) recorded
+@pytest.mark.parametrize("one_call", [False, True])
+def test_step_can_be_captured_into_a_graph(tg, one_call):
+    """tg_score_candidates + tg_assign, or tg_step (streams forked and joined with events, no memsets) recorded
     into a HIP graph: every replay, with eager launches and synchronisations in between, reproduces the
     eager result."""
     import torch
@@ -111,8 +136,11 @@ def test_step_can_be_captured_into_a_graph(tg):
     cost, bufs = P.alloc_cost(), P.alloc_assign()
 
     def step():
-        P.score(cost)
-        P.assign(cost, bufs)
+        if one_call:
+            P.step(cost, bufs)
+        else:
+            P.score(cost)
+            P.assign(cost, bufs)
 
     step()
     torch.cuda.synchronize()
