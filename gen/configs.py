@@ -423,12 +423,12 @@ def with_core_maps(p, numa_cores, seed=0):
 
 
 def with_extra_quotas(p, frac=0.5, seed=0, max_extra=3):
-    """Adds ``act_quota_mask`` to a problem (in place): a fraction of the API actions that are pinned to a quota
+    """Adds ``act_quota_mask`` to a problem or a trace (in place): a fraction of the API actions that are pinned to a quota
     also name up to ``max_extra`` other quotas of their snapshot (by rank among its API nodes, first 64 only)."""
     rng = np.random.default_rng(seed + 515)
-    N, M = p["N"], p["M"]
-    mask = np.zeros(p["B"] * N, np.uint64)
-    for b in range(p["B"]):
+    B, N, M = (p["B"], p["N"], p["M"]) if "B" in p else (p["S"], p["A"], p["M"])     # a problem or a trace
+    mask = np.zeros(B * N, np.uint64)
+    for b in range(B):
         api = np.flatnonzero(p["node_type"][b * M:(b + 1) * M] == TYPE_API)[:64]
         if len(api) < 2:
             continue

@@ -267,6 +267,10 @@ typedef struct {
   const int64_t *restore_us;        /* [n_services] in [0, 2^36)                                 */
   int32_t n_services;               /* 1..TG_MAX_SERVICES                                        */
   int32_t cache_slots;              /* 1..TG_MAX_SERVICES                                        */
+  /* Several quotas per action as in tg_problem_desc.act_quota_mask (ranks among the API nodes of
+   * the scenario): the action starts only in a tick in which every named quota holds a whole
+   * token, and takes one from each.  NULL: none. */
+  const uint64_t *act_quota_mask;   /* [S*A] */
 } tg_trace_desc;
 
 /* Device outputs of tg_replay_trace. */

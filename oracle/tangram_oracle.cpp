@@ -519,6 +519,7 @@ struct orc_trace {
   const int64_t* arrival_us; const uint8_t* act_type; const uint8_t* act_model; const int64_t* act_t_ori_us;
   const uint32_t* act_kmask; const uint32_t* act_param; const int32_t* act_pin_node;
   const int32_t* act_service; const int64_t* restore_us;           // both or neither (Sec. 5.3)
+  const uint64_t* act_quota_mask;                                  // [S*A] further quotas of an API action (Sec. 4.1), or NULL
 };
 
 }  // extern "C"
@@ -772,7 +773,8 @@ void orc_replay(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us, int64
       for (int i : waiting)
         acts.push_back(Act{t->act_type[a0 + i], t->act_model[a0 + i], t->act_t_ori_us[a0 + i], now - t->arrival_us[a0 + i],
                            t->act_kmask[a0 + i], t->act_param[a0 + i], t->act_pin_node[a0 + i], 0, 0,
-                           t->act_service ? t->act_service[a0 + i] : -1});
+                           t->act_service ? t->act_service[a0 + i] : -1,
+                           t->act_quota_mask ? t->act_quota_mask[a0 + i] : 0});
       std::vector<Node> nodes(M);
       for (int j = 0; j < M; ++j) {
         Node& nd = nodes[j];
@@ -808,7 +810,12 @@ void orc_replay(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us, int64
           used_at[(size_t)j * 64 + sv] = ++seq[j];
         }
         Run u{now + dur, j, k, 0};
-        if (nodes[j].type == T_API) tok[j] -= (int64_t)k * 1000000;
+        if (nodes[j].type == T_API) {
+          tok[j] -= (int64_t)k * 1000000;
+          int r = 0;                                         // one token of every further quota it names (Sec. 4.1)
+          for (int x = 0; x < M; ++x)
+            if (t->node_type[n0 + x] == T_API) { if (r < 64 && (acts[w].extra >> r & 1ull)) tok[x] -= 1000000; ++r; }
+        }
         else {
           if (nodes[j].type == T_GPU) u.gstart = mask_alloc(gmask[j], k);
           rem[j] -= k;

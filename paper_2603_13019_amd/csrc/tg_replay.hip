@@ -31,6 +31,7 @@ struct TgTraceDev {
   const uint32_t* speedup;
   const int32_t* act_service;     // [S*A] service of a GPU action or -1; nullptr: the trace has no services (Sec. 5.3)
   const int64_t* restore;         // [TG_MAX_SERVICES]
+  const uint64_t* act_quota;      // [S*A] further quotas of an API action (ranks among the scenario's API nodes), or nullptr (Sec. 4.1)
 };
 
 struct tg_trace {
@@ -312,7 +313,8 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
       tg_wave_sync();
       TgPlaceIo io;
       io.act_kmask = T.act_kmask + abase; io.act_static = T.act_static + abase; io.act_pin = T.act_pin + abase;
-      io.act_aux = nullptr; io.act_quota = nullptr;               // traces carry no second resource and one quota per action
+      io.act_aux = nullptr;                                       // traces carry no second resource
+      io.act_quota = T.act_quota && ty == TG_TYPE_API ? T.act_quota + abase : nullptr;
       io.act_service = T.act_service ? T.act_service + abase : nullptr; io.restore = T.restore;
       io.act_pin_rank = nullptr;
       io.node_rank = T.node_rank + nbase; io.nodes = nodes; io.dur = dur; io.cost = nullptr; io.cost_row_len = 0;
@@ -397,7 +399,14 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
         const int64_t fin = now + delay + dur[(size_t)id * K + q];
         o_start[id] = now; o_fin[id] = fin;
         atomicAdd(&s_started, 1);
-        if (ty == TG_TYPE_API) { atomicAdd((unsigned long long*)&live_tok[j], (unsigned long long)(-(int64_t)k * 1000000)); }
+        if (ty == TG_TYPE_API) {
+          atomicAdd((unsigned long long*)&live_tok[j], (unsigned long long)(-(int64_t)k * 1000000));
+          if (T.act_quota) {                                      // one token of every further quota the action names
+            const int32_t* api = T.tnode_idx + nbase + T.tnode_off[s * 4 + TG_TYPE_API];
+            for (uint64_t more = T.act_quota[abase + id]; more; more &= more - 1)
+              atomicAdd((unsigned long long*)&live_tok[api[__builtin_ctzll(more)]], (unsigned long long)(-1000000ll));
+          }
+        }
         else if (ty == TG_TYPE_CPU) {
           atomicSub(&live_free[j], k);
           const int d = atomicAdd(&s_nrun, 1);
@@ -546,6 +555,7 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
     const size_t o_arr = add(nA * 8), o_atype = add(nA), o_amodel = add(nA), o_astat = add(nA), o_aT = add(nA * 8),
                  o_amask = add(nA * 4), o_aparam = add(nA * 4), o_apin = add(nA * 4);
     const size_t o_asvc = add(svc ? nA * 4 : 0), o_rest = add(svc ? TG_MAX_SERVICES * 8 : 0);
+    const size_t o_aquota = add(d->act_quota_mask ? nA * 8 : 0);
     const size_t o_speed = add(std::max<size_t>((size_t)d->n_classes * K, 1) * 4);
     auto at = [&](size_t off) { return host.data() + off; };
     int max_kind = 0, max_cap_cpu = 0, max_heap = 0;
@@ -603,6 +613,15 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
           if (pin >= 0) infeasible = pin >= M || d->node_type[(size_t)s * M + pin] != ty || kmin > d->node_cap[(size_t)s * M + pin];
           else infeasible = kmin > max_cap[(size_t)s * 3 + ty];
         }
+        if (d->act_quota_mask) {                             // further quotas: a pinned API action names other API nodes
+          const uint64_t more = d->act_quota_mask[g];
+          if (more) {
+            const bool pinned_api = ty == TG_TYPE_API && pin >= 0 && pin < M && d->node_type[(size_t)s * M + pin] == TG_TYPE_API;
+            if (!pinned_api || (cnt[TG_TYPE_API] < 64 && (more >> cnt[TG_TYPE_API])) ||
+                (more >> ((int32_t*)at(o_rank))[(size_t)s * M + pin] & 1ull)) { delete t; return TG_E_INVALID_ARG; }
+          }
+          ((uint64_t*)at(o_aquota))[g] = more;
+        }
         if (pin >= M) pin = M;
         if (svc) {
           const int sv = d->act_service[g] < 0 ? -1 : d->act_service[g];
@@ -648,6 +667,7 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
     v.act_service = svc ? (const int32_t*)(base + o_asvc) : nullptr;
     v.restore = svc ? (const int64_t*)(base + o_rest) : nullptr;
     v.cache_slots = svc ? d->cache_slots : 0;
+    v.act_quota = d->act_quota_mask ? (const uint64_t*)(base + o_aquota) : nullptr;
     v.speedup = (const uint32_t*)(base + o_speed);
     t->max_nodes_of_kind = max_kind; t->max_cap_cpu = max_cap_cpu; t->max_heap = max_heap;
     for (int k = 0; k < 3; ++k) t->max_nodes_kind[k] = max_of_kind[k];

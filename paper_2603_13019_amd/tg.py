@@ -45,7 +45,8 @@ class TraceDesc(C.Structure):
         ("flags", C.c_uint32), ("tick_us", C.c_int64)] + [(n, C.c_void_p) for n in (
             "k_list", "type_k", "speedup_q16", "node_type", "node_cap", "quota_rate", "quota_tok0_micro",
             "arrival_us", "act_type", "act_model", "act_t_ori_us", "act_kmask", "act_param", "act_pin_node",
-            "act_service", "restore_us")] + [("n_services", C.c_int32), ("cache_slots", C.c_int32)]
+            "act_service", "restore_us")] + [("n_services", C.c_int32), ("cache_slots", C.c_int32),
+                                             ("act_quota_mask", C.c_void_p)]
 
 
 class ReplayOut(C.Structure):
@@ -230,7 +231,7 @@ class Trace:
         d.flags = 0
         d.tick_us = int(t["tick_us"])
         keep = []
-        _fill(d, t, [f[0] for f in TraceDesc._fields_[9:-2]], keep)
+        _fill(d, t, [f[0] for f in TraceDesc._fields_[9:-3]] + ["act_quota_mask"], keep)
         d.n_services = len(t["restore_us"]) if t.get("restore_us") is not None else 0
         d.cache_slots = int(t.get("cache_slots", 64))
         h = C.c_void_p()

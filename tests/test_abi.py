@@ -39,7 +39,7 @@ def test_strerror(tg):
 def test_struct_layouts_match_header(tg):
     assert C.sizeof(tg.ProblemDesc) == 8 * 4 + 25 * 8 + 4 * 4
     assert C.sizeof(tg.AssignOut) == 9 * 8
-    assert C.sizeof(tg.TraceDesc) == 8 * 4 + 8 + 16 * 8 + 2 * 4
+    assert C.sizeof(tg.TraceDesc) == 8 * 4 + 8 + 16 * 8 + 2 * 4 + 8
     assert C.sizeof(tg.ReplayOut) == 8 * 8
     assert tg.SUMMARY_DTYPE.itemsize == 8 + 16 + 24 + 24 + 8 + 24
 
@@ -121,6 +121,21 @@ def test_trace_services_are_validated(tg):
     cpu_calls[np.flatnonzero(~gpu)[0]] = 1
     assert _trace_rc(tg, dict(t, **dict(ok, act_service=cpu_calls))) == -1   # only GPU actions call services
     assert _trace_rc(tg, dict(t, **dict(ok, restore_us=np.array([5, 1 << 36], np.int64)))) == -2
+
+
+def test_trace_quota_masks_are_validated(tg):
+    t = gen.make_trace(S=1, A=60, seed=8, cluster=(1, 8, 1, 3), type_probs=(0.3, 0.2, 0.5), max_ticks=100)
+    gen.with_extra_quotas(t, frac=1.0, seed=1)
+    api = np.flatnonzero(t["node_type"] == gen.TYPE_API)
+    i = int(np.flatnonzero(t["act_quota_mask"] != 0)[0])
+    own = int(np.flatnonzero(api == t["act_pin_node"][i])[0])
+    m = t["act_quota_mask"].copy(); m[i] |= np.uint64(1 << own)
+    assert _trace_rc(tg, dict(t, act_quota_mask=m)) == -1      # the action's own quota
+    m = t["act_quota_mask"].copy(); m[i] |= np.uint64(1 << 3)
+    assert _trace_rc(tg, dict(t, act_quota_mask=m)) == -1      # a quota the scenario does not have
+    c = int(np.flatnonzero(t["act_type"] == gen.TYPE_CPU)[0])
+    m = t["act_quota_mask"].copy(); m[c] = np.uint64(1)
+    assert _trace_rc(tg, dict(t, act_quota_mask=m)) == -1      # only API actions draw on quotas
 
 
 def test_second_resource_arrays_come_in_pairs(tg):
@@ -234,7 +249,7 @@ def _trace_rc(tg, t):
     d.flags = 0
     d.tick_us = int(t["tick_us"])
     keep = []
-    tg._fill(d, t, [f[0] for f in tg.TraceDesc._fields_[9:-2]], keep)
+    tg._fill(d, t, [f[0] for f in tg.TraceDesc._fields_[9:-3]] + ["act_quota_mask"], keep)
     d.n_services = int(t.get("n_services", len(t["restore_us"]) if t.get("restore_us") is not None else 0))
     d.cache_slots = int(t.get("cache_slots", 64))
     h = C.c_void_p()

@@ -76,6 +76,8 @@ def test_replay_random_sweep(tg, orc):
                            rate_per_s=float(rng.choice([20.0, 100.0, 500.0])), horizon_s=float(rng.choice([1.0, 5.0, 20.0])),
                            max_ticks=int(rng.choice([60, 5000, 60000])), pin_frac=float(rng.choice([0.0, 0.3, 0.8])))
         t["depth"] = int(rng.integers(1, 5))
+        if n_api >= 2 and rng.random() < 0.6:
+            gen.with_extra_quotas(t, frac=float(rng.random()), seed=seed, max_extra=int(rng.integers(1, 4)))
         if n_gpu and rng.random() < 0.6:
             _with_services(t, seed, n_services=int(rng.choice([1, 4, 20])), slots=int(rng.choice([1, 2, 5])))
         _compare(_replay_gpu(tg, t), orc.replay(t), range(t["S"]), t["A"])
@@ -168,3 +170,20 @@ def test_replay_elastic_vs_fixed_dop(tg, orc):
         mean[name] = float(got["mean_act_us"].mean())
     print({k: round(v / 1e6, 3) for k, v in mean.items()}, flush=True)
     assert mean["elastic"] < mean["dop4"] < mean["dop16"]
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_replay_several_quotas(tg, orc, seed):
+    """Sec. 4.1 in the replay: API actions that take a token from several buckets when they start."""
+    print("case replay quotas", seed, flush=True)
+    n_api = (2, 3, 5, 16, 70)[seed % 5]                        # 70 quotas: the LDS node table of the admission
+    t = gen.make_trace(S=3, A=300 + 80 * seed, seed=700 + seed, cluster=(1 + seed % 2, 16, seed % 2, n_api),
+                       type_probs=(0.2, 0.1, 0.7), rate_per_s=float((100, 400, 1500)[seed % 3]), horizon_s=3.0, max_ticks=30000)
+    t["depth"] = 1 + seed % 3
+    gen.with_extra_quotas(t, frac=0.6, seed=seed, max_extra=1 + seed % 4)
+    if seed % 2:
+        _with_services(t, seed, n_services=5, slots=2)
+    want = orc.replay(t)
+    if seed % 3 == 2:                                          # the heavily loaded cases: the masks delay somebody
+        assert (want["start_us"] != orc.replay(dict(t, act_quota_mask=None))["start_us"]).any()
+    _compare(_replay_gpu(tg, t), want, range(t["S"]), t["A"])
