@@ -36,6 +36,30 @@ def test_strerror(tg):
     assert tg.strerror(-99) == "unknown error"
 
 
+def test_field_offsets_match_the_compiled_header(tg, tmp_path):
+    """Every field of the four structs sits where a C compiler puts it: a small program that includes
+    include/tg.h prints offsetof() of the fields by name, the binding's ctypes structures must agree."""
+    import subprocess
+    structs = {"tg_problem_desc": tg.ProblemDesc, "tg_assign_out": tg.AssignOut, "tg_trace_desc": tg.TraceDesc,
+               "tg_replay_out": tg.ReplayOut}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "tg.h"', 'int main(void) {']
+    for cname, st in structs.items():
+        lines.append(f'  printf("{cname} %zu\\n", sizeof({cname}));')
+        for fname, _ in st._fields_:
+            lines.append(f'  printf("{cname}.{fname} %zu\\n", offsetof({cname}, {fname}));')
+    lines += ['  printf("tg_summary %zu\\n", sizeof(tg_summary));', '  return 0;', '}']
+    src = tmp_path / "offsets.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "offsets"
+    subprocess.check_call(["gcc", "-I", os.path.join(ROOT, "include"), "-o", str(exe), str(src)])
+    got = dict(l.split() for l in subprocess.check_output([str(exe)], text=True).splitlines())
+    for cname, st in structs.items():
+        assert int(got[cname]) == C.sizeof(st), cname
+        for fname, _ in st._fields_:
+            assert int(got[f"{cname}.{fname}"]) == getattr(st, fname).offset, f"{cname}.{fname}"
+    assert int(got["tg_summary"]) == tg.SUMMARY_DTYPE.itemsize
+
+
 def test_struct_layouts_match_header(tg):
     assert C.sizeof(tg.ProblemDesc) == 8 * 4 + 25 * 8 + 4 * 4
     assert C.sizeof(tg.AssignOut) == 9 * 8
