@@ -50,7 +50,7 @@ class Problem(C.Structure):
             "k_list", "type_k", "speedup_q16", "node_type", "node_cap", "node_free", "node_backlog_us",
             "node_chunks", "node_busy_off", "node_busy_rel_us", "act_type", "act_model", "act_t_ori_us",
             "act_age_us", "act_kmask", "act_param", "act_pin_node", "act_task", "node_aux_free", "act_aux",
-            "act_service", "node_resident", "restore_us", "act_quota_mask", "node_core_free")] + [("numa_cores", C.c_int32), ("gpu_pooled", C.c_int32)]
+            "act_service", "node_resident", "restore_us", "act_quota_mask", "node_core_free")] + [("numa_cores", C.c_int32), ("gpu_pooled", C.c_int32), ("queue_prefix", C.c_int32)]
 
 
 class Summary(C.Structure):
@@ -133,9 +133,10 @@ def _problem(p):
     for n in ("B", "N", "M", "K", "n_classes", "n_tasks", "depth"):
         setattr(s, n, int(p[n]))
     s.order_policy = int(p.get("order_policy", 0))      # 0: first come first served, 1: least estimated ACT first
-    _fill(s, p, [f[0] for f in Problem._fields_[8:-2]], keep)
+    _fill(s, p, [f[0] for f in Problem._fields_[8:-3]], keep)
     s.numa_cores = int(p.get("numa_cores", 0))          # cores per NUMA domain (with node_core_free)
     s.gpu_pooled = int(p.get("gpu_pooled", 0))          # 1: the GPU nodes of a snapshot are one pool of chunks
+    s.queue_prefix = int(p.get("queue_prefix", 0))      # 1: one admitted prefix of the whole queue instead of one per pool
     return s, keep
 
 

@@ -287,7 +287,7 @@ enum { ORDER_FCFS = 0, ORDER_COST = 1 };
 
 // ---- one scheduling step on one snapshot (Alg. 1 applied per resource pool) -------------
 StepOut step(const Tables& tb, const std::vector<Act>& acts, std::vector<Node> nodes, int order_policy = ORDER_FCFS,
-             int numa_cores = 0, bool gpu_pooled = false) {
+             int numa_cores = 0, bool gpu_pooled = false, bool queue_prefix = false) {
   const int N = (int)acts.size(), M = (int)nodes.size(), K = tb.K;
   // Sec. 5.3 / Alg. 4: the GPU manager runs the algorithm for the GPU cluster as a whole, and the
   // state of Alg. 4 counts the chunks of every size it has, whichever node they are on.  In that
@@ -371,10 +371,15 @@ StepOut step(const Tables& tb, const std::vector<Act>& acts, std::vector<Node> n
       if ((a.extra >> r & 1ull) && rem[api_nodes[r]] < 1) return false;
     return true;
   };
+  // queue_prefix: Alg. 1 as printed takes the longest prefix of the whole waiting queue that the
+  // resources accommodate, so the first action that does not fit ends the admission for every
+  // action behind it, of whatever kind.  Otherwise a misfit only closes its own pool (its node,
+  // if it is pinned), as the managers of Sec. 5.2 schedule their resources independently.
+  bool queue_closed = false;
   for (int i : visit) {
     if (o.reason[i] == R_INFEASIBLE) continue;
     const Act& a = acts[i];
-    if (type_closed[a.type] || (a.pin >= 0 && closed[a.pin])) {
+    if (queue_closed || type_closed[a.type] || (a.pin >= 0 && closed[a.pin])) {
       o.reason[i] = R_PREFIX;
       if (a.pin >= 0) waiting_pinned[a.pin].push_back(i);
       continue;
@@ -394,6 +399,7 @@ StepOut step(const Tables& tb, const std::vector<Act>& acts, std::vector<Node> n
     if (bj < 0) {
       if (a.pin >= 0) { closed[a.pin] = 1; waiting_pinned[a.pin].push_back(i); }
       else type_closed[a.type] = 1;
+      if (queue_prefix) queue_closed = true;
       o.reason[i] = R_PREFIX;
       continue;
     }
@@ -502,6 +508,7 @@ struct orc_problem {
   const uint64_t* act_quota_mask;                           // [B*N] further quotas of an API action, or NULL
   const uint64_t* node_core_free; int32_t numa_cores;       // [B*M*4] free-core bitmaps of CPU nodes, or NULL (then numa_cores = 0)
   int32_t gpu_pooled;                                       // 1: the GPU nodes of a snapshot form one pool of chunks (Alg. 4's state)
+  int32_t queue_prefix;                                     // 1: one admitted prefix of the whole queue (Alg. 1 as printed) instead of one per pool
 };
 
 struct orc_summary {
@@ -620,7 +627,8 @@ void orc_assign(const orc_problem* p, int32_t* node, int32_t* units, int64_t* ac
   for (int b = 0; b < p->B; ++b) {
     const std::vector<Act> acts = acts_of(p, b);
     const std::vector<Node> nodes = nodes_of(p, b);
-    const StepOut o = step(tb, acts, nodes, p->order_policy, p->node_core_free ? p->numa_cores : 0, p->gpu_pooled != 0);
+    const StepOut o = step(tb, acts, nodes, p->order_policy, p->node_core_free ? p->numa_cores : 0, p->gpu_pooled != 0,
+                           p->queue_prefix != 0);
     const size_t a0 = (size_t)b * p->N, n0 = (size_t)b * p->M;
     orc_summary s;
     std::memset(&s, 0, sizeof s);

@@ -48,6 +48,7 @@ def _place(p, b):
     home, reason = np.full(N, -1), np.zeros(N, int)
     api = [j for j in range(M) if nt[j] == gen.TYPE_API][:64]
     closed, type_closed = set(), set()
+    whole_queue = bool(p.get("queue_prefix", 0))                # one prefix of the whole queue instead of one per pool
     for i in range(N):
         g = b * N + i
         t, pin = int(p["act_type"][g]), int(p["act_pin_node"][g])
@@ -57,7 +58,7 @@ def _place(p, b):
         if not feasible:
             reason[i] = 3
             continue
-        if t in type_closed or (pin >= 0 and pin in closed):
+        if t in type_closed or (pin >= 0 and pin in closed) or (whole_queue and (closed or type_closed)):
             reason[i] = 1
             continue
         kmin = int(p["k_list"][ops[0]])
