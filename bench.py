@@ -128,6 +128,25 @@ def pooled_section(a, tg, gen, torch, p):
     return res
 
 
+def queue_prefix_section(a, tg, torch, p):
+    """The same workload with one admitted prefix of the whole queue (Alg. 1 as printed) instead of one per pool:
+    time of tg_assign (the placement runs twice) and how many actions are still selected."""
+    P = tg.Problem(dict(p, queue_prefix=1))
+    bufs = P.alloc_assign()
+    for _ in range(3):
+        P.assign(None, bufs)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n = max(5, a.steps // 5)
+    e0.record()
+    for _ in range(n):
+        P.assign(None, bufs)
+    e1.record()
+    torch.cuda.synchronize()
+    s = tg.summary_to_numpy(bufs["summary"])
+    P.free()
+    return {"assign_ms": e0.elapsed_time(e1) / n, "selected_fraction": float(s["n_selected"].sum()) / (P.B * P.N)}
+
+
 def replay_section(a, tg, gen, torch):
     """Workload 5 (batched trace replay): S scenarios x 10 000 Poisson arrivals over 200 s, rescheduling every
     100 ms, on the default cluster (256x128 cores, 32x8 GPUs, 16 quotas) and on the contended one (4x32 cores,
@@ -321,6 +340,7 @@ def main():
         out["order_policy_cost"] = order_section(a, tg, torch, p, s)
         out["core_sets"] = core_sets_section(a, tg, gen, torch, p)
         out["gpu_pooled"] = pooled_section(a, tg, gen, torch, p)
+        out["queue_prefix"] = queue_prefix_section(a, tg, torch, p)
     if a.replay_scenarios > 0 and a.only == "step":
         out["replay"] = replay_section(a, tg, gen, torch)
 

@@ -149,7 +149,13 @@ typedef struct {
    * node_backlog_us, no GPU action pinned, no services (else TG_E_INVALID_ARG), and pooled chunk
    * counts within TG_MAX_CHUNK_STATES (else TG_E_RANGE).  0: every node on its own. */
   int32_t gpu_pooled;
-  int32_t reserved_;              /* 0                                                           */
+  /* 1: Alg. 1 as printed - the admitted candidates are the longest prefix of the whole waiting
+   * queue (in visiting order: FCFS rank, or with TG_ORDER_COST the key and then the FCFS rank,
+   * over all kinds of resource together) that the resources accommodate: the first action that
+   * does not fit, and every action behind it, waits (TG_DEFER_PREFIX), whatever its kind.
+   * 0: one such prefix per pool - a misfit closes the queue of its own kind of resource, or of its
+   * node if it is pinned (the managers of Sec. 5.2 schedule their resources independently). */
+  int32_t queue_prefix;
 } tg_problem_desc;
 
 /* Per-snapshot result of tg_assign.  Only mean_act_us and util are floating point. */

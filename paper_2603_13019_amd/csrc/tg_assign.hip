@@ -32,6 +32,8 @@ struct AssignWs {
   int32_t* class_ctl;    // [2*kClasses + 2] per class: number of nodes, next node to hand out; then, for the light
                          // class, how many of its nodes were filed at the front and at the back of its list
   int32_t* visit;        // [B*N] TG_ORDER_COST: action ids grouped by kind in visiting order (else unused)
+  uint64_t* gkey;        // [B*N] whole-queue prefix under TG_ORDER_COST: (key, action id) of every action (else unused)
+  uint64_t* stop;        // [B]   whole-queue prefix: place in the visiting order at which the admission ends (else unused)
 };
 
 // Nodes are processed in classes of candidate count so that the LDS a wavefront needs (the
@@ -59,8 +61,11 @@ size_t carve(const tg_problem* p, char* base, AssignWs* w) {
   char* e = take(nN * 4); char* f = take(nN * 4); char* g = take(nN * 4); char* h = take(nN * 4);
   char* cl = take(nN * 4 * kClasses); char* cc = take((2 * kClasses + 2) * 4);
   char* vi = take(p->order_policy == TG_ORDER_COST ? nA * 4 : 0);
+  char* gk = take(p->queue_prefix && p->order_policy == TG_ORDER_COST ? nA * 8 : 0);
+  char* st = take(p->queue_prefix ? (size_t)p->dev.B * 8 : 0);
   if (w) {
     w->class_list = (int32_t*)cl; w->class_ctl = (int32_t*)cc; w->visit = (int32_t*)vi;
+    w->gkey = (uint64_t*)gk; w->stop = (uint64_t*)st;
     w->dur = (int64_t*)a; w->slot = (int32_t*)b; w->order = (int32_t*)c; w->dorder = (int32_t*)d;
     w->nl_off = (int32_t*)e; w->nl_cnt = (int32_t*)f; w->dl_off = (int32_t*)g; w->dl_cnt = (int32_t*)h;
   }
@@ -97,7 +102,8 @@ constexpr int kOrderThreads = 256;
 constexpr uint64_t kOrderKeyInf = (1ull << 46) - 1;
 
 __global__ __launch_bounds__(kOrderThreads) void tg_order_kernel(TgDev P, const int64_t* __restrict__ dur, const TgBlock* __restrict__ blocks,
-                                                                 int32_t* __restrict__ visit, int n_pad_max) {
+                                                                 int32_t* __restrict__ visit, int n_pad_max,
+                                                                 uint64_t* __restrict__ gkey) {
   extern __shared__ __align__(16) unsigned char smem[];
   uint64_t* s_key = reinterpret_cast<uint64_t*>(smem);                       // [n_pad]
   __shared__ unsigned long long s_minback[TG_MAX_K + 1];                       // by number of options the capacity admits
@@ -156,6 +162,7 @@ __global__ __launch_bounds__(kOrderThreads) void tg_order_kernel(TgDev P, const 
         }
       }
       key = best << 17 | (uint32_t)x;
+      if (gkey) gkey[g] = best << 17 | (uint32_t)id;                          // place in the order of the whole queue
     }
     s_key[x] = key;
   }
@@ -176,13 +183,39 @@ __global__ __launch_bounds__(kOrderThreads) void tg_order_kernel(TgDev P, const 
 }
 
 // ------------------------------------------------------------------------------------------
+// Whole-queue prefix: the admission of a snapshot ends at the first action, in the visiting
+// order of the whole queue, that a pass with one prefix per pool makes wait (before it nothing is
+// closed, so both rules agree up to there).  stop[b] = that action's place in the order.
+__global__ __launch_bounds__(256) void tg_stop_kernel(TgDev P, tg_assign_out O, const uint64_t* __restrict__ gkey,
+                                                      uint64_t* __restrict__ stop) {
+  __shared__ unsigned long long s_min;
+  const int b = blockIdx.x;
+  if (threadIdx.x == 0) s_min = ~0ull;
+  __syncthreads();
+  uint64_t m = ~0ull;
+  for (int i = threadIdx.x; i < P.N; i += 256) {
+    const size_t g = (size_t)b * P.N + i;
+    if (O.defer_reason[g] != TG_DEFER_PREFIX) continue;
+    const uint64_t k = gkey ? gkey[g] : (uint64_t)i;
+    m = k < m ? k : m;
+  }
+  m = tg_wave_min_u64(m);
+  if ((threadIdx.x & (TG_WAVE - 1)) == 0) atomicMin(&s_min, (unsigned long long)m);
+  __syncthreads();
+  if (threadIdx.x == 0) stop[b] = s_min;
+}
+
+// ------------------------------------------------------------------------------------------
 // MAXR / MAXR_EXT / LDS_TABLE: the variants of tg_place_pool compiled into this instantiation;
 // the host picks the narrowest one that takes every pool of the problem.
-template <int MAXR, int MAXR_EXT, bool LDS_TABLE>
+// WHOLE_QUEUE: with `stop` the pool's actions behind stop[b] in the order of the whole queue
+// (gkey: their places under TG_ORDER_COST, else the action id is the place) are not admitted.
+template <int MAXR, int MAXR_EXT, bool LDS_TABLE, bool WHOLE_QUEUE>
 __global__ __launch_bounds__(TG_WAVE) void tg_place_kernel(TgDev P, const int64_t* __restrict__ dur,
                                                            const int64_t* __restrict__ cost,
                                                            const TgBlock* __restrict__ blocks, AssignWs W,
-                                                           tg_assign_out O, int lds_nodes, const int32_t* __restrict__ visit) {
+                                                           tg_assign_out O, int lds_nodes, const int32_t* __restrict__ visit,
+                                                           const uint64_t* __restrict__ gkey, const uint64_t* __restrict__ stop) {
   extern __shared__ __align__(16) unsigned char smem[];
   TgPoolLds S;
   tg_pool_lds_carve(smem, lds_nodes, &S);
@@ -214,7 +247,51 @@ __global__ __launch_bounds__(TG_WAVE) void tg_place_kernel(TgDev P, const int64_
   if (cost) { const TgBlock blk = blocks[b * 3 + t]; io.cost = cost + blk.cost_off; io.cost_row_len = blk.M_t * blk.K_t; }
   io.out_node = O.node + abase; io.out_units = O.units + abase; io.out_act = O.act_us + abase;
   io.out_reason = O.defer_reason + abase; io.slot = W.slot + abase;
-  tg_place_pool<MAXR, MAXR_EXT, LDS_TABLE>(S, io, acts, Nt, Mt, t == TG_TYPE_GPU, lane);
+  int n_adm = Nt;
+  if constexpr (WHOLE_QUEUE) {
+    if (stop) {                                       // the pool's list ascends in that order: bisection
+      const uint64_t lim = stop[b];
+      int lo = 0, hi = Nt;
+      while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        const int id = acts[mid];
+        const uint64_t k = gkey ? gkey[abase + id] : (uint64_t)id;
+        if (k < lim) lo = mid + 1; else hi = mid;
+      }
+      n_adm = lo;
+    }
+  }
+  tg_place_pool<MAXR, MAXR_EXT, LDS_TABLE>(S, io, acts, n_adm, Mt, t == TG_TYPE_GPU, lane);
+  if constexpr (WHOLE_QUEUE) {
+    // everybody behind the end of the prefix waits; those pinned to a node join its waiting list
+    for (int base = n_adm; base < Nt; base += TG_WAVE) {
+      const int cnt = min(TG_WAVE, Nt - base);
+      int id = 0, pr = -1, stat = 1;
+      if (lane < cnt) {
+        id = acts[base + lane];
+        stat = (int)io.act_static[id];
+        const int pin = io.act_pin[id];
+        if (pin >= 0 && !stat) pr = io.node_rank[pin];
+      }
+      int slot = 0;
+      for (uint64_t pinned = __ballot(pr >= 0); pinned; pinned &= pinned - 1) {   // one after the other: the lists keep the visiting order
+        const int l = __builtin_ctzll(pinned);
+        const int r = __builtin_amdgcn_readlane(pr, l);
+        const int s = S.dcnt[r];
+        if (lane == l) slot = s;
+        tg_wave_sync();
+        if (lane == 0) S.dcnt[r] = s + 1;
+        tg_wave_sync();
+      }
+      if (lane < cnt) {
+        io.out_node[id] = -1;
+        io.out_reason[id] = (uint8_t)(stat ? TG_DEFER_INFEASIBLE : TG_DEFER_PREFIX);
+        io.slot[id] = slot; io.out_units[id] = 0;
+        if (io.out_act) io.out_act[id] = -1;
+      }
+    }
+    tg_wave_sync();
+  }
 
   tg_pool_extents(S, nodes, Mt, a0, W.nl_off + nbase, W.nl_cnt + nbase, W.dl_off + nbase, W.dl_cnt + nbase, lane);
 }
@@ -613,7 +690,8 @@ extern "C" int tg_assign(const tg_problem* p, const int64_t* d_cost, const tg_as
     const size_t order_lds = (size_t)n_pad * 8;
     if (order_lds > 48 * 1024)
       TG_HIP_CHECK(hipFuncSetAttribute((const void*)tg_order_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)order_lds));
-    hipLaunchKernelGGL(tg_order_kernel, dim3(P.B * 3), dim3(kOrderThreads), order_lds, s, P, W.dur, p->d_blocks, W.visit, n_pad);
+    hipLaunchKernelGGL(tg_order_kernel, dim3(P.B * 3), dim3(kOrderThreads), order_lds, s, P, W.dur, p->d_blocks, W.visit, n_pad,
+                       p->queue_prefix ? W.gkey : nullptr);
     visit = W.visit;
   }
   // the rows of the score tensor are in FCFS order: another visiting order recomputes Eq. 2 instead
@@ -624,15 +702,25 @@ extern "C" int tg_assign(const tg_problem* p, const int64_t* d_cost, const tg_as
     const bool ext = P.act_aux || P.act_service || P.act_quota;
     const int mk = p->max_nodes_of_kind;
     const int width = place_cost || mk > 16 * TG_WAVE ? 0 : mk <= TG_WAVE ? 1 : mk <= 4 * TG_WAVE ? 4 : 16;
-    using PlaceKernel = void (*)(TgDev, const int64_t*, const int64_t*, const TgBlock*, AssignWs, tg_assign_out, int, const int32_t*);
-    PlaceKernel k = width == 0 ? tg_place_kernel<0, 0, true>
-                  : width == 1 ? (ext ? tg_place_kernel<1, 1, false> : tg_place_kernel<1, 0, false>)
-                  : width == 4 ? (ext ? tg_place_kernel<4, 4, false> : tg_place_kernel<4, 0, false>)
-                               : (ext ? tg_place_kernel<16, 16, false> : tg_place_kernel<16, 0, false>);
+    using PlaceKernel = void (*)(TgDev, const int64_t*, const int64_t*, const TgBlock*, AssignWs, tg_assign_out, int, const int32_t*,
+                                 const uint64_t*, const uint64_t*);
+    PlaceKernel k = p->queue_prefix ? tg_place_kernel<0, 0, true, true>
+                  : width == 0 ? tg_place_kernel<0, 0, true, false>
+                  : width == 1 ? (ext ? tg_place_kernel<1, 1, false, false> : tg_place_kernel<1, 0, false, false>)
+                  : width == 4 ? (ext ? tg_place_kernel<4, 4, false, false> : tg_place_kernel<4, 0, false, false>)
+                               : (ext ? tg_place_kernel<16, 16, false, false> : tg_place_kernel<16, 0, false, false>);
     if (place_lds > 64 * 1024)
       TG_HIP_CHECK(hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)place_lds));
     hipLaunchKernelGGL(k, dim3(P.B * 3), dim3(TG_WAVE), place_lds, s, P, W.dur, place_cost, p->d_blocks, W, *out,
-                       p->max_nodes_of_kind, visit);
+                       p->max_nodes_of_kind, visit, nullptr, nullptr);
+    if (p->queue_prefix) {
+      // one prefix of the whole queue: the pass above (one prefix per pool) finds where it ends, a
+      // second pass admits the actions before that place and leaves the others waiting
+      const uint64_t* gkey = visit ? W.gkey : nullptr;
+      hipLaunchKernelGGL(tg_stop_kernel, dim3(P.B), dim3(256), 0, s, P, *out, gkey, W.stop);
+      hipLaunchKernelGGL(k, dim3(P.B * 3), dim3(TG_WAVE), place_lds, s, P, W.dur, place_cost, p->d_blocks, W, *out,
+                         p->max_nodes_of_kind, visit, gkey, W.stop);
+    }
   }
   hipLaunchKernelGGL(tg_lists_kernel, dim3((unsigned)((nA + nN + 255) / 256)), dim3(256), 0, s, P, W, *out);
   // Persistent wavefronts pull nodes of their class and, when it is exhausted, of the lighter

@@ -136,6 +136,7 @@ extern "C" int tg_build_problem(const tg_problem_desc* desc, void* hip_stream, t
   if (!desc || !out) return TG_E_INVALID_ARG;
   *out = nullptr;
   if (desc->gpu_pooled != 0 && desc->gpu_pooled != 1) return TG_E_INVALID_ARG;
+  if (desc->queue_prefix != 0 && desc->queue_prefix != 1) return TG_E_INVALID_ARG;
   tg_problem_desc folded = *desc;
   PoolFold fold;
   if (desc->gpu_pooled) {
@@ -464,7 +465,7 @@ extern "C" int tg_build_problem(const tg_problem_desc* desc, void* hip_stream, t
     p->score_wgs = (int)wgs;
     p->n_candidates = total;
     p->max_nodes_of_kind = max_kind;
-    p->order_policy = d->order_policy; p->max_actions_of_kind = max_acts_kind;
+    p->order_policy = d->order_policy; p->queue_prefix = d->queue_prefix; p->max_actions_of_kind = max_acts_kind;
     p->max_free_cpu = max_free_cpu;
     p->max_heap = max_heap;
     p->nodes_free_gt16 = free_gt16; p->nodes_free_gt64 = free_gt64;

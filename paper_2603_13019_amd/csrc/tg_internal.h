@@ -96,6 +96,7 @@ struct tg_problem {
   hipStream_t score_stream;
   hipEvent_t ev_score_fork, ev_score_done;
   int order_policy;        // TG_ORDER_*
+  int queue_prefix;        // 1: one admitted prefix of the whole queue instead of one per pool
   int max_actions_of_kind; // largest N_t over all snapshots and kinds
   int max_nodes_of_kind;   // largest M_t over all snapshots and kinds
   int max_free_cpu;        // largest node_free over CPU nodes

@@ -78,6 +78,7 @@ def _build_rc(tg, p):
     d.n_services = int(p.get("n_services", len(p["restore_us"]) if p.get("restore_us") is not None else 0))
     d.numa_cores = int(p.get("numa_cores", 0))
     d.gpu_pooled = int(p.get("gpu_pooled", 0))
+    d.queue_prefix = int(p.get("queue_prefix", 0))
     h = C.c_void_p()
     rc = tg.load().tg_build_problem(C.byref(d), None, C.byref(h))
     assert rc != 0 and not h.value
@@ -229,6 +230,8 @@ def test_pooled_gpus_are_validated(tg):
     p["node_backlog_us"][g] = 0
     p["gpu_pooled"] = 1
     assert _build_rc(tg, dict(p, gpu_pooled=2)) == -1
+    assert _build_rc(tg, dict(p, gpu_pooled=0, queue_prefix=2)) == -1
+    assert _build_rc(tg, dict(p, gpu_pooled=0, queue_prefix=-1)) == -1
     q = dict(p); q["node_backlog_us"] = p["node_backlog_us"].copy(); q["node_backlog_us"][g[1]] = 5
     assert _build_rc(tg, q) == -1                               # a pool has one backlog
     q = dict(p); q["act_pin_node"] = p["act_pin_node"].copy()

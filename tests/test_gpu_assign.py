@@ -293,12 +293,14 @@ def _sweep_problem(seed):
         gen.with_extra_quotas(p, frac=float(rng.random()), seed=seed, max_extra=int(rng.integers(1, 6)))
     if rng.random() < 0.5:
         gen.with_core_maps(p, int(rng.choice([4, 8, 16, 32, 64])), seed)
+    p["queue_prefix"] = int(rng.random() < 0.3)              # one prefix of the whole queue instead of one per pool
     return p, use_cost
 
 
 def test_assign_random_sweep(tg, orc):
     """200 problems with every parameter drawn at random (sizes, kinds, capacities, options, depth, busy
-    lists, pins, duration scale, visiting order, second resource, services, pooled GPUs, several quotas, core maps, with and without the score tensor)."""
+    lists, pins, duration scale, visiting order, second resource, services, pooled GPUs, several quotas, core maps, whole-queue prefix,
+    with and without the score tensor)."""
     for seed in range(3000, 3200):
         p, use_cost = _sweep_problem(seed)
         _compare(_assign_gpu(tg, p, use_cost=use_cost), orc.assign(p), f"sweep seed {seed}")
@@ -508,3 +510,49 @@ def test_assign_several_quotas_config3_slice(tg, orc):
     base = orc.assign(dict(p, act_quota_mask=None))
     assert (want["reason"] != base["reason"]).any()
     _compare(_assign_gpu(tg, p), want)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_assign_queue_prefix_random_problems(tg, orc, seed):
+    """One admitted prefix of the whole queue (Alg. 1 as printed): both visiting orders, with and without the
+    score tensor, next to the second resource, services, several quotas, core maps and pooled GPUs."""
+    print("case", seed, flush=True)
+    p = gen.make_random_problem(1300 + seed, B=4, N=80 + 25 * seed, n_cpu=1 + seed % 4, n_gpu=1 + seed % 3, n_api=seed % 3,
+                                depth=1 + seed % 3, busy=seed % 2 == 0, cpu_cap_hi=24 + 8 * (seed % 3),
+                                pin_frac=(0.0, 0.3, 0.8)[seed % 3])
+    if seed % 4 == 1:
+        _add_second_resource(p, seed, scarce=False)
+    if seed % 4 == 2:
+        _add_services(p, seed)
+    if seed % 4 == 3 and seed % 3:
+        gen.with_extra_quotas(p, 0.5, seed)
+    if seed % 5 == 0:
+        gen.with_core_maps(p, 8, seed)
+    if seed % 4 == 0:
+        _pooled(p)
+    p["queue_prefix"] = 1
+    p["order_policy"] = seed // 2 % 2
+    want = orc.assign(p)
+    _compare(_assign_gpu(tg, p, use_cost=seed % 2 == 1), want, f"seed {seed}")
+    per_pool = orc.assign(dict(p, queue_prefix=0))
+    assert (per_pool["reason"] != want["reason"]).any(), "the whole-queue prefix should bind here"
+
+
+def test_assign_queue_prefix_code_paths(tg, orc):
+    for case in sorted(CODE_PATHS):
+        for order in (0, 1):
+            print("case", case, order, flush=True)
+            p = dict(_code_path_problem(case), queue_prefix=1, order_policy=order)
+            _compare(_assign_gpu(tg, p), orc.assign(p), f"{case} order {order}")
+
+
+def test_assign_queue_prefix_config2_full(tg, orc):
+    """Workload 2 at full size: the GPU pool of a snapshot runs out long before its CPU pool, so the one prefix
+    ends early and far fewer actions are selected than with one prefix per pool."""
+    p = dict(gen.make_config(2), queue_prefix=1)
+    want = orc.assign(p)
+    _compare(_assign_gpu(tg, p), want, "config 2")
+    per_pool = orc.assign(dict(p, queue_prefix=0))
+    assert want["summary"]["n_assigned"].sum() < per_pool["summary"]["n_assigned"].sum()
+    p["order_policy"] = 1
+    _compare(_assign_gpu(tg, p), orc.assign(p), "config 2, cost order")
