@@ -69,7 +69,7 @@ class Trace(C.Structure):
         ("tick_us", C.c_int64)] + [(n, C.c_void_p) for n in (
             "k_list", "type_k", "speedup_q16", "node_type", "node_cap", "quota_rate", "quota_tok0_micro",
             "arrival_us", "act_type", "act_model", "act_t_ori_us", "act_kmask", "act_param", "act_pin_node",
-            "act_service", "restore_us", "act_quota_mask")]
+            "act_service", "restore_us", "act_quota_mask")] + [("queue_prefix", C.c_int32)]
 
 
 _DT = dict(k_list=np.int32, type_k=np.int32, speedup_q16=np.uint32, node_type=np.uint8, node_cap=np.int32,
@@ -147,7 +147,8 @@ def _trace(t):
         setattr(s, n, int(t[n]))
     s.tick_us = int(t["tick_us"])
     s.cache_slots = int(t.get("cache_slots", 64))
-    _fill(s, t, [f[0] for f in Trace._fields_[9:]], keep)
+    s.queue_prefix = int(t.get("queue_prefix", 0))       # 1: every step admits one prefix of the whole waiting queue
+    _fill(s, t, [f[0] for f in Trace._fields_[9:-1]], keep)
     return s, keep
 
 

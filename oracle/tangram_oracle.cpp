@@ -527,6 +527,7 @@ struct orc_trace {
   const uint32_t* act_kmask; const uint32_t* act_param; const int32_t* act_pin_node;
   const int32_t* act_service; const int64_t* restore_us;           // both or neither (Sec. 5.3)
   const uint64_t* act_quota_mask;                                  // [S*A] further quotas of an API action (Sec. 4.1), or NULL
+  int32_t queue_prefix;                                            // 1: every step admits one prefix of the whole waiting queue
 };
 
 }  // extern "C"
@@ -797,7 +798,7 @@ void orc_replay(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us, int64
         if (nodes[u.node].type != T_API)
           for (int c = 0; c < u.k; ++c) nodes[u.node].busy.push_back(u.fin - now);
       // (4) the scheduling step; (5) selected actions start now
-      const StepOut o = step(tb, acts, nodes);
+      const StepOut o = step(tb, acts, nodes, ORDER_FCFS, 0, false, t->queue_prefix != 0);
       std::vector<int> still;
       for (size_t w = 0; w < waiting.size(); ++w) {
         const int i = waiting[w];
