@@ -180,6 +180,19 @@ def replay_section(a, tg, gen, torch):
             res[name]["cpu_oracle_actions_per_sec"] = n * 10_000 / dt
             res[name]["cpu_oracle_sample"] = f"{n} scenarios, 1 core"
         T.free()
+        if contended:
+            # the same trace with one admitted prefix of the whole queue per step (Alg. 1 as printed): two admission passes per tick
+            T = tg.Trace(dict(t, queue_prefix=1))
+            bufs = T.alloc()
+            T.replay(bufs)
+            torch.cuda.synchronize()
+            e0.record()
+            T.replay(bufs)
+            e1.record()
+            torch.cuda.synchronize()
+            res[name]["queue_prefix"] = {"ms": e0.elapsed_time(e1), "mean_act_us": float(bufs["mean_act_us"].mean().item()),
+                                         "started": int(bufs["n_started"].sum().item())}
+            T.free()
     # scheduler ablation (the paper's Fig. 7 on synthetic traces): elastic units against fixed DoP 4 and 16
     t = gen.make_trace(S=64, A=2000, seed=7, cluster=(4, 32, 0, 0), type_probs=(1, 0, 0), rate_per_s=30.0,
                        horizon_s=2000 / 30.0, max_ticks=400000, pin_frac=0.0)

@@ -247,10 +247,13 @@ int tg_step(const tg_problem *p, int64_t *d_cost, const tg_assign_out *out, void
  * service, if any).  Action arrays have S*A entries and
  * must be sorted by arrival within a scenario; node arrays have S*M entries.
  */
+/* tg_trace_desc.flags: every step admits one prefix of the whole waiting queue (as queue_prefix
+ * of tg_problem_desc) instead of one prefix per pool */
+enum { TG_TRACE_QUEUE_PREFIX = 1 };
 typedef struct {
   int32_t S, A, M, K, n_classes, depth;
   int32_t max_ticks; /* the replay of a scenario stops after this many ticks                    */
-  uint32_t flags;    /* must be 0                                                               */
+  uint32_t flags;    /* TG_TRACE_QUEUE_PREFIX or 0; other bits must be clear                    */
   int64_t tick_us;   /* rescheduling period                                                     */
   const int32_t *k_list, *type_k;
   const uint32_t *speedup_q16;

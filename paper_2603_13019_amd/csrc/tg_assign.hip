@@ -249,49 +249,10 @@ __global__ __launch_bounds__(TG_WAVE) void tg_place_kernel(TgDev P, const int64_
   io.out_reason = O.defer_reason + abase; io.slot = W.slot + abase;
   int n_adm = Nt;
   if constexpr (WHOLE_QUEUE) {
-    if (stop) {                                       // the pool's list ascends in that order: bisection
-      const uint64_t lim = stop[b];
-      int lo = 0, hi = Nt;
-      while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        const int id = acts[mid];
-        const uint64_t k = gkey ? gkey[abase + id] : (uint64_t)id;
-        if (k < lim) lo = mid + 1; else hi = mid;
-      }
-      n_adm = lo;
-    }
+    if (stop) n_adm = tg_prefix_len(acts, Nt, gkey ? gkey + abase : nullptr, stop[b]);
   }
   tg_place_pool<MAXR, MAXR_EXT, LDS_TABLE>(S, io, acts, n_adm, Mt, t == TG_TYPE_GPU, lane);
-  if constexpr (WHOLE_QUEUE) {
-    // everybody behind the end of the prefix waits; those pinned to a node join its waiting list
-    for (int base = n_adm; base < Nt; base += TG_WAVE) {
-      const int cnt = min(TG_WAVE, Nt - base);
-      int id = 0, pr = -1, stat = 1;
-      if (lane < cnt) {
-        id = acts[base + lane];
-        stat = (int)io.act_static[id];
-        const int pin = io.act_pin[id];
-        if (pin >= 0 && !stat) pr = io.node_rank[pin];
-      }
-      int slot = 0;
-      for (uint64_t pinned = __ballot(pr >= 0); pinned; pinned &= pinned - 1) {   // one after the other: the lists keep the visiting order
-        const int l = __builtin_ctzll(pinned);
-        const int r = __builtin_amdgcn_readlane(pr, l);
-        const int s = S.dcnt[r];
-        if (lane == l) slot = s;
-        tg_wave_sync();
-        if (lane == 0) S.dcnt[r] = s + 1;
-        tg_wave_sync();
-      }
-      if (lane < cnt) {
-        io.out_node[id] = -1;
-        io.out_reason[id] = (uint8_t)(stat ? TG_DEFER_INFEASIBLE : TG_DEFER_PREFIX);
-        io.slot[id] = slot; io.out_units[id] = 0;
-        if (io.out_act) io.out_act[id] = -1;
-      }
-    }
-    tg_wave_sync();
-  }
+  if constexpr (WHOLE_QUEUE) tg_place_tail(S, io, acts, n_adm, Nt, lane);   // everybody behind the end of the prefix waits
 
   tg_pool_extents(S, nodes, Mt, a0, W.nl_off + nbase, W.nl_cnt + nbase, W.dl_off + nbase, W.dl_cnt + nbase, lane);
 }

@@ -21,6 +21,7 @@
 
 struct TgTraceDev {
   int S, A, M, K, n_classes, depth, max_ticks, cache_slots;
+  int queue_prefix;               // 1: every step admits one prefix of the whole waiting queue (Alg. 1 as printed)
   int64_t tick_us;
   int k_list[TG_MAX_K];
   int type_k[4];
@@ -171,10 +172,11 @@ struct ReplayLds {
   int busy_slots;
 };
 
+template <bool WHOLE_QUEUE>   // every step admits one prefix of the whole waiting queue (two admission passes per tick)
 __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, ReplayWs W, tg_replay_out O, ReplayLds LD,
                                                              TgNodeLdsPlan plan) {
   extern __shared__ __align__(16) unsigned char smem[];
-  __shared__ int s_wcnt[3], s_next, s_started, s_nrun, s_wave_cnt[kWaves], s_hist[256], s_sel[2];
+  __shared__ int s_wcnt[3], s_next, s_started, s_nrun, s_wave_cnt[kWaves], s_hist[256], s_sel[2], s_stop;
   __shared__ long long s_sum;
   const int s = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int A = T.A, M = T.M, K = T.K;
@@ -295,7 +297,11 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
     const int wcs[3] = {wc0, wc1, wc2};
     const int woff[3] = {0, wc0, wc0 + wc1};
 
-    // (4a) admission + node choice, one wavefront per resource kind
+    // (4a) admission + node choice, one wavefront per resource kind.  With the whole-queue prefix a first pass
+    // (one prefix per kind) shows where the admission ends - at the first waiting action, in arrival order, that it
+    // defers - and a second pass admits only the actions before that one.
+    constexpr int n_pass = WHOLE_QUEUE ? 2 : 1;
+    for (int pass = 0; pass < n_pass; ++pass) {
     for (int ty = wave; ty < 3; ty += kWaves) {
       const int n0 = T.tnode_off[s * 4 + ty], Mt = T.tnode_off[s * 4 + ty + 1] - n0;
       const int32_t* nodes = T.tnode_idx + nbase + n0;
@@ -320,11 +326,27 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
       io.node_rank = T.node_rank + nbase; io.nodes = nodes; io.dur = dur; io.cost = nullptr; io.cost_row_len = 0;
       io.K = K; io.Kt = T.type_k[ty];
       io.out_node = o_node; io.out_units = o_units; io.out_act = nullptr; io.out_reason = reason; io.slot = slot;
-      tg_place_pool<4, 1>(S, io, wl[ty], wcs[ty], Mt, ty == TG_TYPE_GPU, lane);
+      const int n_adm = pass == 0 ? wcs[ty] : tg_prefix_len(wl[ty], wcs[ty], nullptr, (uint64_t)s_stop);   // ids ascend with the arrivals
+      tg_place_pool<4, 1>(S, io, wl[ty], n_adm, Mt, ty == TG_TYPE_GPU, lane);
+      if constexpr (WHOLE_QUEUE) { if (pass == 1) tg_place_tail(S, io, wl[ty], n_adm, wcs[ty], lane); }
       tg_pool_extents(S, nodes, Mt, woff[ty], nl_off, nl_cnt, dl_off, dl_cnt, lane);
     }
     __threadfence_block();
     __syncthreads();
+    if (pass + 1 < n_pass) {
+      if (tid == 0) s_stop = INT32_MAX;
+      __syncthreads();
+      int first = INT32_MAX;
+      for (int ty = 0; ty < 3; ++ty)
+        for (int x = tid; x < wcs[ty]; x += kThreads) {
+          const int id = wl[ty][x];
+          if (reason[id] == TG_DEFER_PREFIX && id < first) first = id;
+        }
+      if (first != INT32_MAX) atomicMin(&s_stop, first);
+      __syncthreads();
+      if (s_stop == INT32_MAX) break;                             // nobody waits: both rules agree
+    }
+    }
     // (4b) group candidates and waiting pinned actions by node
     for (int ty = 0; ty < 3; ++ty)
       for (int x = tid; x < wcs[ty]; x += kThreads) {
@@ -513,7 +535,7 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
   if (!d || !out) return TG_E_INVALID_ARG;
   *out = nullptr;
   const int S = d->S, A = d->A, M = d->M, K = d->K;
-  if (S < 1 || A < 1 || M < 1 || d->flags != 0 || d->max_ticks < 1 || d->tick_us < 1) return TG_E_INVALID_ARG;
+  if (S < 1 || A < 1 || M < 1 || (d->flags & ~(uint32_t)TG_TRACE_QUEUE_PREFIX) != 0 || d->max_ticks < 1 || d->tick_us < 1) return TG_E_INVALID_ARG;
   if (d->depth < 1 || d->depth > TG_MAX_DEPTH) return TG_E_INVALID_ARG;
   const bool svc = d->act_service != nullptr;
   if (svc != (d->restore_us != nullptr)) return TG_E_INVALID_ARG;
@@ -667,6 +689,7 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
     v.act_service = svc ? (const int32_t*)(base + o_asvc) : nullptr;
     v.restore = svc ? (const int64_t*)(base + o_rest) : nullptr;
     v.cache_slots = svc ? d->cache_slots : 0;
+    v.queue_prefix = (d->flags & TG_TRACE_QUEUE_PREFIX) ? 1 : 0;
     v.act_quota = d->act_quota_mask ? (const uint64_t*)(base + o_aquota) : nullptr;
     v.speedup = (const uint32_t*)(base + o_speed);
     t->max_nodes_of_kind = max_kind; t->max_cap_cpu = max_cap_cpu; t->max_heap = max_heap;
@@ -720,9 +743,10 @@ extern "C" int tg_replay_trace(const tg_trace* t, const tg_replay_out* out, void
   while (LD.node_waves > 1 && off + LD.node_waves * node_bytes > half_cu) LD.node_waves >>= 1;
   const size_t lds = off + LD.node_waves * node_bytes;
   if (lds > 160 * 1024 - 2048) return TG_E_RANGE;
-  TG_HIP_CHECK(hipFuncSetAttribute((const void*)tg_replay_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  auto kernel = T.queue_prefix ? tg_replay_kernel<true> : tg_replay_kernel<false>;
+  TG_HIP_CHECK(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   const size_t total = (size_t)T.S * T.A * T.K;
   hipLaunchKernelGGL(tg_trace_dur_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, T, W.dur);
-  hipLaunchKernelGGL(tg_replay_kernel, dim3(T.S), dim3(kThreads), lds, s, T, W, *out, LD, plan);
+  hipLaunchKernelGGL(kernel, dim3(T.S), dim3(kThreads), lds, s, T, W, *out, LD, plan);
   return hipGetLastError() == hipSuccess ? TG_OK : TG_E_HIP;
 }

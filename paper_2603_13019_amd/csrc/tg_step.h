@@ -602,6 +602,54 @@ __device__ static inline void tg_place_pool(const TgPoolLds& S, const TgPlaceIo&
   tg_wave_sync();
 }
 
+// Whole-queue prefix (Alg. 1 as printed): how many actions of a pool's list come before place
+// `lim` of the whole queue's visiting order.  The list ascends in that order (gkey: the places
+// under TG_ORDER_COST, else the action id is the place), so the count is found by bisection.
+__device__ static inline int tg_prefix_len(const int32_t* acts, int Nt, const uint64_t* gkey, uint64_t lim) {
+  int lo = 0, hi = Nt;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    const int id = acts[mid];
+    const uint64_t k = gkey ? gkey[id] : (uint64_t)id;
+    if (k < lim) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
+// The actions acts[n_adm .. Nt) lie behind the end of the admitted prefix: they wait (or can
+// never run), and those pinned to a node join its waiting list behind the ones tg_place_pool
+// has put there.
+__device__ static inline void tg_place_tail(const TgPoolLds& S, const TgPlaceIo& io, const int32_t* acts, int n_adm, int Nt,
+                                            int lane) {
+  for (int base = n_adm; base < Nt; base += TG_WAVE) {
+    const int cnt = min(TG_WAVE, Nt - base);
+    int id = 0, pr = -1, stat = 1;
+    if (lane < cnt) {
+      id = acts[base + lane];
+      stat = (int)io.act_static[id];
+      const int pin = io.act_pin[id];
+      if (pin >= 0 && !stat) pr = io.node_rank[pin];
+    }
+    int slot = 0;
+    for (uint64_t pinned = __ballot(pr >= 0); pinned; pinned &= pinned - 1) {   // one after the other: the lists keep the visiting order
+      const int l = __builtin_ctzll(pinned);
+      const int r = __builtin_amdgcn_readlane(pr, l);
+      const int s = S.dcnt[r];
+      if (lane == l) slot = s;
+      tg_wave_sync();
+      if (lane == 0) S.dcnt[r] = s + 1;
+      tg_wave_sync();
+    }
+    if (lane < cnt) {
+      io.out_node[id] = -1;
+      io.out_reason[id] = (uint8_t)(stat ? TG_DEFER_INFEASIBLE : TG_DEFER_PREFIX);
+      io.slot[id] = slot; io.out_units[id] = 0;
+      if (io.out_act) io.out_act[id] = -1;
+    }
+  }
+  tg_wave_sync();
+}
+
 // List extents per node after tg_place_pool: exclusive scan of the per-node counts in rank
 // order, starting at `a0` (the pool's first slot in the order arrays).
 __device__ static inline void tg_pool_extents(const TgPoolLds& S, const int32_t* nodes, int Mt, int a0, int32_t* nl_off,

@@ -229,7 +229,7 @@ class Trace:
         d = TraceDesc()
         for n in ("S", "A", "M", "K", "n_classes", "depth", "max_ticks"):
             setattr(d, n, int(t[n]))
-        d.flags = 0
+        d.flags = 1 if int(t.get("queue_prefix", 0)) else 0      # TG_TRACE_QUEUE_PREFIX
         d.tick_us = int(t["tick_us"])
         keep = []
         _fill(d, t, [f[0] for f in TraceDesc._fields_[9:-3]] + ["act_quota_mask"], keep)

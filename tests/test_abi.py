@@ -273,7 +273,7 @@ def _trace_rc(tg, t):
     d = tg.TraceDesc()
     for n in ("S", "A", "M", "K", "n_classes", "depth", "max_ticks"):
         setattr(d, n, int(t[n]))
-    d.flags = 0
+    d.flags = int(t.get("flags", 0))
     d.tick_us = int(t["tick_us"])
     keep = []
     tg._fill(d, t, [f[0] for f in tg.TraceDesc._fields_[9:-3]] + ["act_quota_mask"], keep)
@@ -289,6 +289,8 @@ BAD_TRACE = {
     "arrivals_not_sorted": (lambda t: t["arrival_us"].__setitem__(5, 0), -1),
     "gpu_node_not_8": (lambda t: t["node_cap"].__setitem__(int(np.flatnonzero(t["node_type"] == gen.TYPE_GPU)[0]), 4), -1),
     "tick_zero": (lambda t: t.__setitem__("tick_us", 0), -1),
+    "unknown_flag": (lambda t: t.__setitem__("flags", 2), -1),
+    "unknown_flag_next_to_a_known_one": (lambda t: t.__setitem__("flags", 5), -1),
     "tokens_above_bucket": (lambda t: t["quota_tok0_micro"].__setitem__(int(np.flatnonzero(t["node_type"] == gen.TYPE_API)[0]), 10**12), -1),
     "t_ori_range": (lambda t: t["act_t_ori_us"].__setitem__(0, 0), -2),
     "class_out_of_range": (lambda t: (t["act_model"].__setitem__(0, 2), t["act_param"].__setitem__(0, 99), t["act_type"].__setitem__(0, 1)), -3),

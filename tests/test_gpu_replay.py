@@ -63,7 +63,8 @@ def test_replay_small(tg, orc, name):
 
 
 def test_replay_random_sweep(tg, orc):
-    """60 small traces with cluster shape, load, tick limit, pins and depth drawn at random."""
+    """60 small traces with cluster shape, load, tick limit, pins, depth, further quotas, services and the prefix rule
+    drawn at random."""
     for seed in range(500, 560):
         rng = np.random.default_rng(seed)
         n_cpu, n_gpu, n_api = int(rng.integers(0, 6)), int(rng.integers(0, 4)), int(rng.integers(0, 4))
@@ -80,6 +81,7 @@ def test_replay_random_sweep(tg, orc):
             gen.with_extra_quotas(t, frac=float(rng.random()), seed=seed, max_extra=int(rng.integers(1, 4)))
         if n_gpu and rng.random() < 0.6:
             _with_services(t, seed, n_services=int(rng.choice([1, 4, 20])), slots=int(rng.choice([1, 2, 5])))
+        t["queue_prefix"] = int(rng.random() < 0.3)                # one prefix of the whole queue per step
         _compare(_replay_gpu(tg, t), orc.replay(t), range(t["S"]), t["A"])
     print("60 traces compared", flush=True)
 
@@ -187,3 +189,38 @@ def test_replay_several_quotas(tg, orc, seed):
     if seed % 3 == 2:                                          # the heavily loaded cases: the masks delay somebody
         assert (want["start_us"] != orc.replay(dict(t, act_quota_mask=None))["start_us"]).any()
     _compare(_replay_gpu(tg, t), want, range(t["S"]), t["A"])
+
+
+@pytest.mark.parametrize("name", [n for n in CASES if n not in ("single_action", "api_only")])
+def test_replay_queue_prefix_small(tg, orc, name):
+    """Every step admits one prefix of the whole waiting queue (Alg. 1 as printed)."""
+    print("case", name, flush=True)
+    t = dict(gen.make_trace(**CASES[name]), queue_prefix=1)
+    want = orc.replay(t)
+    _compare(_replay_gpu(tg, t), want, range(t["S"]), t["A"])
+    if name.startswith("contended"):
+        assert (orc.replay(dict(t, queue_prefix=0))["start_us"] != want["start_us"]).any(), "the rule should bind here"
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_replay_queue_prefix_with_quotas_and_services(tg, orc, seed):
+    t = gen.make_trace(S=3, A=500, seed=700 + seed, cluster=(2, 16, 2, 3), rate_per_s=120.0, horizon_s=4.0, max_ticks=30000,
+                       pin_frac=(0.0, 0.3, 0.8)[seed % 3])
+    t["depth"] = 1 + seed % 3
+    if seed % 2:
+        gen.with_extra_quotas(t, frac=0.5, seed=seed)
+    if seed % 3:
+        _with_services(t, seed, n_services=4, slots=2)
+    t["queue_prefix"] = 1
+    _compare(_replay_gpu(tg, t), orc.replay(t), range(3), 500)
+
+
+def test_replay_queue_prefix_config5_contended_sampled(tg, orc):
+    """Workload 5's contended shape, 64 scenarios on the GPU, 3 of them against the oracle."""
+    t = dict(gen.make_trace(S=64, A=10_000, seed=5, contended=True, max_ticks=200_000), queue_prefix=1)
+    got = _replay_gpu(tg, t)
+    sample = (0, 31, 63)
+    want = orc.replay(t, 0, 1)
+    _compare(got, want, (0,), 10_000)
+    for s in sample[1:]:
+        _compare(got, orc.replay(t, s, s + 1), (s,), 10_000)
