@@ -556,3 +556,12 @@ def test_assign_queue_prefix_config2_full(tg, orc):
     assert want["summary"]["n_assigned"].sum() < per_pool["summary"]["n_assigned"].sum()
     p["order_policy"] = 1
     _compare(_assign_gpu(tg, p), orc.assign(p), "config 2, cost order")
+
+
+def test_assign_queue_prefix_keeps_the_head(tg, orc):
+    """The eviction loop never drops a node's first candidate, even where an empty selection would score better."""
+    from test_oracle_queue_prefix import head_problem
+    p, cpu = head_problem()
+    want = orc.assign(p)
+    assert want["reason"][0] == 0 and want["units"][0] == 8
+    _compare(_assign_gpu(tg, p), want, "head kept")

@@ -245,6 +245,27 @@ def test_dp_chunks_is_optimal(orc, seed):
     assert sum(dict(opts[i])[int(ks[i])] for i in range(m)) == v
 
 
+def test_dp_chunks_tie_rules(orc):
+    """Equal totals: the end state with the smallest code (fewest large chunks left) wins, and on the way to a
+    state the smaller source state, then the smaller option.  Hand-worked on tiny cases."""
+    INF = pyref.INF
+    k_list = [1, 2, 4, 8]
+    # one action, every option costs 5, one free chunk of 8: the end states are (1,1,1,0), (0,1,1,0), (0,0,1,0)
+    # and (0,0,0,0); the last has the smallest code, so the action gets all 8 GPUs
+    v, ks = orc.dp_chunks(np.array([[5, 5, 5, 5]], np.int64), k_list, (0, 0, 0, 1))
+    assert (v, list(ks)) == (5, [8])
+    # a free chunk of 2 and one of 4, two actions that may take 2 or 4 GPUs at 10 each: [2,4] and [4,2] both end
+    # in the empty state (code 0, the smallest; [2,2] leaves a chunk of 2).  Bounds (1,1,1,1): after [2] the state is
+    # (0,0,1,0) = code 4, after [4] it is (0,1,0,0) = code 2 - the smaller source state wins: [4,2]
+    dur = np.array([[INF, 10, 10, INF], [INF, 10, 10, INF]], np.int64)
+    v, ks = orc.dp_chunks(dur, k_list, (0, 1, 1, 0))
+    assert (v, list(ks)) == (20, [4, 2])
+    # same source state, two options with the same total and the same end state cannot happen (an option fixes the
+    # end state), so the option only decides between end states: cheaper total first, then the smaller code
+    v, ks = orc.dp_chunks(np.array([[7, 5, 5, 9]], np.int64), k_list, (0, 0, 0, 1))
+    assert (v, list(ks)) == (5, [4])
+
+
 # ---------------------------------------------------------------- Alg. 2 estimate
 def test_estimate_single_machine_sum_of_completion_times(orc):
     T = [5, 3, 9, 1, 7]

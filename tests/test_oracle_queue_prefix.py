@@ -180,3 +180,42 @@ def test_nobody_is_admitted_behind_a_waiting_action(orc, seed):
             n = _first_blocked(r)
             assert not np.isin(r[n:], (0, 2)).any()
             assert not (r[:n] == 1).any()
+
+
+def head_problem():
+    """One node with 8 free cores; the head scales badly (10 s on one core, 9.9 s on eight); behind it an API action
+    finds no token, which ends the whole-queue prefix, so seven one-second actions pinned to the node wait."""
+    p = gen.make_random_problem(5, B=1, N=9, n_cpu=1, n_gpu=0, n_api=1, bad_frac=0.0, pin_frac=0.0, busy=False, k_list=(1, 2, 4, 8))
+    p["type_k"][gen.TYPE_GPU] = 0
+    cpu = int(np.flatnonzero(p["node_type"] == gen.TYPE_CPU)[0])
+    api = int(np.flatnonzero(p["node_type"] == gen.TYPE_API)[0])
+    p["node_cap"][cpu] = p["node_free"][cpu] = 8
+    p["node_cap"][api], p["node_free"][api] = 4, 0
+    p["node_backlog_us"][:] = 0
+    p["act_age_us"][:] = 0
+    p["act_type"][:] = gen.TYPE_CPU
+    p["act_type"][1] = gen.TYPE_API
+    p["act_pin_node"][:] = cpu
+    p["act_pin_node"][1] = api
+    p["act_model"][:] = 0
+    p["act_kmask"][:] = 1
+    p["act_t_ori_us"][:] = 1_000_000
+    p["act_model"][0], p["act_kmask"][0], p["act_t_ori_us"][0] = 1, 0b1111, 10_000_000
+    p["act_param"][0] = 11_429                                  # parallel fraction in ppm: 10 s -> 9.9 s on eight cores
+    p["queue_prefix"], p["depth"] = 1, 2
+    return p, cpu
+
+
+def test_the_head_of_a_node_is_never_evicted(orc):
+    """Alg. 1's eviction loop stops at one candidate even where keeping nobody would look better (every step must make
+    progress).  DPArrange gives the head all eight cores: 9.9 + 7 * 10.9 = 86.2 s with the seven waiting behind it.
+    Keeping nobody would estimate the head on one core next to the seven, 10 + 7 * 1 = 17 s - less, and still the head
+    stays."""
+    p, cpu = head_problem()
+    d8 = orc.duration(1, 10_000_000, 11_429, 8)
+    assert 9_899_000 < d8 < 9_901_000
+    o = orc.assign(p)
+    assert list(o["reason"]) == [0] + [1] * 8
+    assert o["units"][0] == 8 and o["act_us"][0] == d8
+    assert o["node_obj"][cpu] == d8 + 7 * (d8 + 1_000_000)
+    assert 10_000_000 + 7 * 1_000_000 < o["node_obj"][cpu]

@@ -41,6 +41,18 @@ def test_hand_worked_case(orc):
     assert int(o["summary"]["n_assigned"][0]) == 3
 
 
+def test_only_the_first_64_quotas_can_be_named(orc):
+    """70 quotas: a mask has 64 bits, so quotas of rank 64 and above can be pinned to but not named.  Quota 64 is
+    empty; an action pinned to quota 1 that names quota 0 does not care, one pinned to quota 64 waits."""
+    tokens = [2] * 70
+    tokens[0], tokens[64] = 3, 0
+    p = _api_problem(70, tokens, pins=[1, 64, 69, 1], extras=[[0], [], [0, 63], [0]])
+    o = orc.assign(p)
+    assert list(o["reason"]) == [0, 1, 0, 0]
+    assert o["node_used"][0] == 3 and o["node_used"][1] == 2 and o["node_used"][63] == 1 and o["node_used"][69] == 1
+    assert o["node_used"][64] == 0
+
+
 def test_no_extras_is_the_plain_problem(orc):
     p = gen.make_random_problem(40, B=2, N=120, n_cpu=1, n_gpu=1, n_api=4)
     a = orc.assign(p)

@@ -51,6 +51,8 @@ def test_uncontended_closed_form(orc):
             assert o["units"][gidx] == k                              # room for everyone: largest allowed option
             assert o["finish_us"][gidx] == start + _dur(t, gidx, k)
         _stats(t, o, s)
+        last = int(o["start_us"][s * t["A"]:(s + 1) * t["A"]].max())
+        assert o["n_ticks"][s] == last // tick + 1                   # the replay ends with the tick of the last start
 
 
 def test_uncontended_gpu_one_at_a_time(orc):
@@ -138,3 +140,19 @@ def test_contended_conservation(orc, seed):
                     else:
                         b.free(where[i], int(un[i]))
         _stats(t, o, s)
+
+
+def test_tick_limit_ends_the_replay(orc):
+    """A single core and ten-second actions arriving together: one start per 100 ticks; with `max_ticks` = 250 the replay
+    stops after exactly that many ticks with three actions started (ticks 0, 100, 200), the others never start."""
+    t = gen.make_trace(S=1, A=6, seed=15, cluster=(1, 1, 0, 0), type_probs=(1, 0, 0), pin_frac=0.0, max_ticks=250)
+    t["arrival_us"][:] = 0
+    t["act_model"][:] = 0
+    t["act_kmask"][:] = 1
+    t["act_t_ori_us"][:] = 10_000_000
+    o = orc.replay(t)
+    assert list(o["start_us"]) == [0, 10_000_000, 20_000_000, -1, -1, -1]
+    assert o["n_started"][0] == 3 and o["n_ticks"][0] == 250
+    o = orc.replay(dict(t, max_ticks=10_000))
+    assert list(o["start_us"]) == [i * 10_000_000 for i in range(6)]
+    assert o["n_ticks"][0] == 501                                    # ticks 0..500

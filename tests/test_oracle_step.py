@@ -225,3 +225,29 @@ def test_golden_config1(orc):
     assert [int(x) for x in o["units"]] == want["units"]
     assert [int(x) for x in o["act_us"]] == want["act_us"]
     assert int(orc.score(gen.make_config(1)).astype(np.uint64).sum()) == want["score_sum_mod64"]
+
+
+def test_gpu_node_without_chunk_counts_is_the_binary_split_of_its_free_gpus(orc):
+    """`node_chunks` absent: a GPU node with f free GPUs holds one free chunk per set bit of f (8 free = one chunk of
+    8).  Must equal the same problem with those counts written out, and a fully free node takes one 8-GPU action,
+    not two."""
+    p = gen.make_random_problem(31, B=1, N=6, n_cpu=0, n_gpu=1, n_api=0, bad_frac=0.0, pin_frac=0.0, busy=False)
+    p["act_type"][:] = gen.TYPE_GPU
+    p["act_model"][:] = 0
+    p["node_cap"][:] = 8
+    p["node_backlog_us"][:] = 0
+    p["node_busy_off"], p["node_busy_rel_us"] = None, None
+    for free in range(9):
+        p["node_free"][:] = free
+        explicit = np.array([free & 1, free >> 1 & 1, free >> 2 & 1, free >> 3 & 1], np.uint8)
+        for need in ([8, 8, 1, 1, 1, 1], [4, 4, 4, 1, 1, 1], [1, 2, 4, 8, 1, 1], [2, 2, 2, 2, 2, 2]):
+            p["act_kmask"][:] = [{1: 1, 2: 2, 4: 4, 8: 8}[k] for k in need]
+            a = orc.assign(dict(p, node_chunks=None))
+            b = orc.assign(dict(p, node_chunks=explicit))
+            for k in ("node", "units", "reason", "act_us"):
+                np.testing.assert_array_equal(a[k], b[k], err_msg=f"free {free} need {need} {k}")
+            # units handed out never exceed what is free, and the admitted prefix is the longest that fits in order
+            assert a["units"].sum() <= free
+        if free == 8:
+            p["act_kmask"][:] = 8
+            assert list(orc.assign(dict(p, node_chunks=None))["reason"]) == [0, 1, 1, 1, 1, 1]
