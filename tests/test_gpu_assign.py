@@ -565,3 +565,39 @@ def test_assign_queue_prefix_keeps_the_head(tg, orc):
     want = orc.assign(p)
     assert want["reason"][0] == 0 and want["units"][0] == 8
     _compare(_assign_gpu(tg, p), want, "head kept")
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_assign_flat_elasticity_ties_everywhere(tg, orc, seed):
+    """Every elastic action follows a table that gains nothing from more units (E(k) k = 1): all options of an action
+    take the same time, so every comparison inside DPArrange is a tie - on CPU nodes fewer units win, on GPU nodes the
+    smaller source state, the smaller option and the smallest end state."""
+    print("case", seed, flush=True)
+    p = gen.make_random_problem(1500 + seed, B=3, N=100 + 30 * seed, n_cpu=1 + seed % 3, n_gpu=1 + seed % 2, n_api=0,
+                                depth=1 + seed % 3, busy=seed % 2 == 0, cpu_cap_hi=32, pin_frac=(0.0, 0.4)[seed % 2])
+    p["speedup_q16"][:] = 65536
+    el = p["act_model"] != 0
+    p["act_model"][el] = 2
+    p["act_param"][el] = np.arange(el.sum()) % p["n_classes"]
+    if seed % 4 == 3:                                          # and one duration for everybody: ties between actions too
+        p["act_t_ori_us"][:] = 700_000
+    want = orc.assign(p)
+    assert (want["reason"] == 0).any()
+    _compare(_assign_gpu(tg, p), want, f"flat {seed}")
+
+
+def test_assign_gpu_nodes_without_chunk_counts(tg, orc):
+    """`node_chunks` absent: a GPU node with f free GPUs holds one free chunk per set bit of f.  Nine snapshots with
+    0..8 free GPUs on their only node, and requests that fit, split or overflow it."""
+    for need in ([8, 8, 1, 1, 1, 1], [4, 4, 4, 1, 1, 1], [1, 2, 4, 8, 1, 1], [2, 2, 2, 2, 2, 2]):
+        p = gen.make_random_problem(31, B=9, N=6, n_cpu=0, n_gpu=1, n_api=0, bad_frac=0.0, pin_frac=0.0, busy=False)
+        p["act_type"][:] = gen.TYPE_GPU
+        p["act_model"][:] = 0
+        p["node_cap"][:] = 8
+        p["node_free"][:] = np.arange(9)
+        p["node_busy_off"], p["node_busy_rel_us"] = None, None
+        p["node_chunks"] = None
+        p["act_kmask"][:] = np.tile([{1: 1, 2: 2, 4: 4, 8: 8}[k] for k in need], 9)
+        want = orc.assign(p)
+        _compare(_assign_gpu(tg, p), want, f"need {need}")
+        assert (want["units"].reshape(9, 6).sum(axis=1) <= np.arange(9)).all()
