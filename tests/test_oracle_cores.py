@@ -50,6 +50,15 @@ def test_spill_takes_the_largest_domains_first():
     assert got == [0, 1, 4, 5, 6, 7, 8] and list(np.flatnonzero(after)) == [9, 10]
 
 
+def test_spill_takes_the_lower_of_two_equally_free_domains_first():
+    free = np.ones(8, np.uint8)                       # two domains of 4, all free; 6 cores do not fit in one
+    got, after = orc.take_cores(free, 4, 6)
+    assert got == [0, 1, 2, 3, 4, 5] and list(np.flatnonzero(after)) == [6, 7]
+    free = np.array([0, 1, 1, 1,  1, 1, 1, 0,  1, 1, 1, 1], np.uint8)   # 3, 3 and 4 free: the 4 first, then the lower 3
+    got, after = orc.take_cores(free, 4, 6)
+    assert got == [1, 2, 8, 9, 10, 11] and list(np.flatnonzero(after)) == [3, 4, 5, 6]
+
+
 @pytest.mark.parametrize("seed", range(40))
 def test_single_allocation_against_exhaustive_search(seed):
     rng = np.random.default_rng(seed)

@@ -156,3 +156,57 @@ def test_tick_limit_ends_the_replay(orc):
     o = orc.replay(dict(t, max_ticks=10_000))
     assert list(o["start_us"]) == [i * 10_000_000 for i in range(6)]
     assert o["n_ticks"][0] == 501                                    # ticks 0..500
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_every_tick_is_one_step_on_the_snapshot_rebuilt_from_the_replays_own_times(orc, seed):
+    """The tick loop around the step: at every tick the cluster state (free cores, release time of every core in use,
+    whole tokens, who waits) is rebuilt here from the start / finish times, units and nodes the replay reported, and one
+    scheduling step on that snapshot (pinned on its own elsewhere) must select exactly the actions the replay started at
+    that tick, on the same nodes with the same units.  CPU nodes and quotas (GPU nodes would need their addresses)."""
+    A = 260
+    t = gen.make_trace(S=1, A=A, seed=120 + seed, cluster=(2 + seed % 2, 8 + 4 * (seed % 3), 0, 2), type_probs=(0.8, 0, 0.2),
+                       rate_per_s=70.0, horizon_s=A / 70.0, max_ticks=50_000, pin_frac=(0.0, 0.3)[seed % 2], cpu_median=700_000)
+    t["depth"] = 1 + seed % 3
+    api = np.flatnonzero(t["node_type"] == gen.TYPE_API)
+    t["quota_rate"][api] = 3 + seed
+    o = orc.replay(t)
+    M, tick = t["M"], int(t["tick_us"])
+    start, fin, units, node = o["start_us"], o["finish_us"], o["units"], o["node"]
+    arr = t["arrival_us"]
+    assert (start >= 0).all()
+    tok = t["quota_tok0_micro"].astype(np.int64).copy()
+    evicted_somewhere = waited_somewhere = False
+    for n in range(int(o["n_ticks"][0])):
+        now = n * tick
+        if n > 0:
+            tok[api] = np.minimum(t["node_cap"][api].astype(np.int64) * 10**6, tok[api] + t["quota_rate"][api].astype(np.int64) * tick)
+        waiting = np.flatnonzero((arr <= now) & (start >= now))
+        if len(waiting):
+            running = np.flatnonzero((start < now) & (fin > now) & (t["act_type"] == gen.TYPE_CPU))
+            free = t["node_cap"].astype(np.int32).copy()
+            busy = [[] for _ in range(M)]
+            for i in running:
+                free[node[i]] -= units[i]
+                busy[node[i]] += [int(fin[i]) - now] * int(units[i])
+            free[api] = (tok[api] // 10**6).astype(np.int32)
+            p = dict(B=1, N=len(waiting), M=M, K=t["K"], n_classes=t["n_classes"], n_tasks=1, depth=t["depth"],
+                     k_list=t["k_list"], type_k=t["type_k"], speedup_q16=t["speedup_q16"],
+                     node_type=t["node_type"], node_cap=t["node_cap"], node_free=free, node_backlog_us=np.zeros(M, np.int64),
+                     node_chunks=None, node_busy_off=np.concatenate([[0], np.cumsum([len(b) for b in busy])]).astype(np.int32),
+                     node_busy_rel_us=np.array([x for b in busy for x in b] or [0], np.int64),
+                     act_age_us=(now - arr[waiting]).astype(np.int64), act_task=None,
+                     **{k: t[k][waiting] for k in ("act_type", "act_model", "act_t_ori_us", "act_kmask", "act_param", "act_pin_node")})
+            s = orc.assign(p)
+            go = start[waiting] == now
+            np.testing.assert_array_equal(s["reason"] == 0, go, err_msg=f"tick {n}")
+            np.testing.assert_array_equal(s["node"][go], node[waiting][go], err_msg=f"tick {n}")
+            np.testing.assert_array_equal(s["units"][go], units[waiting][go], err_msg=f"tick {n}")
+            np.testing.assert_array_equal(s["act_us"][go], (fin - arr)[waiting][go], err_msg=f"tick {n}")
+            evicted_somewhere |= bool((s["reason"] == 2).any())
+            waited_somewhere |= bool((s["reason"] == 1).any())
+        for i in np.flatnonzero((start == now) & (t["act_type"] == gen.TYPE_API)):
+            tok[node[i]] -= 10**6
+    assert waited_somewhere
+    if seed % 3:
+        assert evicted_somewhere
