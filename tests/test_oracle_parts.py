@@ -148,6 +148,11 @@ def test_dp_units_ties_prefer_fewer_units(orc):
     dur = np.array([[10, 10, 10], [10, 10, 5]], np.int64)
     v, ks = orc.dp_units(dur, k_list, 8)
     assert v == 15 and list(ks) == [1, 4]
+    # three units for two tasks that take 10 on one unit and 7 on two: [2,1] and [1,2] both total 17 on all three
+    # units; the strict comparison with the options in ascending order keeps the smaller option of the later task
+    dur = np.array([[10, 7, pyref.INF], [10, 7, pyref.INF]], np.int64)
+    v, ks = orc.dp_units(dur, k_list, 3)
+    assert v == 17 and list(ks) == [2, 1]
 
 
 @pytest.mark.parametrize("seed", range(6))
