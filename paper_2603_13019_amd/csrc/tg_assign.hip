@@ -4,6 +4,8 @@
 //   tg_order_kernel    only for the second visiting order: keys + sort of every pool's queue
 //   tg_place_kernel    Alg. 1's prefix admission at minimum units, node choice by least
 //                      estimated completion time (Eq. 2)            one wavefront per (snapshot, kind)
+//   tg_stop_kernel     only for the whole-queue prefix: where the admission of a snapshot ends, between two
+//                      passes of tg_place_kernel
 //   tg_lists_kernel    groups admitted / waiting-pinned actions by node, FCFS inside a node
 //   tg_node_kernel     the rest of Alg. 1 per node: DPArrange (Alg. 3 / Alg. 4) + greedy tail
 //                      eviction on the approximated objective (Alg. 2)   one wavefront per node
@@ -665,8 +667,7 @@ extern "C" int tg_assign(const tg_problem* p, const int64_t* d_cost, const tg_as
     const int width = place_cost || mk > 16 * TG_WAVE ? 0 : mk <= TG_WAVE ? 1 : mk <= 4 * TG_WAVE ? 4 : 16;
     using PlaceKernel = void (*)(TgDev, const int64_t*, const int64_t*, const TgBlock*, AssignWs, tg_assign_out, int, const int32_t*,
                                  const uint64_t*, const uint64_t*);
-    PlaceKernel k = p->queue_prefix ? tg_place_kernel<0, 0, true, true>
-                  : width == 0 ? tg_place_kernel<0, 0, true, false>
+    PlaceKernel k = width == 0 ? tg_place_kernel<0, 0, true, false>
                   : width == 1 ? (ext ? tg_place_kernel<1, 1, false, false> : tg_place_kernel<1, 0, false, false>)
                   : width == 4 ? (ext ? tg_place_kernel<4, 4, false, false> : tg_place_kernel<4, 0, false, false>)
                                : (ext ? tg_place_kernel<16, 16, false, false> : tg_place_kernel<16, 0, false, false>);
@@ -678,8 +679,11 @@ extern "C" int tg_assign(const tg_problem* p, const int64_t* d_cost, const tg_as
       // one prefix of the whole queue: the pass above (one prefix per pool) finds where it ends, a
       // second pass admits the actions before that place and leaves the others waiting
       const uint64_t* gkey = visit ? W.gkey : nullptr;
+      PlaceKernel k2 = tg_place_kernel<0, 0, true, true>;
+      if (place_lds > 64 * 1024)
+        TG_HIP_CHECK(hipFuncSetAttribute((const void*)k2, hipFuncAttributeMaxDynamicSharedMemorySize, (int)place_lds));
       hipLaunchKernelGGL(tg_stop_kernel, dim3(P.B), dim3(256), 0, s, P, *out, gkey, W.stop);
-      hipLaunchKernelGGL(k, dim3(P.B * 3), dim3(TG_WAVE), place_lds, s, P, W.dur, place_cost, p->d_blocks, W, *out,
+      hipLaunchKernelGGL(k2, dim3(P.B * 3), dim3(TG_WAVE), place_lds, s, P, W.dur, place_cost, p->d_blocks, W, *out,
                          p->max_nodes_of_kind, visit, gkey, W.stop);
     }
   }
