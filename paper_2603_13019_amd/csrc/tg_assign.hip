@@ -376,9 +376,11 @@ __global__ __launch_bounds__(TG_WAVE) void tg_node_kernel(TgDev P, const int64_t
       in.nd = __builtin_amdgcn_readlane(my_nd, j); in.dlist = W.dorder + abase + __builtin_amdgcn_readlane(my_doff, j);
       in.n_busy = __builtin_amdgcn_readlane(my_nbusy, j);
       in.busy = P.node_busy_rel + __builtin_amdgcn_readlane(my_boff, j);
+      const bool single = in.m == 1 && in.nd == 0;                // one candidate, nobody waiting: no table, no heap
       // the release times are read by every objective evaluation: keep them behind the plan's block
       tg_wave_sync();                                             // the previous node's readers are done
-      for (int c = lane; c < in.n_busy; c += TG_WAVE) reinterpret_cast<int64_t*>(smem + plan.total)[c] = in.busy[c];
+      if (!single)
+        for (int c = lane; c < in.n_busy; c += TG_WAVE) reinterpret_cast<int64_t*>(smem + plan.total)[c] = in.busy[c];
       in.busy_lds_off = plan.total;
       in.act_model = P.act_model + abase; in.act_kmask = P.act_kmask + abase; in.dur = dur + abase * P.K;
       in.K = P.K; in.depth = P.depth;
@@ -389,7 +391,7 @@ __global__ __launch_bounds__(TG_WAVE) void tg_node_kernel(TgDev P, const int64_t
       out.node = O.node + abase; out.units = O.units + abase; out.act = O.act_us + abase; out.reason = O.defer_reason + abase;
       out.age = P.act_age + abase;
       int used = 0;
-      const int64_t obj = tg_node_schedule<1>(smem, plan, in, out, lane, 0, &used);
+      const int64_t obj = single ? tg_node_single(in, out, lane, &used) : tg_node_schedule<1>(smem, plan, in, out, lane, 0, &used);
       if (lane == 0) {
         if (O.node_obj) O.node_obj[gn] = obj;
         if (O.node_used) O.node_used[gn] = used;

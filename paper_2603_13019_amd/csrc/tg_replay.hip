@@ -370,8 +370,9 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
       const int j = jb + jl;
       const int m = __builtin_amdgcn_readlane(my_m, jl);
       const int ty = T.node_type[nbase + j];
+      const bool single = m == 1 && dl_cnt[j] == 0;               // one candidate, nobody waiting: no table, no heap
       int nb = 0;
-      if (ty != TG_TYPE_API) {
+      if (ty != TG_TYPE_API && !single) {
         const int n = s_nrun;
         for (int base = 0; base < n; base += TG_WAVE) {
           const int x = base + lane;
@@ -398,7 +399,8 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
       TgNodeOut out;
       out.node = o_node; out.units = o_units; out.act = nullptr; out.reason = reason; out.age = nullptr;
       int used_units;
-      tg_node_schedule<1>(node_mem, plan, in, out, lane, 0, &used_units);
+      if (single) tg_node_single(in, out, lane, &used_units);
+      else tg_node_schedule<1>(node_mem, plan, in, out, lane, 0, &used_units);
      }
     }
     __threadfence_block();

@@ -1148,6 +1148,46 @@ __device__ static inline void tg_dp_units32(uint32_t* prev, uint32_t* cur, const
   }
 }
 
+// A node with one candidate and nobody waiting for it needs no table and no heap: DPArrange over
+// one action is its fastest allowed option that fits (equal durations: fewer units on counted
+// resources; on GPU nodes the option that leaves the smaller chunk state, as the chunk DP ends in
+// the smallest state among the best), the eviction loop has nothing to evict and the estimate of
+// an empty queue is 0.  Same results as tg_node_schedule, lane q looks at option q.
+__device__ static inline int64_t tg_node_single(const TgNodeIn& in, const TgNodeOut& out, int lane, int* used_units) {
+  const int K = in.K;
+  const int id = in.clist[0];
+  const uint32_t mask = in.act_kmask[id];
+  const bool elastic = in.act_model[id] != TG_MODEL_NONE;
+  const int64_t delay = tg_restore_delay(in, id);
+  const int my_k = (int)(in.kword >> (8 * (lane & (TG_MAX_K - 1))) & 0xff);
+  uint64_t key = ~0ull;
+  if (lane < K && (mask >> lane & 1u) && (elastic || lane == __builtin_ctz(mask))) {
+    const int64_t d = in.dur[(size_t)id * K + lane];
+    if (!elastic) key = (uint64_t)(d + delay) << 12;              // runs on its minimum units (Alg. 1)
+    else if (d != TG_INF && my_k <= in.cap) {
+      if (in.type == TG_TYPE_GPU) {
+        if (my_k <= tg_chunk_largest(in.chunks)) {
+          const int r0 = max((int)(in.chunks & 0xff), 1) + 1, r1 = max((int)(in.chunks >> 8 & 0xff), 1) + 1,
+                    r2 = max((int)(in.chunks >> 16 & 0xff), 1) + 1;
+          const uint32_t c = tg_chunk_take(in.chunks, my_k);
+          const int code = (int)(c & 0xff) + r0 * ((int)(c >> 8 & 0xff) + r1 * ((int)(c >> 16 & 0xff) + r2 * (int)(c >> 24)));
+          key = (uint64_t)(d + delay) << 12 | (uint32_t)code;
+        }
+      } else if (my_k <= in.free_units) key = (uint64_t)(d + delay) << 12 | (uint32_t)my_k;
+    }
+  }
+  const uint64_t best = tg_wave_min_u64(key);                       // admission has made sure that the minimum units fit
+  const int q = __builtin_ctzll(__ballot(key == best));
+  const int k = (int)(in.kword >> (8 * q) & 0xff);
+  const int64_t d = (int64_t)(best >> 12);
+  if (lane == 0) {
+    out.units[id] = k;
+    if (out.act) out.act[id] = (out.age ? out.age[id] : 0) + in.backlog + d;
+  }
+  *used_units = k;
+  return elastic ? d + in.backlog : -1;
+}
+
 // One node, scheduled by a team of NW wavefronts (NW = 1: a single wavefront, no workgroup
 // barrier anywhere).  Wavefront 0 fills the DPArrange table for all prefixes; the objective of
 // NW consecutive prefix lengths is then evaluated in parallel, one per wavefront, and the
