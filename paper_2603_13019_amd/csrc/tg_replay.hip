@@ -476,9 +476,9 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
       live_free[j] = (int)mk;
       if (T.act_service) { W.live_res[nbase + j] = res; W.use_seq[nbase + j] = seq; }
     }
-    for (int j = tid; j < M; j += kThreads) { nl_cnt[j] = 0; dl_cnt[j] = 0; }
     __threadfence_block();
-    __syncthreads();
+    __syncthreads();                                              // the GPU nodes' lists have been read
+    for (int j = tid; j < M; j += kThreads) { nl_cnt[j] = 0; dl_cnt[j] = 0; }
     // waiting lists keep the actions that did not start, in order
     for (int ty = 0; ty < 3; ++ty) {
       const int n = compact_stable(wl[ty], wcs[ty], [&](int id) { return o_node[id] < 0; }, s_wave_cnt);

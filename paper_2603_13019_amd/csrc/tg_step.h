@@ -690,13 +690,16 @@ struct TgNodeLdsPlan {
   int sel_rows;     // prefix lengths backtracked per batch (<= 64)
   int off_F;        // objectives of one round of evaluations + flags
   int off_q0;       // minimum-unit option of every candidate
+  int cand_rows;    // candidates the per-candidate tables hold.  Nodes whose actions are elastic never have more (a
+                    // candidate takes at least one of the node's free units); a quota may, its actions are never elastic
   int heap_slots;   // heap entries per wavefront of the team
   int off_wd, off_wu, wait_slots;   // minimum-unit duration and unit count of the first waiting actions pinned to the node
   int total;        // bytes per wavefront
 };
 
-// LDS layout of one wavefront for nodes with at most `m_cap` candidates (m never exceeds the
-// node's free units either).
+// LDS layout of one wavefront for CPU and GPU nodes with at most `m_cap` candidates (m never
+// exceeds the node's free units either).  Quotas can hold more candidates than that: their
+// actions are not elastic, so they need none of the tables.
 __host__ static inline TgNodeLdsPlan tg_node_lds_plan(int max_free_cpu, int max_free_gpu, int max_states, int max_heap, int K,
                                                       int m_cap = 1 << 30, int sel_rows = TG_WAVE, int n_waves = 1,
                                                       int wait_slots = TG_WAVE) {
@@ -708,6 +711,7 @@ __host__ static inline TgNodeLdsPlan tg_node_lds_plan(int max_free_cpu, int max_
   if ((size_t)m_gpu * max_states * 2 > choice) choice = (size_t)m_gpu * max_states * 2;
   size_t off = 0;
   auto take = [&](size_t b) { const size_t r = off; off += (b + 15) & ~size_t(15); return (int)r; };
+  p.cand_rows = mmax;
   p.off_cdur = take((size_t)mmax * K * 8);
   const size_t dp64 = (size_t)width * 2 * 8, dp32 = (size_t)(width + 2 + TG_WAVE) * 2 * 4;   // 32-bit rows carry sentinels
   size_t dp = dp64 > dp32 ? dp64 : dp32;
@@ -1239,7 +1243,7 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
           int64_t d = row[q];
           if (k_of(q) > in.cap) d = TG_INF;
           else if (d != TG_INF) d += delay;
-          s_cdur[x * K + q] = d;
+          if (x < plan.cand_rows) s_cdur[x * K + q] = d;            // a quota with more candidates: nothing elastic, rows unused
         }
     }
     const int any_el = __any(el);

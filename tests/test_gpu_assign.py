@@ -601,3 +601,18 @@ def test_assign_gpu_nodes_without_chunk_counts(tg, orc):
         want = orc.assign(p)
         _compare(_assign_gpu(tg, p), want, f"need {need}")
         assert (want["units"].reshape(9, 6).sum(axis=1) <= np.arange(9)).all()
+
+
+def test_assign_quota_with_more_candidates_than_any_node_has_units(tg, orc):
+    """A quota with hundreds of tokens next to CPU nodes of 4 cores: the quota's candidate list is far longer than the
+    per-node tables (sized for the units of CPU and GPU nodes) - it needs none of them, its actions are not elastic."""
+    p = gen.make_random_problem(1600, B=3, N=500, n_cpu=2, n_gpu=1, n_api=1, cpu_cap_hi=4, bad_frac=0.0, pin_frac=0.2,
+                                type_probs=(0.15, 0.05, 0.8))
+    api = p["node_type"] == gen.TYPE_API
+    p["node_cap"][api] = 450
+    p["node_free"][api] = 420
+    want = orc.assign(p)
+    N, M = p["N"], p["M"]
+    per_quota = np.bincount(want["node"][(want["reason"] == 0)] + 0, minlength=M)
+    assert want["node_used"][api].max() > 300
+    _compare(_assign_gpu(tg, p), want, "long quota list")

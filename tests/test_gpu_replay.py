@@ -224,3 +224,31 @@ def test_replay_queue_prefix_config5_contended_sampled(tg, orc):
     _compare(got, want, (0,), 10_000)
     for s in sample[1:]:
         _compare(got, orc.replay(t, s, s + 1), (s,), 10_000)
+
+
+def test_replay_quota_with_more_candidates_than_any_node_has_units(tg, orc):
+    """A quota can admit far more actions in one step than a CPU or GPU node has units (its actions are never elastic, so
+    the per-node tables of the scheduler, sized for the nodes' units, are not used for it): 300 API actions arrive
+    together on a cluster whose only other node has 4 cores."""
+    t = gen.make_trace(S=3, A=320, seed=71, cluster=(1, 4, 0, 1), type_probs=(0.06, 0, 0.94), rate_per_s=50.0, horizon_s=6.4,
+                       max_ticks=20000, pin_frac=0.5)
+    t["arrival_us"][:] = np.tile(np.sort(np.concatenate([np.zeros(300, np.int64), np.arange(20) * 150_000 + 7])), 3)
+    api = t["node_type"] == gen.TYPE_API
+    t["node_cap"][api] = 400
+    t["quota_tok0_micro"][api] = 350_000_000
+    want = orc.replay(t)
+    first = want["start_us"].reshape(3, 320)
+    assert ((first == 0).sum(axis=1) > 200).all(), "hundreds of candidates on the quota in the first step"
+    _compare(_replay_gpu(tg, t), want, range(3), 320)
+
+
+def test_replay_gpu_nodes_behind_64_other_nodes(tg, orc):
+    """GPU nodes whose index in the scenario is above 64: their start loop and the clearing of the per-node list
+    lengths run in different wavefronts of the workgroup."""
+    t = gen.make_trace(S=3, A=900, seed=72, cluster=(70, 4, 6, 0), type_probs=(0.4, 0.6, 0), rate_per_s=150.0, horizon_s=6.0,
+                       max_ticks=20000, pin_frac=0.3)
+    M = t["M"]
+    assert (np.flatnonzero(t["node_type"][:M] == gen.TYPE_GPU) >= 64).all()
+    want = orc.replay(t)
+    assert (want["start_us"] >= 0).all()
+    _compare(_replay_gpu(tg, t), want, range(3), 900)
