@@ -69,7 +69,8 @@ class Trace(C.Structure):
         ("tick_us", C.c_int64)] + [(n, C.c_void_p) for n in (
             "k_list", "type_k", "speedup_q16", "node_type", "node_cap", "quota_rate", "quota_tok0_micro",
             "arrival_us", "act_type", "act_model", "act_t_ori_us", "act_kmask", "act_param", "act_pin_node",
-            "act_service", "restore_us", "act_quota_mask")] + [("queue_prefix", C.c_int32)]
+            "act_service", "restore_us", "act_quota_mask")] + [("queue_prefix", C.c_int32)] + [
+        ("node_aux", C.c_void_p), ("act_aux", C.c_void_p)]
 
 
 _DT = dict(k_list=np.int32, type_k=np.int32, speedup_q16=np.uint32, node_type=np.uint8, node_cap=np.int32,
@@ -78,7 +79,7 @@ _DT = dict(k_list=np.int32, type_k=np.int32, speedup_q16=np.uint32, node_type=np
            act_age_us=np.int64, act_kmask=np.uint32, act_param=np.uint32, act_pin_node=np.int32,
            act_task=np.int32, quota_rate=np.int32, quota_tok0_micro=np.int64, arrival_us=np.int64,
            node_aux_free=np.int32, act_aux=np.int32, act_service=np.int32, node_resident=np.uint64, restore_us=np.int64,
-           node_core_free=np.uint64, act_quota_mask=np.uint64)
+           node_core_free=np.uint64, act_quota_mask=np.uint64, node_aux=np.int32)
 
 
 def lib():
@@ -148,7 +149,7 @@ def _trace(t):
     s.tick_us = int(t["tick_us"])
     s.cache_slots = int(t.get("cache_slots", 64))
     s.queue_prefix = int(t.get("queue_prefix", 0))       # 1: every step admits one prefix of the whole waiting queue
-    _fill(s, t, [f[0] for f in Trace._fields_[9:-1]], keep)
+    _fill(s, t, [f[0] for f in Trace._fields_[9:-3]] + ["node_aux", "act_aux"], keep)
     return s, keep
 
 

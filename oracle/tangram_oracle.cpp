@@ -528,6 +528,7 @@ struct orc_trace {
   const int32_t* act_service; const int64_t* restore_us;           // both or neither (Sec. 5.3)
   const uint64_t* act_quota_mask;                                  // [S*A] further quotas of an API action (Sec. 4.1), or NULL
   int32_t queue_prefix;                                            // 1: every step admits one prefix of the whole waiting queue
+  const int32_t* node_aux; const int32_t* act_aux;                 // [S*M], [S*A] second resource (Sec. 4.1, 5.2); both or neither
 };
 
 }  // extern "C"
@@ -742,7 +743,7 @@ void orc_replay(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us, int64
   const int A = t->A, M = t->M;
   for (int s = s_lo; s < s_hi; ++s) {
     const size_t a0 = (size_t)s * A, n0 = (size_t)s * M;
-    struct Run { int64_t fin; int node, k, gstart; };
+    struct Run { int64_t fin; int node, k, gstart, aux; };
     std::vector<Run> running;
     std::vector<int> rem(M, 0), gmask(M, 0);
     std::vector<int64_t> tok(M, 0);
@@ -751,7 +752,12 @@ void orc_replay(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us, int64
     std::vector<uint64_t> resident(M, 0);
     std::vector<int64_t> used_at((size_t)M * 64, 0);        // per node and service: sequence number of its last use
     std::vector<int64_t> seq(M, 0);
+    // Second resource of a node (Sec. 4.1, 5.2: e.g. memory next to cores): an action that is free to choose
+    // its node holds its demand from start to finish; pinned actions hold none (the share of their
+    // trajectory is not part of a trace).
+    std::vector<int> aux_rem(M, INT32_MAX);
     for (int j = 0; j < M; ++j) {
+      if (t->node_aux) aux_rem[j] = t->node_aux[n0 + j];
       rem[j] = t->node_cap[n0 + j];
       if (t->node_type[n0 + j] == T_GPU) gmask[j] = (1 << t->node_cap[n0 + j]) - 1;
       if (t->node_type[n0 + j] == T_API) tok[j] = t->quota_tok0_micro[n0 + j];
@@ -767,6 +773,7 @@ void orc_replay(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us, int64
           const Run& u = running[r];
           if (t->node_type[n0 + u.node] == T_GPU) gmask[u.node] |= ((1 << (1 << chunk_level(u.k))) - 1) << u.gstart;
           rem[u.node] += u.k;
+          if (t->node_aux) aux_rem[u.node] += u.aux;
           running[r] = running.back(); running.pop_back();
         } else ++r;
       }
@@ -781,7 +788,8 @@ void orc_replay(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us, int64
       std::vector<Act> acts;
       for (int i : waiting)
         acts.push_back(Act{t->act_type[a0 + i], t->act_model[a0 + i], t->act_t_ori_us[a0 + i], now - t->arrival_us[a0 + i],
-                           t->act_kmask[a0 + i], t->act_param[a0 + i], t->act_pin_node[a0 + i], 0, 0,
+                           t->act_kmask[a0 + i], t->act_param[a0 + i], t->act_pin_node[a0 + i], 0,
+                           t->act_aux ? t->act_aux[a0 + i] : 0,
                            t->act_service ? t->act_service[a0 + i] : -1,
                            t->act_quota_mask ? t->act_quota_mask[a0 + i] : 0});
       std::vector<Node> nodes(M);
@@ -789,6 +797,7 @@ void orc_replay(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us, int64
         Node& nd = nodes[j];
         nd.type = t->node_type[n0 + j]; nd.cap = t->node_cap[n0 + j]; nd.backlog = 0;
         nd.resident = resident[j];
+        nd.aux_free = aux_rem[j];
         for (int x = 0; x < 4; ++x) nd.chunks[x] = 0;
         if (nd.type == T_API) nd.free = (int)(tok[j] / 1000000);
         else if (nd.type == T_GPU) { mask_chunks(gmask[j], nd.chunks); nd.free = __builtin_popcount(gmask[j]); }
@@ -818,7 +827,7 @@ void orc_replay(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us, int64
           resident[j] |= 1ull << sv;
           used_at[(size_t)j * 64 + sv] = ++seq[j];
         }
-        Run u{now + dur, j, k, 0};
+        Run u{now + dur, j, k, 0, t->act_aux && acts[w].pin < 0 ? acts[w].aux : 0};
         if (nodes[j].type == T_API) {
           tok[j] -= (int64_t)k * 1000000;
           int r = 0;                                         // one token of every further quota it names (Sec. 4.1)
@@ -828,6 +837,7 @@ void orc_replay(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us, int64
         else {
           if (nodes[j].type == T_GPU) u.gstart = mask_alloc(gmask[j], k);
           rem[j] -= k;
+          if (t->node_aux) aux_rem[j] -= u.aux;
           running.push_back(u);
         }
         start_us[a0 + i] = now; finish_us[a0 + i] = now + dur; units[a0 + i] = k; node[a0 + i] = j;

@@ -170,6 +170,11 @@ def test_every_tick_is_one_step_on_the_snapshot_rebuilt_from_the_replays_own_tim
     t["depth"] = 1 + seed % 3
     api = np.flatnonzero(t["node_type"] == gen.TYPE_API)
     t["quota_rate"][api] = 3 + seed
+    with_aux = seed >= 3                                         # a second resource held from start to finish by unpinned actions
+    if with_aux:
+        rng = np.random.default_rng(seed)
+        t["act_aux"] = rng.integers(0, 30, A).astype(np.int32)
+        t["node_aux"] = rng.integers(40, 100, t["M"]).astype(np.int32)
     o = orc.replay(t)
     M, tick = t["M"], int(t["tick_us"])
     start, fin, units, node = o["start_us"], o["finish_us"], o["units"], o["node"]
@@ -190,12 +195,19 @@ def test_every_tick_is_one_step_on_the_snapshot_rebuilt_from_the_replays_own_tim
                 free[node[i]] -= units[i]
                 busy[node[i]] += [int(fin[i]) - now] * int(units[i])
             free[api] = (tok[api] // 10**6).astype(np.int32)
+            extra = {}
+            if with_aux:
+                left = t["node_aux"].astype(np.int64).copy()
+                for i in running:
+                    if t["act_pin_node"][i] < 0:
+                        left[node[i]] -= t["act_aux"][i]
+                extra = dict(node_aux_free=left.astype(np.int32), act_aux=t["act_aux"][waiting])
             p = dict(B=1, N=len(waiting), M=M, K=t["K"], n_classes=t["n_classes"], n_tasks=1, depth=t["depth"],
                      k_list=t["k_list"], type_k=t["type_k"], speedup_q16=t["speedup_q16"],
                      node_type=t["node_type"], node_cap=t["node_cap"], node_free=free, node_backlog_us=np.zeros(M, np.int64),
                      node_chunks=None, node_busy_off=np.concatenate([[0], np.cumsum([len(b) for b in busy])]).astype(np.int32),
                      node_busy_rel_us=np.array([x for b in busy for x in b] or [0], np.int64),
-                     act_age_us=(now - arr[waiting]).astype(np.int64), act_task=None,
+                     act_age_us=(now - arr[waiting]).astype(np.int64), act_task=None, **extra,
                      **{k: t[k][waiting] for k in ("act_type", "act_model", "act_t_ori_us", "act_kmask", "act_param", "act_pin_node")})
             s = orc.assign(p)
             go = start[waiting] == now
