@@ -280,6 +280,13 @@ typedef struct {
    * the scenario): the action starts only in a tick in which every named quota holds a whole
    * token, and takes one from each.  NULL: none. */
   const uint64_t *act_quota_mask;   /* [S*A] */
+  /* Second, co-constrained resource (Sec. 4.1, 5.2), the node_aux_free / act_aux of a tg_problem_desc;
+   * both arrays or neither: an action that is free to choose its node (act_pin_node < 0) starts
+   * only on a node that has act_aux of the resource left and holds it from its start to its
+   * finish; pinned actions hold none (the share of their trajectory is not part of a trace).
+   * Values >= 0. */
+  const int32_t *node_aux;          /* [S*M] what every node has of it                           */
+  const int32_t *act_aux;           /* [S*A]                                                     */
 } tg_trace_desc;
 
 /* Device outputs of tg_replay_trace. */

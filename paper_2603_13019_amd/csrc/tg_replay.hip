@@ -33,6 +33,8 @@ struct TgTraceDev {
   const int32_t* act_service;     // [S*A] service of a GPU action or -1; nullptr: the trace has no services (Sec. 5.3)
   const int64_t* restore;         // [TG_MAX_SERVICES]
   const uint64_t* act_quota;      // [S*A] further quotas of an API action (ranks among the scenario's API nodes), or nullptr (Sec. 4.1)
+  const int32_t* node_aux;        // [S*M] second resource of every node, or nullptr: none (Sec. 4.1, 5.2)
+  const int32_t* act_aux;         // [S*A] what an action that is free to choose its node holds of it while it runs
 };
 
 struct tg_trace {
@@ -63,6 +65,9 @@ struct ReplayWs {
   uint64_t* live_res;  // [S*M] services resident on the node
   int32_t* used_at;    // [S*M*64] per node and service: sequence number of its last use
   int32_t* use_seq;    // [S*M] uses counted so far
+  // second resource (only with node_aux / act_aux)
+  int32_t* live_aux;   // [S*M] what the node has left
+  int32_t* run_aux;    // [S*A] what the running action holds, alongside run_fin / run_info
 };
 
 size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
@@ -78,7 +83,9 @@ size_t carve(const TgTraceDev& T, char* base, ReplayWs* w) {
   p[13] = take(nN * 8);
   const bool svc = T.act_service != nullptr;
   char* q0 = take(svc ? nN * 8 : 0); char* q1 = take(svc ? nN * 64 * 4 : 0); char* q2 = take(svc ? nN * 4 : 0);
+  char* x0 = take(T.node_aux ? nN * 4 : 0); char* x1 = take(T.node_aux ? nA * 4 : 0);
   if (w) {
+    w->live_aux = (int32_t*)x0; w->run_aux = (int32_t*)x1;
     w->live_res = (uint64_t*)q0; w->used_at = (int32_t*)q1; w->use_seq = (int32_t*)q2;
     w->dur = (int64_t*)p[0]; w->slot = (int32_t*)p[1]; w->order = (int32_t*)p[2]; w->dorder = (int32_t*)p[3];
     w->wlist = (int32_t*)p[4]; w->run_fin = (int64_t*)p[5]; w->run_info = (int32_t*)p[6]; w->reason = (uint8_t*)p[7];
@@ -210,6 +217,7 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
     live_tok[j] = ty == TG_TYPE_API ? T.quota_tok0[nbase + j] : 0;
     nl_cnt[j] = 0; dl_cnt[j] = 0;
     if (T.act_service) { W.live_res[nbase + j] = 0; W.use_seq[nbase + j] = 0; }   // nothing resident at time 0
+    if (T.node_aux) W.live_aux[nbase + j] = T.node_aux[nbase + j];
   }
   if (tid == 0) { s_wcnt[0] = s_wcnt[1] = s_wcnt[2] = 0; s_next = 0; s_started = 0; s_nrun = 0; }
   __syncthreads();
@@ -235,13 +243,15 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
       int out = 0;
       for (int base = 0; base < n; base += kThreads) {
         const int x = base + tid;
-        int keep = 0, info = 0;
+        int keep = 0, info = 0, held = 0;
         int64_t fin = 0;
         if (x < n) {
           fin = run_fin[x]; info = run_info[x];
+          if (T.node_aux) held = W.run_aux[abase + x];
           keep = fin > now;
           if (!keep) {
             const int node = info & 0xffff, k = (info >> 16) & 0xff, g0 = (info >> 24) & 0xff;
+            if (held) atomicAdd(&W.live_aux[nbase + node], held);   // the second resource comes back with the units
             if (T.node_type[nbase + node] == TG_TYPE_GPU) atomicOr(&live_free[node], (int)(((1u << (1 << tg_chunk_level(k))) - 1u) << g0));
             else atomicAdd(&live_free[node], k);
           }
@@ -251,7 +261,11 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
         __syncthreads();
         int before = 0, total = 0;
         for (int w = 0; w < kWaves; ++w) { const int c = s_wave_cnt[w]; if (w < wave) before += c; total += c; }
-        if (keep) { const int d = out + before + __popcll(bal & ((1ull << lane) - 1ull)); run_fin[d] = fin; run_info[d] = info; }
+        if (keep) {
+          const int d = out + before + __popcll(bal & ((1ull << lane) - 1ull));
+          run_fin[d] = fin; run_info[d] = info;
+          if (T.node_aux) W.run_aux[abase + d] = held;
+        }
         out += total;
         __syncthreads();
       }
@@ -315,11 +329,12 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
                  : ty == TG_TYPE_API ? (int32_t)(live_tok[j] / 1000000) : live_free[j];
         S.cnt[r] = 0; S.dcnt[r] = 0; S.closed[r] = 0;
         if (T.act_service) S.res[r] = W.live_res[nbase + j];
+        if (T.node_aux) S.aux[r] = W.live_aux[nbase + j];
       }
       tg_wave_sync();
       TgPlaceIo io;
       io.act_kmask = T.act_kmask + abase; io.act_static = T.act_static + abase; io.act_pin = T.act_pin + abase;
-      io.act_aux = nullptr;                                       // traces carry no second resource
+      io.act_aux = T.act_aux ? T.act_aux + abase : nullptr;
       io.act_quota = T.act_quota && ty == TG_TYPE_API ? T.act_quota + abase : nullptr;
       io.act_service = T.act_service ? T.act_service + abase : nullptr; io.restore = T.restore;
       io.act_pin_rank = nullptr;
@@ -435,6 +450,11 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
           atomicSub(&live_free[j], k);
           const int d = atomicAdd(&s_nrun, 1);
           run_fin[d] = fin; run_info[d] = j | k << 16;
+          if (T.node_aux) {                                       // held from start to finish by an action that chose its node
+            const int held = T.act_pin[abase + id] < 0 ? T.act_aux[abase + id] : 0;
+            W.run_aux[abase + d] = held;
+            if (held) atomicSub(&W.live_aux[nbase + j], held);
+          }
         }
       }
     if (T.act_service) __syncthreads();                           // the residency of the tick's start has been read
@@ -443,6 +463,7 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
       const int m = nl_cnt[j];
       if (m == 0) continue;
       uint32_t mk = (uint32_t)live_free[j];
+      int aux_left = T.node_aux ? W.live_aux[nbase + j] : 0;
       const uint64_t res0 = T.act_service ? W.live_res[nbase + j] : 0;
       uint64_t res = res0;
       int32_t* used = W.used_at + (nbase + j) * 64;
@@ -472,8 +493,14 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
           used[sv] = ++seq;
         }
         run_fin[d] = now + delay + dur[(size_t)id * K + q]; run_info[d] = j | k << 16 | g0 << 24;
+        if (T.node_aux) {
+          const int held = T.act_pin[abase + id] < 0 ? T.act_aux[abase + id] : 0;
+          W.run_aux[abase + d] = held;
+          aux_left -= held;
+        }
       }
       live_free[j] = (int)mk;
+      if (T.node_aux) W.live_aux[nbase + j] = aux_left;
       if (T.act_service) { W.live_res[nbase + j] = res; W.use_seq[nbase + j] = seq; }
     }
     __threadfence_block();
@@ -541,6 +568,7 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
   if (d->depth < 1 || d->depth > TG_MAX_DEPTH) return TG_E_INVALID_ARG;
   const bool svc = d->act_service != nullptr;
   if (svc != (d->restore_us != nullptr)) return TG_E_INVALID_ARG;
+  if ((d->node_aux != nullptr) != (d->act_aux != nullptr)) return TG_E_INVALID_ARG;
   if (svc) {
     if (d->n_services < 1 || d->n_services > TG_MAX_SERVICES || d->cache_slots < 1 || d->cache_slots > TG_MAX_SERVICES) return TG_E_INVALID_ARG;
     for (int x = 0; x < d->n_services; ++x) if (d->restore_us[x] < 0 || d->restore_us[x] >= TG_T_ORI_LIMIT) return TG_E_RANGE;
@@ -580,6 +608,14 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
                  o_amask = add(nA * 4), o_aparam = add(nA * 4), o_apin = add(nA * 4);
     const size_t o_asvc = add(svc ? nA * 4 : 0), o_rest = add(svc ? TG_MAX_SERVICES * 8 : 0);
     const size_t o_aquota = add(d->act_quota_mask ? nA * 8 : 0);
+    const bool aux = d->node_aux != nullptr;
+    const size_t o_naux = add(aux ? nN * 4 : 0), o_aaux = add(aux ? nA * 4 : 0);
+    if (aux) {
+      for (size_t g = 0; g < nN; ++g) if (d->node_aux[g] < 0) { delete t; return TG_E_INVALID_ARG; }
+      for (size_t g = 0; g < nA; ++g) if (d->act_aux[g] < 0) { delete t; return TG_E_INVALID_ARG; }
+      std::memcpy(host.data() + o_naux, d->node_aux, nN * 4);
+      std::memcpy(host.data() + o_aaux, d->act_aux, nA * 4);
+    }
     const size_t o_speed = add(std::max<size_t>((size_t)d->n_classes * K, 1) * 4);
     auto at = [&](size_t off) { return host.data() + off; };
     int max_kind = 0, max_cap_cpu = 0, max_heap = 0;
@@ -693,6 +729,8 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
     v.cache_slots = svc ? d->cache_slots : 0;
     v.queue_prefix = (d->flags & TG_TRACE_QUEUE_PREFIX) ? 1 : 0;
     v.act_quota = d->act_quota_mask ? (const uint64_t*)(base + o_aquota) : nullptr;
+    v.node_aux = aux ? (const int32_t*)(base + o_naux) : nullptr;
+    v.act_aux = aux ? (const int32_t*)(base + o_aaux) : nullptr;
     v.speedup = (const uint32_t*)(base + o_speed);
     t->max_nodes_of_kind = max_kind; t->max_cap_cpu = max_cap_cpu; t->max_heap = max_heap;
     for (int k = 0; k < 3; ++k) t->max_nodes_kind[k] = max_of_kind[k];

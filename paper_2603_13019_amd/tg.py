@@ -46,7 +46,8 @@ class TraceDesc(C.Structure):
             "k_list", "type_k", "speedup_q16", "node_type", "node_cap", "quota_rate", "quota_tok0_micro",
             "arrival_us", "act_type", "act_model", "act_t_ori_us", "act_kmask", "act_param", "act_pin_node",
             "act_service", "restore_us")] + [("n_services", C.c_int32), ("cache_slots", C.c_int32),
-                                             ("act_quota_mask", C.c_void_p)]
+                                             ("act_quota_mask", C.c_void_p), ("node_aux", C.c_void_p),
+                                             ("act_aux", C.c_void_p)]
 
 
 class ReplayOut(C.Structure):
@@ -64,7 +65,7 @@ _DT = dict(k_list=np.int32, type_k=np.int32, speedup_q16=np.uint32, node_type=np
            act_age_us=np.int64, act_kmask=np.uint32, act_param=np.uint32, act_pin_node=np.int32,
            act_task=np.int32, quota_rate=np.int32, quota_tok0_micro=np.int64, arrival_us=np.int64,
            node_aux_free=np.int32, act_aux=np.int32, act_service=np.int32, node_resident=np.uint64, restore_us=np.int64,
-           node_core_free=np.uint64, act_quota_mask=np.uint64)
+           node_core_free=np.uint64, act_quota_mask=np.uint64, node_aux=np.int32)
 
 EXPORTS = ("tg_build_problem", "tg_free_problem", "tg_num_candidates", "tg_assign_workspace_bytes",
            "tg_score_candidates", "tg_assign", "tg_step", "tg_build_trace", "tg_free_trace", "tg_replay_workspace_bytes",
@@ -232,7 +233,7 @@ class Trace:
         d.flags = 1 if int(t.get("queue_prefix", 0)) else 0      # TG_TRACE_QUEUE_PREFIX
         d.tick_us = int(t["tick_us"])
         keep = []
-        _fill(d, t, [f[0] for f in TraceDesc._fields_[9:-3]] + ["act_quota_mask"], keep)
+        _fill(d, t, [f[0] for f in TraceDesc._fields_[9:-5]] + ["act_quota_mask", "node_aux", "act_aux"], keep)
         d.n_services = len(t["restore_us"]) if t.get("restore_us") is not None else 0
         d.cache_slots = int(t.get("cache_slots", 64))
         h = C.c_void_p()

@@ -82,8 +82,17 @@ def test_replay_random_sweep(tg, orc):
         if n_gpu and rng.random() < 0.6:
             _with_services(t, seed, n_services=int(rng.choice([1, 4, 20])), slots=int(rng.choice([1, 2, 5])))
         t["queue_prefix"] = int(rng.random() < 0.3)                # one prefix of the whole queue per step
+        if rng.random() < 0.4:                                     # a second resource held by the actions that chose their node
+            _with_aux(t, seed, scarce=bool(rng.integers(0, 2)))
         _compare(_replay_gpu(tg, t), orc.replay(t), range(t["S"]), t["A"])
     print("60 traces compared", flush=True)
+
+
+def _with_aux(t, seed, scarce):
+    rng = np.random.default_rng(seed + 5)
+    t["act_aux"] = rng.integers(0, 40, t["S"] * t["A"]).astype(np.int32)
+    t["node_aux"] = rng.integers(40 if scarce else 400, 120 if scarce else 4000, t["S"] * t["M"]).astype(np.int32)
+    return t
 
 
 def _with_services(t, seed, n_services, slots):
@@ -252,3 +261,34 @@ def test_replay_gpu_nodes_behind_64_other_nodes(tg, orc):
     want = orc.replay(t)
     assert (want["start_us"] >= 0).all()
     _compare(_replay_gpu(tg, t), want, range(3), 900)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_replay_second_resource(tg, orc, seed):
+    """A second resource per node (memory next to cores) held from start to finish by every action that was free to
+    choose its node: CPU and GPU nodes, with and without pins, services, further quotas and the whole-queue prefix."""
+    print("case", seed, flush=True)
+    t = gen.make_trace(S=3, A=450, seed=800 + seed, cluster=(2 + seed % 3, 16, 1 + seed % 2, 2), rate_per_s=110.0, horizon_s=4.0,
+                       max_ticks=40000, pin_frac=(0.0, 0.3, 0.7)[seed % 3])
+    t["depth"] = 1 + seed % 3
+    plain = orc.replay(t)
+    _with_aux(t, seed, scarce=True)
+    if seed % 4 == 1:
+        _with_services(t, seed, n_services=4, slots=2)
+    if seed % 4 == 2:
+        gen.with_extra_quotas(t, frac=0.5, seed=seed)
+    t["queue_prefix"] = int(seed % 4 == 3)
+    want = orc.replay(t)
+    _compare(_replay_gpu(tg, t), want, range(3), 450)
+    if seed % 4 == 0:
+        assert (plain["start_us"] != want["start_us"]).any(), "the second resource should delay somebody"
+
+
+def test_replay_second_resource_wide_pools(tg, orc):
+    """More than 64 nodes of a kind: the admission with a second resource runs on the node table in LDS."""
+    t = gen.make_trace(S=2, A=1200, seed=820, cluster=(90, 8, 3, 0), type_probs=(0.8, 0.2, 0), rate_per_s=400.0, horizon_s=3.0,
+                       max_ticks=20000, pin_frac=0.2)
+    rng = np.random.default_rng(3)
+    t["act_aux"] = rng.integers(0, 40, t["S"] * t["A"]).astype(np.int32)
+    t["node_aux"] = rng.integers(20, 60, t["S"] * t["M"]).astype(np.int32)
+    _compare(_replay_gpu(tg, t), orc.replay(t), range(2), 1200)
