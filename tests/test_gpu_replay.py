@@ -292,3 +292,11 @@ def test_replay_second_resource_wide_pools(tg, orc):
     t["act_aux"] = rng.integers(0, 40, t["S"] * t["A"]).astype(np.int32)
     t["node_aux"] = rng.integers(20, 60, t["S"] * t["M"]).astype(np.int32)
     _compare(_replay_gpu(tg, t), orc.replay(t), range(2), 1200)
+
+
+def test_replay_longest_trace(tg, orc):
+    """The most arrivals a scenario may have (131 072), 400 per second on the default cluster: 40 new actions per tick."""
+    t = gen.make_trace(S=1, A=131072, seed=31, rate_per_s=400.0, horizon_s=131072 / 400.0, max_ticks=100000)
+    want = orc.replay(t)
+    assert want["n_started"][0] == 131072
+    _compare(_replay_gpu(tg, t), want, (0,), 131072)
