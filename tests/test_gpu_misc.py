@@ -169,3 +169,39 @@ def test_step_can_be_captured_into_a_graph(tg, one_call):
         torch.cuda.synchronize()
     del g
     P.free()
+
+
+def test_steps_of_several_problems_in_flight(tg):
+    """Independent problems stepped at the same time on streams of their own (each problem has its own internal streams
+    and events) give what each gives alone; also two launches of the same problem into different outputs."""
+    import torch
+    probs = [gen.make_config(2, B=24, seed=70 + i) for i in range(3)]
+    P = [tg.Problem(p) for p in probs]
+    keys = ("node", "units", "act_us", "defer_reason", "summary", "node_used", "node_obj", "task_sum_us")
+    ref = []
+    for x in P:                                                # one at a time
+        c, b = x.alloc_cost(), x.alloc_assign()
+        x.step(c, b)
+        torch.cuda.synchronize()
+        ref.append((c.clone(), {k: b[k].clone() for k in keys}))
+    streams = [torch.cuda.Stream() for _ in range(4)]
+    work = [(P[0], P[0].alloc_cost(), P[0].alloc_assign()), (P[1], P[1].alloc_cost(), P[1].alloc_assign()),
+            (P[2], P[2].alloc_cost(), P[2].alloc_assign()), (P[0], P[0].alloc_cost(), P[0].alloc_assign())]
+    which = [0, 1, 2, 0]
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for x, (prob, c, b) in enumerate(work):
+            c.fill_(-7)
+            for k in keys:
+                b[k].fill_(0)
+        torch.cuda.synchronize()
+        for x, (prob, c, b) in enumerate(work):
+            with torch.cuda.stream(streams[x]):
+                prob.step(c, b)
+        torch.cuda.synchronize()
+        for x, (prob, c, b) in enumerate(work):
+            assert torch.equal(c, ref[which[x]][0]), f"run {rep} launch {x}: score tensor"
+            for k in keys:
+                assert torch.equal(b[k], ref[which[x]][1][k]), f"run {rep} launch {x}: {k}"
+    for x in P:
+        x.free()
