@@ -70,7 +70,7 @@ class Trace(C.Structure):
             "k_list", "type_k", "speedup_q16", "node_type", "node_cap", "quota_rate", "quota_tok0_micro",
             "arrival_us", "act_type", "act_model", "act_t_ori_us", "act_kmask", "act_param", "act_pin_node",
             "act_service", "restore_us", "act_quota_mask")] + [("queue_prefix", C.c_int32)] + [
-        ("node_aux", C.c_void_p), ("act_aux", C.c_void_p)]
+        ("node_aux", C.c_void_p), ("act_aux", C.c_void_p), ("numa_cores", C.c_int32)]
 
 
 _DT = dict(k_list=np.int32, type_k=np.int32, speedup_q16=np.uint32, node_type=np.uint8, node_cap=np.int32,
@@ -112,7 +112,7 @@ def lib():
         L.orc_mask_alloc.restype = C.c_int
         L.orc_mask_alloc.argtypes = [C.POINTER(C.c_int), C.c_int]
         L.orc_replay.restype = None
-        L.orc_replay.argtypes = [C.c_void_p, C.c_int, C.c_int] + [C.c_void_p] * 8
+        L.orc_replay.argtypes = [C.c_void_p, C.c_int, C.c_int] + [C.c_void_p] * 9
         _lib = L
     return _lib
 
@@ -149,7 +149,8 @@ def _trace(t):
     s.tick_us = int(t["tick_us"])
     s.cache_slots = int(t.get("cache_slots", 64))
     s.queue_prefix = int(t.get("queue_prefix", 0))       # 1: every step admits one prefix of the whole waiting queue
-    _fill(s, t, [f[0] for f in Trace._fields_[9:-3]] + ["node_aux", "act_aux"], keep)
+    s.numa_cores = int(t.get("numa_cores", 0))           # > 0: CPU actions get named cores (NUMA domains of that many)
+    _fill(s, t, [f[0] for f in Trace._fields_[9:-4]] + ["node_aux", "act_aux"], keep)
     return s, keep
 
 
@@ -253,6 +254,9 @@ def replay(t, s_lo=0, s_hi=None):
     out = dict(start_us=np.full(S * A, -1, np.int64), finish_us=np.full(S * A, -1, np.int64),
                units=np.zeros(S * A, np.int32), node=np.full(S * A, -1, np.int32), mean_act=np.zeros(S),
                p99_act=np.full(S, -1, np.int64), n_started=np.zeros(S, np.int32), n_ticks=np.zeros(S, np.int32))
+    if int(t.get("numa_cores", 0)) > 0:
+        out["core_set"] = np.zeros(S * A * 4, np.uint64)
     lib().orc_replay(C.addressof(s), int(s_lo), int(s_hi), *[out[k].ctypes.data for k in
-                     ("start_us", "finish_us", "units", "node", "mean_act", "p99_act", "n_started", "n_ticks")])
+                     ("start_us", "finish_us", "units", "node", "mean_act", "p99_act", "n_started", "n_ticks")],
+                     out["core_set"].ctypes.data if "core_set" in out else None)
     return out

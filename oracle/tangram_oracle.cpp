@@ -529,6 +529,7 @@ struct orc_trace {
   const uint64_t* act_quota_mask;                                  // [S*A] further quotas of an API action (Sec. 4.1), or NULL
   int32_t queue_prefix;                                            // 1: every step admits one prefix of the whole waiting queue
   const int32_t* node_aux; const int32_t* act_aux;                 // [S*M], [S*A] second resource (Sec. 4.1, 5.2); both or neither
+  int32_t numa_cores;                                              // > 0: CPU actions are given named cores (Sec. 5.2), all free at time 0
 };
 
 }  // extern "C"
@@ -738,12 +739,13 @@ int orc_mask_chunks(int mask, uint8_t* out) { int c[4]; mask_chunks(mask, c); fo
 int orc_mask_alloc(int* mask, int k) { return mask_alloc(*mask, k); }
 
 void orc_replay(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us, int64_t* finish_us, int32_t* units,
-                int32_t* node, double* mean_act, int64_t* p99_act, int32_t* n_started, int32_t* n_ticks) {
+                int32_t* node, double* mean_act, int64_t* p99_act, int32_t* n_started, int32_t* n_ticks,
+                uint64_t* core_set /* [S*A*4] or NULL; written when numa_cores > 0 */) {
   const Tables tb{t->K, t->k_list, t->type_k, t->speedup_q16, t->depth, t->act_service ? t->restore_us : nullptr};
   const int A = t->A, M = t->M;
   for (int s = s_lo; s < s_hi; ++s) {
     const size_t a0 = (size_t)s * A, n0 = (size_t)s * M;
-    struct Run { int64_t fin; int node, k, gstart, aux; };
+    struct Run { int64_t fin; int node, k, gstart, aux; std::vector<int> cores; };
     std::vector<Run> running;
     std::vector<int> rem(M, 0), gmask(M, 0);
     std::vector<int64_t> tok(M, 0);
@@ -756,7 +758,14 @@ void orc_replay(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us, int64
     // its node holds its demand from start to finish; pinned actions hold none (the share of their
     // trajectory is not part of a trace).
     std::vector<int> aux_rem(M, INT32_MAX);
+    // Sec. 5.2: the CPU manager names the cores of every action.  All cores are free at time 0; an action keeps
+    // the cores the step gave it (tg_assign's rule, node by node in visiting order) until it finishes.
+    const int numa = core_set ? t->numa_cores : 0;
+    std::vector<std::vector<char>> core_free(M);
+    if (numa > 0)
+      for (int i = 0; i < A; ++i) for (int w = 0; w < 4; ++w) core_set[(a0 + i) * 4 + w] = 0;
     for (int j = 0; j < M; ++j) {
+      if (numa > 0 && t->node_type[n0 + j] == T_CPU) core_free[j].assign(t->node_cap[n0 + j], 1);
       if (t->node_aux) aux_rem[j] = t->node_aux[n0 + j];
       rem[j] = t->node_cap[n0 + j];
       if (t->node_type[n0 + j] == T_GPU) gmask[j] = (1 << t->node_cap[n0 + j]) - 1;
@@ -774,6 +783,7 @@ void orc_replay(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us, int64
           if (t->node_type[n0 + u.node] == T_GPU) gmask[u.node] |= ((1 << (1 << chunk_level(u.k))) - 1) << u.gstart;
           rem[u.node] += u.k;
           if (t->node_aux) aux_rem[u.node] += u.aux;
+          for (int c : u.cores) core_free[u.node][c] = 1;
           running[r] = running.back(); running.pop_back();
         } else ++r;
       }
@@ -798,6 +808,7 @@ void orc_replay(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us, int64
         nd.type = t->node_type[n0 + j]; nd.cap = t->node_cap[n0 + j]; nd.backlog = 0;
         nd.resident = resident[j];
         nd.aux_free = aux_rem[j];
+        if (numa > 0 && nd.type == T_CPU) nd.core_free = core_free[j];
         for (int x = 0; x < 4; ++x) nd.chunks[x] = 0;
         if (nd.type == T_API) nd.free = (int)(tok[j] / 1000000);
         else if (nd.type == T_GPU) { mask_chunks(gmask[j], nd.chunks); nd.free = __builtin_popcount(gmask[j]); }
@@ -807,7 +818,7 @@ void orc_replay(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us, int64
         if (nodes[u.node].type != T_API)
           for (int c = 0; c < u.k; ++c) nodes[u.node].busy.push_back(u.fin - now);
       // (4) the scheduling step; (5) selected actions start now
-      const StepOut o = step(tb, acts, nodes, ORDER_FCFS, 0, false, t->queue_prefix != 0);
+      const StepOut o = step(tb, acts, nodes, ORDER_FCFS, numa, false, t->queue_prefix != 0);
       std::vector<int> still;
       for (size_t w = 0; w < waiting.size(); ++w) {
         const int i = waiting[w];
@@ -838,6 +849,10 @@ void orc_replay(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us, int64
           if (nodes[j].type == T_GPU) u.gstart = mask_alloc(gmask[j], k);
           rem[j] -= k;
           if (t->node_aux) aux_rem[j] -= u.aux;
+          if (numa > 0 && nodes[j].type == T_CPU) {
+            u.cores = o.cores[w];
+            for (int c : u.cores) { core_free[j][c] = 0; core_set[(a0 + i) * 4 + c / 64] |= 1ull << (c % 64); }
+          }
           running.push_back(u);
         }
         start_us[a0 + i] = now; finish_us[a0 + i] = now + dur; units[a0 + i] = k; node[a0 + i] = j;
