@@ -287,6 +287,12 @@ typedef struct {
    * Values >= 0. */
   const int32_t *node_aux;          /* [S*M] what every node has of it                           */
   const int32_t *act_aux;           /* [S*A]                                                     */
+  /* Named cores (Sec. 5.2) as numa_cores / core_set of a step: 4, 8, 16, 32 or 64 cores per NUMA
+   * domain, all cores of every CPU node free at time 0; a CPU action gets its cores by the rule of
+   * tg_assign_out.core_set in the step that selects it and keeps them until it finishes;
+   * tg_replay_out.core_set is then required.  0: cores are not named. */
+  int32_t numa_cores;
+  int32_t reserved_;                /* 0                                                         */
 } tg_trace_desc;
 
 /* Device outputs of tg_replay_trace. */
@@ -299,6 +305,8 @@ typedef struct {
   int64_t *p99_act_us; /* [S] nearest-rank 99th percentile of the same, -1 if none started        */
   int32_t *n_started;  /* [S]                                                                    */
   int32_t *n_ticks;    /* [S] ticks simulated                                                    */
+  uint64_t *core_set;  /* [S*A*4] cores of every started CPU action, as tg_assign_out.core_set; needed with
+                          numa_cores > 0 (written completely), ignored otherwise                */
 } tg_replay_out;
 
 int tg_build_trace(const tg_trace_desc *desc, void *hip_stream, tg_trace **out);

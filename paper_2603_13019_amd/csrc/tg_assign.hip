@@ -474,22 +474,6 @@ __global__ __launch_bounds__(256) void tg_summary_kernel(TgDev P, tg_assign_out 
 // of the node's map and a node of up to 256 cores has at most 64 domains).  The node's selected
 // actions take their cores one after the other in the order of its candidate list.
 
-// the k lowest set bits of m (1 <= k <= popcount(m)): binary descent to the k-th set bit
-__device__ static inline uint64_t tg_lowest_bits(uint64_t m, int k) {
-  if (k <= 4) {                                                   // the usual case: peel the bits off one by one
-    uint64_t rest = m;
-    for (int x = 0; x < k; ++x) rest &= rest - 1;
-    return m ^ rest;
-  }
-  int pos = 0, r = k;
-#pragma unroll
-  for (int w = 32; w >= 1; w >>= 1) {
-    const int c = __popcll((m >> pos) & ((1ull << w) - 1));
-    if (r > c) { pos += w; r -= c; }
-  }
-  return m & ((2ull << pos) - 1);
-}
-
 __global__ __launch_bounds__(256) void tg_cores_clear_kernel(unsigned long long* core_set, size_t n) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i < n) core_set[i] = 0;
@@ -520,25 +504,8 @@ __global__ __launch_bounds__(kCoresWaves * TG_WAVE) void tg_cores_kernel(TgDev P
     for (int l = 0; l < n; ++l) {
       const int a = __builtin_amdgcn_readlane(my_a, l), k = __builtin_amdgcn_readlane(my_k, l);
       if (k == 0) continue;                                       // evicted: no cores
-      int cnt = __popcll(dm);
-      uint64_t take = 0;
-      // the domain with the fewest free cores that holds all k; key = (free cores, domain)
-      const uint32_t fit = tg_wave_min_u32(cnt >= k ? (uint32_t)cnt << 8 | (uint32_t)lane : 0xffffffffu);
-      const bool one_domain = fit != 0xffffffffu;
-      if (one_domain) {
-        if (lane == (int)(fit & 0xff)) take = tg_lowest_bits(dm, k);
-      } else {
-        // no domain holds k: whole domains, most free cores first, until k cores are found
-        int left = k;
-        while (left > 0) {
-          const uint32_t big = tg_wave_min_u32(cnt > 0 ? (uint32_t)(64 - cnt) << 8 | (uint32_t)lane : 0xffffffffu);
-          if (big == 0xffffffffu) break;                          // cannot happen: a node hands out at most its free cores
-          const int have = 64 - (int)(big >> 8), t = have < left ? have : left;
-          if (lane == (int)(big & 0xff)) { take = tg_lowest_bits(dm, t); cnt -= t; }
-          left -= t;
-        }
-      }
-      dm ^= take;
+      bool one_domain;
+      const uint64_t take = tg_take_cores(dm, k, lane, &one_domain);
       // the map of every action was cleared before this kernel: only the words that get cores are touched
       if (take) {
         unsigned long long* dst = (unsigned long long*)O.core_set + (abase + a) * 4 + word;

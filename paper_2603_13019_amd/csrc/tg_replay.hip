@@ -35,6 +35,7 @@ struct TgTraceDev {
   const uint64_t* act_quota;      // [S*A] further quotas of an API action (ranks among the scenario's API nodes), or nullptr (Sec. 4.1)
   const int32_t* node_aux;        // [S*M] second resource of every node, or nullptr: none (Sec. 4.1, 5.2)
   const int32_t* act_aux;         // [S*A] what an action that is free to choose its node holds of it while it runs
+  int numa_cores;                 // > 0: CPU actions get named cores, NUMA domains of this many (Sec. 5.2)
 };
 
 struct tg_trace {
@@ -68,6 +69,9 @@ struct ReplayWs {
   // second resource (only with node_aux / act_aux)
   int32_t* live_aux;   // [S*M] what the node has left
   int32_t* run_aux;    // [S*A] what the running action holds, alongside run_fin / run_info
+  // named cores (only with numa_cores > 0)
+  uint64_t* live_cores;  // [S*M*4] free cores of every CPU node
+  int32_t* run_id;       // [S*A] the running action's id (its cores are in the output map), alongside run_fin / run_info
 };
 
 size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
@@ -84,7 +88,9 @@ size_t carve(const TgTraceDev& T, char* base, ReplayWs* w) {
   const bool svc = T.act_service != nullptr;
   char* q0 = take(svc ? nN * 8 : 0); char* q1 = take(svc ? nN * 64 * 4 : 0); char* q2 = take(svc ? nN * 4 : 0);
   char* x0 = take(T.node_aux ? nN * 4 : 0); char* x1 = take(T.node_aux ? nA * 4 : 0);
+  char* c0 = take(T.numa_cores ? nN * 32 : 0); char* c1 = take(T.numa_cores ? nA * 4 : 0);
   if (w) {
+    w->live_cores = (uint64_t*)c0; w->run_id = (int32_t*)c1;
     w->live_aux = (int32_t*)x0; w->run_aux = (int32_t*)x1;
     w->live_res = (uint64_t*)q0; w->used_at = (int32_t*)q1; w->use_seq = (int32_t*)q2;
     w->dur = (int64_t*)p[0]; w->slot = (int32_t*)p[1]; w->order = (int32_t*)p[2]; w->dorder = (int32_t*)p[3];
@@ -211,6 +217,14 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
   int64_t* o_fin = O.finish_us + abase;
 
   for (int i = tid; i < A; i += kThreads) { o_node[i] = -1; o_units[i] = 0; o_start[i] = -1; o_fin[i] = -1; }
+  if (T.numa_cores) {
+    for (size_t i = tid; i < (size_t)A * 4; i += kThreads) O.core_set[abase * 4 + i] = 0;
+    for (int x = tid; x < M * 4; x += kThreads) {                 // every core of a CPU node is free at time 0
+      const int j = x >> 2, w = x & 3, cap = T.node_cap[nbase + j];
+      const int bits = T.node_type[nbase + j] == TG_TYPE_CPU ? min(max(cap - 64 * w, 0), 64) : 0;
+      W.live_cores[(nbase + j) * 4 + w] = bits == 64 ? ~0ull : (1ull << bits) - 1ull;
+    }
+  }
   for (int j = tid; j < M; j += kThreads) {
     const int ty = T.node_type[nbase + j], cap = T.node_cap[nbase + j];
     live_free[j] = ty == TG_TYPE_GPU ? (int)((1u << cap) - 1u) : cap;
@@ -243,15 +257,23 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
       int out = 0;
       for (int base = 0; base < n; base += kThreads) {
         const int x = base + tid;
-        int keep = 0, info = 0, held = 0;
+        int keep = 0, info = 0, held = 0, rid = 0;
         int64_t fin = 0;
         if (x < n) {
           fin = run_fin[x]; info = run_info[x];
           if (T.node_aux) held = W.run_aux[abase + x];
+          if (T.numa_cores) rid = W.run_id[abase + x];
           keep = fin > now;
           if (!keep) {
             const int node = info & 0xffff, k = (info >> 16) & 0xff, g0 = (info >> 24) & 0xff;
             if (held) atomicAdd(&W.live_aux[nbase + node], held);   // the second resource comes back with the units
+            if (T.numa_cores && T.node_type[nbase + node] == TG_TYPE_CPU) {   // and so do the cores
+              for (int w = 0; w < 4; ++w) {
+                const int id = rid;
+                const unsigned long long cs = O.core_set[(abase + id) * 4 + w];
+                if (cs) atomicOr((unsigned long long*)&W.live_cores[(nbase + node) * 4 + w], cs);
+              }
+            }
             if (T.node_type[nbase + node] == TG_TYPE_GPU) atomicOr(&live_free[node], (int)(((1u << (1 << tg_chunk_level(k))) - 1u) << g0));
             else atomicAdd(&live_free[node], k);
           }
@@ -265,6 +287,7 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
           const int d = out + before + __popcll(bal & ((1ull << lane) - 1ull));
           run_fin[d] = fin; run_info[d] = info;
           if (T.node_aux) W.run_aux[abase + d] = held;
+          if (T.numa_cores) W.run_id[abase + d] = rid;
         }
         out += total;
         __syncthreads();
@@ -450,6 +473,7 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
           atomicSub(&live_free[j], k);
           const int d = atomicAdd(&s_nrun, 1);
           run_fin[d] = fin; run_info[d] = j | k << 16;
+          if (T.numa_cores) W.run_id[abase + d] = id;
           if (T.node_aux) {                                       // held from start to finish by an action that chose its node
             const int held = T.act_pin[abase + id] < 0 ? T.act_aux[abase + id] : 0;
             W.run_aux[abase + d] = held;
@@ -493,6 +517,7 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
           used[sv] = ++seq;
         }
         run_fin[d] = now + delay + dur[(size_t)id * K + q]; run_info[d] = j | k << 16 | g0 << 24;
+        if (T.numa_cores) W.run_id[abase + d] = id;
         if (T.node_aux) {
           const int held = T.act_pin[abase + id] < 0 ? T.act_aux[abase + id] : 0;
           W.run_aux[abase + d] = held;
@@ -502,6 +527,37 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
       live_free[j] = (int)mk;
       if (T.node_aux) W.live_aux[nbase + j] = aux_left;
       if (T.act_service) { W.live_res[nbase + j] = res; W.use_seq[nbase + j] = seq; }
+    }
+    // (5b) named cores (Sec. 5.2): the selected actions of a CPU node take theirs one after the other in list order,
+    // lane = NUMA domain; every wavefront looks at the same 64 list lengths and takes every kWaves-th node with a list
+    if (T.numa_cores) {
+      const int nc = T.numa_cores;
+      const int word = (lane * nc) >> 6, shift = (lane * nc) & 63;
+      int seen = 0;
+      for (int jb = 0; jb < M; jb += TG_WAVE) {
+        const int jn = jb + lane;
+        uint64_t todo = __ballot(jn < M && nl_cnt[jn < M ? jn : 0] > 0 && T.node_type[nbase + (jn < M ? jn : 0)] == TG_TYPE_CPU);
+        while (todo) {
+          const int j = jb + __builtin_ctzll(todo);
+          todo &= todo - 1;
+          if ((seen++ & (kWaves - 1)) != wave) continue;
+          const int m = nl_cnt[j], n_dom = (T.node_cap[nbase + j] + nc - 1) / nc;
+          uint64_t dm = 0, gone = 0;                              // free cores of this lane's domain; what it gives in this tick
+          if (lane < n_dom) {
+            dm = W.live_cores[(nbase + j) * 4 + word] >> shift;
+            if (nc < 64) dm &= (1ull << nc) - 1;
+          }
+          for (int x = 0; x < m; ++x) {
+            const int a = order[nl_off[j] + x];
+            if (o_node[a] < 0) break;                             // evicted tail
+            bool one_domain;
+            const uint64_t take = tg_take_cores(dm, o_units[a], lane, &one_domain);
+            gone |= take;
+            if (take) atomicOr((unsigned long long*)&O.core_set[(abase + a) * 4 + word], (unsigned long long)(take << shift));
+          }
+          if (gone) atomicAnd((unsigned long long*)&W.live_cores[(nbase + j) * 4 + word], ~(unsigned long long)(gone << shift));
+        }
+      }
     }
     __threadfence_block();
     __syncthreads();                                              // the GPU nodes' lists have been read
@@ -569,6 +625,9 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
   const bool svc = d->act_service != nullptr;
   if (svc != (d->restore_us != nullptr)) return TG_E_INVALID_ARG;
   if ((d->node_aux != nullptr) != (d->act_aux != nullptr)) return TG_E_INVALID_ARG;
+  if (d->numa_cores != 0 && d->numa_cores != 4 && d->numa_cores != 8 && d->numa_cores != 16 && d->numa_cores != 32 &&
+      d->numa_cores != 64) return TG_E_INVALID_ARG;
+  if (d->reserved_ != 0) return TG_E_INVALID_ARG;
   if (svc) {
     if (d->n_services < 1 || d->n_services > TG_MAX_SERVICES || d->cache_slots < 1 || d->cache_slots > TG_MAX_SERVICES) return TG_E_INVALID_ARG;
     for (int x = 0; x < d->n_services; ++x) if (d->restore_us[x] < 0 || d->restore_us[x] >= TG_T_ORI_LIMIT) return TG_E_RANGE;
@@ -731,6 +790,7 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
     v.act_quota = d->act_quota_mask ? (const uint64_t*)(base + o_aquota) : nullptr;
     v.node_aux = aux ? (const int32_t*)(base + o_naux) : nullptr;
     v.act_aux = aux ? (const int32_t*)(base + o_aaux) : nullptr;
+    v.numa_cores = d->numa_cores;
     v.speedup = (const uint32_t*)(base + o_speed);
     t->max_nodes_of_kind = max_kind; t->max_cap_cpu = max_cap_cpu; t->max_heap = max_heap;
     for (int k = 0; k < 3; ++k) t->max_nodes_kind[k] = max_of_kind[k];
@@ -757,7 +817,7 @@ extern "C" int tg_replay_workspace_bytes(const tg_trace* t, size_t* bytes) {
 
 extern "C" int tg_replay_trace(const tg_trace* t, const tg_replay_out* out, void* d_ws, size_t ws_bytes, void* hip_stream) {
   if (!t || !out || !out->start_us || !out->finish_us || !out->units || !out->node || !out->mean_act_us ||
-      !out->p99_act_us || !out->n_started || !out->n_ticks)
+      !out->p99_act_us || !out->n_started || !out->n_ticks || (t->dev.numa_cores && !out->core_set))
     return TG_E_INVALID_ARG;
   if (!d_ws || ((uintptr_t)d_ws & 255) || ws_bytes < carve(t->dev, nullptr, nullptr)) return TG_E_WORKSPACE;
   hipStream_t s = (hipStream_t)hip_stream;

@@ -1152,6 +1152,49 @@ __device__ static inline void tg_dp_units32(uint32_t* prev, uint32_t* cur, const
   }
 }
 
+// the k lowest set bits of m (1 <= k <= popcount(m)): binary descent to the k-th set bit
+__device__ static inline uint64_t tg_lowest_bits(uint64_t m, int k) {
+  if (k <= 4) {                                                   // the usual case: peel the bits off one by one
+    uint64_t rest = m;
+    for (int x = 0; x < k; ++x) rest &= rest - 1;
+    return m ^ rest;
+  }
+  int pos = 0, r = k;
+#pragma unroll
+  for (int w = 32; w >= 1; w >>= 1) {
+    const int c = __popcll((m >> pos) & ((1ull << w) - 1));
+    if (r > c) { pos += w; r -= c; }
+  }
+  return m & ((2ull << pos) - 1);
+}
+
+// One allocation of k cores on a CPU node (Sec. 5.2: the cores of an action are named, one NUMA
+// domain where possible).  Lane d holds the free cores of domain d in the low bits of `dm` (0 for
+// lanes beyond the node's domains).  If a domain has k free cores: the one with the fewest that
+// still has them (lowest domain on ties), its lowest-numbered free cores; otherwise whole domains,
+// the one with the most free cores first (lowest on ties), until k cores are found.  Returns the
+// bits this lane gives and clears them in `dm`; *one_domain tells whether a single lane gave all.
+__device__ static inline uint64_t tg_take_cores(uint64_t& dm, int k, int lane, bool* one_domain) {
+  int cnt = __popcll(dm);
+  uint64_t take = 0;
+  const uint32_t fit = tg_wave_min_u32(cnt >= k ? (uint32_t)cnt << 8 | (uint32_t)lane : 0xffffffffu);   // key = (free cores, domain)
+  *one_domain = fit != 0xffffffffu;
+  if (*one_domain) {
+    if (lane == (int)(fit & 0xff)) take = tg_lowest_bits(dm, k);
+  } else {
+    int left = k;
+    while (left > 0) {
+      const uint32_t big = tg_wave_min_u32(cnt > 0 ? (uint32_t)(64 - cnt) << 8 | (uint32_t)lane : 0xffffffffu);
+      if (big == 0xffffffffu) break;                              // cannot happen: a node hands out at most its free cores
+      const int have = 64 - (int)(big >> 8), t = have < left ? have : left;
+      if (lane == (int)(big & 0xff)) { take = tg_lowest_bits(dm, t); cnt -= t; }
+      left -= t;
+    }
+  }
+  dm ^= take;
+  return take;
+}
+
 // A node with one candidate and nobody waiting for it needs no table and no heap: DPArrange over
 // one action is its fastest allowed option that fits (equal durations: fewer units on counted
 // resources; on GPU nodes the option that leaves the smaller chunk state, as the chunk DP ends in

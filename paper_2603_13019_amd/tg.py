@@ -47,12 +47,12 @@ class TraceDesc(C.Structure):
             "arrival_us", "act_type", "act_model", "act_t_ori_us", "act_kmask", "act_param", "act_pin_node",
             "act_service", "restore_us")] + [("n_services", C.c_int32), ("cache_slots", C.c_int32),
                                              ("act_quota_mask", C.c_void_p), ("node_aux", C.c_void_p),
-                                             ("act_aux", C.c_void_p)]
+                                             ("act_aux", C.c_void_p), ("numa_cores", C.c_int32), ("reserved_", C.c_int32)]
 
 
 class ReplayOut(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("start_us", "finish_us", "units", "node", "mean_act_us", "p99_act_us",
-                                          "n_started", "n_ticks")]
+                                          "n_started", "n_ticks", "core_set")]
 
 
 SUMMARY_DTYPE = np.dtype([("sum_act_us", "<i8"), ("n_selected", "<i4"), ("n_prefix", "<i4"), ("n_evicted", "<i4"),
@@ -233,13 +233,15 @@ class Trace:
         d.flags = 1 if int(t.get("queue_prefix", 0)) else 0      # TG_TRACE_QUEUE_PREFIX
         d.tick_us = int(t["tick_us"])
         keep = []
-        _fill(d, t, [f[0] for f in TraceDesc._fields_[9:-5]] + ["act_quota_mask", "node_aux", "act_aux"], keep)
+        _fill(d, t, [f[0] for f in TraceDesc._fields_[9:-7]] + ["act_quota_mask", "node_aux", "act_aux"], keep)
+        d.numa_cores = int(t.get("numa_cores", 0))
         d.n_services = len(t["restore_us"]) if t.get("restore_us") is not None else 0
         d.cache_slots = int(t.get("cache_slots", 64))
         h = C.c_void_p()
         _check(L.tg_build_trace(C.byref(d), _stream(), C.byref(h)), "tg_build_trace")
         self._h = h
         self.S, self.A, self.M = int(t["S"]), int(t["A"]), int(t["M"])
+        self.has_cores = int(t.get("numa_cores", 0)) > 0
         ws = C.c_size_t()
         _check(L.tg_replay_workspace_bytes(h, C.byref(ws)), "tg_replay_workspace_bytes")
         self.ws_bytes = int(ws.value)
@@ -255,7 +257,9 @@ class Trace:
         import torch
         dev = "cuda"
         n = self.S * self.A
+        cores = dict(core_set=torch.empty(n * 4, dtype=torch.int64, device=dev)) if self.has_cores else {}
         return dict(
+            **cores,
             start_us=torch.empty(n, dtype=torch.int64, device=dev), finish_us=torch.empty(n, dtype=torch.int64, device=dev),
             units=torch.empty(n, dtype=torch.int32, device=dev), node=torch.empty(n, dtype=torch.int32, device=dev),
             mean_act_us=torch.empty(self.S, dtype=torch.float64, device=dev),
@@ -269,7 +273,7 @@ class Trace:
             bufs = self.alloc()
         o = ReplayOut()
         for n, _ in ReplayOut._fields_:
-            setattr(o, n, bufs[n].data_ptr())
+            setattr(o, n, bufs[n].data_ptr() if bufs.get(n) is not None else None)
         _check(load().tg_replay_trace(self._h, C.byref(o), _ptr(bufs["ws"]), bufs["ws"].numel(), _stream()),
                "tg_replay_trace")
         return bufs

@@ -63,8 +63,8 @@ def test_field_offsets_match_the_compiled_header(tg, tmp_path):
 def test_struct_layouts_match_header(tg):
     assert C.sizeof(tg.ProblemDesc) == 8 * 4 + 25 * 8 + 4 * 4
     assert C.sizeof(tg.AssignOut) == 9 * 8
-    assert C.sizeof(tg.TraceDesc) == 8 * 4 + 8 + 16 * 8 + 2 * 4 + 3 * 8
-    assert C.sizeof(tg.ReplayOut) == 8 * 8
+    assert C.sizeof(tg.TraceDesc) == 8 * 4 + 8 + 16 * 8 + 2 * 4 + 3 * 8 + 2 * 4
+    assert C.sizeof(tg.ReplayOut) == 9 * 8
     assert tg.SUMMARY_DTYPE.itemsize == 8 + 16 + 24 + 24 + 8 + 24
 
 
@@ -276,7 +276,8 @@ def _trace_rc(tg, t):
     d.flags = int(t.get("flags", 0))
     d.tick_us = int(t["tick_us"])
     keep = []
-    tg._fill(d, t, [f[0] for f in tg.TraceDesc._fields_[9:-5]] + ["act_quota_mask", "node_aux", "act_aux"], keep)
+    tg._fill(d, t, [f[0] for f in tg.TraceDesc._fields_[9:-7]] + ["act_quota_mask", "node_aux", "act_aux"], keep)
+    d.numa_cores = int(t.get("numa_cores", 0))
     d.n_services = int(t.get("n_services", len(t["restore_us"]) if t.get("restore_us") is not None else 0))
     d.cache_slots = int(t.get("cache_slots", 64))
     h = C.c_void_p()
@@ -290,6 +291,8 @@ BAD_TRACE = {
     "gpu_node_not_8": (lambda t: t["node_cap"].__setitem__(int(np.flatnonzero(t["node_type"] == gen.TYPE_GPU)[0]), 4), -1),
     "tick_zero": (lambda t: t.__setitem__("tick_us", 0), -1),
     "unknown_flag": (lambda t: t.__setitem__("flags", 2), -1),
+    "numa_domain_not_a_power_of_two": (lambda t: t.__setitem__("numa_cores", 12), -1),
+    "numa_domain_too_small": (lambda t: t.__setitem__("numa_cores", 2), -1),
     "second_resource_half_given": (lambda t: t.__setitem__("node_aux", np.ones(t["S"] * t["M"], np.int32)), -1),
     "second_resource_negative": (lambda t: (t.__setitem__("node_aux", np.ones(t["S"] * t["M"], np.int32)),
                                             t.__setitem__("act_aux", np.full(t["S"] * t["A"], -1, np.int32))), -1),

@@ -21,8 +21,9 @@ def _replay_gpu(tg, t):
     import torch
     T = tg.Trace(t)
     bufs = T.alloc()
-    for k in ("start_us", "finish_us", "units", "node", "p99_act_us", "n_started", "n_ticks"):
-        bufs[k].fill_(-5)
+    for k in ("start_us", "finish_us", "units", "node", "p99_act_us", "n_started", "n_ticks", "core_set"):
+        if k in bufs:
+            bufs[k].fill_(-5)
     T.replay(bufs)
     torch.cuda.synchronize()
     out = {k: v.cpu().numpy() for k, v in bufs.items() if k != "ws"}
@@ -39,6 +40,10 @@ def _compare(got, want, scenarios, A):
         assert got["n_ticks"][s] == want["n_ticks"][s]
         assert got["p99_act_us"][s] == want["p99_act"][s]
         np.testing.assert_allclose(got["mean_act_us"][s], want["mean_act"][s], rtol=1e-9, atol=0)
+        assert ("core_set" in got) == ("core_set" in want)
+        if "core_set" in want:
+            np.testing.assert_array_equal(got["core_set"].view(np.uint64)[4 * s * A:4 * (s + 1) * A], want["core_set"][4 * s * A:4 * (s + 1) * A],
+                                          err_msg=f"scenario {s} core_set")
 
 
 CASES = {
@@ -84,6 +89,8 @@ def test_replay_random_sweep(tg, orc):
         t["queue_prefix"] = int(rng.random() < 0.3)                # one prefix of the whole queue per step
         if rng.random() < 0.4:                                     # a second resource held by the actions that chose their node
             _with_aux(t, seed, scarce=bool(rng.integers(0, 2)))
+        if rng.random() < 0.4:                                     # CPU actions get named cores
+            t["numa_cores"] = int(rng.choice([4, 8, 16, 32, 64]))
         _compare(_replay_gpu(tg, t), orc.replay(t), range(t["S"]), t["A"])
     print("60 traces compared", flush=True)
 
@@ -300,3 +307,31 @@ def test_replay_longest_trace(tg, orc):
     want = orc.replay(t)
     assert want["n_started"][0] == 131072
     _compare(_replay_gpu(tg, t), want, (0,), 131072)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_replay_core_sets(tg, orc, seed):
+    """Named cores (NUMA domains of 4-64 cores, nodes of 16-256 cores): every CPU action keeps the cores its step gave
+    it until it finishes; with pins, the second resource and the whole-queue prefix in the mix."""
+    print("case", seed, flush=True)
+    cap, numa = ((16, 4), (48, 8), (128, 16), (256, 64), (256, 4), (40, 16), (128, 32), (24, 8))[seed]
+    t = gen.make_trace(S=3, A=500, seed=840 + seed, cluster=(2 + seed % 3, cap, 1, 1), rate_per_s=130.0, horizon_s=4.0,
+                       max_ticks=40000, pin_frac=(0.0, 0.3)[seed % 2], type_probs=(0.8, 0.1, 0.1))
+    t["numa_cores"] = numa
+    if seed % 4 == 2:
+        _with_aux(t, seed, scarce=True)
+    t["queue_prefix"] = int(seed % 4 == 3)
+    want = orc.replay(t)
+    sets = want["core_set"].reshape(-1, 4)
+    bits = np.array([sum(bin(int(w)).count("1") for w in row) for row in sets])
+    cpu = (t["act_type"] == gen.TYPE_CPU) & (want["start_us"] >= 0)
+    assert (bits[cpu] == want["units"][cpu]).all() and (bits[~cpu] == 0).all()
+    _compare(_replay_gpu(tg, t), want, range(3), 500)
+
+
+def test_replay_core_sets_many_cpu_nodes(tg, orc):
+    """More CPU nodes than a wavefront has lanes: the nodes with starts are found 64 at a time."""
+    t = gen.make_trace(S=2, A=1500, seed=860, cluster=(150, 16, 2, 0), type_probs=(0.9, 0.1, 0), rate_per_s=500.0, horizon_s=3.0,
+                       max_ticks=20000, pin_frac=0.2)
+    t["numa_cores"] = 8
+    _compare(_replay_gpu(tg, t), orc.replay(t), range(2), 1500)
