@@ -335,3 +335,14 @@ def test_replay_core_sets_many_cpu_nodes(tg, orc):
                        max_ticks=20000, pin_frac=0.2)
     t["numa_cores"] = 8
     _compare(_replay_gpu(tg, t), orc.replay(t), range(2), 1500)
+
+
+def test_replay_with_named_cores_needs_the_output_map(tg):
+    t = gen.make_trace(S=1, A=20, seed=1, contended=True)
+    t["numa_cores"] = 8
+    T = tg.Trace(t)
+    bufs = T.alloc()
+    bufs["core_set"] = None
+    with pytest.raises(tg.TgError):
+        T.replay(bufs)
+    T.free()
