@@ -193,6 +193,32 @@ def replay_section(a, tg, gen, torch):
             res[name]["queue_prefix"] = {"ms": e0.elapsed_time(e1), "mean_act_us": float(bufs["mean_act_us"].mean().item()),
                                          "started": int(bufs["n_started"].sum().item())}
             T.free()
+            # the same trace with named cores (NUMA domains of 16) and with a second resource per node that binds now and then
+            import numpy as np
+            rng = np.random.default_rng(11)
+            variants = {"named_cores": dict(t, numa_cores=16),
+                        "second_resource": dict(t, act_aux=rng.integers(0, 40, t["S"] * t["A"]).astype(np.int32),
+                                                node_aux=rng.integers(300, 600, t["S"] * t["M"]).astype(np.int32))}
+            for vname, tv in variants.items():
+                T = tg.Trace(tv)
+                bufs = T.alloc()
+                T.replay(bufs)
+                torch.cuda.synchronize()
+                e0.record()
+                T.replay(bufs)
+                e1.record()
+                torch.cuda.synchronize()
+                res[name][vname] = {"ms": e0.elapsed_time(e1), "mean_act_us": float(bufs["mean_act_us"].mean().item()),
+                                    "started": int(bufs["n_started"].sum().item())}
+                if vname == "named_cores":                       # sample: multi-core CPU actions of 8 scenarios whose cores share a domain
+                    n8 = 8 * t["A"]
+                    sets = bufs["core_set"][:4 * n8].cpu().numpy().view(np.uint64).reshape(-1, 4)
+                    units = bufs["units"][:n8].cpu().numpy()
+                    multi = np.flatnonzero((units > 1) & sets.any(axis=1))
+                    one = sum(len({(64 * w + c) // 16 for w in range(4) for c in range(0, 64, 16) if int(sets[g][w]) >> c & 0xffff}) == 1
+                              for g in multi)
+                    res[name][vname].update(multi_core_actions_sampled=int(len(multi)), in_one_domain=int(one))
+                T.free()
     # scheduler ablation (the paper's Fig. 7 on synthetic traces): elastic units against fixed DoP 4 and 16
     t = gen.make_trace(S=64, A=2000, seed=7, cluster=(4, 32, 0, 0), type_probs=(1, 0, 0), rate_per_s=30.0,
                        horizon_s=2000 / 30.0, max_ticks=400000, pin_frac=0.0)
