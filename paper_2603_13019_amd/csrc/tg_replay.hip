@@ -505,7 +505,7 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
         if (sv >= 0) {
           if (!(res0 >> sv & 1ull)) delay = T.restore[sv];
           // the service is resident from now on and the most recently used one (Sec. 5.3, LRU)
-          if (!(res >> sv & 1ull) && __popcll(res) >= T.cache_slots) {
+          if (!(res >> sv & 1ull) && (int)__popcll(res) >= T.cache_slots) {
             int victim = -1;
             for (uint64_t left = res; left; left &= left - 1) {   // ascending id: the smaller one wins ties
               const int y = __builtin_ctzll(left);
