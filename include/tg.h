@@ -309,6 +309,18 @@ typedef struct {
                           numa_cores > 0 (written completely), ignored otherwise                */
 } tg_replay_out;
 
+/*
+ * tg_build_trace validates and packs a trace description like tg_build_problem does a problem
+ * (same error codes; also TG_E_INVALID_ARG for arrivals that are not sorted, a GPU node that does
+ * not have 8 GPUs, more tokens than the bucket holds, an unknown flag) and returns after its copy
+ * to the device; the trace owns only that copy.  tg_replay_trace runs the replay of all S
+ * scenarios: one launch computing Eq. 1 for every action, one persistent workgroup per scenario
+ * (Sec. 4.2's step every tick, see above); all outputs are written completely.  d_ws: device
+ * workspace of at least tg_replay_workspace_bytes(), 256-byte aligned, used by one replay at a
+ * time.  Errors: TG_E_INVALID_ARG (a null output, core_set missing with numa_cores > 0),
+ * TG_E_WORKSPACE, TG_E_RANGE (the node tables of a scenario do not fit the LDS of a compute
+ * unit), TG_E_HIP.
+ */
 int tg_build_trace(const tg_trace_desc *desc, void *hip_stream, tg_trace **out);
 void tg_free_trace(tg_trace *t);
 int tg_replay_workspace_bytes(const tg_trace *t, size_t *bytes);
