@@ -411,15 +411,19 @@ def main():
     if not a.no_cpu_baseline:
         from oracle import orc
         orc.lib()
-        t0 = time.perf_counter()
-        orc.score(p)
-        t_score = time.perf_counter() - t0
-        t0 = time.perf_counter()
-        orc.assign(p)
-        t_assign = time.perf_counter() - t0
+        big = n_cand > 2 * 10**8                                  # workloads 3 and 4: one pass is enough
+        t_score = t_assign = float("inf")
+        for _ in range(1 if big else 4):                          # ~10 s of one host core on workload 2; the best pass counts
+            t0 = time.perf_counter()
+            orc.score(p)
+            t_score = min(t_score, time.perf_counter() - t0)
+            t0 = time.perf_counter()
+            orc.assign(p)
+            t_assign = min(t_assign, time.perf_counter() - t0)
         out["cpu_baseline"] = {
             "value": n_cand / (t_score + t_assign), "unit": "candidates/s", "cores": 1, "kind": "oracle",
-            "sample": f"all {P.B} snapshots of the same workload, one pass (score {t_score:.2f} s + assign {t_assign:.2f} s)",
+            "sample": f"all {P.B} snapshots of the same workload, best of {1 if big else 4} passes "
+                      f"(score {t_score:.2f} s + assign {t_assign:.2f} s)",
             "actions_scheduled_per_sec": n_act / t_assign, "score_candidates_per_sec": n_cand / t_score,
             "host_cores_total": os.cpu_count(),
         }
