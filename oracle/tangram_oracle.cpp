@@ -279,8 +279,8 @@ struct StepOut {
   std::vector<int32_t> extra_used;                    // tokens taken from a quota by actions of other quotas
 };
 
-// Order in which a pool's waiting queue is visited (Sec. 4.2: FCFS in the paper, and the
-// algorithm "can work with other ordering algorithms").  ORDER_COST is one such other order:
+// Order in which a pool's waiting queue is visited (Sec. 4.2: FCFS in the paper, which notes
+// that the algorithm also runs on top of other orderings).  ORDER_COST is one such other order:
 // ascending least estimated ACT (Eq. 2) over the action's candidates at the snapshot, i.e. the
 // smallest entry of its row of the score tensor; equal keys keep their FCFS rank.
 enum { ORDER_FCFS = 0, ORDER_COST = 1 };
