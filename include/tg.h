@@ -41,7 +41,7 @@ extern "C" {
 #define TG_INF INT64_MAX
 
 enum { TG_OK = 0, TG_E_INVALID_ARG = -1, TG_E_RANGE = -2, TG_E_ELASTICITY = -3, TG_E_WORKSPACE = -4,
-       TG_E_HIP = -5, TG_E_NOMEM = -6 };
+       TG_E_HIP = -5, TG_E_NOMEM = -6, TG_E_STATIC_WS = -7 };
 
 /* resource kinds (Sec. 5) and elasticity models of an action (Sec. 4.1, Eq. 1) */
 enum { TG_TYPE_CPU = 0, TG_TYPE_GPU = 1, TG_TYPE_API = 2, TG_N_TYPES = 3 };
@@ -228,6 +228,20 @@ int tg_score_candidates(const tg_problem *p, int64_t *d_cost, void *hip_stream);
  */
 int tg_assign(const tg_problem *p, const int64_t *d_cost, const tg_assign_out *out, void *d_ws, size_t ws_bytes,
               void *hip_stream);
+
+/*
+ * tg_assign for callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments, results
+ * and errors as tg_assign, but the workspace is an array of TG_STATIC_WS_BYTES in the library's own
+ * device data (every GPU the library runs on holds one copy until the process ends); the call
+ * allocates nothing.  A problem whose tg_assign_workspace_bytes() exceeds TG_STATIC_WS_BYTES is
+ * refused with TG_E_STATIC_WS before anything is launched (workload 2, B = 256 x N = 1024, needs
+ * 15 MB).  All calls on one GPU share that GPU's array: it keeps the previous call's contents (the
+ * kernels clear what they need cleared), and two calls in flight on the same GPU at the same time
+ * race - the caller orders them on one stream or with events.
+ */
+#define TG_STATIC_WS_BYTES (32u << 20)
+int tg_assign_static(const tg_problem *p, const int64_t *d_cost, const tg_assign_out *out, void *hip_stream);
 
 /*
  * One whole step in one call: tg_score_candidates and tg_assign for the same problem, the score

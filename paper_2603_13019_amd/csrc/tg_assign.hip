@@ -19,6 +19,7 @@
 // batch of snapshots.  The per-node stage runs as up to three concurrent launches, one per class
 // of candidate count, whose persistent wavefronts pull nodes from class lists.
 #include <algorithm>
+#include <atomic>
 
 #include "tg_step.h"
 
@@ -591,11 +592,52 @@ extern "C" int tg_step(const tg_problem* p, int64_t* d_cost, const tg_assign_out
   return rs ? rs : ra;
 }
 
+// Workspace of tg_assign_static: one array per GPU in the library's own device data, so that the entry
+// point never allocates.  Host code reaches it only through the address hipGetSymbolAddress returns for
+// the current device (the array's name is no device address on the host), looked up once per device.
+static __device__ __align__(256) unsigned char scratch[TG_STATIC_WS_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+int static_workspace(void** ptr) {
+  int dev = -1;
+  TG_HIP_CHECK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return TG_E_HIP;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {                                                       // first call on this device (racing threads find the same address)
+    TG_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p || ((uintptr_t)p & 255)) return TG_E_HIP;
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  *ptr = p;
+  return TG_OK;
+}
+
+int assign_launch(const tg_problem* p, const int64_t* d_cost, const tg_assign_out* out, void* d_ws, hipStream_t s);
+}  // namespace
+
 extern "C" int tg_assign(const tg_problem* p, const int64_t* d_cost, const tg_assign_out* out, void* d_ws,
                          size_t ws_bytes, void* hip_stream) {
   const int rc_args = check_assign_args(p, out, d_ws, ws_bytes);
   if (rc_args) return rc_args;
-  hipStream_t s = (hipStream_t)hip_stream;
+  return assign_launch(p, d_cost, out, d_ws, (hipStream_t)hip_stream);
+}
+
+extern "C" int tg_assign_static(const tg_problem* p, const int64_t* d_cost, const tg_assign_out* out, void* hip_stream) {
+  if (!p) return TG_E_INVALID_ARG;
+  if (carve(p, nullptr, nullptr) > (size_t)TG_STATIC_WS_BYTES) return TG_E_STATIC_WS;
+  void* ws = nullptr;
+  const int rc_ws = static_workspace(&ws);
+  if (rc_ws) return rc_ws;
+  const int rc_args = check_assign_args(p, out, ws, TG_STATIC_WS_BYTES);
+  if (rc_args) return rc_args;
+  return assign_launch(p, d_cost, out, ws, (hipStream_t)hip_stream);
+}
+
+namespace {
+int assign_launch(const tg_problem* p, const int64_t* d_cost, const tg_assign_out* out, void* d_ws, hipStream_t s) {
   const TgDev& P = p->dev;
   AssignWs W;
   carve(p, (char*)d_ws, &W);
@@ -708,3 +750,4 @@ extern "C" int tg_assign(const tg_problem* p, const int64_t* d_cost, const tg_as
   hipLaunchKernelGGL(tg_summary_kernel, dim3(P.B), dim3(256), 0, s, P, *out);
   return hipGetLastError() == hipSuccess ? TG_OK : TG_E_HIP;
 }
+}  // namespace

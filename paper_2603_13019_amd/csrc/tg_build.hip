@@ -63,6 +63,7 @@ extern "C" const char* tg_strerror(int code) {
     case TG_E_WORKSPACE: return "workspace missing, misaligned or too small";
     case TG_E_HIP: return "HIP runtime call failed";
     case TG_E_NOMEM: return "out of memory";
+    case TG_E_STATIC_WS: return "the problem needs more workspace than the library's static buffer holds";
     default: return "unknown error";
   }
 }
