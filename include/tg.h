@@ -21,9 +21,10 @@
  *     their host-to-device copies have completed).  Results are valid once the caller has
  *     synchronised the stream.
  *   - A tg_problem / tg_trace is immutable after it is built and owns only its packed device
- *     copy of the inputs (plus, for a tg_problem, three internal streams and their events on
- *     which tg_assign and tg_step run part of their work, forked from and joined back into `hip_stream`).
- *     No other entry point allocates device memory.  Launches that use the same tg_problem may
+ *     copy of the inputs (plus, for a tg_problem, a scratch array of one int64 per (action, option)
+ *     into which every tg_score_candidates / tg_step call writes the same durations, and three internal
+ *     streams and their events on which tg_assign and tg_step run part of their work, forked from and
+ *     joined back into `hip_stream`).  No other entry point allocates device memory.  Launches that use the same tg_problem may
  *     be in flight together (each with its own outputs and workspace), but the host calls that
  *     enqueue them must not overlap: one thread at a time per tg_problem.
  *   - Index of an action inside its snapshot == its first-come rank == its action id.

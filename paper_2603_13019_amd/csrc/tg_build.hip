@@ -198,9 +198,8 @@ extern "C" int tg_build_problem(const tg_problem_desc* desc, void* hip_stream, t
   }
 
   const size_t nN = (size_t)B * M, nA = (size_t)B * N;
-  tg_problem* p = new (std::nothrow) tg_problem();
+  tg_problem* p = new (std::nothrow) tg_problem();                  // value-initialised: every plain member is zero
   if (!p) return TG_E_NOMEM;
-  std::memset(p, 0, sizeof *p);
   Arena ar;
   try {
     // ---------------- nodes
@@ -355,8 +354,9 @@ extern "C" int tg_build_problem(const tg_problem_desc* desc, void* hip_stream, t
     // ---------------- blocks of the score tensor and the score kernel's work split
     const size_t o_blocks = ar.add((size_t)B * 3 * sizeof(TgBlock));
     const size_t o_rowrec = ar.add(nA * sizeof(TgRowRec)), o_rowpin = ar.add(nA * 4), o_nword = ar.add(nN * 8);
-    int64_t total = 0, wgs = 0;
-    int lds_nodes = 1, dur_slots = 2, row_slots = 2;
+    const size_t o_snaps = ar.add((size_t)B * sizeof(TgScoreSnap));
+    int64_t total = 0;
+    std::vector<int32_t> snap_chunks((size_t)B, 0);
     for (int b = 0; b < B; ++b)
       for (int t = 0; t < 3; ++t) {
         TgBlock& k = ar.at<TgBlock>(o_blocks)[(size_t)b * 3 + t];
@@ -367,18 +367,16 @@ extern "C" int tg_build_problem(const tg_problem_desc* desc, void* hip_stream, t
         k.entries = (int64_t)k.rows * k.M_t * k.K_t;
         if (k.entries >= (1ll << 31) - (1 << 20)) { delete p; return TG_E_RANGE; }   // 32-bit indices inside a block
         const uint32_t lr = (uint32_t)(k.M_t * k.K_t);
-        k.magic_lr = lr > 1 ? (uint32_t)((1ull << 32) / lr) + 1u : 0u;
-        k.magic_k = k.K_t > 1 ? (uint32_t)((1ull << 32) / (uint32_t)k.K_t) + 1u : 0u;
         k.cost_off = total;
-        k.wg_off = (int32_t)wgs;
-        wgs += (k.entries ? (k.entries + (k.cost_off & 1) + TG_SCORE_SPAN - 1) / TG_SCORE_SPAN : 0);
         total += k.entries;
+        TgScoreKind& sk = ar.at<TgScoreSnap>(o_snaps)[b].kind[t];
+        sk.cost_off = k.cost_off; sk.inv_lr = lr ? 1.0 / (double)lr : 0.0; sk.entries = (int32_t)k.entries;
+        sk.a_off = k.a_off; sk.n_off = k.n_off; sk.M_t = (uint16_t)k.M_t; sk.K_t = (uint16_t)k.K_t;
+        sk.magic_k = k.K_t ? (1u << 20) / (uint32_t)k.K_t + 1u : 0u; sk.rows = k.rows;
         if (k.entries) {
-          const int rows = (int)std::min<int64_t>(TG_SCORE_SPAN / lr + 2, k.rows);
-          lds_nodes = std::max<int>(lds_nodes, k.M_t);   // a span that crosses a row end needs every node
-          row_slots = std::max(row_slots, rows);
-          dur_slots = std::max(dur_slots, rows * k.K_t);
+          snap_chunks[b] += (int32_t)((k.entries + (k.cost_off & 1) + TG_SCORE_CHUNK - 1) / TG_SCORE_CHUNK);
         }
+        if (t == 2) ar.at<TgScoreSnap>(o_snaps)[b].chunks = snap_chunks[b];
         // kind-grouped views: row of every action, pin rank per row, node word per rank
         for (int r = 0; r < k.rows; ++r) {
           const int i = ar.at<int32_t>(o_taidx)[(size_t)b * N + ta[t] + r];
@@ -403,22 +401,52 @@ extern "C" int tg_build_problem(const tg_problem_desc* desc, void* hip_stream, t
           if (svc) ar.at<uint64_t>(o_nresk)[(size_t)b * M + tn[t] + r] = d->node_resident[g];
         }
       }
-    if (wgs >= (1ll << 31)) { delete p; return TG_E_RANGE; }
-    // workgroup -> block lookup of the score kernel (one load instead of a search)
-    const size_t o_wgtab = ar.add(std::max<size_t>((size_t)wgs, 1) * 4);
-    for (int x = 0; x < B * 3; ++x) {
-      const TgBlock& k = ar.at<TgBlock>(o_blocks)[x];
-      const int64_t n = (k.entries ? (k.entries + (k.cost_off & 1) + TG_SCORE_SPAN - 1) / TG_SCORE_SPAN : 0);
-      for (int64_t w = 0; w < n; ++w) ar.at<int32_t>(o_wgtab)[k.wg_off + w] = x;
+    // The score kernel runs on a grid (chunk, snapshot) as wide as the largest snapshot of the launch: one launch
+    // over all snapshots in index order (workgroups then start in the order of the tensor) unless that leaves more
+    // than an eighth of the grid without a chunk; then the snapshots are sorted by size and launched in groups
+    // inside which the same bound holds.
+    std::vector<TgScoreLaunch> launches;
+    auto add_launch = [&](int first, int count, int max_chunks) {     // the grid's second dimension holds at most 65535 snapshots
+      for (int x = 0; x < count; x += 65535) launches.push_back({first + x, std::min(65535, count - x), max_chunks});
+    };
+    {
+      int64_t sum = 0;
+      int mx = 0;
+      for (int b = 0; b < B; ++b) { sum += snap_chunks[b]; mx = std::max(mx, snap_chunks[b]); }
+      const int64_t slack = 4096;
+      if (mx > 0 && (int64_t)mx * B <= sum + sum / 8 + slack) add_launch(0, B, mx);
+      else if (mx > 0) {
+        std::vector<int> order((size_t)B);
+        for (int b = 0; b < B; ++b) order[b] = b;
+        std::stable_sort(order.begin(), order.end(), [&](int a, int c) { return snap_chunks[a] > snap_chunks[c]; });
+        std::vector<TgScoreSnap> sorted((size_t)B);
+        for (int x = 0; x < B; ++x) sorted[x] = ar.at<TgScoreSnap>(o_snaps)[order[x]];
+        std::memcpy(ar.at<TgScoreSnap>(o_snaps), sorted.data(), (size_t)B * sizeof(TgScoreSnap));
+        int first = 0;
+        while (first < B && sorted[first].chunks > 0) {
+          const int gmax = sorted[first].chunks;
+          int64_t gsum = 0;
+          int x = first;
+          while (x < B && sorted[x].chunks > 0) {                   // extend while the group's grid stays mostly full
+            const int64_t s2 = gsum + sorted[x].chunks, cnt = x - first + 1;
+            if ((int64_t)gmax * cnt > s2 + s2 / 8 + slack) break;
+            gsum = s2; ++x;
+          }
+          add_launch(first, x - first, gmax);
+          first = x;
+        }
+      }
     }
 
     // ---------------- ship
     p->arena_bytes = ar.host.size();
+    if (nA * (size_t)K >= (1ull << 31)) { delete p; return TG_E_RANGE; }        // (action, option) pairs are indexed in 32 bits
     if (hipMalloc(&p->d_arena, p->arena_bytes) != hipSuccess) { delete p; return TG_E_NOMEM; }
+    if (hipMalloc((void**)&p->d_score_dur, std::max<size_t>(nA * K, 1) * 8) != hipSuccess) { (void)hipFree(p->d_arena); delete p; return TG_E_NOMEM; }
     hipStream_t s = (hipStream_t)hip_stream;
     if (hipMemcpyAsync(p->d_arena, ar.host.data(), ar.host.size(), hipMemcpyHostToDevice, s) != hipSuccess ||
         hipStreamSynchronize(s) != hipSuccess) {
-      (void)hipFree(p->d_arena); delete p; return TG_E_HIP;
+      (void)hipFree(p->d_arena); (void)hipFree(p->d_score_dur); delete p; return TG_E_HIP;
     }
     bool ok = hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming) == hipSuccess;
     for (int i = 0; i < 2 && ok; ++i)
@@ -461,9 +489,9 @@ extern "C" int tg_build_problem(const tg_problem_desc* desc, void* hip_stream, t
     v.row_rec = (const TgRowRec*)(base + o_rowrec); v.row_pin = (const int32_t*)(base + o_rowpin);
     v.node_word = (const uint64_t*)(base + o_nword);
     p->d_blocks = (TgBlock*)(base + o_blocks);
-    p->d_wg_block = (const int32_t*)(base + o_wgtab);
+    p->d_score_snaps = (const TgScoreSnap*)(base + o_snaps);
+    p->score_launches = launches;
     p->n_blocks = B * 3;
-    p->score_wgs = (int)wgs;
     p->n_candidates = total;
     p->max_nodes_of_kind = max_kind;
     p->order_policy = d->order_policy; p->queue_prefix = d->queue_prefix; p->max_actions_of_kind = max_acts_kind;
@@ -472,7 +500,7 @@ extern "C" int tg_build_problem(const tg_problem_desc* desc, void* hip_stream, t
     p->nodes_free_gt16 = free_gt16; p->nodes_free_gt64 = free_gt64;
     p->max_free_gpu = max_free_gpu;
     p->max_chunk_states = max_states;
-    p->score_lds_nodes = lds_nodes; p->score_dur_slots = (dur_slots + 1) & ~1; p->score_row_slots = row_slots;
+
   } catch (const std::bad_alloc&) {
     tg_free_problem(p);
     return TG_E_NOMEM;
@@ -484,6 +512,7 @@ extern "C" int tg_build_problem(const tg_problem_desc* desc, void* hip_stream, t
 extern "C" void tg_free_problem(tg_problem* p) {
   if (!p) return;
   if (p->d_arena) (void)hipFree(p->d_arena);
+  if (p->d_score_dur) (void)hipFree(p->d_score_dur);
   for (int i = 0; i < 2; ++i) {
     if (p->side_stream[i]) (void)hipStreamDestroy(p->side_stream[i]);
     if (p->ev_join[i]) (void)hipEventDestroy(p->ev_join[i]);

@@ -5,10 +5,13 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
+#include <vector>
+
 #include "tg.h"
 
 #define TG_WAVE 64
-#define TG_SCORE_SPAN 4096  // entries of the score tensor per workgroup: 8 steps of 256 lanes x 2 entries
+#define TG_SCORE_CHUNK 512  // entries of the score tensor per workgroup (4 KB): 128 lanes x 2 pairs
 
 // Packed device copy of a problem.  Passed to kernels by value; all pointers are device memory.
 struct TgDev {
@@ -71,12 +74,34 @@ struct TgRowRec {
 struct TgBlock {
   int64_t cost_off;   // first entry of the block in the tensor
   int64_t entries;    // rows * M_t * K_t  (< 2^31)
-  int32_t wg_off;     // first workgroup of the score kernel that works on this block
   int32_t rows, M_t, K_t, b, t;
   int32_t a_off;      // b*N + first action of the kind in the kind-grouped order
   int32_t n_off;      // b*M + first node of the kind in the kind-grouped order
-  uint32_t magic_lr;  // floor(2^32 / (M_t*K_t)) + 1: x / (M_t*K_t) == umulhi(x, magic) for the x used
-  uint32_t magic_k;   // same for K_t
+};
+
+// What the score kernel needs of one block, and the three blocks of a snapshot in one record
+// that a workgroup reads with a single uniform load.
+struct TgScoreKind {
+  int64_t cost_off;   // first entry of the block in the tensor
+  double inv_lr;      // 1 / (M_t * K_t)
+  int32_t entries;    // rows * M_t * K_t, 0: no such block
+  int32_t a_off, n_off;   // as TgBlock
+  uint16_t M_t, K_t;
+  uint32_t magic_k;   // floor(2^20 / K_t) + 1: x / K_t == (x * magic_k) >> 20 for x < 2^17
+  int32_t rows;       // actions of the kind
+};
+static_assert(sizeof(TgScoreKind) == 40, "three of them and eight more bytes make a snapshot's record");
+struct TgScoreSnap {
+  TgScoreKind kind[3];
+  int32_t chunks;     // workgroups that cover the three blocks
+  int32_t pad_;
+};
+static_assert(sizeof(TgScoreSnap) == 128, "one record per snapshot, read as two 64-byte scalar loads");
+
+// One launch of the score kernel: snapshots first .. first + n_snaps of the record array on a
+// grid of max_chunks x n_snaps workgroups.
+struct TgScoreLaunch {
+  int first, n_snaps, max_chunks;
 };
 
 struct tg_problem {
@@ -84,9 +109,9 @@ struct tg_problem {
   void* d_arena;
   size_t arena_bytes;
   TgBlock* d_blocks;       // inside the arena
-  const int32_t* d_wg_block;  // score kernel: workgroup -> block index
   int n_blocks;
-  int score_wgs;
+  const TgScoreSnap* d_score_snaps;          // inside the arena, in launch order
+  std::vector<TgScoreLaunch> score_launches; // usually one: all snapshots in index order
   int64_t n_candidates;
   // tg_assign runs the node classes side by side: two side streams (default priority) forked
   // from and joined back into the caller's stream with events
@@ -103,9 +128,16 @@ struct tg_problem {
   int max_heap;            // largest free + busy over CPU and GPU nodes
   size_t nodes_free_gt16, nodes_free_gt64;   // nodes with more than 16 / 64 free units: bounds on the nodes that can hold as many candidates
   int max_free_gpu, max_chunk_states;
-  int score_lds_nodes;     // largest node table a score workgroup stages
-  int score_dur_slots, score_row_slots;   // (row, option) durations and rows one workgroup may touch
+  int64_t* d_score_dur;    // [B*N*K] scratch of tg_score_candidates: getDur per (kind-grouped row, option); every call
+                           // writes the same values, so calls that overlap do not disturb each other
 };
+
+// the unit counts k_list[0..8), one byte each
+__host__ __device__ static inline uint64_t tg_pack_k(const int* k_list) {
+  uint64_t w = 0;
+  for (int q = 0; q < TG_MAX_K; ++q) w |= (uint64_t)(uint32_t)k_list[q] << (8 * q);
+  return w;
+}
 
 __host__ __device__ static inline int tg_chunk_level(int k) { return k <= 1 ? 0 : (k <= 2 ? 1 : (k <= 4 ? 2 : 3)); }
 
@@ -114,7 +146,12 @@ __host__ __device__ static inline int tg_chunk_level(int k) { return k <= 1 ? 0 
 // A double-precision reciprocal gives the quotient to within a few units; the remainder test
 // makes it exact.
 __device__ static inline int64_t tg_ceil_div(uint64_t num, uint32_t den) {
-  uint64_t q = (uint64_t)((double)num * (1.0 / (double)den));
+  // reciprocal: the hardware estimate refined by two Newton steps (any small error is removed below)
+  const double dd = (double)den;
+  double inv = __builtin_amdgcn_rcp(dd);
+  inv = __builtin_fma(__builtin_fma(-dd, inv, 1.0), inv, inv);
+  inv = __builtin_fma(__builtin_fma(-dd, inv, 1.0), inv, inv);
+  uint64_t q = (uint64_t)((double)num * inv);
   int64_t r = (int64_t)(num - q * (uint64_t)den);
   while (r < 0) { --q; r += den; }
   while (r >= (int64_t)den) { ++q; r -= den; }

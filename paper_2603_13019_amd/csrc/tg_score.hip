@@ -2,141 +2,243 @@
 // candidate - Eq. 1 (duration on k units) inside Eq. 2 (queueing + execution) of the paper -
 // written as one dense int64 tensor.
 //
-// The kernel is a pure write stream (8 bytes per candidate, inputs are ~0.1 byte per
-// candidate), so it is organised around 16-byte fully coalesced stores:
-//   * a workgroup (256 lanes) owns one contiguous span of 4096 entries of one (snapshot, kind)
-//     block; one table lookup tells it which;
-//   * it evaluates Eq. 1 once per (row, option) of its span into LDS from kind-grouped 16-byte
-//     action records, and stages the node words (backlog | options the capacity admits) and the
-//     pin ranks of its rows - all prepared at build time, so the dependent-load chain before
-//     the first store is three loads deep;
-//   * then every lane walks the span in 8 steps of 512 entries, two adjacent entries (one
-//     16-byte non-temporal store) per lane and step, keeping its (row, node, option)
-//     coordinates by mixed-radix increments.
+// Two kernels.  tg_score_dur_kernel evaluates Eq. 1 once per (action, option) into a scratch
+// array of the problem (0.6 % of the tensor's size).  tg_score_kernel then is a pure write
+// stream (8 bytes per candidate; its inputs are ~0.1 byte per candidate and come from cache).
+// On this memory system such a stream runs fastest as short-lived workgroups that each write
+// 4 KB and are dispatched in address order, so that the chip as a whole writes one moving window
+// of a few MB; what a workgroup does before its stores must then stay short, because nothing
+// amortises it - which is why the divisions of Eq. 1 are not done here:
+//   * a workgroup is 128 lanes (up to 16 resident per compute unit) and owns 512 consecutive
+//     entries of one (snapshot, kind) block; each lane stores two 16-byte pairs;
+//   * the launch is a grid (chunk, snapshot): the three blocks of a snapshot sit in one
+//     128-byte record, read with one uniform load; a comparison of the chunk index with the
+//     blocks' chunk counts picks the block - no per-workgroup lookup table, and workgroups are
+//     dispatched in the order of the tensor.  Snapshots of unequal size leave some workgroups
+//     of the grid without a chunk (they exit at once); very unequal snapshots are launched in
+//     groups of similar size;
+//   * after that one load everything a lane needs - node word, duration and pin of each of its
+//     four entries - is fetched in a single further round trip; no LDS, no barrier.
+#include <cstddef>
+
 #include "tg_internal.h"
 
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kStep = 2 * kThreads;
+constexpr int kThreads = 128;
+static_assert(TG_SCORE_CHUNK == 4 * kThreads, "every lane stores two pairs of entries");
+
+// The few fields of a problem the kernels read (a short argument list: its loads are the first
+// thing every workgroup waits for).
+struct ScoreArgs {
+  const TgScoreSnap* snaps;       // this launch's snapshots
+  const TgRowRec* row_rec;
+  const int32_t* row_pin;
+  const uint64_t* node_word;
+  const uint64_t* row_svc;        // SVC only
+  const uint64_t* node_res_k;     // SVC only
+  const uint32_t* speedup;
+  int64_t* dur;                   // [rows * K] getDur per (kind-grouped row, option), TG_INF where not allowed
+  int64_t* cost;
+  uint64_t kword;                 // unit counts, one byte each
+  int K;                          // options per row of dur and of the speedup table
+  uint32_t magic_K;               // floor(2^32 / K) + 1
+  uint32_t n_rows_K;              // rows * K
+};
+
+// x / d for x < 2^31, with inv = 1.0 / d: the product is within 2^-21 of the true quotient, so
+// its integer part is the quotient or one below; the remainder test makes it exact.
+__device__ inline uint32_t div_u31(uint32_t x, uint32_t d, double inv) {
+  uint32_t q = (uint32_t)((double)x * inv);
+  const uint32_t r = x - q * d;
+  if (r >= d) q += (int32_t)r < 0 ? -1 : 1;
+  return q;
+}
+
+// Eq. 1 for every (row, option), rows in kind-grouped order; one lane per pair.  The three
+// elasticity models are three (numerator, denominator) pairs of the same rounded-up division,
+// so the lanes of a wavefront do not diverge on the model.
+__global__ __launch_bounds__(256) void tg_score_dur_kernel(const ScoreArgs A) {
+  const uint32_t x = blockIdx.x * 256u + threadIdx.x;
+  if (x >= A.n_rows_K) return;
+  uint32_t g = A.K == 1 ? x : __umulhi(x, A.magic_K);                     // x / K, at most one too large
+  if (g * (uint32_t)A.K > x) --g;
+  const int q = (int)(x - g * (uint32_t)A.K);
+  const TgRowRec rec = A.row_rec[g];
+  const bool amdahl = rec.model == TG_MODEL_AMDAHL, table = rec.model == TG_MODEL_TABLE;
+  const uint32_t k = (uint32_t)(A.kword >> (8 * q) & 0xff);
+  const uint32_t sp = A.speedup[table ? rec.param * (uint32_t)A.K + (uint32_t)q : 0u];
+  const uint32_t w = (1000000u - rec.param) * k + rec.param;             // < 2^26
+  const uint64_t num = amdahl ? (uint64_t)rec.T * w : table ? (uint64_t)rec.T << 16 : (uint64_t)rec.T;
+  const uint32_t den = amdahl ? 1000000u * k : table ? sp : 1u;
+  const int64_t d = tg_ceil_div(num, den);
+  A.dur[x] = (rec.kmask >> q & 1u) ? (d < 1 ? 1 : d) : TG_INF;
+}
+
+// v of lane `src` (any lane may ask for any lane's value)
+__device__ inline int64_t lane_pick64(int64_t v, int src) {
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_ds_bpermute(src * 4, (int)(uint32_t)v);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_ds_bpermute(src * 4, (int)(uint32_t)((uint64_t)v >> 32));
+  return (int64_t)((uint64_t)hi << 32 | lo);
+}
+
+constexpr int kKindWords = sizeof(TgScoreKind) / 4;   // cost_off, inv_lr, entries, a_off, n_off, M_t | K_t << 16, magic_k, rows
+static_assert(kKindWords == 10 && offsetof(TgScoreKind, entries) == 16 && offsetof(TgScoreKind, M_t) == 28 &&
+              offsetof(TgScoreKind, K_t) == 30 && offsetof(TgScoreKind, rows) == 36, "the kernel reads the record word by word");
+
+// One chunk (number x) of 512 entries of the block whose record words are k.  FAST: see tg_score_kernel.
+template <bool SVC, bool FAST>
+__device__ inline void score_chunk(const ScoreArgs& A, const uint32_t (&k)[kKindWords], int x) {
+  const int64_t cost_off = (int64_t)((uint64_t)k[1] << 32 | k[0]);
+  const double inv_lr = __builtin_bit_cast(double, (uint64_t)k[3] << 32 | k[2]);
+  const int n = (int)k[4], a_off = (int)k[5], n_off = (int)k[6], row_last = (int)k[9] - 1;
+  const int Mt = (int)(k[7] & 0xffffu), K = (int)(k[7] >> 16);
+  const uint32_t mk = k[8];
+  const uint32_t Lr = (uint32_t)(Mt * K);
+  // Lanes own adjacent pairs aligned to 16 bytes in the whole tensor: when the block starts at
+  // an odd entry the chunks are shifted down by one and entry -1 does not exist.
+  const int odd = (int)(cost_off & 1);
+  const int e0 = x * TG_SCORE_CHUNK - odd;                                // may be -1
+  const int e1 = min(n, e0 + TG_SCORE_CHUNK);
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int w0 = e0 + wave * 256;                                         // first pair of this wavefront
+  if (w0 >= e1) return;                                                   // nothing left for it in the block
+  const int f0 = w0 < 0 ? 0 : w0;                                         // its first existing entry
+  const int row0 = (int)div_u31((uint32_t)f0, Lr, inv_lr);
+  const uint32_t col0 = (uint32_t)f0 - (uint32_t)row0 * Lr;               // place of entry f0 in its row
+
+  const uint64_t* words = A.node_word + n_off;
+  const uint64_t* resk = SVC ? A.node_res_k + n_off : nullptr;
+  const int64_t* dur = A.dur + (size_t)a_off * A.K;
+  const int32_t* pins = A.row_pin + a_off;
+  const uint64_t* rsvc = SVC ? A.row_svc + a_off : nullptr;
+  // FAST: the wavefront's entries lie in two rows.  Lane z < 2K fetches getDur of (row z / K, option z % K), lanes 0
+  // and 1 the pins of the two rows; every lane then picks what its entries need out of those lanes' registers
+  // (one data exchange inside the wavefront instead of a load per entry).
+  int64_t dv = 0;
+  uint64_t sv2 = 0;
+  int pv = 0;
+  if (FAST) {
+    const int r = lane >= K ? 1 : 0;
+    const int rd = min(row0 + r, row_last), rp = min(row0 + (lane & 1), row_last);
+    if (lane < 2 * K) dv = dur[(size_t)rd * A.K + (lane - r * K)];
+    if (lane < 2) { pv = pins[rp]; if (SVC) sv2 = rsvc[rp]; }
+  }
+
+  // values of both pairs first, then the two stores back to back (nothing is waited for between them)
+  int64_t v[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int p = w0 + i * 128 + 2 * lane;
+    const int pa = min(max(p, 0), n - 1);                                 // coordinates are taken inside the block
+    int row;
+    uint32_t col;
+    if (FAST) {                                                           // the wavefront crosses at most one row end
+      col = col0 + (uint32_t)(pa - f0);
+      const bool wrap = col >= Lr;
+      col -= wrap ? Lr : 0u;
+      row = row0 + (wrap ? 1 : 0);
+    } else {
+      row = (int)div_u31((uint32_t)pa, Lr, inv_lr);
+      col = (uint32_t)pa - (uint32_t)row * Lr;
+    }
+    const int j = (int)((col * mk) >> 20);                                // col / K: exact for col < 2^17
+    const int q = (int)col - j * K;
+    // the second entry of the pair is one step on - unless entry p = -1 does not exist: then entry 0 is the second
+    const bool step = p >= 0;
+    const bool wq = step && q + 1 == K, wj = wq && j + 1 == Mt;
+    const int q2 = wq ? 0 : q + (step ? 1 : 0), j2 = wj ? 0 : j + (wq ? 1 : 0);
+    const int row2 = min(row + (wj ? 1 : 0), row_last);                   // an entry past the end is not stored
+    const int rows[2] = {row, row2}, js[2] = {j, j2}, qs[2] = {q, q2};
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      uint64_t nw, res = 0, sw = 0;
+      int64_t d;
+      int pin;
+      if (FAST) {
+        const int rl = rows[h] - row0;
+        nw = words[js[h]];
+        d = lane_pick64(dv, rl * K + qs[h]); pin = __builtin_amdgcn_ds_bpermute(rl * 4, pv);
+        if (SVC) { res = resk[js[h]]; sw = (uint64_t)lane_pick64((int64_t)sv2, rl); }
+      } else {
+        nw = words[js[h]]; d = dur[(size_t)rows[h] * A.K + qs[h]]; pin = pins[rows[h]];
+        if (SVC) { res = resk[js[h]]; sw = rsvc[rows[h]]; }
+      }
+      const bool ok = (d != TG_INF) & (qs[h] < (int)(nw >> 48)) & ((pin == -1) | (pin == js[h]));   // no short cut: no load waits for another
+      int64_t val = ok ? (int64_t)(nw & 0xffffffffffffull) + d : TG_INF;
+      if (SVC && ok) {
+        const int sv = (int)(sw >> 48);                                    // service + 1, 0: none
+        if (sv && !(res >> (sv - 1) & 1ull)) val += (int64_t)(sw & 0xffffffffffffull);
+      }
+      v[i][h] = val;
+    }
+  }
+  int64_t* out = A.cost + cost_off;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int p = w0 + i * 128 + 2 * lane;
+    const bool ok0 = p >= 0 && p < e1, ok1 = p + 1 < e1;
+    if (ok0 && ok1) {
+      int64_t __attribute__((ext_vector_type(2))) pv = {v[i][0], v[i][1]};
+      __builtin_nontemporal_store(pv, reinterpret_cast<int64_t __attribute__((ext_vector_type(2)))*>(out + p));
+    } else {
+      if (ok0) __builtin_nontemporal_store(v[i][0], out + p);
+      if (ok1) __builtin_nontemporal_store(v[i][1], out + p + 1);
+    }
+  }
+}
 
 // SVC: the problem has services (Sec. 5.3): an entry whose action calls a service that is not
 // resident on the node carries the service's restore time on top of Eq. 2.
 template <bool SVC>
-__global__ __launch_bounds__(kThreads) void tg_score_kernel(TgDev P, const TgBlock* __restrict__ blocks,
-                                                            const int32_t* __restrict__ wg_block, int lds_nodes,
-                                                            int dur_slots, int row_slots, int64_t* __restrict__ cost) {
-  extern __shared__ __align__(16) unsigned char smem[];
-  int64_t* s_dur = reinterpret_cast<int64_t*>(smem);                    // [dur_slots]
-  uint64_t* s_node = reinterpret_cast<uint64_t*>(s_dur + dur_slots);     // [lds_nodes]
-  uint64_t* s_res = s_node + lds_nodes;                                  // [lds_nodes]  services resident on the node   (SVC)
-  uint64_t* s_rsvc = s_res + (SVC ? lds_nodes : 0);                      // [row_slots]  restore time | (service+1) << 48 (SVC)
-  int32_t* s_pin = reinterpret_cast<int32_t*>(s_rsvc + (SVC ? ((row_slots + 1) & ~1) : 0));   // [row_slots]
-
-  const int wg = blockIdx.x;
-  const TgBlock blk = blocks[wg_block[wg]];
-  const int K = blk.K_t, Mt = blk.M_t;
-  const uint32_t Lr = (uint32_t)(Mt * K);
-  // Every block has fewer than 2^31 entries, so all index arithmetic is 32-bit.  Lanes own
-  // adjacent pairs aligned to 16 bytes in the whole tensor: when the block starts at an odd
-  // entry the spans are shifted down by one and entry -1 does not exist.
-  const int n = (int)blk.entries;
-  const int odd = (int)(blk.cost_off & 1);
-  const int e0 = (wg - blk.wg_off) * TG_SCORE_SPAN - odd;              // may be -1
-  const int e1 = min(n, e0 + TG_SCORE_SPAN);
-  const int f0 = e0 < 0 ? 0 : e0;                                       // first existing entry
-  const int row0 = (int)((uint32_t)f0 / Lr), row1 = (int)((uint32_t)(e1 - 1) / Lr);
-  const int nrows = row1 - row0 + 1;
-  // node window: a single partial row needs only the nodes it touches
-  int j0 = 0, j1 = Mt - 1;
-  if (nrows == 1) { j0 = (int)(((uint32_t)f0 - (uint32_t)row0 * Lr) / (uint32_t)K); j1 = (int)(((uint32_t)(e1 - 1) - (uint32_t)row0 * Lr) / (uint32_t)K); }
-
-  const TgRowRec* recs = P.row_rec + blk.a_off + row0;
-  const int32_t* pins = P.row_pin + blk.a_off + row0;
-  const uint64_t* words = P.node_word + blk.n_off;
-  const int tid = threadIdx.x;
-
-  for (int x = tid; x < nrows * K; x += kThreads) {
-    const int r = x / K, q = x - r * K;
-    const TgRowRec rec = recs[r];
-    int64_t d = TG_INF;
-    if (rec.kmask >> q & 1u) {
-      const uint32_t sp = rec.model == TG_MODEL_TABLE ? P.speedup[rec.param * P.K + q] : 0u;
-      d = tg_duration(rec.model, rec.T, rec.param, P.k_list[q], sp);
-    }
-    s_dur[x] = d;
-  }
-  for (int r = tid; r < nrows; r += kThreads) s_pin[r] = pins[r];
-  for (int j = j0 + tid; j <= j1; j += kThreads) s_node[j - j0] = words[j];
-  if (SVC) {
-    for (int r = tid; r < nrows; r += kThreads) s_rsvc[r] = P.row_svc[blk.a_off + row0 + r];
-    for (int j = j0 + tid; j <= j1; j += kThreads) s_res[j - j0] = P.node_res_k[blk.n_off + j];
-  }
-  __syncthreads();
-
-  int64_t* out = cost + blk.cost_off;
-  // coordinates of this lane's first entry, and of a step of 512 entries, in radix (row, Mt, K)
-  int e = e0 + 2 * tid;
-  const uint32_t ec = (uint32_t)(e < 0 ? 0 : e);
-  int row = (int)(ec / Lr);
-  const uint32_t col = ec - (uint32_t)row * Lr;
-  int j = (int)(col / (uint32_t)K), q = (int)(col - (uint32_t)j * (uint32_t)K);
-  if (e < 0 && --q < 0) {                                              // step back to the entry before the block
-    q = K - 1;
-    if (--j < 0) { j = Mt - 1; --row; }
-  }
-  const int srow = (int)((uint32_t)kStep / Lr), srem = kStep - srow * (int)Lr, sj = srem / K, sq = srem - sj * K;
-
-  for (; e < e1; e += kStep) {
-    int64_t v[2];
-    int rr = row, jj = j, qq = q;
+__global__ __launch_bounds__(kThreads) void tg_score_kernel(const ScoreArgs A) {
+  // one uniform 128-byte load (the records are never written while a problem exists: constant
+  // address space, scalar loads); every word stays in a scalar register
+  typedef const __attribute__((address_space(4))) uint32_t* ConstWords;
+  ConstWords src = (ConstWords)(A.snaps + blockIdx.y);
+  uint32_t w[3 * kKindWords];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      if (h == 1) {
-        if (++qq == K) { qq = 0; if (++jj == Mt) { jj = 0; ++rr; } }
-      }
-      int64_t val = TG_INF;
-      if (e + h >= 0 && e + h < e1) {
-        const uint64_t nw = s_node[jj - j0];
-        const int64_t d = s_dur[(rr - row0) * K + qq];
-        const int pin = s_pin[rr - row0];
-        const bool ok = d != TG_INF && qq < (int)(nw >> 48) && (pin == -1 || pin == jj);
-        if (ok) val = (int64_t)(nw & 0xffffffffffffull) + d;
-        if (SVC && ok) {
-          const uint64_t sw = s_rsvc[rr - row0];
-          const int sv = (int)(sw >> 48);                                // service + 1, 0: none
-          if (sv && !(s_res[jj - j0] >> (sv - 1) & 1ull)) val += (int64_t)(sw & 0xffffffffffffull);
-        }
-      }
-      v[h] = val;
-    }
-    if (e >= 0 && e + 1 < e1) {
-      int64_t __attribute__((ext_vector_type(2))) pv = {v[0], v[1]};
-      __builtin_nontemporal_store(pv, reinterpret_cast<int64_t __attribute__((ext_vector_type(2)))*>(out + e));
-    } else {
-      if (e >= 0) __builtin_nontemporal_store(v[0], out + e);
-      if (e + 1 < e1) __builtin_nontemporal_store(v[1], out + e + 1);
-    }
-    // advance by one step
-    q += sq; if (q >= K) { q -= K; ++j; }
-    j += sj; if (j >= Mt) { j -= Mt; ++row; }
-    row += srow;
+  for (int i = 0; i < 3 * kKindWords; ++i) w[i] = src[i];
+  int x = (int)blockIdx.x;
+  int c[3];
+#pragma unroll
+  for (int t = 0; t < 3; ++t) {
+    const int entries = (int)w[t * kKindWords + 4], odd = (int)(w[t * kKindWords] & 1u);
+    c[t] = entries ? (entries + odd + TG_SCORE_CHUNK - 1) / TG_SCORE_CHUNK : 0;
   }
+  int t = 0;
+  if (x >= c[0]) { x -= c[0]; t = 1; if (x >= c[1]) { x -= c[1]; t = 2; if (x >= c[2]) return; } }
+  // the chosen block's words, picked out of the record in registers (no second load)
+  uint32_t k[kKindWords];
+#pragma unroll
+  for (int i = 0; i < kKindWords; ++i) k[i] = t == 0 ? w[i] : t == 1 ? w[kKindWords + i] : w[2 * kKindWords + i];
+  // Rows of 256 entries or more: the 256 entries of a wavefront lie in two rows, whose durations and pins a
+  // few lanes fetch for all.  Other blocks (few nodes: a small part of any tensor) load them per entry.
+  const int Mt = (int)(k[7] & 0xffffu), K = (int)(k[7] >> 16);
+  if (Mt * K >= TG_SCORE_CHUNK / 2) score_chunk<SVC, true>(A, k, x);
+  else score_chunk<SVC, false>(A, k, x);
 }
 
 }  // namespace
 
 int tg_launch_score(const tg_problem* p, int64_t* d_cost, hipStream_t s) {
-  if (p->score_wgs == 0) return TG_OK;
+  if (p->score_launches.empty()) return TG_OK;
   const bool svc = p->dev.act_service != nullptr;
-  const size_t lds = (size_t)p->score_dur_slots * 8 + (size_t)p->score_lds_nodes * 8 + (size_t)p->score_row_slots * 4 +
-                     (svc ? (size_t)p->score_lds_nodes * 8 + (size_t)((p->score_row_slots + 1) & ~1) * 8 : 0);
-  if (svc)
-    hipLaunchKernelGGL(tg_score_kernel<true>, dim3(p->score_wgs), dim3(kThreads), lds, s, p->dev, p->d_blocks, p->d_wg_block,
-                       p->score_lds_nodes, p->score_dur_slots, p->score_row_slots, d_cost);
-  else
-    hipLaunchKernelGGL(tg_score_kernel<false>, dim3(p->score_wgs), dim3(kThreads), lds, s, p->dev, p->d_blocks, p->d_wg_block,
-                       p->score_lds_nodes, p->score_dur_slots, p->score_row_slots, d_cost);
+  ScoreArgs a;
+  a.row_rec = p->dev.row_rec; a.row_pin = p->dev.row_pin; a.node_word = p->dev.node_word;
+  a.row_svc = p->dev.row_svc; a.node_res_k = p->dev.node_res_k; a.speedup = p->dev.speedup;
+  a.dur = p->d_score_dur; a.cost = d_cost; a.kword = tg_pack_k(p->dev.k_list); a.K = p->dev.K;
+  a.magic_K = a.K > 1 ? (uint32_t)((1ull << 32) / (uint32_t)a.K) + 1u : 0u;
+  const size_t pairs = (size_t)p->dev.B * p->dev.N * a.K;                 // < 2^32: checked when the problem was built
+  a.n_rows_K = (uint32_t)pairs;
+  a.snaps = p->d_score_snaps;
+  hipLaunchKernelGGL(tg_score_dur_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, s, a);
+  for (const TgScoreLaunch& g : p->score_launches) {
+    a.snaps = p->d_score_snaps + g.first;
+    const dim3 grid((unsigned)g.max_chunks, (unsigned)g.n_snaps, 1);
+    if (svc) hipLaunchKernelGGL(tg_score_kernel<true>, grid, dim3(kThreads), 0, s, a);
+    else hipLaunchKernelGGL(tg_score_kernel<false>, grid, dim3(kThreads), 0, s, a);
+  }
   return hipGetLastError() == hipSuccess ? TG_OK : TG_E_HIP;
 }
 

@@ -762,12 +762,6 @@ __device__ static inline int64_t tg_restore_delay(const TgNodeIn& in, int id) {
   return sv >= 0 && !(in.resident >> sv & 1ull) ? in.restore[sv] : 0;
 }
 
-__host__ __device__ static inline uint64_t tg_pack_k(const int* k_list) {
-  uint64_t w = 0;
-  for (int q = 0; q < TG_MAX_K; ++q) w |= (uint64_t)(uint32_t)k_list[q] << (8 * q);
-  return w;
-}
-
 struct TgNodeOut {
   int32_t* node; int32_t* units; int64_t* act; uint8_t* reason;
   const int64_t* age;
