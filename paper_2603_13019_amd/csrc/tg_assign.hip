@@ -260,6 +260,42 @@ __global__ __launch_bounds__(TG_WAVE) void tg_place_kernel(TgDev P, const int64_
   tg_pool_extents(S, nodes, Mt, a0, W.nl_off + nbase, W.nl_cnt + nbase, W.dl_off + nbase, W.dl_cnt + nbase, lane);
 }
 
+// The same admission decided in rounds of up to 64 actions (tg_place_pool_rounds): plain problems (no second
+// resource, services or further quotas), estimates recomputed, pools of up to 64 R nodes whose backlogs lie
+// within 2^31 us of each other.
+template <int R>
+__global__ __launch_bounds__(TG_WAVE) void tg_place_rounds_kernel(TgDev P, const int64_t* __restrict__ dur, AssignWs W,
+                                                                  tg_assign_out O, int lds_nodes, const int32_t* __restrict__ visit) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  TgPoolLds S;
+  tg_pool_lds_carve(smem, lds_nodes, &S);
+  const int b = blockIdx.x / 3, t = blockIdx.x - 3 * b, lane = threadIdx.x;
+  const int a0 = P.tact_off[b * 4 + t], Nt = P.tact_off[b * 4 + t + 1] - a0;
+  const int n0 = P.tnode_off[b * 4 + t], Mt = P.tnode_off[b * 4 + t + 1] - n0;
+  const size_t abase = (size_t)b * P.N, nbase = (size_t)b * P.M;
+  const int32_t* acts = (visit ? visit : P.tact_idx) + abase + a0;   // visiting order of the pool
+  const int32_t* nodes = P.tnode_idx + nbase + n0;
+  if (lane < TG_MAX_K) S.k[lane] = P.k_list[lane];
+  for (int r = lane; r < Mt; r += TG_WAVE) {
+    const size_t g = nbase + nodes[r];
+    S.back[r] = P.node_backlog[g];
+    S.lim[r] = t == TG_TYPE_GPU ? (int32_t)P.node_chunks[g] : P.node_free[g];
+    S.cnt[r] = 0; S.dcnt[r] = 0; S.closed[r] = 0;
+  }
+  __syncthreads();
+  TgPlaceIo io;
+  io.act_kmask = P.act_kmask + abase; io.act_static = P.act_static + abase; io.act_pin = P.act_pin + abase;
+  io.act_aux = nullptr; io.act_service = nullptr; io.restore = nullptr; io.act_quota = nullptr;
+  io.act_pin_rank = P.act_pin_rank + abase;
+  io.node_rank = P.node_rank + nbase; io.nodes = nodes; io.dur = dur + abase * P.K; io.K = P.K; io.Kt = P.type_k[t];
+  io.cost = nullptr; io.cost_row_len = 0;
+  io.out_node = O.node + abase; io.out_units = O.units + abase; io.out_act = O.act_us + abase;
+  io.out_reason = O.defer_reason + abase; io.slot = W.slot + abase;
+  if (t == TG_TYPE_GPU) tg_place_pool_rounds<R, true>(S, io, acts, Nt, Mt, lane);
+  else tg_place_pool_rounds<R, false>(S, io, acts, Nt, Mt, lane);
+  tg_pool_extents(S, nodes, Mt, a0, W.nl_off + nbase, W.nl_cnt + nbase, W.dl_off + nbase, W.dl_cnt + nbase, lane);
+}
+
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void tg_lists_kernel(TgDev P, AssignWs W, tg_assign_out O) {
   const size_t g = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -682,10 +718,19 @@ int assign_launch(const tg_problem* p, const int64_t* d_cost, const tg_assign_ou
                   : width == 1 ? (ext ? tg_place_kernel<1, 1, false, false> : tg_place_kernel<1, 0, false, false>)
                   : width == 4 ? (ext ? tg_place_kernel<4, 4, false, false> : tg_place_kernel<4, 0, false, false>)
                                : (ext ? tg_place_kernel<16, 16, false, false> : tg_place_kernel<16, 0, false, false>);
-    if (place_lds > 64 * 1024)
-      TG_HIP_CHECK(hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)place_lds));
-    hipLaunchKernelGGL(k, dim3(P.B * 3), dim3(TG_WAVE), place_lds, s, P, W.dur, place_cost, p->d_blocks, W, *out,
-                       p->max_nodes_of_kind, visit, nullptr, nullptr);
+    if (!ext && width != 0 && p->backlog_spread < (1ll << 31)) {
+      // plain problem: the admission in rounds of up to 64 actions
+      using RoundsKernel = void (*)(TgDev, const int64_t*, AssignWs, tg_assign_out, int, const int32_t*);
+      RoundsKernel kr = width == 1 ? tg_place_rounds_kernel<1> : width == 4 ? tg_place_rounds_kernel<4> : tg_place_rounds_kernel<16>;
+      if (place_lds > 64 * 1024)
+        TG_HIP_CHECK(hipFuncSetAttribute((const void*)kr, hipFuncAttributeMaxDynamicSharedMemorySize, (int)place_lds));
+      hipLaunchKernelGGL(kr, dim3(P.B * 3), dim3(TG_WAVE), place_lds, s, P, W.dur, W, *out, p->max_nodes_of_kind, visit);
+    } else {
+      if (place_lds > 64 * 1024)
+        TG_HIP_CHECK(hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)place_lds));
+      hipLaunchKernelGGL(k, dim3(P.B * 3), dim3(TG_WAVE), place_lds, s, P, W.dur, place_cost, p->d_blocks, W, *out,
+                         p->max_nodes_of_kind, visit, nullptr, nullptr);
+    }
     if (p->queue_prefix) {
       // one prefix of the whole queue: the pass above (one prefix per pool) finds where it ends, a
       // second pass admits the actions before that place and leaves the others waiting

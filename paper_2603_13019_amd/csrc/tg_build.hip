@@ -229,8 +229,10 @@ extern "C" int tg_build_problem(const tg_problem_desc* desc, void* hip_stream, t
     std::vector<int> max_cap((size_t)B * 3, -1);
     int max_kind = 0, max_free_cpu = 0, max_heap = 0, max_free_gpu = 0, max_states = 1;
     size_t free_gt16 = 0, free_gt64 = 0;
+    int64_t backlog_spread = 0;
     for (int b = 0; b < B; ++b) {
       int cnt[3] = {0, 0, 0};
+      int64_t bl_lo[3] = {TG_INF, TG_INF, TG_INF}, bl_hi[3] = {0, 0, 0};
       for (int j = 0; j < M; ++j) {
         const size_t g = (size_t)b * M + j;
         const int t = d->node_type[g], cap = d->node_cap[g], fr = d->node_free[g];
@@ -238,6 +240,7 @@ extern "C" int tg_build_problem(const tg_problem_desc* desc, void* hip_stream, t
         if ((t == TG_TYPE_CPU && cap > TG_MAX_CPU_UNITS) || (t == TG_TYPE_GPU && cap > TG_MAX_GPU_UNITS)) { delete p; return TG_E_RANGE; }
         const int64_t bl = d->node_backlog_us[g];
         if (bl < 0 || bl >= TG_TIME_LIMIT) { delete p; return TG_E_RANGE; }
+        bl_lo[t] = std::min(bl_lo[t], bl); bl_hi[t] = std::max(bl_hi[t], bl);
         int nb = 0;
         if (d->node_busy_off) {
           nb = d->node_busy_off[g + 1] - d->node_busy_off[g];
@@ -277,6 +280,7 @@ extern "C" int tg_build_problem(const tg_problem_desc* desc, void* hip_stream, t
         ar.at<int32_t>(o_tnidx)[(size_t)b * M + fill[t]++] = j;
       }
       for (int t = 0; t < 3; ++t) max_kind = std::max(max_kind, cnt[t]);
+      for (int t = 0; t < 3; ++t) if (cnt[t]) backlog_spread = std::max(backlog_spread, bl_hi[t] - bl_lo[t]);
       if (max_kind > TG_MAX_NODES_OF_KIND) { delete p; return TG_E_RANGE; }
     }
     ar.at<int32_t>(o_nboff)[nN] = (int32_t)n_busy;
@@ -494,6 +498,7 @@ extern "C" int tg_build_problem(const tg_problem_desc* desc, void* hip_stream, t
     p->n_blocks = B * 3;
     p->n_candidates = total;
     p->max_nodes_of_kind = max_kind;
+    p->backlog_spread = backlog_spread;
     p->order_policy = d->order_policy; p->queue_prefix = d->queue_prefix; p->max_actions_of_kind = max_acts_kind;
     p->max_free_cpu = max_free_cpu;
     p->max_heap = max_heap;

@@ -124,6 +124,7 @@ struct tg_problem {
   int queue_prefix;        // 1: one admitted prefix of the whole queue instead of one per pool
   int max_actions_of_kind; // largest N_t over all snapshots and kinds
   int max_nodes_of_kind;   // largest M_t over all snapshots and kinds
+  int64_t backlog_spread;  // largest (max - min) backlog over the nodes of one kind in one snapshot
   int max_free_cpu;        // largest node_free over CPU nodes
   int max_heap;            // largest free + busy over CPU and GPU nodes
   size_t nodes_free_gt16, nodes_free_gt64;   // nodes with more than 16 / 64 free units: bounds on the nodes that can hold as many candidates

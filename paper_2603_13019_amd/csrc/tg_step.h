@@ -441,6 +441,237 @@ __device__ static inline void tg_place_pool_regs(const TgPoolLds& S, const TgPla
   tg_wave_sync();
 }
 
+// Wavefront-wide OR of a small bit mask (data-parallel-primitive moves as in the minima above).
+__device__ static inline uint32_t tg_wave_or_u32(uint32_t v) {
+#define TG_DPP_OR_STEP(CTRL, ROWMASK) v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROWMASK, 0xf, false);
+  TG_DPP_OR_STEP(0x111, 0xf) TG_DPP_OR_STEP(0x112, 0xf) TG_DPP_OR_STEP(0x114, 0xf) TG_DPP_OR_STEP(0x118, 0xf)
+  TG_DPP_OR_STEP(0x142, 0xa) TG_DPP_OR_STEP(0x143, 0xc)
+#undef TG_DPP_OR_STEP
+  return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+
+// Admission of a pool in rounds instead of action by action - same decisions as the serial loop.
+//
+// Within one step the units left on a node only shrink and closed nodes stay closed, so for a
+// given action the estimate of every node only rises (or the node drops out) as earlier actions
+// are admitted.  Hence: if all 64 actions of a chunk decide at once on the table as it stands
+// (lane = action), the decision of an action is the serial one as long as, after the admissions
+// of the actions before it, (a) it is pinned and still fits its node, or (b) it is free and the
+// node it chose still offers it the same largest option - every other node can only have become
+// worse, and ties went to the smaller index already.  A round therefore decides all remaining
+// actions of the chunk, finds for each the units taken from its node by the earlier ones (exact
+// prefix sums per node), commits the longest prefix of actions whose decisions hold, and the next
+// round starts at the first one that does not.  The first action of a round sees the true table,
+// so every round commits at least one action; an action that closes something (a pinned action
+// that does not fit closes its node, a free one with no candidate closes the pool) ends its round.
+// On GPU nodes a chunk taken from a node changes its state in a way sums do not describe, so there
+// only the first action of a round that touches a node is committed.
+//
+// The estimate of a free action on a node depends on the node only through its backlog and
+// through which options still fit (a prefix of the option list: its "class"), so an action
+// minimises over one representative per class - the node with the smallest (backlog, rank) - in
+// at most K steps, instead of over all nodes; the representatives are recomputed only for
+// classes whose membership changed.
+//
+// Needs: no second resource / services / further quotas, estimates recomputed (no score tensor),
+// Mt <= 64 R, and all backlogs of the pool within 2^31 of the smallest (`bmin`).  The LDS arrays
+// aux / res of S, unused without those options, serve as per-node counters.
+template <int R, bool GPU>
+__device__ static inline void tg_place_pool_rounds(const TgPoolLds& S, const TgPlaceIo& io, const int32_t* acts, int Nt,
+                                                   int Mt, int lane) {
+  enum { kNone = 0, kInfeasible, kPrefix, kWait, kMisfit, kNoFit, kAdmit };
+  Nt = __builtin_amdgcn_readfirstlane(Nt);
+  Mt = __builtin_amdgcn_readfirstlane(Mt);
+  const int Kt = __builtin_amdgcn_readfirstlane(io.Kt);
+  tg_wave_sync();
+  for (int u = lane; u <= TG_MAX_UNIT; u += TG_WAVE) {
+    uint32_t f = 0;
+    for (int q = 0; q < Kt; ++q) f |= (S.k[q] <= u ? 1u : 0u) << q;
+    S.fit[u] = (uint8_t)f;
+  }
+  int32_t* win_a = S.aux;                                         // admitted this round, per node
+  int32_t* win_w = reinterpret_cast<int32_t*>(S.res);             // put on the waiting list this round, per node
+  int64_t bmin = TG_INF;
+  for (int r = lane; r < Mt; r += TG_WAVE) { win_a[r] = 0; win_w[r] = 0; const int64_t b = S.back[r]; bmin = b < bmin ? b : bmin; }
+  bmin = (int64_t)tg_wave_min_u64((uint64_t)bmin);
+  tg_wave_sync();
+  auto fit_of = [&](int32_t lim) {
+    const int u = GPU ? tg_chunk_largest((uint32_t)lim) : lim;
+    return (uint32_t)S.fit[u < 0 ? 0 : u < TG_MAX_UNIT ? u : TG_MAX_UNIT];
+  };
+  uint32_t back32[R];
+  int cls[R];                                                     // options that fit into what the node has left; 0: closed or full
+#pragma unroll
+  for (int s = 0; s < R; ++s) { const int r = lane + TG_WAVE * s; back32[s] = r < Mt ? (uint32_t)(S.back[r] - bmin) : 0u; cls[s] = -1; }
+  uint64_t rep[TG_MAX_K + 1];                                     // per class: (backlog offset << 12 | rank) of its best node, ~0: empty
+#pragma unroll
+  for (int c = 0; c <= TG_MAX_K; ++c) rep[c] = ~0ull;
+  bool pool_closed = false;
+  auto pack_res = [](int rank, int slot, int reason) { return (uint32_t)(rank + 1) | (uint32_t)slot << 13 | (uint32_t)reason << 30; };
+  const uint64_t lt_mask = (1ull << lane) - 1ull;
+
+  struct Stage {
+    int id, pin;
+    uint32_t mask, stat;
+    int64_t d[TG_MAX_K];
+  };
+  auto fetch_id = [&](int base) { return base + lane < Nt ? acts[base + lane] : 0; };
+  auto fetch = [&](int base, int id, Stage& st) {
+    st.id = id; st.pin = -1; st.mask = 0; st.stat = 0;
+#pragma unroll
+    for (int q = 0; q < TG_MAX_K; ++q) st.d[q] = TG_INF;
+    if (base + lane < Nt) {
+      st.mask = io.act_kmask[id]; st.stat = io.act_static[id] ? 1u : 0u;
+      st.pin = io.act_pin_rank ? io.act_pin_rank[id] : io.act_pin[id];
+#pragma unroll
+      for (int q = 0; q < TG_MAX_K; ++q) if (q < io.K) st.d[q] = io.dur[(size_t)id * io.K + q];
+    }
+  };
+  int next_id = fetch_id(0);
+  Stage cur;
+  fetch(0, next_id, cur);
+  next_id = fetch_id(TG_WAVE);
+  for (int base = 0; base < Nt; base += TG_WAVE) {
+    const int cnt = min(TG_WAVE, Nt - base);
+    const int my_id = cur.id;
+    uint32_t mask = 0, stat = 0;
+    int kmin = 0, pr = -1;
+    if (lane < cnt) {
+      mask = cur.mask & 0xffu; stat = cur.stat;
+      pr = cur.pin;
+      if (!io.act_pin_rank) pr = pr >= 0 && !stat ? io.node_rank[pr] : -1;
+      kmin = mask ? S.k[__builtin_ctz(mask)] : 0;
+    }
+    tg_wave_sync();                                  // the previous chunk's readers are done with S.dur
+    if (lane < cnt) {
+#pragma unroll
+      for (int q = 0; q < TG_MAX_K; ++q) if (q < io.K) S.dur[lane * io.K + q] = cur.d[q];
+    }
+    Stage nxt;                                       // in flight while this chunk is admitted
+    fetch(base + TG_WAVE, next_id, nxt);
+    next_id = fetch_id(base + 2 * TG_WAVE);
+    tg_wave_sync();
+    uint32_t my_res = 0;
+    int f0 = 0;                                      // first action of the chunk that is not committed yet
+    while (f0 < cnt) {
+      // ---- the table as it stands: class of every node, representatives of the classes that changed
+      uint32_t dirty = 0;
+#pragma unroll
+      for (int s = 0; s < R; ++s) {
+        const int r = lane + TG_WAVE * s;
+        int c = 0;
+        if (r < Mt && !S.closed[r]) c = __builtin_popcount(fit_of(S.lim[r]));
+        if (c != cls[s]) { dirty |= (cls[s] >= 0 ? 1u << cls[s] : 0u) | 1u << c; cls[s] = c; }
+      }
+      dirty = tg_wave_or_u32(dirty);
+#pragma unroll
+      for (int c = 1; c <= TG_MAX_K; ++c) {
+        if (!(dirty >> c & 1u)) continue;
+        uint64_t key = ~0ull;
+#pragma unroll
+        for (int s = 0; s < R; ++s) {
+          const uint64_t k2 = (uint64_t)back32[s] << 12 | (uint32_t)(lane + TG_WAVE * s);
+          if (cls[s] == c && k2 < key) key = k2;
+        }
+        rep[c] = tg_wave_min_u64(key);
+      }
+      // ---- every remaining action decides on this table
+      const bool active = lane >= f0 && lane < cnt;
+      int dec = kNone, node = -1;
+      if (active) {
+        if (stat) dec = kInfeasible;
+        else if (pr >= 0) {
+          const bool fits = (mask & fit_of(S.lim[pr])) != 0;
+          if (pool_closed || S.closed[pr]) dec = kWait;
+          else if (fits) { dec = kAdmit; node = pr; }
+          else dec = kMisfit;
+        } else if (pool_closed) dec = kPrefix;
+        else {
+          uint64_t best = ~0ull;
+#pragma unroll
+          for (int c = 1; c <= TG_MAX_K; ++c) {
+            if (rep[c] == ~0ull) continue;                        // the same in all lanes
+            const uint32_t ok = mask & ((1u << c) - 1u);
+            if (ok == 0) continue;
+            const uint64_t e = (rep[c] >> 12) + (uint64_t)S.dur[lane * io.K + (31 - __builtin_clz(ok))];
+            const uint64_t key = e << 12 | (rep[c] & 0xfffull);
+            best = key < best ? key : best;
+          }
+          if (best == ~0ull) dec = kNoFit;
+          else { dec = kAdmit; node = (int)(best & 0xfffull); }
+        }
+      }
+      // ---- for actions that enter a list: how many of the earlier ones enter the same list, and the units they take
+      const bool waits = dec == kWait || dec == kMisfit;
+      const bool listed = dec == kAdmit || waits;
+      const int lkey = dec == kAdmit ? node : waits ? pr + 4096 : -1;   // list identity
+      int32_t* win = dec == kAdmit ? win_a + node : win_w + (waits ? pr : 0);
+      if (listed) atomicAdd(win, 1);
+      tg_wave_sync();
+      const int shared = listed ? *win : 0;
+      tg_wave_sync();
+      if (listed) *win = 0;
+      int rank = 0, before = 0;
+      for (uint64_t todo = __ballot(shared > 1); todo;) {
+        const int k0 = __builtin_amdgcn_readlane(lkey, __builtin_ctzll(todo));
+        const bool in = lkey == k0;
+        const uint64_t m = __ballot(in);
+        if (in) rank = __popcll(m & lt_mask);
+        if (!GPU && k0 < 4096) {                                  // units taken from the node by the earlier ones
+          const int inc = tg_wave_scan_i32(in ? kmin : 0);
+          if (in) before = inc - kmin;
+        }
+        todo &= ~m;
+      }
+      // ---- which decisions hold after the earlier actions of the round
+      bool valid = true;
+      int lim_n = 0;
+      if (dec == kAdmit) {
+        lim_n = S.lim[node];
+        if (GPU) valid = rank == 0;
+        else {
+          const uint32_t fo = mask & fit_of(lim_n), fn = mask & fit_of(lim_n - before);
+          valid = fn != 0 && (pr >= 0 || (31 - __builtin_clz(fn)) == (31 - __builtin_clz(fo | 1u)));
+        }
+      }
+      const uint64_t bad = __ballot(active && !valid), ends = __ballot(dec == kMisfit || dec == kNoFit);
+      int f = cnt;
+      if (bad) f = __builtin_ctzll(bad);
+      if (ends) f = min(f, __builtin_ctzll(ends) + 1);
+      // ---- commit actions f0 .. f-1
+      const bool commit = active && lane < f;
+      int slot = 0;
+      if (commit && dec == kAdmit) slot = S.cnt[node] + rank;
+      if (commit && waits) slot = S.dcnt[pr] + rank;
+      tg_wave_sync();                                             // every list length read before any is changed
+      if (commit) {
+        if (dec == kAdmit) {
+          atomicAdd(&S.cnt[node], 1);
+          if (GPU) S.lim[node] = (int32_t)tg_chunk_take((uint32_t)lim_n, kmin);
+          else atomicSub(&S.lim[node], kmin);
+          my_res = pack_res(node, slot, TG_SELECTED);
+        } else if (waits) {
+          atomicAdd(&S.dcnt[pr], 1);
+          if (dec == kMisfit) S.closed[pr] = 1;
+          my_res = pack_res(-1, slot, TG_DEFER_PREFIX);
+        } else my_res = pack_res(-1, 0, dec == kInfeasible ? TG_DEFER_INFEASIBLE : TG_DEFER_PREFIX);
+      }
+      if (__ballot(commit && dec == kNoFit)) pool_closed = true;
+      tg_wave_sync();
+      f0 = f;
+    }
+    if (lane < cnt) {
+      const int res_rank = (int)(my_res & 0x1fffu) - 1, res_slot = (int)(my_res >> 13 & 0x1ffffu), res_reason = (int)(my_res >> 30);
+      io.out_node[my_id] = res_rank >= 0 ? io.nodes[res_rank] : -1;
+      io.out_reason[my_id] = (uint8_t)res_reason;
+      io.slot[my_id] = res_slot;
+      if (res_reason != TG_SELECTED) { io.out_units[my_id] = 0; if (io.out_act) io.out_act[my_id] = -1; }
+    }
+    cur = nxt;
+  }
+  tg_wave_sync();
+}
+
 // The loop specialised on whether the pool's units are buddy chunks (GPU) or plain counts.
 template <int R, bool AUX>
 __device__ static inline void tg_place_pool_regs_kind(const TgPoolLds& S, const TgPlaceIo& io, const int32_t* acts, int Nt,
