@@ -47,6 +47,7 @@ struct AssignWs {
 // tg_assign below.
 constexpr int kClasses = 3;
 constexpr int kSelRows = 32;     // prefix lengths backtracked per batch
+constexpr int kLightBatch = 8;   // nodes of the light class a wavefront takes per fetch
 // One wavefront per node.  Teams of several wavefronts (tg_node_schedule<NW>, NW > 1) are
 // implemented but switched off: on workload 2 a launch with NW = 4 did not finish, and the cause
 // has not been found yet, so only NW = 1 (no workgroup barrier anywhere) is instantiated.
@@ -372,7 +373,7 @@ __global__ __launch_bounds__(TG_WAVE) void tg_node_kernel(TgDev P, const int64_t
     // wavefronts of the class's own launch, one batch each by their index (thousands of
     // wavefronts start together: no queue at the counter); everything behind it is handed out
     // by the counter.
-    const int batch = cur == 0 ? 4 : cur == 1 ? 2 : 1;
+    const int batch = cur == 0 ? kLightBatch : cur == 1 ? 2 : 1;
     const int head = (cur == 0 ? grid0 : cur == 1 ? grid1 : grid2) * batch;
     int idx0 = 0;
     if (first) idx0 = (int)blockIdx.x * batch;
@@ -401,7 +402,62 @@ __global__ __launch_bounds__(TG_WAVE) void tg_node_kernel(TgDev P, const int64_t
       if (P.has_busy) { my_boff = P.node_busy_off[my_gn]; my_nbusy = P.node_busy_off[my_gn + 1] - my_boff; }
       if (P.node_resident) my_resident = (int64_t)P.node_resident[my_gn];
     }
+    // Light nodes in closed form, eight at a time (lane = 8 * node + candidate).  On a CPU node or quota with
+    // nobody waiting, nothing running and at most 8 candidates whose individually fastest options fit the free
+    // units together, DPArrange is not constrained: its table decomposes and every candidate takes its fastest
+    // allowed option (fewest units among equals: the only allocation with the least total and, among those, the
+    // fewest units).  The eviction loop then stops at once: without its last candidate the objective trades that
+    // candidate's fastest duration for an estimate that starts it no earlier than the backlog on one of its first
+    // `depth` options, which is never less.  Alg. 1's result is therefore everybody selected on those units, the
+    // objective the sum of the durations plus the backlog once per candidate.
+    uint64_t fast_done = 0;                                         // bit 8j: node j of the batch is finished
+    if (cur == 0 && !P.act_service) {
+      const int sj = lane >> 3, slot = lane & 7;
+      const int s_gn = __shfl(my_gn, sj), s_type = __shfl(my_type, sj), s_cap = __shfl(my_cap, sj), s_free = __shfl(my_free, sj);
+      const int s_m = __shfl(my_m, sj), s_off = __shfl(my_off, sj), s_nd = __shfl(my_nd, sj), s_nbusy = __shfl(my_nbusy, sj);
+      const int64_t s_backlog = __shfl(my_backlog, sj);
+      const bool elig = sj < nb && s_type != TG_TYPE_GPU && s_nd == 0 && s_nbusy == 0 && s_m >= 1 && s_m <= 8;
+      const bool cand = elig && slot < s_m;
+      const size_t abase = (size_t)(s_gn / P.M) * P.N;
+      size_t ga = 0;
+      if (cand) ga = abase + W.order[abase + s_off + slot];
+      uint32_t mask = 0;
+      int model = 0;
+      int64_t age = 0, d[TG_MAX_K];
+#pragma unroll
+      for (int q = 0; q < TG_MAX_K; ++q) d[q] = TG_INF;
+      if (cand) {
+        mask = P.act_kmask[ga]; model = P.act_model[ga]; age = P.act_age[ga];
+#pragma unroll
+        for (int q = 0; q < TG_MAX_K; ++q) if (q < P.K) d[q] = dur[ga * P.K + q];
+      }
+      int64_t bd = TG_INF;
+      int bk = 0;
+#pragma unroll
+      for (int q = 0; q < TG_MAX_K; ++q) {                          // ascending units, strict <: fewer units win ties
+        const int kq = P.k_list[q < P.K ? q : 0];
+        if (q < P.K && (mask >> q & 1u) && kq <= s_cap && d[q] < bd) { bd = d[q]; bk = kq; }
+      }
+      int tot_k = cand ? bk : 0, any_el = cand && model != TG_MODEL_NONE ? 1 : 0;
+      int64_t tot_d = cand && bd != TG_INF ? bd : 0;
+      int bad = cand && bd == TG_INF ? 1 : 0;                       // cannot happen after admission; then the general path decides
+#pragma unroll
+      for (int o = 1; o < 8; o <<= 1) {
+        tot_k += __shfl_xor(tot_k, o); any_el |= __shfl_xor(any_el, o); bad |= __shfl_xor(bad, o); tot_d += __shfl_xor(tot_d, o);
+      }
+      const bool node_ok = elig && !bad && tot_k <= s_free;
+      if (cand && node_ok) {
+        O.units[ga] = bk;
+        O.act_us[ga] = age + s_backlog + bd;
+      }
+      if (node_ok && slot == 0) {
+        if (O.node_obj) O.node_obj[s_gn] = any_el ? tot_d + (int64_t)s_m * s_backlog : -1;
+        if (O.node_used) O.node_used[s_gn] = tot_k;
+      }
+      fast_done = __ballot(node_ok && slot == 0);
+    }
     for (int j = 0; j < nb; ++j) {
+      if (fast_done >> (8 * j) & 1ull) continue;
       const int gn = __builtin_amdgcn_readlane(my_gn, j);
       const int b = gn / P.M;
       const size_t abase = (size_t)b * P.N;
