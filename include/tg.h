@@ -245,13 +245,21 @@ int tg_assign(const tg_problem *p, const int64_t *d_cost, const tg_assign_out *o
 int tg_assign_static(const tg_problem *p, const int64_t *d_cost, const tg_assign_out *out, void *hip_stream);
 
 /*
- * One whole step in one call: tg_score_candidates and tg_assign for the same problem, the score
- * tensor written on a stream of the problem's own next to the assignment (which recomputes its
- * estimates and does not read the tensor), forked from and joined back into `hip_stream`.  Same
- * arguments, results and errors as the two calls (d_cost must not be NULL unless the problem has
- * no candidate); everything is complete once `hip_stream` has been synchronised.
+ * One whole step in one call: tg_score_candidates and tg_assign for the same problem.  The assignment
+ * recomputes its estimates and does not read the tensor.  The score kernels run on a second stream: a tensor
+ * of 2^29 candidates (4 GB) or more is written first and the assignment follows (side by side the two only
+ * slow each other down); a smaller one is written next to the first, light kernels of the assignment
+ * (durations, admission, lists) and the per-node stage (DPArrange, eviction) follows when it is written;
+ * everything is forked from and joined back into `hip_stream`.  Same arguments, results and errors as the
+ * two calls (d_cost must not be NULL unless the problem has no candidate); everything is complete once
+ * `hip_stream` has been synchronised.  What can fail without a launch (argument checks, kernel
+ * attributes) is done before the fork.
+ * tg_step runs the score kernels on a stream of the problem's own; tg_step_on on the caller's
+ * `score_stream` (a hipStream_t other than `hip_stream`, e.g. to bracket them with events of its own).
  */
 int tg_step(const tg_problem *p, int64_t *d_cost, const tg_assign_out *out, void *d_ws, size_t ws_bytes, void *hip_stream);
+int tg_step_on(const tg_problem *p, int64_t *d_cost, const tg_assign_out *out, void *d_ws, size_t ws_bytes, void *hip_stream,
+               void *score_stream);
 
 /*
  * S independent arrival traces replayed against their own clusters.  Every tick_us of simulated

@@ -667,21 +667,42 @@ int check_assign_args(const tg_problem* p, const tg_assign_out* out, const void*
 }
 }  // namespace
 
-extern "C" int tg_step(const tg_problem* p, int64_t* d_cost, const tg_assign_out* out, void* d_ws, size_t ws_bytes,
-                       void* hip_stream) {
+namespace {
+int assign_launch(const tg_problem* p, const int64_t* d_cost, const tg_assign_out* out, void* d_ws, hipStream_t s,
+                  hipEvent_t before_nodes, bool prepare_only);
+}  // namespace
+
+extern "C" int tg_step_on(const tg_problem* p, int64_t* d_cost, const tg_assign_out* out, void* d_ws, size_t ws_bytes,
+                          void* hip_stream, void* score_stream) {
   const int rc = check_assign_args(p, out, d_ws, ws_bytes);
   if (rc) return rc;
-  if ((!d_cost && p->n_candidates) || ((uintptr_t)d_cost & 15)) return TG_E_INVALID_ARG;
-  hipStream_t s = (hipStream_t)hip_stream;
-  // the assignment does not read the tensor: the HBM-bound score kernel runs on a stream of its own
-  // next to the latency-bound assignment, forked from and joined back into the caller's stream
+  if ((!d_cost && p->n_candidates) || ((uintptr_t)d_cost & 15) || score_stream == hip_stream) return TG_E_INVALID_ARG;
+  hipStream_t s = (hipStream_t)hip_stream, ss = (hipStream_t)score_stream;
+  // everything that can fail for a reason other than a launch comes first: on such an error nothing has been launched
+  const int rp = assign_launch(p, nullptr, out, d_ws, s, nullptr, true);
+  if (rp) return rp;
+  // The assignment does not read the tensor, so the two could run side by side - but the score kernels and the
+  // per-node stage both live on the vector ALUs' issue slots (measured: next to each other each takes as long as
+  // both in a row), and the score kernels' short workgroups need all of the chip's wavefront slots to keep HBM busy.
+  // So: a large tensor (4 GB and more) is written first, with the chip to itself, and the assignment follows; a
+  // small one is written next to the first, light kernels of the assignment (durations, admission, lists: a few
+  // wavefronts per compute unit, too short to matter) and only the per-node stage waits for it.  Forked from and
+  // joined back into the caller's stream.
+  const bool big = p->n_candidates >= (1ll << 29);
   TG_HIP_CHECK(hipEventRecord(p->ev_score_fork, s));
-  TG_HIP_CHECK(hipStreamWaitEvent(p->score_stream, p->ev_score_fork, 0));
-  const int rs = tg_launch_score(p, d_cost, p->score_stream);
-  TG_HIP_CHECK(hipEventRecord(p->ev_score_done, p->score_stream));
-  const int ra = tg_assign(p, nullptr, out, d_ws, ws_bytes, hip_stream);
-  TG_HIP_CHECK(hipStreamWaitEvent(s, p->ev_score_done, 0));
+  TG_HIP_CHECK(hipStreamWaitEvent(ss, p->ev_score_fork, 0));
+  const int rs = tg_launch_score(p, d_cost, ss);
+  TG_HIP_CHECK(hipEventRecord(p->ev_score_done, ss));
+  if (big) TG_HIP_CHECK(hipStreamWaitEvent(s, p->ev_score_done, 0));
+  const int ra = assign_launch(p, nullptr, out, d_ws, s, big ? nullptr : p->ev_score_done, false);
+  if (!big) TG_HIP_CHECK(hipStreamWaitEvent(s, p->ev_score_done, 0));
   return rs ? rs : ra;
+}
+
+extern "C" int tg_step(const tg_problem* p, int64_t* d_cost, const tg_assign_out* out, void* d_ws, size_t ws_bytes,
+                       void* hip_stream) {
+  if (!p) return TG_E_INVALID_ARG;
+  return tg_step_on(p, d_cost, out, d_ws, ws_bytes, hip_stream, p->score_stream);
 }
 
 // Workspace of tg_assign_static: one array per GPU in the library's own device data, so that the entry
@@ -707,14 +728,13 @@ int static_workspace(void** ptr) {
   return TG_OK;
 }
 
-int assign_launch(const tg_problem* p, const int64_t* d_cost, const tg_assign_out* out, void* d_ws, hipStream_t s);
 }  // namespace
 
 extern "C" int tg_assign(const tg_problem* p, const int64_t* d_cost, const tg_assign_out* out, void* d_ws,
                          size_t ws_bytes, void* hip_stream) {
   const int rc_args = check_assign_args(p, out, d_ws, ws_bytes);
   if (rc_args) return rc_args;
-  return assign_launch(p, d_cost, out, d_ws, (hipStream_t)hip_stream);
+  return assign_launch(p, d_cost, out, d_ws, (hipStream_t)hip_stream, nullptr, false);
 }
 
 extern "C" int tg_assign_static(const tg_problem* p, const int64_t* d_cost, const tg_assign_out* out, void* hip_stream) {
@@ -725,11 +745,14 @@ extern "C" int tg_assign_static(const tg_problem* p, const int64_t* d_cost, cons
   if (rc_ws) return rc_ws;
   const int rc_args = check_assign_args(p, out, ws, TG_STATIC_WS_BYTES);
   if (rc_args) return rc_args;
-  return assign_launch(p, d_cost, out, ws, (hipStream_t)hip_stream);
+  return assign_launch(p, d_cost, out, ws, (hipStream_t)hip_stream, nullptr, false);
 }
 
 namespace {
-int assign_launch(const tg_problem* p, const int64_t* d_cost, const tg_assign_out* out, void* d_ws, hipStream_t s) {
+// before_nodes: an event the per-node stage waits for (tg_step: the score kernels), or nullptr.
+// prepare_only: do what can fail before anything is launched (the kernels' LDS limits) and return.
+int assign_launch(const tg_problem* p, const int64_t* d_cost, const tg_assign_out* out, void* d_ws, hipStream_t s,
+                  hipEvent_t before_nodes, bool prepare_only) {
   const TgDev& P = p->dev;
   AssignWs W;
   carve(p, (char*)d_ws, &W);
@@ -748,7 +771,7 @@ int assign_launch(const tg_problem* p, const int64_t* d_cost, const tg_assign_ou
     TG_HIP_CHECK(hipFuncSetAttribute((const void*)tg_node_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, max_lds));
 
   const size_t nN = (size_t)P.B * P.M;
-  hipLaunchKernelGGL(tg_dur_kernel, dim3((unsigned)((nA * P.K + 255) / 256)), dim3(256), 0, s, P, W.dur, W.class_ctl);
+  if (!prepare_only) hipLaunchKernelGGL(tg_dur_kernel, dim3((unsigned)((nA * P.K + 255) / 256)), dim3(256), 0, s, P, W.dur, W.class_ctl);
   const int32_t* visit = nullptr;
   if (p->order_policy == TG_ORDER_COST) {
     int n_pad = 1;
@@ -756,7 +779,7 @@ int assign_launch(const tg_problem* p, const int64_t* d_cost, const tg_assign_ou
     const size_t order_lds = (size_t)n_pad * 8;
     if (order_lds > 48 * 1024)
       TG_HIP_CHECK(hipFuncSetAttribute((const void*)tg_order_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)order_lds));
-    hipLaunchKernelGGL(tg_order_kernel, dim3(P.B * 3), dim3(kOrderThreads), order_lds, s, P, W.dur, p->d_blocks, W.visit, n_pad,
+    if (!prepare_only) hipLaunchKernelGGL(tg_order_kernel, dim3(P.B * 3), dim3(kOrderThreads), order_lds, s, P, W.dur, p->d_blocks, W.visit, n_pad,
                        p->queue_prefix ? W.gkey : nullptr);
     visit = W.visit;
   }
@@ -780,11 +803,11 @@ int assign_launch(const tg_problem* p, const int64_t* d_cost, const tg_assign_ou
       RoundsKernel kr = width == 1 ? tg_place_rounds_kernel<1> : width == 4 ? tg_place_rounds_kernel<4> : tg_place_rounds_kernel<16>;
       if (place_lds > 64 * 1024)
         TG_HIP_CHECK(hipFuncSetAttribute((const void*)kr, hipFuncAttributeMaxDynamicSharedMemorySize, (int)place_lds));
-      hipLaunchKernelGGL(kr, dim3(P.B * 3), dim3(TG_WAVE), place_lds, s, P, W.dur, W, *out, p->max_nodes_of_kind, visit);
+      if (!prepare_only) hipLaunchKernelGGL(kr, dim3(P.B * 3), dim3(TG_WAVE), place_lds, s, P, W.dur, W, *out, p->max_nodes_of_kind, visit);
     } else {
       if (place_lds > 64 * 1024)
         TG_HIP_CHECK(hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)place_lds));
-      hipLaunchKernelGGL(k, dim3(P.B * 3), dim3(TG_WAVE), place_lds, s, P, W.dur, place_cost, p->d_blocks, W, *out,
+      if (!prepare_only) hipLaunchKernelGGL(k, dim3(P.B * 3), dim3(TG_WAVE), place_lds, s, P, W.dur, place_cost, p->d_blocks, W, *out,
                          p->max_nodes_of_kind, visit, nullptr, nullptr);
     }
     if (p->queue_prefix) {
@@ -794,15 +817,17 @@ int assign_launch(const tg_problem* p, const int64_t* d_cost, const tg_assign_ou
       PlaceKernel k2 = tg_place_kernel<0, 0, true, true>;
       if (place_lds > 64 * 1024)
         TG_HIP_CHECK(hipFuncSetAttribute((const void*)k2, hipFuncAttributeMaxDynamicSharedMemorySize, (int)place_lds));
-      hipLaunchKernelGGL(tg_stop_kernel, dim3(P.B), dim3(256), 0, s, P, *out, gkey, W.stop);
-      hipLaunchKernelGGL(k2, dim3(P.B * 3), dim3(TG_WAVE), place_lds, s, P, W.dur, place_cost, p->d_blocks, W, *out,
+      if (!prepare_only) hipLaunchKernelGGL(tg_stop_kernel, dim3(P.B), dim3(256), 0, s, P, *out, gkey, W.stop);
+      if (!prepare_only) hipLaunchKernelGGL(k2, dim3(P.B * 3), dim3(TG_WAVE), place_lds, s, P, W.dur, place_cost, p->d_blocks, W, *out,
                          p->max_nodes_of_kind, visit, gkey, W.stop);
     }
   }
-  hipLaunchKernelGGL(tg_lists_kernel, dim3((unsigned)((nA + nN + 255) / 256)), dim3(256), 0, s, P, W, *out);
+  if (!prepare_only) hipLaunchKernelGGL(tg_lists_kernel, dim3((unsigned)((nA + nN + 255) / 256)), dim3(256), 0, s, P, W, *out);
   // Persistent wavefronts pull nodes of their class and, when it is exhausted, of the lighter
   // classes.  The classes are independent and each is bound by the latency of its own
   // wavefronts, so the two light classes run on side streams next to the heavy one.
+  if (prepare_only) return TG_OK;
+  if (before_nodes) TG_HIP_CHECK(hipStreamWaitEvent(s, before_nodes, 0));
   TG_HIP_CHECK(hipEventRecord(p->ev_fork, s));
   // LDS decides how many wavefronts a CU holds.  The heaviest class that can have nodes gets one
   // wavefront per possible node as far as 80 % of a CU's LDS go; its wavefronts that find no node

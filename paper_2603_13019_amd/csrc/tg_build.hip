@@ -444,9 +444,9 @@ extern "C" int tg_build_problem(const tg_problem_desc* desc, void* hip_stream, t
 
     // ---------------- ship
     p->arena_bytes = ar.host.size();
-    if (nA * (size_t)K >= (1ull << 31)) { delete p; return TG_E_RANGE; }        // (action, option) pairs are indexed in 32 bits
+    if (nA * (size_t)(K + 1) >= (1ull << 31)) { delete p; return TG_E_RANGE; }  // the slots of the score scratch are indexed in 32 bits
     if (hipMalloc(&p->d_arena, p->arena_bytes) != hipSuccess) { delete p; return TG_E_NOMEM; }
-    if (hipMalloc((void**)&p->d_score_dur, std::max<size_t>(nA * K, 1) * 8) != hipSuccess) { (void)hipFree(p->d_arena); delete p; return TG_E_NOMEM; }
+    if (hipMalloc((void**)&p->d_score_dur, std::max<size_t>(nA * (K + 1), 1) * 8) != hipSuccess) { (void)hipFree(p->d_arena); delete p; return TG_E_NOMEM; }
     hipStream_t s = (hipStream_t)hip_stream;
     if (hipMemcpyAsync(p->d_arena, ar.host.data(), ar.host.size(), hipMemcpyHostToDevice, s) != hipSuccess ||
         hipStreamSynchronize(s) != hipSuccess) {

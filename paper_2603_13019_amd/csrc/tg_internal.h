@@ -129,7 +129,7 @@ struct tg_problem {
   int max_heap;            // largest free + busy over CPU and GPU nodes
   size_t nodes_free_gt16, nodes_free_gt64;   // nodes with more than 16 / 64 free units: bounds on the nodes that can hold as many candidates
   int max_free_gpu, max_chunk_states;
-  int64_t* d_score_dur;    // [B*N*K] scratch of tg_score_candidates: getDur per (kind-grouped row, option); every call
+  int64_t* d_score_dur;    // [B*N*(K+1)] scratch of tg_score_candidates: getDur per (kind-grouped row, option), then the row's pin; every call
                            // writes the same values, so calls that overlap do not disturb each other
 };
 

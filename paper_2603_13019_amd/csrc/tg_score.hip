@@ -25,8 +25,14 @@
 
 namespace {
 
-constexpr int kThreads = 128;
-static_assert(TG_SCORE_CHUNK == 4 * kThreads, "every lane stores two pairs of entries");
+#ifndef TG_SCORE_PAIRS
+#define TG_SCORE_PAIRS 4
+#endif
+constexpr int kPairs = TG_SCORE_PAIRS;                  // 16-byte pairs every lane stores
+constexpr int kThreads = TG_SCORE_CHUNK / (2 * kPairs);
+constexpr int kWaveSpan = 2 * TG_WAVE * kPairs;         // entries per wavefront
+constexpr int kWaveRows = kPairs <= 2 ? 2 : 3;          // rows of 256 entries or more that span can touch
+static_assert(kThreads % TG_WAVE == 0 && (kPairs == 2 || kPairs == 4), "whole wavefronts, two or four pairs per lane");
 
 // The few fields of a problem the kernels read (a short argument list: its loads are the first
 // thing every workgroup waits for).
@@ -38,12 +44,12 @@ struct ScoreArgs {
   const uint64_t* row_svc;        // SVC only
   const uint64_t* node_res_k;     // SVC only
   const uint32_t* speedup;
-  int64_t* dur;                   // [rows * K] getDur per (kind-grouped row, option), TG_INF where not allowed
+  int64_t* dur;                   // [rows * (K + 1)] per kind-grouped row: getDur per option (TG_INF where not allowed), then the row's pin
   int64_t* cost;
   uint64_t kword;                 // unit counts, one byte each
-  int K;                          // options per row of dur and of the speedup table
-  uint32_t magic_K;               // floor(2^32 / K) + 1
-  uint32_t n_rows_K;              // rows * K
+  int K;                          // options per row of the speedup table; a row of dur has one slot more
+  uint32_t magic_K1;              // floor(2^32 / (K + 1)) + 1
+  int N, M;                       // actions and nodes per snapshot
 };
 
 // x / d for x < 2^31, with inv = 1.0 / d: the product is within 2^-21 of the true quotient, so
@@ -57,22 +63,38 @@ __device__ inline uint32_t div_u31(uint32_t x, uint32_t d, double inv) {
 
 // Eq. 1 for every (row, option), rows in kind-grouped order; one lane per pair.  The three
 // elasticity models are three (numerator, denominator) pairs of the same rounded-up division,
-// so the lanes of a wavefront do not diverge on the model.
+// so the lanes of a wavefront do not diverge on the model.  A row of the scratch array holds
+// the K durations and, in a last slot, the row's pin - so that a score workgroup fetches all it
+// needs of its rows with one load.  The kernel also reads every node word once: the score
+// kernel's workgroups are too short-lived to wait for memory, and what was read just before
+// them is still in the memory-side cache when they ask for it.
 __global__ __launch_bounds__(256) void tg_score_dur_kernel(const ScoreArgs A) {
-  const uint32_t x = blockIdx.x * 256u + threadIdx.x;
-  if (x >= A.n_rows_K) return;
-  uint32_t g = A.K == 1 ? x : __umulhi(x, A.magic_K);                     // x / K, at most one too large
-  if (g * (uint32_t)A.K > x) --g;
-  const int q = (int)(x - g * (uint32_t)A.K);
-  const TgRowRec rec = A.row_rec[g];
-  const bool amdahl = rec.model == TG_MODEL_AMDAHL, table = rec.model == TG_MODEL_TABLE;
-  const uint32_t k = (uint32_t)(A.kword >> (8 * q) & 0xff);
-  const uint32_t sp = A.speedup[table ? rec.param * (uint32_t)A.K + (uint32_t)q : 0u];
-  const uint32_t w = (1000000u - rec.param) * k + rec.param;             // < 2^26
-  const uint64_t num = amdahl ? (uint64_t)rec.T * w : table ? (uint64_t)rec.T << 16 : (uint64_t)rec.T;
-  const uint32_t den = amdahl ? 1000000u * k : table ? sp : 1u;
-  const int64_t d = tg_ceil_div(num, den);
-  A.dur[x] = (rec.kmask >> q & 1u) ? (d < 1 ? 1 : d) : TG_INF;
+  const uint32_t x = blockIdx.x * 256u + threadIdx.x;                     // slot inside the snapshot
+  const TgScoreKind& first = A.snaps[blockIdx.y].kind[0];                 // its rows and nodes start where those of its first kind do
+  const uint32_t K1 = (uint32_t)A.K + 1u;
+  if (x >= (uint32_t)A.N * K1) return;
+  uint32_t r = __umulhi(x, A.magic_K1);                                   // x / (K + 1), at most one too large
+  if (r * K1 > x) --r;
+  const int q = (int)(x - r * K1);
+  const size_t g = (size_t)first.a_off + r;
+  const uint64_t warm = x < (uint32_t)A.M ? A.node_word[(size_t)first.n_off + x] : 0ull;   // never all ones (the options are counted in 4 bits)
+  int64_t out;
+  if (q == A.K) out = __builtin_nontemporal_load(A.row_pin + g);
+  else {
+    // read once: kept out of the caches the score kernel's inputs should stay in
+    const int64_t T = __builtin_nontemporal_load(&A.row_rec[g].T);
+    const uint64_t rest = __builtin_nontemporal_load(reinterpret_cast<const uint64_t*>(&A.row_rec[g].param));
+    const uint32_t param = (uint32_t)rest, kmask = (uint32_t)(rest >> 32) & 0xffffu, model = (uint32_t)(rest >> 48) & 0xffu;
+    const bool amdahl = model == TG_MODEL_AMDAHL, table = model == TG_MODEL_TABLE;
+    const uint32_t k = (uint32_t)(A.kword >> (8 * q) & 0xff);
+    const uint32_t sp = A.speedup[table ? param * (uint32_t)A.K + (uint32_t)q : 0u];
+    const uint32_t w = (1000000u - param) * k + param;                   // < 2^26
+    const uint64_t num = amdahl ? (uint64_t)T * w : table ? (uint64_t)T << 16 : (uint64_t)T;
+    const uint32_t den = amdahl ? 1000000u * k : table ? sp : 1u;
+    const int64_t d = tg_ceil_div(num, den);
+    out = (kmask >> q & 1u) ? (d < 1 ? 1 : d) : TG_INF;
+  }
+  A.dur[g * K1 + (uint32_t)q] = warm == ~0ull ? 0 : out;
 }
 
 // v of lane `src` (any lane may ask for any lane's value)
@@ -101,49 +123,58 @@ __device__ inline void score_chunk(const ScoreArgs& A, const uint32_t (&k)[kKind
   const int e0 = x * TG_SCORE_CHUNK - odd;                                // may be -1
   const int e1 = min(n, e0 + TG_SCORE_CHUNK);
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int w0 = e0 + wave * 256;                                         // first pair of this wavefront
+  const int w0 = e0 + wave * kWaveSpan;                                   // first pair of this wavefront
   if (w0 >= e1) return;                                                   // nothing left for it in the block
   const int f0 = w0 < 0 ? 0 : w0;                                         // its first existing entry
-  const int row0 = (int)div_u31((uint32_t)f0, Lr, inv_lr);
+  // the wavefront's first entry: its row, node and option - the same in all lanes, kept in scalar registers
+  const int row0 = __builtin_amdgcn_readfirstlane((int)div_u31((uint32_t)f0, Lr, inv_lr));
   const uint32_t col0 = (uint32_t)f0 - (uint32_t)row0 * Lr;               // place of entry f0 in its row
+  const int j0 = (int)((col0 * mk) >> 20), q0 = (int)col0 - j0 * K;       // col0 / K: exact for col0 < 2^17
 
   const uint64_t* words = A.node_word + n_off;
   const uint64_t* resk = SVC ? A.node_res_k + n_off : nullptr;
-  const int64_t* dur = A.dur + (size_t)a_off * A.K;
-  const int32_t* pins = A.row_pin + a_off;
+  const int K1 = A.K + 1;                                                // slots per row of dur: the options, then the pin
+  const int64_t* dur = A.dur + (size_t)a_off * K1;
   const uint64_t* rsvc = SVC ? A.row_svc + a_off : nullptr;
-  // FAST: the wavefront's entries lie in two rows.  Lane z < 2K fetches getDur of (row z / K, option z % K), lanes 0
-  // and 1 the pins of the two rows; every lane then picks what its entries need out of those lanes' registers
-  // (one data exchange inside the wavefront instead of a load per entry).
+  // FAST: the wavefront's entries lie in two rows.  Lane z < 2 (K + 1) fetches slot z % (K + 1) of row z / (K + 1)
+  // (durations, then the pin); every lane then picks what its entries need out of those lanes' registers (one data
+  // exchange inside the wavefront instead of loads per entry).
   int64_t dv = 0;
   uint64_t sv2 = 0;
-  int pv = 0;
   if (FAST) {
-    const int r = lane >= K ? 1 : 0;
-    const int rd = min(row0 + r, row_last), rp = min(row0 + (lane & 1), row_last);
-    if (lane < 2 * K) dv = dur[(size_t)rd * A.K + (lane - r * K)];
-    if (lane < 2) { pv = pins[rp]; if (SVC) sv2 = rsvc[rp]; }
+    const int r = lane >= 2 * K1 ? 2 : lane >= K1 ? 1 : 0;
+    const int rd = min(row0 + r, row_last), rp = min(row0 + min(lane, kWaveRows - 1), row_last);
+    if (lane < kWaveRows * K1) dv = dur[(size_t)rd * K1 + (lane - r * K1)];
+    if (SVC && lane < kWaveRows) sv2 = rsvc[rp];
   }
 
-  // values of both pairs first, then the two stores back to back (nothing is waited for between them)
-  int64_t v[2][2];
+  // values of all pairs first, then the stores back to back (nothing is waited for between them)
+  int64_t v[kPairs][2];
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < kPairs; ++i) {
     const int p = w0 + i * 128 + 2 * lane;
     const int pa = min(max(p, 0), n - 1);                                 // coordinates are taken inside the block
-    int row;
-    uint32_t col;
-    if (FAST) {                                                           // the wavefront crosses at most one row end
-      col = col0 + (uint32_t)(pa - f0);
-      const bool wrap = col >= Lr;
-      col -= wrap ? Lr : 0u;
-      row = row0 + (wrap ? 1 : 0);
+    int row, j, q;
+    if (FAST) {
+      // (node, option) of the entry from those of the wavefront's first entry: the offset is below 512, so the
+      // division by K is a 24-bit multiplication (full rate); at most kWaveRows - 1 row ends are crossed
+      const uint32_t t = (uint32_t)q0 + (uint32_t)(pa - f0);
+      const uint32_t ja = __umul24(t, mk) >> 20;                          // t / K: exact for t < 2^17
+      q = (int)(t - __umul24(ja, (uint32_t)K));
+      j = j0 + (int)ja;
+      row = row0;
+#pragma unroll
+      for (int w = 1; w < kWaveRows; ++w) {
+        const bool wrap = j >= Mt;
+        j -= wrap ? Mt : 0;
+        row += wrap ? 1 : 0;
+      }
     } else {
       row = (int)div_u31((uint32_t)pa, Lr, inv_lr);
-      col = (uint32_t)pa - (uint32_t)row * Lr;
+      const uint32_t col = (uint32_t)pa - (uint32_t)row * Lr;
+      j = (int)((col * mk) >> 20);                                        // col / K: exact for col < 2^17
+      q = (int)col - j * K;
     }
-    const int j = (int)((col * mk) >> 20);                                // col / K: exact for col < 2^17
-    const int q = (int)col - j * K;
     // the second entry of the pair is one step on - unless entry p = -1 does not exist: then entry 0 is the second
     const bool step = p >= 0;
     const bool wq = step && q + 1 == K, wj = wq && j + 1 == Mt;
@@ -156,12 +187,12 @@ __device__ inline void score_chunk(const ScoreArgs& A, const uint32_t (&k)[kKind
       int64_t d;
       int pin;
       if (FAST) {
-        const int rl = rows[h] - row0;
-        nw = words[js[h]];
-        d = lane_pick64(dv, rl * K + qs[h]); pin = __builtin_amdgcn_ds_bpermute(rl * 4, pv);
+        const int rl = rows[h] - row0, base = (int)__umul24((uint32_t)rl, (uint32_t)K1);
+        nw = *reinterpret_cast<const uint64_t*>(reinterpret_cast<const char*>(words) + ((uint32_t)js[h] << 3));   // 32-bit offset from a uniform base
+        d = lane_pick64(dv, base + qs[h]); pin = __builtin_amdgcn_ds_bpermute((base + A.K) * 4, (int)(uint32_t)dv);
         if (SVC) { res = resk[js[h]]; sw = (uint64_t)lane_pick64((int64_t)sv2, rl); }
       } else {
-        nw = words[js[h]]; d = dur[(size_t)rows[h] * A.K + qs[h]]; pin = pins[rows[h]];
+        nw = words[js[h]]; d = dur[(size_t)rows[h] * K1 + qs[h]]; pin = (int)dur[(size_t)rows[h] * K1 + A.K];
         if (SVC) { res = resk[js[h]]; sw = rsvc[rows[h]]; }
       }
       const bool ok = (d != TG_INF) & (qs[h] < (int)(nw >> 48)) & ((pin == -1) | (pin == js[h]));   // no short cut: no load waits for another
@@ -175,7 +206,7 @@ __device__ inline void score_chunk(const ScoreArgs& A, const uint32_t (&k)[kKind
   }
   int64_t* out = A.cost + cost_off;
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < kPairs; ++i) {
     const int p = w0 + i * 128 + 2 * lane;
     const bool ok0 = p >= 0 && p < e1, ok1 = p + 1 < e1;
     if (ok0 && ok1) {
@@ -228,17 +259,23 @@ int tg_launch_score(const tg_problem* p, int64_t* d_cost, hipStream_t s) {
   a.row_rec = p->dev.row_rec; a.row_pin = p->dev.row_pin; a.node_word = p->dev.node_word;
   a.row_svc = p->dev.row_svc; a.node_res_k = p->dev.node_res_k; a.speedup = p->dev.speedup;
   a.dur = p->d_score_dur; a.cost = d_cost; a.kword = tg_pack_k(p->dev.k_list); a.K = p->dev.K;
-  a.magic_K = a.K > 1 ? (uint32_t)((1ull << 32) / (uint32_t)a.K) + 1u : 0u;
-  const size_t pairs = (size_t)p->dev.B * p->dev.N * a.K;                 // < 2^32: checked when the problem was built
-  a.n_rows_K = (uint32_t)pairs;
-  a.snaps = p->d_score_snaps;
-  hipLaunchKernelGGL(tg_score_dur_kernel, dim3((unsigned)((pairs + 255) / 256)), dim3(256), 0, s, a);
-  for (const TgScoreLaunch& g : p->score_launches) {
-    a.snaps = p->d_score_snaps + g.first;
-    const dim3 grid((unsigned)g.max_chunks, (unsigned)g.n_snaps, 1);
-    if (svc) hipLaunchKernelGGL(tg_score_kernel<true>, grid, dim3(kThreads), 0, s, a);
-    else hipLaunchKernelGGL(tg_score_kernel<false>, grid, dim3(kThreads), 0, s, a);
-  }
+  a.magic_K1 = (uint32_t)((1ull << 32) / (uint32_t)(a.K + 1)) + 1u;
+  a.N = p->dev.N; a.M = p->dev.M;
+  // Slabs of snapshots, each first through tg_score_dur_kernel and then through tg_score_kernel: the durations of a
+  // slab (about 24 MB) are read while they are still in the memory-side cache, whatever ran before the call and
+  // whatever runs next to it.
+  const size_t per_snap = (size_t)a.N * (a.K + 1) * 8;
+  const int slab = (int)std::max<size_t>(1, std::min<size_t>(65535, (24u << 20) / std::max<size_t>(per_snap, 1)));
+  const unsigned dur_x = (unsigned)(((size_t)a.N * (a.K + 1) + 255) / 256);
+  for (const TgScoreLaunch& g : p->score_launches)
+    for (int s0 = 0; s0 < g.n_snaps; s0 += slab) {
+      const int n = std::min(slab, g.n_snaps - s0);
+      a.snaps = p->d_score_snaps + g.first + s0;
+      hipLaunchKernelGGL(tg_score_dur_kernel, dim3(dur_x, (unsigned)n, 1), dim3(256), 0, s, a);
+      const dim3 grid((unsigned)g.max_chunks, (unsigned)n, 1);
+      if (svc) hipLaunchKernelGGL(tg_score_kernel<true>, grid, dim3(kThreads), 0, s, a);
+      else hipLaunchKernelGGL(tg_score_kernel<false>, grid, dim3(kThreads), 0, s, a);
+    }
   return hipGetLastError() == hipSuccess ? TG_OK : TG_E_HIP;
 }
 

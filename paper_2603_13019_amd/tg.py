@@ -68,7 +68,7 @@ _DT = dict(k_list=np.int32, type_k=np.int32, speedup_q16=np.uint32, node_type=np
            node_core_free=np.uint64, act_quota_mask=np.uint64, node_aux=np.int32)
 
 EXPORTS = ("tg_build_problem", "tg_free_problem", "tg_num_candidates", "tg_assign_workspace_bytes",
-           "tg_score_candidates", "tg_assign", "tg_assign_static", "tg_step", "tg_build_trace", "tg_free_trace", "tg_replay_workspace_bytes",
+           "tg_score_candidates", "tg_assign", "tg_assign_static", "tg_step", "tg_step_on", "tg_build_trace", "tg_free_trace", "tg_replay_workspace_bytes",
            "tg_replay_trace", "tg_strerror")
 
 
@@ -94,6 +94,7 @@ def load():
         L.tg_assign.argtypes = [vp, vp, vp, vp, C.c_size_t, vp]
         L.tg_assign_static.argtypes = [vp, vp, vp, vp]
         L.tg_step.argtypes = [vp, vp, vp, vp, C.c_size_t, vp]
+        L.tg_step_on.argtypes = [vp, vp, vp, vp, C.c_size_t, vp, vp]
         L.tg_build_trace.argtypes = [vp, vp, C.POINTER(vp)]
         L.tg_free_trace.argtypes = [vp]
         L.tg_free_trace.restype = None
@@ -217,12 +218,17 @@ class Problem:
         _check(load().tg_assign_static(self._h, _ptr(cost), C.byref(o), _stream()), "tg_assign_static")
         return bufs
 
-    def step(self, cost, bufs):
-        """tg_step: the score tensor into ``cost`` and the assignment into ``bufs`` in one call."""
+    def step(self, cost, bufs, score_stream=None):
+        """tg_step: the score tensor into ``cost`` and the assignment into ``bufs`` in one call; with ``score_stream``
+        (a torch.cuda.Stream other than the current one) tg_step_on: the score kernels run on that stream."""
         o = AssignOut()
         for n, _ in AssignOut._fields_:
             setattr(o, n, bufs[n].data_ptr() if bufs.get(n) is not None else None)
-        _check(load().tg_step(self._h, _ptr(cost), C.byref(o), _ptr(bufs["ws"]), bufs["ws"].numel(), _stream()), "tg_step")
+        if score_stream is None:
+            _check(load().tg_step(self._h, _ptr(cost), C.byref(o), _ptr(bufs["ws"]), bufs["ws"].numel(), _stream()), "tg_step")
+        else:
+            _check(load().tg_step_on(self._h, _ptr(cost), C.byref(o), _ptr(bufs["ws"]), bufs["ws"].numel(), _stream(),
+                                     C.c_void_p(score_stream.cuda_stream)), "tg_step_on")
         return cost, bufs
 
 
