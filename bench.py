@@ -27,10 +27,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of tg_score_kernel on workload 3 from the FETCH_SIZE / WRITE_SIZE counter runs
-# (profiles/score_config3_hbm_counters.md), each scaled by what the same counter reads for a plain device copy of
-# the tensor.  Valid for the kernel as profiled; None once tg_score_kernel has changed since.
-SCORE_TRAFFIC_CONFIG3_BYTES = None
+# HBM bytes per tg_score_candidates call on workload 3 (8 slabs of tg_score_dur_kernel + tg_score_kernel) from the
+# FETCH_SIZE / WRITE_SIZE counter runs (profiles/score_config3_hbm_counters.md), each scaled by what the same counter reads
+# for a plain device copy of the tensor: (26 108 256 + 196 608) KiB written x 1.000 + (535 280 + 50 968) KiB fetched x 2.000.
+# Valid for the kernels as profiled; set to None when they change.
+SCORE_TRAFFIC_CONFIG3_BYTES = (26108256 + 196608 + 2 * (535280 + 50968)) * 1024
 
 
 def order_section(a, tg, torch, p, s_fcfs):
