@@ -48,10 +48,6 @@ struct AssignWs {
 constexpr int kClasses = 3;
 constexpr int kSelRows = 32;     // prefix lengths backtracked per batch
 constexpr int kLightBatch = 8;   // nodes of the light class a wavefront takes per fetch
-// One wavefront per node.  Teams of several wavefronts (tg_node_schedule<NW>, NW > 1) are
-// implemented but switched off: on workload 2 a launch with NW = 4 did not finish, and the cause
-// has not been found yet, so only NW = 1 (no workgroup barrier anywhere) is instantiated.
-constexpr int kClassWaves[kClasses] = {1, 1, 1};
 constexpr int kClassCap0 = 16, kClassCap1 = 64;
 __host__ __device__ constexpr int class_cap(int c) { return c == 0 ? kClassCap0 : c == 1 ? kClassCap1 : 1 << 30; }
 
@@ -484,7 +480,7 @@ __global__ __launch_bounds__(TG_WAVE) void tg_node_kernel(TgDev P, const int64_t
       out.node = O.node + abase; out.units = O.units + abase; out.act = O.act_us + abase; out.reason = O.defer_reason + abase;
       out.age = P.act_age + abase;
       int used = 0;
-      const int64_t obj = single ? tg_node_single(in, out, lane, &used) : tg_node_schedule<1>(smem, plan, in, out, lane, 0, &used);
+      const int64_t obj = single ? tg_node_single(in, out, lane, &used) : tg_node_schedule(smem, plan, in, out, lane, &used);
       if (lane == 0) {
         if (O.node_obj) O.node_obj[gn] = obj;
         if (O.node_used) O.node_used[gn] = used;
@@ -762,7 +758,7 @@ int assign_launch(const tg_problem* p, const int64_t* d_cost, const tg_assign_ou
   TgNodeLdsPlan plans[kClasses];
   int max_lds = 0;
   for (int c = 0; c < kClasses; ++c) {
-    plans[c] = tg_node_lds_plan(p->max_free_cpu, p->max_free_gpu, p->max_chunk_states, p->max_heap, P.K, class_cap(c), kSelRows, kClassWaves[c]);
+    plans[c] = tg_node_lds_plan(p->max_free_cpu, p->max_free_gpu, p->max_chunk_states, p->max_heap, P.K, class_cap(c), kSelRows);
     max_lds = plans[c].total > max_lds ? plans[c].total : max_lds;
   }
   const int busy_lds = ((p->max_heap + 1) & ~1) * 8;              // a node's busy list has at most max_heap entries
@@ -860,7 +856,6 @@ int assign_launch(const tg_problem* p, const int64_t* d_cost, const tg_assign_ou
     const unsigned grid = (unsigned)grids[c];
     hipStream_t cs = c < 2 ? p->side_stream[c] : s;
     if (c < 2) { TG_HIP_CHECK(hipStreamWaitEvent(cs, p->ev_fork, 0)); forked[c] = true; }
-    static_assert(kClassWaves[0] == 1 && kClassWaves[1] == 1 && kClassWaves[2] == 1, "only single-wavefront teams are enabled");
     hipLaunchKernelGGL(tg_node_kernel, dim3(grid), dim3(TG_WAVE), plans[c].total + busy_lds, cs, P, W.dur, W, *out, plans[c], c,
                        grids[0], grids[1], grids[2]);
     if (c < 2) TG_HIP_CHECK(hipEventRecord(p->ev_join[c], cs));

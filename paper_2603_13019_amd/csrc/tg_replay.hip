@@ -438,7 +438,7 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
       out.node = o_node; out.units = o_units; out.act = nullptr; out.reason = reason; out.age = nullptr;
       int used_units;
       if (single) tg_node_single(in, out, lane, &used_units);
-      else tg_node_schedule<1>(node_mem, plan, in, out, lane, 0, &used_units);
+      else tg_node_schedule(node_mem, plan, in, out, lane, &used_units);
      }
     }
     __threadfence_block();
@@ -824,7 +824,7 @@ extern "C" int tg_replay_trace(const tg_trace* t, const tg_replay_out* out, void
   const TgTraceDev& T = t->dev;
   ReplayWs W;
   carve(T, (char*)d_ws, &W);
-  const TgNodeLdsPlan plan = tg_node_lds_plan(t->max_cap_cpu, 8, t->max_chunk_states, t->max_heap, T.K, 1 << 30, 8, 1, TG_WAVE);
+  const TgNodeLdsPlan plan = tg_node_lds_plan(t->max_cap_cpu, 8, t->max_chunk_states, t->max_heap, T.K, 1 << 30, 8, TG_WAVE);
   // LDS of a workgroup: one placement block per kind, then one per-node block for each wavefront
   // that runs DPArrange.  Two workgroups fit a CU when the total stays under half of its LDS, so
   // large clusters give per-node blocks to fewer wavefronts rather than lose the second workgroup.

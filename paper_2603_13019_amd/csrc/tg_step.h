@@ -923,7 +923,7 @@ struct TgNodeLdsPlan {
   int off_q0;       // minimum-unit option of every candidate
   int cand_rows;    // candidates the per-candidate tables hold.  Nodes whose actions are elastic never have more (a
                     // candidate takes at least one of the node's free units); a quota may, its actions are never elastic
-  int heap_slots;   // heap entries per wavefront of the team
+  int heap_slots;   // heap entries
   int off_wd, off_wu, wait_slots;   // minimum-unit duration and unit count of the first waiting actions pinned to the node
   int total;        // bytes per wavefront
 };
@@ -932,7 +932,7 @@ struct TgNodeLdsPlan {
 // exceeds the node's free units either).  Quotas can hold more candidates than that: their
 // actions are not elastic, so they need none of the tables.
 __host__ static inline TgNodeLdsPlan tg_node_lds_plan(int max_free_cpu, int max_free_gpu, int max_states, int max_heap, int K,
-                                                      int m_cap = 1 << 30, int sel_rows = TG_WAVE, int n_waves = 1,
+                                                      int m_cap = 1 << 30, int sel_rows = TG_WAVE,
                                                       int wait_slots = TG_WAVE) {
   TgNodeLdsPlan p;
   const int m_cpu = max_free_cpu < m_cap ? max_free_cpu : m_cap, m_gpu = max_free_gpu < m_cap ? max_free_gpu : m_cap;
@@ -948,12 +948,12 @@ __host__ static inline TgNodeLdsPlan tg_node_lds_plan(int max_free_cpu, int max_
   size_t dp = dp64 > dp32 ? dp64 : dp32;
   p.heap_slots = (max_heap + 2) & ~1;
   const size_t heap = (size_t)p.heap_slots * 8;
-  // a single wavefront fills the DP rows first and stages heaps only afterwards: one block serves both
-  if (n_waves == 1 && heap > dp) dp = heap;
+  // the wavefront fills the DP rows first and stages heaps only afterwards: one block serves both
+  if (heap > dp) dp = heap;
   p.off_dp = take(dp);
   p.off_choice = take(choice + 16);
-  p.off_heap = n_waves == 1 ? p.off_dp : take(heap * n_waves);
-  p.off_F = take((size_t)(n_waves + 4) * 8);
+  p.off_heap = p.off_dp;
+  p.off_F = take(5 * 8);
   p.off_q0 = take((size_t)mmax);
   p.off_rowbest = take((size_t)(mmax + 1) * 8);
   p.off_rowarg = take((size_t)(mmax + 1) * 4);
@@ -1460,39 +1460,35 @@ __device__ static inline int64_t tg_node_single(const TgNodeIn& in, const TgNode
   return elastic ? d + in.backlog : -1;
 }
 
-// One node, scheduled by a team of NW wavefronts (NW = 1: a single wavefront, no workgroup
-// barrier anywhere).  Wavefront 0 fills the DPArrange table for all prefixes; the objective of
-// NW consecutive prefix lengths is then evaluated in parallel, one per wavefront, and the
-// greedy rule of Alg. 1 (stop at the first length whose objective does not drop) is applied to
-// the values in order, so the result is the sequential algorithm's.  Returns the final
-// approximated objective (or -1 when the node holds no elastic action and everything simply
-// runs on its minimum units).  `smem` is the team's LDS block laid out by `plan`.
-template <int NW>
+// One node, scheduled by one wavefront (no workgroup barrier anywhere): the DPArrange table for
+// all prefixes, then the greedy rule of Alg. 1 - evict from the tail while the approximated
+// objective of Alg. 2 drops.  Returns the final approximated objective (or -1 when the node
+// holds no elastic action and everything simply runs on its minimum units).  `smem` is the
+// wavefront's LDS block laid out by `plan`.
 __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgNodeLdsPlan& plan, const TgNodeIn& in,
-                                                  const TgNodeOut& out, int lane, int wave, int* used_units) {
+                                                  const TgNodeOut& out, int lane, int* used_units) {
   int64_t* s_cdur = reinterpret_cast<int64_t*>(smem + plan.off_cdur);
   int64_t* s_dp = reinterpret_cast<int64_t*>(smem + plan.off_dp);
   uint8_t* s_choice = smem + plan.off_choice;
   uint16_t* s_choice16 = reinterpret_cast<uint16_t*>(smem + plan.off_choice);
-  int64_t* s_heap = reinterpret_cast<int64_t*>(smem + plan.off_heap) + (size_t)wave * plan.heap_slots;   // per wavefront
+  int64_t* s_heap = reinterpret_cast<int64_t*>(smem + plan.off_heap);
   int64_t* s_rowbest = reinterpret_cast<int64_t*>(smem + plan.off_rowbest);
   int32_t* s_rowarg = reinterpret_cast<int32_t*>(smem + plan.off_rowarg);
   uint8_t* s_sel = smem + plan.off_sel;                           // [sel_rows][sel_stride] option of candidate x for L = top - l
   int32_t* s_k = reinterpret_cast<int32_t*>(smem + plan.off_k);
-  int64_t* s_F = reinterpret_cast<int64_t*>(smem + plan.off_F);   // [NW] objectives of one round, [NW] elastic?, [NW+1] time origin, [NW+2] 32-bit times? [NW+3] 32-bit DP?
+  int64_t* s_F = reinterpret_cast<int64_t*>(smem + plan.off_F);   // [1] elastic? [2] time origin [3] 32-bit times? [4] 32-bit DP?
   uint8_t* s_q0 = smem + plan.off_q0;                             // minimum-unit option of candidate x
   int64_t* s_wd = reinterpret_cast<int64_t*>(smem + plan.off_wd);
   uint8_t* s_wu = smem + plan.off_wu;
   const TgWaitLds W = {s_wd, s_wu, plan.wait_slots};
   const int m = in.m, K = in.K, U = in.free_units;
   const bool gpu = in.type == TG_TYPE_GPU;
-  auto team_sync = [&]() { if (NW > 1) __syncthreads(); else tg_wave_sync(); };
 
   const uint64_t kword = in.kword;                                // unit counts, one byte each
   auto k_of = [&](int q) { return (int)(kword >> (8 * q) & 0xff); };
 
-  team_sync();
-  if (wave == 0) {
+  tg_wave_sync();
+  {
     if (lane < TG_MAX_K) s_k[lane] = k_of(lane);
     // lane = candidate: its elasticity model and its row of durations as this node sees them
     // (options above the node's capacity removed, restore delay added) in two dependent round
@@ -1515,12 +1511,12 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
         }
     }
     const int any_el = __any(el);
-    if (lane == 0) s_F[NW] = any_el ? 1 : 0;
+    if (lane == 0) s_F[1] = any_el ? 1 : 0;
   }
-  team_sync();
-  if (s_F[NW] == 0) {                                             // Alg. 1: no elastic action in the group, nothing to scale
+  tg_wave_sync();
+  if (s_F[1] == 0) {                                             // Alg. 1: no elastic action in the group, nothing to scale
     int used = 0;
-    if (wave == 0) {
+    {
       for (int x = lane; x < m; x += TG_WAVE) {
         const int id = in.clist[x];
         const int q0 = __builtin_ctz(in.act_kmask[id]);
@@ -1535,7 +1531,7 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
   }
 
   int stride = 0;                                                 // entries per choice row
-  if (wave == 0) {
+  {
     tg_wave_sync();                                               // the rows staged above
     // minimum-unit option of every candidate, and the range all times of this node's estimates
     // stay in: above `lo`, below the latest initial release plus every waiting duration
@@ -1569,9 +1565,9 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
       bmin = (int64_t)tg_wave_min_u64((uint64_t)bmin);
       const int64_t top_t = in.backlog + maxd > bmax ? in.backlog + maxd : bmax;
       if (lane == 0) {
-        s_F[NW + 1] = bmin;
-        s_F[NW + 2] = (top_t + sumd - bmin) < 0xfffffff0ll ? 1 : 0;   // estimates in 32 bits
-        s_F[NW + 3] = sumc < (int64_t)kDpInf32 ? 1 : 0;               // DP totals below the 32-bit "unreachable" mark
+        s_F[2] = bmin;
+        s_F[3] = (top_t + sumd - bmin) < 0xfffffff0ll ? 1 : 0;   // estimates in 32 bits
+        s_F[4] = sumc < (int64_t)kDpInf32 ? 1 : 0;               // DP totals below the 32-bit "unreachable" mark
       }
       tg_wave_sync();
     }
@@ -1587,7 +1583,7 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
       sm = tg_wave_sum_i32(sm);
       const int n = min(U, sm);
       stride = tg_choice_stride(n);
-      if (s_F[NW + 3] != 0) {
+      if (s_F[4] != 0) {
         uint32_t* r0 = reinterpret_cast<uint32_t*>(s_dp) + TG_WAVE;               // cell 0 of the two rows
         uint32_t* r1 = r0 + plan.dp_width + 2 + TG_WAVE;
         switch (K) {
@@ -1653,17 +1649,17 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
 
   // ---- Alg. 2: objective of keeping the first L candidates ---------------------------------
   const int H = U + in.n_busy;
-  team_sync();                                                     // wavefront 0's tables are complete
-  const int64_t t_lo = s_F[NW + 1];
-  const bool narrow = s_F[NW + 2] != 0;
+  tg_wave_sync();                                                     // wavefront 0's tables are complete
+  const int64_t t_lo = s_F[2];
+  const bool narrow = s_F[3] != 0;
   // Allocations of up to 64 consecutive prefix lengths at once: lane l of wavefront 0 walks the
   // choice table back from the best end state of C[:top-l]; evaluations only look them up.
-  int top = 0;                                                     // uniform over the team
+  int top = 0;                                                     // longest prefix the allocation table covers
   auto backtrack_batch = [&](int new_top) {
     top = new_top;
-    team_sync();                                                   // nobody still reads the old table
+    tg_wave_sync();                                                   // nobody still reads the old table
     const int Lm = top - lane;
-    if (wave == 0 && lane < plan.sel_rows && Lm >= 1) {
+    if (lane < plan.sel_rows && Lm >= 1) {
       int st = s_rowarg[Lm];
       uint8_t* row = s_sel + (size_t)lane * plan.sel_stride;
       int hold = 0;                                                // option of the odd candidate of the current byte
@@ -1675,7 +1671,7 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
         else { row[(i - 1) >> 1] = (uint8_t)(q | hold << 4); hold = 0; }
       }
     }
-    team_sync();
+    tg_wave_sync();
   };
   auto objective = [&](int L) -> int64_t {                         // one wavefront, table covers L
     const uint8_t* sel = s_sel + (size_t)(top - L) * plan.sel_stride;
@@ -1705,33 +1701,19 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
   };
 
   // ---- Alg. 1's eviction loop: evict from the tail while the objective drops ----------------
-  // Round by round, wavefront w evaluates the prefix length base - w; the values are then
-  // consumed in decreasing length exactly as the sequential loop would.
   int L = m;                                                       // accepted length
-  int64_t obj = 0;
-  bool have = false, done = false;
-  int base = m;
-  while (!done) {
-    const int lowest = max(base - NW + 1, 1);
-    if (base > top || lowest <= top - plan.sel_rows) backtrack_batch(base);
-    const int mine = base - wave;
-    if (mine >= 1) { const int64_t f = objective(mine); if (lane == 0) s_F[wave] = f; }
-    team_sync();
-    for (int w = 0; w < NW && !done; ++w) {
-      const int Lc = base - w;
-      if (Lc < 1) { done = true; break; }
-      const int64_t f = s_F[w];
-      if (!have) { obj = f; have = true; L = Lc; }
-      else if (f >= obj) done = true;                              // a tie stops the eviction
-      else { obj = f; L = Lc; }
-      if (L == 1) done = true;
-    }
-    base -= NW;
-    team_sync();                                                   // s_F is rewritten next round
+  if (L > top || L <= top - plan.sel_rows) backtrack_batch(L);
+  int64_t obj = objective(L);
+  while (L > 1) {
+    if (L - 1 <= top - plan.sel_rows) backtrack_batch(L - 1);
+    const int64_t f = objective(L - 1);
+    if (f >= obj) break;                                           // a tie stops the eviction
+    obj = f;
+    --L;
   }
   if (L > top || L <= top - plan.sel_rows) backtrack_batch(L);
   int used = 0;
-  if (wave == 0) {
+  {
     const uint8_t* sel = s_sel + (size_t)(top - L) * plan.sel_stride;
     for (int x = lane; x < m; x += TG_WAVE) {
       const int id = in.clist[x];
@@ -1748,7 +1730,7 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
     used = tg_wave_sum_i32(used);
   }
   *used_units = used;
-  team_sync();
+  tg_wave_sync();
   return obj;
 }
 
