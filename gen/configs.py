@@ -445,6 +445,51 @@ def with_extra_quotas(p, frac=0.5, seed=0, max_extra=3):
     return p
 
 
+def trace_with_aux(t, seed, scarce):
+    """Adds a second resource to a trace (in place): what every node has of it and what an action holds of it."""
+    rng = np.random.default_rng(seed + 5)
+    t["act_aux"] = rng.integers(0, 40, t["S"] * t["A"]).astype(np.int32)
+    t["node_aux"] = rng.integers(40 if scarce else 400, 120 if scarce else 4000, t["S"] * t["M"]).astype(np.int32)
+    return t
+
+
+def trace_with_services(t, seed, n_services, slots):
+    """Adds services to a trace (in place): the service of every GPU action (-1: none), restore times, cache slots."""
+    rng = np.random.default_rng(seed)
+    sv = rng.integers(-1, n_services, t["S"] * t["A"]).astype(np.int32)
+    sv[t["act_type"] != TYPE_GPU] = -1                         # services live on GPU nodes
+    t["act_service"] = sv
+    t["restore_us"] = (rng.integers(0, 9, n_services) * 150_000).astype(np.int64)
+    t["cache_slots"] = slots
+    return t
+
+
+def random_trace(seed):
+    """One small trace with cluster shape, load, tick limit, pins, depth, further quotas, services, the prefix rule,
+    a second resource and named cores drawn at random from ``seed``."""
+    rng = np.random.default_rng(seed)
+    n_cpu, n_gpu, n_api = int(rng.integers(0, 6)), int(rng.integers(0, 4)), int(rng.integers(0, 4))
+    if n_cpu + n_gpu + n_api == 0:
+        n_cpu = 2
+    probs = np.array([0.6 * (n_cpu > 0), 0.25 * (n_gpu > 0), 0.15 * (n_api > 0)])
+    t = make_trace(S=int(rng.integers(1, 5)), A=int(rng.integers(1, 600)), seed=seed,
+                   cluster=(n_cpu, int(rng.choice([4, 16, 48, 128])), n_gpu, n_api),
+                   type_probs=tuple((probs / probs.sum()).tolist()),
+                   rate_per_s=float(rng.choice([20.0, 100.0, 500.0])), horizon_s=float(rng.choice([1.0, 5.0, 20.0])),
+                   max_ticks=int(rng.choice([60, 5000, 60000])), pin_frac=float(rng.choice([0.0, 0.3, 0.8])))
+    t["depth"] = int(rng.integers(1, 5))
+    if n_api >= 2 and rng.random() < 0.6:
+        with_extra_quotas(t, frac=float(rng.random()), seed=seed, max_extra=int(rng.integers(1, 4)))
+    if n_gpu and rng.random() < 0.6:
+        trace_with_services(t, seed, n_services=int(rng.choice([1, 4, 20])), slots=int(rng.choice([1, 2, 5])))
+    t["queue_prefix"] = int(rng.random() < 0.3)                # one prefix of the whole queue per step
+    if rng.random() < 0.4:                                     # a second resource held by the actions that chose their node
+        trace_with_aux(t, seed, scarce=bool(rng.integers(0, 2)))
+    if rng.random() < 0.4:                                     # CPU actions get named cores
+        t["numa_cores"] = int(rng.choice([4, 8, 16, 32, 64]))
+    return t
+
+
 def with_fixed_dop(t, k):
     """Copy of a trace (or problem) in which every elastic action may only run on exactly ``k`` units
     (the fixed degree-of-parallelism baselines of the paper's scheduler ablation); actions that do not

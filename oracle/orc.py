@@ -113,6 +113,8 @@ def lib():
         L.orc_mask_alloc.argtypes = [C.POINTER(C.c_int), C.c_int]
         L.orc_replay.restype = None
         L.orc_replay.argtypes = [C.c_void_p, C.c_int, C.c_int] + [C.c_void_p] * 9
+        L.orc_replay_extents.restype = None
+        L.orc_replay_extents.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p]
         _lib = L
     return _lib
 
@@ -260,3 +262,18 @@ def replay(t, s_lo=0, s_hi=None):
                      ("start_us", "finish_us", "units", "node", "mean_act", "p99_act", "n_started", "n_ticks")],
                      out["core_set"].ctypes.data if "core_set" in out else None)
     return out
+
+
+EXTENTS = ("wait_cpu", "wait_gpu", "wait_api", "running", "cand_cpu_elastic", "cand_gpu_elastic", "cand_node",
+           "cand_step", "pinned_wait_step", "busy_units", "heap_entries", "chunk_states", "dp_cells", "nodes_cpu",
+           "nodes_gpu", "nodes_api")
+
+
+def replay_extents(t, s_lo=0, s_hi=None):
+    """Largest sizes the steps of each replayed scenario worked on: {name: [S] int64} (orc_replay_extents)."""
+    s, keep = _trace(t)
+    S = int(t["S"])
+    s_hi = S if s_hi is None else s_hi
+    ext = np.zeros((S, len(EXTENTS)), np.int64)
+    lib().orc_replay_extents(C.addressof(s), int(s_lo), int(s_hi), ext.ctypes.data)
+    return {n: ext[:, x].copy() for x, n in enumerate(EXTENTS)}

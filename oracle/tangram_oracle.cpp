@@ -738,9 +738,16 @@ static int mask_alloc(int& mask, int k) {               // best fit, lowest addr
 int orc_mask_chunks(int mask, uint8_t* out) { int c[4]; mask_chunks(mask, c); for (int x = 0; x < 4; ++x) out[x] = (uint8_t)c[x]; return 0; }
 int orc_mask_alloc(int* mask, int k) { return mask_alloc(*mask, k); }
 
-void orc_replay(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us, int64_t* finish_us, int32_t* units,
-                int32_t* node, double* mean_act, int64_t* p99_act, int32_t* n_started, int32_t* n_ticks,
-                uint64_t* core_set /* [S*A*4] or NULL; written when numa_cores > 0 */) {
+// `ext` (NULL, or [S * ORC_N_EXTENTS]) only observes: per scenario, the largest value over all steps of the
+// sizes a step works on (list lengths, candidates per node, heap entries ...).  No decision reads it.
+enum { ORC_EXT_WAIT_CPU = 0, ORC_EXT_WAIT_GPU, ORC_EXT_WAIT_API, ORC_EXT_RUNNING, ORC_EXT_CAND_CPU_ELASTIC,
+       ORC_EXT_CAND_GPU_ELASTIC, ORC_EXT_CAND_NODE, ORC_EXT_CAND_STEP, ORC_EXT_PINNED_WAIT_STEP, ORC_EXT_BUSY_UNITS,
+       ORC_EXT_HEAP_ENTRIES, ORC_EXT_CHUNK_STATES, ORC_EXT_DP_CELLS, ORC_EXT_NODES_CPU, ORC_EXT_NODES_GPU,
+       ORC_EXT_NODES_API, ORC_N_EXTENTS };
+
+static void replay_run(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us, int64_t* finish_us, int32_t* units,
+                       int32_t* node, double* mean_act, int64_t* p99_act, int32_t* n_started, int32_t* n_ticks,
+                       uint64_t* core_set, int64_t* ext) {
   const Tables tb{t->K, t->k_list, t->type_k, t->speedup_q16, t->depth, t->act_service ? t->restore_us : nullptr};
   const int A = t->A, M = t->M;
   for (int s = s_lo; s < s_hi; ++s) {
@@ -819,6 +826,37 @@ void orc_replay(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us, int64
           for (int c = 0; c < u.k; ++c) nodes[u.node].busy.push_back(u.fin - now);
       // (4) the scheduling step; (5) selected actions start now
       const StepOut o = step(tb, acts, nodes, ORDER_FCFS, numa, false, t->queue_prefix != 0);
+      if (ext) {
+        int64_t* e = ext + (size_t)s * ORC_N_EXTENTS;
+        auto up = [&](int x, int64_t v) { if (v > e[x]) e[x] = v; };
+        int64_t wk[3] = {0, 0, 0};
+        for (const Act& a : acts) ++wk[a.type];
+        up(ORC_EXT_WAIT_CPU, wk[T_CPU]); up(ORC_EXT_WAIT_GPU, wk[T_GPU]); up(ORC_EXT_WAIT_API, wk[T_API]);
+        up(ORC_EXT_RUNNING, (int64_t)running.size());
+        std::vector<int> cand(M, 0), elastic(M, 0);
+        int64_t cand_step = 0, pinned_wait = 0;
+        for (size_t w = 0; w < acts.size(); ++w) {
+          if (o.home[w] >= 0) { ++cand[o.home[w]]; ++cand_step; if (acts[w].model != 0) elastic[o.home[w]] = 1; }
+          else if (o.reason[w] == R_PREFIX && acts[w].pin >= 0) ++pinned_wait;
+        }
+        up(ORC_EXT_CAND_STEP, cand_step); up(ORC_EXT_PINNED_WAIT_STEP, pinned_wait);
+        for (int j = 0; j < M; ++j) {
+          if (cand[j] == 0) continue;
+          const Node& nd = nodes[j];
+          up(ORC_EXT_CAND_NODE, cand[j]);
+          if (nd.type == T_API) continue;
+          up(ORC_EXT_BUSY_UNITS, (int64_t)nd.busy.size());
+          up(ORC_EXT_HEAP_ENTRIES, (int64_t)nd.busy.size() + nd.free);
+          if (nd.type == T_GPU) {
+            int64_t st = 1;
+            for (int x = 0; x < 4; ++x) st *= std::max(nd.chunks[x], 1) + 1;
+            up(ORC_EXT_CHUNK_STATES, st);
+            if (elastic[j]) up(ORC_EXT_CAND_GPU_ELASTIC, cand[j]);
+          } else {
+            if (elastic[j]) { up(ORC_EXT_CAND_CPU_ELASTIC, cand[j]); up(ORC_EXT_DP_CELLS, (int64_t)nd.free + 1); }
+          }
+        }
+      }
       std::vector<int> still;
       for (size_t w = 0; w < waiting.size(); ++w) {
         const int i = waiting[w];
@@ -870,6 +908,33 @@ void orc_replay(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us, int64
     mean_act[s] = n ? (double)sum / (double)n : 0.0;
     p99_act[s] = n ? acts_done[(size_t)((99 * (int64_t)n + 99) / 100) - 1] : -1;   // nearest rank
   }
+}
+
+void orc_replay(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us, int64_t* finish_us, int32_t* units,
+                int32_t* node, double* mean_act, int64_t* p99_act, int32_t* n_started, int32_t* n_ticks,
+                uint64_t* core_set /* [S*A*4] or NULL; written when numa_cores > 0 */) {
+  replay_run(t, s_lo, s_hi, start_us, finish_us, units, node, mean_act, p99_act, n_started, n_ticks, core_set, nullptr);
+}
+
+// The same replay, reporting only what it observed: ext[s * 16 + x] = the largest value of extent x over the
+// steps of scenario s (rows of scenarios outside [s_lo, s_hi) are left alone).  Used to check, on the CPU, the
+// capacities a batched implementation sizes its buffers with.
+void orc_replay_extents(const orc_trace* t, int s_lo, int s_hi, int64_t* ext) {
+  const size_t nA = (size_t)t->S * t->A;
+  std::vector<int64_t> st(nA), fi(nA), p99(t->S);
+  std::vector<int32_t> un(nA), no(nA), ns(t->S), nt(t->S);
+  std::vector<double> mean(t->S);
+  std::vector<uint64_t> cs(t->numa_cores > 0 ? nA * 4 : 0);
+  for (int s = s_lo; s < s_hi; ++s) {
+    int64_t* e = ext + (size_t)s * ORC_N_EXTENTS;
+    for (int x = 0; x < ORC_N_EXTENTS; ++x) e[x] = 0;
+    for (int j = 0; j < t->M; ++j) {
+      const int ty = t->node_type[(size_t)s * t->M + j];
+      ++e[ty == T_CPU ? ORC_EXT_NODES_CPU : ty == T_GPU ? ORC_EXT_NODES_GPU : ORC_EXT_NODES_API];
+    }
+  }
+  replay_run(t, s_lo, s_hi, st.data(), fi.data(), un.data(), no.data(), mean.data(), p99.data(), ns.data(), nt.data(),
+             cs.empty() ? nullptr : cs.data(), ext);
 }
 
 }  // extern "C"

@@ -71,45 +71,13 @@ def test_replay_random_sweep(tg, orc):
     """60 small traces with cluster shape, load, tick limit, pins, depth, further quotas, services and the prefix rule
     drawn at random."""
     for seed in range(500, 560):
-        rng = np.random.default_rng(seed)
-        n_cpu, n_gpu, n_api = int(rng.integers(0, 6)), int(rng.integers(0, 4)), int(rng.integers(0, 4))
-        if n_cpu + n_gpu + n_api == 0:
-            n_cpu = 2
-        probs = np.array([0.6 * (n_cpu > 0), 0.25 * (n_gpu > 0), 0.15 * (n_api > 0)])
-        t = gen.make_trace(S=int(rng.integers(1, 5)), A=int(rng.integers(1, 600)), seed=seed,
-                           cluster=(n_cpu, int(rng.choice([4, 16, 48, 128])), n_gpu, n_api),
-                           type_probs=tuple((probs / probs.sum()).tolist()),
-                           rate_per_s=float(rng.choice([20.0, 100.0, 500.0])), horizon_s=float(rng.choice([1.0, 5.0, 20.0])),
-                           max_ticks=int(rng.choice([60, 5000, 60000])), pin_frac=float(rng.choice([0.0, 0.3, 0.8])))
-        t["depth"] = int(rng.integers(1, 5))
-        if n_api >= 2 and rng.random() < 0.6:
-            gen.with_extra_quotas(t, frac=float(rng.random()), seed=seed, max_extra=int(rng.integers(1, 4)))
-        if n_gpu and rng.random() < 0.6:
-            _with_services(t, seed, n_services=int(rng.choice([1, 4, 20])), slots=int(rng.choice([1, 2, 5])))
-        t["queue_prefix"] = int(rng.random() < 0.3)                # one prefix of the whole queue per step
-        if rng.random() < 0.4:                                     # a second resource held by the actions that chose their node
-            _with_aux(t, seed, scarce=bool(rng.integers(0, 2)))
-        if rng.random() < 0.4:                                     # CPU actions get named cores
-            t["numa_cores"] = int(rng.choice([4, 8, 16, 32, 64]))
+        t = gen.random_trace(seed)
         _compare(_replay_gpu(tg, t), orc.replay(t), range(t["S"]), t["A"])
     print("60 traces compared", flush=True)
 
 
-def _with_aux(t, seed, scarce):
-    rng = np.random.default_rng(seed + 5)
-    t["act_aux"] = rng.integers(0, 40, t["S"] * t["A"]).astype(np.int32)
-    t["node_aux"] = rng.integers(40 if scarce else 400, 120 if scarce else 4000, t["S"] * t["M"]).astype(np.int32)
-    return t
-
-
-def _with_services(t, seed, n_services, slots):
-    rng = np.random.default_rng(seed)
-    sv = rng.integers(-1, n_services, t["S"] * t["A"]).astype(np.int32)
-    sv[t["act_type"] != gen.TYPE_GPU] = -1                     # services live on GPU nodes
-    t["act_service"] = sv
-    t["restore_us"] = (rng.integers(0, 9, n_services) * 150_000).astype(np.int64)
-    t["cache_slots"] = slots
-    return t
+_with_aux = gen.trace_with_aux
+_with_services = gen.trace_with_services
 
 
 @pytest.mark.parametrize("seed", range(8))
