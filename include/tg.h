@@ -349,6 +349,34 @@ void tg_free_trace(tg_trace *t);
 int tg_replay_workspace_bytes(const tg_trace *t, size_t *bytes);
 int tg_replay_trace(const tg_trace *t, const tg_replay_out *out, void *d_ws, size_t ws_bytes, void *hip_stream);
 
+/*
+ * Capacities of the replay's buffers, for checking on the host (Sec. 4.2's step works on lists and
+ * tables whose sizes change from tick to tick; the replay kernel sizes its local-memory blocks and
+ * workspace slices once per trace).  tg_replay_capacity reads only the host arrays of `desc`
+ * (node_type, node_cap and the scalar fields), touches no device and fills cap[TG_REPLAY_N_CAPS]
+ * (host) with the largest value each quantity may take in a step of a scenario of this trace for
+ * every index of the kernel to stay inside its block:
+ *   WAIT_CPU / WAIT_GPU / WAIT_API   length of a kind's waiting list
+ *   RUNNING                          running CPU and GPU actions
+ *   CAND_CPU_ELASTIC / _GPU_ELASTIC  candidates on one CPU / GPU node that has an elastic candidate (rows of the
+ *                                    duration, choice, best-total and allocation tables)
+ *   CAND_NODE                        candidates on any one node (a quota's are bounded by its list only)
+ *   CAND_STEP / PINNED_WAIT_STEP     candidates, and waiting actions pinned to a node, over all nodes of a step
+ *   BUSY_UNITS                       units of the running actions of a node that has candidates
+ *   HEAP_ENTRIES                     those plus the node's free units (Alg. 2's completion heap)
+ *   CHUNK_STATES                     states of Alg. 4's table on one GPU node
+ *   DP_CELLS                         cells of a row of Alg. 3's table: free units of a CPU node + 1
+ *   NODES_CPU / _GPU / _API          nodes of a kind in one scenario
+ * Errors: TG_E_INVALID_ARG, TG_E_RANGE (same conditions as tg_build_trace for the fields it reads, and a
+ * scenario whose tables do not fit the local memory of a compute unit).
+ */
+enum { TG_REPLAY_CAP_WAIT_CPU = 0, TG_REPLAY_CAP_WAIT_GPU, TG_REPLAY_CAP_WAIT_API, TG_REPLAY_CAP_RUNNING,
+       TG_REPLAY_CAP_CAND_CPU_ELASTIC, TG_REPLAY_CAP_CAND_GPU_ELASTIC, TG_REPLAY_CAP_CAND_NODE, TG_REPLAY_CAP_CAND_STEP,
+       TG_REPLAY_CAP_PINNED_WAIT_STEP, TG_REPLAY_CAP_BUSY_UNITS, TG_REPLAY_CAP_HEAP_ENTRIES, TG_REPLAY_CAP_CHUNK_STATES,
+       TG_REPLAY_CAP_DP_CELLS, TG_REPLAY_CAP_NODES_CPU, TG_REPLAY_CAP_NODES_GPU, TG_REPLAY_CAP_NODES_API,
+       TG_REPLAY_N_CAPS };
+int tg_replay_capacity(const tg_trace_desc *desc, int64_t *cap);
+
 const char *tg_strerror(int code);
 
 #ifdef __cplusplus

@@ -38,11 +38,19 @@ struct TgTraceDev {
   int numa_cores;                 // > 0: CPU actions get named cores, NUMA domains of this many (Sec. 5.2)
 };
 
+// What the sizes of a trace's tables follow from: nodes of every kind in one scenario, capacities.
+struct TraceMaxima {
+  int nodes_kind[3];        // most nodes of a kind in one scenario
+  int max_cap_cpu;          // largest CPU node
+  int max_heap;             // largest CPU or GPU node: entries of Alg. 2's heap
+  int max_chunk_states;     // states of Alg. 4's table on one node
+};
+
 struct tg_trace {
   TgTraceDev dev;
   void* d_arena;
   size_t arena_bytes;
-  int max_nodes_of_kind, max_nodes_kind[3], max_cap_cpu, max_heap, max_chunk_states;
+  TraceMaxima mx;
 };
 
 namespace {
@@ -184,6 +192,50 @@ struct ReplayLds {
   int node_waves;      // wavefronts that own a per-node block (DPArrange + eviction): 4, 2 or 1
   int busy_slots;
 };
+
+// Node counts and capacities of every scenario (host arrays of the description).
+int trace_maxima(const tg_trace_desc* d, TraceMaxima* mx) {
+  *mx = TraceMaxima{{0, 0, 0}, 0, 0, 60};   // an 8-GPU node never has more than 4,2,1,1 free chunks of size 1,2,4,8
+  for (int s = 0; s < d->S; ++s) {
+    int cnt[3] = {0, 0, 0};
+    for (int j = 0; j < d->M; ++j) {
+      const size_t g = (size_t)s * d->M + j;
+      const int ty = d->node_type[g], cap = d->node_cap[g];
+      if (ty >= TG_N_TYPES || cap < 0) return TG_E_INVALID_ARG;
+      if (ty == TG_TYPE_GPU && cap != 8) return TG_E_INVALID_ARG;
+      if (ty == TG_TYPE_CPU && cap > TG_MAX_CPU_UNITS) return TG_E_RANGE;
+      ++cnt[ty];
+      if (ty != TG_TYPE_API) mx->max_heap = std::max(mx->max_heap, cap);
+      if (ty == TG_TYPE_CPU) mx->max_cap_cpu = std::max(mx->max_cap_cpu, cap);
+    }
+    for (int k = 0; k < 3; ++k) {
+      mx->nodes_kind[k] = std::max(mx->nodes_kind[k], cnt[k]);
+      if (cnt[k] > TG_MAX_NODES_OF_KIND) return TG_E_RANGE;
+    }
+  }
+  return TG_OK;
+}
+
+// LDS of a workgroup: one placement block per kind, then one per-node block for each wavefront
+// that runs DPArrange.  Two workgroups fit a CU when the total stays under half of its LDS, so
+// large clusters give per-node blocks to fewer wavefronts rather than lose the second workgroup.
+int replay_layout(const TraceMaxima& mx, int K, ReplayLds* LD, TgNodeLdsPlan* plan, size_t* lds_bytes) {
+  *plan = tg_node_lds_plan(mx.max_cap_cpu, 8, mx.max_chunk_states, mx.max_heap, K, 1 << 30, 8, TG_WAVE);
+  LD->busy_slots = (mx.max_heap + 1 + 1) & ~1;
+  size_t off = 0;
+  for (int k = 0; k < 3; ++k) {
+    LD->pool_nodes[k] = std::max(mx.nodes_kind[k], 1);
+    LD->pool_off[k] = (int)off;
+    off += (tg_pool_lds_bytes(LD->pool_nodes[k]) + 15) & ~size_t(15);
+  }
+  LD->node_off = (int)off;
+  const size_t node_bytes = (size_t)plan->total + (size_t)LD->busy_slots * 8;
+  const size_t half_cu = 80 * 1024 - 2048;                      // the kernel also has ~1.3 KB of static LDS
+  LD->node_waves = kWaves;
+  while (LD->node_waves > 1 && off + LD->node_waves * node_bytes > half_cu) LD->node_waves >>= 1;
+  *lds_bytes = off + LD->node_waves * node_bytes;
+  return *lds_bytes > 160 * 1024 - 2048 ? TG_E_RANGE : TG_OK;
+}
 
 template <bool WHOLE_QUEUE>   // every step admits one prefix of the whole waiting queue (two admission passes per tick)
 __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, ReplayWs W, tg_replay_out O, ReplayLds LD,
@@ -654,12 +706,16 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
       !d->act_model || !d->act_t_ori_us || !d->act_kmask || !d->act_param || !d->act_pin_node)
     return TG_E_INVALID_ARG;
 
+  TraceMaxima mx;
+  const int mx_err = trace_maxima(d, &mx);
+  if (mx_err != TG_OK) return mx_err;
   const size_t nN = (size_t)S * M, nA = (size_t)S * A;
   std::vector<char> host;
   auto add = [&](size_t bytes) { size_t off = (host.size() + 255) & ~size_t(255); host.resize(off + bytes, 0); return off; };
   tg_trace* t = new (std::nothrow) tg_trace();
   if (!t) return TG_E_NOMEM;
   std::memset(t, 0, sizeof *t);
+  t->mx = mx;
   try {
     const size_t o_ntype = add(nN), o_ncap = add(nN * 4), o_rate = add(nN * 4), o_tok = add(nN * 8), o_rank = add(nN * 4),
                  o_tnidx = add(nN * 4), o_tnoff = add((size_t)S * 16);
@@ -677,8 +733,6 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
     }
     const size_t o_speed = add(std::max<size_t>((size_t)d->n_classes * K, 1) * 4);
     auto at = [&](size_t off) { return host.data() + off; };
-    int max_kind = 0, max_cap_cpu = 0, max_heap = 0;
-    int max_of_kind[3] = {0, 0, 0};
     std::vector<int> max_cap((size_t)S * 3, -1);
     for (int s = 0; s < S; ++s) {
       int cnt[3] = {0, 0, 0};
@@ -692,9 +746,6 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
           const int64_t tok = d->quota_tok0_micro[g];
           if (d->quota_rate[g] < 0 || tok < 0 || tok > (int64_t)cap * 1000000) { delete t; return TG_E_INVALID_ARG; }
           if ((int64_t)d->quota_rate[g] * d->tick_us >= (1ll << 50)) { delete t; return TG_E_RANGE; }
-        } else {
-          max_heap = std::max(max_heap, cap);
-          if (ty == TG_TYPE_CPU) max_cap_cpu = std::max(max_cap_cpu, cap);
         }
         ((uint8_t*)at(o_ntype))[g] = (uint8_t)ty;
         ((int32_t*)at(o_ncap))[g] = cap;
@@ -707,8 +758,6 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
       off[0] = 0; off[1] = cnt[0]; off[2] = cnt[0] + cnt[1]; off[3] = M;
       int fill[3] = {off[0], off[1], off[2]};
       for (int j = 0; j < M; ++j) ((int32_t*)at(o_tnidx))[(size_t)s * M + fill[d->node_type[(size_t)s * M + j]]++] = j;
-      for (int k = 0; k < 3; ++k) { max_kind = std::max(max_kind, cnt[k]); max_of_kind[k] = std::max(max_of_kind[k], cnt[k]); }
-      if (max_kind > TG_MAX_NODES_OF_KIND) { delete t; return TG_E_RANGE; }
       int64_t sumT = 0, prev = 0;
       for (int i = 0; i < A; ++i) {
         const size_t g = (size_t)s * A + i;
@@ -792,9 +841,6 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
     v.act_aux = aux ? (const int32_t*)(base + o_aaux) : nullptr;
     v.numa_cores = d->numa_cores;
     v.speedup = (const uint32_t*)(base + o_speed);
-    t->max_nodes_of_kind = max_kind; t->max_cap_cpu = max_cap_cpu; t->max_heap = max_heap;
-    for (int k = 0; k < 3; ++k) t->max_nodes_kind[k] = max_of_kind[k];
-    t->max_chunk_states = 60;   // an 8-GPU node never has more than 4,2,1,1 free chunks of size 1,2,4,8
   } catch (const std::bad_alloc&) {
     delete t;
     return TG_E_NOMEM;
@@ -824,29 +870,55 @@ extern "C" int tg_replay_trace(const tg_trace* t, const tg_replay_out* out, void
   const TgTraceDev& T = t->dev;
   ReplayWs W;
   carve(T, (char*)d_ws, &W);
-  const TgNodeLdsPlan plan = tg_node_lds_plan(t->max_cap_cpu, 8, t->max_chunk_states, t->max_heap, T.K, 1 << 30, 8, TG_WAVE);
-  // LDS of a workgroup: one placement block per kind, then one per-node block for each wavefront
-  // that runs DPArrange.  Two workgroups fit a CU when the total stays under half of its LDS, so
-  // large clusters give per-node blocks to fewer wavefronts rather than lose the second workgroup.
+  TgNodeLdsPlan plan;
   ReplayLds LD;
-  LD.busy_slots = (t->max_heap + 1 + 1) & ~1;
-  size_t off = 0;
-  for (int k = 0; k < 3; ++k) {
-    LD.pool_nodes[k] = std::max(t->max_nodes_kind[k], 1);
-    LD.pool_off[k] = (int)off;
-    off += (tg_pool_lds_bytes(LD.pool_nodes[k]) + 15) & ~size_t(15);
-  }
-  LD.node_off = (int)off;
-  const size_t node_bytes = (size_t)plan.total + (size_t)LD.busy_slots * 8;
-  const size_t half_cu = 80 * 1024 - 2048;                      // the kernel also has ~1.3 KB of static LDS
-  LD.node_waves = kWaves;
-  while (LD.node_waves > 1 && off + LD.node_waves * node_bytes > half_cu) LD.node_waves >>= 1;
-  const size_t lds = off + LD.node_waves * node_bytes;
-  if (lds > 160 * 1024 - 2048) return TG_E_RANGE;
+  size_t lds;
+  const int fit = replay_layout(t->mx, T.K, &LD, &plan, &lds);
+  if (fit != TG_OK) return fit;
   auto kernel = T.queue_prefix ? tg_replay_kernel<true> : tg_replay_kernel<false>;
   TG_HIP_CHECK(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   const size_t total = (size_t)T.S * T.A * T.K;
   hipLaunchKernelGGL(tg_trace_dur_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, T, W.dur);
   hipLaunchKernelGGL(kernel, dim3(T.S), dim3(kThreads), lds, s, T, W, *out, LD, plan);
   return hipGetLastError() == hipSuccess ? TG_OK : TG_E_HIP;
+}
+
+extern "C" int tg_replay_capacity(const tg_trace_desc* d, int64_t* cap) {
+  if (!d || !cap || !d->node_type || !d->node_cap) return TG_E_INVALID_ARG;
+  if (d->S < 1 || d->A < 1 || d->M < 1 || d->K < 1 || d->K > TG_MAX_K) return TG_E_INVALID_ARG;
+  if (d->A > TG_MAX_ACTIONS || d->M > 65535) return TG_E_RANGE;
+  TraceMaxima mx;
+  const int err = trace_maxima(d, &mx);
+  if (err != TG_OK) return err;
+  TgNodeLdsPlan plan;
+  ReplayLds LD;
+  size_t lds;
+  const int fit = replay_layout(mx, d->K, &LD, &plan, &lds);
+  if (fit != TG_OK) return fit;
+  // lists in the workspace: one slice of A entries per scenario each (waiting list per kind, running set,
+  // candidate order, waiting-pinned order)
+  cap[TG_REPLAY_CAP_WAIT_CPU] = cap[TG_REPLAY_CAP_WAIT_GPU] = cap[TG_REPLAY_CAP_WAIT_API] = d->A;
+  cap[TG_REPLAY_CAP_RUNNING] = d->A;
+  cap[TG_REPLAY_CAP_CAND_NODE] = cap[TG_REPLAY_CAP_CAND_STEP] = cap[TG_REPLAY_CAP_PINNED_WAIT_STEP] = d->A;
+  // per-node tables of a wavefront, from the byte ranges of the plan itself
+  const int64_t choice_bytes = plan.off_F - plan.off_choice - 16;
+  const int64_t rows_tables = std::min<int64_t>({plan.cand_rows,                                     // durations, minimum option
+                                                 plan.off_rowbest - plan.off_q0,
+                                                 (plan.off_rowarg - plan.off_rowbest) / 8 - 1,       // best totals of rows 0..m
+                                                 (plan.off_sel - plan.off_rowarg) / 4 - 1,
+                                                 2 * (int64_t)plan.sel_stride});                     // allocation rows, 4 bits each
+  const int64_t rows_cpu = mx.max_cap_cpu > 0 ? choice_bytes / std::max(tg_choice_stride(mx.max_cap_cpu), 1) : 0;
+  const int64_t rows_gpu = choice_bytes / ((int64_t)mx.max_chunk_states * 2);
+  cap[TG_REPLAY_CAP_CAND_CPU_ELASTIC] = std::min(rows_tables, rows_cpu);
+  cap[TG_REPLAY_CAP_CAND_GPU_ELASTIC] = std::min(rows_tables, rows_gpu);
+  cap[TG_REPLAY_CAP_BUSY_UNITS] = LD.busy_slots;
+  cap[TG_REPLAY_CAP_HEAP_ENTRIES] = std::min(plan.heap_slots, 4 * TG_WAVE);                          // LDS staging; register heap
+  const int64_t dp_bytes = plan.off_choice - plan.off_dp;
+  cap[TG_REPLAY_CAP_CHUNK_STATES] = std::min<int64_t>({mx.max_chunk_states, plan.dp_width, dp_bytes / 16, 512});   // rows; 9-bit state keys
+  // a row of Alg. 3's table as the kernel stores it: 64-bit cells, or 32-bit cells behind 64 sentinels
+  cap[TG_REPLAY_CAP_DP_CELLS] = std::min<int64_t>({plan.dp_width, dp_bytes / 16, dp_bytes / 8 - 2 - TG_WAVE});
+  cap[TG_REPLAY_CAP_NODES_CPU] = LD.pool_nodes[0];
+  cap[TG_REPLAY_CAP_NODES_GPU] = LD.pool_nodes[1];
+  cap[TG_REPLAY_CAP_NODES_API] = LD.pool_nodes[2];
+  return TG_OK;
 }

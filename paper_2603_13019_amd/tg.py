@@ -16,6 +16,8 @@ from . import build as _build
 _lib = None
 
 OK = 0
+E_INVALID_ARG = -1
+E_RANGE = -2
 INF = np.iinfo(np.int64).max
 
 
@@ -69,7 +71,7 @@ _DT = dict(k_list=np.int32, type_k=np.int32, speedup_q16=np.uint32, node_type=np
 
 EXPORTS = ("tg_build_problem", "tg_free_problem", "tg_num_candidates", "tg_assign_workspace_bytes",
            "tg_score_candidates", "tg_assign", "tg_assign_static", "tg_step", "tg_step_on", "tg_build_trace", "tg_free_trace", "tg_replay_workspace_bytes",
-           "tg_replay_trace", "tg_strerror")
+           "tg_replay_trace", "tg_replay_capacity", "tg_strerror")
 
 
 def library_path():
@@ -100,6 +102,7 @@ def load():
         L.tg_free_trace.restype = None
         L.tg_replay_workspace_bytes.argtypes = [vp, C.POINTER(C.c_size_t)]
         L.tg_replay_trace.argtypes = [vp, vp, vp, C.c_size_t, vp]
+        L.tg_replay_capacity.argtypes = [vp, vp]
         L.tg_strerror.argtypes = [C.c_int]
         L.tg_strerror.restype = C.c_char_p
         _lib = L
@@ -236,21 +239,39 @@ def summary_to_numpy(summary_bytes):
     return np.frombuffer(summary_bytes.cpu().numpy().tobytes(), dtype=SUMMARY_DTYPE)
 
 
+REPLAY_CAPS = ("wait_cpu", "wait_gpu", "wait_api", "running", "cand_cpu_elastic", "cand_gpu_elastic", "cand_node",
+               "cand_step", "pinned_wait_step", "busy_units", "heap_entries", "chunk_states", "dp_cells", "nodes_cpu",
+               "nodes_gpu", "nodes_api")
+
+
+def _trace_desc(t: dict):
+    d = TraceDesc()
+    for n in ("S", "A", "M", "K", "n_classes", "depth", "max_ticks"):
+        setattr(d, n, int(t[n]))
+    d.flags = 1 if int(t.get("queue_prefix", 0)) else 0      # TG_TRACE_QUEUE_PREFIX
+    d.tick_us = int(t["tick_us"])
+    keep = []
+    _fill(d, t, [f[0] for f in TraceDesc._fields_[9:-7]] + ["act_quota_mask", "node_aux", "act_aux"], keep)
+    d.numa_cores = int(t.get("numa_cores", 0))
+    d.n_services = len(t["restore_us"]) if t.get("restore_us") is not None else 0
+    d.cache_slots = int(t.get("cache_slots", 64))
+    return d, keep
+
+
+def replay_capacity(t: dict):
+    """tg_replay_capacity: {name: largest value the replay's buffers hold}; host only, no device needed."""
+    d, keep = _trace_desc(t)
+    cap = np.zeros(len(REPLAY_CAPS), np.int64)
+    _check(load().tg_replay_capacity(C.byref(d), cap.ctypes.data), "tg_replay_capacity")
+    return dict(zip(REPLAY_CAPS, cap.tolist()))
+
+
 class Trace:
     """S arrival traces packed on the device (tg_build_trace)."""
 
     def __init__(self, t: dict):
         L = load()
-        d = TraceDesc()
-        for n in ("S", "A", "M", "K", "n_classes", "depth", "max_ticks"):
-            setattr(d, n, int(t[n]))
-        d.flags = 1 if int(t.get("queue_prefix", 0)) else 0      # TG_TRACE_QUEUE_PREFIX
-        d.tick_us = int(t["tick_us"])
-        keep = []
-        _fill(d, t, [f[0] for f in TraceDesc._fields_[9:-7]] + ["act_quota_mask", "node_aux", "act_aux"], keep)
-        d.numa_cores = int(t.get("numa_cores", 0))
-        d.n_services = len(t["restore_us"]) if t.get("restore_us") is not None else 0
-        d.cache_slots = int(t.get("cache_slots", 64))
+        d, keep = _trace_desc(t)
         h = C.c_void_p()
         _check(L.tg_build_trace(C.byref(d), _stream(), C.byref(h)), "tg_build_trace")
         self._h = h
