@@ -1701,15 +1701,15 @@ __device__ static inline int64_t tg_node_schedule(unsigned char* smem, const TgN
   };
 
   // ---- Alg. 1's eviction loop: evict from the tail while the objective drops ----------------
+  // (one call site for the objective: inlined twice it costs the replay kernel its second wavefront per SIMD)
   int L = m;                                                       // accepted length
-  if (L > top || L <= top - plan.sel_rows) backtrack_batch(L);
-  int64_t obj = objective(L);
-  while (L > 1) {
-    if (L - 1 <= top - plan.sel_rows) backtrack_batch(L - 1);
-    const int64_t f = objective(L - 1);
-    if (f >= obj) break;                                           // a tie stops the eviction
+  int64_t obj = 0;
+  for (int Lc = m; Lc >= 1; --Lc) {
+    if (Lc > top || Lc <= top - plan.sel_rows) backtrack_batch(Lc);
+    const int64_t f = objective(Lc);
+    if (Lc < m && f >= obj) break;                                 // a tie stops the eviction
     obj = f;
-    --L;
+    L = Lc;
   }
   if (L > top || L <= top - plan.sel_rows) backtrack_batch(L);
   int used = 0;

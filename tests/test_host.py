@@ -90,3 +90,18 @@ def test_binding_fails_loudly_without_a_gpu():
         tg.Problem(gen.make_config(1))
     with pytest.raises((tg.TgError, RuntimeError)):
         tg.Trace(gen.make_trace(S=1, A=10, seed=1, contended=True))
+
+
+def test_kernels_keep_their_registers_and_occupancy():
+    """From the compiler's own resource report of the build in the tree: no kernel spills to scratch memory, and the
+    persistent replay kernel keeps two wavefronts per SIMD (with one, a replay takes twice as long)."""
+    import json
+    from paper_2603_13019_amd import build
+    if not os.path.exists(build.RESOURCES):
+        build.build_library()
+    k = json.load(open(build.RESOURCES))
+    assert len(k) >= 20
+    for name, r in k.items():
+        assert r["ScratchSize"] == 0, name
+    replay = [r for name, r in k.items() if "tg_replay_kernel" in name]
+    assert len(replay) == 2 and all(r["Occupancy"] >= 2 for r in replay)
