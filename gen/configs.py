@@ -490,6 +490,44 @@ def random_trace(seed):
     return t
 
 
+NODE_ARRAYS = ("node_type", "node_cap", "node_free", "node_backlog_us", "node_chunks", "node_aux_free", "node_resident",
+               "node_core_free")
+
+
+def with_shared_nodes(p):
+    """Two views of one problem whose snapshots all see the node table of snapshot 0: ``(shared, expanded)``.
+    ``shared`` carries the table once (``nodes_shared = 1``, node arrays of M entries), ``expanded`` carries B
+    copies of it.  Pins move to a node of the action's own kind in that table where it has one."""
+    B, N, M = p["B"], p["N"], p["M"]
+    shared, expanded = dict(p), dict(p)
+    for k in NODE_ARRAYS:
+        v = p.get(k)
+        if v is None:
+            continue
+        per = len(v) // B
+        shared[k] = v[:per].copy()
+        expanded[k] = np.tile(v[:per], B)
+    if p.get("node_busy_off") is not None:
+        off, rel = p["node_busy_off"], p["node_busy_rel_us"]
+        per = int(off[M])
+        shared["node_busy_off"] = off[:M + 1].copy()
+        shared["node_busy_rel_us"] = rel[:per].copy()
+        expanded["node_busy_off"] = np.concatenate([off[:M] + b * per for b in range(B)] + [[B * per]]).astype(np.int32)
+        expanded["node_busy_rel_us"] = np.tile(rel[:per], B)
+    nt = p["node_type"][:M]
+    pin = p["act_pin_node"].copy()
+    for g in np.flatnonzero(pin >= 0):
+        own = np.flatnonzero(nt == p["act_type"][g])
+        if len(own) and pin[g] < M:
+            pin[g] = own[pin[g] % len(own)]
+    shared["act_pin_node"] = pin
+    expanded["act_pin_node"] = pin.copy()
+    if p.get("act_quota_mask") is not None:                       # ranks among the API nodes of the old tables: drop
+        shared["act_quota_mask"] = expanded["act_quota_mask"] = None
+    shared["nodes_shared"] = 1
+    return shared, expanded
+
+
 def with_fixed_dop(t, k):
     """Copy of a trace (or problem) in which every elastic action may only run on exactly ``k`` units
     (the fixed degree-of-parallelism baselines of the paper's scheduler ablation); actions that do not

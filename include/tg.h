@@ -78,8 +78,8 @@ typedef struct tg_trace tg_trace;     /* opaque */
 
 /*
  * B snapshots, each with N queued actions (W of Alg. 1, FCFS order) and M nodes (R of Alg. 1).
- * All arrays are host memory.  Node arrays have B*M entries, action arrays B*N entries,
- * snapshot-major.
+ * All arrays are host memory.  Node arrays have B*M entries (M with nodes_shared), action arrays
+ * B*N entries, snapshot-major.
  */
 typedef struct {
   int32_t B, N, M, K;
@@ -157,6 +157,12 @@ typedef struct {
    * 0: one such prefix per pool - a misfit closes the queue of its own kind of resource, or of its
    * node if it is pinned (the managers of Sec. 5.2 schedule their resources independently). */
   int32_t queue_prefix;
+  /* 1: one node table for all snapshots (the same cluster seen at B instants' queues, R of Alg. 1 given once):
+   * every node array then has M entries ([M*4] for node_chunks and node_core_free, node_busy_off [M+1]) instead
+   * of B*M, and node indices (act_pin_node) mean the same node in every snapshot.  The builder writes the table
+   * out per snapshot, so device memory and every result are as with B identical tables.  0: node arrays [B*M]. */
+  int32_t nodes_shared;
+  int32_t reserved_;              /* 0 */
 } tg_problem_desc;
 
 /* Per-snapshot result of tg_assign.  Only mean_act_us and util are floating point. */

@@ -133,9 +133,67 @@ int fold_gpu_pool(const tg_problem_desc* d, PoolFold* f) {
 
 }  // namespace
 
+namespace {
+int build_problem(const tg_problem_desc* desc, void* hip_stream, tg_problem** out);
+
+// nodes_shared: the description holds one node table for all snapshots.  The per-snapshot tables
+// the rest of the builder (and every kernel) works on are written out on the host: B copies.
+struct SharedNodes {
+  std::vector<uint8_t> type, chunks;
+  std::vector<int32_t> cap, free_, busy_off, aux;
+  std::vector<int64_t> backlog, busy_rel;
+  std::vector<uint64_t> resident, cores;
+};
+
+template <class T>
+const T* tile(const T* src, size_t per, int B, std::vector<T>* dst) {
+  if (!src) return nullptr;
+  dst->resize(per * B);
+  for (int b = 0; b < B; ++b) std::copy(src, src + per, dst->begin() + (size_t)b * per);
+  return dst->data();
+}
+}  // namespace
+
 extern "C" int tg_build_problem(const tg_problem_desc* desc, void* hip_stream, tg_problem** out) {
   if (!desc || !out) return TG_E_INVALID_ARG;
   *out = nullptr;
+  if (desc->nodes_shared != 0 && desc->nodes_shared != 1) return TG_E_INVALID_ARG;
+  if (desc->reserved_ != 0) return TG_E_INVALID_ARG;
+  if (!desc->nodes_shared) return build_problem(desc, hip_stream, out);
+  const int B = desc->B, M = desc->M;
+  if (B < 1 || M < 1 || (int64_t)B * M >= (1ll << 31)) return B < 1 || M < 1 ? TG_E_INVALID_ARG : TG_E_RANGE;
+  try {
+    SharedNodes sn;
+    tg_problem_desc d = *desc;
+    d.nodes_shared = 0;
+    d.node_type = tile(desc->node_type, M, B, &sn.type);
+    d.node_cap = tile(desc->node_cap, M, B, &sn.cap);
+    d.node_free = tile(desc->node_free, M, B, &sn.free_);
+    d.node_backlog_us = tile(desc->node_backlog_us, M, B, &sn.backlog);
+    d.node_chunks = tile(desc->node_chunks, (size_t)M * 4, B, &sn.chunks);
+    d.node_aux_free = tile(desc->node_aux_free, M, B, &sn.aux);
+    d.node_resident = tile(desc->node_resident, M, B, &sn.resident);
+    d.node_core_free = tile(desc->node_core_free, (size_t)M * 4, B, &sn.cores);
+    if (desc->node_busy_off) {                                    // CSR of one table -> CSR of B tables
+      const int32_t* off = desc->node_busy_off;
+      if (off[0] != 0) return TG_E_INVALID_ARG;
+      for (int j = 0; j < M; ++j) if (off[j + 1] < off[j]) return TG_E_INVALID_ARG;
+      const int64_t per = off[M];
+      if (per * B >= (1ll << 31)) return TG_E_RANGE;
+      if (per > 0 && !desc->node_busy_rel_us) return TG_E_INVALID_ARG;
+      sn.busy_off.resize((size_t)B * M + 1);
+      for (int b = 0; b < B; ++b)
+        for (int j = 0; j < M; ++j) sn.busy_off[(size_t)b * M + j] = (int32_t)(b * per + off[j]);
+      sn.busy_off[(size_t)B * M] = (int32_t)(B * per);
+      d.node_busy_off = sn.busy_off.data();
+      d.node_busy_rel_us = per > 0 ? tile(desc->node_busy_rel_us, (size_t)per, B, &sn.busy_rel) : desc->node_busy_rel_us;
+    }
+    return build_problem(&d, hip_stream, out);
+  } catch (const std::bad_alloc&) { return TG_E_NOMEM; }
+}
+
+namespace {
+int build_problem(const tg_problem_desc* desc, void* hip_stream, tg_problem** out) {
   if (desc->gpu_pooled != 0 && desc->gpu_pooled != 1) return TG_E_INVALID_ARG;
   if (desc->queue_prefix != 0 && desc->queue_prefix != 1) return TG_E_INVALID_ARG;
   tg_problem_desc folded = *desc;
@@ -513,6 +571,7 @@ extern "C" int tg_build_problem(const tg_problem_desc* desc, void* hip_stream, t
   *out = p;
   return TG_OK;
 }
+}  // namespace
 
 extern "C" void tg_free_problem(tg_problem* p) {
   if (!p) return;

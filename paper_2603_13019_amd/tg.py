@@ -34,7 +34,7 @@ class ProblemDesc(C.Structure):
             "node_chunks", "node_busy_off", "node_busy_rel_us", "act_type", "act_model", "act_t_ori_us",
             "act_age_us", "act_kmask", "act_param", "act_pin_node", "act_task", "node_aux_free", "act_aux",
             "act_service", "node_resident", "restore_us", "node_core_free", "act_quota_mask")] + [(n, C.c_int32) for n in
-                                                                        ("n_services", "numa_cores", "gpu_pooled", "queue_prefix")]
+                                                                        ("n_services", "numa_cores", "gpu_pooled", "queue_prefix", "nodes_shared", "reserved_")]
 
 
 class AssignOut(C.Structure):
@@ -148,11 +148,12 @@ class Problem:
             setattr(d, n, int(p[n]))
         d.order_policy = int(p.get("order_policy", 0))
         keep = []
-        _fill(d, p, [f[0] for f in ProblemDesc._fields_[8:-4]], keep)
+        _fill(d, p, [f[0] for f in ProblemDesc._fields_[8:-6]], keep)
         d.n_services = len(p["restore_us"]) if p.get("restore_us") is not None else 0
         d.numa_cores = int(p.get("numa_cores", 0))
         d.gpu_pooled = int(p.get("gpu_pooled", 0))
         d.queue_prefix = int(p.get("queue_prefix", 0))
+        d.nodes_shared = int(p.get("nodes_shared", 0))
         self.has_cores = p.get("node_core_free") is not None
         h = C.c_void_p()
         _check(L.tg_build_problem(C.byref(d), _stream(), C.byref(h)), "tg_build_problem")

@@ -61,7 +61,7 @@ def test_field_offsets_match_the_compiled_header(tg, tmp_path):
 
 
 def test_struct_layouts_match_header(tg):
-    assert C.sizeof(tg.ProblemDesc) == 8 * 4 + 25 * 8 + 4 * 4
+    assert C.sizeof(tg.ProblemDesc) == 8 * 4 + 25 * 8 + 6 * 4
     assert C.sizeof(tg.AssignOut) == 9 * 8
     assert C.sizeof(tg.TraceDesc) == 8 * 4 + 8 + 16 * 8 + 2 * 4 + 3 * 8 + 2 * 4
     assert C.sizeof(tg.ReplayOut) == 9 * 8
@@ -74,11 +74,13 @@ def _build_rc(tg, p):
         setattr(d, n, int(p[n]))
     d.order_policy = int(p.get("order_policy", 0))
     keep = []
-    tg._fill(d, p, [f[0] for f in tg.ProblemDesc._fields_[8:-4]], keep)
+    tg._fill(d, p, [f[0] for f in tg.ProblemDesc._fields_[8:-6]], keep)
     d.n_services = int(p.get("n_services", len(p["restore_us"]) if p.get("restore_us") is not None else 0))
     d.numa_cores = int(p.get("numa_cores", 0))
     d.gpu_pooled = int(p.get("gpu_pooled", 0))
     d.queue_prefix = int(p.get("queue_prefix", 0))
+    d.nodes_shared = int(p.get("nodes_shared", 0))
+    d.reserved_ = int(p.get("reserved_", 0))
     h = C.c_void_p()
     rc = tg.load().tg_build_problem(C.byref(d), None, C.byref(h))
     assert rc != 0 and not h.value
@@ -89,6 +91,8 @@ BAD = {
     "k_list_not_ascending": (lambda p: p["k_list"].__setitem__(1, 1), -1),
     "unit_above_limit": (lambda p: p["k_list"].__setitem__(3, 65), -1),
     "order_policy": (lambda p: p.__setitem__("order_policy", 2), -1),
+    "nodes_shared_flag": (lambda p: p.__setitem__("nodes_shared", 2), -1),
+    "reserved_field": (lambda p: p.__setitem__("reserved_", 1), -1),
     "depth": (lambda p: p.__setitem__("depth", 9), -1),
     "free_above_cap": (lambda p: p["node_free"].__setitem__(0, 33), -1),
     "node_kind": (lambda p: p["node_type"].__setitem__(0, 7), -1),

@@ -616,3 +616,31 @@ def test_assign_quota_with_more_candidates_than_any_node_has_units(tg, orc):
     per_quota = np.bincount(want["node"][(want["reason"] == 0)] + 0, minlength=M)
     assert want["node_used"][api].max() > 300
     _compare(_assign_gpu(tg, p), want, "long quota list")
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_assign_shared_node_table(tg, orc, seed):
+    """nodes_shared: one node table for all snapshots.  The library, given the table once, must produce what the
+    oracle produces for B copies of it - tensor, assignment and summaries - also with busy lists, a second
+    resource, services and core maps in the table."""
+    import torch
+    p = gen.make_random_problem(300 + seed, B=5, N=50 + 9 * seed, n_cpu=1 + seed % 4, n_gpu=seed % 3, n_api=seed % 2,
+                                depth=1 + seed % 3, busy=seed % 2 == 0, cpu_cap_hi=24 + 8 * (seed % 3))
+    if seed % 3 == 1:
+        _add_second_resource(p, seed, scarce=True)
+    if seed % 3 == 2:
+        _add_services(p, seed)
+    if seed % 4 == 3:
+        gen.with_core_maps(p, 8, seed)
+    shared, expanded = gen.with_shared_nodes(p)
+    assert len(shared["node_type"]) == p["M"] and len(expanded["node_type"]) == p["B"] * p["M"]
+    want = orc.assign(expanded)
+    _compare(_assign_gpu(tg, shared, use_cost=seed % 2 == 1), want, f"seed {seed}")
+    P = tg.Problem(shared)
+    cost = P.score()
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(cost.cpu().numpy(), orc.score(expanded))
+    P.free()
+    if seed == 0:
+        shared["queue_prefix"] = expanded["queue_prefix"] = 1
+        _compare(_assign_gpu(tg, shared), orc.assign(expanded), "whole-queue prefix")
