@@ -37,12 +37,7 @@ SCORE_TRAFFIC_CONFIG3_BYTES = (26108256 + 196608 + 2 * (535280 + 50968)) * 1024
 def order_section(a, tg, torch, p, s_fcfs):
     """The same workload scheduled in the second visiting order (least estimated ACT first instead of first come
     first served): time of tg_assign, and what the order does to the selected set."""
-    try:
-        P = tg.Problem(dict(p, order_policy=1))
-    except tg.TgError as e:
-        if e.code != -2:
-            raise
-        return {"skipped": "a pool of this workload has more actions than the sort of this order takes (8192)"}
+    P = tg.Problem(dict(p, order_policy=1))
     bufs = P.alloc_assign()
     for _ in range(3):
         P.assign(None, bufs)

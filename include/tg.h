@@ -67,7 +67,6 @@ enum { TG_MAX_K = 8, TG_MAX_UNIT = 64, TG_MAX_CPU_UNITS = 256, TG_MAX_GPU_UNITS 
        TG_MAX_CHUNK_STATES = 512, TG_MAX_DEPTH = 4,
        TG_MAX_ACTIONS = 131072,      /* N, actions per snapshot / A, actions per scenario          */
        TG_MAX_NODES_OF_KIND = 4096,  /* nodes of one resource kind in one snapshot               */
-       TG_MAX_SORTED_POOL = 8192,    /* TG_ORDER_COST: actions of one kind in one snapshot       */
        TG_MAX_SERVICES = 64 };
 #define TG_T_ORI_LIMIT (1ll << 36)  /* 1 <= T_ori < 2^36 us                                      */
 #define TG_TIME_LIMIT (1ll << 40)   /* backlog, age, busy release times in [0, 2^40)              */
@@ -86,7 +85,7 @@ typedef struct {
   int32_t n_classes; /* rows of speedup_q16                                                     */
   int32_t n_tasks;   /* act_task values are in [0, n_tasks); segment key of the per-task sums    */
   int32_t depth;     /* options tried for the first waiting action in Alg. 2's estimate; 2 in the paper's runs */
-  int32_t order_policy; /* TG_ORDER_FCFS (0) or TG_ORDER_COST; the latter needs every pool <= TG_MAX_SORTED_POOL actions, else TG_E_RANGE */
+  int32_t order_policy; /* TG_ORDER_FCFS (0) or TG_ORDER_COST */
   const int32_t *k_list;  /* [K] ascending unit counts (the discrete sets of Sec. 4.1), 1..TG_MAX_UNIT */
   const int32_t *type_k;  /* [3] type t may use k_list[0 .. type_k[t]); GPU entries must be 1,2,4,8; API <= 1 */
   const uint32_t *speedup_q16; /* [n_classes*K] round(65536*E(k_q)*k_q); nondecreasing in q, in [65536, 65536*k_q] */

@@ -37,6 +37,8 @@ struct AssignWs {
   int32_t* visit;        // [B*N] TG_ORDER_COST: action ids grouped by kind in visiting order (else unused)
   uint64_t* gkey;        // [B*N] whole-queue prefix under TG_ORDER_COST: (key, action id) of every action (else unused)
   uint64_t* stop;        // [B]   whole-queue prefix: place in the visiting order at which the admission ends (else unused)
+  uint64_t *okey_a, *okey_b;   // [B*N] each, TG_ORDER_COST with a pool too large for one workgroup's sort: sorted runs of
+                               // keys, merged from one buffer into the other (else unused)
 };
 
 // Nodes are processed in classes of candidate count so that the LDS a wavefront needs (the
@@ -51,6 +53,8 @@ constexpr int kLightBatch = 8;   // nodes of the light class a wavefront takes p
 constexpr int kClassCap0 = 16, kClassCap1 = 64;
 __host__ __device__ constexpr int class_cap(int c) { return c == 0 ? kClassCap0 : c == 1 ? kClassCap1 : 1 << 30; }
 
+constexpr int kOrderTile = 8192;      // TG_ORDER_COST: keys one workgroup sorts in LDS; larger pools are sorted tile by tile and merged
+
 size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
 size_t carve(const tg_problem* p, char* base, AssignWs* w) {
@@ -63,7 +67,10 @@ size_t carve(const tg_problem* p, char* base, AssignWs* w) {
   char* vi = take(p->order_policy == TG_ORDER_COST ? nA * 4 : 0);
   char* gk = take(p->queue_prefix && p->order_policy == TG_ORDER_COST ? nA * 8 : 0);
   char* st = take(p->queue_prefix ? (size_t)p->dev.B * 8 : 0);
+  const bool big_sort = p->order_policy == TG_ORDER_COST && p->max_actions_of_kind > kOrderTile;
+  char* ka = take(big_sort ? nA * 8 : 0); char* kb = take(big_sort ? nA * 8 : 0);
   if (w) {
+    w->okey_a = (uint64_t*)ka; w->okey_b = (uint64_t*)kb;
     w->class_list = (int32_t*)cl; w->class_ctl = (int32_t*)cc; w->visit = (int32_t*)vi;
     w->gkey = (uint64_t*)gk; w->stop = (uint64_t*)st;
     w->dur = (int64_t*)a; w->slot = (int32_t*)b; w->order = (int32_t*)c; w->dorder = (int32_t*)d;
@@ -100,73 +107,67 @@ __global__ __launch_bounds__(256) void tg_dur_kernel(TgDev P, int64_t* __restric
 // and sorted by a bitonic network in LDS; one workgroup per (snapshot, kind).
 constexpr int kOrderThreads = 256;
 constexpr uint64_t kOrderKeyInf = (1ull << 46) - 1;
+constexpr int kMergeTile = 2048;      // merged keys one workgroup of the merge kernel produces
 
-__global__ __launch_bounds__(kOrderThreads) void tg_order_kernel(TgDev P, const int64_t* __restrict__ dur, const TgBlock* __restrict__ blocks,
-                                                                 int32_t* __restrict__ visit, int n_pad_max,
-                                                                 uint64_t* __restrict__ gkey) {
-  extern __shared__ __align__(16) unsigned char smem[];
-  uint64_t* s_key = reinterpret_cast<uint64_t*>(smem);                       // [n_pad]
-  __shared__ unsigned long long s_minback[TG_MAX_K + 1];                       // by number of options the capacity admits
-  __shared__ unsigned long long s_minres[TG_MAX_SERVICES][TG_MAX_K + 1];       // the same over the nodes a service is resident on
-  const int b = blockIdx.x / 3, t = blockIdx.x - 3 * b, tid = threadIdx.x;
-  const int a0 = P.tact_off[b * 4 + t], Nt = P.tact_off[b * 4 + t + 1] - a0;
-  const int n0 = P.tnode_off[b * 4 + t], Mt = P.tnode_off[b * 4 + t + 1] - n0;
-  if (Nt == 0) return;
-  const size_t abase = (size_t)b * P.N, nbase = (size_t)b * P.M;
-  const int32_t* acts = P.tact_idx + abase + a0;
-  const TgBlock blk = blocks[b * 3 + t];
+struct OrderLds {
+  unsigned long long minback[TG_MAX_K + 1];                       // by number of options the capacity admits
+  unsigned long long minres[TG_MAX_SERVICES][TG_MAX_K + 1];       // the same over the nodes a service is resident on
+};
+
+// Smallest backlog of every group of nodes of the pool (all threads of the workgroup take part).
+__device__ static inline void order_minima(const TgDev& P, const TgBlock& blk, int Mt, OrderLds& L) {
+  const int tid = threadIdx.x;
   const uint64_t* words = P.node_word + blk.n_off;                            // backlog | options admitted << 48, rank order
   const bool svc = P.act_service != nullptr;
-  if (tid <= TG_MAX_K) s_minback[tid] = ~0ull;
-  if (svc) for (int x = tid; x < TG_MAX_SERVICES * (TG_MAX_K + 1); x += kOrderThreads) (&s_minres[0][0])[x] = ~0ull;
+  if (tid <= TG_MAX_K) L.minback[tid] = ~0ull;
+  if (svc) for (int x = tid; x < TG_MAX_SERVICES * (TG_MAX_K + 1); x += kOrderThreads) (&L.minres[0][0])[x] = ~0ull;
   __syncthreads();
   for (int r = tid; r < Mt; r += kOrderThreads) {
     const uint64_t nw = words[r];
-    atomicMin(&s_minback[nw >> 48], (unsigned long long)(nw & 0xffffffffffffull));
+    atomicMin(&L.minback[nw >> 48], (unsigned long long)(nw & 0xffffffffffffull));
     if (svc)
       for (uint64_t left = P.node_res_k[blk.n_off + r]; left; left &= left - 1)
-        atomicMin(&s_minres[__builtin_ctzll(left)][nw >> 48], (unsigned long long)(nw & 0xffffffffffffull));
+        atomicMin(&L.minres[__builtin_ctzll(left)][nw >> 48], (unsigned long long)(nw & 0xffffffffffffull));
   }
   __syncthreads();
-  int n_pad = 1;
-  while (n_pad < Nt) n_pad <<= 1;
-  const int Kt = P.type_k[t];
-  for (int x = tid; x < n_pad; x += kOrderThreads) {
-    uint64_t key = ~0ull;                                                     // padding sorts behind everything
-    if (x < Nt) {
-      const int id = acts[x];
-      const size_t g = abase + id;
-      uint64_t best = kOrderKeyInf;
-      if (!P.act_static[g]) {
-        const uint32_t mask = P.act_kmask[g];
-        const int64_t* drow = dur + g * P.K;
-        const int pin = P.act_pin[g];
-        const int sv = svc ? P.act_service[g] : -1;
-        const uint64_t rest = sv >= 0 ? (uint64_t)P.restore[sv] : 0;           // paid where the service is not resident
-        if (pin >= 0) {
-          const int pr = P.node_rank[nbase + pin];
-          const uint64_t nw = words[pr];
-          const uint32_t ok = mask & ((1u << (nw >> 48)) - 1u);
-          const uint64_t delay = sv >= 0 && !(P.node_res_k[blk.n_off + pr] >> sv & 1ull) ? rest : 0;
-          if (ok) best = (nw & 0xffffffffffffull) + delay + (uint64_t)drow[31 - __builtin_clz(ok)];
-        } else {
-          for (int c = 1; c <= Kt; ++c) {                                     // nodes whose capacity admits options 0..c-1
-            uint64_t mb = s_minback[c];
-            const uint32_t ok = mask & ((1u << c) - 1u);
-            if (mb == ~0ull || ok == 0) continue;
-            mb += rest;                                                       // any node, restoring; or one that has the service
-            if (sv >= 0 && s_minres[sv][c] < mb) mb = s_minres[sv][c];
-            const uint64_t e = mb + (uint64_t)drow[31 - __builtin_clz(ok)];
-            best = e < best ? e : best;
-          }
-        }
-      }
-      key = best << 17 | (uint32_t)x;
-      if (gkey) gkey[g] = best << 17 | (uint32_t)id;                          // place in the order of the whole queue
+}
+
+// Key of one action: its least estimated ACT (Eq. 2) over its candidates, kOrderKeyInf if it has none.
+__device__ static inline uint64_t order_key(const TgDev& P, const TgBlock& blk, const int64_t* __restrict__ dur, const OrderLds& L,
+                                            size_t abase, size_t nbase, int id, int Kt) {
+  const size_t g = abase + id;
+  uint64_t best = kOrderKeyInf;
+  if (P.act_static[g]) return best;
+  const uint64_t* words = P.node_word + blk.n_off;
+  const bool svc = P.act_service != nullptr;
+  const uint32_t mask = P.act_kmask[g];
+  const int64_t* drow = dur + g * P.K;
+  const int pin = P.act_pin[g];
+  const int sv = svc ? P.act_service[g] : -1;
+  const uint64_t rest = sv >= 0 ? (uint64_t)P.restore[sv] : 0;               // paid where the service is not resident
+  if (pin >= 0) {
+    const int pr = P.node_rank[nbase + pin];
+    const uint64_t nw = words[pr];
+    const uint32_t ok = mask & ((1u << (nw >> 48)) - 1u);
+    const uint64_t delay = sv >= 0 && !(P.node_res_k[blk.n_off + pr] >> sv & 1ull) ? rest : 0;
+    if (ok) best = (nw & 0xffffffffffffull) + delay + (uint64_t)drow[31 - __builtin_clz(ok)];
+  } else {
+    for (int c = 1; c <= Kt; ++c) {                                         // nodes whose capacity admits options 0..c-1
+      uint64_t mb = L.minback[c];
+      const uint32_t ok = mask & ((1u << c) - 1u);
+      if (mb == ~0ull || ok == 0) continue;
+      mb += rest;                                                           // any node, restoring; or one that has the service
+      if (sv >= 0 && L.minres[sv][c] < mb) mb = L.minres[sv][c];
+      const uint64_t e = mb + (uint64_t)drow[31 - __builtin_clz(ok)];
+      best = e < best ? e : best;
     }
-    s_key[x] = key;
   }
-  __syncthreads();
+  return best;
+}
+
+// Bitonic sort of s_key[0 .. n_pad) in LDS, ascending (all threads of the workgroup).
+__device__ static inline void order_sort_lds(uint64_t* s_key, int n_pad) {
+  const int tid = threadIdx.x;
   for (int k = 2; k <= n_pad; k <<= 1)
     for (int j = k >> 1; j > 0; j >>= 1) {
       for (int x = tid; x < n_pad; x += kOrderThreads) {
@@ -179,7 +180,125 @@ __global__ __launch_bounds__(kOrderThreads) void tg_order_kernel(TgDev P, const 
       }
       __syncthreads();
     }
+}
+
+// Pools of at most kOrderTile actions: one workgroup per (snapshot, kind) computes the keys, sorts them and
+// writes the visiting order.
+__global__ __launch_bounds__(kOrderThreads) void tg_order_kernel(TgDev P, const int64_t* __restrict__ dur, const TgBlock* __restrict__ blocks,
+                                                                 int32_t* __restrict__ visit, int n_pad_max,
+                                                                 uint64_t* __restrict__ gkey) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  uint64_t* s_key = reinterpret_cast<uint64_t*>(smem);                       // [n_pad]
+  __shared__ OrderLds L;
+  const int b = blockIdx.x / 3, t = blockIdx.x - 3 * b, tid = threadIdx.x;
+  const int a0 = P.tact_off[b * 4 + t], Nt = P.tact_off[b * 4 + t + 1] - a0;
+  const int n0 = P.tnode_off[b * 4 + t], Mt = P.tnode_off[b * 4 + t + 1] - n0;
+  if (Nt == 0) return;
+  const size_t abase = (size_t)b * P.N, nbase = (size_t)b * P.M;
+  const int32_t* acts = P.tact_idx + abase + a0;
+  const TgBlock blk = blocks[b * 3 + t];
+  order_minima(P, blk, Mt, L);
+  int n_pad = 1;
+  while (n_pad < Nt) n_pad <<= 1;
+  const int Kt = P.type_k[t];
+  for (int x = tid; x < n_pad; x += kOrderThreads) {
+    uint64_t key = ~0ull;                                                     // padding sorts behind everything
+    if (x < Nt) {
+      const int id = acts[x];
+      const uint64_t best = order_key(P, blk, dur, L, abase, nbase, id, Kt);
+      key = best << 17 | (uint32_t)x;
+      if (gkey) gkey[abase + id] = best << 17 | (uint32_t)id;                 // place in the order of the whole queue
+    }
+    s_key[x] = key;
+  }
+  __syncthreads();
+  order_sort_lds(s_key, n_pad);
   for (int x = tid; x < Nt; x += kOrderThreads) visit[abase + a0 + x] = acts[(int)(s_key[x] & 0x1ffff)];
+}
+
+// Larger pools, first step: workgroup (tile, pool) computes the keys of kOrderTile consecutive actions of the
+// pool, sorts them in LDS and writes the sorted run to `runs` (laid out like the pool's slice of the visiting order).
+__global__ __launch_bounds__(kOrderThreads) void tg_order_runs_kernel(TgDev P, const int64_t* __restrict__ dur, const TgBlock* __restrict__ blocks,
+                                                                      uint64_t* __restrict__ runs, uint64_t* __restrict__ gkey) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  uint64_t* s_key = reinterpret_cast<uint64_t*>(smem);                       // [kOrderTile]
+  __shared__ OrderLds L;
+  const int pool = blockIdx.y, b = pool / 3, t = pool - 3 * b, tid = threadIdx.x;
+  const int a0 = P.tact_off[b * 4 + t], Nt = P.tact_off[b * 4 + t + 1] - a0;
+  const int n0 = P.tnode_off[b * 4 + t], Mt = P.tnode_off[b * 4 + t + 1] - n0;
+  const int x0 = (int)blockIdx.x * kOrderTile;
+  if (x0 >= Nt) return;
+  const size_t abase = (size_t)b * P.N, nbase = (size_t)b * P.M;
+  const int32_t* acts = P.tact_idx + abase + a0;
+  const TgBlock blk = blocks[b * 3 + t];
+  order_minima(P, blk, Mt, L);
+  const int cnt = min(kOrderTile, Nt - x0);
+  int n_pad = 1;
+  while (n_pad < cnt) n_pad <<= 1;
+  const int Kt = P.type_k[t];
+  for (int y = tid; y < n_pad; y += kOrderThreads) {
+    uint64_t key = ~0ull;
+    if (y < cnt) {
+      const int x = x0 + y, id = acts[x];
+      const uint64_t best = order_key(P, blk, dur, L, abase, nbase, id, Kt);
+      key = best << 17 | (uint32_t)x;
+      if (gkey) gkey[abase + id] = best << 17 | (uint32_t)id;
+    }
+    s_key[y] = key;
+  }
+  __syncthreads();
+  order_sort_lds(s_key, n_pad);
+  for (int y = tid; y < cnt; y += kOrderThreads) runs[abase + a0 + x0 + y] = s_key[y];
+}
+
+// Number of elements of a[0 .. na) that precede the `diag`-th element of the merge of a and b (keys are distinct).
+template <class Ptr>
+__device__ static inline int merge_split(Ptr a, int na, Ptr b, int nb, int diag) {
+  int lo = max(0, diag - nb), hi = min(diag, na);
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;                                          // take mid+1 from a?  a[mid] must precede b[diag-mid-1]
+    if (a[mid] < b[diag - mid - 1]) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
+// Larger pools, merge step: sorted runs of `run` keys are merged pairwise into runs of 2 * run (src -> dst).
+// Workgroup (tile, pool) produces kMergeTile consecutive keys of the result: it finds by bisection which
+// stretch of either run they come from, loads both stretches into LDS and every thread merges 8 keys from its
+// own split point.  The last pass writes the visiting order itself instead of keys.
+__global__ __launch_bounds__(kOrderThreads) void tg_order_merge_kernel(TgDev P, const uint64_t* __restrict__ src, uint64_t* __restrict__ dst,
+                                                                       int32_t* __restrict__ visit, int run) {
+  __shared__ uint64_t s_in[kMergeTile];
+  __shared__ int s_split[2];
+  const int pool = blockIdx.y, b = pool / 3, t = pool - 3 * b, tid = threadIdx.x;
+  const int a0 = P.tact_off[b * 4 + t], Nt = P.tact_off[b * 4 + t + 1] - a0;
+  const int o0 = (int)blockIdx.x * kMergeTile;                               // first key of the result this workgroup writes
+  if (o0 >= Nt) return;
+  const size_t abase = (size_t)b * P.N;
+  const int32_t* acts = P.tact_idx + abase + a0;
+  const uint64_t* in = src + abase + a0;
+  const int pair0 = o0 / (2 * run) * (2 * run);                              // kMergeTile divides 2 * run: a tile lies in one pair
+  const int na = min(run, Nt - pair0), nb = min(run, max(0, Nt - pair0 - run));
+  const uint64_t* A = in + pair0;
+  const uint64_t* Bq = A + na;
+  const int d0 = o0 - pair0, d1 = min(d0 + kMergeTile, na + nb);
+  if (tid < 2) s_split[tid] = merge_split(A, na, Bq, nb, tid == 0 ? d0 : d1);
+  __syncthreads();
+  const int sa0 = s_split[0], sa1 = s_split[1], sb0 = d0 - sa0, sb1 = d1 - sa1;
+  const int ca = sa1 - sa0, cb = sb1 - sb0;                                  // ca + cb = d1 - d0 <= kMergeTile
+  for (int x = tid; x < ca; x += kOrderThreads) s_in[x] = A[sa0 + x];
+  for (int x = tid; x < cb; x += kOrderThreads) s_in[ca + x] = Bq[sb0 + x];
+  __syncthreads();
+  constexpr int kPer = kMergeTile / kOrderThreads;
+  const int total = ca + cb, my0 = min(tid * kPer, total), my1 = min(my0 + kPer, total);
+  int ia = merge_split(s_in, ca, s_in + ca, cb, my0), ib = my0 - ia;
+  for (int o = my0; o < my1; ++o) {
+    const bool from_a = ib >= cb || (ia < ca && s_in[ia] < s_in[ca + ib]);
+    const uint64_t k = from_a ? s_in[ia] : s_in[ca + ib];
+    ia += from_a; ib += !from_a;
+    if (visit) visit[abase + a0 + o0 + o] = acts[(int)(k & 0x1ffff)];
+    else dst[abase + a0 + o0 + o] = k;
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -770,13 +889,32 @@ int assign_launch(const tg_problem* p, const int64_t* d_cost, const tg_assign_ou
   if (!prepare_only) hipLaunchKernelGGL(tg_dur_kernel, dim3((unsigned)((nA * P.K + 255) / 256)), dim3(256), 0, s, P, W.dur, W.class_ctl);
   const int32_t* visit = nullptr;
   if (p->order_policy == TG_ORDER_COST) {
-    int n_pad = 1;
-    while (n_pad < p->max_actions_of_kind) n_pad <<= 1;
-    const size_t order_lds = (size_t)n_pad * 8;
-    if (order_lds > 48 * 1024)
-      TG_HIP_CHECK(hipFuncSetAttribute((const void*)tg_order_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)order_lds));
-    if (!prepare_only) hipLaunchKernelGGL(tg_order_kernel, dim3(P.B * 3), dim3(kOrderThreads), order_lds, s, P, W.dur, p->d_blocks, W.visit, n_pad,
-                       p->queue_prefix ? W.gkey : nullptr);
+    uint64_t* gkey = p->queue_prefix ? W.gkey : nullptr;
+    if (p->max_actions_of_kind <= kOrderTile) {
+      int n_pad = 1;
+      while (n_pad < p->max_actions_of_kind) n_pad <<= 1;
+      const size_t order_lds = (size_t)n_pad * 8;
+      if (order_lds > 48 * 1024)
+        TG_HIP_CHECK(hipFuncSetAttribute((const void*)tg_order_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)order_lds));
+      if (!prepare_only) hipLaunchKernelGGL(tg_order_kernel, dim3(P.B * 3), dim3(kOrderThreads), order_lds, s, P, W.dur, p->d_blocks, W.visit, n_pad, gkey);
+    } else {
+      // a pool too large for one workgroup: sorted runs of kOrderTile keys, then pairwise merges of the runs
+      const size_t runs_lds = (size_t)kOrderTile * 8;
+      TG_HIP_CHECK(hipFuncSetAttribute((const void*)tg_order_runs_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)runs_lds));
+      const unsigned pools = (unsigned)P.B * 3;
+      if (!prepare_only) {
+        hipLaunchKernelGGL(tg_order_runs_kernel, dim3((p->max_actions_of_kind + kOrderTile - 1) / kOrderTile, pools), dim3(kOrderThreads),
+                           runs_lds, s, P, W.dur, p->d_blocks, W.okey_a, gkey);
+        const uint64_t* src = W.okey_a;
+        uint64_t* dst = W.okey_b;
+        const unsigned tiles = (unsigned)((p->max_actions_of_kind + kMergeTile - 1) / kMergeTile);
+        for (int run = kOrderTile; run < p->max_actions_of_kind; run *= 2) {
+          const bool last = 2 * (int64_t)run >= p->max_actions_of_kind;
+          hipLaunchKernelGGL(tg_order_merge_kernel, dim3(tiles, pools), dim3(kOrderThreads), 0, s, P, src, dst, last ? W.visit : nullptr, run);
+          const uint64_t* was = src; src = dst; dst = const_cast<uint64_t*>(was);
+        }
+      }
+    }
     visit = W.visit;
   }
   // the rows of the score tensor are in FCFS order: another visiting order recomputes Eq. 2 instead

@@ -401,7 +401,6 @@ int build_problem(const tg_problem_desc* desc, void* hip_stream, tg_problem** ou
       }
       if (sumT >= TG_SUM_T_LIMIT) { delete p; return TG_E_RANGE; }
       for (int t = 0; t < 3; ++t) max_acts_kind = std::max(max_acts_kind, cnt[t]);
-      if (d->order_policy == TG_ORDER_COST && max_acts_kind > TG_MAX_SORTED_POOL) { delete p; return TG_E_RANGE; }
       int32_t* off = ar.at<int32_t>(o_taoff) + (size_t)b * 4;
       off[0] = 0; off[1] = cnt[0]; off[2] = cnt[0] + cnt[1]; off[3] = N;
       int fill[3] = {off[0], off[1], off[2]};

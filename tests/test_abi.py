@@ -251,13 +251,6 @@ def test_pooled_gpus_are_validated(tg):
     assert _build_rc(tg, dict(big, gpu_pooled=1)) == -2         # more than 64 GPUs in one pool
 
 
-def test_cost_order_needs_pools_it_can_sort(tg):
-    p = gen.make_random_problem(9, B=1, N=8300, n_cpu=2, n_gpu=0, n_api=0)
-    assert (p["act_type"] == gen.TYPE_CPU).all()
-    p["type_k"][gen.TYPE_GPU] = 0
-    assert _build_rc(tg, dict(p, order_policy=1)) == -2        # more than TG_MAX_SORTED_POOL actions in one pool
-
-
 def test_null_arguments(tg):
     L = tg.load()
     assert L.tg_step(None, None, None, None, 0, None) == -1

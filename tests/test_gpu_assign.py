@@ -177,6 +177,41 @@ def test_assign_cost_order_code_paths(tg, orc):
         _compare(_assign_gpu(tg, p), orc.assign(p), f"cost order {case}")
 
 
+LARGE_POOLS = {
+    # pools beyond the 8192 keys one workgroup sorts: runs merged pairwise in 1, 2, 3 and 4 passes; a last run of one key;
+    # runs that stay single through a pass; pools of very different size side by side
+    "two_runs_one_key": dict(seed=70, B=1, N=8193, n_cpu=40, n_gpu=0, n_api=0, cpu_cap_hi=6, pin_frac=0.2, type_probs=(1, 0, 0)),
+    "three_runs": dict(seed=71, B=1, N=20000, n_cpu=120, n_gpu=0, n_api=0, cpu_cap_hi=6, pin_frac=0.3, type_probs=(1, 0, 0)),
+    "five_runs_two_kinds": dict(seed=72, B=2, N=48000, n_cpu=150, n_gpu=30, n_api=2, cpu_cap_hi=6, pin_frac=0.2, type_probs=(0.8, 0.15, 0.05)),
+    "nine_runs": dict(seed=73, B=1, N=70000, n_cpu=200, n_gpu=0, n_api=0, cpu_cap_hi=6, pin_frac=0.1, type_probs=(1, 0, 0)),
+    "the_largest_queue": dict(seed=74, B=1, N=131072, n_cpu=250, n_gpu=0, n_api=0, cpu_cap_hi=6, pin_frac=0.1, type_probs=(1, 0, 0)),
+}
+
+
+@pytest.mark.parametrize("case", list(LARGE_POOLS))
+def test_assign_cost_order_large_pools(tg, orc, case):
+    """Second visiting order on pools larger than one workgroup sorts: sorted runs, merged pairwise."""
+    print("case cost order", case, flush=True)
+    kw = LARGE_POOLS[case]
+    p = _roomy(gen.make_random_problem(**kw), 128, 0.9, kw["seed"])
+    if kw["n_gpu"] == 0:
+        p["type_k"][gen.TYPE_GPU] = 0
+    p["order_policy"] = 1
+    want = orc.assign(p)
+    assert (want["reason"] == 0).sum() > 2000 and (want["reason"] == 1).any(), "the case should select many and defer"
+    _compare(_assign_gpu(tg, p), want, case)
+    if case == "three_runs":
+        p["queue_prefix"] = 1                                      # the place of every action in the order of the whole queue
+        _compare(_assign_gpu(tg, p), orc.assign(p), case + " whole-queue prefix")
+
+
+def test_assign_cost_order_config4_full(tg, orc):
+    """Workload 4 (one snapshot, a CPU pool of 52 000 actions) under the second visiting order."""
+    p = gen.make_config(4)
+    p["order_policy"] = 1
+    _compare(_assign_gpu(tg, p), orc.assign(p))
+
+
 def test_assign_cost_order_config2_full(tg, orc):
     """Workload 2 at full size under the second visiting order."""
     p = gen.make_config(2)
