@@ -277,6 +277,7 @@ struct StepOut {
   std::vector<int32_t> home;                          // node an action was admitted to (kept when evicted)
   std::vector<std::vector<int>> cores;                // cores of every selected CPU action (numa_cores > 0)
   std::vector<int32_t> extra_used;                    // tokens taken from a quota by actions of other quotas
+  std::vector<int> visit;                             // the order in which the queue was visited (a permutation of 0..N-1)
 };
 
 // Order in which a pool's waiting queue is visited (Sec. 4.2: FCFS in the paper, which notes
@@ -343,6 +344,7 @@ StepOut step(const Tables& tb, const std::vector<Act>& acts, std::vector<Node> n
     }
     std::stable_sort(visit.begin(), visit.end(), [&](int x, int y) { return key[x] < key[y]; });
   }
+  o.visit = visit;
 
   // Alg. 1, admission: prefix of the visiting order admitted with minimum units; node choice by least estimated ACT
   // Second, co-constrained resource (Sec. 4.1: the cost of an action is a vector; Sec. 5.2: a node
@@ -530,6 +532,7 @@ struct orc_trace {
   int32_t queue_prefix;                                            // 1: every step admits one prefix of the whole waiting queue
   const int32_t* node_aux; const int32_t* act_aux;                 // [S*M], [S*A] second resource (Sec. 4.1, 5.2); both or neither
   int32_t numa_cores;                                              // > 0: CPU actions are given named cores (Sec. 5.2), all free at time 0
+  int32_t order_policy;                                            // ORDER_FCFS, or ORDER_COST: every step visits the queue by least estimated ACT
 };
 
 }  // extern "C"
@@ -825,7 +828,9 @@ static void replay_run(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us
         if (nodes[u.node].type != T_API)
           for (int c = 0; c < u.k; ++c) nodes[u.node].busy.push_back(u.fin - now);
       // (4) the scheduling step; (5) selected actions start now
-      const StepOut o = step(tb, acts, nodes, ORDER_FCFS, numa, false, t->queue_prefix != 0);
+      // Sec. 4.2: the step also runs on top of another ordering of the queue; the waiting queue itself stays in
+      // arrival order, every step orders it anew (the estimates change with what is resident where)
+      const StepOut o = step(tb, acts, nodes, t->order_policy, numa, false, t->queue_prefix != 0);
       if (ext) {
         int64_t* e = ext + (size_t)s * ORC_N_EXTENTS;
         auto up = [&](int x, int64_t v) { if (v > e[x]) e[x] = v; };
@@ -857,10 +862,13 @@ static void replay_run(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us
           }
         }
       }
+      // selected actions start in the order the step visited them (chunks and cache slots are handed out in the
+      // order its allocation assumed; under FCFS that is the arrival order); the others keep waiting, in arrival order
       std::vector<int> still;
-      for (size_t w = 0; w < waiting.size(); ++w) {
+      for (size_t w = 0; w < waiting.size(); ++w) if (o.node[w] < 0) still.push_back(waiting[w]);
+      for (int w : o.visit) {
         const int i = waiting[w];
-        if (o.node[w] < 0) { still.push_back(i); continue; }
+        if (o.node[w] < 0) continue;
         const int j = o.node[w], k = o.units[w];
         int q = 0; while (tb.k_list[q] != k) ++q;
         // realised = modelled duration: the delay is the one the step saw (residency at the tick's start)

@@ -175,6 +175,15 @@ def test_every_tick_is_one_step_on_the_snapshot_rebuilt_from_the_replays_own_tim
         rng = np.random.default_rng(seed)
         t["act_aux"] = rng.integers(0, 30, A).astype(np.int32)
         t["node_aux"] = rng.integers(40, 100, t["M"]).astype(np.int32)
+    _, evicted_somewhere = check_every_tick_is_one_step(orc, t, with_aux)
+    if seed % 3:
+        assert evicted_somewhere
+
+
+def check_every_tick_is_one_step(orc, t, with_aux=False):
+    """Body of the pin above, for CPU nodes and quotas; the trace's visiting order (``order_policy``) is the step's."""
+    A = t["A"]
+    api = np.flatnonzero(t["node_type"] == gen.TYPE_API)
     o = orc.replay(t)
     M, tick = t["M"], int(t["tick_us"])
     start, fin, units, node = o["start_us"], o["finish_us"], o["units"], o["node"]
@@ -203,6 +212,7 @@ def test_every_tick_is_one_step_on_the_snapshot_rebuilt_from_the_replays_own_tim
                         left[node[i]] -= t["act_aux"][i]
                 extra = dict(node_aux_free=left.astype(np.int32), act_aux=t["act_aux"][waiting])
             p = dict(B=1, N=len(waiting), M=M, K=t["K"], n_classes=t["n_classes"], n_tasks=1, depth=t["depth"],
+                     order_policy=int(t.get("order_policy", 0)),
                      k_list=t["k_list"], type_k=t["type_k"], speedup_q16=t["speedup_q16"],
                      node_type=t["node_type"], node_cap=t["node_cap"], node_free=free, node_backlog_us=np.zeros(M, np.int64),
                      node_chunks=None, node_busy_off=np.concatenate([[0], np.cumsum([len(b) for b in busy])]).astype(np.int32),
@@ -220,5 +230,4 @@ def test_every_tick_is_one_step_on_the_snapshot_rebuilt_from_the_replays_own_tim
         for i in np.flatnonzero((start == now) & (t["act_type"] == gen.TYPE_API)):
             tok[node[i]] -= 10**6
     assert waited_somewhere
-    if seed % 3:
-        assert evicted_somewhere
+    return o, evicted_somewhere
