@@ -36,6 +36,8 @@ struct TgTraceDev {
   const int32_t* node_aux;        // [S*M] second resource of every node, or nullptr: none (Sec. 4.1, 5.2)
   const int32_t* act_aux;         // [S*A] what an action that is free to choose its node holds of it while it runs
   int numa_cores;                 // > 0: CPU actions get named cores, NUMA domains of this many (Sec. 5.2)
+  int order_cost;                 // 1: every step visits the waiting queue by least estimated ACT (Sec. 4.2), ties by arrival
+  const int32_t* kind_cap;        // [S*3] largest node of every kind in the scenario (-1: none); only with order_cost
 };
 
 // What the sizes of a trace's tables follow from: nodes of every kind in one scenario, capacities.
@@ -80,6 +82,9 @@ struct ReplayWs {
   // named cores (only with numa_cores > 0)
   uint64_t* live_cores;  // [S*M*4] free cores of every CPU node
   int32_t* run_id;       // [S*A] the running action's id (its cores are in the output map), alongside run_fin / run_info
+  // second visiting order (only with order_cost)
+  uint64_t* okey;        // [S*A] (least estimated ACT of the action << 17) | action id: its place in the visiting order
+  int32_t* wlist2;       // [S*3*A] the other half of the waiting lists' ping-pong (new arrivals are merged into the sorted list)
 };
 
 size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
@@ -97,7 +102,9 @@ size_t carve(const TgTraceDev& T, char* base, ReplayWs* w) {
   char* q0 = take(svc ? nN * 8 : 0); char* q1 = take(svc ? nN * 64 * 4 : 0); char* q2 = take(svc ? nN * 4 : 0);
   char* x0 = take(T.node_aux ? nN * 4 : 0); char* x1 = take(T.node_aux ? nA * 4 : 0);
   char* c0 = take(T.numa_cores ? nN * 32 : 0); char* c1 = take(T.numa_cores ? nA * 4 : 0);
+  char* k0 = take(T.order_cost ? nA * 8 : 0); char* k1 = take(T.order_cost ? nA * 3 * 4 : 0);
   if (w) {
+    w->okey = (uint64_t*)k0; w->wlist2 = (int32_t*)k1;
     w->live_cores = (uint64_t*)c0; w->run_id = (int32_t*)c1;
     w->live_aux = (int32_t*)x0; w->run_aux = (int32_t*)x1;
     w->live_res = (uint64_t*)q0; w->used_at = (int32_t*)q1; w->use_seq = (int32_t*)q2;
@@ -123,6 +130,28 @@ __global__ __launch_bounds__(256) void tg_trace_dur_kernel(TgTraceDev T, int64_t
     d = tg_duration(model, T.act_T[g], param, T.k_list[q], sp);
   }
   dur[x] = d;
+}
+
+// Second visiting order: the key of an action is its least estimated ACT over its candidates (Eq. 2).  In a replay
+// every backlog is 0 and, without services, nothing is restored, so the key is the action's duration on the largest
+// allowed option that the largest node it may use admits (durations do not grow with the units) - a constant of the
+// action.  Packed with the action id (ids ascend with the arrivals) into its place in the visiting order.
+constexpr uint64_t kKeyInf = (1ull << 46) - 1;
+
+__global__ __launch_bounds__(256) void tg_trace_key_kernel(TgTraceDev T, const int64_t* __restrict__ dur, uint64_t* __restrict__ okey) {
+  const size_t g = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (g >= (size_t)T.S * T.A) return;
+  const int s = (int)(g / T.A), i = (int)(g - (size_t)s * T.A);
+  uint64_t key = kKeyInf;
+  if (!T.act_static[g]) {
+    const int ty = T.act_type[g], pin = T.act_pin[g];
+    const int cap = pin >= 0 ? T.node_cap[(size_t)s * T.M + pin] : T.kind_cap[s * 3 + ty];
+    int c = 0;
+    while (c < T.type_k[ty] && T.k_list[c] <= cap) ++c;
+    const uint32_t ok = T.act_kmask[g] & ((1u << c) - 1u);
+    if (ok) key = (uint64_t)dur[g * T.K + (31 - __builtin_clz(ok))];
+  }
+  okey[g] = key << 17 | (uint32_t)i;
 }
 
 // free chunks (sizes 1,2,4,8) of an 8-GPU node as packed 8-bit counts: a chunk is an aligned
@@ -237,11 +266,14 @@ int replay_layout(const TraceMaxima& mx, int K, ReplayLds* LD, TgNodeLdsPlan* pl
   return *lds_bytes > 160 * 1024 - 2048 ? TG_E_RANGE : TG_OK;
 }
 
-template <bool WHOLE_QUEUE>   // every step admits one prefix of the whole waiting queue (two admission passes per tick)
+// WHOLE_QUEUE: every step admits one prefix of the whole waiting queue (two admission passes per tick).
+// COST: every step visits the queue by least estimated ACT; the waiting lists are kept sorted by (key, id).
+template <bool WHOLE_QUEUE, bool COST>
 __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, ReplayWs W, tg_replay_out O, ReplayLds LD,
                                                              TgNodeLdsPlan plan) {
   extern __shared__ __align__(16) unsigned char smem[];
-  __shared__ int s_wcnt[3], s_next, s_started, s_nrun, s_wave_cnt[kWaves], s_hist[256], s_sel[2], s_stop;
+  __shared__ int s_wcnt[3], s_next, s_started, s_nrun, s_wave_cnt[kWaves], s_hist[256], s_sel[2], s_newcnt[3], s_pos[TG_WAVE];
+  __shared__ unsigned long long s_stop;
   __shared__ long long s_sum;
   const int s = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int A = T.A, M = T.M, K = T.K;
@@ -254,6 +286,10 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
   const uint8_t* act_type = T.act_type + abase;
   const int64_t* dur = W.dur + abase * K;
   int32_t* wl[3] = {W.wlist + abase * 3, W.wlist + abase * 3 + A, W.wlist + abase * 3 + 2 * (size_t)A};
+  int32_t* wl_other[3] = {nullptr, nullptr, nullptr};            // COST: where the next merge of a kind's list writes
+  const uint64_t* okey = COST ? W.okey + abase : nullptr;
+  if constexpr (COST)
+    for (int ty = 0; ty < 3; ++ty) wl_other[ty] = W.wlist2 + abase * 3 + (size_t)ty * A;
   int64_t* run_fin = W.run_fin + abase;
   int32_t* run_info = W.run_info + abase;
   int32_t* live_free = W.live_free + nbase;
@@ -378,7 +414,51 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
         nx += __popcll(bal);
         if (bal != ~0ull) break;
       }
-      if (lane == 0) { s_next = nx; s_wcnt[0] = wc[0]; s_wcnt[1] = wc[1]; s_wcnt[2] = wc[2]; }
+      if (lane == 0) {
+        if constexpr (COST) { s_newcnt[0] = wc[0] - s_wcnt[0]; s_newcnt[1] = wc[1] - s_wcnt[1]; s_newcnt[2] = wc[2] - s_wcnt[2]; }
+        s_next = nx; s_wcnt[0] = wc[0]; s_wcnt[1] = wc[1]; s_wcnt[2] = wc[2];
+      }
+    }
+    if constexpr (COST) {
+      // The arrivals of this tick sit behind the sorted part of their kind's list.  They are merged into it 64 at a
+      // time: wavefront 0 ranks the 64 among themselves and finds by bisection how many old entries precede each
+      // (keys are distinct: the id is part of them); every old entry then moves up by the number of new ones that
+      // precede it, into the list's other buffer.
+      __threadfence_block();
+      __syncthreads();
+      for (int ty = 0; ty < 3; ++ty) {
+        int n_new = s_newcnt[ty], n_old = s_wcnt[ty] - n_new;
+        while (n_new > 0) {
+          const int32_t* src = wl[ty];
+          int32_t* dst = wl_other[ty];
+          const int c = min(TG_WAVE, n_new);
+          if (wave == 0) {
+            const int id = lane < c ? src[n_old + lane] : 0;
+            const uint64_t key = lane < c ? okey[id] : ~0ull;
+            int rank = 0;
+            for (int m = 0; m < c; ++m) rank += (uint64_t)tg_readlane_i64((int64_t)key, m) < key ? 1 : 0;
+            int lo = 0, hi = n_old;                                // old entries that precede this one
+            while (__any(lo < hi)) {
+              const int mid = (lo + hi) >> 1;
+              const bool go = lo < hi;
+              const uint64_t k = go ? okey[src[mid]] : 0;
+              if (go) { if (k < key) lo = mid + 1; else hi = mid; }
+            }
+            if (lane < c) { s_pos[rank] = lo; dst[lo + rank] = id; }
+          }
+          __syncthreads();
+          for (int x = tid; x < n_old; x += kThreads) {           // s_pos ascends: new entries with s_pos <= x precede old entry x
+            int lo = 0, hi = c;
+            while (lo < hi) { const int mid = (lo + hi) >> 1; if (s_pos[mid] <= x) lo = mid + 1; else hi = mid; }
+            dst[x + lo] = src[x];
+          }
+          for (int x = n_old + c + tid; x < n_old + n_new; x += kThreads) dst[x] = src[x];   // arrivals still to be merged
+          __threadfence_block();
+          __syncthreads();
+          wl_other[ty] = wl[ty]; wl[ty] = dst;
+          n_old += c; n_new -= c;
+        }
+      }
     }
     __threadfence_block();
     __syncthreads();
@@ -416,7 +496,7 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
       io.node_rank = T.node_rank + nbase; io.nodes = nodes; io.dur = dur; io.cost = nullptr; io.cost_row_len = 0;
       io.K = K; io.Kt = T.type_k[ty];
       io.out_node = o_node; io.out_units = o_units; io.out_act = nullptr; io.out_reason = reason; io.slot = slot;
-      const int n_adm = pass == 0 ? wcs[ty] : tg_prefix_len(wl[ty], wcs[ty], nullptr, (uint64_t)s_stop);   // ids ascend with the arrivals
+      const int n_adm = pass == 0 ? wcs[ty] : tg_prefix_len(wl[ty], wcs[ty], okey, (uint64_t)s_stop);   // the lists ascend in place (FCFS: the id)
       tg_place_pool<4, 1>(S, io, wl[ty], n_adm, Mt, ty == TG_TYPE_GPU, lane);
       if constexpr (WHOLE_QUEUE) { if (pass == 1) tg_place_tail(S, io, wl[ty], n_adm, wcs[ty], lane); }
       tg_pool_extents(S, nodes, Mt, woff[ty], nl_off, nl_cnt, dl_off, dl_cnt, lane);
@@ -424,17 +504,18 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
     __threadfence_block();
     __syncthreads();
     if (pass + 1 < n_pass) {
-      if (tid == 0) s_stop = INT32_MAX;
+      if (tid == 0) s_stop = ~0ull;
       __syncthreads();
-      int first = INT32_MAX;
+      unsigned long long first = ~0ull;                           // place, in the order of the whole queue, of the first action that waits
       for (int ty = 0; ty < 3; ++ty)
         for (int x = tid; x < wcs[ty]; x += kThreads) {
           const int id = wl[ty][x];
-          if (reason[id] == TG_DEFER_PREFIX && id < first) first = id;
+          const unsigned long long place = COST ? okey[id] : (unsigned long long)id;
+          if (reason[id] == TG_DEFER_PREFIX && place < first) first = place;
         }
-      if (first != INT32_MAX) atomicMin(&s_stop, first);
+      if (first != ~0ull) atomicMin(&s_stop, first);
       __syncthreads();
-      if (s_stop == INT32_MAX) break;                             // nobody waits: both rules agree
+      if (s_stop == ~0ull) break;                                 // nobody waits: both rules agree
     }
     }
     // (4b) group candidates and waiting pinned actions by node
@@ -679,7 +760,8 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
   if ((d->node_aux != nullptr) != (d->act_aux != nullptr)) return TG_E_INVALID_ARG;
   if (d->numa_cores != 0 && d->numa_cores != 4 && d->numa_cores != 8 && d->numa_cores != 16 && d->numa_cores != 32 &&
       d->numa_cores != 64) return TG_E_INVALID_ARG;
-  if (d->reserved_ != 0) return TG_E_INVALID_ARG;
+  if (d->order_policy != TG_ORDER_FCFS && d->order_policy != TG_ORDER_COST) return TG_E_INVALID_ARG;
+  if (d->order_policy == TG_ORDER_COST && d->act_service) return TG_E_INVALID_ARG;   // keys would change with the caches: not built
   if (svc) {
     if (d->n_services < 1 || d->n_services > TG_MAX_SERVICES || d->cache_slots < 1 || d->cache_slots > TG_MAX_SERVICES) return TG_E_INVALID_ARG;
     for (int x = 0; x < d->n_services; ++x) if (d->restore_us[x] < 0 || d->restore_us[x] >= TG_T_ORI_LIMIT) return TG_E_RANGE;
@@ -731,6 +813,7 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
       std::memcpy(host.data() + o_naux, d->node_aux, nN * 4);
       std::memcpy(host.data() + o_aaux, d->act_aux, nA * 4);
     }
+    const size_t o_kcap = add(d->order_policy == TG_ORDER_COST ? (size_t)S * 3 * 4 : 0);
     const size_t o_speed = add(std::max<size_t>((size_t)d->n_classes * K, 1) * 4);
     auto at = [&](size_t off) { return host.data() + off; };
     std::vector<int> max_cap((size_t)S * 3, -1);
@@ -807,6 +890,7 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
       }
       if (sumT >= TG_SUM_T_LIMIT) { delete t; return TG_E_RANGE; }
     }
+    if (d->order_policy == TG_ORDER_COST) std::memcpy(at(o_kcap), max_cap.data(), (size_t)S * 3 * 4);
     if (d->n_classes) std::memcpy(at(o_speed), d->speedup_q16, (size_t)d->n_classes * K * 4);
     if (svc) std::memcpy(at(o_rest), d->restore_us, (size_t)d->n_services * 8);
 
@@ -840,6 +924,8 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
     v.node_aux = aux ? (const int32_t*)(base + o_naux) : nullptr;
     v.act_aux = aux ? (const int32_t*)(base + o_aaux) : nullptr;
     v.numa_cores = d->numa_cores;
+    v.order_cost = d->order_policy == TG_ORDER_COST ? 1 : 0;
+    v.kind_cap = v.order_cost ? (const int32_t*)(base + o_kcap) : nullptr;
     v.speedup = (const uint32_t*)(base + o_speed);
   } catch (const std::bad_alloc&) {
     delete t;
@@ -875,10 +961,13 @@ extern "C" int tg_replay_trace(const tg_trace* t, const tg_replay_out* out, void
   size_t lds;
   const int fit = replay_layout(t->mx, T.K, &LD, &plan, &lds);
   if (fit != TG_OK) return fit;
-  auto kernel = T.queue_prefix ? tg_replay_kernel<true> : tg_replay_kernel<false>;
+  auto kernel = T.order_cost ? (T.queue_prefix ? tg_replay_kernel<true, true> : tg_replay_kernel<false, true>)
+                             : (T.queue_prefix ? tg_replay_kernel<true, false> : tg_replay_kernel<false, false>);
   TG_HIP_CHECK(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   const size_t total = (size_t)T.S * T.A * T.K;
   hipLaunchKernelGGL(tg_trace_dur_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, T, W.dur);
+  if (T.order_cost)
+    hipLaunchKernelGGL(tg_trace_key_kernel, dim3((unsigned)(((size_t)T.S * T.A + 255) / 256)), dim3(256), 0, s, T, W.dur, W.okey);
   hipLaunchKernelGGL(kernel, dim3(T.S), dim3(kThreads), lds, s, T, W, *out, LD, plan);
   return hipGetLastError() == hipSuccess ? TG_OK : TG_E_HIP;
 }

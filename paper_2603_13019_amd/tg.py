@@ -49,7 +49,7 @@ class TraceDesc(C.Structure):
             "arrival_us", "act_type", "act_model", "act_t_ori_us", "act_kmask", "act_param", "act_pin_node",
             "act_service", "restore_us")] + [("n_services", C.c_int32), ("cache_slots", C.c_int32),
                                              ("act_quota_mask", C.c_void_p), ("node_aux", C.c_void_p),
-                                             ("act_aux", C.c_void_p), ("numa_cores", C.c_int32), ("reserved_", C.c_int32)]
+                                             ("act_aux", C.c_void_p), ("numa_cores", C.c_int32), ("order_policy", C.c_int32)]
 
 
 class ReplayOut(C.Structure):
@@ -254,6 +254,7 @@ def _trace_desc(t: dict):
     keep = []
     _fill(d, t, [f[0] for f in TraceDesc._fields_[9:-7]] + ["act_quota_mask", "node_aux", "act_aux"], keep)
     d.numa_cores = int(t.get("numa_cores", 0))
+    d.order_policy = int(t.get("order_policy", 0))
     d.n_services = len(t["restore_us"]) if t.get("restore_us") is not None else 0
     d.cache_slots = int(t.get("cache_slots", 64))
     return d, keep

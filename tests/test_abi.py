@@ -275,6 +275,7 @@ def _trace_rc(tg, t):
     keep = []
     tg._fill(d, t, [f[0] for f in tg.TraceDesc._fields_[9:-7]] + ["act_quota_mask", "node_aux", "act_aux"], keep)
     d.numa_cores = int(t.get("numa_cores", 0))
+    d.order_policy = int(t.get("order_policy", 0))
     d.n_services = int(t.get("n_services", len(t["restore_us"]) if t.get("restore_us") is not None else 0))
     d.cache_slots = int(t.get("cache_slots", 64))
     h = C.c_void_p()
@@ -294,6 +295,8 @@ BAD_TRACE = {
     "second_resource_negative": (lambda t: (t.__setitem__("node_aux", np.ones(t["S"] * t["M"], np.int32)),
                                             t.__setitem__("act_aux", np.full(t["S"] * t["A"], -1, np.int32))), -1),
     "unknown_flag_next_to_a_known_one": (lambda t: t.__setitem__("flags", 5), -1),
+    "unknown_visiting_order": (lambda t: t.__setitem__("order_policy", 2), -1),
+    "cost_order_with_services": (lambda t: (t.__setitem__("order_policy", 1), gen.trace_with_services(t, 1, 4, 2)), -1),
     "tokens_above_bucket": (lambda t: t["quota_tok0_micro"].__setitem__(int(np.flatnonzero(t["node_type"] == gen.TYPE_API)[0]), 10**12), -1),
     "t_ori_range": (lambda t: t["act_t_ori_us"].__setitem__(0, 0), -2),
     "class_out_of_range": (lambda t: (t["act_model"].__setitem__(0, 2), t["act_param"].__setitem__(0, 99), t["act_type"].__setitem__(0, 1)), -3),

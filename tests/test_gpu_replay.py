@@ -314,3 +314,60 @@ def test_replay_with_named_cores_needs_the_output_map(tg):
     with pytest.raises(tg.TgError):
         T.replay(bufs)
     T.free()
+
+
+@pytest.mark.parametrize("name", ["contended_small", "contended_burst", "default_cluster", "cpu_only_tiny_cluster", "gpu_only", "api_only",
+                                  "tick_limit", "single_action"])
+@pytest.mark.parametrize("queue_prefix", [0, 1])
+def test_replay_cost_order_small(tg, orc, name, queue_prefix):
+    """Second visiting order in the replay (least estimated ACT first): sorted waiting lists, the arrivals of a tick merged in."""
+    print("case cost order", name, queue_prefix, flush=True)
+    t = dict(gen.make_trace(**CASES[name]), order_policy=1, queue_prefix=queue_prefix)
+    want = orc.replay(t)
+    _compare(_replay_gpu(tg, t), want, range(t["S"]), t["A"])
+    if name.startswith("contended") and not queue_prefix:
+        assert (want["start_us"] != orc.replay(dict(t, order_policy=0))["start_us"]).any(), "the order should matter"
+
+
+def test_replay_cost_order_bursts_and_ties(tg, orc):
+    """Hundreds of arrivals in one tick (merged 64 at a time), everybody at time 0, and few distinct durations (equal keys:
+    arrival order decides)."""
+    t = gen.make_trace(S=3, A=900, seed=41, contended=True, rate_per_s=3000.0, horizon_s=0.3, max_ticks=60000)
+    t["order_policy"] = 1
+    _compare(_replay_gpu(tg, t), orc.replay(t), range(3), 900)
+    t["arrival_us"][:] = 0
+    _compare(_replay_gpu(tg, t), orc.replay(t), range(3), 900)
+    t["act_t_ori_us"] = (1 + t["act_t_ori_us"] % 3) * 400_000
+    t["arrival_us"] = np.tile(np.sort(np.random.default_rng(2).integers(0, 40, 900)) * 50_000, 3).astype(np.int64)
+    _compare(_replay_gpu(tg, t), orc.replay(t), range(3), 900)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_replay_cost_order_with_every_other_option(tg, orc, seed):
+    """Cost order next to further quotas, the second resource, named cores, the whole-queue prefix, depths 1-4, pins."""
+    t = gen.make_trace(S=3, A=450, seed=900 + seed, cluster=(2 + seed % 3, 16, 1 + seed % 2, 3), rate_per_s=130.0, horizon_s=3.5,
+                       max_ticks=40000, pin_frac=(0.0, 0.3, 0.8)[seed % 3])
+    t["depth"] = 1 + seed % 4
+    gen.with_extra_quotas(t, frac=0.5, seed=seed)
+    if seed % 2:
+        _with_aux(t, seed, scarce=bool(seed & 2))
+    if seed % 3 == 0:
+        t["numa_cores"] = 8
+    t["queue_prefix"] = int(seed >= 3)
+    t["order_policy"] = 1
+    _compare(_replay_gpu(tg, t), orc.replay(t), range(3), 450)
+
+
+def test_replay_cost_order_config5_contended_sampled(tg, orc):
+    S, A = 64, 10_000
+    t = dict(gen.make_trace(S=S, A=A, seed=5, contended=True, max_ticks=200_000), order_policy=1)
+    got = _replay_gpu(tg, t)
+    pick = [0, 31, 63]
+    want = orc.replay(t, 0, 1)
+    for s in pick[1:]:
+        w = orc.replay(t, s, s + 1)
+        for k in want:
+            per = want[k].shape[0] // S
+            want[k][s * per:(s + 1) * per] = w[k][s * per:(s + 1) * per]
+    _compare(got, want, pick, A)
+    assert (got["n_started"] == A).all()

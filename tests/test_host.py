@@ -104,4 +104,4 @@ def test_kernels_keep_their_registers_and_occupancy():
     for name, r in k.items():
         assert r["ScratchSize"] == 0, name
     replay = [r for name, r in k.items() if "tg_replay_kernel" in name]
-    assert len(replay) == 2 and all(r["Occupancy"] >= 2 for r in replay)
+    assert len(replay) == 4 and all(r["Occupancy"] >= 2 for r in replay)
