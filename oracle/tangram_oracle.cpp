@@ -533,6 +533,7 @@ struct orc_trace {
   const int32_t* node_aux; const int32_t* act_aux;                 // [S*M], [S*A] second resource (Sec. 4.1, 5.2); both or neither
   int32_t numa_cores;                                              // > 0: CPU actions are given named cores (Sec. 5.2), all free at time 0
   int32_t order_policy;                                            // ORDER_FCFS, or ORDER_COST: every step visits the queue by least estimated ACT
+  int32_t gpu_pooled;                                              // 1: every step sees the GPU nodes as one pool of chunks (Sec. 5.3, Alg. 4)
 };
 
 }  // extern "C"
@@ -830,7 +831,9 @@ static void replay_run(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us
       // (4) the scheduling step; (5) selected actions start now
       // Sec. 4.2: the step also runs on top of another ordering of the queue; the waiting queue itself stays in
       // arrival order, every step orders it anew (the estimates change with what is resident where)
-      const StepOut o = step(tb, acts, nodes, t->order_policy, numa, false, t->queue_prefix != 0);
+      // gpu_pooled: the step schedules the GPU cluster as one resource and names, for every action it selects, the
+      // node whose chunk it takes; the action then holds GPUs of that node until it finishes
+      const StepOut o = step(tb, acts, nodes, t->order_policy, numa, t->gpu_pooled != 0, t->queue_prefix != 0);
       if (ext) {
         int64_t* e = ext + (size_t)s * ORC_N_EXTENTS;
         auto up = [&](int x, int64_t v) { if (v > e[x]) e[x] = v; };
@@ -845,9 +848,19 @@ static void replay_run(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us
           else if (o.reason[w] == R_PREFIX && acts[w].pin >= 0) ++pinned_wait;
         }
         up(ORC_EXT_CAND_STEP, cand_step); up(ORC_EXT_PINNED_WAIT_STEP, pinned_wait);
+        Node pooled;                                              // what the step made of the GPU nodes under gpu_pooled
+        int pool = -1;
+        if (t->gpu_pooled)
+          for (int j = 0; j < M; ++j) {
+            if (nodes[j].type != T_GPU) continue;
+            if (pool < 0) { pool = j; pooled = nodes[j]; continue; }
+            pooled.free += nodes[j].free;
+            for (int x = 0; x < 4; ++x) pooled.chunks[x] += nodes[j].chunks[x];
+            pooled.busy.insert(pooled.busy.end(), nodes[j].busy.begin(), nodes[j].busy.end());
+          }
         for (int j = 0; j < M; ++j) {
           if (cand[j] == 0) continue;
-          const Node& nd = nodes[j];
+          const Node& nd = j == pool ? pooled : nodes[j];
           up(ORC_EXT_CAND_NODE, cand[j]);
           if (nd.type == T_API) continue;
           up(ORC_EXT_BUSY_UNITS, (int64_t)nd.busy.size());
