@@ -193,10 +193,11 @@ def replay_section(a, tg, gen, torch):
             res[name]["queue_prefix"] = {"ms": e0.elapsed_time(e1), "mean_act_us": float(bufs["mean_act_us"].mean().item()),
                                          "started": int(bufs["n_started"].sum().item())}
             T.free()
-            # the same trace in the second visiting order, with named cores (NUMA domains of 16) and with a second resource per node that binds now and then
+            # the same trace in the second visiting order, with pooled GPU nodes, with named cores (NUMA domains of 16) and with a second resource per node that binds now and then
             import numpy as np
             rng = np.random.default_rng(11)
             variants = {"cost_order": dict(t, order_policy=1),       # the queue visited by least estimated ACT every tick
+                        "gpu_pooled": gen.trace_with_pooled_gpus(dict(t)),   # the GPU nodes as one pool of chunks (GPU actions unpinned)
                         "named_cores": dict(t, numa_cores=16),
                         "second_resource": dict(t, act_aux=rng.integers(0, 40, t["S"] * t["A"]).astype(np.int32),
                                                 node_aux=rng.integers(300, 600, t["S"] * t["M"]).astype(np.int32))}

@@ -9,6 +9,6 @@ from .configs import (  # noqa: F401
     TYPE_CPU, TYPE_GPU, TYPE_API,
     MODEL_NONE, MODEL_AMDAHL, MODEL_TABLE,
     make_config, make_random_problem, make_trace, subset_problem, slice_problem, with_fixed_dop, with_core_maps, with_extra_quotas,
-    random_trace, trace_with_aux, trace_with_services, with_shared_nodes,
+    random_trace, trace_with_aux, trace_with_services, trace_with_pooled_gpus, with_shared_nodes,
     PROBLEM_ARRAYS, TRACE_ARRAYS,
 )

@@ -489,6 +489,15 @@ def random_trace(seed):
         t["numa_cores"] = int(rng.choice([4, 8, 16, 32, 64]))
     if rng.random() < 0.35 and t.get("act_service") is None:   # the queue visited by least estimated ACT
         t["order_policy"] = 1
+    if n_gpu and rng.random() < 0.4 and t.get("act_service") is None and t.get("node_aux") is None:
+        trace_with_pooled_gpus(t)                              # the GPU nodes as one pool of chunks
+    return t
+
+
+def trace_with_pooled_gpus(t):
+    """Marks a trace (in place) as one whose GPU nodes are scheduled as one pool; GPU actions lose their pins."""
+    t["act_pin_node"] = np.where(t["act_type"] == TYPE_GPU, -1, t["act_pin_node"]).astype(np.int32)
+    t["gpu_pooled"] = 1
     return t
 
 

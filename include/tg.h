@@ -277,11 +277,17 @@ int tg_step_on(const tg_problem *p, int64_t *d_cost, const tg_assign_out *out, v
  */
 /* tg_trace_desc.flags: every step admits one prefix of the whole waiting queue (as queue_prefix
  * of tg_problem_desc) instead of one prefix per pool */
-enum { TG_TRACE_QUEUE_PREFIX = 1 };
+enum { TG_TRACE_QUEUE_PREFIX = 1,
+       /* the GPU nodes of a scenario form one pool of chunks in every step (as gpu_pooled in tg_problem_desc): the step
+        * names the node whose chunk a selected action takes - the smallest free chunk of the cluster that holds it, on the
+        * lowest-numbered node that has one - and `node` reports that node.  Needs: no GPU action pinned, no services, no
+        * second resource (TG_E_INVALID_ARG), at most 5 GPU nodes per scenario (the pooled chunk counts of more could pass
+        * TG_MAX_CHUNK_STATES: TG_E_RANGE). */
+       TG_TRACE_GPU_POOLED = 2 };
 typedef struct {
   int32_t S, A, M, K, n_classes, depth;
   int32_t max_ticks; /* the replay of a scenario stops after this many ticks                    */
-  uint32_t flags;    /* TG_TRACE_QUEUE_PREFIX or 0; other bits must be clear                    */
+  uint32_t flags;    /* TG_TRACE_QUEUE_PREFIX | TG_TRACE_GPU_POOLED or 0; other bits must be clear  */
   int64_t tick_us;   /* rescheduling period                                                     */
   const int32_t *k_list, *type_k;
   const uint32_t *speedup_q16;

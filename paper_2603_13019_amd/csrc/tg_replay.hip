@@ -36,6 +36,7 @@ struct TgTraceDev {
   const int32_t* node_aux;        // [S*M] second resource of every node, or nullptr: none (Sec. 4.1, 5.2)
   const int32_t* act_aux;         // [S*A] what an action that is free to choose its node holds of it while it runs
   int numa_cores;                 // > 0: CPU actions get named cores, NUMA domains of this many (Sec. 5.2)
+  int gpu_pooled;                 // 1: every step sees the GPU nodes of the scenario as one pool of chunks (Sec. 5.3, Alg. 4)
   int order_cost;                 // 1: every step visits the waiting queue by least estimated ACT (Sec. 4.2), ties by arrival
   const int32_t* kind_cap;        // [S*3] largest node of every kind in the scenario (-1: none); only with order_cost
 };
@@ -44,9 +45,16 @@ struct TgTraceDev {
 struct TraceMaxima {
   int nodes_kind[3];        // most nodes of a kind in one scenario
   int max_cap_cpu;          // largest CPU node
-  int max_heap;             // largest CPU or GPU node: entries of Alg. 2's heap
-  int max_chunk_states;     // states of Alg. 4's table on one node
+  int max_free_gpu;         // GPUs of the largest GPU resource a step schedules: a node's 8, or those of a pool
+  int max_heap;             // largest CPU or GPU resource: entries of Alg. 2's heap
+  int max_chunk_states;     // states of Alg. 4's table on one GPU resource
 };
+
+// Most states (product of max(count, 1) + 1 over the four chunk sizes) the summed free-chunk counts of n 8-GPU nodes
+// can have, n = 0..5: the largest product over all sums of n count vectors, each the counts of one of the 256 free
+// masks of a node.  Six nodes could reach 810, above TG_MAX_CHUNK_STATES.
+constexpr int kPoolNodesMax = 5;
+constexpr int kPoolStates[kPoolNodesMax + 1] = {1, 40, 100, 196, 324, 512};
 
 struct tg_trace {
   TgTraceDev dev;
@@ -224,7 +232,8 @@ struct ReplayLds {
 
 // Node counts and capacities of every scenario (host arrays of the description).
 int trace_maxima(const tg_trace_desc* d, TraceMaxima* mx) {
-  *mx = TraceMaxima{{0, 0, 0}, 0, 0, 60};   // an 8-GPU node never has more than 4,2,1,1 free chunks of size 1,2,4,8
+  *mx = TraceMaxima{{0, 0, 0}, 0, 8, 0, 60};   // an 8-GPU node never has more than 4,2,1,1 free chunks of size 1,2,4,8
+  const bool pooled = (d->flags & TG_TRACE_GPU_POOLED) != 0;
   for (int s = 0; s < d->S; ++s) {
     int cnt[3] = {0, 0, 0};
     for (int j = 0; j < d->M; ++j) {
@@ -241,6 +250,13 @@ int trace_maxima(const tg_trace_desc* d, TraceMaxima* mx) {
       mx->nodes_kind[k] = std::max(mx->nodes_kind[k], cnt[k]);
       if (cnt[k] > TG_MAX_NODES_OF_KIND) return TG_E_RANGE;
     }
+    if (pooled && cnt[TG_TYPE_GPU] > kPoolNodesMax) return TG_E_RANGE;
+  }
+  if (pooled && mx->nodes_kind[TG_TYPE_GPU] > 0) {                // the pool is one resource of all the scenario's GPUs
+    const int n = mx->nodes_kind[TG_TYPE_GPU];
+    mx->max_free_gpu = 8 * n;
+    mx->max_heap = std::max(mx->max_heap, 8 * n);
+    mx->max_chunk_states = std::max(mx->max_chunk_states, kPoolStates[n]);
   }
   return TG_OK;
 }
@@ -249,7 +265,7 @@ int trace_maxima(const tg_trace_desc* d, TraceMaxima* mx) {
 // that runs DPArrange.  Two workgroups fit a CU when the total stays under half of its LDS, so
 // large clusters give per-node blocks to fewer wavefronts rather than lose the second workgroup.
 int replay_layout(const TraceMaxima& mx, int K, ReplayLds* LD, TgNodeLdsPlan* plan, size_t* lds_bytes) {
-  *plan = tg_node_lds_plan(mx.max_cap_cpu, 8, mx.max_chunk_states, mx.max_heap, K, 1 << 30, 8, TG_WAVE);
+  *plan = tg_node_lds_plan(mx.max_cap_cpu, mx.max_free_gpu, mx.max_chunk_states, mx.max_heap, K, 1 << 30, 8, TG_WAVE);
   LD->busy_slots = (mx.max_heap + 1 + 1) & ~1;
   size_t off = 0;
   for (int k = 0; k < 3; ++k) {
@@ -472,15 +488,21 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
     constexpr int n_pass = WHOLE_QUEUE ? 2 : 1;
     for (int pass = 0; pass < n_pass; ++pass) {
     for (int ty = wave; ty < 3; ty += kWaves) {
-      const int n0 = T.tnode_off[s * 4 + ty], Mt = T.tnode_off[s * 4 + ty + 1] - n0;
+      const int n0 = T.tnode_off[s * 4 + ty], Mt_all = T.tnode_off[s * 4 + ty + 1] - n0;
       const int32_t* nodes = T.tnode_idx + nbase + n0;
+      // pooled GPUs: the first GPU node stands for the pool, with the free chunks of all of them (at most 5 nodes)
+      const bool pooled = T.gpu_pooled && ty == TG_TYPE_GPU;
+      const int Mt = pooled ? min(Mt_all, 1) : Mt_all;
+      int32_t pool_chunks = 0;
+      if (pooled) pool_chunks = tg_wave_sum_i32(lane < Mt_all ? (int32_t)mask_chunks((uint32_t)live_free[nodes[lane]]) : 0);
       TgPoolLds S;
       tg_pool_lds_carve(smem + LD.pool_off[ty], LD.pool_nodes[ty], &S);
       if (lane < TG_MAX_K) S.k[lane] = T.k_list[lane];
       for (int r = lane; r < Mt; r += TG_WAVE) {
         const int j = nodes[r];
         S.back[r] = 0;
-        S.lim[r] = ty == TG_TYPE_GPU ? (int32_t)mask_chunks((uint32_t)live_free[j])
+        S.lim[r] = pooled ? pool_chunks
+                 : ty == TG_TYPE_GPU ? (int32_t)mask_chunks((uint32_t)live_free[j])
                  : ty == TG_TYPE_API ? (int32_t)(live_tok[j] / 1000000) : live_free[j];
         S.cnt[r] = 0; S.dcnt[r] = 0; S.closed[r] = 0;
         if (T.act_service) S.res[r] = W.live_res[nbase + j];
@@ -541,6 +563,7 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
       const int j = jb + jl;
       const int m = __builtin_amdgcn_readlane(my_m, jl);
       const int ty = T.node_type[nbase + j];
+      const bool pooled = T.gpu_pooled && ty == TG_TYPE_GPU;      // j is the first GPU node: it stands for all of them
       const bool single = m == 1 && dl_cnt[j] == 0;               // one candidate, nobody waiting: no table, no heap
       int nb = 0;
       if (ty != TG_TYPE_API && !single) {
@@ -549,7 +572,10 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
           const int x = base + lane;
           int k = 0;
           int64_t fin = 0;
-          if (x < n) { const int info = run_info[x]; if ((info & 0xffff) == j) { k = (info >> 16) & 0xff; fin = run_fin[x] - now; } }
+          if (x < n) {
+            const int info = run_info[x], on = info & 0xffff;
+            if (pooled ? T.node_type[nbase + on] == TG_TYPE_GPU : on == j) { k = (info >> 16) & 0xff; fin = run_fin[x] - now; }
+          }
           const int inc = tg_wave_scan_i32(k);
           for (int c = 0; c < k; ++c) s_busy[nb + inc - k + c] = fin;
           nb += __builtin_amdgcn_readlane(inc, TG_WAVE - 1);
@@ -560,6 +586,13 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
       const uint32_t lf = (uint32_t)live_free[j];
       in.free_units = ty == TG_TYPE_GPU ? __popc(lf) : ty == TG_TYPE_API ? (int)(live_tok[j] / 1000000) : (int)lf;
       in.chunks = ty == TG_TYPE_GPU ? mask_chunks(lf) : 0;
+      if (pooled) {                                               // units, free GPUs and free chunks of the whole pool
+        const int g0 = T.tnode_off[s * 4 + TG_TYPE_GPU], n_gpu = T.tnode_off[s * 4 + TG_TYPE_GPU + 1] - g0;
+        const uint32_t mf = lane < n_gpu ? (uint32_t)live_free[T.tnode_idx[nbase + g0 + lane]] : 0u;
+        in.cap = 8 * n_gpu;
+        in.free_units = tg_wave_sum_i32(__popc(mf));
+        in.chunks = (uint32_t)tg_wave_sum_i32(lane < n_gpu ? (int32_t)mask_chunks(mf) : 0);
+      }
       in.backlog = 0;
       in.m = m; in.clist = order + nl_off[j]; in.nd = dl_cnt[j]; in.dlist = dorder + dl_off[j];
       in.n_busy = nb; in.busy = nullptr; in.busy_lds_off = plan.total;
@@ -615,7 +648,39 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
         }
       }
     if (T.act_service) __syncthreads();                           // the residency of the tick's start has been read
-    for (int r = tid; r < T.tnode_off[s * 4 + 2] - T.tnode_off[s * 4 + 1]; r += kThreads) {
+    if (T.gpu_pooled) {
+      // The pool's selected actions, in list order, take their real chunks (Sec. 5.3's rule over the cluster): the
+      // smallest free chunk that holds the action, on the lowest-numbered node that has one - the same sequence of
+      // takes the pool's chunk counts went through in the step, so every take succeeds.  One thread: the order matters.
+      const int g0 = T.tnode_off[s * 4 + TG_TYPE_GPU], n_gpu = T.tnode_off[s * 4 + TG_TYPE_GPU + 1] - g0;
+      if (tid == 0 && n_gpu > 0) {
+        const int32_t* gpu_nodes = T.tnode_idx + nbase + g0;
+        const int pool = gpu_nodes[0], m = nl_cnt[pool];
+        for (int x = 0; x < m; ++x) {
+          const int id = order[nl_off[pool] + x];
+          if (o_node[id] < 0) break;                              // evicted tail
+          const int k = o_units[id], lvl = tg_chunk_level(k);
+          int best = -1, best_level = 4;
+          for (int r = 0; r < n_gpu; ++r) {
+            const uint32_t c = mask_chunks((uint32_t)live_free[gpu_nodes[r]]);
+            for (int b = lvl; b < best_level; ++b)
+              if ((c >> (8 * b)) & 0xffu) { best = r; best_level = b; break; }
+          }
+          if (best < 0) { o_node[id] = -1; continue; }           // cannot happen: the pool's counts had such a chunk
+          const int j = gpu_nodes[best];
+          uint32_t mk = (uint32_t)live_free[j];
+          const int first = mask_alloc(mk, k) & 7;
+          live_free[j] = (int)mk;
+          int q = 0;
+          while (q < K - 1 && T.k_list[q] != k) ++q;
+          const int d = atomicAdd(&s_nrun, 1);
+          run_fin[d] = now + dur[(size_t)id * K + q]; run_info[d] = j | k << 16 | first << 24;
+          if (T.numa_cores) W.run_id[abase + d] = id;
+          o_node[id] = j;
+        }
+      }
+    }
+    for (int r = tid; r < (T.gpu_pooled ? 0 : T.tnode_off[s * 4 + 2] - T.tnode_off[s * 4 + 1]); r += kThreads) {
       const int j = T.tnode_idx[nbase + T.tnode_off[s * 4 + 1] + r];
       const int m = nl_cnt[j];
       if (m == 0) continue;
@@ -753,7 +818,7 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
   if (!d || !out) return TG_E_INVALID_ARG;
   *out = nullptr;
   const int S = d->S, A = d->A, M = d->M, K = d->K;
-  if (S < 1 || A < 1 || M < 1 || (d->flags & ~(uint32_t)TG_TRACE_QUEUE_PREFIX) != 0 || d->max_ticks < 1 || d->tick_us < 1) return TG_E_INVALID_ARG;
+  if (S < 1 || A < 1 || M < 1 || (d->flags & ~(uint32_t)(TG_TRACE_QUEUE_PREFIX | TG_TRACE_GPU_POOLED)) != 0 || d->max_ticks < 1 || d->tick_us < 1) return TG_E_INVALID_ARG;
   if (d->depth < 1 || d->depth > TG_MAX_DEPTH) return TG_E_INVALID_ARG;
   const bool svc = d->act_service != nullptr;
   if (svc != (d->restore_us != nullptr)) return TG_E_INVALID_ARG;
@@ -762,6 +827,8 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
       d->numa_cores != 64) return TG_E_INVALID_ARG;
   if (d->order_policy != TG_ORDER_FCFS && d->order_policy != TG_ORDER_COST) return TG_E_INVALID_ARG;
   if (d->order_policy == TG_ORDER_COST && d->act_service) return TG_E_INVALID_ARG;   // keys would change with the caches: not built
+  const bool pooled = (d->flags & TG_TRACE_GPU_POOLED) != 0;
+  if (pooled && (d->act_service || d->node_aux)) return TG_E_INVALID_ARG;            // a pool has no per-node cache or second resource
   if (svc) {
     if (d->n_services < 1 || d->n_services > TG_MAX_SERVICES || d->cache_slots < 1 || d->cache_slots > TG_MAX_SERVICES) return TG_E_INVALID_ARG;
     for (int x = 0; x < d->n_services; ++x) if (d->restore_us[x] < 0 || d->restore_us[x] >= TG_T_ORI_LIMIT) return TG_E_RANGE;
@@ -858,6 +925,7 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
         if (model == TG_MODEL_NONE) mask &= (~mask + 1u);
         int pin = d->act_pin_node[g];
         if (pin < 0) pin = -1;
+        if (pooled && ty == TG_TYPE_GPU && pin >= 0) { delete t; return TG_E_INVALID_ARG; }   // a pool has no pins
         bool infeasible = mask == 0;
         if (!infeasible) {
           const int kmin = d->k_list[__builtin_ctz(mask)];
@@ -920,6 +988,7 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
     v.restore = svc ? (const int64_t*)(base + o_rest) : nullptr;
     v.cache_slots = svc ? d->cache_slots : 0;
     v.queue_prefix = (d->flags & TG_TRACE_QUEUE_PREFIX) ? 1 : 0;
+    v.gpu_pooled = pooled ? 1 : 0;
     v.act_quota = d->act_quota_mask ? (const uint64_t*)(base + o_aquota) : nullptr;
     v.node_aux = aux ? (const int32_t*)(base + o_naux) : nullptr;
     v.act_aux = aux ? (const int32_t*)(base + o_aaux) : nullptr;

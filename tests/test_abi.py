@@ -288,7 +288,12 @@ BAD_TRACE = {
     "arrivals_not_sorted": (lambda t: t["arrival_us"].__setitem__(5, 0), -1),
     "gpu_node_not_8": (lambda t: t["node_cap"].__setitem__(int(np.flatnonzero(t["node_type"] == gen.TYPE_GPU)[0]), 4), -1),
     "tick_zero": (lambda t: t.__setitem__("tick_us", 0), -1),
-    "unknown_flag": (lambda t: t.__setitem__("flags", 2), -1),
+    "unknown_flag": (lambda t: t.__setitem__("flags", 4), -1),
+    "pooled_gpus_with_a_pinned_gpu_action": (lambda t: (t.__setitem__("flags", 2), t["act_type"].__setitem__(7, 1), t["act_kmask"].__setitem__(7, 1),
+                                                        t["act_model"].__setitem__(7, 0),
+                                                        t["act_pin_node"].__setitem__(7, int(np.flatnonzero(t["node_type"] == gen.TYPE_GPU)[0]))), -1),
+    "pooled_gpus_with_services": (lambda t: (t.__setitem__("flags", 2), gen.trace_with_services(t, 1, 4, 2)), -1),
+    "pooled_gpus_with_a_second_resource": (lambda t: (t.__setitem__("flags", 2), gen.trace_with_aux(t, 1, False)), -1),
     "numa_domain_not_a_power_of_two": (lambda t: t.__setitem__("numa_cores", 12), -1),
     "numa_domain_too_small": (lambda t: t.__setitem__("numa_cores", 2), -1),
     "second_resource_half_given": (lambda t: t.__setitem__("node_aux", np.ones(t["S"] * t["M"], np.int32)), -1),

@@ -371,3 +371,35 @@ def test_replay_cost_order_config5_contended_sampled(tg, orc):
             want[k][s * per:(s + 1) * per] = w[k][s * per:(s + 1) * per]
     _compare(got, want, pick, A)
     assert (got["n_started"] == A).all()
+
+
+_pooled = gen.trace_with_pooled_gpus
+
+
+@pytest.mark.parametrize("n_gpu", [1, 2, 3, 4, 5])
+def test_replay_pooled_gpus(tg, orc, n_gpu):
+    """The GPU nodes of a scenario scheduled as one pool of chunks in every tick (Sec. 5.3, Alg. 4): pooled placement, Alg. 4 on the
+    summed chunk counts, real chunks handed out cluster-wide."""
+    print("case pooled", n_gpu, flush=True)
+    for seed, probs, rate in ((0, (0, 1, 0), 50.0 * n_gpu), (1, (0.4, 0.5, 0.1), 80.0 * n_gpu)):
+        t = _pooled(gen.make_trace(S=3, A=500, seed=950 + 10 * n_gpu + seed, cluster=(2 * seed, 16, n_gpu, seed), type_probs=probs,
+                                   rate_per_s=rate, horizon_s=4.0, max_ticks=100_000, pin_frac=0.3))
+        t["depth"] = 1 + (n_gpu + seed) % 4
+        want = orc.replay(t)
+        _compare(_replay_gpu(tg, t), want, range(3), 500)
+        if n_gpu > 1 and seed == 0:
+            plain = orc.replay(dict(t, gpu_pooled=0))
+            assert (plain["start_us"] != want["start_us"]).any() or (plain["node"] != want["node"]).any(), "pooling should matter"
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_replay_pooled_gpus_with_other_options(tg, orc, seed):
+    """Pooled GPUs next to the whole-queue prefix, the cost order, named cores and further quotas."""
+    t = _pooled(gen.make_trace(S=3, A=450, seed=980 + seed, cluster=(2, 16, 2 + seed, 3), rate_per_s=140.0, horizon_s=3.0,
+                               max_ticks=60_000, pin_frac=0.4))
+    gen.with_extra_quotas(t, frac=0.5, seed=seed)
+    t["queue_prefix"] = seed % 2
+    t["order_policy"] = int(seed >= 2)
+    if seed % 2 == 0:
+        t["numa_cores"] = 8
+    _compare(_replay_gpu(tg, t), orc.replay(t), range(3), 450)

@@ -112,3 +112,35 @@ def test_capacity_rejects_what_the_builder_rejects():
     with pytest.raises(tg.TgError) as e:
         tg.replay_capacity(bad)
     assert e.value.code == tg.E_INVALID_ARG
+
+
+def _pooled_trace(S, A, seed, n_gpu, rate, horizon_s, n_cpu=2):
+    t = gen.make_trace(S=S, A=A, seed=seed, cluster=(n_cpu, 16, n_gpu, 1), type_probs=(0.3, 0.6, 0.1), rate_per_s=rate,
+                       horizon_s=horizon_s, max_ticks=200_000, pin_frac=0.3)
+    t["act_pin_node"] = np.where(t["act_type"] == gen.TYPE_GPU, -1, t["act_pin_node"]).astype(np.int32)
+    t["gpu_pooled"] = 1
+    return t
+
+
+@pytest.mark.parametrize("n_gpu", [1, 2, 3, 4, 5])
+def test_pooled_gpu_clusters(orc, n_gpu):
+    """The GPU nodes of a scenario as one pool: up to 40 candidates and heap entries on one resource, chunk states of the
+    summed counts."""
+    from pyref import Buddy
+    vecs = {Buddy(m).counts() for m in range(256)}
+    sums = {(0, 0, 0, 0)}
+    for _ in range(n_gpu):
+        sums = {tuple(a + b for a, b in zip(u, v)) for u in sums for v in vecs}
+    most = max(int(np.prod([max(c, 1) + 1 for c in v])) for v in sums)   # over everything n nodes' masks can add up to
+    for queue_prefix in (0, 1):
+        t = dict(_pooled_trace(2, 600, 30 + n_gpu, n_gpu, 40.0 * n_gpu + 40, 4.0), queue_prefix=queue_prefix)
+        cap, seen = _check(t, orc, f"{n_gpu} pooled nodes")
+        assert cap["chunk_states"] >= most and cap["heap_entries"] >= 8 * n_gpu and cap["cand_gpu_elastic"] >= 8 * n_gpu
+    assert int(seen["heap_entries"].max()) >= 8 * n_gpu and int(seen["chunk_states"].max()) > (40 if n_gpu > 1 else 8)
+
+
+def test_pools_the_replay_refuses():
+    t = _pooled_trace(1, 40, 3, 6, 50.0, 1.0)
+    with pytest.raises(tg.TgError) as e:
+        tg.replay_capacity(t)
+    assert e.value.code == tg.E_RANGE                               # six nodes: their chunk counts can pass the table's 512 states
