@@ -48,7 +48,7 @@ struct AssignWs {
 // bounds the heavier classes; how the LDS of a CU is split between the launches is decided in
 // tg_assign below.
 constexpr int kClasses = 3;
-constexpr int kSelRows = 32;     // prefix lengths backtracked per batch
+constexpr int kSelRows = 24;     // prefix lengths backtracked per batch (a heavy wavefront of a 128-core cluster then fits 20 KB of LDS)
 constexpr int kLightBatch = 8;   // nodes of the light class a wavefront takes per fetch
 constexpr int kClassCap0 = 16, kClassCap1 = 64;
 __host__ __device__ constexpr int class_cap(int c) { return c == 0 ? kClassCap0 : c == 1 ? kClassCap1 : 1 << 30; }
@@ -964,9 +964,11 @@ int assign_launch(const tg_problem* p, const int64_t* d_cost, const tg_assign_ou
   if (before_nodes) TG_HIP_CHECK(hipStreamWaitEvent(s, before_nodes, 0));
   TG_HIP_CHECK(hipEventRecord(p->ev_fork, s));
   // LDS decides how many wavefronts a CU holds.  The heaviest class that can have nodes gets one
-  // wavefront per possible node as far as 80 % of a CU's LDS go; its wavefronts that find no node
-  // of their own (and those that finish early) serve the class below, so the middle class is only
-  // launched from what the light class - the bulk of the nodes - leaves over.
+  // wavefront per possible node as far as 80 % of a CU's LDS go - 90 % where there can be many more
+  // heavy nodes than such wavefronts (a heavy wavefront is bound by its own latency, and the light
+  // ones cannot take its nodes); its wavefronts that find no node of their own (and those that
+  // finish early) serve the class below, so the middle class is only launched from what the light
+  // class - the bulk of the nodes - leaves over.
   const size_t bound[kClasses] = {nN, p->nodes_free_gt16, p->nodes_free_gt64};
   const int kCus = 256, kLdsPerCu = 160 * 1024, kLdsGranule = 1024;   // allocations are rounded up (granule assumed, not documented)
   const int heavy = bound[2] > 0 ? 2 : bound[1] > 0 ? 1 : 0;      // classes above it are empty
@@ -978,6 +980,8 @@ int assign_launch(const tg_problem* p, const int64_t* d_cost, const tg_assign_ou
   int lds_left = kLdsPerCu;
   if (heavy > 0) {
     per_cu[heavy] = std::max(1, std::min(want[heavy], kLdsPerCu * 8 / 10 / bytes[heavy]));
+    if (bound[heavy] >= (size_t)8 * kCus * per_cu[heavy])
+      per_cu[heavy] = std::max(per_cu[heavy], std::min(want[heavy], kLdsPerCu * 9 / 10 / bytes[heavy]));
     lds_left -= per_cu[heavy] * bytes[heavy];
   }
   // a thin heavy launch cannot absorb a long middle list: then the middle class keeps wavefronts of its own

@@ -286,7 +286,7 @@ int build_problem(const tg_problem_desc* desc, void* hip_stream, tg_problem** ou
     const size_t o_nbrel = ar.add(std::max<size_t>(n_busy, 1) * 8);
     std::vector<int> max_cap((size_t)B * 3, -1);
     int max_kind = 0, max_free_cpu = 0, max_heap = 0, max_free_gpu = 0, max_states = 1;
-    size_t free_gt16 = 0, free_gt64 = 0;
+    size_t free_gt16 = 0, free_gt64 = 0, nodes_by_actions_gt64 = 0;
     int64_t backlog_spread = 0;
     for (int b = 0; b < B; ++b) {
       int cnt[3] = {0, 0, 0};
@@ -401,6 +401,7 @@ int build_problem(const tg_problem_desc* desc, void* hip_stream, tg_problem** ou
       }
       if (sumT >= TG_SUM_T_LIMIT) { delete p; return TG_E_RANGE; }
       for (int t = 0; t < 3; ++t) max_acts_kind = std::max(max_acts_kind, cnt[t]);
+      for (int t = 0; t < 3; ++t) nodes_by_actions_gt64 += (size_t)cnt[t] / 65;   // a node with more than 64 candidates needs 65 actions of its kind
       int32_t* off = ar.at<int32_t>(o_taoff) + (size_t)b * 4;
       off[0] = 0; off[1] = cnt[0]; off[2] = cnt[0] + cnt[1]; off[3] = N;
       int fill[3] = {off[0], off[1], off[2]};
@@ -559,7 +560,7 @@ int build_problem(const tg_problem_desc* desc, void* hip_stream, tg_problem** ou
     p->order_policy = d->order_policy; p->queue_prefix = d->queue_prefix; p->max_actions_of_kind = max_acts_kind;
     p->max_free_cpu = max_free_cpu;
     p->max_heap = max_heap;
-    p->nodes_free_gt16 = free_gt16; p->nodes_free_gt64 = free_gt64;
+    p->nodes_free_gt16 = free_gt16; p->nodes_free_gt64 = std::min(free_gt64, nodes_by_actions_gt64);
     p->max_free_gpu = max_free_gpu;
     p->max_chunk_states = max_states;
 

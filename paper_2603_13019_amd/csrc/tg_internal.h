@@ -127,7 +127,8 @@ struct tg_problem {
   int64_t backlog_spread;  // largest (max - min) backlog over the nodes of one kind in one snapshot
   int max_free_cpu;        // largest node_free over CPU nodes
   int max_heap;            // largest free + busy over CPU and GPU nodes
-  size_t nodes_free_gt16, nodes_free_gt64;   // nodes with more than 16 / 64 free units: bounds on the nodes that can hold as many candidates
+  size_t nodes_free_gt16, nodes_free_gt64;   // bounds on the nodes that can hold more than 16 / 64 candidates: nodes with as many free
+                                             // units (for 64 also: no more than a 65th of the actions of the node's kind)
   int max_free_gpu, max_chunk_states;
   int64_t* d_score_dur;    // [B*N*(K+1)] scratch of tg_score_candidates: getDur per (kind-grouped row, option), then the row's pin; every call
                            // writes the same values, so calls that overlap do not disturb each other
