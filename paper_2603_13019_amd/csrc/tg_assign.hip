@@ -437,33 +437,33 @@ __global__ __launch_bounds__(256) void tg_lists_kernel(TgDev P, AssignWs W, tg_a
     if (m == 0) { if (O.node_used) O.node_used[gn] = 0; }
     else cls = m <= kClassCap0 ? 0 : m <= kClassCap1 ? 1 : 2;
   }
-  const int lane = threadIdx.x & 63;
-  for (int c = 1; c < kClasses; ++c) {
-    const uint64_t bal = __ballot(cls == c);
-    if (bal == 0) continue;
-    const int leader = __ffsll((unsigned long long)bal) - 1;
-    int base = 0;
-    if (lane == leader) base = atomicAdd(&W.class_ctl[2 * c], __popcll(bal));   // order inside a class does not matter
-    base = __shfl(base, leader);
-    if (cls == c) W.class_list[(size_t)c * nN + base + __popcll(bal & ((1ull << lane) - 1ull))] = (int32_t)gn;
+  // Places in the class lists: the four wavefronts of the workgroup add up their counts in LDS and one thread takes
+  // the workgroup's stretch of every list with one atomic each (thousands of wavefronts on one counter would queue).
+  // Order inside a class does not matter.  The light class holds most nodes and is handed out in batches: its dearer
+  // nodes (GPU nodes: chunk states instead of unit counts) are filed from the front of the list, the others from the
+  // back, so that the batches taken last are the cheap ones.
+  __shared__ int s_cnt[4][4], s_base[4];                          // [wavefront][list], list = heavier classes 1, 2, light front, light back
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const bool dear = cls == 0 && P.node_type[is_node ? gn : 0] == TG_TYPE_GPU;
+  const int which = cls == 1 ? 0 : cls == 2 ? 1 : dear ? 2 : cls == 0 ? 3 : -1;
+  uint64_t bal[4];
+#pragma unroll
+  for (int l = 0; l < 4; ++l) { bal[l] = __ballot(which == l); if (lane == 0) s_cnt[wave][l] = __popcll(bal[l]); }
+  __syncthreads();
+  if (threadIdx.x < 4) {
+    const int l = threadIdx.x, total = s_cnt[0][l] + s_cnt[1][l] + s_cnt[2][l] + s_cnt[3][l];
+    int32_t* ctr = &W.class_ctl[l == 0 ? 2 : l == 1 ? 4 : l == 2 ? 2 * kClasses : 2 * kClasses + 1];
+    s_base[l] = total ? atomicAdd(ctr, total) : 0;
   }
-  // The light class holds most nodes and is handed out in batches: its dearer nodes (GPU nodes:
-  // chunk states instead of unit counts) are filed from the front of the list, the others from
-  // the back, so that the batches taken last are the cheap ones.
-  {
-    const bool dear = cls == 0 && P.node_type[is_node ? gn : 0] == TG_TYPE_GPU;
-    const uint64_t bal_f = __ballot(dear), bal_b = __ballot(cls == 0 && !dear);
-    if ((bal_f | bal_b) != 0) {
-      int base_f = 0, base_b = 0;
-      if (lane == 0) {                                            // both counters in flight together
-        if (bal_f) base_f = atomicAdd(&W.class_ctl[2 * kClasses], __popcll(bal_f));
-        if (bal_b) base_b = atomicAdd(&W.class_ctl[2 * kClasses + 1], __popcll(bal_b));
-      }
-      base_f = __builtin_amdgcn_readfirstlane(base_f); base_b = __builtin_amdgcn_readfirstlane(base_b);
-      const uint64_t below = (1ull << lane) - 1ull;
-      if (dear) W.class_list[(size_t)base_f + __popcll(bal_f & below)] = (int32_t)gn;
-      else if (cls == 0) W.class_list[nN - 1 - ((size_t)base_b + __popcll(bal_b & below))] = (int32_t)gn;
-    }
+  __syncthreads();
+  if (which >= 0) {
+    int before = 0;
+    for (int w = 0; w < wave; ++w) before += s_cnt[w][which];
+    const size_t at = (size_t)s_base[which] + before + __popcll(bal[which] & ((1ull << lane) - 1ull));
+    if (which == 0) W.class_list[nN + at] = (int32_t)gn;
+    else if (which == 1) W.class_list[2 * nN + at] = (int32_t)gn;
+    else if (which == 2) W.class_list[at] = (int32_t)gn;
+    else W.class_list[nN - 1 - at] = (int32_t)gn;
   }
 }
 
