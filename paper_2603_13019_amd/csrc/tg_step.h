@@ -1069,6 +1069,28 @@ struct TgHeapSorted {
     }
     return fin;
   }
+
+  // The same action on D heaps at once (the depths of Alg. 2 side by side): one loop over its units, the D
+  // independent chains inside it, so that their dependent instructions overlap.
+  template <int D>
+  __device__ static inline void take_all(V (&h)[D][NS], int u, V dd, int lane, uint64_t (&obj)[D]) {
+    V fin[D];
+#pragma unroll
+    for (int k = 0; k < D; ++k) fin[k] = (V)__builtin_amdgcn_readlane((int)h[k][0], u - 1) + dd;
+    for (int c = 0; c < u; ++c) {
+#pragma unroll
+      for (int k = 0; k < D; ++k)
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+          const V nxt = s + 1 < NS ? (V)__builtin_amdgcn_readlane((int)h[k][s + 1 < NS ? s + 1 : s], 0) : kPad;
+          const V sh = (V)__builtin_amdgcn_update_dpp((int)nxt, (int)h[k][s], 0x130, 0xf, 0xf, false);
+          const V hi = h[k][s] > fin[k] ? h[k][s] : fin[k];
+          h[k][s] = sh < hi ? sh : hi;
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < D; ++k) obj[k] += (uint64_t)fin[k];
+  }
 };
 
 // TgHeapWide: 64-bit times, unsorted, four slots per lane; a unit is found by a wavefront-wide
@@ -1102,6 +1124,12 @@ struct TgHeapWide {
 #pragma unroll
     for (int s = 0; s < 4; ++s) if (h[s] == kMark) h[s] = fin;
     return fin;
+  }
+
+  template <int D>
+  __device__ static inline void take_all(V (&h)[D][4], int u, V dd, int lane, uint64_t (&obj)[D]) {
+#pragma unroll
+    for (int k = 0; k < D; ++k) obj[k] += (uint64_t)take(h[k], u, dd, lane);
   }
 };
 
@@ -1199,8 +1227,7 @@ __device__ static inline void tg_estimate_run(const TgNodeIn& in, const TgWaitLd
       todo &= todo - 1;
       const int u = __builtin_amdgcn_readlane(my_u, l);
       const V dd = lane_d(l);
-#pragma unroll
-      for (int k = 0; k < D; ++k) obj[k] += (uint64_t)HP::take(hv[k], u, dd, lane);
+      HP::template take_all<D>(hv, u, dd, lane, obj);
       ++n_done;
     }
   }
