@@ -1395,9 +1395,16 @@ __device__ static inline void tg_dp_units32(uint32_t* prev, uint32_t* cur, const
       if (besta < bv) { bv = besta; bj = (uint32_t)j; }
       if (have2 && bestb < bv) { bv = bestb; bj = (uint32_t)(j + 1); }
     }
-    // best over used <= n, fewest units on ties
+    // best over used <= n, fewest units on ties.  With one pass per row (n <= 128) the cells ascend with the lanes:
+    // the smallest argument is that of the lowest lane that holds the minimum.
     const uint32_t vmin = tg_wave_min_u32(bv);
-    const uint32_t jmin = tg_wave_min_u32(bv == vmin ? bj : 0xffffffffu);
+    uint32_t jmin;
+    if (n <= 2 * TG_WAVE) {
+      const uint64_t at_min = __ballot(bv == vmin);
+      jmin = (uint32_t)__builtin_amdgcn_readlane((int)bj, __builtin_ctzll(at_min));
+    } else {
+      jmin = tg_wave_min_u32(bv == vmin ? bj : 0xffffffffu);
+    }
     if (lane == 0) { s_rowbest[i] = (int64_t)vmin; s_rowarg[i] = (int)(jmin & 511); cur[0] = kDpInf32; }
     uint32_t* tmp = prev; prev = cur; cur = tmp;
     tg_wave_sync();
