@@ -97,3 +97,35 @@ def test_token_levels_from_the_oracles_own_starts(orc, seed):
                 for j in need:
                     tok[j] -= 10**6
             assert all(v >= 0 for v in tok.values()), (s, n)
+
+
+def test_a_quota_beyond_rank_63_is_never_named(orc):
+    """66 quotas: a mask names ranks 0-63 only, so the bucket of rank 64 is drawn on by its own actions alone - their
+    start times do not depend on what the actions of other quotas name (bit 0 of a mask must not reach rank 64)."""
+    A, n_api = 400, 66
+    t = _api_trace(1, A, n_api, 77)
+    t["arrival_us"][:] = 0
+    rng = np.random.default_rng(5)
+    pin = rng.integers(0, n_api, A).astype(np.int32)
+    pin[::3] = 64                                                   # a third of the actions belong to the quota of rank 64
+    t["act_pin_node"] = pin
+    t["node_cap"][:] = 3; t["quota_tok0_micro"][:] = 2_000_000; t["quota_rate"][:] = 4   # scarce tokens everywhere
+    plain = orc.replay(t)
+    mask = np.where(pin == 64, 0, 1).astype(np.uint64)             # everybody else also names rank 0 ...
+    mask[pin == 0] = 2                                              # ... (its own actions name rank 1 instead)
+    t["act_quota_mask"] = mask
+    named = orc.replay(t)
+    own = pin == 64
+    np.testing.assert_array_equal(named["start_us"][own], plain["start_us"][own])
+    assert (named["start_us"][~own] != plain["start_us"][~own]).any()     # the masks do bind for the others
+    # and the bucket of rank 64 follows its closed form: 2 tokens at first, 4 micro-tokens x tick per tick after
+    tick = int(t["tick_us"])
+    tok, done, n, starts = 2_000_000, 0, 0, named["start_us"][own]
+    while done < own.sum() and n < 20000:
+        if n > 0:
+            tok = min(3_000_000, tok + 4 * tick)
+        go = min(tok // 10**6, int(own.sum()) - done)
+        assert (starts[done:done + go] == n * tick).all(), n
+        tok -= go * 10**6
+        done += go
+        n += 1
