@@ -216,17 +216,17 @@ __global__ __launch_bounds__(kOrderThreads) void tg_order_kernel(TgDev P, const 
   for (int x = tid; x < Nt; x += kOrderThreads) visit[abase + a0 + x] = acts[(int)(s_key[x] & 0x1ffff)];
 }
 
-// Larger pools, first step: workgroup (tile, pool) computes the keys of kOrderTile consecutive actions of the
+// Larger pools, first step: workgroup (pool, tile) computes the keys of kOrderTile consecutive actions of the
 // pool, sorts them in LDS and writes the sorted run to `runs` (laid out like the pool's slice of the visiting order).
 __global__ __launch_bounds__(kOrderThreads) void tg_order_runs_kernel(TgDev P, const int64_t* __restrict__ dur, const TgBlock* __restrict__ blocks,
                                                                       uint64_t* __restrict__ runs, uint64_t* __restrict__ gkey) {
   extern __shared__ __align__(16) unsigned char smem[];
   uint64_t* s_key = reinterpret_cast<uint64_t*>(smem);                       // [kOrderTile]
   __shared__ OrderLds L;
-  const int pool = blockIdx.y, b = pool / 3, t = pool - 3 * b, tid = threadIdx.x;
+  const int pool = blockIdx.x, b = pool / 3, t = pool - 3 * b, tid = threadIdx.x;   // pools along x: there can be more than 65 535
   const int a0 = P.tact_off[b * 4 + t], Nt = P.tact_off[b * 4 + t + 1] - a0;
   const int n0 = P.tnode_off[b * 4 + t], Mt = P.tnode_off[b * 4 + t + 1] - n0;
-  const int x0 = (int)blockIdx.x * kOrderTile;
+  const int x0 = (int)blockIdx.y * kOrderTile;
   if (x0 >= Nt) return;
   const size_t abase = (size_t)b * P.N, nbase = (size_t)b * P.M;
   const int32_t* acts = P.tact_idx + abase + a0;
@@ -263,16 +263,16 @@ __device__ static inline int merge_split(Ptr a, int na, Ptr b, int nb, int diag)
 }
 
 // Larger pools, merge step: sorted runs of `run` keys are merged pairwise into runs of 2 * run (src -> dst).
-// Workgroup (tile, pool) produces kMergeTile consecutive keys of the result: it finds by bisection which
+// Workgroup (pool, tile) produces kMergeTile consecutive keys of the result: it finds by bisection which
 // stretch of either run they come from, loads both stretches into LDS and every thread merges 8 keys from its
 // own split point.  The last pass writes the visiting order itself instead of keys.
 __global__ __launch_bounds__(kOrderThreads) void tg_order_merge_kernel(TgDev P, const uint64_t* __restrict__ src, uint64_t* __restrict__ dst,
                                                                        int32_t* __restrict__ visit, int run) {
   __shared__ uint64_t s_in[kMergeTile];
   __shared__ int s_split[2];
-  const int pool = blockIdx.y, b = pool / 3, t = pool - 3 * b, tid = threadIdx.x;
+  const int pool = blockIdx.x, b = pool / 3, t = pool - 3 * b, tid = threadIdx.x;
   const int a0 = P.tact_off[b * 4 + t], Nt = P.tact_off[b * 4 + t + 1] - a0;
-  const int o0 = (int)blockIdx.x * kMergeTile;                               // first key of the result this workgroup writes
+  const int o0 = (int)blockIdx.y * kMergeTile;                               // first key of the result this workgroup writes
   if (o0 >= Nt) return;
   const size_t abase = (size_t)b * P.N;
   const int32_t* acts = P.tact_idx + abase + a0;
@@ -903,14 +903,14 @@ int assign_launch(const tg_problem* p, const int64_t* d_cost, const tg_assign_ou
       TG_HIP_CHECK(hipFuncSetAttribute((const void*)tg_order_runs_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)runs_lds));
       const unsigned pools = (unsigned)P.B * 3;
       if (!prepare_only) {
-        hipLaunchKernelGGL(tg_order_runs_kernel, dim3((p->max_actions_of_kind + kOrderTile - 1) / kOrderTile, pools), dim3(kOrderThreads),
+        hipLaunchKernelGGL(tg_order_runs_kernel, dim3(pools, (p->max_actions_of_kind + kOrderTile - 1) / kOrderTile), dim3(kOrderThreads),
                            runs_lds, s, P, W.dur, p->d_blocks, W.okey_a, gkey);
         const uint64_t* src = W.okey_a;
         uint64_t* dst = W.okey_b;
         const unsigned tiles = (unsigned)((p->max_actions_of_kind + kMergeTile - 1) / kMergeTile);
         for (int run = kOrderTile; run < p->max_actions_of_kind; run *= 2) {
           const bool last = 2 * (int64_t)run >= p->max_actions_of_kind;
-          hipLaunchKernelGGL(tg_order_merge_kernel, dim3(tiles, pools), dim3(kOrderThreads), 0, s, P, src, dst, last ? W.visit : nullptr, run);
+          hipLaunchKernelGGL(tg_order_merge_kernel, dim3(pools, tiles), dim3(kOrderThreads), 0, s, P, src, dst, last ? W.visit : nullptr, run);
           const uint64_t* was = src; src = dst; dst = const_cast<uint64_t*>(was);
         }
       }
