@@ -403,3 +403,21 @@ def test_replay_pooled_gpus_with_other_options(tg, orc, seed):
     if seed % 2 == 0:
         t["numa_cores"] = 8
     _compare(_replay_gpu(tg, t), orc.replay(t), range(3), 450)
+
+
+def test_replay_pooled_gpus_burst_on_five_nodes(tg, orc):
+    """Thousands of GPU actions within half a second on a pool of 40 GPUs: up to 39 candidates on the one resource, Alg. 4 on
+    hundreds of chunk states, queues of thousands."""
+    t = _pooled(gen.make_trace(S=2, A=3000, seed=77, cluster=(0, 0, 5, 0), type_probs=(0, 1, 0), rate_per_s=5000.0, horizon_s=0.5,
+                               max_ticks=400000))
+    want = orc.replay(t)
+    assert (want["n_started"] == 3000).all()
+    _compare(_replay_gpu(tg, t), want, range(2), 3000)
+
+
+def test_replay_cost_order_longest_trace(tg, orc):
+    """The longest trace the builder takes (131 072 arrivals) in the second visiting order."""
+    A = 131072
+    t = gen.make_trace(S=1, A=A, seed=31, rate_per_s=400.0, horizon_s=A / 400.0, max_ticks=100000)
+    t["order_policy"] = 1
+    _compare(_replay_gpu(tg, t), orc.replay(t), [0], A)
