@@ -361,6 +361,20 @@ int tg_build_trace(const tg_trace_desc *desc, void *hip_stream, tg_trace **out);
 void tg_free_trace(tg_trace *t);
 int tg_replay_workspace_bytes(const tg_trace *t, size_t *bytes);
 int tg_replay_trace(const tg_trace *t, const tg_replay_out *out, void *d_ws, size_t ws_bytes, void *hip_stream);
+/*
+ * The replay in pieces: a run can stop after any number of ticks and go on later, e.g. to look at the schedule in
+ * between.  restart != 0: every scenario starts at time 0 (tg_replay_trace is restart = 1 with max_ticks ticks);
+ * restart == 0: every scenario goes on where the last call on this workspace and these output buffers stopped -
+ * both hold the whole state and must not have been touched in between (a workspace that does not carry the mark of
+ * an earlier call on a trace of this shape is refused on the device: n_ticks of every scenario becomes -1 and nothing
+ * else is written).  n_ticks >= 1: ticks of simulated time this
+ * call advances every unfinished scenario by (never past max_ticks).  After every call the outputs are those of a
+ * replay whose max_ticks is the tick reached: start / finish / units / node of the actions started so far, n_ticks
+ * the tick reached (or the tick after the last start, if everything has started), the statistics over the actions
+ * started so far.  Errors as tg_replay_trace; TG_E_INVALID_ARG for n_ticks < 1.
+ */
+int tg_replay_trace_part(const tg_trace *t, const tg_replay_out *out, void *d_ws, size_t ws_bytes, int restart, int n_ticks,
+                         void *hip_stream);
 
 /*
  * Capacities of the replay's buffers, for checking on the host (Sec. 4.2's step works on lists and

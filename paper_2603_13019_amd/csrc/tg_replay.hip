@@ -91,6 +91,7 @@ struct ReplayWs {
   uint64_t* live_cores;  // [S*M*4] free cores of every CPU node
   int32_t* run_id;       // [S*A] the running action's id (its cores are in the output map), alongside run_fin / run_info
   // second visiting order (only with order_cost)
+  int32_t* resume;       // [S*16] what a scenario needs besides the arrays above to go on where a call stopped
   uint64_t* okey;        // [S*A] (least estimated ACT of the action << 17) | action id: its place in the visiting order
   int32_t* wlist2;       // [S*3*A] the other half of the waiting lists' ping-pong (new arrivals are merged into the sorted list)
 };
@@ -111,7 +112,9 @@ size_t carve(const TgTraceDev& T, char* base, ReplayWs* w) {
   char* x0 = take(T.node_aux ? nN * 4 : 0); char* x1 = take(T.node_aux ? nA * 4 : 0);
   char* c0 = take(T.numa_cores ? nN * 32 : 0); char* c1 = take(T.numa_cores ? nA * 4 : 0);
   char* k0 = take(T.order_cost ? nA * 8 : 0); char* k1 = take(T.order_cost ? nA * 3 * 4 : 0);
+  char* rs = take((size_t)T.S * 16 * 4);
   if (w) {
+    w->resume = (int32_t*)rs;
     w->okey = (uint64_t*)k0; w->wlist2 = (int32_t*)k1;
     w->live_cores = (uint64_t*)c0; w->run_id = (int32_t*)c1;
     w->live_aux = (int32_t*)x0; w->run_aux = (int32_t*)x1;
@@ -286,7 +289,7 @@ int replay_layout(const TraceMaxima& mx, int K, ReplayLds* LD, TgNodeLdsPlan* pl
 // COST: every step visits the queue by least estimated ACT; the waiting lists are kept sorted by (key, id).
 template <bool WHOLE_QUEUE, bool COST>
 __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, ReplayWs W, tg_replay_out O, ReplayLds LD,
-                                                             TgNodeLdsPlan plan) {
+                                                             TgNodeLdsPlan plan, int restart, int n_ticks) {
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int s_wcnt[3], s_next, s_started, s_nrun, s_wave_cnt[kWaves], s_hist[256], s_sel[2], s_newcnt[3], s_pos[TG_WAVE];
   __shared__ unsigned long long s_stop;
@@ -320,6 +323,16 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
   int64_t* o_start = O.start_us + abase;
   int64_t* o_fin = O.finish_us + abase;
 
+  // restart: every scenario at time 0.  Otherwise the call goes on where the last one on this workspace and these
+  // outputs stopped: everything but a few counters lives in them.
+  int32_t* resume = W.resume + (size_t)s * 16;
+  const int resume_mark = 0x54470000 ^ (A * 31 + M);              // left behind by every call; a workspace without it has nothing to go on from
+  if (!restart && resume[9] != resume_mark) {
+    if (tid == 0) O.n_ticks[s] = -1;
+    return;
+  }
+  int tick = 0, last_tick = 0;
+  if (restart) {
   for (int i = tid; i < A; i += kThreads) { o_node[i] = -1; o_units[i] = 0; o_start[i] = -1; o_fin[i] = -1; }
   if (T.numa_cores) {
     for (size_t i = tid; i < (size_t)A * 4; i += kThreads) O.core_set[abase * 4 + i] = 0;
@@ -338,16 +351,25 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
     if (T.node_aux) W.live_aux[nbase + j] = T.node_aux[nbase + j];
   }
   if (tid == 0) { s_wcnt[0] = s_wcnt[1] = s_wcnt[2] = 0; s_next = 0; s_started = 0; s_nrun = 0; }
+  } else {
+    if (tid == 0) { s_wcnt[0] = resume[0]; s_wcnt[1] = resume[1]; s_wcnt[2] = resume[2]; s_next = resume[3]; s_started = resume[4]; s_nrun = resume[5]; }
+    tick = resume[6]; last_tick = resume[7];
+    if constexpr (COST) {                                         // which buffer holds the waiting list of a kind
+      const int parity = resume[8];
+      for (int ty = 0; ty < 3; ++ty)
+        if (parity >> ty & 1) { int32_t* o = wl[ty]; wl[ty] = wl_other[ty]; wl_other[ty] = o; }
+    }
+  }
   __syncthreads();
 
-  int tick = 0, last_tick = 0;
-  while (tick < T.max_ticks) {
+  const int tick_end = (int)min((int64_t)T.max_ticks, (int64_t)tick + n_ticks);   // this call's share of simulated time
+  while (tick < tick_end) {
     if (s_started >= A) break;
     // nothing waiting: jump to the tick of the next arrival (releases and refills commute with idle ticks)
     if (s_wcnt[0] + s_wcnt[1] + s_wcnt[2] == 0) {
       const int64_t na = arrival[s_next];                       // s_next < A because not everything has started
       const int64_t tk = (na + T.tick_us - 1) / T.tick_us;
-      if (tk >= T.max_ticks) { tick = T.max_ticks; break; }
+      if (tk >= tick_end) { tick = tick_end; break; }
       if ((int)tk > tick) tick = (int)tk;
     }
     const int64_t now = (int64_t)tick * T.tick_us;
@@ -771,6 +793,14 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
 
   // ---- per-scenario statistics: mean and nearest-rank p99 of ACT = finish - arrival ----------
   __syncthreads();
+  if (tid == 0) {
+    resume[0] = s_wcnt[0]; resume[1] = s_wcnt[1]; resume[2] = s_wcnt[2]; resume[3] = s_next; resume[4] = s_started; resume[5] = s_nrun;
+    resume[6] = tick; resume[7] = last_tick;
+    int parity = 0;
+    if constexpr (COST)
+      for (int ty = 0; ty < 3; ++ty) parity |= (wl[ty] != W.wlist + abase * 3 + (size_t)ty * A ? 1 : 0) << ty;
+    resume[8] = parity; resume[9] = resume_mark;
+  }
   if (tid == 0) s_sum = 0;
   __syncthreads();
   const int n_started = s_started;
@@ -1016,7 +1046,9 @@ extern "C" int tg_replay_workspace_bytes(const tg_trace* t, size_t* bytes) {
   return TG_OK;
 }
 
-extern "C" int tg_replay_trace(const tg_trace* t, const tg_replay_out* out, void* d_ws, size_t ws_bytes, void* hip_stream) {
+extern "C" int tg_replay_trace_part(const tg_trace* t, const tg_replay_out* out, void* d_ws, size_t ws_bytes, int restart, int n_ticks,
+                                    void* hip_stream) {
+  if (n_ticks < 1) return TG_E_INVALID_ARG;
   if (!t || !out || !out->start_us || !out->finish_us || !out->units || !out->node || !out->mean_act_us ||
       !out->p99_act_us || !out->n_started || !out->n_ticks || (t->dev.numa_cores && !out->core_set))
     return TG_E_INVALID_ARG;
@@ -1034,11 +1066,18 @@ extern "C" int tg_replay_trace(const tg_trace* t, const tg_replay_out* out, void
                              : (T.queue_prefix ? tg_replay_kernel<true, false> : tg_replay_kernel<false, false>);
   TG_HIP_CHECK(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   const size_t total = (size_t)T.S * T.A * T.K;
-  hipLaunchKernelGGL(tg_trace_dur_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, T, W.dur);
-  if (T.order_cost)
-    hipLaunchKernelGGL(tg_trace_key_kernel, dim3((unsigned)(((size_t)T.S * T.A + 255) / 256)), dim3(256), 0, s, T, W.dur, W.okey);
-  hipLaunchKernelGGL(kernel, dim3(T.S), dim3(kThreads), lds, s, T, W, *out, LD, plan);
+  if (restart) {                                                  // durations and places stay in the workspace for the calls that go on
+    hipLaunchKernelGGL(tg_trace_dur_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, T, W.dur);
+    if (T.order_cost)
+      hipLaunchKernelGGL(tg_trace_key_kernel, dim3((unsigned)(((size_t)T.S * T.A + 255) / 256)), dim3(256), 0, s, T, W.dur, W.okey);
+  }
+  hipLaunchKernelGGL(kernel, dim3(T.S), dim3(kThreads), lds, s, T, W, *out, LD, plan, restart ? 1 : 0, n_ticks);
   return hipGetLastError() == hipSuccess ? TG_OK : TG_E_HIP;
+}
+
+extern "C" int tg_replay_trace(const tg_trace* t, const tg_replay_out* out, void* d_ws, size_t ws_bytes, void* hip_stream) {
+  if (!t) return TG_E_INVALID_ARG;
+  return tg_replay_trace_part(t, out, d_ws, ws_bytes, 1, t->dev.max_ticks, hip_stream);
 }
 
 extern "C" int tg_replay_capacity(const tg_trace_desc* d, int64_t* cap) {

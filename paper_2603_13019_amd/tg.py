@@ -71,7 +71,7 @@ _DT = dict(k_list=np.int32, type_k=np.int32, speedup_q16=np.uint32, node_type=np
 
 EXPORTS = ("tg_build_problem", "tg_free_problem", "tg_num_candidates", "tg_assign_workspace_bytes",
            "tg_score_candidates", "tg_assign", "tg_assign_static", "tg_step", "tg_step_on", "tg_build_trace", "tg_free_trace", "tg_replay_workspace_bytes",
-           "tg_replay_trace", "tg_replay_capacity", "tg_strerror")
+           "tg_replay_trace", "tg_replay_trace_part", "tg_replay_capacity", "tg_strerror")
 
 
 def library_path():
@@ -102,6 +102,7 @@ def load():
         L.tg_free_trace.restype = None
         L.tg_replay_workspace_bytes.argtypes = [vp, C.POINTER(C.c_size_t)]
         L.tg_replay_trace.argtypes = [vp, vp, vp, C.c_size_t, vp]
+        L.tg_replay_trace_part.argtypes = [vp, vp, vp, C.c_size_t, C.c_int, C.c_int, vp]
         L.tg_replay_capacity.argtypes = [vp, vp]
         L.tg_strerror.argtypes = [C.c_int]
         L.tg_strerror.restype = C.c_char_p
@@ -313,4 +314,13 @@ class Trace:
             setattr(o, n, bufs[n].data_ptr() if bufs.get(n) is not None else None)
         _check(load().tg_replay_trace(self._h, C.byref(o), _ptr(bufs["ws"]), bufs["ws"].numel(), _stream()),
                "tg_replay_trace")
+        return bufs
+
+    def replay_part(self, bufs, restart, n_ticks):
+        """tg_replay_trace_part: ``n_ticks`` more ticks on ``bufs`` (from time 0 with ``restart``)."""
+        o = ReplayOut()
+        for n, _ in ReplayOut._fields_:
+            setattr(o, n, bufs[n].data_ptr() if bufs.get(n) is not None else None)
+        _check(load().tg_replay_trace_part(self._h, C.byref(o), _ptr(bufs["ws"]), bufs["ws"].numel(), int(bool(restart)), int(n_ticks),
+                                           _stream()), "tg_replay_trace_part")
         return bufs
