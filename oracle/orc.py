@@ -71,7 +71,7 @@ class Trace(C.Structure):
             "arrival_us", "act_type", "act_model", "act_t_ori_us", "act_kmask", "act_param", "act_pin_node",
             "act_service", "restore_us", "act_quota_mask")] + [("queue_prefix", C.c_int32)] + [
         ("node_aux", C.c_void_p), ("act_aux", C.c_void_p), ("numa_cores", C.c_int32), ("order_policy", C.c_int32),
-        ("gpu_pooled", C.c_int32)]
+        ("gpu_pooled", C.c_int32), ("cache_per_gpu", C.c_int32)]
 
 
 _DT = dict(k_list=np.int32, type_k=np.int32, speedup_q16=np.uint32, node_type=np.uint8, node_cap=np.int32,
@@ -155,7 +155,8 @@ def _trace(t):
     s.numa_cores = int(t.get("numa_cores", 0))           # > 0: CPU actions get named cores (NUMA domains of that many)
     s.order_policy = int(t.get("order_policy", 0))       # 1: every step visits the queue by least estimated ACT
     s.gpu_pooled = int(t.get("gpu_pooled", 0))           # 1: every step sees the GPU nodes as one pool of chunks
-    _fill(s, t, [f[0] for f in Trace._fields_[9:-6]] + ["node_aux", "act_aux"], keep)
+    s.cache_per_gpu = int(t.get("cache_per_gpu", 0))     # 1: every GPU of a GPU node keeps its own cache of services
+    _fill(s, t, [f[0] for f in Trace._fields_[9:-7]] + ["node_aux", "act_aux"], keep)
     return s, keep
 
 

@@ -534,6 +534,7 @@ struct orc_trace {
   int32_t numa_cores;                                              // > 0: CPU actions are given named cores (Sec. 5.2), all free at time 0
   int32_t order_policy;                                            // ORDER_FCFS, or ORDER_COST: every step visits the queue by least estimated ACT
   int32_t gpu_pooled;                                              // 1: every step sees the GPU nodes as one pool of chunks (Sec. 5.3, Alg. 4)
+  int32_t cache_per_gpu;                                           // 1: every GPU of a GPU node keeps its own cache of services (Sec. 5.3)
 };
 
 }  // extern "C"
@@ -739,6 +740,36 @@ static int mask_alloc(int& mask, int k) {               // best fit, lowest addr
   return -1;
 }
 
+// Sec. 5.3, with a cache on every GPU: the allocation takes from the lowest level that has a free chunk, as above;
+// among that level's free chunks one that already caches the requested service comes first.  A block of GPUs caches
+// a service when every GPU of it does.  Taken here: the first free chunk of the level that holds an aligned block of
+// the action's size caching the service, and the first such block of it; without one, the first chunk's first block.
+static int mask_alloc_cached(int& mask, int k, int sv, const uint64_t* gpu_res, bool* hit) {
+  const int a = chunk_level(k), need = 1 << a;
+  *hit = false;
+  for (int lvl = a; lvl < 4; ++lvl) {
+    const int sz = 1 << lvl;
+    std::vector<int> chunks;                               // starts of the free chunks of this level, ascending
+    for (int s = 0; s < 8; s += sz) {
+      const int blk = ((1 << sz) - 1) << s;
+      if ((mask & blk) != blk) continue;
+      if (lvl < 3) { const int ps = s & ~(2 * sz - 1); const int pb = ((1 << (2 * sz)) - 1) << ps; if ((mask & pb) == pb) continue; }
+      chunks.push_back(s);
+    }
+    if (chunks.empty()) continue;
+    int take = chunks[0];
+    for (size_t c = 0; c < chunks.size() && !*hit; ++c)
+      for (int b = chunks[c]; b < chunks[c] + sz && !*hit; b += need) {
+        bool all = true;
+        for (int g = b; g < b + need; ++g) all = all && (gpu_res[g] >> sv & 1ull);
+        if (all) { take = b; *hit = true; }
+      }
+    mask &= ~(((1 << need) - 1) << take);
+    return take;
+  }
+  return -1;
+}
+
 int orc_mask_chunks(int mask, uint8_t* out) { int c[4]; mask_chunks(mask, c); for (int x = 0; x < 4; ++x) out[x] = (uint8_t)c[x]; return 0; }
 int orc_mask_alloc(int* mask, int k) { return mask_alloc(*mask, k); }
 
@@ -765,6 +796,14 @@ static void replay_run(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us
     std::vector<uint64_t> resident(M, 0);
     std::vector<int64_t> used_at((size_t)M * 64, 0);        // per node and service: sequence number of its last use
     std::vector<int64_t> seq(M, 0);
+    // cache_per_gpu: on GPU nodes the cache belongs to the GPU - each keeps up to cache_slots services of its own,
+    // least recently used out first.  An action finds its service resident when every GPU of the block it is given
+    // caches it; afterwards every GPU of the block does, as its most recently used one.  The step keeps its
+    // per-node view: it counts a service as resident on a node when any GPU of the node caches it, so what an
+    // action really waits for a restore is known only once it has its GPUs (never less than the step assumed).
+    const bool per_gpu = t->cache_per_gpu != 0 && tb.restore_us;
+    std::vector<uint64_t> gpu_res(per_gpu ? (size_t)M * 8 : 0, 0);
+    std::vector<int64_t> gpu_used(per_gpu ? (size_t)M * 8 * 64 : 0, 0);
     // Second resource of a node (Sec. 4.1, 5.2: e.g. memory next to cores): an action that is free to choose
     // its node holds its demand from start to finish; pinned actions hold none (the share of their
     // trajectory is not part of a trace).
@@ -818,6 +857,7 @@ static void replay_run(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us
         Node& nd = nodes[j];
         nd.type = t->node_type[n0 + j]; nd.cap = t->node_cap[n0 + j]; nd.backlog = 0;
         nd.resident = resident[j];
+        if (per_gpu && nd.type == T_GPU) for (int g = 0; g < 8; ++g) nd.resident |= gpu_res[(size_t)j * 8 + g];
         nd.aux_free = aux_rem[j];
         if (numa > 0 && nd.type == T_CPU) nd.core_free = core_free[j];
         for (int x = 0; x < 4; ++x) nd.chunks[x] = 0;
@@ -884,10 +924,31 @@ static void replay_run(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us
         if (o.node[w] < 0) continue;
         const int j = o.node[w], k = o.units[w];
         int q = 0; while (tb.k_list[q] != k) ++q;
-        // realised = modelled duration: the delay is the one the step saw (residency at the tick's start)
-        const int64_t dur = restore_delay(tb, acts[w], nodes[j]) + duration(tb, acts[w], q);
+        // realised = modelled duration: the delay is the one the step saw (residency at the tick's start) -
+        // except with a cache per GPU, below
+        int64_t dur = restore_delay(tb, acts[w], nodes[j]) + duration(tb, acts[w], q);
         const int sv = acts[w].service;
-        if (sv >= 0 && tb.restore_us) {                      // the service is (now) resident and most recently used
+        int gstart = -1;
+        if (per_gpu && nodes[j].type == T_GPU && sv >= 0) {
+          // the delay is the one of the GPUs the action gets: none if all of them cache the service
+          bool hit;
+          gstart = mask_alloc_cached(gmask[j], k, sv, &gpu_res[(size_t)j * 8], &hit);
+          dur = (hit ? 0 : tb.restore_us[sv]) + duration(tb, acts[w], q);
+          ++seq[j];
+          for (int g = gstart; g < gstart + (1 << chunk_level(k)); ++g) {
+            uint64_t& res = gpu_res[(size_t)j * 8 + g];
+            int64_t* used = &gpu_used[((size_t)j * 8 + g) * 64];
+            if (!(res >> sv & 1ull) && __builtin_popcountll(res) >= t->cache_slots) {
+              int victim = -1;
+              for (int x = 0; x < 64; ++x)
+                if ((res >> x & 1ull) && (victim < 0 || used[x] < used[victim])) victim = x;
+              res &= ~(1ull << victim);
+            }
+            res |= 1ull << sv;
+            used[sv] = seq[j];
+          }
+        }
+        else if (sv >= 0 && tb.restore_us) {                 // the service is (now) resident and most recently used
           if (!(resident[j] >> sv & 1ull) && __builtin_popcountll(resident[j]) >= t->cache_slots) {
             int victim = -1;
             for (int x = 0; x < 64; ++x)
@@ -905,7 +966,7 @@ static void replay_run(const orc_trace* t, int s_lo, int s_hi, int64_t* start_us
             if (t->node_type[n0 + x] == T_API) { if (r < 64 && (acts[w].extra >> r & 1ull)) tok[x] -= 1000000; ++r; }
         }
         else {
-          if (nodes[j].type == T_GPU) u.gstart = mask_alloc(gmask[j], k);
+          if (nodes[j].type == T_GPU) u.gstart = gstart >= 0 ? gstart : mask_alloc(gmask[j], k);
           rem[j] -= k;
           if (t->node_aux) aux_rem[j] -= u.aux;
           if (numa > 0 && nodes[j].type == T_CPU) {
