@@ -248,6 +248,12 @@ def replay_section(a, tg, gen, torch):
         torch.cuda.synchronize()
         cache[f"slots_{slots}"] = float(bufs["mean_act_us"].mean().item())
         T.free()
+        # the same with the cache on every GPU (Sec. 5.3: the chunk that caches the service comes first)
+        T = tg.Trace(dict(t, cache_per_gpu=1))
+        bufs = T.replay()
+        torch.cuda.synchronize()
+        cache[f"slots_{slots}_per_gpu"] = float(bufs["mean_act_us"].mean().item())
+        T.free()
     res["service_cache_mean_act_us"] = dict(cache, workload="64 scenarios x 2000 GPU actions at 20/s on 4 nodes x 8 GPUs, "
                                                            "6 services, 2 s to restore one")
     return res

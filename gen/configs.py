@@ -465,8 +465,8 @@ def trace_with_services(t, seed, n_services, slots):
 
 
 def random_trace(seed):
-    """One small trace with cluster shape, load, tick limit, pins, depth, further quotas, services, the prefix rule,
-    a second resource and named cores drawn at random from ``seed``."""
+    """One small trace with cluster shape, load, tick limit, pins, depth, further quotas, services (cached per node or per GPU), the
+    prefix rule, a second resource, named cores, the visiting order and pooled GPUs drawn at random from ``seed``."""
     rng = np.random.default_rng(seed)
     n_cpu, n_gpu, n_api = int(rng.integers(0, 6)), int(rng.integers(0, 4)), int(rng.integers(0, 4))
     if n_cpu + n_gpu + n_api == 0:
@@ -491,6 +491,8 @@ def random_trace(seed):
         t["order_policy"] = 1
     if n_gpu and rng.random() < 0.4 and t.get("act_service") is None and t.get("node_aux") is None:
         trace_with_pooled_gpus(t)                              # the GPU nodes as one pool of chunks
+    if t.get("act_service") is not None and rng.random() < 0.5:
+        t["cache_per_gpu"] = 1                                 # the cache of services on every GPU instead of the node
     return t
 
 

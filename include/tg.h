@@ -283,11 +283,20 @@ enum { TG_TRACE_QUEUE_PREFIX = 1,
         * lowest-numbered node that has one - and `node` reports that node.  Needs: no GPU action pinned, no services, no
         * second resource (TG_E_INVALID_ARG), at most 5 GPU nodes per scenario (the pooled chunk counts of more could pass
         * TG_MAX_CHUNK_STATES: TG_E_RANGE). */
-       TG_TRACE_GPU_POOLED = 2 };
+       TG_TRACE_GPU_POOLED = 2,
+       /* Sec. 5.3 with the cache on the GPU instead of the node (ignored without services): every GPU of a GPU node
+        * keeps up to cache_slots services of its own, least recently used out first.  An action finds its service
+        * resident when every GPU of the block it is given caches it; afterwards every GPU of the block does.  The
+        * allocation takes from the lowest level that has a free chunk, as always; among that level's free chunks the
+        * first that holds an aligned block of the action's size caching the service gives that block, otherwise the
+        * first chunk gives its first block.  The step keeps its view per node - a service counts as resident where any
+        * GPU of the node caches it - so the delay an action really pays (none or restore_us) is known once it has its
+        * GPUs and is never less than the step assumed. */
+       TG_TRACE_CACHE_PER_GPU = 4 };
 typedef struct {
   int32_t S, A, M, K, n_classes, depth;
   int32_t max_ticks; /* the replay of a scenario stops after this many ticks                    */
-  uint32_t flags;    /* TG_TRACE_QUEUE_PREFIX | TG_TRACE_GPU_POOLED or 0; other bits must be clear  */
+  uint32_t flags;    /* TG_TRACE_QUEUE_PREFIX | _GPU_POOLED | _CACHE_PER_GPU or 0; other bits clear  */
   int64_t tick_us;   /* rescheduling period                                                     */
   const int32_t *k_list, *type_k;
   const uint32_t *speedup_q16;

@@ -37,6 +37,7 @@ struct TgTraceDev {
   const int32_t* act_aux;         // [S*A] what an action that is free to choose its node holds of it while it runs
   int numa_cores;                 // > 0: CPU actions get named cores, NUMA domains of this many (Sec. 5.2)
   int gpu_pooled;                 // 1: every step sees the GPU nodes of the scenario as one pool of chunks (Sec. 5.3, Alg. 4)
+  int cache_per_gpu;              // 1 (only with services): every GPU of a GPU node keeps its own cache (Sec. 5.3)
   int order_cost;                 // 1: every step visits the waiting queue by least estimated ACT (Sec. 4.2), ties by arrival
   const int32_t* kind_cap;        // [S*3] largest node of every kind in the scenario (-1: none); only with order_cost
 };
@@ -91,6 +92,7 @@ struct ReplayWs {
   uint64_t* live_cores;  // [S*M*4] free cores of every CPU node
   int32_t* run_id;       // [S*A] the running action's id (its cores are in the output map), alongside run_fin / run_info
   // second visiting order (only with order_cost)
+  uint64_t* gpu_res;     // [S*M*8] services resident on every GPU of a node (only with cache_per_gpu; used_at then has 8 x 64 per node)
   int32_t* resume;       // [S*16] what a scenario needs besides the arrays above to go on where a call stopped
   uint64_t* okey;        // [S*A] (least estimated ACT of the action << 17) | action id: its place in the visiting order
   int32_t* wlist2;       // [S*3*A] the other half of the waiting lists' ping-pong (new arrivals are merged into the sorted list)
@@ -108,13 +110,15 @@ size_t carve(const TgTraceDev& T, char* base, ReplayWs* w) {
   for (int x = 8; x < 13; ++x) p[x] = take(nN * 4);
   p[13] = take(nN * 8);
   const bool svc = T.act_service != nullptr;
-  char* q0 = take(svc ? nN * 8 : 0); char* q1 = take(svc ? nN * 64 * 4 : 0); char* q2 = take(svc ? nN * 4 : 0);
+  const size_t caches = T.cache_per_gpu ? 8 : 1;                  // per node
+  char* q0 = take(svc ? nN * 8 : 0); char* q1 = take(svc ? nN * caches * 64 * 4 : 0); char* q2 = take(svc ? nN * 4 : 0);
+  char* q3 = take(T.cache_per_gpu ? nN * 8 * 8 : 0);
   char* x0 = take(T.node_aux ? nN * 4 : 0); char* x1 = take(T.node_aux ? nA * 4 : 0);
   char* c0 = take(T.numa_cores ? nN * 32 : 0); char* c1 = take(T.numa_cores ? nA * 4 : 0);
   char* k0 = take(T.order_cost ? nA * 8 : 0); char* k1 = take(T.order_cost ? nA * 3 * 4 : 0);
   char* rs = take((size_t)T.S * 16 * 4);
   if (w) {
-    w->resume = (int32_t*)rs;
+    w->resume = (int32_t*)rs; w->gpu_res = (uint64_t*)q3;
     w->okey = (uint64_t*)k0; w->wlist2 = (int32_t*)k1;
     w->live_cores = (uint64_t*)c0; w->run_id = (int32_t*)c1;
     w->live_aux = (int32_t*)x0; w->run_aux = (int32_t*)x1;
@@ -348,6 +352,7 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
     live_tok[j] = ty == TG_TYPE_API ? T.quota_tok0[nbase + j] : 0;
     nl_cnt[j] = 0; dl_cnt[j] = 0;
     if (T.act_service) { W.live_res[nbase + j] = 0; W.use_seq[nbase + j] = 0; }   // nothing resident at time 0
+    if (T.cache_per_gpu) for (int g = 0; g < 8; ++g) W.gpu_res[(nbase + j) * 8 + g] = 0;
     if (T.node_aux) W.live_aux[nbase + j] = T.node_aux[nbase + j];
   }
   if (tid == 0) { s_wcnt[0] = s_wcnt[1] = s_wcnt[2] = 0; s_next = 0; s_started = 0; s_nrun = 0; }
@@ -718,11 +723,55 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
         const int k = o_units[id];
         int q = 0;
         while (q < K - 1 && T.k_list[q] != k) ++q;
-        const int g0 = mask_alloc(mk, k) & 7;
-        const int d = atomicAdd(&s_nrun, 1);
-        int64_t delay = 0;
         const int sv = T.act_service ? T.act_service[abase + id] : -1;
-        if (sv >= 0) {
+        int g0;
+        int64_t delay = 0;
+        if (T.cache_per_gpu && sv >= 0) {
+          // A cache on every GPU (Sec. 5.3): the allocation takes from the lowest level that has a free chunk; of
+          // that level's chunks the first that holds a block of the action's size whose GPUs all cache the service
+          // gives that block.  Masks of 8 GPUs; a block or chunk is marked at its first GPU.
+          uint64_t* gr = W.gpu_res + (nbase + j) * 8;
+          const int a = tg_chunk_level(k);
+          uint32_t f[4], hb = 0;
+          for (int g = 0; g < 8; ++g) hb |= (uint32_t)(gr[g] >> sv & 1ull) << g;
+          f[0] = mk;
+          f[1] = f[0] & (f[0] >> 1) & 0x55u; f[2] = f[1] & (f[1] >> 2) & 0x11u; f[3] = f[2] & (f[2] >> 4) & 0x01u;
+          if (a >= 1) hb = hb & (hb >> 1) & 0x55u;
+          if (a >= 2) hb = hb & (hb >> 2) & 0x11u;
+          if (a >= 3) hb = hb & (hb >> 4) & 0x01u;
+          g0 = 0;
+          bool hit = false;
+          for (int lvl = a; lvl < 4; ++lvl) {
+            uint32_t top = f[lvl];                                // free blocks of the level that are no part of a larger free block
+            if (lvl < 3) top &= ~(f[lvl + 1] | f[lvl + 1] << (1 << lvl));
+            if (!top) continue;
+            const uint32_t pick = hb & top * ((1u << (1 << lvl)) - 1u);   // blocks caching it inside these chunks
+            hit = pick != 0;
+            g0 = __builtin_ctz(hit ? pick : top);
+            break;
+          }
+          mk &= ~(((1u << (1 << a)) - 1u) << g0);
+          if (!hit) delay = T.restore[sv];
+          ++seq;
+          for (int g = g0; g < g0 + (1 << a); ++g) {              // resident and most recently used on every GPU of the block
+            uint64_t rg = gr[g];
+            int32_t* ug = W.used_at + ((nbase + j) * 8 + g) * 64;
+            if (!(rg >> sv & 1ull) && (int)__popcll(rg) >= T.cache_slots) {
+              int victim = -1;
+              for (uint64_t left = rg; left; left &= left - 1) {
+                const int y = __builtin_ctzll(left);
+                if (victim < 0 || ug[y] < ug[victim]) victim = y;
+              }
+              rg &= ~(1ull << victim);
+            }
+            gr[g] = rg | 1ull << sv;
+            ug[sv] = seq;
+          }
+          o_fin[id] = now + delay + dur[(size_t)id * K + q];     // known only now: the step saw the node's caches together
+        }
+        else g0 = mask_alloc(mk, k) & 7;
+        const int d = atomicAdd(&s_nrun, 1);
+        if (sv >= 0 && !T.cache_per_gpu) {
           if (!(res0 >> sv & 1ull)) delay = T.restore[sv];
           // the service is resident from now on and the most recently used one (Sec. 5.3, LRU)
           if (!(res >> sv & 1ull) && (int)__popcll(res) >= T.cache_slots) {
@@ -746,6 +795,10 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
       }
       live_free[j] = (int)mk;
       if (T.node_aux) W.live_aux[nbase + j] = aux_left;
+      if (T.cache_per_gpu) {                                      // what the next step sees of this node: cached on any of its GPUs
+        res = 0;
+        for (int g = 0; g < 8; ++g) res |= W.gpu_res[(nbase + j) * 8 + g];
+      }
       if (T.act_service) { W.live_res[nbase + j] = res; W.use_seq[nbase + j] = seq; }
     }
     // (5b) named cores (Sec. 5.2): the selected actions of a CPU node take theirs one after the other in list order,
@@ -848,7 +901,7 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
   if (!d || !out) return TG_E_INVALID_ARG;
   *out = nullptr;
   const int S = d->S, A = d->A, M = d->M, K = d->K;
-  if (S < 1 || A < 1 || M < 1 || (d->flags & ~(uint32_t)(TG_TRACE_QUEUE_PREFIX | TG_TRACE_GPU_POOLED)) != 0 || d->max_ticks < 1 || d->tick_us < 1) return TG_E_INVALID_ARG;
+  if (S < 1 || A < 1 || M < 1 || (d->flags & ~(uint32_t)(TG_TRACE_QUEUE_PREFIX | TG_TRACE_GPU_POOLED | TG_TRACE_CACHE_PER_GPU)) != 0 || d->max_ticks < 1 || d->tick_us < 1) return TG_E_INVALID_ARG;
   if (d->depth < 1 || d->depth > TG_MAX_DEPTH) return TG_E_INVALID_ARG;
   const bool svc = d->act_service != nullptr;
   if (svc != (d->restore_us != nullptr)) return TG_E_INVALID_ARG;
@@ -1019,6 +1072,7 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
     v.cache_slots = svc ? d->cache_slots : 0;
     v.queue_prefix = (d->flags & TG_TRACE_QUEUE_PREFIX) ? 1 : 0;
     v.gpu_pooled = pooled ? 1 : 0;
+    v.cache_per_gpu = svc && (d->flags & TG_TRACE_CACHE_PER_GPU) ? 1 : 0;
     v.act_quota = d->act_quota_mask ? (const uint64_t*)(base + o_aquota) : nullptr;
     v.node_aux = aux ? (const int32_t*)(base + o_naux) : nullptr;
     v.act_aux = aux ? (const int32_t*)(base + o_aaux) : nullptr;

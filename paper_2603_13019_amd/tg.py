@@ -250,7 +250,8 @@ def _trace_desc(t: dict):
     d = TraceDesc()
     for n in ("S", "A", "M", "K", "n_classes", "depth", "max_ticks"):
         setattr(d, n, int(t[n]))
-    d.flags = (1 if int(t.get("queue_prefix", 0)) else 0) | (2 if int(t.get("gpu_pooled", 0)) else 0)   # TG_TRACE_QUEUE_PREFIX, _GPU_POOLED
+    d.flags = ((1 if int(t.get("queue_prefix", 0)) else 0) | (2 if int(t.get("gpu_pooled", 0)) else 0)   # TG_TRACE_QUEUE_PREFIX, _GPU_POOLED
+               | (4 if int(t.get("cache_per_gpu", 0)) else 0))                                           # _CACHE_PER_GPU
     d.tick_us = int(t["tick_us"])
     keep = []
     _fill(d, t, [f[0] for f in TraceDesc._fields_[9:-7]] + ["act_quota_mask", "node_aux", "act_aux"], keep)

@@ -288,7 +288,7 @@ BAD_TRACE = {
     "arrivals_not_sorted": (lambda t: t["arrival_us"].__setitem__(5, 0), -1),
     "gpu_node_not_8": (lambda t: t["node_cap"].__setitem__(int(np.flatnonzero(t["node_type"] == gen.TYPE_GPU)[0]), 4), -1),
     "tick_zero": (lambda t: t.__setitem__("tick_us", 0), -1),
-    "unknown_flag": (lambda t: t.__setitem__("flags", 4), -1),
+    "unknown_flag": (lambda t: t.__setitem__("flags", 8), -1),
     "pooled_gpus_with_a_pinned_gpu_action": (lambda t: (t.__setitem__("flags", 2), t["act_type"].__setitem__(7, 1), t["act_kmask"].__setitem__(7, 1),
                                                         t["act_model"].__setitem__(7, 0),
                                                         t["act_pin_node"].__setitem__(7, int(np.flatnonzero(t["node_type"] == gen.TYPE_GPU)[0]))), -1),
@@ -299,7 +299,7 @@ BAD_TRACE = {
     "second_resource_half_given": (lambda t: t.__setitem__("node_aux", np.ones(t["S"] * t["M"], np.int32)), -1),
     "second_resource_negative": (lambda t: (t.__setitem__("node_aux", np.ones(t["S"] * t["M"], np.int32)),
                                             t.__setitem__("act_aux", np.full(t["S"] * t["A"], -1, np.int32))), -1),
-    "unknown_flag_next_to_a_known_one": (lambda t: t.__setitem__("flags", 5), -1),
+    "unknown_flag_next_to_a_known_one": (lambda t: t.__setitem__("flags", 9), -1),
     "unknown_visiting_order": (lambda t: t.__setitem__("order_policy", 2), -1),
     "cost_order_with_services": (lambda t: (t.__setitem__("order_policy", 1), gen.trace_with_services(t, 1, 4, 2)), -1),
     "tokens_above_bucket": (lambda t: t["quota_tok0_micro"].__setitem__(int(np.flatnonzero(t["node_type"] == gen.TYPE_API)[0]), 10**12), -1),

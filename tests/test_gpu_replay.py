@@ -421,3 +421,51 @@ def test_replay_cost_order_longest_trace(tg, orc):
     t = gen.make_trace(S=1, A=A, seed=31, rate_per_s=400.0, horizon_s=A / 400.0, max_ticks=100000)
     t["order_policy"] = 1
     _compare(_replay_gpu(tg, t), orc.replay(t), [0], A)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_replay_cache_per_gpu(tg, orc, seed):
+    """Sec. 5.3 with a cache on every GPU: the block that caches the service comes first, the delay follows the GPUs
+    an action gets.  Clusters of 1-3 GPU nodes, 2-64 services, 1-64 slots, with pins, the prefix rule, a second
+    resource and further quotas."""
+    print("case cache per gpu", seed, flush=True)
+    t = gen.make_trace(S=3, A=500 + 100 * seed, seed=370 + seed, cluster=(1 + seed % 2, 16, 1 + seed % 3, seed % 2 * 3),
+                       type_probs=(0.2, 0.7, 0.1) if seed % 2 else (0.3, 0.7, 0.0),
+                       rate_per_s=(30.0, 60.0, 150.0)[seed % 3], horizon_s=12.0, max_ticks=80000, pin_frac=0.3)
+    _with_services(t, seed, n_services=(2, 5, 9, 64)[seed % 4], slots=(1, 2, 3, 64)[(seed // 2) % 4])
+    if seed % 4 == 1:
+        t["queue_prefix"] = 1
+    if seed % 4 == 2:
+        _with_aux(t, seed, scarce=True)
+    if seed % 4 == 3:
+        gen.with_extra_quotas(t, frac=0.6, seed=seed)
+    per_node = orc.replay(t)
+    t["cache_per_gpu"] = 1
+    want = orc.replay(t)
+    assert (want["finish_us"] != per_node["finish_us"]).any()
+    _compare(_replay_gpu(tg, t), want, range(t["S"]), t["A"])
+
+
+def test_replay_cache_per_gpu_many_gpu_nodes(tg, orc):
+    t = gen.make_trace(S=2, A=1500, seed=381, cluster=(0, 0, 70, 0), type_probs=(0, 1, 0), rate_per_s=400.0, horizon_s=4.0,
+                       max_ticks=80000, pin_frac=0.2)
+    _with_services(t, 9, n_services=12, slots=2)
+    t["cache_per_gpu"] = 1
+    _compare(_replay_gpu(tg, t), orc.replay(t), range(t["S"]), t["A"])
+
+
+def test_replay_cache_per_gpu_block_choice(tg, orc):
+    """One node, hand-made arrivals: the chunk that caches the service before the lowest one, the level before the
+    cache, the block inside a larger chunk, blocks of 2, 4 and 8 GPUs."""
+    from test_oracle_replay_gpu_cache import _node_trace
+    cases = [
+        [(0, 1, 1000, -1), (1, 1, 5, 0), (2, 1, 1000, -1), (3, 1, 5, 1), (100, 1, 50, 1), (110, 1, 50, 0)],
+        [(0, 4, 20, -1), (1, 1, 5, 0), (100, 1, 1000, -1), (101, 1, 5, 0)],
+        [(0, 4, 20, -1), (1, 1, 5, 0), (100, 1, 50, 0), (101, 1, 50, 0), (200, 1, 50, 0), (201, 1, 50, 0), (202, 1, 50, 0)],
+        [(0, 1, 5, 0), (100, 2, 5, 0), (200, 2, 5, 0), (300, 4, 5, 0), (400, 4, 5, 0), (500, 8, 5, 0), (600, 8, 5, 0), (700, 1, 5, 0)],
+        [(0, 2, 50, 1), (1, 2, 50, 0), (2, 4, 50, 1), (100, 4, 5, 1), (101, 2, 5, 0), (102, 2, 5, 1), (103, 1, 5, 0)],
+    ]
+    for rows in cases:
+        for slots in (1, 2):
+            t = _node_trace(rows, [300_000, 700_000], slots)
+            _compare(_replay_gpu(tg, t), orc.replay(t), range(1), len(rows))
