@@ -1,11 +1,18 @@
 // tg_replay_trace: S independent arrival traces, one persistent workgroup per scenario.
 //
 // Every tick the workgroup runs the same scheduling step as tg_assign (the wavefront-level
-// functions of tg_step.h) on the scenario's live state: the three resource pools are placed by
-// three wavefronts in parallel, the nodes that received candidates are spread over the
-// wavefronts that own a per-node LDS block for DPArrange + eviction, and selected actions start
-// at the tick (GPU nodes also update their cache of resident services then).  The tick loop
-// is bounded by max_ticks, so every wavefront leaves the kernel.
+// functions of tg_step.h) on the scenario's live state: the three resource pools are placed,
+// the nodes that received candidates run DPArrange + eviction in a per-node LDS block, and
+// selected actions start at the tick (GPU nodes also update their cache of resident services
+// then).  The tick loop is bounded by max_ticks, so every wavefront leaves the kernel.
+//
+// A workgroup is ONE wavefront (kWaves): a tick is a chain of dependent memory accesses that
+// keeps a wavefront waiting most of the time, and registers allow eight wavefronts per CU
+// whatever their grouping - eight scenarios in flight per CU finish a batch of thousands twice
+// as fast as two scenarios with four wavefronts each, whose extra wavefronts mostly idle at
+// barriers.  The code below is written for kWaves wavefronts (kinds and nodes are dealt out
+// by wavefront index); the LDS of the placement and of the node stage overlap, since the
+// placement tables are dead when the node stage begins, so that eight workgroups fit a CU.
 //
 // Live state per scenario (global workspace, L2 resident): free cores per CPU node, free-GPU
 // bit mask per GPU node (a free chunk is a maximal aligned free block, so releasing coalesces
@@ -66,7 +73,7 @@ struct tg_trace {
 
 namespace {
 
-constexpr int kWaves = 4;
+constexpr int kWaves = 1;
 constexpr int kThreads = kWaves * TG_WAVE;
 
 struct ReplayWs {
@@ -268,24 +275,26 @@ int trace_maxima(const tg_trace_desc* d, TraceMaxima* mx) {
   return TG_OK;
 }
 
-// LDS of a workgroup: one placement block per kind, then one per-node block for each wavefront
-// that runs DPArrange.  Two workgroups fit a CU when the total stays under half of its LDS, so
-// large clusters give per-node blocks to fewer wavefronts rather than lose the second workgroup.
+// LDS of a workgroup: one placement block per kind (one for all kinds when a single wavefront places them one
+// after the other) and, in the same bytes, one per-node block for each wavefront that runs DPArrange - the
+// placement tables are exported to the workspace before the node stage begins.  8 / kWaves workgroups fit a CU
+// when the total stays under that share of its LDS; beyond it fewer wavefronts get a per-node block.
 int replay_layout(const TraceMaxima& mx, int K, ReplayLds* LD, TgNodeLdsPlan* plan, size_t* lds_bytes) {
   *plan = tg_node_lds_plan(mx.max_cap_cpu, mx.max_free_gpu, mx.max_chunk_states, mx.max_heap, K, 1 << 30, 8, TG_WAVE);
   LD->busy_slots = (mx.max_heap + 1 + 1) & ~1;
-  size_t off = 0;
+  size_t pools = 0;
   for (int k = 0; k < 3; ++k) {
     LD->pool_nodes[k] = std::max(mx.nodes_kind[k], 1);
-    LD->pool_off[k] = (int)off;
-    off += (tg_pool_lds_bytes(LD->pool_nodes[k]) + 15) & ~size_t(15);
+    const size_t bytes = (tg_pool_lds_bytes(LD->pool_nodes[k]) + 15) & ~size_t(15);
+    LD->pool_off[k] = kWaves == 1 ? 0 : (int)pools;               // one wavefront places the kinds one after the other
+    pools = kWaves == 1 ? std::max(pools, bytes) : pools + bytes;
   }
-  LD->node_off = (int)off;
+  LD->node_off = 0;                                               // the placement blocks are dead when the node stage begins
   const size_t node_bytes = (size_t)plan->total + (size_t)LD->busy_slots * 8;
-  const size_t half_cu = 80 * 1024 - 2048;                      // the kernel also has ~1.3 KB of static LDS
+  const size_t share = 160 * 1024 / (8 / kWaves) - 512;           // of a CU's LDS, next to the kernel's static ~0.3 KB
   LD->node_waves = kWaves;
-  while (LD->node_waves > 1 && off + LD->node_waves * node_bytes > half_cu) LD->node_waves >>= 1;
-  *lds_bytes = off + LD->node_waves * node_bytes;
+  while (LD->node_waves > 1 && LD->node_waves * node_bytes > share) LD->node_waves >>= 1;
+  *lds_bytes = std::max<size_t>({pools, LD->node_waves * node_bytes, 1024});   // 1 KB: the histogram of the statistics
   return *lds_bytes > 160 * 1024 - 2048 ? TG_E_RANGE : TG_OK;
 }
 
@@ -295,7 +304,7 @@ template <bool WHOLE_QUEUE, bool COST>
 __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, ReplayWs W, tg_replay_out O, ReplayLds LD,
                                                              TgNodeLdsPlan plan, int restart, int n_ticks) {
   extern __shared__ __align__(16) unsigned char smem[];
-  __shared__ int s_wcnt[3], s_next, s_started, s_nrun, s_wave_cnt[kWaves], s_hist[256], s_sel[2], s_newcnt[3], s_pos[TG_WAVE];
+  __shared__ int s_wcnt[3], s_next, s_started, s_nrun, s_wave_cnt[kWaves], s_sel[2], s_newcnt[3], s_pos[TG_WAVE];
   __shared__ unsigned long long s_stop;
   __shared__ long long s_sum;
   const int s = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -862,12 +871,13 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
   atomicAdd((unsigned long long*)&s_sum, (unsigned long long)sum);
   __syncthreads();
   // radix select of the rank-th smallest ACT, one byte per pass from the top
+  int* s_hist = reinterpret_cast<int*>(smem);                     // the tables of the ticks are dead
   int64_t p99 = -1;
   if (n_started > 0) {
     int rank = (int)((99ll * n_started + 99) / 100);             // 1-based
     uint64_t prefix = 0;
     for (int shift = 56; shift >= 0; shift -= 8) {
-      s_hist[tid] = 0;
+      for (int b = tid; b < 256; b += kThreads) s_hist[b] = 0;
       __syncthreads();
       for (int i = tid; i < A; i += kThreads)
         if (o_start[i] >= 0) {
