@@ -524,6 +524,7 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
     constexpr int n_pass = WHOLE_QUEUE ? 2 : 1;
     for (int pass = 0; pass < n_pass; ++pass) {
     for (int ty = wave; ty < 3; ty += kWaves) {
+      if (wcs[ty] == 0) continue;                                 // nobody waits for this kind: its list lengths are still zero
       const int n0 = T.tnode_off[s * 4 + ty], Mt_all = T.tnode_off[s * 4 + ty + 1] - n0;
       const int32_t* nodes = T.tnode_idx + nbase + n0;
       // pooled GPUs: the first GPU node stands for the pool, with the free chunks of all of them (at most 5 nodes)
@@ -590,8 +591,54 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
     int n_seen = 0;                                               // nodes with candidates met so far
     for (int jb = 0; jb < M; jb += TG_WAVE) {
      // every wavefront looks at the same 64 list lengths and takes every kWaves-th node that has candidates
-     const int my_m = jb + lane < M ? nl_cnt[jb + lane] : 0;
-     uint64_t todo = __ballot(my_m > 0);
+     const int jn = jb + lane;
+     const int my_m = jn < M ? nl_cnt[jn] : 0;
+     // A node with one candidate and nobody waiting for it needs no table and no heap (as tg_node_single): its
+     // action takes the fastest allowed option that fits.  All such nodes of the 64 at once, lane = node - their
+     // loads travel together instead of node after node.
+     bool lone = false;
+     if (my_m == 1) {
+       const int ty = T.node_type[nbase + jn];
+       lone = dl_cnt[jn] == 0 && !(T.gpu_pooled && ty == TG_TYPE_GPU);
+       if (lone && wave == 0) {
+         const int id = order[nl_off[jn]];
+         const uint32_t mask = T.act_kmask[abase + id];
+         const bool elastic = T.act_model[abase + id] != TG_MODEL_NONE;
+         const int cap = T.node_cap[nbase + jn];
+         const uint32_t lf = (uint32_t)live_free[jn];
+         const int free_units = ty == TG_TYPE_API ? (int)(live_tok[jn] / 1000000) : (int)lf;
+         const uint32_t chunks = ty == TG_TYPE_GPU ? mask_chunks(lf) : 0;
+         int64_t delay = 0;
+         if (T.act_service) {
+           const int sv = T.act_service[abase + id];
+           if (sv >= 0 && !(W.live_res[nbase + jn] >> sv & 1ull)) delay = T.restore[sv];
+         }
+         const int q_min = __builtin_ctz(mask);
+         uint64_t best = ~0ull;
+         int k_best = T.k_list[0];
+         for (int q = 0; q < K; ++q) {
+           if (!(mask >> q & 1u) || !(elastic || q == q_min)) continue;
+           const int64_t d = dur[(size_t)id * K + q];
+           const int kq = T.k_list[q];
+           uint64_t key = ~0ull;
+           if (!elastic) key = (uint64_t)(d + delay) << 12;        // runs on its minimum units (Alg. 1)
+           else if (d != TG_INF && kq <= cap) {
+             if (ty == TG_TYPE_GPU) {
+               if (kq <= tg_chunk_largest(chunks)) {               // ties: the option that leaves the smaller chunk state
+                 const int r0 = max((int)(chunks & 0xff), 1) + 1, r1 = max((int)(chunks >> 8 & 0xff), 1) + 1,
+                           r2 = max((int)(chunks >> 16 & 0xff), 1) + 1;
+                 const uint32_t c = tg_chunk_take(chunks, kq);
+                 const int code = (int)(c & 0xff) + r0 * ((int)(c >> 8 & 0xff) + r1 * ((int)(c >> 16 & 0xff) + r2 * (int)(c >> 24)));
+                 key = (uint64_t)(d + delay) << 12 | (uint32_t)code;
+               }
+             } else if (kq <= free_units) key = (uint64_t)(d + delay) << 12 | (uint32_t)kq;   // ties: fewer units
+           }
+           if (key < best) { best = key; k_best = kq; }
+         }
+         o_units[id] = k_best;
+       }
+     }
+     uint64_t todo = __ballot(my_m > 0 && !lone);
      while (todo) {
       const int jl = __ffsll((unsigned long long)todo) - 1;
       todo &= todo - 1;
