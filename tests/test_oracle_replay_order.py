@@ -99,3 +99,82 @@ def test_gpu_chunks_are_handed_out_in_visiting_order(orc):
         for _, d in ev:
             used += d
             assert 0 <= used <= 8
+
+
+# --- the second visiting order next to the service cache: the keys move with what is resident (Sec. 4.2, 5.3) ----------
+
+def _whole_node_trace(T_ticks, services, restore_ticks, slots, arrivals_ticks, tick=100_000, per_gpu=0):
+    """One 8-GPU node; every action takes all 8 GPUs without elasticity: one machine whose set-up time for a job
+    depends on what its cache holds."""
+    A = len(T_ticks)
+    t = gen.make_trace(S=1, A=A, seed=1, cluster=(0, 0, 1, 0), type_probs=(0, 1, 0), pin_frac=0.0, max_ticks=10**6, tick_us=tick)
+    k8 = [int(k) for k in t["k_list"]].index(8)
+    t["arrival_us"] = np.asarray(arrivals_ticks, np.int64) * tick
+    t["act_model"] = np.zeros(A, np.uint8)
+    t["act_kmask"] = np.full(A, 1 << k8, np.uint32)
+    t["act_t_ori_us"] = np.asarray(T_ticks, np.int64) * tick
+    t["act_pin_node"] = np.full(A, -1, np.int32)
+    t["act_service"] = np.asarray(services, np.int32)
+    t["restore_us"] = np.asarray(restore_ticks, np.int64) * tick
+    t["cache_slots"] = slots
+    t["cache_per_gpu"] = per_gpu
+    t["order_policy"] = 1
+    return t
+
+
+def _one_machine_with_cache(T, sv, restore, slots, arr):
+    """Independent simulation on the tick grid: whenever the machine is free, the arrived job with the least
+    (run time + restore time unless its service is cached) starts, earlier arrival on ties; LRU cache."""
+    A = len(T)
+    start, fin = [-1] * A, [-1] * A
+    cache, seq, free_at, now = {}, 0, 0, 0
+    while min(start) < 0:
+        here = [i for i in range(A) if start[i] < 0 and arr[i] <= now]
+        if here and free_at <= now:
+            cost = lambda i: T[i] + (restore[sv[i]] if sv[i] >= 0 and sv[i] not in cache else 0)
+            i = min(here, key=lambda x: (cost(x), x))
+            start[i], fin[i] = now, now + cost(i)
+            free_at = fin[i]
+            if sv[i] >= 0:
+                if sv[i] not in cache and len(cache) >= slots:
+                    del cache[min(cache, key=lambda y: (cache[y], y))]
+                seq += 1
+                cache[sv[i]] = seq
+        now += 1
+    return start, fin
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_cost_order_with_services_follows_the_cache(orc, seed):
+    rng = np.random.default_rng(900 + seed)
+    A = 40
+    T = rng.integers(1, 6, A).tolist()
+    n_sv = int(rng.integers(2, 5))
+    sv = rng.integers(-1, n_sv, A).tolist()
+    restore = rng.integers(1, 9, n_sv).tolist()
+    slots = int(rng.integers(1, 3))
+    arr = sorted(rng.integers(0, 60 if seed % 2 else 1, A).tolist())       # odd seeds: arrivals over time; even: all at once
+    want_start, want_fin = _one_machine_with_cache(T, sv, restore, slots, arr)
+    for per_gpu in (0, 1):                                                  # whole-node actions: both caches are the same
+        t = _whole_node_trace(T, sv, restore, slots, arr, per_gpu=per_gpu)
+        o = orc.replay(t)
+        np.testing.assert_array_equal(o["start_us"], np.asarray(want_start, np.int64) * t["tick_us"])
+        np.testing.assert_array_equal(o["finish_us"], np.asarray(want_fin, np.int64) * t["tick_us"])
+    fcfs = orc.replay(dict(t, order_policy=0))
+    assert (fcfs["start_us"] != o["start_us"]).any()
+    # the cache changes the order, not only the durations: the static keys (run time alone) give another schedule
+    static = np.lexsort((np.arange(A), np.asarray(T)))
+    by_key = np.argsort(o["start_us"], kind="stable")
+    if seed % 2 == 0:
+        assert (by_key != static).any()
+
+
+def test_cost_order_with_free_restores_is_the_plain_cost_order(orc):
+    t = gen.make_trace(S=2, A=500, seed=98, contended=True, rate_per_s=80.0, horizon_s=5.0, max_ticks=20000)
+    t["order_policy"] = 1
+    base = orc.replay(t)
+    gen.trace_with_services(t, 3, n_services=5, slots=1)
+    t["restore_us"][:] = 0
+    o = orc.replay(t)
+    for k in ("start_us", "finish_us", "units", "node"):
+        np.testing.assert_array_equal(o[k], base[k])
