@@ -487,7 +487,7 @@ def random_trace(seed):
         trace_with_aux(t, seed, scarce=bool(rng.integers(0, 2)))
     if rng.random() < 0.4:                                     # CPU actions get named cores
         t["numa_cores"] = int(rng.choice([4, 8, 16, 32, 64]))
-    if rng.random() < 0.35 and t.get("act_service") is None:   # the queue visited by least estimated ACT
+    if rng.random() < 0.35:                                    # the queue visited by least estimated ACT
         t["order_policy"] = 1
     if n_gpu and rng.random() < 0.4 and t.get("act_service") is None and t.get("node_aux") is None:
         trace_with_pooled_gpus(t)                              # the GPU nodes as one pool of chunks

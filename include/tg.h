@@ -336,8 +336,10 @@ typedef struct {
    * tg_replay_out.core_set is then required.  0: cores are not named. */
   int32_t numa_cores;
   int32_t order_policy;             /* TG_ORDER_FCFS (0), or TG_ORDER_COST: every tick's step visits the waiting queue by least
-                                     * estimated ACT (equal keys by arrival), and the actions it selects start in that order;
-                                     * not together with services (the keys would change with the caches): TG_E_INVALID_ARG */
+                                     * estimated ACT (equal keys by arrival), and the actions it selects start in that order.
+                                     * With services the estimate of a GPU action counts the restore time unless a node it
+                                     * may run on has the service resident when the tick begins, so its place moves with
+                                     * the caches */
 } tg_trace_desc;
 
 /* Device outputs of tg_replay_trace. */

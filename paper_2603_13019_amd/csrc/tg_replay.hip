@@ -102,6 +102,8 @@ struct ReplayWs {
   uint64_t* gpu_res;     // [S*M*8] services resident on every GPU of a node (only with cache_per_gpu; used_at then has 8 x 64 per node)
   int32_t* resume;       // [S*16] what a scenario needs besides the arrays above to go on where a call stopped
   uint64_t* okey;        // [S*A] (least estimated ACT of the action << 17) | action id: its place in the visiting order
+  uint64_t* okey0;       // [S*A] the same without any restore delay, and
+  uint64_t* skey;        // [S*A] the keys of a waiting list in list order (both only with order_cost and services)
   int32_t* wlist2;       // [S*3*A] the other half of the waiting lists' ping-pong (new arrivals are merged into the sorted list)
 };
 
@@ -123,10 +125,11 @@ size_t carve(const TgTraceDev& T, char* base, ReplayWs* w) {
   char* x0 = take(T.node_aux ? nN * 4 : 0); char* x1 = take(T.node_aux ? nA * 4 : 0);
   char* c0 = take(T.numa_cores ? nN * 32 : 0); char* c1 = take(T.numa_cores ? nA * 4 : 0);
   char* k0 = take(T.order_cost ? nA * 8 : 0); char* k1 = take(T.order_cost ? nA * 3 * 4 : 0);
+  char* k2 = take(T.order_cost && svc ? nA * 8 : 0); char* k3 = take(T.order_cost && svc ? nA * 8 : 0);
   char* rs = take((size_t)T.S * 16 * 4);
   if (w) {
     w->resume = (int32_t*)rs; w->gpu_res = (uint64_t*)q3;
-    w->okey = (uint64_t*)k0; w->wlist2 = (int32_t*)k1;
+    w->okey = (uint64_t*)k0; w->wlist2 = (int32_t*)k1; w->okey0 = (uint64_t*)k2; w->skey = (uint64_t*)k3;
     w->live_cores = (uint64_t*)c0; w->run_id = (int32_t*)c1;
     w->live_aux = (int32_t*)x0; w->run_aux = (int32_t*)x1;
     w->live_res = (uint64_t*)q0; w->used_at = (int32_t*)q1; w->use_seq = (int32_t*)q2;
@@ -160,7 +163,8 @@ __global__ __launch_bounds__(256) void tg_trace_dur_kernel(TgTraceDev T, int64_t
 // action.  Packed with the action id (ids ascend with the arrivals) into its place in the visiting order.
 constexpr uint64_t kKeyInf = (1ull << 46) - 1;
 
-__global__ __launch_bounds__(256) void tg_trace_key_kernel(TgTraceDev T, const int64_t* __restrict__ dur, uint64_t* __restrict__ okey) {
+__global__ __launch_bounds__(256) void tg_trace_key_kernel(TgTraceDev T, const int64_t* __restrict__ dur, uint64_t* __restrict__ okey,
+                                                           uint64_t* __restrict__ okey0) {
   const size_t g = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (g >= (size_t)T.S * T.A) return;
   const int s = (int)(g / T.A), i = (int)(g - (size_t)s * T.A);
@@ -174,6 +178,7 @@ __global__ __launch_bounds__(256) void tg_trace_key_kernel(TgTraceDev T, const i
     if (ok) key = (uint64_t)dur[g * T.K + (31 - __builtin_clz(ok))];
   }
   okey[g] = key << 17 | (uint32_t)i;
+  if (T.act_service) okey0[g] = key << 17 | (uint32_t)i;          // the replay adds this tick's restore delay to it
 }
 
 // free chunks (sizes 1,2,4,8) of an 8-GPU node as packed 8-bit counts: a chunk is an aligned
@@ -319,7 +324,7 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
   const int64_t* dur = W.dur + abase * K;
   int32_t* wl[3] = {W.wlist + abase * 3, W.wlist + abase * 3 + A, W.wlist + abase * 3 + 2 * (size_t)A};
   int32_t* wl_other[3] = {nullptr, nullptr, nullptr};            // COST: where the next merge of a kind's list writes
-  const uint64_t* okey = COST ? W.okey + abase : nullptr;
+  uint64_t* okey = COST ? W.okey + abase : nullptr;
   if constexpr (COST)
     for (int ty = 0; ty < 3; ++ty) wl_other[ty] = W.wlist2 + abase * 3 + (size_t)ty * A;
   int64_t* run_fin = W.run_fin + abase;
@@ -479,6 +484,50 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
       __threadfence_block();
       __syncthreads();
       for (int ty = 0; ty < 3; ++ty) {
+        if (ty == TG_TYPE_GPU && T.act_service) {
+          // With services the keys follow the caches (Sec. 5.3): an action whose service is cached on no node it may
+          // run on is dearer by the restore time.  So this tick's keys of all waiting GPU actions are written anew
+          // and the list is ordered from scratch, by counting for every entry the keys below its own (keys are
+          // distinct: the id is part of them) - 64 keys at a time across the lanes.
+          const int n = s_wcnt[ty];
+          if (n == 0) continue;
+          const int g0 = T.tnode_off[s * 4 + TG_TYPE_GPU], n_gpu = T.tnode_off[s * 4 + TG_TYPE_GPU + 1] - g0;
+          uint64_t any = 0;                                         // cached on some GPU node
+          for (int r = lane; r < n_gpu; r += TG_WAVE) any |= W.live_res[nbase + T.tnode_idx[nbase + g0 + r]];
+          any = (uint64_t)tg_wave_or_u32((uint32_t)any) | (uint64_t)tg_wave_or_u32((uint32_t)(any >> 32)) << 32;
+          const int32_t* src = wl[ty];
+          int32_t* dst = wl_other[ty];
+          uint64_t* skey = W.skey + abase;
+          for (int x = tid; x < n; x += kThreads) {
+            const int id = src[x];
+            uint64_t key = W.okey0[abase + id] >> 17;
+            const int sv = T.act_service[abase + id];
+            if (sv >= 0 && key != kKeyInf) {
+              const int pin = T.act_pin[abase + id];
+              const uint64_t res = pin >= 0 ? W.live_res[nbase + pin] : any;
+              if (!(res >> sv & 1ull)) key += (uint64_t)T.restore[sv];
+            }
+            const uint64_t packed = key << 17 | (uint32_t)id;
+            okey[id] = packed; skey[x] = packed;
+          }
+          __threadfence_block();
+          __syncthreads();
+          for (int xb = 0; xb < n; xb += kThreads) {
+            const int x = xb + tid;
+            const uint64_t mine = x < n ? skey[x] : ~0ull;
+            int rank = 0;
+            for (int base = 0; base < n; base += TG_WAVE) {
+              const uint64_t kb = base + lane < n ? skey[base + lane] : ~0ull;
+              const int c = min(TG_WAVE, n - base);
+              for (int m = 0; m < c; ++m) rank += (uint64_t)tg_readlane_i64((int64_t)kb, m) < mine ? 1 : 0;
+            }
+            if (x < n) dst[rank] = (int)(mine & 0x1ffffu);
+          }
+          __threadfence_block();
+          __syncthreads();
+          wl_other[ty] = wl[ty]; wl[ty] = dst;
+          continue;
+        }
         int n_new = s_newcnt[ty], n_old = s_wcnt[ty] - n_new;
         while (n_new > 0) {
           const int32_t* src = wl[ty];
@@ -966,7 +1015,6 @@ extern "C" int tg_build_trace(const tg_trace_desc* d, void* hip_stream, tg_trace
   if (d->numa_cores != 0 && d->numa_cores != 4 && d->numa_cores != 8 && d->numa_cores != 16 && d->numa_cores != 32 &&
       d->numa_cores != 64) return TG_E_INVALID_ARG;
   if (d->order_policy != TG_ORDER_FCFS && d->order_policy != TG_ORDER_COST) return TG_E_INVALID_ARG;
-  if (d->order_policy == TG_ORDER_COST && d->act_service) return TG_E_INVALID_ARG;   // keys would change with the caches: not built
   const bool pooled = (d->flags & TG_TRACE_GPU_POOLED) != 0;
   if (pooled && (d->act_service || d->node_aux)) return TG_E_INVALID_ARG;            // a pool has no per-node cache or second resource
   if (svc) {
@@ -1180,7 +1228,7 @@ extern "C" int tg_replay_trace_part(const tg_trace* t, const tg_replay_out* out,
   if (restart) {                                                  // durations and places stay in the workspace for the calls that go on
     hipLaunchKernelGGL(tg_trace_dur_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, T, W.dur);
     if (T.order_cost)
-      hipLaunchKernelGGL(tg_trace_key_kernel, dim3((unsigned)(((size_t)T.S * T.A + 255) / 256)), dim3(256), 0, s, T, W.dur, W.okey);
+      hipLaunchKernelGGL(tg_trace_key_kernel, dim3((unsigned)(((size_t)T.S * T.A + 255) / 256)), dim3(256), 0, s, T, W.dur, W.okey, W.okey0);
   }
   hipLaunchKernelGGL(kernel, dim3(T.S), dim3(kThreads), lds, s, T, W, *out, LD, plan, restart ? 1 : 0, n_ticks);
   return hipGetLastError() == hipSuccess ? TG_OK : TG_E_HIP;

@@ -301,7 +301,6 @@ BAD_TRACE = {
                                             t.__setitem__("act_aux", np.full(t["S"] * t["A"], -1, np.int32))), -1),
     "unknown_flag_next_to_a_known_one": (lambda t: t.__setitem__("flags", 9), -1),
     "unknown_visiting_order": (lambda t: t.__setitem__("order_policy", 2), -1),
-    "cost_order_with_services": (lambda t: (t.__setitem__("order_policy", 1), gen.trace_with_services(t, 1, 4, 2)), -1),
     "tokens_above_bucket": (lambda t: t["quota_tok0_micro"].__setitem__(int(np.flatnonzero(t["node_type"] == gen.TYPE_API)[0]), 10**12), -1),
     "t_ori_range": (lambda t: t["act_t_ori_us"].__setitem__(0, 0), -2),
     "class_out_of_range": (lambda t: (t["act_model"].__setitem__(0, 2), t["act_param"].__setitem__(0, 99), t["act_type"].__setitem__(0, 1)), -3),

@@ -469,3 +469,53 @@ def test_replay_cache_per_gpu_block_choice(tg, orc):
         for slots in (1, 2):
             t = _node_trace(rows, [300_000, 700_000], slots)
             _compare(_replay_gpu(tg, t), orc.replay(t), range(1), len(rows))
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_replay_cost_order_with_services(tg, orc, seed):
+    """The second visiting order next to the service cache: this tick's keys count the restore time unless a node the
+    action may run on caches its service.  GPU-heavy clusters under load (queues of tens to hundreds), caches per node
+    and per GPU, pins, the prefix rule, a second resource."""
+    print("case cost order with services", seed, flush=True)
+    t = gen.make_trace(S=3, A=500 + 100 * seed, seed=470 + seed, cluster=(1 + seed % 2, 16, 1 + seed % 3, seed % 2 * 2),
+                       type_probs=(0.2, 0.7, 0.1) if seed % 2 else (0.3, 0.7, 0.0),
+                       rate_per_s=(60.0, 150.0, 400.0)[seed % 3], horizon_s=(12.0, 6.0, 3.0)[seed % 3], max_ticks=80000,
+                       pin_frac=(0.3, 0.0, 0.8)[(seed // 3) % 3])
+    _with_services(t, seed, n_services=(2, 5, 9, 64)[seed % 4], slots=(1, 2, 3, 64)[(seed // 2) % 4])
+    t["order_policy"] = 1
+    t["cache_per_gpu"] = seed % 2
+    if seed % 4 == 1:
+        t["queue_prefix"] = 1
+    if seed % 4 == 2:
+        _with_aux(t, seed, scarce=True)
+    want = orc.replay(t)
+    fcfs = orc.replay(dict(t, order_policy=0))
+    assert (want["start_us"] != fcfs["start_us"]).any()
+    _compare(_replay_gpu(tg, t), want, range(t["S"]), t["A"])
+
+
+def test_replay_cost_order_with_services_one_machine(tg, orc):
+    """Whole-node actions on one node: the machine whose set-up time follows its cache (the oracle's pin)."""
+    from test_oracle_replay_order import _whole_node_trace
+    for seed in range(6):
+        rng = np.random.default_rng(900 + seed)
+        A = 40
+        T = rng.integers(1, 6, A).tolist()
+        n_sv = int(rng.integers(2, 5))
+        sv = rng.integers(-1, n_sv, A).tolist()
+        restore = rng.integers(1, 9, n_sv).tolist()
+        slots = int(rng.integers(1, 3))
+        arr = sorted(rng.integers(0, 60 if seed % 2 else 1, A).tolist())
+        for per_gpu in (0, 1):
+            t = _whole_node_trace(T, sv, restore, slots, arr, per_gpu=per_gpu)
+            _compare(_replay_gpu(tg, t), orc.replay(t), range(1), A)
+
+
+def test_replay_cost_order_with_services_long_queue(tg, orc):
+    """A burst that leaves more than a thousand GPU actions waiting: the ordering pass runs over many blocks of 64."""
+    t = gen.make_trace(S=2, A=3000, seed=483, cluster=(0, 0, 2, 0), type_probs=(0, 1, 0), rate_per_s=3000.0, horizon_s=1.0,
+                       max_ticks=400000, pin_frac=0.2)
+    _with_services(t, 11, n_services=7, slots=2)
+    t["order_policy"] = 1
+    want = orc.replay(t)
+    _compare(_replay_gpu(tg, t), want, range(t["S"]), t["A"])
