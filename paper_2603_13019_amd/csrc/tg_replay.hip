@@ -626,14 +626,16 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
       if (s_stop == ~0ull) break;                                 // nobody waits: both rules agree
     }
     }
-    // (4b) group candidates and waiting pinned actions by node
-    for (int ty = 0; ty < 3; ++ty)
-      for (int x = tid; x < wcs[ty]; x += kThreads) {
-        const int id = wl[ty][x];
-        const int r = reason[id];
-        if (r == TG_SELECTED) order[nl_off[o_node[id]] + slot[id]] = id;
-        else if (r == TG_DEFER_PREFIX && T.act_pin[abase + id] >= 0) dorder[dl_off[T.act_pin[abase + id]] + slot[id]] = id;
-      }
+    // (4b) group candidates and waiting pinned actions by node (the three lists as one range: their loads travel together)
+    const int wtot = wc0 + wc1 + wc2;
+    for (int x = tid; x < wtot; x += kThreads) {
+      const int ty = x < woff[1] ? 0 : x < woff[2] ? 1 : 2;
+      const int32_t* list = ty == 0 ? wl[0] : ty == 1 ? wl[1] : wl[2];
+      const int id = list[x - (ty == 0 ? 0 : ty == 1 ? woff[1] : woff[2])];
+      const int r = reason[id];
+      if (r == TG_SELECTED) order[nl_off[o_node[id]] + slot[id]] = id;
+      else if (r == TG_DEFER_PREFIX && T.act_pin[abase + id] >= 0) dorder[dl_off[T.act_pin[abase + id]] + slot[id]] = id;
+    }
     __threadfence_block();
     __syncthreads();
     // (4c) per node: DPArrange + greedy eviction; the running actions of the node seed the heap
@@ -742,9 +744,11 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
     __threadfence_block();
     __syncthreads();
     // (5) selected actions start now.  CPU / API: any order; GPU nodes: FCFS order on the mask
-    for (int ty = 0; ty < 3; ++ty)
-      for (int x = tid; x < wcs[ty]; x += kThreads) {
-        const int id = wl[ty][x];
+    for (int x = tid; x < wtot; x += kThreads) {
+      {
+        const int ty = x < woff[1] ? 0 : x < woff[2] ? 1 : 2;
+        const int32_t* list = ty == 0 ? wl[0] : ty == 1 ? wl[1] : wl[2];
+        const int id = list[x - (ty == 0 ? 0 : ty == 1 ? woff[1] : woff[2])];
         const int j = o_node[id];
         if (j < 0) continue;
         const int k = o_units[id];
@@ -779,6 +783,7 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
           }
         }
       }
+    }
     if (T.act_service) __syncthreads();                           // the residency of the tick's start has been read
     if (T.gpu_pooled) {
       // The pool's selected actions, in list order, take their real chunks (Sec. 5.3's rule over the cluster): the
