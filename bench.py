@@ -259,6 +259,18 @@ def replay_section(a, tg, gen, torch):
     return res
 
 
+def host_cpu_model():
+    """Model name of the host processor the oracle is timed on (first entry of /proc/cpuinfo), or None."""
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return None
+
+
 def time_steps(a, tg, torch, P, cost, bufs, mode, steps, warmup):
     """`steps` timed steps after `warmup` untimed ones.  Returns (ms per step, mean ms of the score kernels, mean ms of
     tg_assign or None), stage times from HIP events on the stream the kernels are launched on.
@@ -493,7 +505,7 @@ def main():
                       f"(score {t_score:.2f} s + assign {t_assign:.2f} s); the GPU's tensor and assignment of these "
                       f"snapshots were compared with the oracle's: equal",
             "actions_scheduled_per_sec": len(sample) * P.N / t_assign, "score_candidates_per_sec": cand_s / t_score,
-            "host_cores_total": os.cpu_count(),
+            "host_cores_total": os.cpu_count(), "host_cpu": host_cpu_model(),
         }
 
     if a.only == "step" and a.extras:
