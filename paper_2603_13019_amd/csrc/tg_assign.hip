@@ -379,7 +379,9 @@ __global__ __launch_bounds__(TG_WAVE) void tg_place_kernel(TgDev P, const int64_
 // The same admission decided in rounds of up to 64 actions (tg_place_pool_rounds): plain problems (no second
 // resource, services or further quotas), estimates recomputed, pools of up to 64 R nodes whose backlogs lie
 // within 2^31 us of each other.
-template <int R>
+// R2: the table width of the GPU and API pools where they are narrower than the CPU pools' R (a wavefront pays for
+// every slot of its table in every round).
+template <int R, int R2>
 __global__ __launch_bounds__(TG_WAVE) void tg_place_rounds_kernel(TgDev P, const int64_t* __restrict__ dur, AssignWs W,
                                                                   tg_assign_out O, int lds_nodes, const int32_t* __restrict__ visit) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -407,7 +409,8 @@ __global__ __launch_bounds__(TG_WAVE) void tg_place_rounds_kernel(TgDev P, const
   io.cost = nullptr; io.cost_row_len = 0;
   io.out_node = O.node + abase; io.out_units = O.units + abase; io.out_act = O.act_us + abase;
   io.out_reason = O.defer_reason + abase; io.slot = W.slot + abase;
-  if (t == TG_TYPE_GPU) tg_place_pool_rounds<R, true>(S, io, acts, Nt, Mt, lane);
+  if (t == TG_TYPE_GPU) tg_place_pool_rounds<R2, true>(S, io, acts, Nt, Mt, lane);
+  else if (t == TG_TYPE_API && R2 != R) tg_place_pool_rounds<R2, false>(S, io, acts, Nt, Mt, lane);
   else tg_place_pool_rounds<R, false>(S, io, acts, Nt, Mt, lane);
   tg_pool_extents(S, nodes, Mt, a0, W.nl_off + nbase, W.nl_cnt + nbase, W.dl_off + nbase, W.dl_cnt + nbase, lane);
 }
@@ -934,7 +937,11 @@ int assign_launch(const tg_problem* p, const int64_t* d_cost, const tg_assign_ou
     if (!ext && width != 0 && p->backlog_spread < (1ll << 31)) {
       // plain problem: the admission in rounds of up to 64 actions
       using RoundsKernel = void (*)(TgDev, const int64_t*, AssignWs, tg_assign_out, int, const int32_t*);
-      RoundsKernel kr = width == 1 ? tg_place_rounds_kernel<1> : width == 4 ? tg_place_rounds_kernel<4> : tg_place_rounds_kernel<16>;
+      const int mo = p->max_nodes_not_cpu;
+      const int width2 = mo <= TG_WAVE ? 1 : mo <= 4 * TG_WAVE ? 4 : 16;
+      RoundsKernel kr = width == 1 ? tg_place_rounds_kernel<1, 1>
+                      : width == 4 ? (width2 == 1 ? tg_place_rounds_kernel<4, 1> : tg_place_rounds_kernel<4, 4>)
+                      : width2 == 1 ? tg_place_rounds_kernel<16, 1> : width2 == 4 ? tg_place_rounds_kernel<16, 4> : tg_place_rounds_kernel<16, 16>;
       if (place_lds > 64 * 1024)
         TG_HIP_CHECK(hipFuncSetAttribute((const void*)kr, hipFuncAttributeMaxDynamicSharedMemorySize, (int)place_lds));
       if (!prepare_only) hipLaunchKernelGGL(kr, dim3(P.B * 3), dim3(TG_WAVE), place_lds, s, P, W.dur, W, *out, p->max_nodes_of_kind, visit);

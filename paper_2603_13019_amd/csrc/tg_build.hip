@@ -285,6 +285,7 @@ int build_problem(const tg_problem_desc* desc, void* hip_stream, tg_problem** ou
     const size_t n_busy = d->node_busy_off ? (size_t)d->node_busy_off[nN] : 0;
     const size_t o_nbrel = ar.add(std::max<size_t>(n_busy, 1) * 8);
     std::vector<int> max_cap((size_t)B * 3, -1);
+    int max_other = 0;                                            // most GPU nodes or quotas of a snapshot
     int max_kind = 0, max_free_cpu = 0, max_heap = 0, max_free_gpu = 0, max_states = 1;
     size_t free_gt16 = 0, free_gt64 = 0, nodes_by_actions_gt64 = 0;
     int64_t backlog_spread = 0;
@@ -338,6 +339,7 @@ int build_problem(const tg_problem_desc* desc, void* hip_stream, tg_problem** ou
         ar.at<int32_t>(o_tnidx)[(size_t)b * M + fill[t]++] = j;
       }
       for (int t = 0; t < 3; ++t) max_kind = std::max(max_kind, cnt[t]);
+      max_other = std::max({max_other, cnt[TG_TYPE_GPU], cnt[TG_TYPE_API]});
       for (int t = 0; t < 3; ++t) if (cnt[t]) backlog_spread = std::max(backlog_spread, bl_hi[t] - bl_lo[t]);
       if (max_kind > TG_MAX_NODES_OF_KIND) { delete p; return TG_E_RANGE; }
     }
@@ -556,6 +558,7 @@ int build_problem(const tg_problem_desc* desc, void* hip_stream, tg_problem** ou
     p->n_blocks = B * 3;
     p->n_candidates = total;
     p->max_nodes_of_kind = max_kind;
+    p->max_nodes_not_cpu = max_other;
     p->backlog_spread = backlog_spread;
     p->order_policy = d->order_policy; p->queue_prefix = d->queue_prefix; p->max_actions_of_kind = max_acts_kind;
     p->max_free_cpu = max_free_cpu;

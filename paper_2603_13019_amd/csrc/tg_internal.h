@@ -124,6 +124,7 @@ struct tg_problem {
   int queue_prefix;        // 1: one admitted prefix of the whole queue instead of one per pool
   int max_actions_of_kind; // largest N_t over all snapshots and kinds
   int max_nodes_of_kind;   // largest M_t over all snapshots and kinds
+  int max_nodes_not_cpu;   // the same over the GPU and API kinds only
   int64_t backlog_spread;  // largest (max - min) backlog over the nodes of one kind in one snapshot
   int max_free_cpu;        // largest node_free over CPU nodes
   int max_heap;            // largest free + busy over CPU and GPU nodes
