@@ -179,6 +179,22 @@ def replay_section(a, tg, gen, torch):
             dt = time.perf_counter() - t0
             res[name]["cpu_oracle_actions_per_sec"] = n * 10_000 / dt
             res[name]["cpu_oracle_sample"] = f"{n} scenarios, 1 core"
+        # the same replay cut into pieces of 250 ticks (tg_replay_trace_part): what stopping and going on costs
+        whole = {k: bufs[k].clone() for k in ("start_us", "finish_us", "units", "node")}
+        limit, done, first = int(t["max_ticks"]), 0, True
+        torch.cuda.synchronize()
+        e0.record()
+        pieces = 0
+        while done < limit:
+            n = 250 if done < 2500 else limit - done                # the arrivals end after 2000 ticks: one last piece for the rest
+            T.replay_part(bufs, restart=first, n_ticks=n)
+            first = False
+            done += n
+            pieces += 1
+        e1.record()
+        torch.cuda.synchronize()
+        res[name]["in_pieces"] = {"pieces": pieces, "ms": e0.elapsed_time(e1),
+                                  "equal": all(bool(torch.equal(whole[k], bufs[k])) for k in whole)}
         T.free()
         if contended:
             # the same trace with one admitted prefix of the whole queue per step (Alg. 1 as printed): two admission passes per tick
