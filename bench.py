@@ -185,7 +185,7 @@ def replay_section(a, tg, gen, torch):
         torch.cuda.synchronize()
         e0.record()
         pieces = 0
-        while done < limit:
+        while done < limit and a.replay_pieces:
             n = 250 if done < 2500 else limit - done                # the arrivals end after 2000 ticks: one last piece for the rest
             T.replay_part(bufs, restart=first, n_ticks=n)
             first = False
@@ -193,8 +193,9 @@ def replay_section(a, tg, gen, torch):
             pieces += 1
         e1.record()
         torch.cuda.synchronize()
-        res[name]["in_pieces"] = {"pieces": pieces, "ms": e0.elapsed_time(e1),
-                                  "equal": all(bool(torch.equal(whole[k], bufs[k])) for k in whole)}
+        if pieces:
+            res[name]["in_pieces"] = {"pieces": pieces, "ms": e0.elapsed_time(e1),
+                                      "equal": all(bool(torch.equal(whole[k], bufs[k])) for k in whole)}
         T.free()
         if contended:
             # the same trace with one admitted prefix of the whole queue per step (Alg. 1 as printed): two admission passes per tick
@@ -417,6 +418,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle (no baseline, no check of the results)")
     ap.add_argument("--replay-scenarios", type=int, default=4096,
                     help="scenarios of workload 5 (10 000 arrivals each) replayed after the timed steps; 0 = skip")
+    ap.add_argument("--replay-pieces", type=int, default=1, help="0: leave out the replays cut into pieces")
     ap.add_argument("--extras", type=int, default=1, help="0: only the timed steps of the chosen workload (and the baseline)")
     ap.add_argument("--only", choices=["step", "score", "assign"], default="step")
     ap.add_argument("--overlap", type=int, default=-1,
