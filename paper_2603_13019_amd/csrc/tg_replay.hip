@@ -964,12 +964,15 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
       for (int ty = 0; ty < 3; ++ty) parity |= (wl[ty] != W.wlist + abase * 3 + (size_t)ty * A ? 1 : 0) << ty;
     resume[8] = parity; resume[9] = resume_mark;
   }
-  if (tid == 0) s_sum = 0;
+  if (tid == 0) { s_sum = 0; s_stop = 0; }
   __syncthreads();
   const int n_started = s_started;
   long long sum = 0;
-  for (int i = tid; i < A; i += kThreads) if (o_start[i] >= 0) sum += o_fin[i] - arrival[i];
+  unsigned long long act_bits = 0;                                // OR of all ACTs: which bytes of them are in use at all
+  for (int i = tid; i < A; i += kThreads)
+    if (o_start[i] >= 0) { const long long act = o_fin[i] - arrival[i]; sum += act; act_bits |= (unsigned long long)act; }
   atomicAdd((unsigned long long*)&s_sum, (unsigned long long)sum);
+  atomicOr(&s_stop, act_bits);                                    // (the admission's stop mark is not needed any more)
   __syncthreads();
   // radix select of the rank-th smallest ACT, one byte per pass from the top
   int* s_hist = reinterpret_cast<int*>(smem);                     // the tables of the ticks are dead
@@ -977,13 +980,14 @@ __global__ __launch_bounds__(kThreads) void tg_replay_kernel(TgTraceDev T, Repla
   if (n_started > 0) {
     int rank = (int)((99ll * n_started + 99) / 100);             // 1-based
     uint64_t prefix = 0;
-    for (int shift = 56; shift >= 0; shift -= 8) {
+    const int top = s_stop ? (63 - __builtin_clzll(s_stop)) & ~7 : 0;   // bytes above it are zero in every ACT: their passes would pick bin 0
+    for (int shift = top; shift >= 0; shift -= 8) {
       for (int b = tid; b < 256; b += kThreads) s_hist[b] = 0;
       __syncthreads();
       for (int i = tid; i < A; i += kThreads)
         if (o_start[i] >= 0) {
           const uint64_t key = (uint64_t)(o_fin[i] - arrival[i]);
-          if (shift == 56 || (key >> (shift + 8)) == prefix) atomicAdd(&s_hist[(key >> shift) & 255], 1);
+          if (shift == top || (key >> (shift + 8)) == prefix) atomicAdd(&s_hist[(key >> shift) & 255], 1);
         }
       __syncthreads();
       if (tid == 0) {
